@@ -1,0 +1,323 @@
+"""Plain CPU fp64 oracle for the GELO obfuscated projection.
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It exists so that the GPU
+library can be checked against something written independently from the paper.
+Only the test-suite, the smoke check and the benchmark's CPU-baseline leg may
+import it; the GPU library never does and shares no code, table or constant
+generator with it.
+
+Everything is float64 numpy, one step per function, no blocking or fusion, in
+the order the paper states the protocol (Section 3.2 "Core Algorithm",
+eqs. 1-4, and Section 3.2.1 "Mitigating Gram Matrix Information Leaks",
+eqs. 5-9).  `numpy.matmul`, `numpy.linalg.svd` and `numpy.median` serve as
+library primitives for single steps (a matrix product, the singular values, a
+median); the Philox generator, the Householder QR, the LU factorisation and
+the triangular solves are written out here.
+
+Every function is pinned by tests that do not call back into this file's own
+formulas (known-answer vectors, closed forms, LAPACK cross-checks, brute
+force, the paper's identities); no function is "parity unpinned" except where
+stated in its docstring.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+# --------------------------------------------------------------------------
+# Counter-based generator: Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11).
+# The paper only says "sample a fresh, random invertible matrix A" (Section
+# 3.2, step 1.2); a counter-based generator makes "fresh per batch, never
+# reused" a matter of never repeating a (seed, batch id) pair.
+# --------------------------------------------------------------------------
+_MASK32 = np.uint64(0xFFFFFFFF)
+_PHILOX_M0 = np.uint64(0xD2511F53)
+_PHILOX_M1 = np.uint64(0xCD9E8D57)
+_PHILOX_W0 = np.uint64(0x9E3779B9)
+_PHILOX_W1 = np.uint64(0xBB67AE85)
+
+STREAM_MIXING = 0        # Gaussian G that A is built from
+STREAM_SHIELD = 1        # Gaussian directions of the shield rows
+STREAM_PERTURB = 2       # second Gaussian of the conditioned non-orthogonal A
+
+
+def philox4x32_10(counter, key):
+    """Ten Philox rounds on 4x32-bit counters with a 2x32-bit key.
+
+    `counter` is a sequence of four equally shaped integer arrays (values
+    < 2**32), `key` a pair of integers.  Returns four uint32 arrays.
+    One round: (c0,c1,c2,c3) -> (hi(M1*c2)^c1^k0, lo(M1*c2), hi(M0*c0)^c3^k1,
+    lo(M0*c0)); the key is advanced by the Weyl constants between rounds.
+    """
+    c0, c1, c2, c3 = (np.asarray(c, dtype=np.uint64) & _MASK32 for c in counter)
+    c0, c1, c2, c3 = np.broadcast_arrays(c0, c1, c2, c3)
+    k0 = np.uint64(int(key[0]) & 0xFFFFFFFF)
+    k1 = np.uint64(int(key[1]) & 0xFFFFFFFF)
+    for rnd in range(10):
+        if rnd > 0:
+            k0 = (k0 + _PHILOX_W0) & _MASK32
+            k1 = (k1 + _PHILOX_W1) & _MASK32
+        p0 = _PHILOX_M0 * c0            # 32x32 -> 64 bit, exact in uint64
+        p1 = _PHILOX_M1 * c2
+        hi0, lo0 = p0 >> np.uint64(32), p0 & _MASK32
+        hi1, lo1 = p1 >> np.uint64(32), p1 & _MASK32
+        c0, c1, c2, c3 = hi1 ^ c1 ^ k0, lo1, hi0 ^ c3 ^ k1, lo0
+    return tuple(c.astype(np.uint32) for c in (c0, c1, c2, c3))
+
+
+def uniform_open01(word):
+    """Top 23 bits of a 32-bit word -> a uniform in (0,1): (2m + 1) * 2**-24.
+
+    2m + 1 < 2**24, so the value is exactly representable in float32 as well
+    as float64: a single-precision implementation sees the same uniforms.
+    """
+    m = (np.asarray(word, dtype=np.uint32) >> np.uint32(9)).astype(np.float64)
+    return (2.0 * m + 1.0) * (2.0 ** -24)
+
+
+def box_muller(word_a, word_b):
+    """Two independent N(0,1) values from two 32-bit words (Box-Muller)."""
+    u1 = uniform_open01(word_a)
+    u2 = uniform_open01(word_b)
+    radius = np.sqrt(-2.0 * np.log(u1))
+    angle = 2.0 * math.pi * u2
+    return radius * np.cos(angle), radius * np.sin(angle)
+
+
+def gaussian_matrix(seed, batch_id, stream, attempt, rows, cols):
+    """rows x cols matrix of i.i.d. N(0,1), a pure function of its arguments.
+
+    Element e = r*cols + c (row-major) is output e mod 4 of Philox block
+    e div 4.  Block q uses counter (q, stream<<8 | attempt, batch_id low,
+    batch_id high) and key (seed low, seed high).  Outputs 0,1 of a block are
+    the Box-Muller pair of words 0,1; outputs 2,3 the pair of words 2,3.
+    """
+    total = rows * cols
+    nblocks = (total + 3) // 4
+    q = np.arange(nblocks, dtype=np.uint64)
+    c1 = np.uint64(((int(stream) & 0xFFFFFF) << 8) | (int(attempt) & 0xFF))
+    c2 = np.uint64(int(batch_id) & 0xFFFFFFFF)
+    c3 = np.uint64((int(batch_id) >> 32) & 0xFFFFFFFF)
+    key = (int(seed) & 0xFFFFFFFF, (int(seed) >> 32) & 0xFFFFFFFF)
+    x0, x1, x2, x3 = philox4x32_10((q, c1, c2, c3), key)
+    z0, z1 = box_muller(x0, x1)
+    z2, z3 = box_muller(x2, x3)
+    flat = np.stack([z0, z1, z2, z3], axis=1).reshape(-1)[:total]
+    return flat.reshape(rows, cols)
+
+
+# --------------------------------------------------------------------------
+# Orthogonal A: Householder QR of a Gaussian matrix (Section 3.2, eq. 3 remark
+# "if A is orthogonal, A^-1 = A^T"; Table 3 names the step "A-gen (QR)").
+# --------------------------------------------------------------------------
+def householder_qr(G):
+    """Unblocked Householder QR.  Returns (Q, R) with Q orthogonal, R upper
+    triangular and Q @ R == G.  Column j is reduced by the reflector
+    I - 2 v v^T / (v^T v),  v = x + sign(x_0) ||x|| e_0,  x = R[j:, j]."""
+    R = np.array(G, dtype=np.float64, copy=True)
+    n = R.shape[0]
+    if R.shape[1] != n:
+        raise ValueError("square matrix expected")
+    Q = np.eye(n)
+    for j in range(n):
+        x = R[j:, j]
+        norm_x = math.sqrt(float(x @ x))
+        if norm_x == 0.0:
+            continue
+        v = x.copy()
+        v[0] += norm_x if x[0] >= 0.0 else -norm_x
+        scale = 2.0 / float(v @ v)
+        R[j:, j:] -= scale * np.outer(v, v @ R[j:, j:])
+        Q[:, j:] -= scale * np.outer(Q[:, j:] @ v, v)
+        R[j + 1:, j] = 0.0
+    return Q, R
+
+
+def orthogonal_from_gaussian(G):
+    """A = Q diag(sign r_ii): the orthogonal factor of the QR factorisation of
+    G whose triangular factor has a positive diagonal.  That factor is unique,
+    and Haar-distributed when G is Gaussian."""
+    Q, R = householder_qr(G)
+    signs = np.where(np.diag(R) < 0.0, -1.0, 1.0)
+    return Q * signs[None, :]
+
+
+# --------------------------------------------------------------------------
+# Non-orthogonal A (Section 3.2.1, Mitigation 1): general invertible matrix,
+# explicit inverse, condition number verified.
+# --------------------------------------------------------------------------
+def lu_partial_pivot(A):
+    """Row-pivoted LU: returns (perm, L, U) with A[perm] == L @ U, L unit lower
+    triangular, U upper triangular.  Raises ZeroDivisionError on a zero pivot."""
+    M = np.array(A, dtype=np.float64, copy=True)
+    n = M.shape[0]
+    perm = np.arange(n)
+    for j in range(n):
+        piv = j + int(np.argmax(np.abs(M[j:, j])))
+        if M[piv, j] == 0.0:
+            raise ZeroDivisionError("singular matrix")
+        if piv != j:
+            M[[j, piv]] = M[[piv, j]]
+            perm[[j, piv]] = perm[[piv, j]]
+        M[j + 1:, j] /= M[j, j]
+        M[j + 1:, j + 1:] -= np.outer(M[j + 1:, j], M[j, j + 1:])
+    L = np.tril(M, -1) + np.eye(n)
+    U = np.triu(M)
+    return perm, L, U
+
+
+def inverse_from_lu(perm, L, U):
+    """Solve L U X = P for X = A^-1 by forward then backward substitution."""
+    n = L.shape[0]
+    X = np.eye(n)[perm]                     # P, rows of the identity permuted
+    for i in range(n):                      # L y = b, unit diagonal
+        X[i] -= L[i, :i] @ X[:i]
+    for i in range(n - 1, -1, -1):          # U x = y
+        X[i] = (X[i] - U[i, i + 1:] @ X[i + 1:]) / U[i, i]
+    return X
+
+
+def inverse(A):
+    return inverse_from_lu(*lu_partial_pivot(A))
+
+
+def cond2(A):
+    """2-norm condition number sigma_max / sigma_min (an orthogonal A has
+    kappa = 1 in this norm, which is the one Section 3.2.1 reasons with)."""
+    s = np.linalg.svd(np.asarray(A, dtype=np.float64), compute_uv=False)
+    return float(s[0] / s[-1]) if s[-1] > 0.0 else math.inf
+
+
+def sample_orthogonal(seed, batch_id, n):
+    """Fresh orthogonal A for one batch; returns (A, A^-1 = A^T)."""
+    G = gaussian_matrix(seed, batch_id, STREAM_MIXING, 0, n, n)
+    A = orthogonal_from_gaussian(G)
+    return A, A.T.copy()
+
+
+def sample_gaussian(seed, batch_id, n, cond_max, max_attempts):
+    """A = G / sqrt(n) (entries N(0, 1/n)); redrawn with the attempt number in
+    the counter until kappa_2(A) <= cond_max.  Returns (A, A^-1, attempt,
+    kappa, kappas_of_all_attempts)."""
+    kappas = []
+    for attempt in range(max_attempts):
+        A = gaussian_matrix(seed, batch_id, STREAM_MIXING, attempt, n, n) / math.sqrt(n)
+        kappa = cond2(A)
+        kappas.append(kappa)
+        if kappa <= cond_max:
+            return A, inverse(A), attempt, kappa, kappas
+    raise RuntimeError("no well-conditioned draw within max_attempts")
+
+
+CONDITIONED_BETA = 0.25
+
+
+def sample_conditioned(seed, batch_id, n, beta=CONDITIONED_BETA):
+    """Well-conditioned dense non-orthogonal A = Q + beta * G2 / sqrt(n), Q the
+    orthogonal matrix of `sample_orthogonal`, G2 an independent Gaussian.
+    ||G2/sqrt(n)||_2 ~ 2, so the singular values stay within about
+    [1-2 beta, 1+2 beta]: kappa of a few, inside the paper's "kappa < 100"
+    advice, while A^T A != I.  (The construction is this build's reading; the
+    paper asks for a well-conditioned general A without saying how to get one.)
+    Returns (A, A^-1, kappa)."""
+    Q, _ = sample_orthogonal(seed, batch_id, n)
+    G2 = gaussian_matrix(seed, batch_id, STREAM_PERTURB, 0, n, n)
+    A = Q + (beta / math.sqrt(n)) * G2
+    return A, inverse(A), cond2(A)
+
+
+# --------------------------------------------------------------------------
+# Shield rows (Section 3.2.1, Mitigation 2, eqs. 7-9).
+# --------------------------------------------------------------------------
+NORM_MEDIAN = 0
+NORM_MEAN = 1
+
+
+def row_norm_statistic(H, stat=NORM_MEDIAN):
+    norms = np.sqrt(np.sum(np.asarray(H, dtype=np.float64) ** 2, axis=1))
+    if stat == NORM_MEDIAN:
+        return float(np.median(norms))      # even count: mean of the two middle values
+    if stat == NORM_MEAN:
+        return float(np.mean(norms))
+    raise ValueError("unknown statistic")
+
+
+def shield_rows(H, directions, scale, stat=NORM_MEDIAN):
+    """S_i = directions_i * scale * m(H) / ||directions_i||: k secret rows,
+    each of norm exactly `scale` times the row-norm statistic of H."""
+    directions = np.asarray(directions, dtype=np.float64)
+    if directions.shape[0] == 0:
+        return directions.reshape(0, np.asarray(H).shape[1])
+    m = row_norm_statistic(H, stat)
+    norms = np.sqrt(np.sum(directions ** 2, axis=1))
+    return directions * (scale * m / norms)[:, None]
+
+
+def sample_shield_directions(seed, batch_id, k, d):
+    return gaussian_matrix(seed, batch_id, STREAM_SHIELD, 0, k, d)
+
+
+# --------------------------------------------------------------------------
+# The protocol (Section 3.2, eqs. 1-3; eq. 8 with shields).
+# --------------------------------------------------------------------------
+def mix(A, H, S=None):
+    """U = A [H; S]  (eq. 1; eq. 8 when shield rows are stacked under H)."""
+    H = np.asarray(H, dtype=np.float64)
+    H_full = H if S is None or len(S) == 0 else np.vstack([H, np.asarray(S, dtype=np.float64)])
+    return np.asarray(A, dtype=np.float64) @ H_full
+
+
+def project(U, W):
+    """Y = U W  (eq. 2), the accelerator's only job."""
+    return np.asarray(U, dtype=np.float64) @ np.asarray(W, dtype=np.float64)
+
+
+def unmix(A_inv, Y, n_data):
+    """Z = (A^-1 Y)[0:n_data]  (eq. 3, then the shield rows are dropped)."""
+    Z_full = np.asarray(A_inv, dtype=np.float64) @ np.asarray(Y, dtype=np.float64)
+    return Z_full[:n_data]
+
+
+def plain_projection(H, W):
+    """What the protocol must reproduce (eq. 4): Z* = H W."""
+    return np.asarray(H, dtype=np.float64) @ np.asarray(W, dtype=np.float64)
+
+
+KIND_ORTHOGONAL = 0
+KIND_GAUSSIAN = 1
+KIND_CONDITIONED = 2
+
+
+def sample_mixing(kind, seed, batch_id, n, cond_max=1e3, max_attempts=64):
+    """Returns (A, A^-1, info) for one batch."""
+    if kind == KIND_ORTHOGONAL:
+        A, A_inv = sample_orthogonal(seed, batch_id, n)
+        return A, A_inv, {"attempt": 0, "kappa": 1.0}
+    if kind == KIND_GAUSSIAN:
+        A, A_inv, attempt, kappa, kappas = sample_gaussian(seed, batch_id, n, cond_max, max_attempts)
+        return A, A_inv, {"attempt": attempt, "kappa": kappa, "kappas": kappas}
+    if kind == KIND_CONDITIONED:
+        A, A_inv, kappa = sample_conditioned(seed, batch_id, n)
+        return A, A_inv, {"attempt": 0, "kappa": kappa}
+    raise ValueError("unknown kind")
+
+
+def qkv_forward(kind, seed, batch_id, H, W, k_shield=0, shield_scale=10.0,
+                stat=NORM_MEDIAN, cond_max=1e3, max_attempts=64):
+    """The whole chain for one batch, every intermediate returned."""
+    H = np.asarray(H, dtype=np.float64)
+    n_data, d = H.shape
+    n = n_data + k_shield
+    A, A_inv, info = sample_mixing(kind, seed, batch_id, n, cond_max, max_attempts)
+    S = shield_rows(H, sample_shield_directions(seed, batch_id, k_shield, d), shield_scale, stat)
+    U = mix(A, H, S)
+    Y = project(U, W)
+    Z = unmix(A_inv, Y, n_data)
+    return {"A": A, "A_inv": A_inv, "S": S, "U": U, "Y": Y, "Z": Z, "info": info}
+
+
+def rel_frobenius(X, X_ref):
+    """||X - X_ref||_F / ||X_ref||_F over the whole matrix."""
+    X_ref = np.asarray(X_ref, dtype=np.float64)
+    return float(np.linalg.norm(np.asarray(X, dtype=np.float64) - X_ref) / np.linalg.norm(X_ref))

@@ -1,0 +1,87 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+Holds input generation only (hidden states H, weights W, workload shapes);
+none of the method's arithmetic lives here, so both the GPU tests and the CPU
+oracle can draw identical inputs from it.
+
+The paper evaluates on Llama-2-7B hidden states and weights (Section 4.1,
+Appendix A: d = 4096, each of Q/K/V/O is 4096 x 4096).  Those are not
+available offline; the stand-ins keep the shapes (d = 4096, fused QKV width
+p = 12288) and use N(0,1) activations with a few high-magnitude "outlier"
+channels, and N(0, 0.02^2) weights.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+KIND_ORTHOGONAL = 0
+KIND_GAUSSIAN = 1
+KIND_CONDITIONED = 2
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    dtype: str            # "f32" or "bf16"
+    n_data: int           # plaintext rows of H
+    k_shield: int         # shield rows appended
+    d: int
+    p: int
+    kind: int
+    outlier_channels: int
+    seed: int
+    shield_scale: float = 10.0
+    cond_max: float = 1e3
+
+    @property
+    def n(self) -> int:
+        return self.n_data + self.k_shield
+
+
+WORKLOADS = {
+    # tiny fp32 case the oracle finishes instantly
+    "tiny_f32": Workload("tiny_f32", "f32", 16, 2, 64, 192, KIND_ORTHOGONAL, 0, 0xC0),
+    # Llama-2-7B-shaped single layer, fp32, non-orthogonal Gaussian A with kappa rejection
+    "llama7b_f32_gaussian": Workload("llama7b_f32_gaussian", "f32", 512, 0, 4096, 12288,
+                                     KIND_GAUSSIAN, 8, 0xC1),
+    # bf16 prefill, orthogonal A + 5% shields (102 rows on 2048 -> n = 2150)
+    "llama7b_bf16_prefill": Workload("llama7b_bf16_prefill", "bf16", 2048, 102, 4096, 12288,
+                                     KIND_ORTHOGONAL, 8, 0xC2),
+    # one layer of the 32-layer sweep: 8 sequences x 512 tokens; even layers
+    "sweep_bf16_orth": Workload("sweep_bf16_orth", "bf16", 4096, 205, 4096, 12288,
+                                KIND_ORTHOGONAL, 8, 0xC3),
+    # ... odd layers: well-conditioned non-orthogonal A, no shields
+    "sweep_bf16_cond": Workload("sweep_bf16_cond", "bf16", 4096, 0, 4096, 12288,
+                                KIND_CONDITIONED, 8, 0xC3),
+    # decode-shaped: 64 tokens per step, 4 shields
+    "decode_bf16": Workload("decode_bf16", "bf16", 64, 4, 4096, 12288, KIND_ORTHOGONAL, 8, 0xC4),
+}
+
+
+def make_hidden(rows: int, d: int, seed: int, outlier_channels: int = 8,
+                outlier_scale: float = 20.0) -> np.ndarray:
+    """rows x d float32 ~ N(0,1); `outlier_channels` distinct seeded columns are
+    multiplied by `outlier_scale` (massive-activation channels of LLM hidden states)."""
+    rng = np.random.default_rng([seed, 0x48])
+    H = rng.standard_normal((rows, d), dtype=np.float32)
+    if outlier_channels > 0:
+        cols = rng.choice(d, size=min(outlier_channels, d), replace=False)
+        H[:, cols] *= np.float32(outlier_scale)
+    return H
+
+
+def make_weight(d: int, p: int, seed: int, std: float = 0.02) -> np.ndarray:
+    """d x p float32 ~ N(0, std^2) (std is a standard deviation, the usual LLM init)."""
+    rng = np.random.default_rng([seed, 0x57])
+    W = rng.standard_normal((d, p), dtype=np.float32)
+    W *= np.float32(std)
+    return W
+
+
+def make_inputs(w: Workload, layer: int = 0):
+    """(H, W) float32 host arrays for one batch of workload `w`."""
+    H = make_hidden(w.n_data, w.d, w.seed * 1000 + layer, w.outlier_channels)
+    W = make_weight(w.d, w.p, w.seed * 1000 + layer)
+    return H, W
