@@ -1,0 +1,133 @@
+/*
+ * gelo.h - C ABI of the GELO obfuscated-projection library for AMD MI355X (gfx950).
+ *
+ * GELO (Section 3.2 "Core Algorithm" of the paper) offloads a projection H*W to
+ * an untrusted accelerator without showing it H:
+ *
+ *   trusted side      A  <- fresh random invertible n x n matrix        (step 1.2)
+ *                     U  =  A * [H ; S]                                 (eq. 1, eq. 8)
+ *   accelerator       Y  =  U * W                                       (eq. 2)
+ *   trusted side      Z  =  A^-1 * Y, shield rows dropped               (eq. 3)
+ *
+ * and Z == H*W (eq. 4).  S are k secret high-norm "shield" rows (Section 3.2.1,
+ * Mitigation 2); A is orthogonal (A^-1 = A^T) or a general well-conditioned
+ * matrix (Mitigation 1).  Both roles run on one GPU here; U and Y are always
+ * materialised in device memory because they are the messages the accelerator
+ * sees (Section 3.1, the observation set O_t).
+ *
+ * Conventions
+ *  - Every matrix pointer is a DEVICE pointer owned by the caller, row-major,
+ *    16-byte aligned, with a leading dimension (in elements) that is a multiple
+ *    of 8.  d and p must be multiples of 8.  The library never frees or keeps
+ *    caller memory.  gelo_ctx and gelo_mixing objects are library-owned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued asynchronously on it; argument errors are reported
+ *    synchronously and enqueue nothing.
+ *  - dtype GELO_F32: H, W, U, Y, Z are float.  GELO_BF16: they are bfloat16
+ *    (upper 16 bits of a float), products accumulate in float, A is generated
+ *    in float and rounded once to bfloat16 for the two mixing products.
+ *  - All calls return a gelo_status; gelo_last_error() gives a message for the
+ *    last failing call on a context.  No exceptions, no aborts.
+ *  - A context is not thread-safe.  Sampling uses context-owned workspace, so
+ *    two gelo_sample_mixing calls on one context must not overlap in time on
+ *    different streams; sampling may overlap mix/project/unmix of other batches.
+ */
+#ifndef GELO_H
+#define GELO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gelo_ctx gelo_ctx;        /* device, Philox key (seed), workspace, set of used batch ids */
+typedef struct gelo_mixing gelo_mixing;  /* the trusted side's secrets for ONE batch: A, A^-1, shield directions */
+
+typedef enum {
+    GELO_OK = 0,
+    GELO_EINVAL = 1,      /* null pointer, non-positive size, bad enum value */
+    GELO_ESHAPE = 2,      /* sizes outside what the kernels support (see each call) */
+    GELO_EDTYPE = 3,      /* dtype of the call and of the mixing object differ */
+    GELO_EALIGN = 4,      /* pointer not 16-byte aligned or leading dimension / width not a multiple of 8 */
+    GELO_ENOMEM = 5,      /* device or host allocation failed */
+    GELO_ECOND = 6,       /* no draw with kappa_2(A) <= cond_max within max_attempts */
+    GELO_ESINGULAR = 7,   /* zero pivot met while factorising A */
+    GELO_EREUSE = 8,      /* batch id already used on this context, or mixing object already consumed */
+    GELO_ESTATE = 9,      /* call out of order (unmix before mix) */
+    GELO_EHIP = 10        /* HIP runtime error; text in gelo_last_error() */
+} gelo_status;
+
+typedef enum { GELO_F32 = 0, GELO_BF16 = 1 } gelo_dtype;
+
+/* How A is drawn (Section 3.2 step 1.2; Section 3.2.1).
+ *  ORTHOGONAL   A = Q diag(sign r_ii) from the Householder QR of a Philox Gaussian; A^-1 = A^T.
+ *  GAUSSIAN     A = G/sqrt(n); redrawn until kappa_2(A) <= cond_max; A^-1 from a pivoted LU.
+ *  CONDITIONED  A = Q + 0.25 G2/sqrt(n): dense, A^T A != I, kappa of a few; A^-1 from a pivoted LU. */
+typedef enum { GELO_ORTHOGONAL = 0, GELO_GAUSSIAN = 1, GELO_CONDITIONED = 2 } gelo_kind;
+
+/* Row-norm statistic of H that the shield rows are scaled by. */
+typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;
+
+#define GELO_MAX_N 5120        /* largest n = n_data + k_shield the factorisation kernels take */
+#define GELO_MAX_ATTEMPTS 255  /* the attempt number is one byte of the Philox counter */
+
+/* Creates a context on HIP device `device` with Philox key `seed`.  `allow_batch_reuse` != 0
+ * switches off the check that a batch id is used at most once (for tests and benchmarks that
+ * replay a batch; production callers pass 0: A must never be reused, Section 3.2 step 1.2). */
+gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_batch_reuse);
+gelo_status gelo_destroy(gelo_ctx* ctx);
+/* Message of the last failing call on `ctx` ("" if none).  Owned by the context. */
+const char* gelo_last_error(const gelo_ctx* ctx);
+const char* gelo_status_string(gelo_status s);
+
+/* Trusted side, Section 3.2 step 1.2.  Draws the secrets of batch `batch_id`: A (n x n,
+ * n = n_data + k_shield), its inverse, and k_shield Gaussian shield directions of width d.
+ * A pure function of (seed, batch_id, kind, n, k_shield, d).  cond_max and max_attempts
+ * (1..GELO_MAX_ATTEMPTS) are used by GELO_GAUSSIAN only, which reads one scalar back per
+ * attempt (the only host synchronisation in the library).  n <= GELO_MAX_N, n_data >= 1,
+ * k_shield >= 0, d a multiple of 8.  *out is owned by the library: release it with
+ * gelo_mixing_free (which recycles its device memory inside the context). */
+gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d,
+                               gelo_dtype dtype, double cond_max, int max_attempts,
+                               uint64_t batch_id, gelo_mixing** out, void* stream);
+
+/* Trusted side, eq. 1 / eqs. 7-8.  Shield rows S_i = g_i * shield_scale * m(H) / ||g_i||, m the
+ * median or mean row 2-norm of H; then U[n x d] = A * [H ; S].  H: n_data x d (ldh), U: n x d (ldu). */
+gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* mixing, const void* H, int64_t ldh,
+                     float shield_scale, gelo_norm_stat stat, void* U, int64_t ldu, void* stream);
+
+/* Accelerator side, eq. 2.  Y[n x p] = U[n x d] * W[d x p].  Touches no secret: it takes no
+ * mixing object.  Also serves as the plain baseline H*W (pass H as U, n = n_data). */
+gelo_status gelo_project(gelo_ctx* ctx, gelo_dtype dtype, int n, int d, int p,
+                         const void* U, int64_t ldu, const void* W, int64_t ldw,
+                         void* Y, int64_t ldy, void* stream);
+
+/* Trusted side, eq. 3 + shield drop.  Z[n_data x p] = (A^-1 * Y)[0:n_data, :]; the shield rows
+ * of the product are never computed.  Y: n x p (ldy).  Marks the mixing consumed: a second
+ * gelo_mix or gelo_unmix on it returns GELO_EREUSE. */
+gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* mixing, int p, const void* Y, int64_t ldy,
+                       void* Z, int64_t ldz, void* stream);
+
+gelo_status gelo_mixing_free(gelo_ctx* ctx, gelo_mixing* mixing);
+
+/* The whole chain for one batch: sample, mix, project, unmix (eqs. 1-3).  H: n_data x d, W: d x p,
+ * Z: n_data x p, all densely packed (leading dimension = width).  U_opt (n x d) and Y_opt (n x p)
+ * receive the two observable messages; if NULL they are written to context workspace instead. */
+gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_data, int k_shield,
+                             int d, int p, const void* H, const void* W, float shield_scale,
+                             gelo_norm_stat stat, double cond_max, int max_attempts, uint64_t batch_id,
+                             void* Z, void* U_opt, void* Y_opt, void* stream);
+
+/* Test hook: copies the secrets of a mixing object to caller DEVICE buffers (any may be NULL):
+ * A and A_inv as float n x n (dense), S as float k_shield x d (dense; valid after gelo_mix).
+ * attempt / kappa are HOST pointers: the accepted attempt number and the library's estimate of
+ * kappa_2(A) (1 for ORTHOGONAL). */
+gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* mixing, float* A, float* A_inv,
+                               float* S, int* attempt, float* kappa, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GELO_H */

@@ -1,0 +1,455 @@
+// C ABI of the GELO library (see include/gelo.h): argument checks, the life cycle of
+// contexts and per-batch mixing objects, and the kernel sequences behind each call.
+// The call structure follows the three phases of the protocol (Section 3.2):
+// trusted side (sample, mix) -> accelerator (project) -> trusted side (unmix).
+#include "../../include/gelo.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <new>
+#include <string>
+#include <unordered_set>
+#include <vector>
+
+#include "gelo_internal.h"
+
+using namespace gelo;
+
+namespace {
+constexpr float kConditionedBeta = 0.25f;
+constexpr int kKappaIterations = 64;
+constexpr uint32_t kStreamMixing = 0, kStreamShield = 1, kStreamPerturb = 2;
+}
+
+struct gelo_mixing {
+    int kind, n_data, k, n, d, dtype;
+    int64_t ldk;                 // leading dimension of A / A^-1 (n rounded up to 64), zero padded
+    void* block;                 // one device allocation holding everything below
+    size_t block_bytes;
+    float* A32; float* Ainv32;
+    uint16_t* A16; uint16_t* Ainv16;
+    float* GS;                   // k x d shield directions
+    float* gsnorm;               // k
+    void* S;                     // k x d shield rows in the compute dtype
+    float* rownorm;              // n_data
+    float* stat;                 // [0] row-norm statistic of H, [1] kappa estimate
+    int attempt;
+    float kappa;                 // host copy (GAUSSIAN); < 0: still only on the device
+    bool in_use, mixed, consumed;
+    uint64_t batch_id;
+    hipEvent_t ready;            // recorded when sampling has been enqueued
+    hipEvent_t released;         // recorded when the object went back to the pool
+    hipStream_t sample_stream, last_stream;
+};
+
+struct gelo_ctx {
+    int device;
+    uint64_t seed;
+    bool allow_reuse;
+    std::unordered_set<uint64_t> used_batches;
+    std::string err;
+    void* factor_ws; size_t factor_ws_bytes;
+    void* chain_ws;  size_t chain_ws_bytes;
+    float* host_scalars;         // pinned: kappa read-back
+    int* host_flag;
+    std::vector<gelo_mixing*> pool;
+};
+
+namespace {
+
+gelo_status fail(gelo_ctx* ctx, gelo_status st, const char* fmt, ...) {
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return st;
+}
+
+gelo_status hip_fail(gelo_ctx* ctx, hipError_t e, const char* what) {
+    return fail(ctx, GELO_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define GELO_HIP(ctx, expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail(ctx, e_, #expr); } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+size_t elem_size(int dtype) { return dtype == GELO_BF16 ? 2 : 4; }
+size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+gelo_status grow(gelo_ctx* ctx, void** buf, size_t* have, size_t need) {
+    if (*have >= need) return GELO_OK;
+    if (*buf) {
+        GELO_HIP(ctx, hipDeviceSynchronize());      // kernels of earlier calls may still use the old buffer
+        GELO_HIP(ctx, hipFree(*buf));
+        *buf = nullptr; *have = 0;
+    }
+    hipError_t e = hipMalloc(buf, need);
+    if (e != hipSuccess) { *buf = nullptr; return fail(ctx, GELO_ENOMEM, "hipMalloc(%zu) failed: %s", need, hipGetErrorString(e)); }
+    *have = need;
+    return GELO_OK;
+}
+
+gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, gelo_mixing** out) {
+    for (gelo_mixing* m : ctx->pool) {
+        if (!m->in_use && m->n_data == n_data && m->k == k && m->d == d && m->dtype == dtype) { *out = m; return GELO_OK; }
+    }
+    gelo_mixing* m = new (std::nothrow) gelo_mixing();
+    if (!m) return fail(ctx, GELO_ENOMEM, "host allocation failed");
+    m->n_data = n_data; m->k = k; m->n = n_data + k; m->d = d; m->dtype = dtype;
+    m->ldk = round_up(m->n, 64);
+    const size_t mat32 = up256((size_t)m->n * m->ldk * 4), mat16 = up256((size_t)m->n * m->ldk * 2);
+    const size_t gs = up256((size_t)(k > 0 ? k : 1) * d * 4), s = up256((size_t)(k > 0 ? k : 1) * d * elem_size(dtype));
+    const size_t small = up256((size_t)(k + 1) * 4) + up256((size_t)n_data * 4) + 256;
+    m->block_bytes = 2 * mat32 + (dtype == GELO_BF16 ? 2 * mat16 : 0) + gs + s + small;
+    hipError_t e = hipMalloc(&m->block, m->block_bytes);
+    if (e != hipSuccess) { delete m; return fail(ctx, GELO_ENOMEM, "hipMalloc(%zu) failed: %s", m->block_bytes, hipGetErrorString(e)); }
+    char* p = (char*)m->block;
+    m->A32 = (float*)p; p += mat32;
+    m->Ainv32 = (float*)p; p += mat32;
+    m->A16 = m->Ainv16 = nullptr;
+    if (dtype == GELO_BF16) { m->A16 = (uint16_t*)p; p += mat16; m->Ainv16 = (uint16_t*)p; p += mat16; }
+    m->GS = (float*)p; p += gs;
+    m->S = p; p += s;
+    m->gsnorm = (float*)p; p += up256((size_t)(k + 1) * 4);
+    m->rownorm = (float*)p; p += up256((size_t)n_data * 4);
+    m->stat = (float*)p;
+    if (hipEventCreateWithFlags(&m->ready, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m->released, hipEventDisableTiming) != hipSuccess) {
+        hipFree(m->block); delete m;
+        return fail(ctx, GELO_EHIP, "hipEventCreate failed");
+    }
+    m->last_stream = nullptr;
+    ctx->pool.push_back(m);
+    *out = m;
+    return GELO_OK;
+}
+
+bool owns(const gelo_ctx* ctx, const gelo_mixing* m) {
+    for (const gelo_mixing* q : ctx->pool) if (q == m) return true;
+    return false;
+}
+
+gelo_status run_gemm(gelo_ctx* ctx, int dtype, const GemmOperands& g, hipStream_t s) {
+    hipError_t e = dtype == GELO_BF16 ? gemm_bf16(g, s) : gemm_f32(g, s);
+    if (e != hipSuccess) return hip_fail(ctx, e, "GEMM launch");
+    return GELO_OK;
+}
+
+gelo_status check_matrix(gelo_ctx* ctx, const char* name, const void* p, int64_t ld, int cols) {
+    if (!p) return fail(ctx, GELO_EINVAL, "%s is NULL", name);
+    if (!aligned16(p)) return fail(ctx, GELO_EALIGN, "%s is not 16-byte aligned", name);
+    if (ld < cols) return fail(ctx, GELO_EINVAL, "leading dimension of %s (%lld) is below its width (%d)", name, (long long)ld, cols);
+    if (ld % 8 != 0) return fail(ctx, GELO_EALIGN, "leading dimension of %s (%lld) is not a multiple of 8", name, (long long)ld);
+    return GELO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* gelo_status_string(gelo_status s) {
+    switch (s) {
+        case GELO_OK: return "ok";
+        case GELO_EINVAL: return "invalid argument";
+        case GELO_ESHAPE: return "unsupported shape";
+        case GELO_EDTYPE: return "dtype mismatch";
+        case GELO_EALIGN: return "misaligned pointer or leading dimension";
+        case GELO_ENOMEM: return "out of memory";
+        case GELO_ECOND: return "no well-conditioned draw within the attempt budget";
+        case GELO_ESINGULAR: return "singular mixing matrix";
+        case GELO_EREUSE: return "batch id or mixing object reused";
+        case GELO_ESTATE: return "call out of order";
+        case GELO_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_batch_reuse) {
+    if (!out) return GELO_EINVAL;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return GELO_EINVAL;
+    if (hipSetDevice(device) != hipSuccess) return GELO_EHIP;
+    gelo_ctx* ctx = new (std::nothrow) gelo_ctx();
+    if (!ctx) return GELO_ENOMEM;
+    ctx->device = device; ctx->seed = seed; ctx->allow_reuse = allow_batch_reuse != 0;
+    ctx->factor_ws = ctx->chain_ws = nullptr; ctx->factor_ws_bytes = ctx->chain_ws_bytes = 0;
+    ctx->host_scalars = nullptr; ctx->host_flag = nullptr;
+    if (hipHostMalloc((void**)&ctx->host_scalars, 64, hipHostMallocDefault) != hipSuccess) { delete ctx; return GELO_ENOMEM; }
+    ctx->host_flag = (int*)(ctx->host_scalars + 8);
+    if (gemm_bf16_init() != hipSuccess || gemm_f32_init() != hipSuccess) {
+        hipHostFree(ctx->host_scalars); delete ctx; return GELO_EHIP;
+    }
+    *out = ctx;
+    return GELO_OK;
+}
+
+gelo_status gelo_destroy(gelo_ctx* ctx) {
+    if (!ctx) return GELO_EINVAL;
+    hipSetDevice(ctx->device);
+    hipDeviceSynchronize();
+    for (gelo_mixing* m : ctx->pool) {
+        hipEventDestroy(m->ready); hipEventDestroy(m->released);
+        hipFree(m->block);
+        delete m;
+    }
+    if (ctx->factor_ws) (void)hipFree(ctx->factor_ws);
+    if (ctx->chain_ws) (void)hipFree(ctx->chain_ws);
+    if (ctx->host_scalars) (void)hipHostFree(ctx->host_scalars);
+    delete ctx;
+    return GELO_OK;
+}
+
+const char* gelo_last_error(const gelo_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d,
+                               gelo_dtype dtype, double cond_max, int max_attempts,
+                               uint64_t batch_id, gelo_mixing** out, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!out) return fail(ctx, GELO_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (kind != GELO_ORTHOGONAL && kind != GELO_GAUSSIAN && kind != GELO_CONDITIONED) return fail(ctx, GELO_EINVAL, "unknown kind %d", (int)kind);
+    if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
+    if (n_data < 1 || k_shield < 0 || d < 1) return fail(ctx, GELO_EINVAL, "n_data=%d k_shield=%d d=%d", n_data, k_shield, d);
+    if (d % 8 != 0) return fail(ctx, GELO_EALIGN, "d=%d is not a multiple of 8", d);
+    const int64_t n64 = (int64_t)n_data + k_shield;
+    if (n64 > GELO_MAX_N) return fail(ctx, GELO_ESHAPE, "n = n_data + k_shield = %lld exceeds GELO_MAX_N = %d", (long long)n64, GELO_MAX_N);
+    const int n = (int)n64;
+    if (kind == GELO_GAUSSIAN) {
+        if (!(cond_max >= 1.0)) return fail(ctx, GELO_EINVAL, "cond_max=%g must be >= 1", cond_max);
+        if (max_attempts < 1 || max_attempts > GELO_MAX_ATTEMPTS) return fail(ctx, GELO_EINVAL, "max_attempts=%d outside 1..%d", max_attempts, GELO_MAX_ATTEMPTS);
+    }
+    if (!ctx->allow_reuse && ctx->used_batches.count(batch_id))
+        return fail(ctx, GELO_EREUSE, "batch id %llu was already used on this context", (unsigned long long)batch_id);
+
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    gelo_status st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, factor_workspace_bytes(n));
+    if (st != GELO_OK) return st;
+    FactorWorkspace ws;
+    factor_workspace_carve(ctx->factor_ws, n, &ws);
+    gelo_mixing* m = nullptr;
+    st = acquire_mixing(ctx, n_data, k_shield, d, dtype, &m);
+    if (st != GELO_OK) return st;
+    if (m->last_stream != nullptr || m->mixed) GELO_HIP(ctx, hipStreamWaitEvent(s, m->released, 0));
+
+    PhiloxStream ps;
+    ps.key0 = (uint32_t)ctx->seed; ps.key1 = (uint32_t)(ctx->seed >> 32);
+    ps.c2 = (uint32_t)batch_id; ps.c3 = (uint32_t)(batch_id >> 32);
+    const int64_t ld = ws.ld, ldk = m->ldk;
+    const bool bf = dtype == GELO_BF16;
+    m->kind = kind; m->attempt = 0; m->kappa = 1.0f;
+
+    auto orthogonal_into_X = [&]() -> hipError_t {
+        ps.c1 = kStreamMixing << 8;
+        hipError_t e = fill_normal(ws.M, ld, n, n, ps, 1.0f, s);
+        if (e == hipSuccess) e = pad_matrix(ws.M, ld, n, ws.n_pad, 0, s);
+        if (e == hipSuccess) e = householder_qr(ws, s);
+        return e;
+    };
+
+    if (kind == GELO_ORTHOGONAL) {
+        GELO_HIP(ctx, orthogonal_into_X());
+        // A = Q diag(sign r_ii); A^-1 = A^T
+        GELO_HIP(ctx, emit_matrix(ws.X, ld, ws.rdiag, n, ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s));
+    } else {
+        bool accepted = false;
+        const int attempts = kind == GELO_GAUSSIAN ? max_attempts : 1;
+        bool singular_last = false;
+        for (int attempt = 0; attempt < attempts && !accepted; ++attempt) {
+            if (kind == GELO_GAUSSIAN) {
+                ps.c1 = (kStreamMixing << 8) | (uint32_t)attempt;
+                GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f / std::sqrt((float)n), s));
+                GELO_HIP(ctx, emit_matrix(ws.M, ld, nullptr, n, ldk, m->A32, m->A16, nullptr, nullptr, s));
+            } else {
+                GELO_HIP(ctx, orthogonal_into_X());
+                GELO_HIP(ctx, emit_matrix(ws.X, ld, ws.rdiag, n, ldk, m->A32, nullptr, nullptr, nullptr, s));
+                ps.c1 = kStreamPerturb << 8;
+                GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f, s));
+                GELO_HIP(ctx, axpy_matrix(m->A32, ldk, ws.M, ld, n, n, kConditionedBeta / std::sqrt((float)n), s));
+                GELO_HIP(ctx, emit_matrix(m->A32, ldk, nullptr, n, ld, ws.M, nullptr, nullptr, nullptr, s));
+                if (bf) GELO_HIP(ctx, emit_matrix(m->A32, ldk, nullptr, n, ldk, nullptr, m->A16, nullptr, nullptr, s));
+            }
+            GELO_HIP(ctx, pad_matrix(ws.M, ld, n, ws.n_pad, 1, s));
+            GELO_HIP(ctx, lu_inverse(ws, s));
+            GELO_HIP(ctx, emit_matrix(ws.X, ld, nullptr, n, ldk, m->Ainv32, m->Ainv16, nullptr, nullptr, s));
+            GELO_HIP(ctx, kappa_estimate(m->A32, m->Ainv32, ldk, n, ws, kKappaIterations, s));
+            GELO_HIP(ctx, hipMemcpyAsync(m->stat + 1, ws.scalars, sizeof(float), hipMemcpyDeviceToDevice, s));
+            if (kind == GELO_GAUSSIAN) {
+                // the one host synchronisation of the library: accept or redraw
+                GELO_HIP(ctx, hipMemcpyAsync(ctx->host_scalars, ws.scalars, sizeof(float), hipMemcpyDeviceToHost, s));
+                GELO_HIP(ctx, hipMemcpyAsync(ctx->host_flag, ws.flag, sizeof(int), hipMemcpyDeviceToHost, s));
+                GELO_HIP(ctx, hipStreamSynchronize(s));
+                singular_last = *ctx->host_flag != 0;
+                const float kappa = ctx->host_scalars[0];
+                if (!singular_last && kappa <= (float)cond_max) { accepted = true; m->attempt = attempt; m->kappa = kappa; }
+            } else {
+                accepted = true; m->kappa = -1.0f;
+            }
+        }
+        if (!accepted) {
+            if (singular_last) return fail(ctx, GELO_ESINGULAR, "zero pivot in the last of %d draws", attempts);
+            return fail(ctx, GELO_ECOND, "no draw with kappa <= %g within %d attempts", cond_max, attempts);
+        }
+    }
+    if (k_shield > 0) {
+        ps.c1 = kStreamShield << 8;
+        GELO_HIP(ctx, fill_normal(m->GS, d, k_shield, d, ps, 1.0f, s));
+        GELO_HIP(ctx, row_norms(m->GS, 0, d, k_shield, d, m->gsnorm, s));
+    }
+    GELO_HIP(ctx, hipEventRecord(m->ready, s));
+    m->in_use = true; m->mixed = false; m->consumed = false; m->batch_id = batch_id;
+    m->sample_stream = s; m->last_stream = s;
+    if (!ctx->allow_reuse) ctx->used_batches.insert(batch_id);
+    *out = m;
+    return GELO_OK;
+}
+
+gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh,
+                     float shield_scale, gelo_norm_stat stat, void* U, int64_t ldu, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or freed");
+    if (stat != GELO_NORM_MEDIAN && stat != GELO_NORM_MEAN) return fail(ctx, GELO_EINVAL, "unknown norm statistic %d", (int)stat);
+    if (m->k > 0 && !(shield_scale > 0.f)) return fail(ctx, GELO_EINVAL, "shield_scale=%g must be positive", (double)shield_scale);
+    gelo_status st = check_matrix(ctx, "H", H, ldh, m->d);
+    if (st == GELO_OK) st = check_matrix(ctx, "U", U, ldu, m->d);
+    if (st != GELO_OK) return st;
+    if (!ctx->allow_reuse && m->mixed) return fail(ctx, GELO_EREUSE, "this mixing object has already mixed a batch");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
+    const bool bf = m->dtype == GELO_BF16;
+    if (m->k > 0) {
+        GELO_HIP(ctx, row_norms(H, bf, ldh, m->n_data, m->d, m->rownorm, s));
+        GELO_HIP(ctx, norm_statistic(m->rownorm, m->n_data, (int)stat, m->stat, s));
+        GELO_HIP(ctx, make_shields(m->GS, m->d, m->gsnorm, m->stat, shield_scale, m->k, m->d, m->S, bf, m->d, s));
+    }
+    GemmOperands g;
+    g.A = bf ? (const void*)m->A16 : (const void*)m->A32; g.lda = m->ldk;
+    g.B0 = H; g.ldb0 = ldh; g.K0 = m->n_data;
+    g.B1 = m->S; g.ldb1 = m->d;
+    g.C = U; g.ldc = ldu;
+    g.M = m->n; g.N = m->d; g.K = m->n;
+    st = run_gemm(ctx, m->dtype, g, s);
+    if (st != GELO_OK) return st;
+    m->mixed = true; m->last_stream = s;
+    return GELO_OK;
+}
+
+gelo_status gelo_project(gelo_ctx* ctx, gelo_dtype dtype, int n, int d, int p,
+                         const void* U, int64_t ldu, const void* W, int64_t ldw,
+                         void* Y, int64_t ldy, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
+    if (n < 1 || d < 1 || p < 1) return fail(ctx, GELO_EINVAL, "n=%d d=%d p=%d", n, d, p);
+    if (d % 8 != 0 || p % 8 != 0) return fail(ctx, GELO_EALIGN, "d=%d and p=%d must be multiples of 8", d, p);
+    gelo_status st = check_matrix(ctx, "U", U, ldu, d);
+    if (st == GELO_OK) st = check_matrix(ctx, "W", W, ldw, p);
+    if (st == GELO_OK) st = check_matrix(ctx, "Y", Y, ldy, p);
+    if (st != GELO_OK) return st;
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    GemmOperands g;
+    g.A = U; g.lda = ldu;
+    g.B0 = W; g.ldb0 = ldw; g.K0 = d;
+    g.B1 = W; g.ldb1 = ldw;
+    g.C = Y; g.ldc = ldy;
+    g.M = n; g.N = p; g.K = d;
+    return run_gemm(ctx, dtype, g, (hipStream_t)stream);
+}
+
+gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* m, int p, const void* Y, int64_t ldy,
+                       void* Z, int64_t ldz, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or freed");
+    if (p < 1) return fail(ctx, GELO_EINVAL, "p=%d", p);
+    if (p % 8 != 0) return fail(ctx, GELO_EALIGN, "p=%d is not a multiple of 8", p);
+    gelo_status st = check_matrix(ctx, "Y", Y, ldy, p);
+    if (st == GELO_OK) st = check_matrix(ctx, "Z", Z, ldz, p);
+    if (st != GELO_OK) return st;
+    if (!ctx->allow_reuse && m->consumed) return fail(ctx, GELO_EREUSE, "this mixing object has already been consumed");
+    if (!m->mixed) return fail(ctx, GELO_ESTATE, "gelo_unmix before gelo_mix");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
+    const bool bf = m->dtype == GELO_BF16;
+    GemmOperands g;
+    g.A = bf ? (const void*)m->Ainv16 : (const void*)m->Ainv32; g.lda = m->ldk;   // rows 0..n_data-1 of A^-1
+    g.B0 = Y; g.ldb0 = ldy; g.K0 = m->n;
+    g.B1 = Y; g.ldb1 = ldy;
+    g.C = Z; g.ldc = ldz;
+    g.M = m->n_data; g.N = p; g.K = m->n;
+    st = run_gemm(ctx, m->dtype, g, s);
+    if (st != GELO_OK) return st;
+    m->consumed = true; m->last_stream = s;
+    return GELO_OK;
+}
+
+gelo_status gelo_mixing_free(gelo_ctx* ctx, gelo_mixing* m) {
+    if (!ctx) return GELO_EINVAL;
+    if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or already freed");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    GELO_HIP(ctx, hipEventRecord(m->released, m->last_stream));
+    m->in_use = false;
+    return GELO_OK;
+}
+
+gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_data, int k_shield,
+                             int d, int p, const void* H, const void* W, float shield_scale,
+                             gelo_norm_stat stat, double cond_max, int max_attempts, uint64_t batch_id,
+                             void* Z, void* U_opt, void* Y_opt, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!H || !W || !Z) return fail(ctx, GELO_EINVAL, "H, W and Z must not be NULL");
+    if (p < 1 || p % 8 != 0) return fail(ctx, p < 1 ? GELO_EINVAL : GELO_EALIGN, "p=%d must be a positive multiple of 8", p);
+    if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
+    if (n_data < 1 || k_shield < 0 || d < 1) return fail(ctx, GELO_EINVAL, "n_data=%d k_shield=%d d=%d", n_data, k_shield, d);
+    const int64_t n = (int64_t)n_data + k_shield;
+    void* U = U_opt; void* Y = Y_opt;
+    if (!U || !Y) {
+        GELO_HIP(ctx, hipSetDevice(ctx->device));
+        const size_t ub = up256((size_t)n * d * elem_size(dtype)), yb = up256((size_t)n * p * elem_size(dtype));
+        gelo_status st = grow(ctx, &ctx->chain_ws, &ctx->chain_ws_bytes, ub + yb);
+        if (st != GELO_OK) return st;
+        if (!U) U = ctx->chain_ws;
+        if (!Y) Y = (char*)ctx->chain_ws + ub;
+    }
+    gelo_mixing* m = nullptr;
+    gelo_status st = gelo_sample_mixing(ctx, kind, n_data, k_shield, d, dtype, cond_max, max_attempts, batch_id, &m, stream);
+    if (st != GELO_OK) return st;
+    st = gelo_mix(ctx, m, H, d, shield_scale, stat, U, d, stream);
+    if (st == GELO_OK) st = gelo_project(ctx, dtype, (int)n, d, p, U, d, W, p, Y, p, stream);
+    if (st == GELO_OK) st = gelo_unmix(ctx, m, p, Y, p, Z, p, stream);
+    const std::string keep = ctx->err;
+    gelo_mixing_free(ctx, m);
+    if (st != GELO_OK) ctx->err = keep;
+    return st;
+}
+
+gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* m, float* A, float* A_inv,
+                               float* S, int* attempt, float* kappa, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or freed");
+    if (S && m->k > 0 && !m->mixed) return fail(ctx, GELO_ESTATE, "shield rows exist only after gelo_mix");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
+    if (A) GELO_HIP(ctx, export_dense(m->A32, 0, m->ldk, m->n, m->n, A, s));
+    if (A_inv) GELO_HIP(ctx, export_dense(m->Ainv32, 0, m->ldk, m->n, m->n, A_inv, s));
+    if (S && m->k > 0) GELO_HIP(ctx, export_dense(m->S, m->dtype == GELO_BF16, m->d, m->k, m->d, S, s));
+    if (attempt) *attempt = m->attempt;
+    if (kappa) {
+        if (m->kappa < 0.f) {
+            GELO_HIP(ctx, hipMemcpyAsync(ctx->host_scalars, m->stat + 1, sizeof(float), hipMemcpyDeviceToHost, s));
+            GELO_HIP(ctx, hipStreamSynchronize(s));
+            *kappa = ctx->host_scalars[0];
+        } else {
+            *kappa = m->kappa;
+        }
+    }
+    return GELO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,100 @@
+// Internal declarations shared by the HIP translation units of the GELO library.
+// Launchers validate nothing: the C ABI layer (api.hip) checks shapes, alignment
+// and bounds on the host before any kernel is enqueued.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gelo {
+
+constexpr int kPanel = 16;          // column-panel width of the QR / LU factorisations
+constexpr int kMaxN = 5120;         // 1024 threads x 5 register-resident rows in the panel kernels
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// ---------------------------------------------------------------- GEMMs ----
+// C[M x N] = A[M x K] * B[K x N], row-major.  B is given as two row segments:
+// rows [0, K0) come from B0 (ldb0), rows [K0, K) from B1 (ldb1); this is how
+// [H ; S] is consumed without a concatenated copy.  Requirements checked by the
+// caller: N % 8 == 0; every pointer 16-byte aligned; leading dimensions multiples
+// of 8 (bf16) / 4 (f32); A readable and ZERO in columns [K, round_up(K, 8)).
+struct GemmOperands {
+    const void* A;  int64_t lda;
+    const void* B0; int64_t ldb0; int K0;
+    const void* B1; int64_t ldb1;
+    void* C;        int64_t ldc;
+    int M, N, K;
+};
+hipError_t gemm_bf16(const GemmOperands& g, hipStream_t stream);
+hipError_t gemm_f32(const GemmOperands& g, hipStream_t stream);
+hipError_t gemm_bf16_init();        // one-time kernel attribute set-up (large dynamic LDS)
+hipError_t gemm_f32_init();
+
+// --------------------------------------------------------------- sampler ---
+struct PhiloxStream {
+    uint32_t key0, key1;            // seed low / high
+    uint32_t c1, c2, c3;            // (stream << 8 | attempt), batch id low, batch id high
+};
+// out[r * ld + c] = scale * N(0,1) for r < rows, c < cols; element e = r*cols + c is output
+// e % 4 of Philox block e / 4 (counter word 0 = block index).
+hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale,
+                       hipStream_t stream);
+// dst[r * ldd + c] += scale * src[r * lds + c] over an rows x cols block
+hipError_t axpy_matrix(float* dst, int64_t ldd, const float* src, int64_t lds, int rows, int cols,
+                       float scale, hipStream_t stream);
+// norms[r] = || X[r, 0:cols] ||_2, X float or bf16
+hipError_t row_norms(const void* X, int is_bf16, int64_t ld, int rows, int cols, float* norms,
+                     hipStream_t stream);
+// *out = median (stat 0; even count: mean of the two middle values) or mean (stat 1) of v[0:count]
+hipError_t norm_statistic(const float* v, int count, int stat, float* out, hipStream_t stream);
+// S[i, :] = G[i, :] * (scale * *stat / gnorm[i]), written as float or bf16 (lds elements per row)
+hipError_t make_shields(const float* G, int64_t ldg, const float* gnorm, const float* stat, float scale,
+                        int k, int d, void* S, int is_bf16, int64_t lds, hipStream_t stream);
+// Writes an n x n float matrix (src, optional per-column sign flip from `rdiag` < 0) into the
+// mixing buffers: dst32 / dst16 get the matrix, dstT32 / dstT16 its transpose (any may be null).
+// Every destination has `ldd` elements per row and its columns [n, ldd) are zero-filled.
+hipError_t emit_matrix(const float* src, int64_t lds, const float* rdiag, int n, int64_t ldd,
+                       float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16,
+                       hipStream_t stream);
+// dense float copy out[r * cols + c] = (float) src[r * ld + c]
+hipError_t export_dense(const void* src, int is_bf16, int64_t ld, int rows, int cols, float* out,
+                        hipStream_t stream);
+
+// --------------------------------------------------------- factorisations --
+// Workspace for one n_pad x ld float problem (n_pad = round_up(n, kPanel), ld = round_up(n, 64)).
+struct FactorWorkspace {
+    float* M;        // the matrix being factorised (G, then R + reflectors / L\U)
+    float* X;        // the result being accumulated (Q, or A^-1)
+    float* Vc;       // per panel: reflector block V with explicit unit diagonal, zeros above
+    float* VT;       // per panel: V * T
+    float* VTt;      // per panel: V * T^T
+    float* Wpart;    // partial products of the skinny reductions
+    float* W;        // kPanel x ld reduced products
+    float* rdiag;    // n_pad: diagonal of R
+    float* vec;      // 4 * ld floats for the power iterations
+    int*   piv;      // n_pad pivot rows
+    int*   flag;     // singular-pivot flag
+    float* scalars;  // [0] kappa estimate, [1] sigma_max^2, [2] 1/sigma_min^2
+    int n_pad; int64_t ld;
+    int wpart_chunks;   // row chunks Wpart can hold
+};
+size_t factor_workspace_bytes(int n);
+void factor_workspace_carve(void* base, int n, FactorWorkspace* ws);
+
+// ws.M holds an n_pad x n_pad matrix (rows/cols beyond n zero).  On return ws.X holds Q of its
+// Householder QR (identity in the padding block) and ws.rdiag the diagonal of R.
+hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t stream);
+// ws.M holds an n_pad x n_pad matrix with an identity block in the padding.  On return ws.X holds
+// its inverse (via row-pivoted LU), *ws.flag != 0 if a zero pivot was met.
+hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t stream);
+// kappa_2 estimate of the n x n matrix A (lda) with inverse Ainv by power iteration on A^T A and
+// Ainv Ainv^T; uses ws.M / ws.X as scratch for the two transposes; result in ws.scalars[0].
+hipError_t kappa_estimate(const float* A, const float* Ainv, int64_t lda, int n, const FactorWorkspace& ws,
+                          int iterations, hipStream_t stream);
+hipError_t set_identity(float* X, int64_t ld, int n_pad, hipStream_t stream);
+hipError_t zero_ints(int* p, int count, hipStream_t stream);
+// zero rows/cols [n, n_pad) of M; optionally put ones on that part of the diagonal
+hipError_t pad_matrix(float* M, int64_t ld, int n, int n_pad, int identity_block, hipStream_t stream);
+
+}  // namespace gelo

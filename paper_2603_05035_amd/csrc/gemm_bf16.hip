@@ -1,0 +1,248 @@
+// bf16 x bf16 -> bf16 GEMM with fp32 accumulation on the gfx950 matrix cores.
+//
+// One kernel serves the three products of the GELO chain (Section 3.2, eqs. 1-3):
+// mix U = A [H;S], project Y = U W and unmix Z = A^-1 Y.  All operands are
+// row-major, so the right-hand operand arrives with the contraction index as
+// its slow axis; the kernel turns 8x4 register blocks of it around with byte
+// permutes to feed v_mfma_f32_32x32x16_bf16, whose lanes want 8 consecutive
+// contraction elements each.
+//
+// Work decomposition: a workgroup owns a BM x BN tile of C and walks K in
+// steps of 64 through a double-buffered LDS stage; a wave owns WM x 128 of the
+// tile as (WM/32) x 4 accumulators of 32 x 32.  The four accumulators along N
+// are column-interleaved (lane j of accumulator c holds column 4j + c), which
+// makes both the LDS reads of B (8 bytes per lane) and the stores of C (4
+// bf16 per lane and row) contiguous across lanes.
+#include "gelo_internal.h"
+
+namespace gelo {
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int BK = 64;
+constexpr int WN = 128;
+constexpr int A_PITCH = BK + 8;   // bf16 elements; 144-byte rows keep 16-byte row reads conflict-free
+
+struct Bf16Args {
+    const uint16_t* A;  int64_t lda;
+    const uint16_t* B0; int64_t ldb0; int K0;
+    const uint16_t* B1; int64_t ldb1;
+    uint16_t* C;        int64_t ldc;
+    int M, N, K;
+    int tiles_m, tiles_n;
+};
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    bf16x2_t v = {(__bf16)lo, (__bf16)hi};      // round-to-nearest-even
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// Workgroups are dealt to the 8 XCDs round-robin; give each XCD (own L2) a contiguous run of
+// tiles, and inside a run walk GROUP_M tile-rows before moving along N so that tiles in flight
+// share A row panels and B column panels.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) {
+    const int total = tiles_m * tiles_n;
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int base = total >> 3, rem = total & 7;
+    const int lid = xcd * base + (xcd < rem ? xcd : rem) + slot;
+    constexpr int GROUP_M = 8;
+    const int per_group = GROUP_M * tiles_n;
+    const int group = lid / per_group;
+    const int first_m = group * GROUP_M;
+    const int gsz = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+    const int in_group = lid - group * per_group;
+    *tm = first_m + in_group % gsz;
+    *tn = in_group / gsz;
+}
+
+template <int BM, int BN, int WM>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64)
+void gemm_bf16_kernel(Bf16Args g) {
+    constexpr int WAVES_N = BN / WN;
+    constexpr int NT = (BM / WM) * WAVES_N * 64;
+    constexpr int MT = WM / 32;
+    constexpr int A_TILE = BM * A_PITCH;          // elements
+    constexpr int B_TILE = BK * BN;
+    constexpr int A_CHUNKS = BM * (BK / 8) / NT;  // 16-byte chunks per thread
+    constexpr int B_CHUNKS = BK * (BN / 8) / NT;
+    static_assert(BM * (BK / 8) % NT == 0 && BK * (BN / 8) % NT == 0, "tile / thread mismatch");
+
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    uint16_t* As = smem;                  // [2][BM][A_PITCH]
+    uint16_t* Bs = smem + 2 * A_TILE;     // [2][BK][BN]
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, &tm, &tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int j = lane & 31, grp = lane >> 5;
+    const int KA = (g.K + 7) & ~7;        // extent of A's readable (zero padded) columns
+    const int k_tiles = (g.K + BK - 1) / BK;
+
+    u32x4_t a_stage[A_CHUNKS], b_stage[B_CHUNKS];
+
+    auto load_global = [&](int kt) {
+        const int k0 = kt * BK;
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const int id = tid + i * NT;
+            const int r = id >> 3, c = id & 7;
+            int row = m0 + r;
+            row = row < g.M ? row : g.M - 1;
+            const int gk = k0 + c * 8;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (gk < KA) v = *reinterpret_cast<const u32x4_t*>(g.A + (int64_t)row * g.lda + gk);
+            a_stage[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            const int id = tid + i * NT;
+            const int r = id / (BN / 8), c = id % (BN / 8);
+            const int gk = k0 + r, gn = n0 + c * 8;
+            u32x4_t v = {0u, 0u, 0u, 0u};
+            if (gk < g.K && gn < g.N) {
+                const uint16_t* p = gk < g.K0 ? g.B0 + (int64_t)gk * g.ldb0 + gn
+                                              : g.B1 + (int64_t)(gk - g.K0) * g.ldb1 + gn;
+                v = *reinterpret_cast<const u32x4_t*>(p);
+            }
+            b_stage[i] = v;
+        }
+    };
+    auto store_lds = [&](int buf) {
+        uint16_t* as = As + buf * A_TILE;
+        uint16_t* bs = Bs + buf * B_TILE;
+#pragma unroll
+        for (int i = 0; i < A_CHUNKS; ++i) {
+            const int id = tid + i * NT;
+            const int r = id >> 3, c = id & 7;
+            *reinterpret_cast<u32x4_t*>(as + r * A_PITCH + c * 8) = a_stage[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_CHUNKS; ++i) {
+            const int id = tid + i * NT;
+            const int r = id / (BN / 8), c = id % (BN / 8);
+            *reinterpret_cast<u32x4_t*>(bs + r * BN + c * 8) = b_stage[i];
+        }
+    };
+
+    f32x16_t acc[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0.f;
+
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+
+    for (int kt = 0; kt < k_tiles; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < k_tiles) load_global(kt + 1);
+
+        const uint16_t* as = As + buf * A_TILE + (wm * WM + j) * A_PITCH + grp * 8;
+        const uint16_t* bs = Bs + buf * B_TILE + (grp * 8) * BN + wn * WN + 4 * j;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8_t a_frag[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                a_frag[mt] = *reinterpret_cast<const bf16x8_t*>(as + mt * 32 * A_PITCH + ks * 16);
+            u32x2_t b_raw[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                b_raw[i] = *reinterpret_cast<const u32x2_t*>(bs + (ks * 16 + i) * BN);
+            bf16x8_t b_frag[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                u32x4_t t;
+                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+                    t[m] = __builtin_amdgcn_perm(b_raw[2 * m + 1][c >> 1], b_raw[2 * m][c >> 1], sel);
+                b_frag[c] = __builtin_bit_cast(bf16x8_t, t);
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag[mt], b_frag[c], acc[mt][c], 0, 0, 0);
+        }
+
+        if (kt + 1 < k_tiles) store_lds(buf ^ 1);
+        __syncthreads();
+    }
+
+    // accumulator element v of lane (j, grp): row 8*(v/4) + 4*grp + v%4, column j of the 32x32 tile
+    const int col = n0 + wn * WN + 4 * j;
+    if (col < g.N) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm * WM + mt * 32 + 8 * (v >> 2) + 4 * grp + (v & 3);
+                if (row < g.M) {
+                    u32x2_t out;
+                    out[0] = pack_bf16x2(acc[mt][0][v], acc[mt][1][v]);
+                    out[1] = pack_bf16x2(acc[mt][2][v], acc[mt][3][v]);
+                    *reinterpret_cast<u32x2_t*>(g.C + (int64_t)row * g.ldc + col) = out;
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM>
+constexpr size_t smem_bytes() { return 2 * (size_t)(BM * A_PITCH + BK * BN) * sizeof(uint16_t); }
+
+template <int BM, int BN, int WM>
+hipError_t launch(const GemmOperands& o, hipStream_t stream) {
+    Bf16Args a;
+    a.A = (const uint16_t*)o.A;   a.lda = o.lda;
+    a.B0 = (const uint16_t*)o.B0; a.ldb0 = o.ldb0; a.K0 = o.K0;
+    a.B1 = (const uint16_t*)o.B1; a.ldb1 = o.ldb1;
+    a.C = (uint16_t*)o.C;         a.ldc = o.ldc;
+    a.M = o.M; a.N = o.N; a.K = o.K;
+    a.tiles_m = (o.M + BM - 1) / BM;
+    a.tiles_n = (o.N + BN - 1) / BN;
+    constexpr int NT = (BM / WM) * (BN / WN) * 64;
+    const size_t lds_bytes = smem_bytes<BM, BN, WM>();
+    hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM>), dim3(a.tiles_m * a.tiles_n), dim3(NT),
+                       lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int WM>
+hipError_t allow_big_lds() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<BM, BN, WM>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BM, BN, WM>());
+}
+
+}  // namespace
+
+hipError_t gemm_bf16_init() {
+    hipError_t e = allow_big_lds<256, 256, 128>();
+    if (e != hipSuccess) return e;
+    e = allow_big_lds<128, 256, 64>();
+    if (e != hipSuccess) return e;
+    return allow_big_lds<128, 128, 64>();
+}
+
+// Tile choice: the largest tile whose grid still fills the 256 compute units.
+hipError_t gemm_bf16(const GemmOperands& o, hipStream_t stream) {
+    if (o.M <= 0 || o.N <= 0 || o.K <= 0) return hipSuccess;
+    auto tiles = [&](int bm, int bn) { return (int64_t)((o.M + bm - 1) / bm) * ((o.N + bn - 1) / bn); };
+    if (tiles(256, 256) >= 256) return launch<256, 256, 128>(o, stream);
+    if (tiles(128, 256) >= 256) return launch<128, 256, 64>(o, stream);
+    return launch<128, 128, 64>(o, stream);
+}
+
+}  // namespace gelo

@@ -1,0 +1,260 @@
+// Trusted-side sampling kernels: the Philox4x32-10 Gaussian source for the mixing
+// matrix A and the shield directions (Section 3.2 step 1.2; Section 3.2.1
+// Mitigation 2), the row-norm statistic of H that sets the shield scale, and the
+// kernels that write A / A^-1 into the layouts the GEMMs read.
+#include "gelo_internal.h"
+
+namespace gelo {
+namespace {
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies
+// and a word permutation, key advanced by Weyl constants between rounds.
+__device__ __forceinline__ void philox4x32_10(uint32_t& c0, uint32_t& c1, uint32_t& c2, uint32_t& c3,
+                                              uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+}
+
+// top 23 bits -> (2m + 1) 2^-24, exact in float, strictly inside (0, 1)
+__device__ __forceinline__ float uniform_open01(uint32_t w) {
+    return (float)(2u * (w >> 9) + 1u) * 5.9604644775390625e-08f;
+}
+
+__device__ __forceinline__ void box_muller(uint32_t wa, uint32_t wb, float* z0, float* z1) {
+    const float radius = sqrtf(-2.0f * logf(uniform_open01(wa)));
+    float s, c;
+    sincospif(2.0f * uniform_open01(wb), &s, &c);
+    *z0 = radius * c;
+    *z1 = radius * s;
+}
+
+__global__ __launch_bounds__(256)
+void fill_normal_kernel(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale) {
+    const int64_t total = (int64_t)rows * cols;
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (q * 4 >= total) return;
+    uint32_t c0 = (uint32_t)q, c1 = ps.c1, c2 = ps.c2, c3 = ps.c3;
+    philox4x32_10(c0, c1, c2, c3, ps.key0, ps.key1);
+    float z[4];
+    box_muller(c0, c1, &z[0], &z[1]);
+    box_muller(c2, c3, &z[2], &z[3]);
+    int64_t e = q * 4;
+    int r = (int)(e / cols), c = (int)(e % cols);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        if (e + t < total) out[(int64_t)r * ld + c] = scale * z[t];
+        if (++c == cols) { c = 0; ++r; }
+    }
+}
+
+__global__ __launch_bounds__(256)
+void axpy_matrix_kernel(float* dst, int64_t ldd, const float* src, int64_t lds, int rows, int cols, float scale) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int r = blockIdx.y;
+    if (c < cols && r < rows) dst[(int64_t)r * ldd + c] += scale * src[(int64_t)r * lds + c];
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t h) { return __uint_as_float(h << 16); }
+
+// one wave per row, fixed summation order
+template <bool BF16>
+__global__ __launch_bounds__(256)
+void row_norms_kernel(const void* X, int64_t ld, int rows, int cols, float* norms) {
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= rows) return;
+    float s = 0.f;
+    if (BF16) {
+        const uint16_t* p = (const uint16_t*)X + (int64_t)row * ld;
+        for (int c = lane * 8; c < cols; c += 64 * 8) {
+            const uint4 v = *reinterpret_cast<const uint4*>(p + c);
+            const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float lo = bf16_bits_to_float(w[t] & 0xFFFFu), hi = bf16_bits_to_float(w[t] >> 16);
+                s = fmaf(lo, lo, s);
+                s = fmaf(hi, hi, s);
+            }
+        }
+    } else {
+        const float* p = (const float*)X + (int64_t)row * ld;
+        for (int c = lane * 4; c < cols; c += 64 * 4) {
+            const float4 v = *reinterpret_cast<const float4*>(p + c);
+            s = fmaf(v.x, v.x, s); s = fmaf(v.y, v.y, s); s = fmaf(v.z, v.z, s); s = fmaf(v.w, v.w, s);
+        }
+    }
+    s = wave_sum(s);
+    if (lane == 0) norms[row] = sqrtf(s);
+}
+
+// Single workgroup.  Median: bitonic sort of the values (padded with +inf to a power of two)
+// in LDS, then the middle element(s).  Mean: tree sum in a fixed order.
+__global__ __launch_bounds__(1024)
+void norm_statistic_kernel(const float* v, int count, int stat, int padded, float* out) {
+    extern __shared__ float buf[];
+    const int tid = threadIdx.x;
+    if (stat == 1) {
+        float s = 0.f;
+        for (int i = tid; i < count; i += 1024) s += v[i];
+        buf[tid] = s;
+        __syncthreads();
+        for (int half = 512; half > 0; half >>= 1) {
+            if (tid < half) buf[tid] += buf[tid + half];
+            __syncthreads();
+        }
+        if (tid == 0) *out = buf[0] / (float)count;
+        return;
+    }
+    for (int i = tid; i < padded; i += 1024) buf[i] = i < count ? v[i] : __builtin_inff();
+    __syncthreads();
+    for (int size = 2; size <= padded; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            for (int i = tid; i < (padded >> 1); i += 1024) {
+                const int lo = 2 * i - (i & (stride - 1));     // index with bit `stride` clear
+                const int hi = lo + stride;
+                const bool ascending = (lo & size) == 0;
+                const float a = buf[lo], b = buf[hi];
+                if ((a > b) == ascending) { buf[lo] = b; buf[hi] = a; }
+            }
+            __syncthreads();
+        }
+    }
+    if (tid == 0) *out = (count & 1) ? buf[count >> 1] : 0.5f * (buf[(count >> 1) - 1] + buf[count >> 1]);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256)
+void make_shields_kernel(const float* G, int64_t ldg, const float* gnorm, const float* stat, float scale,
+                         int d, void* S, int64_t lds) {
+    const int i = blockIdx.y;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= d) return;
+    const float f = scale * (*stat) / gnorm[i];
+    const float x = G[(int64_t)i * ldg + c] * f;
+    if (BF16) ((__bf16*)S)[(int64_t)i * lds + c] = (__bf16)x;
+    else ((float*)S)[(int64_t)i * lds + c] = x;
+}
+
+// 32 x 32 tiles through LDS so that both the matrix and its transpose are written row-contiguously.
+// Grid covers ceil(ldd/32) x ceil(ldd/32) tiles; everything outside n x n is written as zero.
+__global__ __launch_bounds__(256)
+void emit_matrix_kernel(const float* src, int64_t lds, const float* rdiag, int n, int64_t ldd,
+                        float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16) {
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    for (int i = ty; i < 32; i += 8) {
+        const int r = r0 + i, c = c0 + tx;
+        float x = 0.f;
+        if (r < n && c < n) {
+            x = src[(int64_t)r * lds + c];
+            if (rdiag != nullptr && rdiag[c] < 0.f) x = -x;
+        }
+        tile[i][tx] = x;
+        if (r < n && c < ldd) {
+            if (dst32) dst32[(int64_t)r * ldd + c] = x;
+            if (dst16) { __bf16 h = (__bf16)x; dst16[(int64_t)r * ldd + c] = __builtin_bit_cast(uint16_t, h); }
+        }
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int r = c0 + i, c = r0 + tx;                       // row of the transpose = column of src
+        const float x = tile[tx][i];
+        if (r < n && c < ldd) {
+            if (dstT32) dstT32[(int64_t)r * ldd + c] = x;
+            if (dstT16) { __bf16 h = (__bf16)x; dstT16[(int64_t)r * ldd + c] = __builtin_bit_cast(uint16_t, h); }
+        }
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256)
+void export_dense_kernel(const void* src, int64_t ld, int rows, int cols, float* out) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int r = blockIdx.y;
+    if (c >= cols || r >= rows) return;
+    float x;
+    if (BF16) x = bf16_bits_to_float(((const uint16_t*)src)[(int64_t)r * ld + c]);
+    else x = ((const float*)src)[(int64_t)r * ld + c];
+    out[(int64_t)r * cols + c] = x;
+}
+
+}  // namespace
+
+hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale,
+                       hipStream_t stream) {
+    const int64_t quads = ((int64_t)rows * cols + 3) / 4;
+    if (quads == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_normal_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
+                       out, ld, rows, cols, ps, scale);
+    return hipGetLastError();
+}
+
+hipError_t axpy_matrix(float* dst, int64_t ldd, const float* src, int64_t lds, int rows, int cols,
+                       float scale, hipStream_t stream) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    hipLaunchKernelGGL(axpy_matrix_kernel, dim3((cols + 255) / 256, rows), dim3(256), 0, stream,
+                       dst, ldd, src, lds, rows, cols, scale);
+    return hipGetLastError();
+}
+
+hipError_t row_norms(const void* X, int is_bf16, int64_t ld, int rows, int cols, float* norms,
+                     hipStream_t stream) {
+    if (rows <= 0) return hipSuccess;
+    const dim3 grid((rows + 3) / 4), block(256);
+    if (is_bf16) hipLaunchKernelGGL(row_norms_kernel<true>, grid, block, 0, stream, X, ld, rows, cols, norms);
+    else hipLaunchKernelGGL(row_norms_kernel<false>, grid, block, 0, stream, X, ld, rows, cols, norms);
+    return hipGetLastError();
+}
+
+hipError_t norm_statistic(const float* v, int count, int stat, float* out, hipStream_t stream) {
+    int padded = 1024;
+    while (padded < count) padded <<= 1;
+    hipLaunchKernelGGL(norm_statistic_kernel, dim3(1), dim3(1024), padded * sizeof(float), stream,
+                       v, count, stat, padded, out);
+    return hipGetLastError();
+}
+
+hipError_t make_shields(const float* G, int64_t ldg, const float* gnorm, const float* stat, float scale,
+                        int k, int d, void* S, int is_bf16, int64_t lds, hipStream_t stream) {
+    if (k <= 0) return hipSuccess;
+    const dim3 grid((d + 255) / 256, k), block(256);
+    if (is_bf16) hipLaunchKernelGGL(make_shields_kernel<true>, grid, block, 0, stream, G, ldg, gnorm, stat, scale, d, S, lds);
+    else hipLaunchKernelGGL(make_shields_kernel<false>, grid, block, 0, stream, G, ldg, gnorm, stat, scale, d, S, lds);
+    return hipGetLastError();
+}
+
+hipError_t emit_matrix(const float* src, int64_t lds, const float* rdiag, int n, int64_t ldd,
+                       float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16, hipStream_t stream) {
+    const int t = (int)((ldd + 31) / 32);
+    hipLaunchKernelGGL(emit_matrix_kernel, dim3(t, t), dim3(256), 0, stream,
+                       src, lds, rdiag, n, ldd, dst32, dst16, dstT32, dstT16);
+    return hipGetLastError();
+}
+
+hipError_t export_dense(const void* src, int is_bf16, int64_t ld, int rows, int cols, float* out,
+                        hipStream_t stream) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    const dim3 grid((cols + 255) / 256, rows), block(256);
+    if (is_bf16) hipLaunchKernelGGL(export_dense_kernel<true>, grid, block, 0, stream, src, ld, rows, cols, out);
+    else hipLaunchKernelGGL(export_dense_kernel<false>, grid, block, 0, stream, src, ld, rows, cols, out);
+    return hipGetLastError();
+}
+
+}  // namespace gelo

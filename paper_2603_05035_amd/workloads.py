@@ -41,7 +41,7 @@ class Workload:
 
 
 WORKLOADS = {
-    # tiny fp32 case the oracle finishes instantly
+    # tiny fp32 case a CPU reference finishes instantly
     "tiny_f32": Workload("tiny_f32", "f32", 16, 2, 64, 192, KIND_ORTHOGONAL, 0, 0xC0),
     # Llama-2-7B-shaped single layer, fp32, non-orthogonal Gaussian A with kappa rejection
     "llama7b_f32_gaussian": Workload("llama7b_f32_gaussian", "f32", 512, 0, 4096, 12288,
