@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the GELO obfuscated QKV projection on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input that already
+sits in HBM: draw a fresh mixing matrix A (Philox + Householder QR, or LU for the
+non-orthogonal kinds), build the shield rows, mix U = A[H;S], project Y = U W, unmix
+Z = A^-1 Y.  Prints ONE JSON line:
+  value      whole-step throughput: algorithmic FLOP of the step (chain + A generation) / time
+  roofline   the dominant kernel (the projection GEMM) against the MFMA peak of its dtype,
+             timed with events on the stream it runs on
+  cpu_baseline  the fp64 CPU oracle timed on the host cores on a bounded sample
+plus per-stage times, the chain-only rate with A already sampled, and the overhead against a
+plain H W GEMM run through the same kernel.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}          # MI355X dense matrix peaks
+KIND_NAME = {0: "orthogonal", 1: "gaussian", 2: "conditioned"}
+
+
+def chain_flops(w):
+    n, nd, d, p = w.n, w.n_data, w.d, w.p
+    return 2.0 * n * n * d + 2.0 * n * d * p + 2.0 * nd * n * p
+
+
+def gen_flops(w, attempts=1):
+    n = float(w.n)
+    qr = 8.0 / 3.0 * n ** 3            # Householder QR with explicit Q
+    lu = 2.0 * n ** 3                  # LU + explicit inverse
+    return {0: qr, 1: lu * attempts, 2: qr + lu}[w.kind]
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama7b_bf16_prefill")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2603_05035_amd import binding as g
+    from paper_2603_05035_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    w = wl.WORKLOADS[args.workload]
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    H32, W32 = wl.make_inputs(w)
+    H = torch.from_numpy(H32).to(tdt).cuda()
+    W = torch.from_numpy(W32).to(tdt).cuda()
+    n, nd, d, p, k = w.n, w.n_data, w.d, w.p, w.k_shield
+    U = torch.empty((n, d), dtype=tdt, device="cuda")
+    Y = torch.empty((n, p), dtype=tdt, device="cuda")
+    Z = torch.empty((nd, p), dtype=tdt, device="cuda")
+    Yplain = torch.empty((nd, p), dtype=tdt, device="cuda")
+    code = g.GELO_BF16 if w.dtype == "bf16" else g.GELO_F32
+    ctx = g.gelo_create(0, w.seed, allow_batch_reuse=False)
+    K, Wm = args.steps, args.warmup
+    next_batch = [0]
+
+    def step():
+        g.gelo_qkv_forward(ctx, w.kind, H, W, Z, k_shield=k, shield_scale=w.shield_scale, cond_max=w.cond_max,
+                           batch_id=next_batch[0], U=U, Y=Y)
+        next_batch[0] += 1
+
+    # ---- whole step, wall clock around K steps ----
+    for _ in range(Wm):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / K
+
+    # ---- per-stage times with events on the launch stream ----
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    stage = {"sample": 0.0, "mix": 0.0, "project": 0.0, "unmix": 0.0, "plain": 0.0}
+    attempts = []
+    for i in range(K):
+        e = [ev() for _ in range(7)]
+        e[0].record()
+        m = g.gelo_sample_mixing(ctx, w.kind, nd, k, d, code, w.cond_max, 64, next_batch[0])
+        next_batch[0] += 1
+        e[1].record()
+        g.gelo_mix(ctx, m, H, U, w.shield_scale)
+        e[2].record()
+        g.gelo_project(ctx, U, W, Y)
+        e[3].record()
+        g.gelo_unmix(ctx, m, Y, Z)
+        e[4].record()
+        g.gelo_project(ctx, H, W, Yplain)
+        e[5].record()
+        torch.cuda.synchronize()
+        if i == 0 and w.kind == 1:
+            attempts.append(g.gelo_mixing_export(ctx, m, n, k, d, want_shields=False)[3] + 1)
+        g.gelo_mixing_free(ctx, m)
+        for name, a, b in (("sample", 0, 1), ("mix", 1, 2), ("project", 2, 3), ("unmix", 3, 4), ("plain", 4, 5)):
+            stage[name] += e[a].elapsed_time(e[b]) / K
+    t_chain = (stage["mix"] + stage["project"] + stage["unmix"]) * 1e-3
+
+    # ---- the dominant kernel alone: the projection GEMM, one launch per event pair ----
+    for _ in range(3):
+        g.gelo_project(ctx, U, W, Y)
+    torch.cuda.synchronize()
+    pairs = []
+    for _ in range(max(K, 20)):
+        a, b = ev(), ev()
+        a.record()
+        g.gelo_project(ctx, U, W, Y)
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    t_proj = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs) * 1e-3
+
+    f_chain, f_gen = chain_flops(w), gen_flops(w, attempts[0] if attempts else 1)
+    f_proj = 2.0 * n * d * p
+    peak = PEAK_TFLOPS[w.dtype]
+    result = {
+        "metric": "GELO QKV-forward TFLOP/s (whole step: A generation + shields + mix + project + unmix)",
+        "value": (f_chain + f_gen) / t_step / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": t_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "n_data": nd, "k_shield": k, "n": n, "d": d, "p": p,
+                   "mixing": KIND_NAME[w.kind], "shield_scale": w.shield_scale},
+        "frac_of_mfma_peak_whole_step": (f_chain + f_gen) / t_step / 1e12 / peak,
+        "chain_only": {"tflops": f_chain / t_chain / 1e12, "frac_of_mfma_peak": f_chain / t_chain / 1e12 / peak,
+                       "ms": t_chain * 1e3, "note": "mix+project+unmix with A already sampled"},
+        "stage_ms": {kk: round(v, 4) for kk, v in stage.items()},
+        "overhead_vs_plain_gemm_pct": {"whole_step": (t_step * 1e3 / stage["plain"] - 1.0) * 100.0,
+                                       "chain_only": (t_chain * 1e3 / stage["plain"] - 1.0) * 100.0,
+                                       "flop_ratio_floor": (f_chain / (2.0 * nd * d * p) - 1.0) * 100.0},
+        "useful_tflops": 2.0 * nd * d * p / t_step / 1e12,
+        "roofline": {"kernel": "gemm (project Y = U W)", "bound": "mfma", "achieved": f_proj / t_proj / 1e12,
+                     "peak": peak, "unit": "TFLOP/s", "frac": f_proj / t_proj / 1e12 / peak, "traffic": None,
+                     "avg_launch_us": t_proj * 1e6},
+    }
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands, on the host cores: mix + project + unmix of this workload in fp64 with
+        # the A of one GPU draw.  Its A generation (a Python-level Householder loop) is left out: at
+        # n = 2150 it alone takes minutes.
+        from oracle import gelo_oracle as oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([t.get("num_threads", 1) for t in threadpool_info()] or [os.cpu_count() or 1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        rows = min(nd, 1024)                      # bounded sample: the first `rows` data rows (+ all shields)
+        m = g.gelo_sample_mixing(ctx, 0, rows, k, d, code, 0.0, 1, next_batch[0])
+        next_batch[0] += 1
+        Us = torch.empty((rows + k, d), dtype=tdt, device="cuda")
+        g.gelo_mix(ctx, m, H[:rows], Us, w.shield_scale)
+        A, A_inv, S, _, _ = g.gelo_mixing_export(ctx, m, rows + k, k, d)
+        torch.cuda.synchronize()
+        g.gelo_mixing_free(ctx, m)
+        A64, Ai64 = A.double().cpu().numpy(), A_inv.double().cpu().numpy()
+        S64 = S.double().cpu().numpy() if S is not None else None
+        H64, W64 = H[:rows].double().cpu().numpy(), W.double().cpu().numpy()
+        t0 = time.perf_counter()
+        Uo = oracle.mix(A64, H64, S64)
+        Yo = oracle.project(Uo, W64)
+        Zo = oracle.unmix(Ai64, Yo, rows)
+        t_cpu = time.perf_counter() - t0
+        ns = rows + k
+        f_sample = 2.0 * ns * ns * d + 2.0 * ns * d * p + 2.0 * rows * ns * p
+        result["cpu_baseline"] = {"value": f_sample / t_cpu / 1e12, "unit": "TFLOP/s", "cores": int(cores),
+                                  "kind": "oracle", "seconds": t_cpu,
+                                  "sample": f"fp64 mix+project+unmix of the first {rows} data rows + {k} shield rows "
+                                            f"(n={ns}, d={d}, p={p}), A from one GPU draw; oracle A generation excluded"}
+        result["cpu_baseline"]["check_rel_err"] = float(np.linalg.norm(Zo - H64 @ W64) / np.linalg.norm(Zo))
+    g.gelo_destroy(ctx)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -9,6 +9,9 @@
 // that keeps its rows in registers (thread t owns rows t, t+NTHR, ...), so the per-column
 // reductions cost a couple of barriers and no memory traffic.  The rank-16 updates of the
 // trailing matrix are bandwidth-bound and run on the vector ALUs.
+#include <type_traits>
+#include <utility>
+
 #include "gelo_internal.h"
 
 namespace gelo {
@@ -22,252 +25,373 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// Sum of NB per-thread values over the workgroup, result broadcast to every thread.
-// red: [NW][NB] floats, fin: [NB] floats of LDS.  Two barriers; callers separate successive
-// uses by at least one more barrier (the panel loops do).
-template <int NW>
-__device__ __forceinline__ void block_sum_vec(float (&v)[NB], float* red, float* fin) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+// compile-time loop: the body sees its index as a constant, so register arrays stay in registers
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(std::make_integer_sequence<int, N>{}, f); }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+template <int PATTERN>
+__device__ __forceinline__ float swizzle(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), PATTERN));
+}
+
+// Index of the value that lane `lane` ends up holding after wave_reduce16.
+__device__ __forceinline__ int reduce16_slot(int lane) {
+    return ((lane >> 2) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 1) & 1) * 2 + (lane & 1);
+}
+
+// Sums 16 per-lane values over the 64 lanes of a wave in ~50 instructions: each exchange step
+// halves the number of values a lane carries (the lane keeps the half its partner does not),
+// so after four steps inside a row of 16 lanes every lane holds ONE value, summed over its row;
+// two more exchanges add the four rows.  Returns, in every lane, the wave total of value
+// reduce16_slot(lane).  All 64 lanes must be active.  The order of additions is fixed.
+__device__ __forceinline__ float wave_reduce16(const float (&t)[NB], int lane) {
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4, b3 = lane & 8;
+    float a[8], c[4], e[2];
 #pragma unroll
-    for (int s = 0; s < NB; ++s) {
-        const float t = wave_sum(v[s]);
-        if (lane == 0) red[wave * NB + s] = t;
+    for (int k = 0; k < 8; ++k) {
+        const float keep = b0 ? t[2 * k + 1] : t[2 * k];
+        const float give = b0 ? t[2 * k] : t[2 * k + 1];
+        a[k] = keep + dpp_mov<0xB1>(give);              // lane ^ 1  (quad_perm [1,0,3,2])
     }
-    __syncthreads();
-    if (tid < NB) {
-        float t = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) t += red[w * NB + tid];
-        fin[tid] = t;
+    for (int k = 0; k < 4; ++k) {
+        const float keep = b1 ? a[2 * k + 1] : a[2 * k];
+        const float give = b1 ? a[2 * k] : a[2 * k + 1];
+        c[k] = keep + dpp_mov<0x4E>(give);              // lane ^ 2  (quad_perm [2,3,0,1])
     }
-    __syncthreads();
 #pragma unroll
-    for (int s = 0; s < NB; ++s) v[s] = fin[s];
+    for (int k = 0; k < 2; ++k) {
+        const float keep = b3 ? c[2 * k + 1] : c[2 * k];
+        const float give = b3 ? c[2 * k] : c[2 * k + 1];
+        e[k] = keep + dpp_mov<0x128>(give);             // lane ^ 8  (row_ror:8)
+    }
+    const float keep = b2 ? e[1] : e[0];
+    const float give = b2 ? e[0] : e[1];
+    float f = keep + swizzle<0x101F>(give);             // lane ^ 4
+    f += swizzle<0x401F>(f);                            // lane ^ 16
+    f += __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, f)));
+    return f;
+}
+
+template <int LANE>
+__device__ __forceinline__ float lane_value(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), LANE));
 }
 
 // ------------------------------------------------------------------ QR panel --
 // Factorises the m x 16 panel at Mp (row stride ld) in place (R on and above the diagonal,
 // reflector tails below, as in LAPACK), and writes for the block reflector I - V T V^T:
-// Vc = V with explicit unit diagonal and zeros above, VT = V T, VTt = V T^T (m x 16 each,
-// row stride ld), and rdiag[0:16] = diag(R).  Reflector j: beta = -sign(alpha) ||x||,
-// tau = (beta - alpha)/beta, v = x / (alpha - beta) below the diagonal; a zero column gets tau = 0.
+// Vc = V with explicit unit diagonal and zeros above (m x 16, row stride ld), T (16 x 16,
+// dense row-major at Tg) and rdiag[0:16] = diag(R).  Reflector j: beta = -sign(alpha) ||x||,
+// tau = (beta - alpha)/beta, v = x / (alpha - beta) below the diagonal; a zero tail gets tau = 0.
+//
+// One workgroup reduction and one barrier per column: with x the column below the diagonal,
+// t[s] = x . P[below, s] for all 16 columns s gives the tail norm (s = j) and, with the broadcast
+// pivot row, v . P[:, s] = scale * t[s] + P[j][s], which is both the update coefficient (s > j)
+// and the Gram entry v_s . v_j that the T factor needs (s < j).  After the reduction lane s of
+// every wave holds the quantities of column s; the update coefficients are then read into
+// scalar registers.  The column loop is unrolled so that all register indices are constants.
 template <int NTHR, int R>
 __global__ __launch_bounds__(NTHR)
-void qr_panel_kernel(float* Mp, float* Vc, float* VT, float* VTt, float* rdiag, int64_t ld, int m) {
+void qr_panel_kernel(float* Mp, float* Vc, float* Tg, float* rdiag, int64_t ld, int m) {
     constexpr int NW = NTHR / 64;
-    __shared__ float red[NW * NB];
-    __shared__ float fin[NB];
-    __shared__ float Tm[NB][NB];
+    __shared__ float red[2][NW][NB];
+    __shared__ float prow[2][NB];
+    __shared__ float Z[NB][NB];          // Z[j][s] = v_j . (column s) at step j
     __shared__ float tau_s[NB];
-    __shared__ float alpha_s;
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15;
+    const int slot = reduce16_slot(lane);
     float P[R][NB];
 #pragma unroll
     for (int i = 0; i < R; ++i) {
         const int r = tid + i * NTHR;
-        if (r < m) {
 #pragma unroll
-            for (int c4 = 0; c4 < NB / 4; ++c4) {
-                const float4 v = *reinterpret_cast<const float4*>(Mp + (int64_t)r * ld + c4 * 4);
-                P[i][c4 * 4 + 0] = v.x; P[i][c4 * 4 + 1] = v.y; P[i][c4 * 4 + 2] = v.z; P[i][c4 * 4 + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < NB; ++c) P[i][c] = 0.f;
+        for (int c4 = 0; c4 < NB / 4; ++c4) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r < m) v = *reinterpret_cast<const float4*>(Mp + (int64_t)r * ld + c4 * 4);
+            P[i][c4 * 4 + 0] = v.x; P[i][c4 * 4 + 1] = v.y; P[i][c4 * 4 + 2] = v.z; P[i][c4 * 4 + 3] = v.w;
         }
     }
-    if (tid < NB) {
-#pragma unroll
-        for (int c = 0; c < NB; ++c) Tm[tid][c] = 0.f;
-    }
 
+    static_for<NB>([&](auto jc) {
+        constexpr int j = decltype(jc)::value;
+        constexpr int pb = j & 1;                       // LDS buffers alternate between columns
+        float t[NB];
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        // ||x below the diagonal||^2 and alpha = x_0
-        float part[NB];
-#pragma unroll
-        for (int s = 0; s < NB; ++s) part[s] = 0.f;
+        for (int s = 0; s < NB; ++s) t[s] = 0.f;
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             const int r = tid + i * NTHR;
-            if (r > j && r < m) part[0] = fmaf(P[i][j], P[i][j], part[0]);
+            if (r > j && r < m) {
+                const float x = P[i][j];
+#pragma unroll
+                for (int s = 0; s < NB; ++s) t[s] = fmaf(x, P[i][s], t[s]);
+            }
         }
-        if (tid == j) alpha_s = P[0][j];
-        block_sum_vec<NW>(part, red, fin);
-        const float xnorm2 = part[0];
-        const float alpha = alpha_s;
+        if (tid == j) {                                 // row j is register row 0 of thread j
+#pragma unroll
+            for (int s = 0; s < NB; ++s) prow[pb][s] = P[0][s];
+        }
+        const float part = wave_reduce16(t, lane);
+        if (lane < NB) red[pb][wave][slot] = part;
+        __syncthreads();
+        float tot = red[pb][0][li];                     // lane (li) now works on column li
+#pragma unroll
+        for (int w = 1; w < NW; ++w) tot += red[pb][w][li];
+        const float pr = prow[pb][li];
+        const float xnorm2 = lane_value<j>(tot);
+        const float alpha = lane_value<j>(pr);
         float beta = alpha, tau = 0.f, scale = 0.f;
         if (xnorm2 > 0.f) {
             beta = -copysignf(sqrtf(fmaf(alpha, alpha, xnorm2)), alpha);
             tau = (beta - alpha) / beta;
             scale = 1.0f / (alpha - beta);
         }
-        // form v_j in place and the dot products of v_j with every other panel column
-        // (columns s > j: the update; columns s < j hold v_s there: the Gram entries T needs)
-        float vr[R];
-#pragma unroll
-        for (int s = 0; s < NB; ++s) part[s] = 0.f;
+        const float wl = fmaf(scale, tot, pr);          // v_j . (column li)
+        if (tid < NB) Z[j][tid] = wl;
+        if (tid == 0) { tau_s[j] = tau; rdiag[j] = beta; }
+        float w[NB];
+        static_for<NB>([&](auto sc) {
+            constexpr int s = decltype(sc)::value;
+            if constexpr (s > j) w[s] = lane_value<s>(wl);
+        });
 #pragma unroll
         for (int i = 0; i < R; ++i) {
             const int r = tid + i * NTHR;
-            float v = 0.f;
-            if (r < m) {
-                if (r > j) { P[i][j] *= scale; v = P[i][j]; }
-                else if (r == j) { P[i][j] = beta; v = 1.f; }
-            }
-            vr[i] = v;
+            if (r > j && r < m) {
+                const float v = P[i][j] * scale;
+                P[i][j] = v;
+                const float tv = tau * v;
 #pragma unroll
-            for (int s = 0; s < NB; ++s)
-                if (s != j) part[s] = fmaf(v, P[i][s], part[s]);
-        }
-        block_sum_vec<NW>(part, red, fin);
+                for (int s = j + 1; s < NB; ++s) P[i][s] = fmaf(-tv, w[s], P[i][s]);
+            } else if (r == j) {
+                P[i][j] = beta;
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const float tv = tau * vr[i];
-#pragma unroll
-            for (int s = j + 1; s < NB; ++s) P[i][s] = fmaf(-tv, part[s], P[i][s]);
-        }
-        // column j of T: T[a][j] = -tau_j sum_{b<j} T[a][b] (v_b . v_j), T[j][j] = tau_j
-        if (tid < NB) {
-            if (tid < j) {
-                float t = 0.f;
-#pragma unroll
-                for (int b = 0; b < j; ++b) t = fmaf(Tm[tid][b], part[b], t);
-                Tm[tid][j] = -tau * t;
-            } else if (tid == j) {
-                Tm[j][j] = tau;
-                tau_s[j] = tau;
-                rdiag[j] = beta;
+                for (int s = j + 1; s < NB; ++s) P[i][s] = fmaf(-tau, w[s], P[i][s]);
             }
         }
-        __syncthreads();
+    });
+    __syncthreads();
+
+    // T by the forward recurrence T[a][j] = -tau_j sum_{b<j} T[a][b] (v_b . v_j), T[j][j] = tau_j;
+    // lane a of the first wave carries row a.
+    if (tid < NB) {
+        float Trow[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) Trow[c] = 0.f;
+        static_for<NB>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            float acc = 0.f;
+#pragma unroll
+            for (int bb = 0; bb < j; ++bb) acc = fmaf(Trow[bb], Z[j][bb], acc);
+            const float tj = tau_s[j];
+            Trow[j] = tid < j ? -tj * acc : (tid == j ? tj : 0.f);
+        });
+#pragma unroll
+        for (int c4 = 0; c4 < NB / 4; ++c4)
+            *reinterpret_cast<float4*>(Tg + tid * NB + c4 * 4) =
+                make_float4(Trow[c4 * 4], Trow[c4 * 4 + 1], Trow[c4 * 4 + 2], Trow[c4 * 4 + 3]);
     }
 
-    // write back the factored panel and the three reflector blocks
+    // write back the factored panel and the clean reflector block
 #pragma unroll
     for (int i = 0; i < R; ++i) {
         const int r = tid + i * NTHR;
-        if (r >= m) continue;
-        float v[NB], vt[NB], vtt[NB];
+        if (r < m) {
+            float* mp = Mp + (int64_t)r * ld;
+            float* vc = Vc + (int64_t)r * ld;
 #pragma unroll
-        for (int c = 0; c < NB; ++c) v[c] = r > c ? P[i][c] : (r == c ? 1.f : 0.f);
+            for (int c4 = 0; c4 < NB / 4; ++c4) {
+                float v[4];
 #pragma unroll
-        for (int c = 0; c < NB; ++c) {
-            float a = 0.f, b = 0.f;
-#pragma unroll
-            for (int k = 0; k < NB; ++k) {
-                if (k <= c) a = fmaf(v[k], Tm[k][c], a);     // (V T)[r][c]
-                if (k >= c) b = fmaf(v[k], Tm[c][k], b);     // (V T^T)[r][c]
+                for (int e = 0; e < 4; ++e) { const int c = c4 * 4 + e; v[e] = r > c ? P[i][c] : (r == c ? 1.f : 0.f); }
+                *reinterpret_cast<float4*>(mp + c4 * 4) = make_float4(P[i][c4 * 4], P[i][c4 * 4 + 1], P[i][c4 * 4 + 2], P[i][c4 * 4 + 3]);
+                *reinterpret_cast<float4*>(vc + c4 * 4) = make_float4(v[0], v[1], v[2], v[3]);
             }
-            vt[c] = a; vtt[c] = b;
-        }
-        float* mp = Mp + (int64_t)r * ld;
-        float* vc = Vc + (int64_t)r * ld;
-        float* vtp = VT + (int64_t)r * ld;
-        float* vttp = VTt + (int64_t)r * ld;
-#pragma unroll
-        for (int c4 = 0; c4 < NB / 4; ++c4) {
-            *reinterpret_cast<float4*>(mp + c4 * 4) = make_float4(P[i][c4 * 4], P[i][c4 * 4 + 1], P[i][c4 * 4 + 2], P[i][c4 * 4 + 3]);
-            *reinterpret_cast<float4*>(vc + c4 * 4) = make_float4(v[c4 * 4], v[c4 * 4 + 1], v[c4 * 4 + 2], v[c4 * 4 + 3]);
-            *reinterpret_cast<float4*>(vtp + c4 * 4) = make_float4(vt[c4 * 4], vt[c4 * 4 + 1], vt[c4 * 4 + 2], vt[c4 * 4 + 3]);
-            *reinterpret_cast<float4*>(vttp + c4 * 4) = make_float4(vtt[c4 * 4], vtt[c4 * 4 + 1], vtt[c4 * 4 + 2], vtt[c4 * 4 + 3]);
         }
     }
 }
 
 // ------------------------------------------------------- skinny rank-16 kernels --
-constexpr int SK_COLS = 64;      // columns per workgroup
-constexpr int SK_ROWS = 256;     // rows per workgroup (chunk)
+// Both work on tiles of 128 rows x 64 columns with 128 threads: thread (ct, rt) owns 4 adjacent
+// columns (one 16-byte access per row) of the 16 rows rt, rt+8, ...
+constexpr int SK_COLS = 64;
+constexpr int SK_ROWS = 128;
+constexpr int SK_THREADS = 128;
 
-// Wpart[chunk][i][col] = sum over the chunk's rows r of V[r][i] * C[r][col]
-__global__ __launch_bounds__(256)
+// Wpart[tile][i][col] = sum over the rows r of tile blockIdx.y of V[r][i] * C[r][col]
+__global__ __launch_bounds__(SK_THREADS)
 void vt_c_partial_kernel(const float* V, int64_t ldv, const float* C, int64_t ldc, int rows, int cols,
                          float* Wpart, int64_t ldw) {
-    __shared__ float Vs[SK_ROWS][NB];
-    __shared__ float red[4][NB][SK_COLS];
+    __shared__ __attribute__((aligned(16))) float Vs[SK_ROWS][NB];
+    __shared__ __attribute__((aligned(16))) float red[8][NB][SK_COLS];
     const int tid = threadIdx.x;
     const int r0 = blockIdx.y * SK_ROWS;
-    {   // row tid of the chunk: 16 contiguous floats
-        const int r = r0 + tid;
 #pragma unroll
-        for (int c4 = 0; c4 < NB / 4; ++c4) {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r < rows) v = *reinterpret_cast<const float4*>(V + (int64_t)r * ldv + c4 * 4);
-            *reinterpret_cast<float4*>(&Vs[tid][c4 * 4]) = v;
-        }
+    for (int t = 0; t < 4; ++t) {                   // 128 rows x 4 chunks of 16 bytes
+        const int id = tid + t * SK_THREADS;
+        const int r = id >> 2, c4 = id & 3;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r0 + r < rows) v = *reinterpret_cast<const float4*>(V + (int64_t)(r0 + r) * ldv + c4 * 4);
+        *reinterpret_cast<float4*>(&Vs[r][c4 * 4]) = v;
     }
     __syncthreads();
-    const int lc = tid & 63, rg = tid >> 6;
-    const int col = blockIdx.x * SK_COLS + lc;
-    float acc[NB];
+    const int ct = tid & 15, rt = tid >> 4;
+    const int col = blockIdx.x * SK_COLS + ct * 4;
+    float acc[NB][4];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) acc[i] = 0.f;
+    for (int i = 0; i < NB; ++i) { acc[i][0] = acc[i][1] = acc[i][2] = acc[i][3] = 0.f; }
     if (col < cols) {
-        const int rbeg = r0 + rg * 64;
-        const int rend = (rbeg + 64 < rows) ? rbeg + 64 : rows;
-        for (int r = rbeg; r < rend; ++r) {
-            const float c = C[(int64_t)r * ldc + col];
-            const float* vs = Vs[r - r0];
+        float4 c[16];
 #pragma unroll
-            for (int i = 0; i < NB; ++i) acc[i] = fmaf(vs[i], c, acc[i]);
+        for (int ii = 0; ii < 16; ++ii) {
+            const int r = r0 + rt + 8 * ii;
+            c[ii] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (r < rows) c[ii] = *reinterpret_cast<const float4*>(C + (int64_t)r * ldc + col);
+        }
+#pragma unroll
+        for (int ii = 0; ii < 16; ++ii) {
+            const float* vs = Vs[rt + 8 * ii];
+#pragma unroll
+            for (int i4 = 0; i4 < NB / 4; ++i4) {
+                const float4 v = *reinterpret_cast<const float4*>(vs + i4 * 4);
+                const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    acc[i4 * 4 + e][0] = fmaf(vv[e], c[ii].x, acc[i4 * 4 + e][0]);
+                    acc[i4 * 4 + e][1] = fmaf(vv[e], c[ii].y, acc[i4 * 4 + e][1]);
+                    acc[i4 * 4 + e][2] = fmaf(vv[e], c[ii].z, acc[i4 * 4 + e][2]);
+                    acc[i4 * 4 + e][3] = fmaf(vv[e], c[ii].w, acc[i4 * 4 + e][3]);
+                }
+            }
         }
     }
 #pragma unroll
-    for (int i = 0; i < NB; ++i) red[rg][i][lc] = acc[i];
+    for (int i = 0; i < NB; ++i)
+        *reinterpret_cast<float4*>(&red[rt][i][ct * 4]) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
     __syncthreads();
-    if (col < cols) {
+    // 16 x 64 outputs of this tile, 8 per thread, each the sum of 8 partials in a fixed order
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int i = rg * 4 + t;
-            const float s = (red[0][i][lc] + red[1][i][lc]) + (red[2][i][lc] + red[3][i][lc]);
-            Wpart[((int64_t)blockIdx.y * NB + i) * ldw + col] = s;
+    for (int t = 0; t < 2; ++t) {
+        const int id = tid + t * SK_THREADS;        // 0..255: (i, 4-column group)
+        const int i = id >> 4, cg = id & 15;
+        const int ocol = blockIdx.x * SK_COLS + cg * 4;
+        if (ocol < cols) {
+            float4 s = *reinterpret_cast<const float4*>(&red[0][i][cg * 4]);
+#pragma unroll
+            for (int g = 1; g < 8; ++g) {
+                const float4 q = *reinterpret_cast<const float4*>(&red[g][i][cg * 4]);
+                s.x += q.x; s.y += q.y; s.z += q.z; s.w += q.w;
+            }
+            *reinterpret_cast<float4*>(Wpart + ((int64_t)blockIdx.y * NB + i) * ldw + ocol) = s;
         }
     }
 }
 
-// W[i][col] = sum_chunk Wpart[chunk][i][col], chunks added in index order
-__global__ __launch_bounds__(256)
-void reduce_w_kernel(const float* Wpart, int chunks, int cols, int64_t ldw, float* W) {
-    const int col = blockIdx.x * 256 + threadIdx.x;
-    const int i = blockIdx.y;
-    if (col >= cols) return;
-    float s = 0.f;
-    for (int c = 0; c < chunks; ++c) s += Wpart[((int64_t)c * NB + i) * ldw + col];
-    W[(int64_t)i * ldw + col] = s;
+// W[0:16, strip] = op(T) * sum_tile Wpart[tile][0:16, strip] for the 64-column strip blockIdx.x;
+// tiles are added in index order; op(T) = T^T if t_transposed.
+__global__ __launch_bounds__(SK_THREADS)
+void reduce_apply_kernel(const float* Wpart, int tiles, int cols, int64_t ldw, const float* T, int t_transposed,
+                         float* W) {
+    __shared__ __attribute__((aligned(16))) float Wsum[NB][SK_COLS];
+    __shared__ float Ts[NB][NB];
+    const int tid = threadIdx.x;
+    if (tid < NB) {
+#pragma unroll
+        for (int c4 = 0; c4 < NB / 4; ++c4)
+            *reinterpret_cast<float4*>(&Ts[tid][c4 * 4]) = *reinterpret_cast<const float4*>(T + tid * NB + c4 * 4);
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int id = tid + t * SK_THREADS;
+        const int i = id >> 4, cg = id & 15;
+        const int ocol = blockIdx.x * SK_COLS + cg * 4;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ocol < cols) {
+#pragma unroll 4
+            for (int tl = 0; tl < tiles; ++tl) {
+                const float4 q = *reinterpret_cast<const float4*>(Wpart + ((int64_t)tl * NB + i) * ldw + ocol);
+                s.x += q.x; s.y += q.y; s.z += q.z; s.w += q.w;
+            }
+        }
+        *reinterpret_cast<float4*>(&Wsum[i][cg * 4]) = s;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int id = tid + t * SK_THREADS;
+        const int i = id >> 4, cg = id & 15;
+        const int ocol = blockIdx.x * SK_COLS + cg * 4;
+        if (ocol < cols) {
+            float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                const float tk = t_transposed ? Ts[k][i] : Ts[i][k];       // (T^T W)[i] or (T W)[i]
+                const float4 q = *reinterpret_cast<const float4*>(&Wsum[k][cg * 4]);
+                o.x = fmaf(tk, q.x, o.x); o.y = fmaf(tk, q.y, o.y); o.z = fmaf(tk, q.z, o.z); o.w = fmaf(tk, q.w, o.w);
+            }
+            *reinterpret_cast<float4*>(W + (int64_t)i * ldw + ocol) = o;
+        }
+    }
 }
 
 // C[r][col] -= sum_i L[r][i] * W[i][col]
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(SK_THREADS)
 void rank16_update_kernel(const float* L, int64_t ldl, const float* W, int64_t ldw, float* C, int64_t ldc,
                           int rows, int cols) {
-    __shared__ float Ls[SK_ROWS][NB];
+    __shared__ __attribute__((aligned(16))) float Ls[SK_ROWS][NB];
     const int tid = threadIdx.x;
     const int r0 = blockIdx.y * SK_ROWS;
-    {
-        const int r = r0 + tid;
 #pragma unroll
-        for (int c4 = 0; c4 < NB / 4; ++c4) {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r < rows) v = *reinterpret_cast<const float4*>(L + (int64_t)r * ldl + c4 * 4);
-            *reinterpret_cast<float4*>(&Ls[tid][c4 * 4]) = v;
-        }
+    for (int t = 0; t < 4; ++t) {
+        const int id = tid + t * SK_THREADS;
+        const int r = id >> 2, c4 = id & 3;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r0 + r < rows) v = *reinterpret_cast<const float4*>(L + (int64_t)(r0 + r) * ldl + c4 * 4);
+        *reinterpret_cast<float4*>(&Ls[r][c4 * 4]) = v;
     }
     __syncthreads();
-    const int lc = tid & 63, rg = tid >> 6;
-    const int col = blockIdx.x * SK_COLS + lc;
+    const int ct = tid & 15, rt = tid >> 4;
+    const int col = blockIdx.x * SK_COLS + ct * 4;
     if (col >= cols) return;
-    float w[NB];
+    float4 w[NB];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) w[i] = W[(int64_t)i * ldw + col];
-    const int rbeg = r0 + rg * 64;
-    const int rend = (rbeg + 64 < rows) ? rbeg + 64 : rows;
-    for (int r = rbeg; r < rend; ++r) {
-        const float* ls = Ls[r - r0];
-        float s = 0.f;
+    for (int i = 0; i < NB; ++i) w[i] = *reinterpret_cast<const float4*>(W + (int64_t)i * ldw + col);
+    float4 c[16];
 #pragma unroll
-        for (int i = 0; i < NB; ++i) s = fmaf(ls[i], w[i], s);
-        C[(int64_t)r * ldc + col] -= s;
+    for (int ii = 0; ii < 16; ++ii) {
+        const int r = r0 + rt + 8 * ii;
+        c[ii] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r < rows) c[ii] = *reinterpret_cast<const float4*>(C + (int64_t)r * ldc + col);
+    }
+#pragma unroll
+    for (int ii = 0; ii < 16; ++ii) {
+        const int r = r0 + rt + 8 * ii;
+        const float* ls = Ls[rt + 8 * ii];
+        float4 s = c[ii];
+#pragma unroll
+        for (int i4 = 0; i4 < NB / 4; ++i4) {
+            const float4 l = *reinterpret_cast<const float4*>(ls + i4 * 4);
+            const float lv[4] = {l.x, l.y, l.z, l.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                s.x = fmaf(-lv[e], w[i4 * 4 + e].x, s.x);
+                s.y = fmaf(-lv[e], w[i4 * 4 + e].y, s.y);
+                s.z = fmaf(-lv[e], w[i4 * 4 + e].z, s.z);
+                s.w = fmaf(-lv[e], w[i4 * 4 + e].w, s.w);
+            }
+        }
+        if (r < rows) *reinterpret_cast<float4*>(C + (int64_t)r * ldc + col) = s;
     }
 }
 
@@ -314,7 +438,8 @@ void lu_panel_kernel(float* Mp, int64_t ld, int m, int* piv, int row_offset, int
         }
     }
 
-#pragma unroll
+    // rolled loop with the columns rotated by one per step (current column = slot 0), as in the QR panel
+#pragma unroll 1
     for (int j = 0; j < NB; ++j) {
         // pivot search over rows >= j: largest |value|, smallest row on ties
         float bv = -1.f;
@@ -323,7 +448,7 @@ void lu_panel_kernel(float* Mp, int64_t ld, int m, int* piv, int row_offset, int
         for (int i = 0; i < R; ++i) {
             const int r = tid + i * NTHR;
             if (r >= j && r < m) {
-                const float a = fabsf(P[i][j]);
+                const float a = fabsf(P[i][0]);
                 if (a > bv) { bv = a; bi = r; }       // rows visited in increasing order per thread
             }
         }
@@ -373,21 +498,29 @@ void lu_panel_kernel(float* Mp, int64_t ld, int m, int* piv, int row_offset, int
 #pragma unroll
         for (int c = 0; c < NB; ++c) prow[c] = rowbuf[1][c];
         if (tid == 0) piv[j] = row_offset + pr;
-        const float pivot = prow[j];
+        const float pivot = prow[0];
+        const int live = NB - j;
         if (pivot != 0.f) {
             const float inv = 1.0f / pivot;
 #pragma unroll
             for (int i = 0; i < R; ++i) {
                 const int r = tid + i * NTHR;
                 if (r > j && r < m) {
-                    const float l = P[i][j] * inv;
-                    P[i][j] = l;
+                    const float l = P[i][0] * inv;
+                    P[i][0] = l;
 #pragma unroll
-                    for (int c = j + 1; c < NB; ++c) P[i][c] = fmaf(-l, prow[c], P[i][c]);
+                    for (int c = 1; c < NB; ++c) if (c < live) P[i][c] = fmaf(-l, prow[c], P[i][c]);
                 }
             }
         } else if (tid == 0) {
             *flag = 1;
+        }
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const float first = P[i][0];
+#pragma unroll
+            for (int c = 0; c < NB - 1; ++c) P[i][c] = P[i][c + 1];
+            P[i][NB - 1] = first;
         }
         __syncthreads();
     }
@@ -499,11 +632,12 @@ void kappa_finish_kernel(const float* xa, const float* xi, int n, float* out) {
 }
 
 template <int NTHR>
-hipError_t launch_qr_panel(int rows_per_thread, float* Mp, float* Vc, float* VT, float* VTt, float* rdiag,
+hipError_t launch_qr_panel(int rows_per_thread, float* Mp, float* Vc, float* Tg, float* rdiag,
                            int64_t ld, int m, hipStream_t s) {
     switch (rows_per_thread) {
-#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((qr_panel_kernel<NTHR, RR>), dim3(1), dim3(NTHR), 0, s, Mp, Vc, VT, VTt, rdiag, ld, m); break;
+#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((qr_panel_kernel<NTHR, RR>), dim3(1), dim3(NTHR), 0, s, Mp, Vc, Tg, rdiag, ld, m); break;
         GELO_CASE(1) GELO_CASE(2) GELO_CASE(3) GELO_CASE(4) GELO_CASE(5)
+        GELO_CASE(6) GELO_CASE(7) GELO_CASE(8) GELO_CASE(9) GELO_CASE(10)
 #undef GELO_CASE
         default: return hipErrorInvalidValue;
     }
@@ -526,22 +660,22 @@ hipError_t rank16_update(const float* L, int64_t ldl, const float* W, int64_t ld
                          int rows, int cols, hipStream_t s) {
     if (rows <= 0 || cols <= 0) return hipSuccess;
     hipLaunchKernelGGL(rank16_update_kernel, dim3((cols + SK_COLS - 1) / SK_COLS, (rows + SK_ROWS - 1) / SK_ROWS),
-                       dim3(256), 0, s, L, ldl, W, ldw, C, ldc, rows, cols);
+                       dim3(SK_THREADS), 0, s, L, ldl, W, ldw, C, ldc, rows, cols);
     return hipGetLastError();
 }
 
-// W (16 x cols, row stride ws.ld) = V^T C over `rows` rows
-hipError_t vt_c(const FactorWorkspace& ws, const float* V, const float* C, int64_t ldc, int rows, int cols,
-                hipStream_t s) {
+// W (16 x cols, row stride ws.ld) = op(T) V^T C over `rows` rows; op(T) = T^T if t_transposed
+hipError_t vt_c(const FactorWorkspace& ws, const float* V, const float* T, int t_transposed, const float* C,
+                int64_t ldc, int rows, int cols, hipStream_t s) {
     if (rows <= 0 || cols <= 0) return hipSuccess;
     const int chunks = (rows + SK_ROWS - 1) / SK_ROWS;
     if (chunks > ws.wpart_chunks) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(vt_c_partial_kernel, dim3((cols + SK_COLS - 1) / SK_COLS, chunks), dim3(256), 0, s,
+    hipLaunchKernelGGL(vt_c_partial_kernel, dim3((cols + SK_COLS - 1) / SK_COLS, chunks), dim3(SK_THREADS), 0, s,
                        V, ws.ld, C, ldc, rows, cols, ws.Wpart, ws.ld);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(reduce_w_kernel, dim3((cols + 255) / 256, NB), dim3(256), 0, s,
-                       ws.Wpart, chunks, cols, ws.ld, ws.W);
+    hipLaunchKernelGGL(reduce_apply_kernel, dim3((cols + SK_COLS - 1) / SK_COLS), dim3(SK_THREADS), 0, s,
+                       ws.Wpart, chunks, cols, ws.ld, T, t_transposed, ws.W);
     return hipGetLastError();
 }
 
@@ -552,8 +686,8 @@ hipError_t vt_c(const FactorWorkspace& ws, const float* V, const float* C, int64
 size_t factor_workspace_bytes(int n) {
     const int64_t n_pad = round_up(n, NB), ld = round_up(n, 64);
     const int64_t chunks = (n_pad + SK_ROWS - 1) / SK_ROWS;
-    int64_t floats = 5 * n_pad * ld + chunks * NB * ld + NB * ld + n_pad + 4 * ld + 64;
-    return (size_t)floats * sizeof(float) + (size_t)(n_pad + 64) * sizeof(int) + 4096;
+    int64_t floats = 3 * n_pad * ld + n_pad * NB + chunks * NB * ld + NB * ld + n_pad + 4 * ld + 64;
+    return (size_t)floats * sizeof(float) + (size_t)(n_pad + ld + 128) * sizeof(int) + 8192;
 }
 
 void factor_workspace_carve(void* base, int n, FactorWorkspace* ws) {
@@ -564,8 +698,7 @@ void factor_workspace_carve(void* base, int n, FactorWorkspace* ws) {
     ws->M = take(n_pad * ld);
     ws->X = take(n_pad * ld);
     ws->Vc = take(n_pad * ld);
-    ws->VT = take(n_pad * ld);
-    ws->VTt = take(n_pad * ld);
+    ws->Tmat = take(n_pad * NB);
     ws->Wpart = take(chunks * NB * ld);
     ws->W = take(NB * ld);
     ws->rdiag = take(n_pad);
@@ -573,6 +706,7 @@ void factor_workspace_carve(void* base, int n, FactorWorkspace* ws) {
     ws->scalars = take(16);
     ws->piv = (int*)take(n_pad);
     ws->flag = (int*)take(16);
+    ws->counters = (int*)take(ld / SK_COLS + 1);
     ws->n_pad = (int)n_pad;
     ws->ld = ld;
     ws->wpart_chunks = (int)chunks;
@@ -603,17 +737,18 @@ hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t s) {
     const int n_pad = ws.n_pad;
     const int64_t ld = ws.ld;
     const int panels = n_pad / NB;
-    // factorise: panel, then trailing columns C <- (I - V T V^T)^T C = C - (V T^T)(V^T C)
+    // factorise: panel, then trailing columns C <- (I - V T V^T)^T C = C - V (T^T (V^T C))
     for (int p = 0; p < panels; ++p) {
         const int c0 = p * NB, m = n_pad - c0;
         const int64_t off = (int64_t)c0 * ld + c0;
-        if (m <= 256 * 5) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M + off, ws.Vc + off, ws.VT + off, ws.VTt + off, ws.rdiag + c0, ld, m, s));
-        else GELO_TRY(launch_qr_panel<1024>((m + 1023) / 1024, ws.M + off, ws.Vc + off, ws.VT + off, ws.VTt + off, ws.rdiag + c0, ld, m, s));
+        float* Tp = ws.Tmat + (int64_t)p * NB * NB;
+        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M + off, ws.Vc + off, Tp, ws.rdiag + c0, ld, m, s));
+        else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M + off, ws.Vc + off, Tp, ws.rdiag + c0, ld, m, s));
         const int cols = n_pad - c0 - NB;
         if (cols > 0) {
             float* C = ws.M + off + NB;
-            GELO_TRY(vt_c(ws, ws.Vc + off, C, ld, m, cols, s));
-            GELO_TRY(rank16_update(ws.VTt + off, ld, ws.W, ld, C, ld, m, cols, s));
+            GELO_TRY(vt_c(ws, ws.Vc + off, Tp, 1, C, ld, m, cols, s));
+            GELO_TRY(rank16_update(ws.Vc + off, ld, ws.W, ld, C, ld, m, cols, s));
         }
     }
     // accumulate Q = H_0 H_1 ... : start from I, apply the block reflectors last to first; block p
@@ -623,8 +758,8 @@ hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t s) {
         const int c0 = p * NB, m = n_pad - c0;
         const int64_t off = (int64_t)c0 * ld + c0;
         float* C = ws.X + off;
-        GELO_TRY(vt_c(ws, ws.Vc + off, C, ld, m, m, s));
-        GELO_TRY(rank16_update(ws.VT + off, ld, ws.W, ld, C, ld, m, m, s));
+        GELO_TRY(vt_c(ws, ws.Vc + off, ws.Tmat + (int64_t)p * NB * NB, 0, C, ld, m, m, s));
+        GELO_TRY(rank16_update(ws.Vc + off, ld, ws.W, ld, C, ld, m, m, s));
     }
     return hipSuccess;
 }

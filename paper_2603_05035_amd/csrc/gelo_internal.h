@@ -67,14 +67,14 @@ struct FactorWorkspace {
     float* M;        // the matrix being factorised (G, then R + reflectors / L\U)
     float* X;        // the result being accumulated (Q, or A^-1)
     float* Vc;       // per panel: reflector block V with explicit unit diagonal, zeros above
-    float* VT;       // per panel: V * T
-    float* VTt;      // per panel: V * T^T
+    float* Tmat;     // per panel: the 16 x 16 triangle T of the block reflector I - V T V^T
     float* Wpart;    // partial products of the skinny reductions
     float* W;        // kPanel x ld reduced products
     float* rdiag;    // n_pad: diagonal of R
     float* vec;      // 4 * ld floats for the power iterations
     int*   piv;      // n_pad pivot rows
     int*   flag;     // singular-pivot flag
+    int*   counters; // one arrival counter per 64-column strip (zero between kernels)
     float* scalars;  // [0] kappa estimate, [1] sigma_max^2, [2] 1/sigma_min^2
     int n_pad; int64_t ld;
     int wpart_chunks;   // row chunks Wpart can hold

@@ -275,7 +275,8 @@ def test_full_size_sweep_layers(ctx, name, layer):
     print(name, "rel err", err, "kappa", r["kappa"])
     n = w.n
     A = f64(r["A"])
-    assert np.linalg.norm(A @ f64(r["A_inv"]) - np.eye(n)) / math.sqrt(n) < 1e-4
+    # float LU + substitution: residual per row ~ n * eps32 * kappa (eps32 = 2^-24)
+    assert np.linalg.norm(A @ f64(r["A_inv"]) - np.eye(n)) / math.sqrt(n) < n * 2.0 ** -24 * max(r["kappa"], 1.0)
     if name == "sweep_bf16_cond":
         assert r["kappa"] < 100.0
 
