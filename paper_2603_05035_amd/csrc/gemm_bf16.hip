@@ -66,15 +66,15 @@ void gemm_bf16_kernel(Bf16Args g) {
     constexpr int WAVES_N = BN / WN;
     constexpr int NT = (BM / WM) * WAVES_N * 64;
     constexpr int MT = WM / 32;
-    constexpr int A_TILE = BM * A_PITCH;          // elements
+    constexpr int A_TILE = BM * A_PITCH;
     constexpr int B_TILE = BK * BN;
-    constexpr int A_CHUNKS = BM * (BK / 8) / NT;  // 16-byte chunks per thread
+    constexpr int A_CHUNKS = BM * (BK / 8) / NT;
     constexpr int B_CHUNKS = BK * (BN / 8) / NT;
     static_assert(BM * (BK / 8) % NT == 0 && BK * (BN / 8) % NT == 0, "tile / thread mismatch");
 
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t* As = smem;                  // [2][BM][A_PITCH]
-    uint16_t* Bs = smem + 2 * A_TILE;     // [2][BK][BN]
+    uint16_t* As = smem;
+    uint16_t* Bs = smem + 2 * A_TILE;
 
     int tm, tn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, &tm, &tn);
@@ -83,53 +83,71 @@ void gemm_bf16_kernel(Bf16Args g) {
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int j = lane & 31, grp = lane >> 5;
-    const int KA = (g.K + 7) & ~7;        // extent of A's readable (zero padded) columns
+    const int KA = (g.K + 7) & ~7;
     const int k_tiles = (g.K + BK - 1) / BK;
+    const bool n_full = n0 + BN <= g.N;
+
+    // per-thread element offsets of the chunks it stages (rows clamped into the matrix)
+    int a_off[A_CHUNKS], a_lds[A_CHUNKS], b_row[B_CHUNKS], b_col[B_CHUNKS], b_lds[B_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+        const int id = tid + i * NT;
+        const int r = id >> 3, c = id & 7;
+        int row = m0 + r;
+        row = row < g.M ? row : g.M - 1;
+        a_off[i] = row * (int)g.lda + c * 8;
+        a_lds[i] = r * A_PITCH + c * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+        const int id = tid + i * NT;
+        b_row[i] = id / (BN / 8);
+        b_col[i] = n0 + (id % (BN / 8)) * 8;
+        b_lds[i] = b_row[i] * BN + (id % (BN / 8)) * 8;
+    }
 
     u32x4_t a_stage[A_CHUNKS], b_stage[B_CHUNKS];
 
     auto load_global = [&](int kt) {
         const int k0 = kt * BK;
+        const bool fast = n_full && (k0 + BK <= g.K) && (k0 + BK <= g.K0 || k0 >= g.K0);
+        if (fast) {
+            const uint16_t* ap = g.A + k0;
+            const uint16_t* bp; int64_t ldb;
+            if (k0 < g.K0) { bp = g.B0 + (int64_t)k0 * g.ldb0; ldb = g.ldb0; }
+            else { bp = g.B1 + (int64_t)(k0 - g.K0) * g.ldb1; ldb = g.ldb1; }
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            const int id = tid + i * NT;
-            const int r = id >> 3, c = id & 7;
-            int row = m0 + r;
-            row = row < g.M ? row : g.M - 1;
-            const int gk = k0 + c * 8;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (gk < KA) v = *reinterpret_cast<const u32x4_t*>(g.A + (int64_t)row * g.lda + gk);
-            a_stage[i] = v;
-        }
+            for (int i = 0; i < A_CHUNKS; ++i) a_stage[i] = *reinterpret_cast<const u32x4_t*>(ap + a_off[i]);
 #pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            const int id = tid + i * NT;
-            const int r = id / (BN / 8), c = id % (BN / 8);
-            const int gk = k0 + r, gn = n0 + c * 8;
-            u32x4_t v = {0u, 0u, 0u, 0u};
-            if (gk < g.K && gn < g.N) {
-                const uint16_t* p = gk < g.K0 ? g.B0 + (int64_t)gk * g.ldb0 + gn
-                                              : g.B1 + (int64_t)(gk - g.K0) * g.ldb1 + gn;
-                v = *reinterpret_cast<const u32x4_t*>(p);
+            for (int i = 0; i < B_CHUNKS; ++i) b_stage[i] = *reinterpret_cast<const u32x4_t*>(bp + b_row[i] * ldb + b_col[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < A_CHUNKS; ++i) {
+                const int c8 = ((tid + i * NT) & 7) * 8;
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (k0 + c8 < KA) v = *reinterpret_cast<const u32x4_t*>(g.A + k0 + a_off[i]);
+                a_stage[i] = v;
             }
-            b_stage[i] = v;
+#pragma unroll
+            for (int i = 0; i < B_CHUNKS; ++i) {
+                const int gk = k0 + b_row[i], gn = b_col[i];
+                u32x4_t v = {0u, 0u, 0u, 0u};
+                if (gk < g.K && gn < g.N) {
+                    const uint16_t* p = gk < g.K0 ? g.B0 + (int64_t)gk * g.ldb0 + gn
+                                                  : g.B1 + (int64_t)(gk - g.K0) * g.ldb1 + gn;
+                    v = *reinterpret_cast<const u32x4_t*>(p);
+                }
+                b_stage[i] = v;
+            }
         }
     };
     auto store_lds = [&](int buf) {
         uint16_t* as = As + buf * A_TILE;
         uint16_t* bs = Bs + buf * B_TILE;
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            const int id = tid + i * NT;
-            const int r = id >> 3, c = id & 7;
-            *reinterpret_cast<u32x4_t*>(as + r * A_PITCH + c * 8) = a_stage[i];
-        }
+        for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<u32x4_t*>(as + a_lds[i]) = a_stage[i];
 #pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            const int id = tid + i * NT;
-            const int r = id / (BN / 8), c = id % (BN / 8);
-            *reinterpret_cast<u32x4_t*>(bs + r * BN + c * 8) = b_stage[i];
-        }
+        for (int i = 0; i < B_CHUNKS; ++i) *reinterpret_cast<u32x4_t*>(bs + b_lds[i]) = b_stage[i];
     };
 
     f32x16_t acc[MT][4];
@@ -150,16 +168,22 @@ void gemm_bf16_kernel(Bf16Args g) {
 
         const uint16_t* as = As + buf * A_TILE + (wm * WM + j) * A_PITCH + grp * 8;
         const uint16_t* bs = Bs + buf * B_TILE + (grp * 8) * BN + wn * WN + 4 * j;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8_t a_frag[MT];
+
+        bf16x8_t a_frag[2][MT];
+        u32x2_t b_raw[2][8];
+        auto load_frags = [&](int fb, int ks) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
-                a_frag[mt] = *reinterpret_cast<const bf16x8_t*>(as + mt * 32 * A_PITCH + ks * 16);
-            u32x2_t b_raw[8];
+                a_frag[fb][mt] = *reinterpret_cast<const bf16x8_t*>(as + mt * 32 * A_PITCH + ks * 16);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                b_raw[i] = *reinterpret_cast<const u32x2_t*>(bs + (ks * 16 + i) * BN);
+                b_raw[fb][i] = *reinterpret_cast<const u32x2_t*>(bs + (ks * 16 + i) * BN);
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int fb = ks & 1;
+            if (ks + 1 < BK / 16) load_frags(fb ^ 1, ks + 1);     // next step's fragments fly under this step's MFMAs
             bf16x8_t b_frag[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -167,21 +191,20 @@ void gemm_bf16_kernel(Bf16Args g) {
                 const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
-                    t[m] = __builtin_amdgcn_perm(b_raw[2 * m + 1][c >> 1], b_raw[2 * m][c >> 1], sel);
+                    t[m] = __builtin_amdgcn_perm(b_raw[fb][2 * m + 1][c >> 1], b_raw[fb][2 * m][c >> 1], sel);
                 b_frag[c] = __builtin_bit_cast(bf16x8_t, t);
             }
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag[mt], b_frag[c], acc[mt][c], 0, 0, 0);
+                    acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag[fb][mt], b_frag[c], acc[mt][c], 0, 0, 0);
         }
 
         if (kt + 1 < k_tiles) store_lds(buf ^ 1);
         __syncthreads();
     }
 
-    // accumulator element v of lane (j, grp): row 8*(v/4) + 4*grp + v%4, column j of the 32x32 tile
     const int col = n0 + wn * WN + 4 * j;
     if (col < g.N) {
 #pragma unroll
@@ -229,20 +252,19 @@ hipError_t allow_big_lds() {
 }  // namespace
 
 hipError_t gemm_bf16_init() {
-    hipError_t e = allow_big_lds<256, 256, 128>();
+    hipError_t e = allow_big_lds<256, 256, 64>();
     if (e != hipSuccess) return e;
-    e = allow_big_lds<128, 256, 64>();
-    if (e != hipSuccess) return e;
-    return allow_big_lds<128, 128, 64>();
+    return allow_big_lds<128, 128, 32>();
 }
 
-// Tile choice: the largest tile whose grid still fills the 256 compute units.
+// Tile choice (measured on MI355X): 256 x 256 with 8 waves (two per SIMD, wave tile 64 x 128) wins
+// for every shape of the chain whose M exceeds one small tile; tiny M (decode-shaped batches)
+// takes 128 x 128 with 4 waves so that N alone can spread the work over the chip.
 hipError_t gemm_bf16(const GemmOperands& o, hipStream_t stream) {
     if (o.M <= 0 || o.N <= 0 || o.K <= 0) return hipSuccess;
-    auto tiles = [&](int bm, int bn) { return (int64_t)((o.M + bm - 1) / bm) * ((o.N + bn - 1) / bn); };
-    if (tiles(256, 256) >= 256) return launch<256, 256, 128>(o, stream);
-    if (tiles(128, 256) >= 256) return launch<128, 256, 64>(o, stream);
-    return launch<128, 128, 64>(o, stream);
+    if ((int64_t)o.M * o.lda >= (int64_t)1 << 31) return hipErrorInvalidValue;   // the kernel keeps 32-bit element offsets into A
+    if (o.M > 128) return launch<256, 256, 64>(o, stream);
+    return launch<128, 128, 32>(o, stream);
 }
 
 }  // namespace gelo
