@@ -395,6 +395,92 @@ void rank16_update_kernel(const float* L, int64_t ldl, const float* W, int64_t l
     }
 }
 
+// ------------------------------------------------- fused block-reflector update --
+// C <- C - V op(T) V^T C for a 16-column strip of C per workgroup, in ONE pass over C: the strip
+// (m x 16, m a multiple of 16) lives in registers as 16 x 16 blocks in the accumulator layout of
+// v_mfma_f32_16x16x4_f32, so the same registers serve as the B operand of W = V^T C (K = rows)
+// and as the accumulator of C -= V W' (K = the 16 reflectors).  Wave w of 8 owns blocks
+// w, w+8, ...; the 8 partial W are added in wave order (fixed order, reproducible), then
+// W' = -op(T) W is formed once per strip.  V (m x 16, row stride ldv) is read through the caches.
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <int NBLK>
+__global__ __launch_bounds__(512)
+void reflect_strip_kernel(const float* __restrict__ V, int64_t ldv, const float* __restrict__ T, int t_transposed,
+                          float* C, int64_t ldc, int nblocks) {
+    __shared__ float Wp[8][NB][NB];
+    __shared__ float Ws[NB][NB];
+    __shared__ float Wn[NB][NB];
+    __shared__ float Ts[NB][NB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    float* Cs = C + (int64_t)blockIdx.x * NB;
+    if (tid < NB * NB) Ts[tid >> 4][tid & 15] = T[tid];
+
+    f32x4_t cr[NBLK];
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        const int blk = wave + 8 * b;
+        cr[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        if (blk < nblocks) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) cr[b][v] = Cs[(int64_t)(16 * blk + 4 * g + v) * ldc + c];
+        }
+    }
+    // W_partial[i][col] = sum over this wave's rows of V[r][i] C[r][col]; MFMA (b, v) contracts the four
+    // rows 16 blk + 4 kk + v (kk = lane / 16): A = V[row][lane % 16], B = the strip register itself
+    f32x4_t w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        const int blk = wave + 8 * b;
+        if (blk < nblocks) {
+            float a[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) a[v] = V[(int64_t)(16 * blk + 4 * g + v) * ldv + c];
+            w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[b][0], w0, 0, 0, 0);
+            w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], cr[b][1], w1, 0, 0, 0);
+            w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], cr[b][2], w0, 0, 0, 0);
+            w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], cr[b][3], w1, 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) Wp[wave][4 * g + v][c] = w0[v] + w1[v];      // accumulator row 4 g + v, column c
+    __syncthreads();
+    if (tid < NB * NB) {
+        const int i = tid >> 4, cc = tid & 15;
+        float sum = Wp[0][i][cc];
+#pragma unroll
+        for (int w = 1; w < 8; ++w) sum += Wp[w][i][cc];
+        Ws[i][cc] = sum;
+    }
+    __syncthreads();
+    if (tid < NB * NB) {
+        const int i = tid >> 4, cc = tid & 15;
+        float o = 0.f;
+#pragma unroll
+        for (int k = 0; k < NB; ++k) o = fmaf(t_transposed ? Ts[k][i] : Ts[i][k], Ws[k][cc], o);
+        Wn[i][cc] = -o;
+    }
+    __syncthreads();
+    // C_block += V_block W': MFMA q contracts reflectors 4 kk + q; A = V[16 blk + lane % 16][4 kk + q]
+    float bq[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) bq[q] = Wn[4 * g + q][c];
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        const int blk = wave + 8 * b;
+        if (blk < nblocks) {
+            const float4 a4 = *reinterpret_cast<const float4*>(V + (int64_t)(16 * blk + c) * ldv + 4 * g);
+            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, bq[0], cr[b], 0, 0, 0);
+            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, bq[1], cr[b], 0, 0, 0);
+            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, bq[2], cr[b], 0, 0, 0);
+            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, bq[3], cr[b], 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Cs[(int64_t)(16 * blk + 4 * g + v) * ldc + c] = cr[b][v];
+        }
+    }
+}
+
 __global__ __launch_bounds__(256)
 void set_identity_kernel(float* X, int64_t ld, int n_pad) {
     const int c = blockIdx.x * 256 + threadIdx.x;
@@ -679,6 +765,22 @@ hipError_t vt_c(const FactorWorkspace& ws, const float* V, const float* T, int t
     return hipGetLastError();
 }
 
+// C (rows x cols, rows and cols multiples of 16) <- (I - V op(T) V^T) C with op(T) = T^T if t_transposed
+hipError_t apply_block_reflector(const float* V, int64_t ldv, const float* T, int t_transposed, float* C, int64_t ldc,
+                                 int rows, int cols, hipStream_t s) {
+    if (rows <= 0 || cols <= 0) return hipSuccess;
+    if (rows % NB != 0 || cols % NB != 0) return hipErrorInvalidValue;
+    const int nblocks = rows / NB;
+    const dim3 grid(cols / NB), block(512);
+    const int per_wave = (nblocks + 7) / 8;
+    if (per_wave <= 5) hipLaunchKernelGGL(reflect_strip_kernel<5>, grid, block, 0, s, V, ldv, T, t_transposed, C, ldc, nblocks);
+    else if (per_wave <= 10) hipLaunchKernelGGL(reflect_strip_kernel<10>, grid, block, 0, s, V, ldv, T, t_transposed, C, ldc, nblocks);
+    else if (per_wave <= 20) hipLaunchKernelGGL(reflect_strip_kernel<20>, grid, block, 0, s, V, ldv, T, t_transposed, C, ldc, nblocks);
+    else if (per_wave <= 40) hipLaunchKernelGGL(reflect_strip_kernel<40>, grid, block, 0, s, V, ldv, T, t_transposed, C, ldc, nblocks);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 #define GELO_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
 
 }  // namespace
@@ -747,8 +849,7 @@ hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t s) {
         const int cols = n_pad - c0 - NB;
         if (cols > 0) {
             float* C = ws.M + off + NB;
-            GELO_TRY(vt_c(ws, ws.Vc + off, Tp, 1, C, ld, m, cols, s));
-            GELO_TRY(rank16_update(ws.Vc + off, ld, ws.W, ld, C, ld, m, cols, s));
+            GELO_TRY(apply_block_reflector(ws.Vc + off, ld, Tp, 1, C, ld, m, cols, s));
         }
     }
     // accumulate Q = H_0 H_1 ... : start from I, apply the block reflectors last to first; block p
@@ -758,8 +859,7 @@ hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t s) {
         const int c0 = p * NB, m = n_pad - c0;
         const int64_t off = (int64_t)c0 * ld + c0;
         float* C = ws.X + off;
-        GELO_TRY(vt_c(ws, ws.Vc + off, ws.Tmat + (int64_t)p * NB * NB, 0, C, ld, m, m, s));
-        GELO_TRY(rank16_update(ws.Vc + off, ld, ws.W, ld, C, ld, m, m, s));
+        GELO_TRY(apply_block_reflector(ws.Vc + off, ld, ws.Tmat + (int64_t)p * NB * NB, 0, C, ld, m, m, s));
     }
     return hipSuccess;
 }
