@@ -481,6 +481,92 @@ void reflect_strip_kernel(const float* __restrict__ V, int64_t ldv, const float*
     }
 }
 
+// Q = B_0 B_1 ... B_last applied to the identity, ONE launch: column strips of Q are independent,
+// so workgroup j keeps strip j (all rows x 16 columns) in registers and applies the block reflectors
+// B_p = I - V_p T_p V_p^T for p = j, j-1, ..., 0 in turn (panels p > j see only zeros of the strip
+// and are skipped).  Same register layout and MFMA scheme as reflect_strip_kernel.  Vall / ld: the
+// matrix of stored reflector blocks (panel p at row and column 16 p); Tall: 16 x 16 triangles.
+template <int NBLK>
+__global__ __launch_bounds__(512)
+void form_q_kernel(const float* __restrict__ Vall, int64_t ld, const float* __restrict__ Tall,
+                   float* X, int64_t ldx, int total_blocks) {
+    __shared__ float Wp[8][NB][NB];
+    __shared__ float Ws[NB][NB];
+    __shared__ float Wn[NB][NB];
+    __shared__ float Ts[NB][NB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 15, g = lane >> 4;
+    const int strip = blockIdx.x;
+
+    f32x4_t cr[NBLK];
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        const int blk = wave + 8 * b;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) cr[b][v] = (blk == strip && 4 * g + v == c) ? 1.f : 0.f;
+    }
+    for (int p = strip; p >= 0; --p) {
+        const float* Vp = Vall + (int64_t)(NB * p) * ld + NB * p;
+        if (tid < NB * NB) Ts[tid >> 4][tid & 15] = Tall[(int64_t)p * NB * NB + tid];
+        f32x4_t w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+            const int blk = wave + 8 * b;
+            if (blk >= p && blk < total_blocks) {
+                float a[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) a[v] = Vp[(int64_t)(16 * (blk - p) + 4 * g + v) * ld + c];
+                w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[b][0], w0, 0, 0, 0);
+                w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], cr[b][1], w1, 0, 0, 0);
+                w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], cr[b][2], w0, 0, 0, 0);
+                w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], cr[b][3], w1, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Wp[wave][4 * g + v][c] = w0[v] + w1[v];
+        __syncthreads();
+        if (tid < NB * NB) {
+            const int i = tid >> 4, cc = tid & 15;
+            float sum = Wp[0][i][cc];
+#pragma unroll
+            for (int w = 1; w < 8; ++w) sum += Wp[w][i][cc];
+            Ws[i][cc] = sum;
+        }
+        __syncthreads();
+        if (tid < NB * NB) {
+            const int i = tid >> 4, cc = tid & 15;
+            float o = 0.f;
+#pragma unroll
+            for (int k = 0; k < NB; ++k) o = fmaf(Ts[i][k], Ws[k][cc], o);
+            Wn[i][cc] = -o;
+        }
+        __syncthreads();
+        float bq[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) bq[q] = Wn[4 * g + q][c];
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b) {
+            const int blk = wave + 8 * b;
+            if (blk >= p && blk < total_blocks) {
+                const float4 a4 = *reinterpret_cast<const float4*>(Vp + (int64_t)(16 * (blk - p) + c) * ld + 4 * g);
+                cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, bq[0], cr[b], 0, 0, 0);
+                cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, bq[1], cr[b], 0, 0, 0);
+                cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, bq[2], cr[b], 0, 0, 0);
+                cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, bq[3], cr[b], 0, 0, 0);
+            }
+        }
+    }
+    float* Xs = X + (int64_t)strip * NB;
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        const int blk = wave + 8 * b;
+        if (blk < total_blocks) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Xs[(int64_t)(16 * blk + 4 * g + v) * ldx + c] = cr[b][v];
+        }
+    }
+}
+
 __global__ __launch_bounds__(256)
 void set_identity_kernel(float* X, int64_t ld, int n_pad) {
     const int c = blockIdx.x * 256 + threadIdx.x;
@@ -852,14 +938,17 @@ hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t s) {
             GELO_TRY(apply_block_reflector(ws.Vc + off, ld, Tp, 1, C, ld, m, cols, s));
         }
     }
-    // accumulate Q = H_0 H_1 ... : start from I, apply the block reflectors last to first; block p
-    // only touches the trailing (n_pad - c0)^2 corner, which is still the identity elsewhere
-    GELO_TRY(set_identity(ws.X, ld, n_pad, s));
-    for (int p = panels - 1; p >= 0; --p) {
-        const int c0 = p * NB, m = n_pad - c0;
-        const int64_t off = (int64_t)c0 * ld + c0;
-        float* C = ws.X + off;
-        GELO_TRY(apply_block_reflector(ws.Vc + off, ld, ws.Tmat + (int64_t)p * NB * NB, 0, C, ld, m, m, s));
+    // accumulate Q = B_0 B_1 ... B_last I in one launch (every column strip independently)
+    {
+        const int total_blocks = n_pad / NB;
+        const dim3 grid(total_blocks), block(512);
+        const int per_wave = (total_blocks + 7) / 8;
+        if (per_wave <= 5) hipLaunchKernelGGL(form_q_kernel<5>, grid, block, 0, s, ws.Vc, ld, ws.Tmat, ws.X, ld, total_blocks);
+        else if (per_wave <= 10) hipLaunchKernelGGL(form_q_kernel<10>, grid, block, 0, s, ws.Vc, ld, ws.Tmat, ws.X, ld, total_blocks);
+        else if (per_wave <= 20) hipLaunchKernelGGL(form_q_kernel<20>, grid, block, 0, s, ws.Vc, ld, ws.Tmat, ws.X, ld, total_blocks);
+        else if (per_wave <= 40) hipLaunchKernelGGL(form_q_kernel<40>, grid, block, 0, s, ws.Vc, ld, ws.Tmat, ws.X, ld, total_blocks);
+        else return hipErrorInvalidValue;
+        GELO_TRY(hipGetLastError());
     }
     return hipSuccess;
 }
