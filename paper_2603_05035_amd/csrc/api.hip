@@ -333,7 +333,7 @@ gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh,
     g.B0 = H; g.ldb0 = ldh; g.K0 = m->n_data;
     g.B1 = m->S; g.ldb1 = m->d;
     g.C = U; g.ldc = ldu;
-    g.M = m->n; g.N = m->d; g.K = m->n;
+    g.M = m->n; g.N = m->d; g.K = m->n; g.a_zero_padded = true;
     st = run_gemm(ctx, m->dtype, g, s);
     if (st != GELO_OK) return st;
     m->mixed = true; m->last_stream = s;
@@ -381,7 +381,7 @@ gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* m, int p, const void* Y, int6
     g.B0 = Y; g.ldb0 = ldy; g.K0 = m->n;
     g.B1 = Y; g.ldb1 = ldy;
     g.C = Z; g.ldc = ldz;
-    g.M = m->n_data; g.N = p; g.K = m->n;
+    g.M = m->n_data; g.N = p; g.K = m->n; g.a_zero_padded = true;
     st = run_gemm(ctx, m->dtype, g, s);
     if (st != GELO_OK) return st;
     m->consumed = true; m->last_stream = s;

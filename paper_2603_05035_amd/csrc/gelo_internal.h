@@ -25,6 +25,7 @@ struct GemmOperands {
     const void* B1; int64_t ldb1;
     void* C;        int64_t ldc;
     int M, N, K;
+    bool a_zero_padded = false;   // A is readable and zero in columns [K, round_up(K, 64))
 };
 hipError_t gemm_bf16(const GemmOperands& g, hipStream_t stream);
 hipError_t gemm_f32(const GemmOperands& g, hipStream_t stream);

@@ -223,6 +223,174 @@ void gemm_bf16_kernel(Bf16Args g) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Fast path: 256 x 256 tile, 8 waves, K step 32, FOUR LDS stages filled by direct-to-LDS loads
+// (global_load_lds_dwordx4: no staging registers, no ds_write), prefetch distance 3, one barrier
+// per K step.  A rows (64 bytes per stage) are stored with their 16-byte chunks XOR-swizzled so
+// that the 16-byte fragment reads of 16 consecutive rows hit distinct banks (measured: zero
+// conflicts); B rows (512 bytes) are stored linearly.  Out-of-range rows / columns are clamped
+// to valid addresses instead of being zero-filled, which is correct because A is zero in
+// columns [K, round_up(K, 32)) (required by the dispatcher) and clamped B rows are finite.
+namespace dma {
+
+constexpr int BM = 256, BN = 256, BKS = 32, STAGES = 4, DIST = 3;
+constexpr int A_BYTES = BM * BKS * 2;           // 16 KB, rows of 64 B, 16-byte chunks swizzled
+constexpr int B_BYTES = BKS * BN * 2;           // 16 KB, rows of 512 B
+constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
+    const uint32_t uni = __builtin_amdgcn_readfirstlane(lds_addr);     // wave-uniform by construction
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(gptr), "s"(uni) : "memory", "m0");
+}
+template <int N> __device__ __forceinline__ void wait_vm() {
+    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+}
+
+__global__ __launch_bounds__(512)
+void gemm_bf16_dma_kernel(Bf16Args g) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    const uint32_t lds_base = (uint32_t)(size_t)lds;
+
+    int tm, tn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, &tm, &tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int j = lane & 31, grp = lane >> 5;
+    const int T = (g.K + BKS - 1) / BKS;
+
+    // kernel arguments pinned in scalar registers (a lane-varying choice between two argument
+    // fields would otherwise be compiled into a per-lane memory load of the argument block)
+    auto uni32 = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
+    auto uni64 = [&](int64_t x) {
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((int)(uint32_t)x), hi = __builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)x >> 32));
+        return (int64_t)(((uint64_t)hi << 32) | lo);
+    };
+    const int K = uni32(g.K), K0 = uni32(g.K0);
+    const int64_t ldb0 = uni64(g.ldb0), ldb1 = uni64(g.ldb1);
+    const uint16_t* B0p = (const uint16_t*)uni64((int64_t)g.B0);
+    const uint16_t* B1p = (const uint16_t*)uni64((int64_t)g.B1);
+
+    // ---- what this lane fetches for every tile: 2 chunks of A and 2 of B ----
+    const uint16_t* a_src[2]; uint32_t a_dst[2];
+    int b_krow[2], b_gn; uint32_t b_dst[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int blk = wave * 2 + i;
+        const int row = blk * 16 + (lane >> 2), cp = lane & 3;
+        const int c = cp ^ (((row >> 1) & 3) ^ ((row >> 3) & 1));
+        int grow = m0 + row; grow = grow < g.M ? grow : g.M - 1;
+        a_src[i] = g.A + (int64_t)grow * g.lda + c * 8;
+        a_dst[i] = blk * 1024;                                  // + lane * 16 implied
+        b_krow[i] = blk * 2 + (lane >> 5);
+        b_dst[i] = A_BYTES + blk * 1024;
+    }
+    { int gn = n0 + (lane & 31) * 8; b_gn = gn < g.N ? gn : g.N - 8; }
+
+    auto issue = [&](int t) {
+        const int k0 = t * BKS;
+        const uint32_t st = lds_base + (t % STAGES) * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) dma16(a_src[i] + k0, st + a_dst[i]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            int gk = k0 + b_krow[i]; gk = gk < K ? gk : K - 1;
+            const bool first = gk < K0;
+            const uint16_t* base = first ? B0p : B1p;
+            const int64_t off = first ? (int64_t)gk * ldb0 : (int64_t)(gk - K0) * ldb1;
+            dma16(base + off + b_gn, st + b_dst[i]);
+        }
+    };
+    // wait until this wave's fetches of tile t have landed (tiles up to min(T-1, t+2) may be in flight)
+    auto wait_tile = [&](int t) {
+        const int later = (T - 1 - t) < 2 ? (T - 1 - t) : 2;
+        if (later >= 2) wait_vm<8>(); else if (later == 1) wait_vm<4>(); else wait_vm<0>();
+    };
+
+    // ---- fragment addressing ----
+    const int a_row0 = wm * 64 + j;                             // + mt * 32
+    const int a_sw = ((j >> 1) & 3) ^ ((j >> 3) & 1);
+    const uint32_t a_frag_off0 = a_row0 * 64;
+    const uint32_t b_frag_off = A_BYTES + (grp * 8) * 512 + (wn * 128 + 4 * j) * 2;
+
+    bf16x8_t a_frag[2][2];
+    u32x2_t b_raw[2][8];
+    auto read_frags = [&](int t) {
+        const uint8_t* st = lds + (t % STAGES) * STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+                a_frag[ks][mt] = *reinterpret_cast<const bf16x8_t*>(st + a_frag_off0 + mt * 32 * 64 + (((ks * 2 + grp) ^ a_sw) * 16));
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                b_raw[ks][i] = *reinterpret_cast<const u32x2_t*>(st + b_frag_off + (ks * 16 + i) * 512);
+        }
+    };
+
+    f32x16_t acc[2][4];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0.f;
+
+    auto mfmas = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8_t b_frag[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                u32x4_t t4;
+                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+                    t4[m] = __builtin_amdgcn_perm(b_raw[ks][2 * m + 1][c >> 1], b_raw[ks][2 * m][c >> 1], sel);
+                b_frag[c] = __builtin_bit_cast(bf16x8_t, t4);
+            }
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag[ks][mt], b_frag[c], acc[mt][c], 0, 0, 0);
+        }
+    };
+
+#pragma unroll
+    for (int t = 0; t < DIST; ++t) if (t < T) issue(t);
+
+    for (int t = 0; t < T; ++t) {
+        wait_tile(t);
+        __builtin_amdgcn_s_barrier();               // tile t has landed for every wave; stage (t-1)%4 is free
+        if (t + DIST < T) issue(t + DIST);
+        read_frags(t);
+        mfmas();
+    }
+
+    const int col = n0 + wn * 128 + 4 * j;
+    if (col < g.N) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm * 64 + mt * 32 + 8 * (v >> 2) + 4 * grp + (v & 3);
+                if (row < g.M) {
+                    u32x2_t out;
+                    out[0] = pack_bf16x2(acc[mt][0][v], acc[mt][1][v]);
+                    out[1] = pack_bf16x2(acc[mt][2][v], acc[mt][3][v]);
+                    *reinterpret_cast<u32x2_t*>(g.C + (int64_t)row * g.ldc + col) = out;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace dma
+
 template <int BM, int BN, int WM>
 constexpr size_t smem_bytes() { return 2 * (size_t)(BM * A_PITCH + BK * BN) * sizeof(uint16_t); }
 
@@ -252,7 +420,10 @@ hipError_t allow_big_lds() {
 }  // namespace
 
 hipError_t gemm_bf16_init() {
-    hipError_t e = allow_big_lds<256, 256, 64>();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dma::gemm_bf16_dma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, dma::STAGES * dma::STAGE_BYTES);
+    if (e != hipSuccess) return e;
+    e = allow_big_lds<256, 256, 64>();
     if (e != hipSuccess) return e;
     return allow_big_lds<128, 128, 32>();
 }
@@ -263,6 +434,19 @@ hipError_t gemm_bf16_init() {
 hipError_t gemm_bf16(const GemmOperands& o, hipStream_t stream) {
     if (o.M <= 0 || o.N <= 0 || o.K <= 0) return hipSuccess;
     if ((int64_t)o.M * o.lda >= (int64_t)1 << 31) return hipErrorInvalidValue;   // the kernel keeps 32-bit element offsets into A
+    if (o.M > 128 && o.N >= 8 && (o.a_zero_padded || o.K % 32 == 0)) {
+        Bf16Args a;
+        a.A = (const uint16_t*)o.A;   a.lda = o.lda;
+        a.B0 = (const uint16_t*)o.B0; a.ldb0 = o.ldb0; a.K0 = o.K0;
+        a.B1 = (const uint16_t*)o.B1; a.ldb1 = o.ldb1;
+        a.C = (uint16_t*)o.C;         a.ldc = o.ldc;
+        a.M = o.M; a.N = o.N; a.K = o.K;
+        a.tiles_m = (o.M + dma::BM - 1) / dma::BM;
+        a.tiles_n = (o.N + dma::BN - 1) / dma::BN;
+        hipLaunchKernelGGL(dma::gemm_bf16_dma_kernel, dim3(a.tiles_m * a.tiles_n), dim3(512),
+                           (size_t)dma::STAGES * dma::STAGE_BYTES, stream, a);
+        return hipGetLastError();
+    }
     if (o.M > 128) return launch<256, 256, 64>(o, stream);
     return launch<128, 128, 32>(o, stream);
 }
