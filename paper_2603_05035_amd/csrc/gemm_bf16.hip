@@ -224,28 +224,28 @@ void gemm_bf16_kernel(Bf16Args g) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast path: 256 x 256 tile, 8 waves, K step 32, FOUR LDS stages filled by direct-to-LDS loads
-// (global_load_lds_dwordx4: no staging registers, no ds_write), prefetch distance 3, one barrier
-// per K step.  A rows (64 bytes per stage) are stored with their 16-byte chunks XOR-swizzled so
-// that the 16-byte fragment reads of 16 consecutive rows hit distinct banks (measured: zero
-// conflicts); B rows (512 bytes) are stored linearly.  Out-of-range rows / columns are clamped
-// to valid addresses instead of being zero-filled, which is correct because A is zero in
-// columns [K, round_up(K, 32)) (required by the dispatcher) and clamped B rows are finite.
+// Fast path: 256 x 256 tile, 8 waves, K step 64, two LDS stages filled by direct-to-LDS loads
+// (global_load_lds_dwordx4: no staging registers, no ds_write), one barrier per K step.  A rows
+// (128 bytes per stage) are stored with their 16-byte chunks XOR-swizzled so that the 16-byte
+// fragment reads of 16 consecutive rows hit distinct banks; B rows (512 bytes) are stored
+// linearly.  Out-of-range rows / columns are clamped to valid addresses instead of being
+// zero-filled, which is correct because A is zero in columns [K, round_up(K, 64)) (required by
+// the dispatcher) and clamped B rows are finite.  Measured against a 32-deep K step with four
+// stages and prefetch distance 3, the longer step wins by 1-5 %: the fixed cost per barrier
+// (wait, barrier, address arithmetic of the fetches, first fragment reads) is paid half as often.
 namespace dma {
 
-constexpr int BM = 256, BN = 256, BKS = 32, STAGES = 4, DIST = 3;
-constexpr int A_BYTES = BM * BKS * 2;           // 16 KB, rows of 64 B, 16-byte chunks swizzled
-constexpr int B_BYTES = BKS * BN * 2;           // 16 KB, rows of 512 B
+// One barrier per 64-deep K step: two LDS stages of 64 KB, the next K step fetched (straight from
+// global memory into LDS, no register staging) while the current one is multiplied.  Fragments
+// are double-buffered per 16-deep MFMA step so LDS reads of step s+1 overlap the MFMAs of step s.
+constexpr int BM = 256, BN = 256, BKS = 64, STAGES = 2;
+constexpr int A_BYTES = BM * BKS * 2;           // 32 KB, rows of 128 B, 16-byte chunks swizzled
+constexpr int B_BYTES = BKS * BN * 2;           // 32 KB, rows of 512 B
 constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
 
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
     const uint32_t uni = __builtin_amdgcn_readfirstlane(lds_addr);     // wave-uniform by construction
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(gptr), "s"(uni) : "memory", "m0");
-}
-template <int N> __device__ __forceinline__ void wait_vm() {
-    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
 }
 
 __global__ __launch_bounds__(512)
@@ -274,14 +274,16 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
     const uint16_t* B0p = (const uint16_t*)uni64((int64_t)g.B0);
     const uint16_t* B1p = (const uint16_t*)uni64((int64_t)g.B1);
 
-    // ---- what this lane fetches for every tile: 2 chunks of A and 2 of B ----
-    const uint16_t* a_src[2]; uint32_t a_dst[2];
-    int b_krow[2], b_gn; uint32_t b_dst[2];
+    // ---- what this lane fetches for every K step: 4 chunks of A and 4 of B (1 KB per wave each) ----
+    // A chunk c of row r sits at position c ^ ((r ^ (r >> 3)) & 7) of the row's eight: the 16 rows a
+    // fragment read touches then fall on distinct banks.
+    const uint16_t* a_src[4]; uint32_t a_dst[4];
+    int b_krow[4], b_gn; uint32_t b_dst[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int blk = wave * 2 + i;
-        const int row = blk * 16 + (lane >> 2), cp = lane & 3;
-        const int c = cp ^ (((row >> 1) & 3) ^ ((row >> 3) & 1));
+    for (int i = 0; i < 4; ++i) {
+        const int blk = wave * 4 + i;
+        const int row = blk * 8 + (lane >> 3), cp = lane & 7;
+        const int c = cp ^ ((row ^ (row >> 3)) & 7);
         int grow = m0 + row; grow = grow < g.M ? grow : g.M - 1;
         a_src[i] = g.A + (int64_t)grow * g.lda + c * 8;
         a_dst[i] = blk * 1024;                                  // + lane * 16 implied
@@ -292,11 +294,11 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
 
     auto issue = [&](int t) {
         const int k0 = t * BKS;
-        const uint32_t st = lds_base + (t % STAGES) * STAGE_BYTES;
+        const uint32_t st = lds_base + (t & 1) * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) dma16(a_src[i] + k0, st + a_dst[i]);
+        for (int i = 0; i < 4; ++i) dma16(a_src[i] + k0, st + a_dst[i]);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 4; ++i) {
             int gk = k0 + b_krow[i]; gk = gk < K ? gk : K - 1;
             const bool first = gk < K0;
             const uint16_t* base = first ? B0p : B1p;
@@ -304,32 +306,12 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
             dma16(base + off + b_gn, st + b_dst[i]);
         }
     };
-    // wait until this wave's fetches of tile t have landed (tiles up to min(T-1, t+2) may be in flight)
-    auto wait_tile = [&](int t) {
-        const int later = (T - 1 - t) < 2 ? (T - 1 - t) : 2;
-        if (later >= 2) wait_vm<8>(); else if (later == 1) wait_vm<4>(); else wait_vm<0>();
-    };
 
     // ---- fragment addressing ----
     const int a_row0 = wm * 64 + j;                             // + mt * 32
-    const int a_sw = ((j >> 1) & 3) ^ ((j >> 3) & 1);
-    const uint32_t a_frag_off0 = a_row0 * 64;
+    const int a_sw = (j ^ (j >> 3)) & 7;                        // mt = 1 flips bit 2
+    const uint32_t a_frag_off0 = a_row0 * 128;
     const uint32_t b_frag_off = A_BYTES + (grp * 8) * 512 + (wn * 128 + 4 * j) * 2;
-
-    bf16x8_t a_frag[2][2];
-    u32x2_t b_raw[2][8];
-    auto read_frags = [&](int t) {
-        const uint8_t* st = lds + (t % STAGES) * STAGE_BYTES;
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-                a_frag[ks][mt] = *reinterpret_cast<const bf16x8_t*>(st + a_frag_off0 + mt * 32 * 64 + (((ks * 2 + grp) ^ a_sw) * 16));
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                b_raw[ks][i] = *reinterpret_cast<const u32x2_t*>(st + b_frag_off + (ks * 16 + i) * 512);
-        }
-    };
 
     f32x16_t acc[2][4];
 #pragma unroll
@@ -339,9 +321,27 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0.f;
 
-    auto mfmas = [&]() {
+    issue(0);
+    for (int t = 0; t < T; ++t) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's share of K step t has landed
+        __builtin_amdgcn_s_barrier();                          // everyone's has, and the other stage is free
+        if (t + 1 < T) issue(t + 1);
+        const uint8_t* st = lds + (t & 1) * STAGE_BYTES;
+        bf16x8_t a_frag[2][2];
+        u32x2_t b_raw[2][8];
+        auto load_frags = [&](int fb, int ks) {
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+            for (int mt = 0; mt < 2; ++mt)
+                a_frag[fb][mt] = *reinterpret_cast<const bf16x8_t*>(st + a_frag_off0 + mt * 32 * 128 + (((ks * 2 + grp) ^ a_sw ^ (mt * 4)) * 16));
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                b_raw[fb][i] = *reinterpret_cast<const u32x2_t*>(st + b_frag_off + (ks * 16 + i) * 512);
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int fb = ks & 1;
+            if (ks + 1 < 4) load_frags(fb ^ 1, ks + 1);
             bf16x8_t b_frag[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -349,26 +349,15 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
                 const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
-                    t4[m] = __builtin_amdgcn_perm(b_raw[ks][2 * m + 1][c >> 1], b_raw[ks][2 * m][c >> 1], sel);
+                    t4[m] = __builtin_amdgcn_perm(b_raw[fb][2 * m + 1][c >> 1], b_raw[fb][2 * m][c >> 1], sel);
                 b_frag[c] = __builtin_bit_cast(bf16x8_t, t4);
             }
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag[ks][mt], b_frag[c], acc[mt][c], 0, 0, 0);
+                    acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag[fb][mt], b_frag[c], acc[mt][c], 0, 0, 0);
         }
-    };
-
-#pragma unroll
-    for (int t = 0; t < DIST; ++t) if (t < T) issue(t);
-
-    for (int t = 0; t < T; ++t) {
-        wait_tile(t);
-        __builtin_amdgcn_s_barrier();               // tile t has landed for every wave; stage (t-1)%4 is free
-        if (t + DIST < T) issue(t + DIST);
-        read_frags(t);
-        mfmas();
     }
 
     const int col = n0 + wn * 128 + 4 * j;
@@ -434,7 +423,7 @@ hipError_t gemm_bf16_init() {
 hipError_t gemm_bf16(const GemmOperands& o, hipStream_t stream) {
     if (o.M <= 0 || o.N <= 0 || o.K <= 0) return hipSuccess;
     if ((int64_t)o.M * o.lda >= (int64_t)1 << 31) return hipErrorInvalidValue;   // the kernel keeps 32-bit element offsets into A
-    if (o.M > 128 && o.N >= 8 && (o.a_zero_padded || o.K % 32 == 0)) {
+    if (o.M > 128 && o.N >= 8 && (o.a_zero_padded || o.K % dma::BKS == 0)) {
         Bf16Args a;
         a.A = (const uint16_t*)o.A;   a.lda = o.lda;
         a.B0 = (const uint16_t*)o.B0; a.ldb0 = o.ldb0; a.K0 = o.K0;
