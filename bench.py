@@ -40,6 +40,66 @@ def gen_flops(w, attempts=1):
     return {0: qr, 1: lu * attempts, 2: qr + lu}[w.kind]
 
 
+CAL_ELEMS = 1 << 28                                   # fp32 elements of the calibration copy: 1 GiB read, 1 GiB written
+SRC_PATH = os.path.join(ROOT, "paper_2603_05035_amd", "csrc", "gemm_bf16.hip")
+TRAFFIC_PATH = os.path.join(ROOT, "profiles", "gemm_project_traffic.json")
+
+
+def write_traffic_record(workload: str, fetch_csv: str, write_csv: str) -> int:
+    """HBM bytes per launch of the projection GEMM from two counter runs.
+
+    FETCH_SIZE and WRITE_SIZE are reported in KiB per dispatch.  Each is scaled by the factor that maps
+    what the same counter reads for the calibration copy (a plain elementwise kernel that reads and
+    writes CAL_ELEMS fp32 values) onto that kernel's known byte count.
+    """
+    import csv
+    import hashlib
+    from paper_2603_05035_amd import workloads as wl
+    w = wl.WORKLOADS[workload]
+    proj_grid = ((w.n + 255) // 256) * ((w.p + 255) // 256) * 512       # threads of the projection launch
+
+    def read(path, counter):
+        gemm, cal = [], []
+        for row in csv.DictReader(open(path, newline="")):
+            if row["Counter_Name"] != counter:
+                continue
+            name, grid, val = row["Kernel_Name"], int(row["Grid_Size"]), float(row["Counter_Value"])
+            if "gemm_bf16_dma_kernel" in name and grid == proj_grid:
+                gemm.append(val)
+            elif "elementwise_kernel" in name and "Mul" in name and grid >= CAL_ELEMS // 64:
+                cal.append(val)
+        if not gemm or not cal:
+            raise SystemExit(f"{path}: {len(gemm)} projection launches, {len(cal)} calibration launches with {counter}")
+        return sum(gemm) / len(gemm), sum(cal) / len(cal), len(gemm), len(cal)
+
+    known = CAL_ELEMS * 4.0
+    f_gemm, f_cal, nf, ncf = read(fetch_csv, "FETCH_SIZE")
+    w_gemm, w_cal, nw, ncw = read(write_csv, "WRITE_SIZE")
+    fetch_factor, write_factor = known / (f_cal * 1024.0), known / (w_cal * 1024.0)
+    fetch_b, write_b = f_gemm * 1024.0 * fetch_factor, w_gemm * 1024.0 * write_factor
+    rec = {
+        "workload": w.name,
+        "kernel": "gemm_bf16_dma_kernel (project Y = U W)",
+        "kernel_source_sha1": hashlib.sha1(open(SRC_PATH, "rb").read()).hexdigest(),
+        "traffic_bytes_per_launch": fetch_b + write_b,
+        "fetch_bytes_per_launch": fetch_b, "write_bytes_per_launch": write_b,
+        "algorithmic_bytes_per_launch": 2.0 * (w.n * w.d + w.d * w.p + w.n * w.p),
+        "raw_KiB": {"FETCH_SIZE": f_gemm, "WRITE_SIZE": w_gemm, "FETCH_SIZE_copy": f_cal, "WRITE_SIZE_copy": w_cal},
+        "calibration": {"copy_bytes_each_way": known, "fetch_factor": fetch_factor, "write_factor": write_factor},
+        "launches_averaged": {"projection": [nf, nw], "copy": [ncf, ncw]},
+        "commands": ["rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o fetch -- "
+                     "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --traffic-calibration",
+                     "rocprofv3 --pmc WRITE_SIZE --output-format csv -d <dir> -o write -- "
+                     "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --traffic-calibration",
+                     "python3 bench.py --write-traffic-record <fetch>_counter_collection.csv <write>_counter_collection.csv"],
+    }
+    with open(TRAFFIC_PATH, "w") as f:
+        json.dump(rec, f, indent=1)
+        f.write("\n")
+    print(json.dumps(rec))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -48,7 +108,14 @@ def main() -> int:
     ap.add_argument("--workload", default="llama7b_bf16_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pipeline", type=int, default=8, help="mixing matrices drawn ahead on side streams")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run a plain elementwise copy of known size (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--write-traffic-record", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: turn the counter_collection.csv files of two rocprofv3 --pmc runs of "
+                         "'bench.py --traffic-calibration' (FETCH_SIZE, then WRITE_SIZE) into profiles/gemm_project_traffic.json")
     args = ap.parse_args()
+    if args.write_traffic_record:
+        return write_traffic_record(args.workload, *args.write_traffic_record)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
@@ -159,11 +226,11 @@ def main() -> int:
     t_chain = (stage["mix"] + stage["project"] + stage["unmix"]) * 1e-3
 
     # ---- the dominant kernel alone: the projection GEMM, one launch per event pair ----
-    for _ in range(3):
+    for _ in range(30):                       # long enough for the clocks to settle under this kernel's load
         g.gelo_project(ctx, U, W, Y)
     torch.cuda.synchronize()
     pairs = []
-    for _ in range(max(K, 20)):
+    for _ in range(max(K, 50)):
         a, b = ev(), ev()
         a.record()
         g.gelo_project(ctx, U, W, Y)
@@ -206,12 +273,20 @@ def main() -> int:
     # kernel source those runs were taken on
     try:
         import hashlib
-        rec = json.load(open(os.path.join(ROOT, "profiles", "gemm_project_traffic.json")))
-        src = open(os.path.join(ROOT, "paper_2603_05035_amd", "csrc", "gemm_bf16.hip"), "rb").read()
+        rec = json.load(open(TRAFFIC_PATH))
+        src = open(SRC_PATH, "rb").read()
         if rec.get("workload") == w.name and rec.get("kernel_source_sha1") == hashlib.sha1(src).hexdigest():
             result["roofline"]["traffic"] = rec["traffic_bytes_per_launch"]
     except Exception:
         pass
+
+    if args.traffic_calibration:
+        src_t = torch.ones(CAL_ELEMS, dtype=torch.float32, device="cuda")
+        dst_t = torch.empty_like(src_t)
+        for _ in range(3):
+            torch.mul(src_t, 1.0, out=dst_t)
+        torch.cuda.synchronize()
+        del src_t, dst_t
 
     if not args.no_cpu_baseline:
         # The oracle as it stands, on the host cores, float64: one whole step (its own Philox sampling,

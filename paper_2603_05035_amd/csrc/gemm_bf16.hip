@@ -43,18 +43,22 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 
 // Workgroups are dealt to the 8 XCDs round-robin; give each XCD (own L2) a contiguous run of
-// tiles, and inside a run walk GROUP_M tile-rows before moving along N so that tiles in flight
-// share A row panels and B column panels.
+// tiles, and inside a run walk a group of tile-rows before moving along N so that tiles in flight
+// share A row panels and B column panels.  The tile-rows are split into equal groups of at most 8
+// (9 rows -> 5 + 4, not 8 + 1): a short last group would hand one XCD a whole row of tiles, i.e.
+// all of B.  Measured on the 2150 x 12288 x 4096 projection, L2 fills drop from 474 MB to 376 MB
+// per launch; the run time does not change (the fills are served at a fraction of peak bandwidth).
 __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int* tm, int* tn) {
     const int total = tiles_m * tiles_n;
     const int xcd = bid & 7, slot = bid >> 3;
     const int base = total >> 3, rem = total & 7;
     const int lid = xcd * base + (xcd < rem ? xcd : rem) + slot;
-    constexpr int GROUP_M = 8;
-    const int per_group = GROUP_M * tiles_n;
+    const int groups = (tiles_m + 7) >> 3;
+    const int group_m = (tiles_m + groups - 1) / groups;
+    const int per_group = group_m * tiles_n;
     const int group = lid / per_group;
-    const int first_m = group * GROUP_M;
-    const int gsz = (tiles_m - first_m) < GROUP_M ? (tiles_m - first_m) : GROUP_M;
+    const int first_m = group * group_m;
+    const int gsz = (tiles_m - first_m) < group_m ? (tiles_m - first_m) : group_m;
     const int in_group = lid - group * per_group;
     *tm = first_m + in_group % gsz;
     *tn = in_group / gsz;
