@@ -100,8 +100,7 @@ __device__ __forceinline__ float lane_value(float v) {
 // every wave holds the quantities of column s; the update coefficients are then read into
 // scalar registers.  The column loop is unrolled so that all register indices are constants.
 template <int NTHR, int R>
-__global__ __launch_bounds__(NTHR)
-void qr_panel_kernel(float* Mp, float* Vc, float* Tg, float* rdiag, int64_t ld, int m) {
+__device__ __forceinline__ void qr_panel_body(float* Mp, float* Vc, float* Tg, float* rdiag, int64_t ld, int m) {
     constexpr int NW = NTHR / 64;
     __shared__ float red[2][NW][NB];
     __shared__ float prow[2][NB];
@@ -220,6 +219,12 @@ void qr_panel_kernel(float* Mp, float* Vc, float* Tg, float* rdiag, int64_t ld, 
             }
         }
     }
+}
+
+template <int NTHR, int R>
+__global__ __launch_bounds__(NTHR)
+void qr_panel_kernel(float* Mp, float* Vc, float* Tg, float* rdiag, int64_t ld, int m) {
+    qr_panel_body<NTHR, R>(Mp, Vc, Tg, rdiag, ld, m);
 }
 
 // ------------------------------------------------------- skinny rank-16 kernels --
@@ -405,16 +410,14 @@ void rank16_update_kernel(const float* L, int64_t ldl, const float* W, int64_t l
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 template <int NBLK>
-__global__ __launch_bounds__(512)
-void reflect_strip_kernel(const float* __restrict__ V, int64_t ldv, const float* __restrict__ T, int t_transposed,
-                          float* C, int64_t ldc, int nblocks) {
+__device__ __forceinline__ void reflect_strip_body(const float* __restrict__ V, int64_t ldv, const float* __restrict__ T,
+                                                   int t_transposed, float* Cs, int64_t ldc, int nblocks) {
     __shared__ float Wp[8][NB][NB];
     __shared__ float Ws[NB][NB];
     __shared__ float Wn[NB][NB];
     __shared__ float Ts[NB][NB];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = lane & 15, g = lane >> 4;
-    float* Cs = C + (int64_t)blockIdx.x * NB;
     if (tid < NB * NB) Ts[tid >> 4][tid & 15] = T[tid];
 
     f32x4_t cr[NBLK];
@@ -481,90 +484,44 @@ void reflect_strip_kernel(const float* __restrict__ V, int64_t ldv, const float*
     }
 }
 
-// Q = B_0 B_1 ... B_last applied to the identity, ONE launch: column strips of Q are independent,
-// so workgroup j keeps strip j (all rows x 16 columns) in registers and applies the block reflectors
-// B_p = I - V_p T_p V_p^T for p = j, j-1, ..., 0 in turn (panels p > j see only zeros of the strip
-// and are skipped).  Same register layout and MFMA scheme as reflect_strip_kernel.  Vall / ld: the
-// matrix of stored reflector blocks (panel p at row and column 16 p); Tall: 16 x 16 triangles.
 template <int NBLK>
 __global__ __launch_bounds__(512)
-void form_q_kernel(const float* __restrict__ Vall, int64_t ld, const float* __restrict__ Tall,
-                   float* X, int64_t ldx, int total_blocks) {
-    __shared__ float Wp[8][NB][NB];
-    __shared__ float Ws[NB][NB];
-    __shared__ float Wn[NB][NB];
-    __shared__ float Ts[NB][NB];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = lane & 15, g = lane >> 4;
-    const int strip = blockIdx.x;
+void reflect_strip_kernel(const float* __restrict__ V, int64_t ldv, const float* __restrict__ T, int t_transposed,
+                          float* C, int64_t ldc, int nblocks) {
+    reflect_strip_body<NBLK>(V, ldv, T, t_transposed, C + (int64_t)blockIdx.x * NB, ldc, nblocks);
+}
 
-    f32x4_t cr[NBLK];
-#pragma unroll
-    for (int b = 0; b < NBLK; ++b) {
-        const int blk = wave + 8 * b;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) cr[b][v] = (blk == strip && 4 * g + v == c) ? 1.f : 0.f;
-    }
-    for (int p = strip; p >= 0; --p) {
-        const float* Vp = Vall + (int64_t)(NB * p) * ld + NB * p;
-        if (tid < NB * NB) Ts[tid >> 4][tid & 15] = Tall[(int64_t)p * NB * NB + tid];
-        f32x4_t w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int b = 0; b < NBLK; ++b) {
-            const int blk = wave + 8 * b;
-            if (blk >= p && blk < total_blocks) {
-                float a[4];
-#pragma unroll
-                for (int v = 0; v < 4; ++v) a[v] = Vp[(int64_t)(16 * (blk - p) + 4 * g + v) * ld + c];
-                w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[b][0], w0, 0, 0, 0);
-                w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], cr[b][1], w1, 0, 0, 0);
-                w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], cr[b][2], w0, 0, 0, 0);
-                w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], cr[b][3], w1, 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int v = 0; v < 4; ++v) Wp[wave][4 * g + v][c] = w0[v] + w1[v];
-        __syncthreads();
-        if (tid < NB * NB) {
-            const int i = tid >> 4, cc = tid & 15;
-            float sum = Wp[0][i][cc];
-#pragma unroll
-            for (int w = 1; w < 8; ++w) sum += Wp[w][i][cc];
-            Ws[i][cc] = sum;
-        }
-        __syncthreads();
-        if (tid < NB * NB) {
-            const int i = tid >> 4, cc = tid & 15;
-            float o = 0.f;
-#pragma unroll
-            for (int k = 0; k < NB; ++k) o = fmaf(Ts[i][k], Ws[k][cc], o);
-            Wn[i][cc] = -o;
-        }
-        __syncthreads();
-        float bq[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) bq[q] = Wn[4 * g + q][c];
-#pragma unroll
-        for (int b = 0; b < NBLK; ++b) {
-            const int blk = wave + 8 * b;
-            if (blk >= p && blk < total_blocks) {
-                const float4 a4 = *reinterpret_cast<const float4*>(Vp + (int64_t)(16 * (blk - p) + c) * ld + 4 * g);
-                cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, bq[0], cr[b], 0, 0, 0);
-                cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, bq[1], cr[b], 0, 0, 0);
-                cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, bq[2], cr[b], 0, 0, 0);
-                cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, bq[3], cr[b], 0, 0, 0);
-            }
-        }
-    }
-    float* Xs = X + (int64_t)strip * NB;
-#pragma unroll
-    for (int b = 0; b < NBLK; ++b) {
-        const int blk = wave + 8 * b;
-        if (blk < total_blocks) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) Xs[(int64_t)(16 * blk + 4 * g + v) * ldx + c] = cr[b][v];
-        }
-    }
+// One launch per QR step p.  The chain of panel factorisations (one workgroup each) is the
+// critical path, so the launch that applies block reflector p also factorises panel p + 1:
+//   workgroup 0        updates the 16 columns of panel p + 1, then factorises them;
+//   the next `wide`    update the remaining trailing columns of the matrix;
+//   the last `acc`     update all columns of the accumulated transposed orthogonal factor
+//                      X <- (I - V T^T V^T) X  (X starts as the identity, ends as Q^T).
+// Every strip reads only V_p, T_p and its own columns; panel p + 1 writes its own columns, its own
+// block of the reflector store and its own T, so the workgroups of one launch never touch the
+// same data.  Waves of workgroup 0 that the panel does not use leave after the strip.
+struct QrStepArgs {
+    const float* V; const float* T;      // reflector block p (rows x 16, row stride ld) and its triangle
+    float* C;                            // trailing columns of rows c0.. : panel p + 1 first
+    float* X;                            // rows c0.. of the accumulator
+    int64_t ld;
+    int nblocks;                         // rows / 16 of step p
+    int wide, acc;                       // strip counts
+    float* Vnext; float* Tnext; float* rdiag_next;   // outputs of panel p + 1
+    int m_next;                          // its row count (0: no further panel)
+};
+
+template <int NTHR, int R, int NBLK>
+__global__ __launch_bounds__(512)
+void qr_step_kernel(QrStepArgs a) {
+    const int b = blockIdx.x;
+    float* Cs = b <= a.wide ? a.C + (int64_t)b * NB : a.X + (int64_t)(b - 1 - a.wide) * NB;
+    reflect_strip_body<NBLK>(a.V, a.ld, a.T, 1, Cs, a.ld, a.nblocks);
+    if (b != 0 || a.m_next <= 0) return;
+    __threadfence_block();
+    __syncthreads();                     // the strip's stores are visible to the whole workgroup
+    if (threadIdx.x >= NTHR) return;
+    qr_panel_body<NTHR, R>(a.C + (int64_t)NB * a.ld, a.Vnext, a.Tnext, a.rdiag_next, a.ld, a.m_next);   // 16 rows further down
 }
 
 __global__ __launch_bounds__(256)
@@ -921,34 +878,86 @@ hipError_t pad_matrix(float* M, int64_t ld, int n, int n_pad, int identity_block
     return hipGetLastError();
 }
 
+namespace {
+
+template <int NTHR, int R, int NBLK>
+hipError_t launch_qr_step_t(const QrStepArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK>), dim3(1 + a.wide + a.acc), dim3(512), 0, s, a);
+    return hipGetLastError();
+}
+
+// Can a panel with R rows per thread (NTHR threads) meet strips with NBLK blocks per wave (PREV: the
+// next smaller strip variant)?  The next panel has 16 (nblocks - 1) rows, so only a few pairs occur.
+constexpr bool qr_step_pair_occurs(int NTHR, int R, int NBLK, int PREV) {
+    const int min_nb = (R - 1) * NTHR / NB + 2, max_nb = R * NTHR / NB + 1;
+    return (min_nb + 7) / 8 <= NBLK && (max_nb + 7) / 8 > PREV;
+}
+
+template <int NTHR, int R>
+hipError_t launch_qr_step_r(int per_wave, const QrStepArgs& a, hipStream_t s) {
+    if (per_wave <= 5) { if constexpr (qr_step_pair_occurs(NTHR, R, 5, 0)) return launch_qr_step_t<NTHR, R, 5>(a, s); }
+    else if (per_wave <= 10) { if constexpr (qr_step_pair_occurs(NTHR, R, 10, 5)) return launch_qr_step_t<NTHR, R, 10>(a, s); }
+    else if (per_wave <= 20) { if constexpr (qr_step_pair_occurs(NTHR, R, 20, 10)) return launch_qr_step_t<NTHR, R, 20>(a, s); }
+    else if (per_wave <= 40) { if constexpr (qr_step_pair_occurs(NTHR, R, 40, 20)) return launch_qr_step_t<NTHR, R, 40>(a, s); }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_qr_step(const QrStepArgs& a, hipStream_t s) {
+    const int per_wave = (a.nblocks + 7) / 8;
+    const int m = a.m_next;
+    if (m <= 1024) {
+        switch ((m + 255) / 256) {
+            case 0: case 1: return launch_qr_step_r<256, 1>(per_wave, a, s);
+            case 2: return launch_qr_step_r<256, 2>(per_wave, a, s);
+            case 3: return launch_qr_step_r<256, 3>(per_wave, a, s);
+            default: return launch_qr_step_r<256, 4>(per_wave, a, s);
+        }
+    }
+    switch ((m + 511) / 512) {
+        case 3: return launch_qr_step_r<512, 3>(per_wave, a, s);
+        case 4: return launch_qr_step_r<512, 4>(per_wave, a, s);
+        case 5: return launch_qr_step_r<512, 5>(per_wave, a, s);
+        case 6: return launch_qr_step_r<512, 6>(per_wave, a, s);
+        case 7: return launch_qr_step_r<512, 7>(per_wave, a, s);
+        case 8: return launch_qr_step_r<512, 8>(per_wave, a, s);
+        case 9: return launch_qr_step_r<512, 9>(per_wave, a, s);
+        case 10: return launch_qr_step_r<512, 10>(per_wave, a, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
 hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t s) {
     const int n_pad = ws.n_pad;
     const int64_t ld = ws.ld;
     const int panels = n_pad / NB;
-    // factorise: panel, then trailing columns C <- (I - V T V^T)^T C = C - V (T^T (V^T C))
+    GELO_TRY(set_identity(ws.X, ld, n_pad, s));
+    // panel 0 on its own; then one launch per step: trailing update + accumulation of Q^T with block
+    // reflector p, and in the same launch the factorisation of panel p + 1
+    {
+        const int m = n_pad;
+        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, ws.Vc, ws.Tmat, ws.rdiag, ld, m, s));
+        else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M, ws.Vc, ws.Tmat, ws.rdiag, ld, m, s));
+    }
     for (int p = 0; p < panels; ++p) {
         const int c0 = p * NB, m = n_pad - c0;
         const int64_t off = (int64_t)c0 * ld + c0;
-        float* Tp = ws.Tmat + (int64_t)p * NB * NB;
-        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M + off, ws.Vc + off, Tp, ws.rdiag + c0, ld, m, s));
-        else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M + off, ws.Vc + off, Tp, ws.rdiag + c0, ld, m, s));
         const int cols = n_pad - c0 - NB;
-        if (cols > 0) {
-            float* C = ws.M + off + NB;
-            GELO_TRY(apply_block_reflector(ws.Vc + off, ld, Tp, 1, C, ld, m, cols, s));
+        QrStepArgs a;
+        a.V = ws.Vc + off; a.T = ws.Tmat + (int64_t)p * NB * NB;
+        a.X = ws.X + (int64_t)c0 * ld;
+        a.ld = ld; a.nblocks = m / NB; a.acc = n_pad / NB;
+        if (cols <= 0) {                      // last block reflector: only the accumulator is left
+            GELO_TRY(apply_block_reflector(a.V, ld, a.T, 1, a.X, ld, m, n_pad, s));
+            break;
         }
-    }
-    // accumulate Q = B_0 B_1 ... B_last I in one launch (every column strip independently)
-    {
-        const int total_blocks = n_pad / NB;
-        const dim3 grid(total_blocks), block(512);
-        const int per_wave = (total_blocks + 7) / 8;
-        if (per_wave <= 5) hipLaunchKernelGGL(form_q_kernel<5>, grid, block, 0, s, ws.Vc, ld, ws.Tmat, ws.X, ld, total_blocks);
-        else if (per_wave <= 10) hipLaunchKernelGGL(form_q_kernel<10>, grid, block, 0, s, ws.Vc, ld, ws.Tmat, ws.X, ld, total_blocks);
-        else if (per_wave <= 20) hipLaunchKernelGGL(form_q_kernel<20>, grid, block, 0, s, ws.Vc, ld, ws.Tmat, ws.X, ld, total_blocks);
-        else if (per_wave <= 40) hipLaunchKernelGGL(form_q_kernel<40>, grid, block, 0, s, ws.Vc, ld, ws.Tmat, ws.X, ld, total_blocks);
-        else return hipErrorInvalidValue;
-        GELO_TRY(hipGetLastError());
+        const int64_t off_next = off + (int64_t)NB * ld + NB;
+        a.C = ws.M + off + NB;
+        a.wide = cols / NB - 1;
+        a.Vnext = ws.Vc + off_next; a.Tnext = ws.Tmat + (int64_t)(p + 1) * NB * NB; a.rdiag_next = ws.rdiag + c0 + NB;
+        a.m_next = m - NB;
+        GELO_TRY(launch_qr_step(a, s));
     }
     return hipSuccess;
 }
@@ -1008,8 +1017,8 @@ hipError_t kappa_estimate(const float* A, const float* Ainv, int64_t lda, int n,
                           int iterations, hipStream_t s) {
     const int64_t ld = ws.ld;
     // transposes into the (now free) factorisation buffers
-    GELO_TRY(emit_matrix(A, lda, nullptr, n, ld, nullptr, nullptr, ws.M, nullptr, s));
-    GELO_TRY(emit_matrix(Ainv, lda, nullptr, n, ld, nullptr, nullptr, ws.X, nullptr, s));
+    GELO_TRY(emit_matrix(A, lda, nullptr, 0, n, ld, nullptr, nullptr, ws.M, nullptr, s));
+    GELO_TRY(emit_matrix(Ainv, lda, nullptr, 0, n, ld, nullptr, nullptr, ws.X, nullptr, s));
     const dim3 grid((n + 3) / 4), block(256);
     float* x = ws.vec;
     float* y = ws.vec + ld;

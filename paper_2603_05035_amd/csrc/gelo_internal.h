@@ -52,10 +52,11 @@ hipError_t norm_statistic(const float* v, int count, int stat, float* out, hipSt
 // S[i, :] = G[i, :] * (scale * *stat / gnorm[i]), written as float or bf16 (lds elements per row)
 hipError_t make_shields(const float* G, int64_t ldg, const float* gnorm, const float* stat, float scale,
                         int k, int d, void* S, int is_bf16, int64_t lds, hipStream_t stream);
-// Writes an n x n float matrix (src, optional per-column sign flip from `rdiag` < 0) into the
-// mixing buffers: dst32 / dst16 get the matrix, dstT32 / dstT16 its transpose (any may be null).
-// Every destination has `ldd` elements per row and its columns [n, ldd) are zero-filled.
-hipError_t emit_matrix(const float* src, int64_t lds, const float* rdiag, int n, int64_t ldd,
+// Writes an n x n float matrix (src, optional sign flip where `rdiag` < 0: per column, or per row
+// if sign_rows is set) into the mixing buffers: dst32 / dst16 get the matrix, dstT32 / dstT16 its
+// transpose (any may be null).  Every destination has `ldd` elements per row and its columns
+// [n, ldd) are zero-filled.
+hipError_t emit_matrix(const float* src, int64_t lds, const float* rdiag, int sign_rows, int n, int64_t ldd,
                        float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16,
                        hipStream_t stream);
 // dense float copy out[r * cols + c] = (float) src[r * ld + c]
@@ -83,8 +84,9 @@ struct FactorWorkspace {
 size_t factor_workspace_bytes(int n);
 void factor_workspace_carve(void* base, int n, FactorWorkspace* ws);
 
-// ws.M holds an n_pad x n_pad matrix (rows/cols beyond n zero).  On return ws.X holds Q of its
-// Householder QR (identity in the padding block) and ws.rdiag the diagonal of R.
+// ws.M holds an n_pad x n_pad matrix (rows/cols beyond n zero).  On return ws.X holds Q^T, the
+// TRANSPOSE of the orthogonal factor of its Householder QR (identity in the padding block), and
+// ws.rdiag the diagonal of R.
 hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t stream);
 // ws.M holds an n_pad x n_pad matrix with an identity block in the padding.  On return ws.X holds
 // its inverse (via row-pivoted LU), *ws.flag != 0 if a zero pivot was met.
