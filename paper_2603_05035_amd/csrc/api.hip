@@ -246,7 +246,7 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
 
     auto orthogonal_into_X = [&]() -> hipError_t {
         ps.c1 = kStreamMixing << 8;
-        hipError_t e = fill_normal(ws.M, ld, n, n, ps, 1.0f, s);
+        hipError_t e = fill_normal(ws.M, ld, n, n, ps, 1.0f, 1, s);          // column-major for the QR
         if (e == hipSuccess) e = pad_matrix(ws.M, ld, n, ws.n_pad, 0, s);
         if (e == hipSuccess) e = householder_qr(ws, s);
         return e;
@@ -254,8 +254,8 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
 
     if (kind == GELO_ORTHOGONAL) {
         GELO_HIP(ctx, orthogonal_into_X());
-        // A = Q diag(sign r_ii); A^-1 = A^T = diag(sign r_ii) Q^T, and X holds Q^T
-        GELO_HIP(ctx, emit_matrix(ws.X, ld, ws.rdiag, 1, n, ldk, m->Ainv32, m->Ainv16, m->A32, m->A16, s));
+        // A = Q diag(sign r_ii); A^-1 = A^T
+        GELO_HIP(ctx, emit_matrix(ws.X, ld, ws.rdiag, n, ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s));
     } else {
         bool accepted = false;
         const int attempts = kind == GELO_GAUSSIAN ? max_attempts : 1;
@@ -263,20 +263,20 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
         for (int attempt = 0; attempt < attempts && !accepted; ++attempt) {
             if (kind == GELO_GAUSSIAN) {
                 ps.c1 = (kStreamMixing << 8) | (uint32_t)attempt;
-                GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f / std::sqrt((float)n), s));
-                GELO_HIP(ctx, emit_matrix(ws.M, ld, nullptr, 0, n, ldk, m->A32, m->A16, nullptr, nullptr, s));
+                GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f / std::sqrt((float)n), 0, s));
+                GELO_HIP(ctx, emit_matrix(ws.M, ld, nullptr, n, ldk, m->A32, m->A16, nullptr, nullptr, s));
             } else {
                 GELO_HIP(ctx, orthogonal_into_X());
-                GELO_HIP(ctx, emit_matrix(ws.X, ld, ws.rdiag, 1, n, ldk, nullptr, nullptr, m->A32, nullptr, s));
+                GELO_HIP(ctx, emit_matrix(ws.X, ld, ws.rdiag, n, ldk, m->A32, nullptr, nullptr, nullptr, s));
                 ps.c1 = kStreamPerturb << 8;
-                GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f, s));
+                GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f, 0, s));
                 GELO_HIP(ctx, axpy_matrix(m->A32, ldk, ws.M, ld, n, n, kConditionedBeta / std::sqrt((float)n), s));
-                GELO_HIP(ctx, emit_matrix(m->A32, ldk, nullptr, 0, n, ld, ws.M, nullptr, nullptr, nullptr, s));
-                if (bf) GELO_HIP(ctx, emit_matrix(m->A32, ldk, nullptr, 0, n, ldk, nullptr, m->A16, nullptr, nullptr, s));
+                GELO_HIP(ctx, emit_matrix(m->A32, ldk, nullptr, n, ld, ws.M, nullptr, nullptr, nullptr, s));
+                if (bf) GELO_HIP(ctx, emit_matrix(m->A32, ldk, nullptr, n, ldk, nullptr, m->A16, nullptr, nullptr, s));
             }
             GELO_HIP(ctx, pad_matrix(ws.M, ld, n, ws.n_pad, 1, s));
             GELO_HIP(ctx, lu_inverse(ws, s));
-            GELO_HIP(ctx, emit_matrix(ws.X, ld, nullptr, 0, n, ldk, m->Ainv32, m->Ainv16, nullptr, nullptr, s));
+            GELO_HIP(ctx, emit_matrix(ws.X, ld, nullptr, n, ldk, m->Ainv32, m->Ainv16, nullptr, nullptr, s));
             GELO_HIP(ctx, kappa_estimate(m->A32, m->Ainv32, ldk, n, ws, kKappaIterations, s));
             GELO_HIP(ctx, hipMemcpyAsync(m->stat + 1, ws.scalars, sizeof(float), hipMemcpyDeviceToDevice, s));
             if (kind == GELO_GAUSSIAN) {
@@ -298,7 +298,7 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
     }
     if (k_shield > 0) {
         ps.c1 = kStreamShield << 8;
-        GELO_HIP(ctx, fill_normal(m->GS, d, k_shield, d, ps, 1.0f, s));
+        GELO_HIP(ctx, fill_normal(m->GS, d, k_shield, d, ps, 1.0f, 0, s));
         GELO_HIP(ctx, row_norms(m->GS, 0, d, k_shield, d, m->gsnorm, s));
     }
     GELO_HIP(ctx, hipEventRecord(m->ready, s));

@@ -99,8 +99,12 @@ __device__ __forceinline__ float lane_value(float v) {
 // and the Gram entry v_s . v_j that the T factor needs (s < j).  After the reduction lane s of
 // every wave holds the quantities of column s; the update coefficients are then read into
 // scalar registers.  The column loop is unrolled so that all register indices are constants.
+// Mp: the panel in column-major order (element (r, c) at Mp[c * ld + r]).  The reflector block is
+// written twice, compactly: Vr[r * 16 + c] (row-major, the A operand of C += V W') and
+// Vt[c * ldt + r] (the A operand of W = V^T C), both with explicit unit diagonal and zeros above.
 template <int NTHR, int R>
-__device__ __forceinline__ void qr_panel_body(float* Mp, float* Vc, float* Tg, float* rdiag, int64_t ld, int m) {
+__device__ __forceinline__ void qr_panel_body(float* Mp, int64_t ld, float* Vr, float* Vt, int64_t ldt, float* Tg,
+                                              float* rdiag, int m) {
     constexpr int NW = NTHR / 64;
     __shared__ float red[2][NW][NB];
     __shared__ float prow[2][NB];
@@ -115,11 +119,7 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, float* Vc, float* Tg, f
     for (int i = 0; i < R; ++i) {
         const int r = tid + i * NTHR;
 #pragma unroll
-        for (int c4 = 0; c4 < NB / 4; ++c4) {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r < m) v = *reinterpret_cast<const float4*>(Mp + (int64_t)r * ld + c4 * 4);
-            P[i][c4 * 4 + 0] = v.x; P[i][c4 * 4 + 1] = v.y; P[i][c4 * 4 + 2] = v.z; P[i][c4 * 4 + 3] = v.w;
-        }
+        for (int c = 0; c < NB; ++c) P[i][c] = r < m ? Mp[(int64_t)c * ld + r] : 0.f;      // consecutive lanes, consecutive addresses
     }
 
     static_for<NB>([&](auto jc) {
@@ -207,15 +207,17 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, float* Vc, float* Tg, f
     for (int i = 0; i < R; ++i) {
         const int r = tid + i * NTHR;
         if (r < m) {
-            float* mp = Mp + (int64_t)r * ld;
-            float* vc = Vc + (int64_t)r * ld;
 #pragma unroll
             for (int c4 = 0; c4 < NB / 4; ++c4) {
                 float v[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { const int c = c4 * 4 + e; v[e] = r > c ? P[i][c] : (r == c ? 1.f : 0.f); }
-                *reinterpret_cast<float4*>(mp + c4 * 4) = make_float4(P[i][c4 * 4], P[i][c4 * 4 + 1], P[i][c4 * 4 + 2], P[i][c4 * 4 + 3]);
-                *reinterpret_cast<float4*>(vc + c4 * 4) = make_float4(v[0], v[1], v[2], v[3]);
+                for (int e = 0; e < 4; ++e) {
+                    const int c = c4 * 4 + e;
+                    v[e] = r > c ? P[i][c] : (r == c ? 1.f : 0.f);
+                    Mp[(int64_t)c * ld + r] = P[i][c];
+                    Vt[(int64_t)c * ldt + r] = v[e];
+                }
+                *reinterpret_cast<float4*>(Vr + (int64_t)r * NB + c4 * 4) = make_float4(v[0], v[1], v[2], v[3]);
             }
         }
     }
@@ -223,8 +225,8 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, float* Vc, float* Tg, f
 
 template <int NTHR, int R>
 __global__ __launch_bounds__(NTHR)
-void qr_panel_kernel(float* Mp, float* Vc, float* Tg, float* rdiag, int64_t ld, int m) {
-    qr_panel_body<NTHR, R>(Mp, Vc, Tg, rdiag, ld, m);
+void qr_panel_kernel(float* Mp, int64_t ld, float* Vr, float* Vt, int64_t ldt, float* Tg, float* rdiag, int m) {
+    qr_panel_body<NTHR, R>(Mp, ld, Vr, Vt, ldt, Tg, rdiag, m);
 }
 
 // ------------------------------------------------------- skinny rank-16 kernels --
@@ -406,12 +408,16 @@ void rank16_update_kernel(const float* L, int64_t ldl, const float* W, int64_t l
 // v_mfma_f32_16x16x4_f32, so the same registers serve as the B operand of W = V^T C (K = rows)
 // and as the accumulator of C -= V W' (K = the 16 reflectors).  Wave w of 8 owns blocks
 // w, w+8, ...; the 8 partial W are added in wave order (fixed order, reproducible), then
-// W' = -op(T) W is formed once per strip.  V (m x 16, row stride ldv) is read through the caches.
+// W' = -op(T) W is formed once per strip.
+// Layouts, chosen so that every global access is one 16-byte load or store per lane: C is
+// column-major (Cs[c * ldc + r]: the four rows 4 g .. 4 g + 3 a lane owns are adjacent), the
+// reflectors come as Vt[i * ldt + r] for the first product and as Vr[r * 16 + i] for the second.
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 template <int NBLK>
-__device__ __forceinline__ void reflect_strip_body(const float* __restrict__ V, int64_t ldv, const float* __restrict__ T,
-                                                   int t_transposed, float* Cs, int64_t ldc, int nblocks) {
+__device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr, const float* __restrict__ Vt, int64_t ldt,
+                                                   const float* __restrict__ T, int t_transposed, float* Cs, int64_t ldc,
+                                                   int nblocks) {
     __shared__ float Wp[8][NB][NB];
     __shared__ float Ws[NB][NB];
     __shared__ float Wn[NB][NB];
@@ -420,15 +426,14 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ V, 
     const int c = lane & 15, g = lane >> 4;
     if (tid < NB * NB) Ts[tid >> 4][tid & 15] = T[tid];
 
+    float* Cl = Cs + (int64_t)c * ldc + 4 * g;               // this lane's column, its first row of block 0
+    const float* Vtl = Vt + (int64_t)c * ldt + 4 * g;        // reflector c, same rows
     f32x4_t cr[NBLK];
 #pragma unroll
     for (int b = 0; b < NBLK; ++b) {
         const int blk = wave + 8 * b;
         cr[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        if (blk < nblocks) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) cr[b][v] = Cs[(int64_t)(16 * blk + 4 * g + v) * ldc + c];
-        }
+        if (blk < nblocks) cr[b] = *reinterpret_cast<const f32x4_t*>(Cl + 16 * blk);
     }
     // W_partial[i][col] = sum over this wave's rows of V[r][i] C[r][col]; MFMA (b, v) contracts the four
     // rows 16 blk + 4 kk + v (kk = lane / 16): A = V[row][lane % 16], B = the strip register itself
@@ -437,9 +442,7 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ V, 
     for (int b = 0; b < NBLK; ++b) {
         const int blk = wave + 8 * b;
         if (blk < nblocks) {
-            float a[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) a[v] = V[(int64_t)(16 * blk + 4 * g + v) * ldv + c];
+            const f32x4_t a = *reinterpret_cast<const f32x4_t*>(Vtl + 16 * blk);
             w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[b][0], w0, 0, 0, 0);
             w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], cr[b][1], w1, 0, 0, 0);
             w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], cr[b][2], w0, 0, 0, 0);
@@ -473,22 +476,21 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ V, 
     for (int b = 0; b < NBLK; ++b) {
         const int blk = wave + 8 * b;
         if (blk < nblocks) {
-            const float4 a4 = *reinterpret_cast<const float4*>(V + (int64_t)(16 * blk + c) * ldv + 4 * g);
-            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.x, bq[0], cr[b], 0, 0, 0);
-            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.y, bq[1], cr[b], 0, 0, 0);
-            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.z, bq[2], cr[b], 0, 0, 0);
-            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4.w, bq[3], cr[b], 0, 0, 0);
-#pragma unroll
-            for (int v = 0; v < 4; ++v) Cs[(int64_t)(16 * blk + 4 * g + v) * ldc + c] = cr[b][v];
+            const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(Vr + (int64_t)(16 * blk + c) * NB + 4 * g);
+            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[0], bq[0], cr[b], 0, 0, 0);
+            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[1], bq[1], cr[b], 0, 0, 0);
+            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[2], bq[2], cr[b], 0, 0, 0);
+            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[3], bq[3], cr[b], 0, 0, 0);
+            *reinterpret_cast<f32x4_t*>(Cl + 16 * blk) = cr[b];
         }
     }
 }
 
 template <int NBLK>
 __global__ __launch_bounds__(512)
-void reflect_strip_kernel(const float* __restrict__ V, int64_t ldv, const float* __restrict__ T, int t_transposed,
-                          float* C, int64_t ldc, int nblocks) {
-    reflect_strip_body<NBLK>(V, ldv, T, t_transposed, C + (int64_t)blockIdx.x * NB, ldc, nblocks);
+void reflect_strip_kernel(const float* __restrict__ Vr, const float* __restrict__ Vt, int64_t ldt,
+                          const float* __restrict__ T, int t_transposed, float* C, int64_t ldc, int nblocks) {
+    reflect_strip_body<NBLK>(Vr, Vt, ldt, T, t_transposed, C + (int64_t)blockIdx.x * NB * ldc, ldc, nblocks);
 }
 
 // One launch per QR step p.  The chain of panel factorisations (one workgroup each) is the
@@ -496,18 +498,20 @@ void reflect_strip_kernel(const float* __restrict__ V, int64_t ldv, const float*
 //   workgroup 0        updates the 16 columns of panel p + 1, then factorises them;
 //   the next `wide`    update the remaining trailing columns of the matrix;
 //   the last `acc`     update all columns of the accumulated transposed orthogonal factor
-//                      X <- (I - V T^T V^T) X  (X starts as the identity, ends as Q^T).
-// Every strip reads only V_p, T_p and its own columns; panel p + 1 writes its own columns, its own
-// block of the reflector store and its own T, so the workgroups of one launch never touch the
+//                      X <- (I - V T^T V^T) X  (X starts as the identity, ends as Q^T; like the
+//                      matrix it is stored column-major, which makes the buffer Q in row-major).
+// Every strip reads only V_p, T_p and its own columns; panel p + 1 writes its own columns, the
+// other pair of reflector buffers and its own T, so the workgroups of one launch never touch the
 // same data.  Waves of workgroup 0 that the panel does not use leave after the strip.
 struct QrStepArgs {
-    const float* V; const float* T;      // reflector block p (rows x 16, row stride ld) and its triangle
-    float* C;                            // trailing columns of rows c0.. : panel p + 1 first
-    float* X;                            // rows c0.. of the accumulator
-    int64_t ld;
+    const float* Vr; const float* Vt;    // reflector block p in both layouts (see reflect_strip_body)
+    const float* T;                      // its 16 x 16 triangle
+    float* C;                            // column-major, (row c0, column c0 + 16): panel p + 1 first
+    float* X;                            // column-major, (row c0, column 0) of the accumulator
+    int64_t ld, ldt;
     int nblocks;                         // rows / 16 of step p
     int wide, acc;                       // strip counts
-    float* Vnext; float* Tnext; float* rdiag_next;   // outputs of panel p + 1
+    float* Vr_next; float* Vt_next; float* Tnext; float* rdiag_next;   // outputs of panel p + 1
     int m_next;                          // its row count (0: no further panel)
 };
 
@@ -515,13 +519,13 @@ template <int NTHR, int R, int NBLK>
 __global__ __launch_bounds__(512)
 void qr_step_kernel(QrStepArgs a) {
     const int b = blockIdx.x;
-    float* Cs = b <= a.wide ? a.C + (int64_t)b * NB : a.X + (int64_t)(b - 1 - a.wide) * NB;
-    reflect_strip_body<NBLK>(a.V, a.ld, a.T, 1, Cs, a.ld, a.nblocks);
+    float* Cs = b <= a.wide ? a.C + (int64_t)b * NB * a.ld : a.X + (int64_t)(b - 1 - a.wide) * NB * a.ld;
+    reflect_strip_body<NBLK>(a.Vr, a.Vt, a.ldt, a.T, 1, Cs, a.ld, a.nblocks);
     if (b != 0 || a.m_next <= 0) return;
     __threadfence_block();
     __syncthreads();                     // the strip's stores are visible to the whole workgroup
     if (threadIdx.x >= NTHR) return;
-    qr_panel_body<NTHR, R>(a.C + (int64_t)NB * a.ld, a.Vnext, a.Tnext, a.rdiag_next, a.ld, a.m_next);   // 16 rows further down
+    qr_panel_body<NTHR, R>(a.C + NB, a.ld, a.Vr_next, a.Vt_next, a.ldt, a.Tnext, a.rdiag_next, a.m_next);   // 16 rows further down
 }
 
 __global__ __launch_bounds__(256)
@@ -761,10 +765,10 @@ void kappa_finish_kernel(const float* xa, const float* xi, int n, float* out) {
 }
 
 template <int NTHR>
-hipError_t launch_qr_panel(int rows_per_thread, float* Mp, float* Vc, float* Tg, float* rdiag,
-                           int64_t ld, int m, hipStream_t s) {
+hipError_t launch_qr_panel(int rows_per_thread, float* Mp, int64_t ld, float* Vr, float* Vt, int64_t ldt, float* Tg,
+                           float* rdiag, int m, hipStream_t s) {
     switch (rows_per_thread) {
-#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((qr_panel_kernel<NTHR, RR>), dim3(1), dim3(NTHR), 0, s, Mp, Vc, Tg, rdiag, ld, m); break;
+#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((qr_panel_kernel<NTHR, RR>), dim3(1), dim3(NTHR), 0, s, Mp, ld, Vr, Vt, ldt, Tg, rdiag, m); break;
         GELO_CASE(1) GELO_CASE(2) GELO_CASE(3) GELO_CASE(4) GELO_CASE(5)
         GELO_CASE(6) GELO_CASE(7) GELO_CASE(8) GELO_CASE(9) GELO_CASE(10)
 #undef GELO_CASE
@@ -809,17 +813,18 @@ hipError_t vt_c(const FactorWorkspace& ws, const float* V, const float* T, int t
 }
 
 // C (rows x cols, rows and cols multiples of 16) <- (I - V op(T) V^T) C with op(T) = T^T if t_transposed
-hipError_t apply_block_reflector(const float* V, int64_t ldv, const float* T, int t_transposed, float* C, int64_t ldc,
-                                 int rows, int cols, hipStream_t s) {
+// C (column-major, rows x cols, both multiples of 16) <- (I - V op(T) V^T) C
+hipError_t apply_block_reflector(const float* Vr, const float* Vt, int64_t ldt, const float* T, int t_transposed,
+                                 float* C, int64_t ldc, int rows, int cols, hipStream_t s) {
     if (rows <= 0 || cols <= 0) return hipSuccess;
     if (rows % NB != 0 || cols % NB != 0) return hipErrorInvalidValue;
     const int nblocks = rows / NB;
     const dim3 grid(cols / NB), block(512);
     const int per_wave = (nblocks + 7) / 8;
-    if (per_wave <= 5) hipLaunchKernelGGL(reflect_strip_kernel<5>, grid, block, 0, s, V, ldv, T, t_transposed, C, ldc, nblocks);
-    else if (per_wave <= 10) hipLaunchKernelGGL(reflect_strip_kernel<10>, grid, block, 0, s, V, ldv, T, t_transposed, C, ldc, nblocks);
-    else if (per_wave <= 20) hipLaunchKernelGGL(reflect_strip_kernel<20>, grid, block, 0, s, V, ldv, T, t_transposed, C, ldc, nblocks);
-    else if (per_wave <= 40) hipLaunchKernelGGL(reflect_strip_kernel<40>, grid, block, 0, s, V, ldv, T, t_transposed, C, ldc, nblocks);
+    if (per_wave <= 5) hipLaunchKernelGGL(reflect_strip_kernel<5>, grid, block, 0, s, Vr, Vt, ldt, T, t_transposed, C, ldc, nblocks);
+    else if (per_wave <= 10) hipLaunchKernelGGL(reflect_strip_kernel<10>, grid, block, 0, s, Vr, Vt, ldt, T, t_transposed, C, ldc, nblocks);
+    else if (per_wave <= 20) hipLaunchKernelGGL(reflect_strip_kernel<20>, grid, block, 0, s, Vr, Vt, ldt, T, t_transposed, C, ldc, nblocks);
+    else if (per_wave <= 40) hipLaunchKernelGGL(reflect_strip_kernel<40>, grid, block, 0, s, Vr, Vt, ldt, T, t_transposed, C, ldc, nblocks);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -930,32 +935,34 @@ hipError_t launch_qr_step(const QrStepArgs& a, hipStream_t s) {
 
 hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t s) {
     const int n_pad = ws.n_pad;
-    const int64_t ld = ws.ld;
+    const int64_t ld = ws.ld, ldt = n_pad;
     const int panels = n_pad / NB;
+    // block reflector p is only needed while step p runs: two compact pairs of buffers alternate
+    float* Vr[2] = {ws.Vc, ws.Vc + (int64_t)n_pad * NB};
+    float* Vt[2] = {ws.Vc + 2 * (int64_t)n_pad * NB, ws.Vc + 3 * (int64_t)n_pad * NB};
     GELO_TRY(set_identity(ws.X, ld, n_pad, s));
     // panel 0 on its own; then one launch per step: trailing update + accumulation of Q^T with block
     // reflector p, and in the same launch the factorisation of panel p + 1
     {
         const int m = n_pad;
-        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, ws.Vc, ws.Tmat, ws.rdiag, ld, m, s));
-        else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M, ws.Vc, ws.Tmat, ws.rdiag, ld, m, s));
+        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, ld, Vr[0], Vt[0], ldt, ws.Tmat, ws.rdiag, m, s));
+        else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M, ld, Vr[0], Vt[0], ldt, ws.Tmat, ws.rdiag, m, s));
     }
     for (int p = 0; p < panels; ++p) {
         const int c0 = p * NB, m = n_pad - c0;
-        const int64_t off = (int64_t)c0 * ld + c0;
         const int cols = n_pad - c0 - NB;
         QrStepArgs a;
-        a.V = ws.Vc + off; a.T = ws.Tmat + (int64_t)p * NB * NB;
-        a.X = ws.X + (int64_t)c0 * ld;
-        a.ld = ld; a.nblocks = m / NB; a.acc = n_pad / NB;
+        a.Vr = Vr[p & 1]; a.Vt = Vt[p & 1]; a.T = ws.Tmat + (int64_t)p * NB * NB;
+        a.X = ws.X + c0;
+        a.ld = ld; a.ldt = ldt; a.nblocks = m / NB; a.acc = n_pad / NB;
         if (cols <= 0) {                      // last block reflector: only the accumulator is left
-            GELO_TRY(apply_block_reflector(a.V, ld, a.T, 1, a.X, ld, m, n_pad, s));
+            GELO_TRY(apply_block_reflector(a.Vr, a.Vt, ldt, a.T, 1, a.X, ld, m, n_pad, s));
             break;
         }
-        const int64_t off_next = off + (int64_t)NB * ld + NB;
-        a.C = ws.M + off + NB;
+        a.C = ws.M + (int64_t)(c0 + NB) * ld + c0;
         a.wide = cols / NB - 1;
-        a.Vnext = ws.Vc + off_next; a.Tnext = ws.Tmat + (int64_t)(p + 1) * NB * NB; a.rdiag_next = ws.rdiag + c0 + NB;
+        a.Vr_next = Vr[(p + 1) & 1]; a.Vt_next = Vt[(p + 1) & 1];
+        a.Tnext = ws.Tmat + (int64_t)(p + 1) * NB * NB; a.rdiag_next = ws.rdiag + c0 + NB;
         a.m_next = m - NB;
         GELO_TRY(launch_qr_step(a, s));
     }
@@ -1017,8 +1024,8 @@ hipError_t kappa_estimate(const float* A, const float* Ainv, int64_t lda, int n,
                           int iterations, hipStream_t s) {
     const int64_t ld = ws.ld;
     // transposes into the (now free) factorisation buffers
-    GELO_TRY(emit_matrix(A, lda, nullptr, 0, n, ld, nullptr, nullptr, ws.M, nullptr, s));
-    GELO_TRY(emit_matrix(Ainv, lda, nullptr, 0, n, ld, nullptr, nullptr, ws.X, nullptr, s));
+    GELO_TRY(emit_matrix(A, lda, nullptr, n, ld, nullptr, nullptr, ws.M, nullptr, s));
+    GELO_TRY(emit_matrix(Ainv, lda, nullptr, n, ld, nullptr, nullptr, ws.X, nullptr, s));
     const dim3 grid((n + 3) / 4), block(256);
     float* x = ws.vec;
     float* y = ws.vec + ld;

@@ -38,9 +38,10 @@ struct PhiloxStream {
     uint32_t c1, c2, c3;            // (stream << 8 | attempt), batch id low, batch id high
 };
 // out[r * ld + c] = scale * N(0,1) for r < rows, c < cols; element e = r*cols + c is output
-// e % 4 of Philox block e / 4 (counter word 0 = block index).
+// e % 4 of Philox block e / 4 (counter word 0 = block index).  With `transposed` the same element
+// goes to out[c * ld + r] (column-major storage of the same matrix).
 hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale,
-                       hipStream_t stream);
+                       int transposed, hipStream_t stream);
 // dst[r * ldd + c] += scale * src[r * lds + c] over an rows x cols block
 hipError_t axpy_matrix(float* dst, int64_t ldd, const float* src, int64_t lds, int rows, int cols,
                        float scale, hipStream_t stream);
@@ -52,11 +53,10 @@ hipError_t norm_statistic(const float* v, int count, int stat, float* out, hipSt
 // S[i, :] = G[i, :] * (scale * *stat / gnorm[i]), written as float or bf16 (lds elements per row)
 hipError_t make_shields(const float* G, int64_t ldg, const float* gnorm, const float* stat, float scale,
                         int k, int d, void* S, int is_bf16, int64_t lds, hipStream_t stream);
-// Writes an n x n float matrix (src, optional sign flip where `rdiag` < 0: per column, or per row
-// if sign_rows is set) into the mixing buffers: dst32 / dst16 get the matrix, dstT32 / dstT16 its
-// transpose (any may be null).  Every destination has `ldd` elements per row and its columns
-// [n, ldd) are zero-filled.
-hipError_t emit_matrix(const float* src, int64_t lds, const float* rdiag, int sign_rows, int n, int64_t ldd,
+// Writes an n x n float matrix (src, optional per-column sign flip from `rdiag` < 0) into the
+// mixing buffers: dst32 / dst16 get the matrix, dstT32 / dstT16 its transpose (any may be null).
+// Every destination has `ldd` elements per row and its columns [n, ldd) are zero-filled.
+hipError_t emit_matrix(const float* src, int64_t lds, const float* rdiag, int n, int64_t ldd,
                        float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16,
                        hipStream_t stream);
 // dense float copy out[r * cols + c] = (float) src[r * ld + c]
@@ -68,7 +68,7 @@ hipError_t export_dense(const void* src, int is_bf16, int64_t ld, int rows, int 
 struct FactorWorkspace {
     float* M;        // the matrix being factorised (G, then R + reflectors / L\U)
     float* X;        // the result being accumulated (Q, or A^-1)
-    float* Vc;       // per panel: reflector block V with explicit unit diagonal, zeros above
+    float* Vc;       // QR: two alternating pairs of compact reflector blocks (n_pad x 16 and 16 x n_pad)
     float* Tmat;     // per panel: the 16 x 16 triangle T of the block reflector I - V T V^T
     float* Wpart;    // partial products of the skinny reductions
     float* W;        // kPanel x ld reduced products
@@ -84,9 +84,10 @@ struct FactorWorkspace {
 size_t factor_workspace_bytes(int n);
 void factor_workspace_carve(void* base, int n, FactorWorkspace* ws);
 
-// ws.M holds an n_pad x n_pad matrix (rows/cols beyond n zero).  On return ws.X holds Q^T, the
-// TRANSPOSE of the orthogonal factor of its Householder QR (identity in the padding block), and
-// ws.rdiag the diagonal of R.
+// ws.M holds an n_pad x n_pad matrix (rows/cols beyond n zero) in COLUMN-major order: element
+// (r, c) at ws.M[c * ld + r] (the trailing updates work on column strips, which are then
+// contiguous in memory).  On return ws.X holds, in the usual row-major order, the orthogonal
+// factor Q of its Householder QR (identity in the padding block), and ws.rdiag the diagonal of R.
 hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t stream);
 // ws.M holds an n_pad x n_pad matrix with an identity block in the padding.  On return ws.X holds
 // its inverse (via row-pivoted LU), *ws.flag != 0 if a zero pivot was met.
