@@ -113,6 +113,28 @@ def test_orthogonal_mixing_matrix(ctx, n_data, k):
     check_orthogonal_A(f64(A), 0xC0FFEE, bid, n, compare_elements=(n <= 400))
 
 
+def test_orthogonal_mixing_matrix_at_the_largest_n(ctx):
+    """n = GELO_MAX_N: the widest register tiling of every QR kernel.  The element-wise comparison
+    with the oracle's Householder QR would take minutes, so A is pinned by what defines it:
+    orthogonal, and A^T G upper triangular with a positive diagonal (the QR factorisation with
+    that sign convention is unique)."""
+    n_data, k = 5000, 120
+    n = n_data + k
+    assert n == g.GELO_MAX_N
+    bid = 777
+    m = g.gelo_sample_mixing(ctx, g.GELO_ORTHOGONAL, n_data, k, 64, g.GELO_F32, 0.0, 1, batch_id=bid)
+    A, A_inv, _, attempt, kappa = g.gelo_mixing_export(ctx, m, n, k, 64, want_shields=False)
+    g.gelo_mixing_free(ctx, m)
+    assert torch.equal(A_inv, A.t())
+    A = f64(A)
+    G = o.gaussian_matrix(0xC0FFEE, bid, o.STREAM_MIXING, 0, n, n)
+    assert np.linalg.norm(A.T @ A - np.eye(n)) / math.sqrt(n) < 1e-5
+    R = A.T @ G
+    assert np.all(np.diag(R) > 0.0)
+    # kappa(G) of a square Gaussian is O(n); the strictly lower part of R is rounding noise of that size
+    assert np.linalg.norm(np.tril(R, -1)) / np.linalg.norm(R) < 20 * (10.0 * n) * 2.0 ** -24 / math.sqrt(n) + 1e-5
+
+
 def test_fresh_per_batch_and_deterministic(ctx):
     c2 = g.gelo_create(0, 0xC0FFEE, allow_batch_reuse=True)
     try:
