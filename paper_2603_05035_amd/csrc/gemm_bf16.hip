@@ -247,24 +247,24 @@ constexpr int A_BYTES = BM * BKS * 2;           // 32 KB, rows of 128 B, 16-byte
 constexpr int B_BYTES = BKS * BN * 2;           // 32 KB, rows of 512 B
 constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
 
+// lds_addr must be wave-uniform (it travels in M0); lane l's 16 bytes land at lds_addr + 16 l
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
-    const uint32_t uni = __builtin_amdgcn_readfirstlane(lds_addr);     // wave-uniform by construction
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(gptr), "s"(uni) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(gptr), "s"(lds_addr) : "memory", "m0");
 }
 
 __global__ __launch_bounds__(512)
 void gemm_bf16_dma_kernel(Bf16Args g) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
-    const uint32_t lds_base = (uint32_t)(size_t)lds;
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)lds);
 
     int tm, tn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, &tm, &tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // in a scalar register: LDS addresses of the fetches stay scalar
     const int wm = wave >> 1, wn = wave & 1;
     const int j = lane & 31, grp = lane >> 5;
-    const int T = (g.K + BKS - 1) / BKS;
 
     // kernel arguments pinned in scalar registers (a lane-varying choice between two argument
     // fields would otherwise be compiled into a per-lane memory load of the argument block)
@@ -274,15 +274,21 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
         return (int64_t)(((uint64_t)hi << 32) | lo);
     };
     const int K = uni32(g.K), K0 = uni32(g.K0);
+    const int T = (K + BKS - 1) / BKS;
     const int64_t ldb0 = uni64(g.ldb0), ldb1 = uni64(g.ldb1);
     const uint16_t* B0p = (const uint16_t*)uni64((int64_t)g.B0);
     const uint16_t* B1p = (const uint16_t*)uni64((int64_t)g.B1);
 
     // ---- what this lane fetches for every K step: 4 chunks of A and 4 of B (1 KB per wave each) ----
     // A chunk c of row r sits at position c ^ ((r ^ (r >> 3)) & 7) of the row's eight: the 16 rows a
-    // fragment read touches then fall on distinct banks.
-    const uint16_t* a_src[4]; uint32_t a_dst[4];
-    int b_krow[4], b_gn; uint32_t b_dst[4];
+    // fragment read touches then fall on distinct banks.  The addresses are a per-lane base plus a
+    // scalar offset per K step; only a K step that straddles the end of B0 or of K takes the
+    // general per-lane path (row clamp, choice of operand).
+    const uint16_t* a_src[4];
+    const uint16_t* b0_src[4];
+    const uint16_t* b1_src[4];
+    int b_krow[4], b_gn;
+    { int gn = n0 + (lane & 31) * 8; b_gn = gn < g.N ? gn : g.N - 8; }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int blk = wave * 4 + i;
@@ -290,24 +296,34 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
         const int c = cp ^ ((row ^ (row >> 3)) & 7);
         int grow = m0 + row; grow = grow < g.M ? grow : g.M - 1;
         a_src[i] = g.A + (int64_t)grow * g.lda + c * 8;
-        a_dst[i] = blk * 1024;                                  // + lane * 16 implied
         b_krow[i] = blk * 2 + (lane >> 5);
-        b_dst[i] = A_BYTES + blk * 1024;
+        b0_src[i] = B0p + (int64_t)b_krow[i] * ldb0 + b_gn;
+        b1_src[i] = B1p + (int64_t)(b_krow[i] - K0) * ldb1 + b_gn;       // only used with a K offset >= K0 added
     }
-    { int gn = n0 + (lane & 31) * 8; b_gn = gn < g.N ? gn : g.N - 8; }
 
     auto issue = [&](int t) {
         const int k0 = t * BKS;
-        const uint32_t st = lds_base + (t & 1) * STAGE_BYTES;
+        const uint32_t st = lds_base + (t & 1) * STAGE_BYTES + wave * 4096;     // + lane * 16 implied
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dma16(a_src[i] + k0, st + a_dst[i]);
+        for (int i = 0; i < 4; ++i) dma16(a_src[i] + k0, st + i * 1024);
+        const uint32_t sb = st + A_BYTES;
+        if (k0 + BKS <= K0) {
+            const int64_t off = (int64_t)k0 * ldb0;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int gk = k0 + b_krow[i]; gk = gk < K ? gk : K - 1;
-            const bool first = gk < K0;
-            const uint16_t* base = first ? B0p : B1p;
-            const int64_t off = first ? (int64_t)gk * ldb0 : (int64_t)(gk - K0) * ldb1;
-            dma16(base + off + b_gn, st + b_dst[i]);
+            for (int i = 0; i < 4; ++i) dma16(b0_src[i] + off, sb + i * 1024);
+        } else if (k0 >= K0 && k0 + BKS <= K) {
+            const int64_t off = (int64_t)k0 * ldb1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) dma16(b1_src[i] + off, sb + i * 1024);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int gk = k0 + b_krow[i]; gk = gk < K ? gk : K - 1;
+                const bool first = gk < K0;
+                const uint16_t* base = first ? B0p : B1p;
+                const int64_t off = first ? (int64_t)gk * ldb0 : (int64_t)(gk - K0) * ldb1;
+                dma16(base + off + b_gn, sb + i * 1024);
+            }
         }
     };
 
