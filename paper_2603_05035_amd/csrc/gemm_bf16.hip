@@ -228,24 +228,34 @@ void gemm_bf16_kernel(Bf16Args g) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast path: 256 x 256 tile, 8 waves, K step 64, two LDS stages filled by direct-to-LDS loads
-// (global_load_lds_dwordx4: no staging registers, no ds_write), one barrier per K step.  A rows
-// (128 bytes per stage) are stored with their 16-byte chunks XOR-swizzled so that the 16-byte
-// fragment reads of 16 consecutive rows hit distinct banks; B rows (512 bytes) are stored
-// linearly.  Out-of-range rows / columns are clamped to valid addresses instead of being
-// zero-filled, which is correct because A is zero in columns [K, round_up(K, 64)) (required by
-// the dispatcher) and clamped B rows are finite.  Measured against a 32-deep K step with four
-// stages and prefetch distance 3, the longer step wins by 1-5 %: the fixed cost per barrier
-// (wait, barrier, address arithmetic of the fetches, first fragment reads) is paid half as often.
+// Fast path: 256 x 256 tile, 8 waves (wave tile 64 x 128), K step 64, two LDS stages filled by
+// direct-to-LDS loads (global_load_lds_dwordx4: no staging registers, no ds_write), one barrier
+// per K step.
+//   A rows (128 bytes per stage) keep their 16-byte chunks XOR-swizzled so that the 16-byte
+//     fragment reads of 16 consecutive rows hit distinct banks.
+//   B rows (512 bytes, K-major as in memory) are read with ds_read_b64_tr_b16, which hands every
+//     lane the four K-consecutive values of one column: the MFMA operand layout, with no
+//     permutes.  Row r keeps its 16-byte chunk c at position c ^ (h(r) << 1),
+//     h(r) = ((r & 3) << 1) | ((r >> 3) & 1), which spreads the four rows one transposing read
+//     touches over all banks (measured: zero conflicts in the main loop).
+//   The MFMA operands are swapped (B fragment first), so the accumulators hold blocks of C^T and a
+//     lane owns 4 consecutive columns of one row; the epilogue goes through LDS once more so that
+//     the global stores are 16 bytes per lane over whole 256-byte row segments.
+// Out-of-range rows / columns are clamped to valid addresses instead of being zero-filled, which
+// is correct because A is zero in columns [K, round_up(K, 64)) (required by the dispatcher) and
+// clamped B rows are finite.  Measured on the 2150 x 12288 x 4096 projection against the
+// alternatives that were tried: K step 32 with four stages and prefetch distance 3 (-4 %),
+// per-lane address arithmetic for the fetches (-5 %), v_perm transposition of B in registers
+// with direct stores (-9 %).
 namespace dma {
 
-// One barrier per 64-deep K step: two LDS stages of 64 KB, the next K step fetched (straight from
-// global memory into LDS, no register staging) while the current one is multiplied.  Fragments
-// are double-buffered per 16-deep MFMA step so LDS reads of step s+1 overlap the MFMAs of step s.
 constexpr int BM = 256, BN = 256, BKS = 64, STAGES = 2;
-constexpr int A_BYTES = BM * BKS * 2;           // 32 KB, rows of 128 B, 16-byte chunks swizzled
+constexpr int A_BYTES = BM * BKS * 2;           // 32 KB, rows of 128 B
 constexpr int B_BYTES = BKS * BN * 2;           // 32 KB, rows of 512 B
 constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+constexpr int EPI_PITCH = 272;                  // bytes per row of a wave's 32 x 128 bf16 output patch
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
 
 // lds_addr must be wave-uniform (it travels in M0); lane l's 16 bytes land at lds_addr + 16 l
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
@@ -280,15 +290,12 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
     const uint16_t* B1p = (const uint16_t*)uni64((int64_t)g.B1);
 
     // ---- what this lane fetches for every K step: 4 chunks of A and 4 of B (1 KB per wave each) ----
-    // A chunk c of row r sits at position c ^ ((r ^ (r >> 3)) & 7) of the row's eight: the 16 rows a
-    // fragment read touches then fall on distinct banks.  The addresses are a per-lane base plus a
-    // scalar offset per K step; only a K step that straddles the end of B0 or of K takes the
-    // general per-lane path (row clamp, choice of operand).
+    // The addresses are a per-lane base plus a scalar offset per K step; only a K step that
+    // straddles the end of B0 or of K takes the general per-lane path (row clamp, choice of operand).
     const uint16_t* a_src[4];
     const uint16_t* b0_src[4];
     const uint16_t* b1_src[4];
-    int b_krow[4], b_gn;
-    { int gn = n0 + (lane & 31) * 8; b_gn = gn < g.N ? gn : g.N - 8; }
+    int b_krow[4], b_gn[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int blk = wave * 4 + i;
@@ -296,9 +303,13 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
         const int c = cp ^ ((row ^ (row >> 3)) & 7);
         int grow = m0 + row; grow = grow < g.M ? grow : g.M - 1;
         a_src[i] = g.A + (int64_t)grow * g.lda + c * 8;
-        b_krow[i] = blk * 2 + (lane >> 5);
-        b0_src[i] = B0p + (int64_t)b_krow[i] * ldb0 + b_gn;
-        b1_src[i] = B1p + (int64_t)(b_krow[i] - K0) * ldb1 + b_gn;       // only used with a K offset >= K0 added
+        const int br = blk * 2 + (lane >> 5);                           // B row of the stage this lane fetches from
+        const int h = ((br & 3) << 1) | ((br >> 3) & 1);
+        const int bc = (lane & 31) ^ (h << 1);                          // the chunk that belongs at this lane's LDS position
+        int gn = n0 + bc * 8; gn = gn < g.N ? gn : g.N - 8;
+        b_krow[i] = br; b_gn[i] = gn;
+        b0_src[i] = B0p + (int64_t)br * ldb0 + gn;
+        b1_src[i] = B1p + (int64_t)(br - K0) * ldb1 + gn;               // only used with a K offset >= K0 added
     }
 
     auto issue = [&](int t) {
@@ -322,7 +333,7 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
                 const bool first = gk < K0;
                 const uint16_t* base = first ? B0p : B1p;
                 const int64_t off = first ? (int64_t)gk * ldb0 : (int64_t)(gk - K0) * ldb1;
-                dma16(base + off + b_gn, sb + i * 1024);
+                dma16(base + off + b_gn[i], sb + i * 1024);
             }
         }
     };
@@ -331,7 +342,17 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
     const int a_row0 = wm * 64 + j;                             // + mt * 32
     const int a_sw = (j ^ (j >> 3)) & 7;                        // mt = 1 flips bit 2
     const uint32_t a_frag_off0 = a_row0 * 128;
-    const uint32_t b_frag_off = A_BYTES + (grp * 8) * 512 + (wn * 128 + 4 * j) * 2;
+    // transposing reads of B: the 16-lane group G = lane / 16 serves columns 16 (G & 1) .. + 15 of a
+    // 32-column MFMA tile and the K rows 8 (G >> 1) + 4 eh + (s >> 2), s = lane % 16, eh = 0, 1
+    const int s16 = lane & 15, G = lane >> 4;
+    const int kg = G >> 1, nh = G & 1;
+    const int hb = ((s16 >> 2) << 1) | kg;                      // h(r) of every row this lane reads
+    uint32_t b_off[4];
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+        const int m = wn * 8 + ct * 2 + nh;                     // 32-byte unit of the row
+        b_off[ct] = A_BYTES + (kg * 8 + (s16 >> 2)) * 512 + ((m ^ hb) * 32) + (s16 & 3) * 8;
+    }
 
     f32x16_t acc[2][4];
 #pragma unroll
@@ -348,53 +369,59 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
         if (t + 1 < T) issue(t + 1);
         const uint8_t* st = lds + (t & 1) * STAGE_BYTES;
         bf16x8_t a_frag[2][2];
-        u32x2_t b_raw[2][8];
+        bf16x8_t b_frag[2][4];
         auto load_frags = [&](int fb, int ks) {
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
                 a_frag[fb][mt] = *reinterpret_cast<const bf16x8_t*>(st + a_frag_off0 + mt * 32 * 128 + (((ks * 2 + grp) ^ a_sw ^ (mt * 4)) * 16));
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                b_raw[fb][i] = *reinterpret_cast<const u32x2_t*>(st + b_frag_off + (ks * 16 + i) * 512);
+            for (int ct = 0; ct < 4; ++ct) {
+                typedef s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * 512));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * 512 + 4 * 512));
+                const s16x8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                b_frag[fb][ct] = __builtin_bit_cast(bf16x8_t, both);
+            }
         };
         load_frags(0, 0);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const int fb = ks & 1;
             if (ks + 1 < 4) load_frags(fb ^ 1, ks + 1);
-            bf16x8_t b_frag[4];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                u32x4_t t4;
-                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-#pragma unroll
-                for (int m = 0; m < 4; ++m)
-                    t4[m] = __builtin_amdgcn_perm(b_raw[fb][2 * m + 1][c >> 1], b_raw[fb][2 * m][c >> 1], sel);
-                b_frag[c] = __builtin_bit_cast(bf16x8_t, t4);
-            }
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_frag[fb][mt], b_frag[c], acc[mt][c], 0, 0, 0);
+                    acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_frag[fb][c], a_frag[fb][mt], acc[mt][c], 0, 0, 0);
         }
     }
 
-    const int col = n0 + wn * 128 + 4 * j;
-    if (col < g.N) {
+    // acc[mt][ct][v] = C[row mt*32 + lane % 32][col ct*32 + 8 (v / 4) + 4 (lane / 32) + v % 4]: through LDS (each
+    // wave its own 32 x 128 bf16 patch, rows padded to 272 bytes), then 16 bytes per lane to memory
+    __builtin_amdgcn_s_barrier();                              // every wave has finished reading the last stage
+    uint8_t* patch = lds + wave * (32 * EPI_PITCH);
+    const int rr = lane >> 4, cc = lane & 15;
+    const int col = n0 + wn * 128 + cc * 8;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * 64 + mt * 32 + 8 * (v >> 2) + 4 * grp + (v & 3);
-                if (row < g.M) {
-                    u32x2_t out;
-                    out[0] = pack_bf16x2(acc[mt][0][v], acc[mt][1][v]);
-                    out[1] = pack_bf16x2(acc[mt][2][v], acc[mt][3][v]);
-                    *reinterpret_cast<u32x2_t*>(g.C + (int64_t)row * g.ldc + col) = out;
-                }
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                u32x2_t out;
+                out[0] = pack_bf16x2(acc[mt][ct][4 * q], acc[mt][ct][4 * q + 1]);
+                out[1] = pack_bf16x2(acc[mt][ct][4 * q + 2], acc[mt][ct][4 * q + 3]);
+                *reinterpret_cast<u32x2_t*>(patch + j * EPI_PITCH + (ct * 32 + 8 * q + 4 * grp) * 2) = out;
             }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int r = it * 4 + rr;
+            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(patch + r * EPI_PITCH + cc * 16);
+            const int row = m0 + wm * 64 + mt * 32 + r;
+            if (row < g.M && col < g.N) *reinterpret_cast<u32x4_t*>(g.C + (int64_t)row * g.ldc + col) = v;
         }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the patch is rewritten for the next 32 rows
     }
 }
 
