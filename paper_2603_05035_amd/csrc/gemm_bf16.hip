@@ -228,56 +228,68 @@ void gemm_bf16_kernel(Bf16Args g) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast path: 256 x 256 tile, 8 waves (wave tile 64 x 128), K step 64, two LDS stages filled by
-// direct-to-LDS loads (global_load_lds_dwordx4: no staging registers, no ds_write), one barrier
-// per K step.
+// Fast path: 256 x BN tile (BN = 256 or 192), 8 waves (wave tile 64 x BN/2), K step 64, two LDS
+// stages filled by direct-to-LDS loads (global_load_lds_dwordx4: no staging registers, no
+// ds_write), one barrier per K step.
 //   A rows (128 bytes per stage) keep their 16-byte chunks XOR-swizzled so that the 16-byte
 //     fragment reads of 16 consecutive rows hit distinct banks.
-//   B rows (512 bytes, K-major as in memory) are read with ds_read_b64_tr_b16, which hands every
+//   B rows (2 BN bytes, K-major as in memory) are read with ds_read_b64_tr_b16, which hands every
 //     lane the four K-consecutive values of one column: the MFMA operand layout, with no
-//     permutes.  Row r keeps its 16-byte chunk c at position c ^ (h(r) << 1),
-//     h(r) = ((r & 3) << 1) | ((r >> 3) & 1), which spreads the four rows one transposing read
-//     touches over all banks (measured: zero conflicts in the main loop).
+//     permutes.  The 16-byte chunks of a row are permuted (XOR for BN = 256, rotation for
+//     BN = 192, see b_chunk_pos) so that the four rows one transposing read touches are spread
+//     over all banks (measured: zero conflicts in the main loop).
 //   The MFMA operands are swapped (B fragment first), so the accumulators hold blocks of C^T and a
 //     lane owns 4 consecutive columns of one row; the epilogue goes through LDS once more so that
-//     the global stores are 16 bytes per lane over whole 256-byte row segments.
+//     the global stores are 16 bytes per lane over whole row segments.
 // Out-of-range rows / columns are clamped to valid addresses instead of being zero-filled, which
 // is correct because A is zero in columns [K, round_up(K, 64)) (required by the dispatcher) and
 // clamped B rows are finite.  Measured on the 2150 x 12288 x 4096 projection against the
 // alternatives that were tried: K step 32 with four stages and prefetch distance 3 (-4 %),
 // per-lane address arithmetic for the fetches (-5 %), v_perm transposition of B in registers
-// with direct stores (-9 %).
+// with direct stores (-9 %).  BN = 192 exists for the tile count: 2048 x 12288 is 384 tiles of
+// 256 x 256 (1.5 rounds on 256 CUs, so 2) but 512 of 256 x 192 (exactly 2 rounds of 0.87 the cost).
 namespace dma {
 
-constexpr int BM = 256, BN = 256, BKS = 64, STAGES = 2;
-constexpr int A_BYTES = BM * BKS * 2;           // 32 KB, rows of 128 B
-constexpr int B_BYTES = BKS * BN * 2;           // 32 KB, rows of 512 B
-constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-constexpr int EPI_PITCH = 272;                  // bytes per row of a wave's 32 x 128 bf16 output patch
+constexpr int BM = 256, BKS = 64, STAGES = 2;
+constexpr int A_BYTES = BM * BKS * 2;           // 32 KB per stage, rows of 128 B
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
+template <int BN> constexpr int lds_bytes() { return STAGES * (A_BYTES + BKS * BN * 2); }
 
 // lds_addr must be wave-uniform (it travels in M0); lane l's 16 bytes land at lds_addr + 16 l
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(gptr), "s"(lds_addr) : "memory", "m0");
 }
 
-__global__ __launch_bounds__(512)
-void gemm_bf16_dma_kernel(Bf16Args g) {
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
-    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)lds);
+// position (in 16-byte chunks) of chunk c of B row r inside the row, and its inverse.  BN = 256: rows r .. r + 3
+// of a transposing read differ in bits 1-2 of the 32-byte unit; BN = 192 (row pitch 384 bytes = 1.5 bank rounds):
+// rows r + 2, r + 3 are rotated by 64 bytes, which puts the four 64-byte spans on the four quarters of the banks.
+template <int BN> __device__ __forceinline__ int b_chunk_pos(int r, int c) {
+    if (BN == 256) return c ^ ((((r & 3) << 1) | ((r >> 3) & 1)) << 1);
+    const int p = c + 4 * ((r >> 1) & 1);
+    return p >= BN / 8 ? p - BN / 8 : p;
+}
+template <int BN> __device__ __forceinline__ int b_chunk_of_pos(int r, int pos) {
+    if (BN == 256) return pos ^ ((((r & 3) << 1) | ((r >> 3) & 1)) << 1);
+    const int c = pos - 4 * ((r >> 1) & 1);
+    return c < 0 ? c + BN / 8 : c;
+}
 
-    int tm, tn;
-    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, &tm, &tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+template <int BN>
+__device__ __forceinline__ void tile_body(const Bf16Args& g, uint8_t* lds, int m0, int n0) {
+    constexpr int NCT = BN / 64;
+    constexpr int ROWB = BN * 2;
+    constexpr int B_BYTES = BKS * ROWB;
+    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int NBD = B_BYTES / 8192;
+    constexpr int CPR = ROWB / 16;
+    constexpr int EPI_PITCH = BN + 16;
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)lds);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // in a scalar register: LDS addresses of the fetches stay scalar
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int j = lane & 31, grp = lane >> 5;
-
-    // kernel arguments pinned in scalar registers (a lane-varying choice between two argument
-    // fields would otherwise be compiled into a per-lane memory load of the argument block)
     auto uni32 = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
     auto uni64 = [&](int64_t x) {
         const uint32_t lo = __builtin_amdgcn_readfirstlane((int)(uint32_t)x), hi = __builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)x >> 32));
@@ -289,13 +301,10 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
     const uint16_t* B0p = (const uint16_t*)uni64((int64_t)g.B0);
     const uint16_t* B1p = (const uint16_t*)uni64((int64_t)g.B1);
 
-    // ---- what this lane fetches for every K step: 4 chunks of A and 4 of B (1 KB per wave each) ----
-    // The addresses are a per-lane base plus a scalar offset per K step; only a K step that
-    // straddles the end of B0 or of K takes the general per-lane path (row clamp, choice of operand).
     const uint16_t* a_src[4];
-    const uint16_t* b0_src[4];
-    const uint16_t* b1_src[4];
-    int b_krow[4], b_gn[4];
+    const uint16_t* b0_src[NBD];
+    const uint16_t* b1_src[NBD];
+    int b_krow[NBD], b_gn[NBD];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int blk = wave * 4 + i;
@@ -303,32 +312,35 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
         const int c = cp ^ ((row ^ (row >> 3)) & 7);
         int grow = m0 + row; grow = grow < g.M ? grow : g.M - 1;
         a_src[i] = g.A + (int64_t)grow * g.lda + c * 8;
-        const int br = blk * 2 + (lane >> 5);                           // B row of the stage this lane fetches from
-        const int h = ((br & 3) << 1) | ((br >> 3) & 1);
-        const int bc = (lane & 31) ^ (h << 1);                          // the chunk that belongs at this lane's LDS position
+    }
+#pragma unroll
+    for (int i = 0; i < NBD; ++i) {
+        const int e = (wave * NBD + i) * 64 + lane;             // 16-byte unit of the B stage this lane fills
+        const int br = e / CPR, cpos = e - br * CPR;
+        const int bc = b_chunk_of_pos<BN>(br, cpos);
         int gn = n0 + bc * 8; gn = gn < g.N ? gn : g.N - 8;
         b_krow[i] = br; b_gn[i] = gn;
         b0_src[i] = B0p + (int64_t)br * ldb0 + gn;
-        b1_src[i] = B1p + (int64_t)(br - K0) * ldb1 + gn;               // only used with a K offset >= K0 added
+        b1_src[i] = B1p + (int64_t)(br - K0) * ldb1 + gn;
     }
 
     auto issue = [&](int t) {
         const int k0 = t * BKS;
-        const uint32_t st = lds_base + (t & 1) * STAGE_BYTES + wave * 4096;     // + lane * 16 implied
+        const uint32_t st = lds_base + (t & 1) * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dma16(a_src[i] + k0, st + i * 1024);
-        const uint32_t sb = st + A_BYTES;
+        for (int i = 0; i < 4; ++i) dma16(a_src[i] + k0, st + (wave * 4 + i) * 1024);
+        const uint32_t sb = st + A_BYTES + wave * NBD * 1024;
         if (k0 + BKS <= K0) {
             const int64_t off = (int64_t)k0 * ldb0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dma16(b0_src[i] + off, sb + i * 1024);
+            for (int i = 0; i < NBD; ++i) dma16(b0_src[i] + off, sb + i * 1024);
         } else if (k0 >= K0 && k0 + BKS <= K) {
             const int64_t off = (int64_t)k0 * ldb1;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) dma16(b1_src[i] + off, sb + i * 1024);
+            for (int i = 0; i < NBD; ++i) dma16(b1_src[i] + off, sb + i * 1024);
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < NBD; ++i) {
                 int gk = k0 + b_krow[i]; gk = gk < K ? gk : K - 1;
                 const bool first = gk < K0;
                 const uint16_t* base = first ? B0p : B1p;
@@ -338,47 +350,44 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
         }
     };
 
-    // ---- fragment addressing ----
-    const int a_row0 = wm * 64 + j;                             // + mt * 32
-    const int a_sw = (j ^ (j >> 3)) & 7;                        // mt = 1 flips bit 2
+    const int a_row0 = wm * 64 + j;
+    const int a_sw = (j ^ (j >> 3)) & 7;
     const uint32_t a_frag_off0 = a_row0 * 128;
-    // transposing reads of B: the 16-lane group G = lane / 16 serves columns 16 (G & 1) .. + 15 of a
-    // 32-column MFMA tile and the K rows 8 (G >> 1) + 4 eh + (s >> 2), s = lane % 16, eh = 0, 1
     const int s16 = lane & 15, G = lane >> 4;
     const int kg = G >> 1, nh = G & 1;
-    const int hb = ((s16 >> 2) << 1) | kg;                      // h(r) of every row this lane reads
-    uint32_t b_off[4];
+    const int rl = kg * 8 + (s16 >> 2);                          // row of the first read; later reads add multiples of 4
+    uint32_t b_off[NCT];
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) {
-        const int m = wn * 8 + ct * 2 + nh;                     // 32-byte unit of the row
-        b_off[ct] = A_BYTES + (kg * 8 + (s16 >> 2)) * 512 + ((m ^ hb) * 32) + (s16 & 3) * 8;
+    for (int ct = 0; ct < NCT; ++ct) {
+        const int m = wn * (NCT * 2) + ct * 2 + nh;
+        b_off[ct] = A_BYTES + rl * ROWB + b_chunk_pos<BN>(rl, 2 * m) * 16 + (s16 & 3) * 8;
     }
 
-    f32x16_t acc[2][4];
+    f32x16_t acc[2][NCT];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
+        for (int c = 0; c < NCT; ++c)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mt][c][v] = 0.f;
 
     issue(0);
     for (int t = 0; t < T; ++t) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's share of K step t has landed
-        __builtin_amdgcn_s_barrier();                          // everyone's has, and the other stage is free
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
         if (t + 1 < T) issue(t + 1);
         const uint8_t* st = lds + (t & 1) * STAGE_BYTES;
         bf16x8_t a_frag[2][2];
-        bf16x8_t b_frag[2][4];
+        bf16x8_t b_frag[2][NCT];
         auto load_frags = [&](int fb, int ks) {
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
                 a_frag[fb][mt] = *reinterpret_cast<const bf16x8_t*>(st + a_frag_off0 + mt * 32 * 128 + (((ks * 2 + grp) ^ a_sw ^ (mt * 4)) * 16));
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct) {
+            for (int ct = 0; ct < NCT; ++ct) {
                 typedef s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
-                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * 512));
-                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * 512 + 4 * 512));
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * ROWB));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * ROWB + 4 * ROWB));
                 const s16x8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                 b_frag[fb][ct] = __builtin_bit_cast(bf16x8_t, both);
             }
@@ -391,21 +400,19 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                for (int c = 0; c < 4; ++c)
+                for (int c = 0; c < NCT; ++c)
                     acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_frag[fb][c], a_frag[fb][mt], acc[mt][c], 0, 0, 0);
         }
     }
 
-    // acc[mt][ct][v] = C[row mt*32 + lane % 32][col ct*32 + 8 (v / 4) + 4 (lane / 32) + v % 4]: through LDS (each
-    // wave its own 32 x 128 bf16 patch, rows padded to 272 bytes), then 16 bytes per lane to memory
-    __builtin_amdgcn_s_barrier();                              // every wave has finished reading the last stage
+    __builtin_amdgcn_s_barrier();
     uint8_t* patch = lds + wave * (32 * EPI_PITCH);
     const int rr = lane >> 4, cc = lane & 15;
-    const int col = n0 + wn * 128 + cc * 8;
+    const int col = n0 + wn * (BN / 2) + cc * 8;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int ct = 0; ct < NCT; ++ct)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 u32x2_t out;
@@ -414,15 +421,26 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
                 *reinterpret_cast<u32x2_t*>(patch + j * EPI_PITCH + (ct * 32 + 8 * q + 4 * grp) * 2) = out;
             }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        if (cc < BN / 16) {
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const int r = it * 4 + rr;
-            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(patch + r * EPI_PITCH + cc * 16);
-            const int row = m0 + wm * 64 + mt * 32 + r;
-            if (row < g.M && col < g.N) *reinterpret_cast<u32x4_t*>(g.C + (int64_t)row * g.ldc + col) = v;
+            for (int it = 0; it < 8; ++it) {
+                const int r = it * 4 + rr;
+                const u32x4_t v = *reinterpret_cast<const u32x4_t*>(patch + r * EPI_PITCH + cc * 16);
+                const int row = m0 + wm * 64 + mt * 32 + r;
+                if (row < g.M && col < g.N) *reinterpret_cast<u32x4_t*>(g.C + (int64_t)row * g.ldc + col) = v;
+            }
         }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the patch is rewritten for the next 32 rows
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
+}
+
+template <int BN>
+__global__ __launch_bounds__(512)
+void gemm_bf16_dma_kernel(Bf16Args g) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    int tm, tn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, &tm, &tn);
+    tile_body<BN>(g, lds, tm * BM, tn * BN);
 }
 
 }  // namespace dma
@@ -456,32 +474,49 @@ hipError_t allow_big_lds() {
 }  // namespace
 
 hipError_t gemm_bf16_init() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dma::gemm_bf16_dma_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, dma::STAGES * dma::STAGE_BYTES);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dma::gemm_bf16_dma_kernel<256>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, dma::lds_bytes<256>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dma::gemm_bf16_dma_kernel<192>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, dma::lds_bytes<192>());
     if (e != hipSuccess) return e;
     e = allow_big_lds<256, 256, 64>();
     if (e != hipSuccess) return e;
     return allow_big_lds<128, 128, 32>();
 }
 
-// Tile choice (measured on MI355X): 256 x 256 with 8 waves (two per SIMD, wave tile 64 x 128) wins
-// for every shape of the chain whose M exceeds one small tile; tiny M (decode-shaped batches)
-// takes 128 x 128 with 4 waves so that N alone can spread the work over the chip.
+namespace {
+
+template <int BN>
+hipError_t launch_dma(const GemmOperands& o, hipStream_t stream) {
+    Bf16Args a;
+    a.A = (const uint16_t*)o.A;   a.lda = o.lda;
+    a.B0 = (const uint16_t*)o.B0; a.ldb0 = o.ldb0; a.K0 = o.K0;
+    a.B1 = (const uint16_t*)o.B1; a.ldb1 = o.ldb1;
+    a.C = (uint16_t*)o.C;         a.ldc = o.ldc;
+    a.M = o.M; a.N = o.N; a.K = o.K;
+    a.tiles_m = (o.M + dma::BM - 1) / dma::BM;
+    a.tiles_n = (o.N + BN - 1) / BN;
+    hipLaunchKernelGGL(dma::gemm_bf16_dma_kernel<BN>, dim3(a.tiles_m * a.tiles_n), dim3(512),
+                       (size_t)dma::lds_bytes<BN>(), stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Tile choice (measured on MI355X): 256-row tiles with 8 waves (two per SIMD) win for every shape
+// of the chain whose M exceeds one small tile; the width is the one with the shorter schedule on
+// the chip's 256 CUs (one tile per CU at a time; a 192-wide tile costs 0.87 of a 256-wide one).
+// Tiny M (decode-shaped batches) takes 128 x 128 with 4 waves so that N alone can spread the work.
 hipError_t gemm_bf16(const GemmOperands& o, hipStream_t stream) {
     if (o.M <= 0 || o.N <= 0 || o.K <= 0) return hipSuccess;
-    if ((int64_t)o.M * o.lda >= (int64_t)1 << 31) return hipErrorInvalidValue;   // the kernel keeps 32-bit element offsets into A
+    if ((int64_t)o.M * o.lda >= (int64_t)1 << 31) return hipErrorInvalidValue;   // the generic kernel keeps 32-bit element offsets into A
     if (o.M > 128 && o.N >= 8 && (o.a_zero_padded || o.K % dma::BKS == 0)) {
-        Bf16Args a;
-        a.A = (const uint16_t*)o.A;   a.lda = o.lda;
-        a.B0 = (const uint16_t*)o.B0; a.ldb0 = o.ldb0; a.K0 = o.K0;
-        a.B1 = (const uint16_t*)o.B1; a.ldb1 = o.ldb1;
-        a.C = (uint16_t*)o.C;         a.ldc = o.ldc;
-        a.M = o.M; a.N = o.N; a.K = o.K;
-        a.tiles_m = (o.M + dma::BM - 1) / dma::BM;
-        a.tiles_n = (o.N + dma::BN - 1) / dma::BN;
-        hipLaunchKernelGGL(dma::gemm_bf16_dma_kernel, dim3(a.tiles_m * a.tiles_n), dim3(512),
-                           (size_t)dma::STAGES * dma::STAGE_BYTES, stream, a);
-        return hipGetLastError();
+        constexpr int kCus = 256;
+        const int64_t tiles_m = (o.M + dma::BM - 1) / dma::BM;
+        const int64_t t256 = tiles_m * ((o.N + 255) / 256), t192 = tiles_m * ((o.N + 191) / 192);
+        const double cost256 = (double)((t256 + kCus - 1) / kCus), cost192 = 0.87 * (double)((t192 + kCus - 1) / kCus);
+        return cost192 < cost256 ? launch_dma<192>(o, stream) : launch_dma<256>(o, stream);
     }
     if (o.M > 128) return launch<256, 256, 64>(o, stream);
     return launch<128, 128, 32>(o, stream);

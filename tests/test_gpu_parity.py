@@ -371,3 +371,23 @@ def test_strided_operands(ctx):
     for t in (U, Y, Z):      # the padding columns of the parent buffers are untouched
         parent = t._base
         assert torch.all(parent[:, t.shape[1]:] == 7.0)
+
+
+@pytest.mark.parametrize("M,K,N,ldy_extra", [
+    (300, 128, 30008, 0),      # 2 x 118 tiles of width 256 beat 2 x 157 of width 192: the 256-wide kernel, ragged last tile
+    (300, 192, 3016, 40),      # one round either way: the 192-wide kernel, ragged last tile, padded output rows
+    (129, 64, 8, 0),           # the narrowest legal output
+    (700, 4096, 520, 8),       # long K (64 K steps), three row tiles with a ragged last one
+])
+def test_project_bf16_fast_path_edges(ctx, M, K, N, ldy_extra):
+    """The direct-to-LDS bf16 kernel at shapes whose last tiles are ragged in M and N, both tile widths."""
+    rng = np.random.default_rng(M * 7 + N)
+    U = dev(rng.standard_normal((M, K)).astype(np.float32), "bf16")
+    W = dev((0.05 * rng.standard_normal((K, N))).astype(np.float32), "bf16")
+    parent = torch.full((M, N + ldy_extra), 3.0, dtype=torch.bfloat16, device="cuda")
+    Y = parent[:, :N]
+    g.gelo_project(ctx, U, W, Y)
+    torch.cuda.synchronize()
+    assert o.rel_frobenius(f64(Y), o.project(f64(U), f64(W))) < TOL_STAGE["bf16"]
+    if ldy_extra:
+        assert torch.all(parent[:, N:] == 3.0)
