@@ -103,11 +103,54 @@ void row_norms_kernel(const void* X, int64_t ld, int rows, int cols, float* norm
     if (lane == 0) norms[row] = sqrtf(s);
 }
 
-// Single workgroup.  Median: bitonic sort of the values (padded with +inf to a power of two)
-// in LDS, then the middle element(s).  Mean: tree sum in a fixed order.
+// The value of 0-based rank `rank` among keys[0:count] (LDS), by radix selection from the most
+// significant byte down: four passes of a 256-bin histogram, each narrowing the candidates to
+// one bin.  Exact (it returns one of the keys).  All 1024 threads call it; hist / pick are LDS.
+__device__ uint32_t select_rank(const uint32_t* keys, int count, int rank, uint32_t* hist, uint32_t* pick) {
+    const int tid = threadIdx.x;
+    uint32_t prefix = 0, mask = 0;
+    for (int pass = 3; pass >= 0; --pass) {
+        const int shift = 8 * pass;
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < count; i += 1024) {
+            const uint32_t k = keys[i];
+            if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            // lane l owns bins 4 l .. 4 l + 3; inclusive scan over the wave finds the bin holding `rank`
+            const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
+            const uint32_t mine = h0 + h1 + h2 + h3;
+            uint32_t incl = mine;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t up = __shfl_up(incl, off, 64);
+                if (tid >= off) incl += up;
+            }
+            const uint32_t before = incl - mine;
+            if ((uint32_t)rank >= before && (uint32_t)rank < incl) {
+                uint32_t r = (uint32_t)rank - before, bin = 4 * tid;
+                if (r >= h0) { r -= h0; ++bin; if (r >= h1) { r -= h1; ++bin; if (r >= h2) { r -= h2; ++bin; } } }
+                pick[0] = bin; pick[1] = r;
+            }
+        }
+        __syncthreads();
+        prefix |= pick[0] << shift;
+        mask |= 255u << shift;
+        rank = (int)pick[1];
+        __syncthreads();                    // pick is rewritten in the next pass
+    }
+    return prefix;
+}
+
+// Single workgroup.  Median: the middle element(s) by radix selection on the bit patterns (row
+// norms are non-negative floats, whose order is that of their bits).  Mean: tree sum in a fixed order.
 __global__ __launch_bounds__(1024)
-void norm_statistic_kernel(const float* v, int count, int stat, int padded, float* out) {
-    extern __shared__ float buf[];
+void norm_statistic_kernel(const float* v, int count, int stat, float* out) {
+    extern __shared__ float buf[];          // max(count, 1024) floats
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t pick[2];
     const int tid = threadIdx.x;
     if (stat == 1) {
         float s = 0.f;
@@ -121,21 +164,16 @@ void norm_statistic_kernel(const float* v, int count, int stat, int padded, floa
         if (tid == 0) *out = buf[0] / (float)count;
         return;
     }
-    for (int i = tid; i < padded; i += 1024) buf[i] = i < count ? v[i] : __builtin_inff();
+    uint32_t* keys = reinterpret_cast<uint32_t*>(buf);
+    for (int i = tid; i < count; i += 1024) keys[i] = __float_as_uint(v[i]);
     __syncthreads();
-    for (int size = 2; size <= padded; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int i = tid; i < (padded >> 1); i += 1024) {
-                const int lo = 2 * i - (i & (stride - 1));     // index with bit `stride` clear
-                const int hi = lo + stride;
-                const bool ascending = (lo & size) == 0;
-                const float a = buf[lo], b = buf[hi];
-                if ((a > b) == ascending) { buf[lo] = b; buf[hi] = a; }
-            }
-            __syncthreads();
-        }
+    const uint32_t hi = select_rank(keys, count, count >> 1, hist, pick);
+    float m = __uint_as_float(hi);
+    if ((count & 1) == 0) {
+        const uint32_t lo = select_rank(keys, count, (count >> 1) - 1, hist, pick);
+        m = 0.5f * (__uint_as_float(lo) + m);
     }
-    if (tid == 0) *out = (count & 1) ? buf[count >> 1] : 0.5f * (buf[(count >> 1) - 1] + buf[count >> 1]);
+    if (tid == 0) *out = m;
 }
 
 template <bool BF16>
@@ -224,10 +262,10 @@ hipError_t row_norms(const void* X, int is_bf16, int64_t ld, int rows, int cols,
 }
 
 hipError_t norm_statistic(const float* v, int count, int stat, float* out, hipStream_t stream) {
-    int padded = 1024;
-    while (padded < count) padded <<= 1;
-    hipLaunchKernelGGL(norm_statistic_kernel, dim3(1), dim3(1024), padded * sizeof(float), stream,
-                       v, count, stat, padded, out);
+    if (count <= 0) return hipErrorInvalidValue;
+    const size_t floats = count > 1024 ? (size_t)count : 1024;
+    hipLaunchKernelGGL(norm_statistic_kernel, dim3(1), dim3(1024), floats * sizeof(float), stream,
+                       v, count, stat, out);
     return hipGetLastError();
 }
 

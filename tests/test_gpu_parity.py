@@ -378,9 +378,12 @@ def test_strided_operands(ctx):
     (300, 192, 3016, 40),      # one round either way: the 192-wide kernel, ragged last tile, padded output rows
     (129, 64, 8, 0),           # the narrowest legal output
     (700, 4096, 520, 8),       # long K (64 K steps), three row tiles with a ragged last one
+    (1, 64, 8, 0), (33, 128, 520, 8), (97, 1024, 72, 0), (128, 640, 136, 16),   # the skinny kernel with 1, 2, 4, 4 waves
+    (68, 64, 200, 0),          # 3 waves, a single K step
 ])
 def test_project_bf16_fast_path_edges(ctx, M, K, N, ldy_extra):
-    """The direct-to-LDS bf16 kernel at shapes whose last tiles are ragged in M and N, both tile widths."""
+    """The direct-to-LDS bf16 kernels (both tile widths, and the skinny one for M <= 128) at shapes whose
+    last tiles are ragged in M and N."""
     rng = np.random.default_rng(M * 7 + N)
     U = dev(rng.standard_normal((M, K)).astype(np.float32), "bf16")
     W = dev((0.05 * rng.standard_normal((K, N))).astype(np.float32), "bf16")
