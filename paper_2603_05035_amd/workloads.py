@@ -57,6 +57,10 @@ WORKLOADS = {
                                 KIND_CONDITIONED, 8, 0xC3),
     # decode-shaped: 64 tokens per step, 4 shields
     "decode_bf16": Workload("decode_bf16", "bf16", 64, 4, 4096, 12288, KIND_ORTHOGONAL, 8, 0xC4),
+    # the attention output projection of the same layer shape (W_o is 4096 x 4096): the same chain with
+    # p = d and a fresh A of its own (the method offloads every linear projection Q, K, V and O)
+    "llama7b_bf16_oproj": Workload("llama7b_bf16_oproj", "bf16", 2048, 102, 4096, 4096,
+                                   KIND_ORTHOGONAL, 8, 0xC5),
 }
 
 

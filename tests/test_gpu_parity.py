@@ -290,6 +290,29 @@ def test_full_size_bf16_prefill(ctx):
     check_orthogonal_A(f64(r["A"]), 0xC0FFEE, 9000 + 64 * w.seed, w.n, compare_elements=False)
 
 
+def test_full_size_o_projection(ctx):
+    """The attention output projection (p = d = 4096): same chain, same kernels, its own fresh A."""
+    w, r = full_size(ctx, "llama7b_bf16_oproj")
+    err = stagewise_check(r, "bf16", w.n_data, w.k_shield)
+    print("bf16 O-projection 2048+102 x 4096 x 4096: rel err", err)
+
+
+def test_layer_qkv_then_o_projection(ctx):
+    """One layer's two offloaded projections, each with a fresh A of its own (Section 3.2: the matrix is
+    never reused): fused QKV (p = 3 d) on the hidden states, then O (p = d) on the attention output,
+    for which a second synthetic activation stands in."""
+    nd, k, d = 150, 8, 256
+    Hq = wl.make_hidden(nd, d, 41, 4)
+    Ho = wl.make_hidden(nd, d, 42, 4)
+    Wqkv, Wo = wl.make_weight(d, 3 * d, 43), wl.make_weight(d, d, 44)
+    rq = run_chain(ctx, g.GELO_ORTHOGONAL, "bf16", Hq, Wqkv, k, batch_id=7100)
+    ro = run_chain(ctx, g.GELO_ORTHOGONAL, "bf16", Ho, Wo, k, batch_id=7101)
+    stagewise_check(rq, "bf16", nd, k)
+    stagewise_check(ro, "bf16", nd, k)
+    assert rq["Z"].shape == (nd, 3 * d) and ro["Z"].shape == (nd, d)
+    assert (rq["A"] - ro["A"]).abs().max() > 0.05          # unrelated mixing matrices
+
+
 @pytest.mark.parametrize("name,layer", [("sweep_bf16_orth", 0), ("sweep_bf16_cond", 1)])
 def test_full_size_sweep_layers(ctx, name, layer):
     w, r = full_size(ctx, name, layer)
