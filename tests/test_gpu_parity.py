@@ -417,3 +417,58 @@ def test_project_bf16_fast_path_edges(ctx, M, K, N, ldy_extra):
     assert o.rel_frobenius(f64(Y), o.project(f64(U), f64(W))) < TOL_STAGE["bf16"]
     if ldy_extra:
         assert torch.all(parent[:, N:] == 3.0)
+
+
+def test_sampling_ahead_on_side_streams_matches_one_stream():
+    """The mixing matrix does not depend on the data, so it may be drawn ahead on another stream and
+    context while earlier batches run; the chain then waits for it through the mixing object.  The
+    results must be bit-identical to the same calls issued on one stream."""
+    nd, k, d, p, depth, batches = 200, 10, 256, 384, 3, 7
+    H = dev(wl.make_hidden(nd, d, 51, 4), "bf16")
+    W = dev(wl.make_weight(d, p, 52), "bf16")
+
+    def one_stream():
+        out = []
+        ctxs = [g.gelo_create(0, 0xABC + s, allow_batch_reuse=False) for s in range(depth)]
+        for b in range(batches):
+            c = ctxs[b % depth]
+            m = g.gelo_sample_mixing(c, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=b)
+            U = torch.empty((nd + k, d), dtype=torch.bfloat16, device="cuda")
+            Y = torch.empty((nd + k, p), dtype=torch.bfloat16, device="cuda")
+            Z = torch.empty((nd, p), dtype=torch.bfloat16, device="cuda")
+            g.gelo_mix(c, m, H, U); g.gelo_project(c, U, W, Y); g.gelo_unmix(c, m, Y, Z)
+            g.gelo_mixing_free(c, m)
+            out.append(Z)
+        torch.cuda.synchronize()
+        for c in ctxs:
+            g.gelo_destroy(c)
+        return out
+
+    def pipelined():
+        out = []
+        ctxs = [g.gelo_create(0, 0xABC + s, allow_batch_reuse=False) for s in range(depth)]
+        side = [torch.cuda.Stream() for _ in range(depth)]
+        ring = [None] * depth
+        for b in range(min(depth, batches)):
+            ring[b] = g.gelo_sample_mixing(ctxs[b], g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=b, stream=side[b])
+        for b in range(batches):
+            s = b % depth
+            c, m = ctxs[s], ring[s]
+            U = torch.empty((nd + k, d), dtype=torch.bfloat16, device="cuda")
+            Y = torch.empty((nd + k, p), dtype=torch.bfloat16, device="cuda")
+            Z = torch.empty((nd, p), dtype=torch.bfloat16, device="cuda")
+            g.gelo_mix(c, m, H, U); g.gelo_project(c, U, W, Y); g.gelo_unmix(c, m, Y, Z)
+            g.gelo_mixing_free(c, m)
+            if b + depth < batches:
+                ring[s] = g.gelo_sample_mixing(c, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=b + depth, stream=side[s])
+            out.append(Z)
+        torch.cuda.synchronize()
+        for c in ctxs:
+            g.gelo_destroy(c)
+        return out
+
+    a, b = one_stream(), pipelined()
+    ref = o.plain_projection(f64(H), f64(W))
+    for za, zb in zip(a, b):
+        assert torch.equal(za, zb)
+        assert o.rel_frobenius(f64(zb), ref) < TOL_END["bf16"]
