@@ -34,6 +34,7 @@ struct Bf16Args {
     uint16_t* C;        int64_t ldc;
     int M, N, K;
     int tiles_m, tiles_n;
+    int narrow_cols = 0;        // mixed-width launch only: tile columns of width 192 after tiles_n columns of width 256
 };
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
@@ -443,6 +444,23 @@ void gemm_bf16_dma_kernel(Bf16Args g) {
     tile_body<BN>(g, lds, tm * BM, tn * BN);
 }
 
+// Both tile widths in one launch: tiles_n columns of 256-wide tiles first (low block ids start first),
+// then narrow_cols columns of 192-wide tiles.  For a tile count between one and two rounds of the
+// chip's CUs this ends after one wide plus one narrow tile time instead of two wide ones.
+__global__ __launch_bounds__(512)
+void gemm_bf16_dma_mixed_kernel(Bf16Args g) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    const int wide_tiles = g.tiles_m * g.tiles_n;
+    int tm, tn;
+    if ((int)blockIdx.x < wide_tiles) {
+        tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, &tm, &tn);
+        tile_body<256>(g, lds, tm * BM, tn * 256);
+    } else {
+        tile_of_block(blockIdx.x - wide_tiles, g.tiles_m, g.narrow_cols, &tm, &tn);
+        tile_body<192>(g, lds, tm * BM, g.tiles_n * 256 + tn * 192);
+    }
+}
+
 }  // namespace dma
 
 // ---------------------------------------------------------------------------------------------
@@ -671,6 +689,9 @@ hipError_t gemm_bf16_init() {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dma::gemm_bf16_dma_kernel<192>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, dma::lds_bytes<192>());
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dma::gemm_bf16_dma_mixed_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, dma::lds_bytes<256>());
+    if (e != hipSuccess) return e;
     e = allow_big_lds<256, 256, 64>();
     if (e != hipSuccess) return e;
     e = allow_skinny_lds<1>();
@@ -692,7 +713,7 @@ hipError_t launch_dma(const GemmOperands& o, hipStream_t stream) {
     a.C = (uint16_t*)o.C;         a.ldc = o.ldc;
     a.M = o.M; a.N = o.N; a.K = o.K;
     a.tiles_m = (o.M + dma::BM - 1) / dma::BM;
-    a.tiles_n = (o.N + BN - 1) / BN;
+    a.tiles_n = (o.N + BN - 1) / BN; a.narrow_cols = 0;
     hipLaunchKernelGGL(dma::gemm_bf16_dma_kernel<BN>, dim3(a.tiles_m * a.tiles_n), dim3(512),
                        (size_t)dma::lds_bytes<BN>(), stream, a);
     return hipGetLastError();
@@ -709,9 +730,35 @@ hipError_t gemm_bf16(const GemmOperands& o, hipStream_t stream) {
     if ((int64_t)o.M * o.lda >= (int64_t)1 << 31) return hipErrorInvalidValue;   // the generic kernel keeps 32-bit element offsets into A
     if (o.M > 128 && o.N >= 8 && (o.a_zero_padded || o.K % dma::BKS == 0)) {
         constexpr int kCus = 256;
+        constexpr double kNarrow = 0.87;         // measured cost of a 192-wide tile relative to a 256-wide one
         const int64_t tiles_m = (o.M + dma::BM - 1) / dma::BM;
         const int64_t t256 = tiles_m * ((o.N + 255) / 256), t192 = tiles_m * ((o.N + 191) / 192);
-        const double cost256 = (double)((t256 + kCus - 1) / kCus), cost192 = 0.87 * (double)((t192 + kCus - 1) / kCus);
+        const double cost256 = (double)((t256 + kCus - 1) / kCus), cost192 = kNarrow * (double)((t192 + kCus - 1) / kCus);
+        // mixed: at most one round of wide tiles and two rounds in all, so that every CU runs at most wide + narrow
+        int best_a = -1, best_b = 0;
+        if (t256 > kCus && tiles_m <= kCus) {
+            int64_t best_width = 0;
+            for (int64_t a = std::min<int64_t>(o.N / 256, kCus / tiles_m); a >= 1; --a) {
+                const int64_t rest = o.N - a * 256;
+                const int64_t b = rest > 0 ? (rest + 191) / 192 : 0;
+                if (b == 0 || tiles_m * (a + b) > 2 * kCus) continue;
+                const int64_t width = a * 256 + b * 192;
+                if (best_a < 0 || width < best_width) { best_a = (int)a; best_b = (int)b; best_width = width; }
+            }
+        }
+        const double cost_mixed = best_a > 0 ? 1.0 + kNarrow : 1e30;
+        if (cost_mixed < cost256 && cost_mixed < cost192) {
+            Bf16Args a;
+            a.A = (const uint16_t*)o.A;   a.lda = o.lda;
+            a.B0 = (const uint16_t*)o.B0; a.ldb0 = o.ldb0; a.K0 = o.K0;
+            a.B1 = (const uint16_t*)o.B1; a.ldb1 = o.ldb1;
+            a.C = (uint16_t*)o.C;         a.ldc = o.ldc;
+            a.M = o.M; a.N = o.N; a.K = o.K;
+            a.tiles_m = (int)tiles_m; a.tiles_n = best_a; a.narrow_cols = best_b;
+            hipLaunchKernelGGL(dma::gemm_bf16_dma_mixed_kernel, dim3((unsigned)(tiles_m * (best_a + best_b))), dim3(512),
+                               (size_t)dma::lds_bytes<256>(), stream, a);
+            return hipGetLastError();
+        }
         return cost192 < cost256 ? launch_dma<192>(o, stream) : launch_dma<256>(o, stream);
     }
     if (o.M > 128) return launch<256, 256, 64>(o, stream);

@@ -398,6 +398,7 @@ def test_strided_operands(ctx):
 
 @pytest.mark.parametrize("M,K,N,ldy_extra", [
     (300, 128, 30008, 0),      # 2 x 118 tiles of width 256 beat 2 x 157 of width 192: the 256-wide kernel, ragged last tile
+    (300, 64, 50008, 0),       # 392 wide tiles or 522 narrow ones: the launch that mixes both widths, ragged last tile
     (300, 192, 3016, 40),      # one round either way: the 192-wide kernel, ragged last tile, padded output rows
     (129, 64, 8, 0),           # the narrowest legal output
     (700, 4096, 520, 8),       # long K (64 K steps), three row tiles with a ragged last one
