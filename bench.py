@@ -54,6 +54,7 @@ def write_traffic_record(workload: str, fetch_csv: str, write_csv: str) -> int:
     """
     import csv
     import hashlib
+    import re
     from paper_2603_05035_amd import workloads as wl
     w = wl.WORKLOADS[workload]
     def read(path, counter):
@@ -83,7 +84,7 @@ def write_traffic_record(workload: str, fetch_csv: str, write_csv: str) -> int:
     fetch_b, write_b = f_gemm * 1024.0 * fetch_factor, w_gemm * 1024.0 * write_factor
     rec = {
         "workload": w.name,
-        "kernel": key[0].split("(")[0].split("::")[-1] + " (project Y = U W)", "grid_threads": key[1],
+        "kernel": re.search(r"gemm_bf16_dma\w*(<\d+>)?", key[0]).group(0) + " (project Y = U W)", "grid_threads": key[1],
         "kernel_source_sha1": hashlib.sha1(open(SRC_PATH, "rb").read()).hexdigest(),
         "traffic_bytes_per_launch": fetch_b + write_b,
         "fetch_bytes_per_launch": fetch_b, "write_bytes_per_launch": write_b,
