@@ -376,7 +376,11 @@ __device__ __forceinline__ void tile_body(const Bf16Args& g, uint8_t* lds, int m
     for (int t = 0; t < T; ++t) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        if (t + 1 < T) issue(t + 1);
+        // The two waves of a SIMD (w and w + 4) would otherwise both spend the start of the K step issuing
+        // fetches while the matrix pipe idles: with the wide tile the second one issues after its first two
+        // MFMA groups instead (measured +3 %; no gain with the narrow tile).
+        constexpr bool STAGGER = BN == 256;
+        if ((!STAGGER || wave < 4) && t + 1 < T) issue(t + 1);
         const uint8_t* st = lds + (t & 1) * STAGE_BYTES;
         bf16x8_t a_frag[2][2];
         bf16x8_t b_frag[2][NCT];
@@ -403,6 +407,7 @@ __device__ __forceinline__ void tile_body(const Bf16Args& g, uint8_t* lds, int m
 #pragma unroll
                 for (int c = 0; c < NCT; ++c)
                     acc[mt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_frag[fb][c], a_frag[fb][mt], acc[mt][c], 0, 0, 0);
+            if (STAGGER && wave >= 4 && ks == 1 && t + 1 < T) issue(t + 1);
         }
     }
 
