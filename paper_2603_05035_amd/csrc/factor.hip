@@ -122,20 +122,23 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, int64_t ld, float* Vr, 
         for (int c = 0; c < NB; ++c) P[i][c] = r < m ? Mp[(int64_t)c * ld + r] : 0.f;      // consecutive lanes, consecutive addresses
     }
 
+    // Rows at or beyond m hold zeros and stay zero, rows tid + i NTHR with i > 0 lie below every
+    // diagonal entry of the panel: only register row 0 needs a test against j, and that test is a
+    // select, so the column loop is straight-line code.
     static_for<NB>([&](auto jc) {
         constexpr int j = decltype(jc)::value;
         constexpr int pb = j & 1;                       // LDS buffers alternate between columns
         float t[NB];
+        {
+            const float x = tid > j ? P[0][j] : 0.f;
 #pragma unroll
-        for (int s = 0; s < NB; ++s) t[s] = 0.f;
+            for (int s = 0; s < NB; ++s) t[s] = x * P[0][s];
+        }
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const int r = tid + i * NTHR;
-            if (r > j && r < m) {
-                const float x = P[i][j];
+        for (int i = 1; i < R; ++i) {
+            const float x = P[i][j];
 #pragma unroll
-                for (int s = 0; s < NB; ++s) t[s] = fmaf(x, P[i][s], t[s]);
-            }
+            for (int s = 0; s < NB; ++s) t[s] = fmaf(x, P[i][s], t[s]);
         }
         if (tid == j) {                                 // row j is register row 0 of thread j
 #pragma unroll
@@ -150,34 +153,38 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, int64_t ld, float* Vr, 
         const float pr = prow[pb][li];
         const float xnorm2 = lane_value<j>(tot);
         const float alpha = lane_value<j>(pr);
-        float beta = alpha, tau = 0.f, scale = 0.f;
-        if (xnorm2 > 0.f) {
-            beta = -copysignf(sqrtf(fmaf(alpha, alpha, xnorm2)), alpha);
-            tau = (beta - alpha) / beta;
-            scale = 1.0f / (alpha - beta);
-        }
+        // beta = -sign(alpha) sqrt(alpha^2 + |x|^2), tau = (beta - alpha) / beta, scale = 1 / (alpha - beta); the
+        // hardware square root and reciprocals (1 ulp) keep this dependent chain short.  A zero tail: tau = 0.
+        const bool tail = xnorm2 > 0.f;
+        const float nrm = __builtin_amdgcn_sqrtf(fmaf(alpha, alpha, xnorm2));
+        const float beta = tail ? -copysignf(nrm, alpha) : alpha;
+        const float tau = tail ? (beta - alpha) * __builtin_amdgcn_rcpf(beta) : 0.f;
+        const float scale = tail ? __builtin_amdgcn_rcpf(alpha - beta) : 0.f;
         const float wl = fmaf(scale, tot, pr);          // v_j . (column li)
-        if (tid < NB) Z[j][tid] = wl;
-        if (tid == 0) { tau_s[j] = tau; rdiag[j] = beta; }
+        if (tid < NB) {
+            Z[j][tid] = wl;
+            if (tid == 0) { tau_s[j] = tau; rdiag[j] = beta; }
+        }
         float w[NB];
         static_for<NB>([&](auto sc) {
             constexpr int s = decltype(sc)::value;
             if constexpr (s > j) w[s] = lane_value<s>(wl);
         });
+        {
+            // register row 0: below the diagonal v = x * scale, on it v = 1 and the entry becomes beta, above it nothing
+            const float v = tid > j ? P[0][j] * scale : (tid == j ? 1.f : 0.f);
+            P[0][j] = tid > j ? v : (tid == j ? beta : P[0][j]);
+            const float tv = tau * v;
 #pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const int r = tid + i * NTHR;
-            if (r > j && r < m) {
-                const float v = P[i][j] * scale;
-                P[i][j] = v;
-                const float tv = tau * v;
+            for (int s = j + 1; s < NB; ++s) P[0][s] = fmaf(-tv, w[s], P[0][s]);
+        }
 #pragma unroll
-                for (int s = j + 1; s < NB; ++s) P[i][s] = fmaf(-tv, w[s], P[i][s]);
-            } else if (r == j) {
-                P[i][j] = beta;
+        for (int i = 1; i < R; ++i) {
+            const float v = P[i][j] * scale;
+            P[i][j] = v;
+            const float tv = tau * v;
 #pragma unroll
-                for (int s = j + 1; s < NB; ++s) P[i][s] = fmaf(-tau, w[s], P[i][s]);
-            }
+            for (int s = j + 1; s < NB; ++s) P[i][s] = fmaf(-tv, w[s], P[i][s]);
         }
     });
     __syncthreads();
