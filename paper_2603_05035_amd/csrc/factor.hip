@@ -435,27 +435,56 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr,
 
     float* Cl = Cs + (int64_t)c * ldc + 4 * g;               // this lane's column, its first row of block 0
     const float* Vtl = Vt + (int64_t)c * ldt + 4 * g;        // reflector c, same rows
+    const float* Vrl = Vr + (int64_t)c * NB + 4 * g;         // row c of a block, reflectors 4 g ..
+    // Blocks past the end are clamped to the last one for every load (a valid address, no branch) and
+    // take no part: their strip registers are zero and they are not stored.  All loads of a phase are
+    // issued ahead of the MFMAs that use them, in groups of GRP blocks, double-buffered: a load
+    // consumed right behind its issue would expose one memory latency per block.
+    constexpr int GRP = 5, NG = NBLK / GRP;
+    static_assert(NBLK % GRP == 0, "blocks per wave must be a multiple of the load group");
+    const int last = nblocks - 1;
     f32x4_t cr[NBLK];
 #pragma unroll
     for (int b = 0; b < NBLK; ++b) {
         const int blk = wave + 8 * b;
-        cr[b] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        if (blk < nblocks) cr[b] = *reinterpret_cast<const f32x4_t*>(Cl + 16 * blk);
+        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(Cl + 16 * (blk < nblocks ? blk : last));
+        const bool valid = blk < nblocks;
+        cr[b] = f32x4_t{valid ? v[0] : 0.f, valid ? v[1] : 0.f, valid ? v[2] : 0.f, valid ? v[3] : 0.f};
     }
     // W_partial[i][col] = sum over this wave's rows of V[r][i] C[r][col]; MFMA (b, v) contracts the four
     // rows 16 blk + 4 kk + v (kk = lane / 16): A = V[row][lane % 16], B = the strip register itself
     f32x4_t w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t va[2][GRP];
+    auto load_vt = [&](int grp) {
 #pragma unroll
-    for (int b = 0; b < NBLK; ++b) {
-        const int blk = wave + 8 * b;
-        if (blk < nblocks) {
-            const f32x4_t a = *reinterpret_cast<const f32x4_t*>(Vtl + 16 * blk);
+        for (int q = 0; q < GRP; ++q) {
+            const int blk = wave + 8 * (grp * GRP + q);
+            va[grp & 1][q] = *reinterpret_cast<const f32x4_t*>(Vtl + 16 * (blk < nblocks ? blk : last));
+        }
+    };
+    load_vt(0);
+#pragma unroll
+    for (int grp = 0; grp < NG; ++grp) {
+        if (grp + 1 < NG) load_vt(grp + 1);
+#pragma unroll
+        for (int q = 0; q < GRP; ++q) {
+            const int b = grp * GRP + q;
+            const f32x4_t a = va[grp & 1][q];
             w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[b][0], w0, 0, 0, 0);
             w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], cr[b][1], w1, 0, 0, 0);
             w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], cr[b][2], w0, 0, 0, 0);
             w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], cr[b][3], w1, 0, 0, 0);
         }
     }
+    // the reflector rows of the second product do not depend on W: fetch the first group before the barriers
+    auto load_vr = [&](int grp) {
+#pragma unroll
+        for (int q = 0; q < GRP; ++q) {
+            const int blk = wave + 8 * (grp * GRP + q);
+            va[grp & 1][q] = *reinterpret_cast<const f32x4_t*>(Vrl + (int64_t)(16 * (blk < nblocks ? blk : last)) * NB);
+        }
+    };
+    load_vr(0);
 #pragma unroll
     for (int v = 0; v < 4; ++v) Wp[wave][4 * g + v][c] = w0[v] + w1[v];      // accumulator row 4 g + v, column c
     __syncthreads();
@@ -480,15 +509,18 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr,
 #pragma unroll
     for (int q = 0; q < 4; ++q) bq[q] = Wn[4 * g + q][c];
 #pragma unroll
-    for (int b = 0; b < NBLK; ++b) {
-        const int blk = wave + 8 * b;
-        if (blk < nblocks) {
-            const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(Vr + (int64_t)(16 * blk + c) * NB + 4 * g);
+    for (int grp = 0; grp < NG; ++grp) {
+        if (grp + 1 < NG) load_vr(grp + 1);
+#pragma unroll
+        for (int q = 0; q < GRP; ++q) {
+            const int b = grp * GRP + q;
+            const int blk = wave + 8 * b;
+            const f32x4_t a4 = va[grp & 1][q];
             cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[0], bq[0], cr[b], 0, 0, 0);
             cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[1], bq[1], cr[b], 0, 0, 0);
             cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[2], bq[2], cr[b], 0, 0, 0);
             cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[3], bq[3], cr[b], 0, 0, 0);
-            *reinterpret_cast<f32x4_t*>(Cl + 16 * blk) = cr[b];
+            if (blk < nblocks) *reinterpret_cast<f32x4_t*>(Cl + 16 * blk) = cr[b];
         }
     }
 }
