@@ -246,16 +246,15 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
 
     auto orthogonal_into_X = [&]() -> hipError_t {
         ps.c1 = kStreamMixing << 8;
-        hipError_t e = fill_normal(ws.M, ld, n, n, ps, 1.0f, 1, s);          // column-major for the QR
-        if (e == hipSuccess) e = pad_matrix(ws.M, ld, n, ws.n_pad, 0, s);
-        if (e == hipSuccess) e = householder_qr(ws, s);
+        hipError_t e = fill_normal(ws.M, ws.n_pad / 16, n, n, ps, 1.0f, 1, s);     // straight into the QR's tiles
+        if (e == hipSuccess) e = householder_qr(ws, n, s);
         return e;
     };
 
     if (kind == GELO_ORTHOGONAL) {
         GELO_HIP(ctx, orthogonal_into_X());
         // A = Q diag(sign r_ii); A^-1 = A^T
-        GELO_HIP(ctx, emit_matrix(ws.X, ld, ws.rdiag, n, ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s));
+        GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s));
     } else {
         bool accepted = false;
         const int attempts = kind == GELO_GAUSSIAN ? max_attempts : 1;
@@ -264,19 +263,19 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
             if (kind == GELO_GAUSSIAN) {
                 ps.c1 = (kStreamMixing << 8) | (uint32_t)attempt;
                 GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f / std::sqrt((float)n), 0, s));
-                GELO_HIP(ctx, emit_matrix(ws.M, ld, nullptr, n, ldk, m->A32, m->A16, nullptr, nullptr, s));
+                GELO_HIP(ctx, emit_matrix(ws.M, ld, 0, nullptr, n, ldk, m->A32, m->A16, nullptr, nullptr, s));
             } else {
                 GELO_HIP(ctx, orthogonal_into_X());
-                GELO_HIP(ctx, emit_matrix(ws.X, ld, ws.rdiag, n, ldk, m->A32, nullptr, nullptr, nullptr, s));
+                GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, nullptr, nullptr, nullptr, s));
                 ps.c1 = kStreamPerturb << 8;
                 GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f, 0, s));
                 GELO_HIP(ctx, axpy_matrix(m->A32, ldk, ws.M, ld, n, n, kConditionedBeta / std::sqrt((float)n), s));
-                GELO_HIP(ctx, emit_matrix(m->A32, ldk, nullptr, n, ld, ws.M, nullptr, nullptr, nullptr, s));
-                if (bf) GELO_HIP(ctx, emit_matrix(m->A32, ldk, nullptr, n, ldk, nullptr, m->A16, nullptr, nullptr, s));
+                GELO_HIP(ctx, emit_matrix(m->A32, ldk, 0, nullptr, n, ld, ws.M, nullptr, nullptr, nullptr, s));
+                if (bf) GELO_HIP(ctx, emit_matrix(m->A32, ldk, 0, nullptr, n, ldk, nullptr, m->A16, nullptr, nullptr, s));
             }
             GELO_HIP(ctx, pad_matrix(ws.M, ld, n, ws.n_pad, 1, s));
             GELO_HIP(ctx, lu_inverse(ws, s));
-            GELO_HIP(ctx, emit_matrix(ws.X, ld, nullptr, n, ldk, m->Ainv32, m->Ainv16, nullptr, nullptr, s));
+            GELO_HIP(ctx, emit_matrix(ws.X, ld, 0, nullptr, n, ldk, m->Ainv32, m->Ainv16, nullptr, nullptr, s));
             GELO_HIP(ctx, kappa_estimate(m->A32, m->Ainv32, ldk, n, ws, kKappaIterations, s));
             GELO_HIP(ctx, hipMemcpyAsync(m->stat + 1, ws.scalars, sizeof(float), hipMemcpyDeviceToDevice, s));
             if (kind == GELO_GAUSSIAN) {

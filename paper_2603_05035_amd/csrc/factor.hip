@@ -99,12 +99,12 @@ __device__ __forceinline__ float lane_value(float v) {
 // and the Gram entry v_s . v_j that the T factor needs (s < j).  After the reduction lane s of
 // every wave holds the quantities of column s; the update coefficients are then read into
 // scalar registers.  The column loop is unrolled so that all register indices are constants.
-// Mp: the panel in column-major order (element (r, c) at Mp[c * ld + r]).  The reflector block is
-// written twice, compactly: Vr[r * 16 + c] (row-major, the A operand of C += V W') and
-// Vt[c * ldt + r] (the A operand of W = V^T C), both with explicit unit diagonal and zeros above.
+// Mp: the panel's first 16 x 16 tile; the tiles of the rows below follow at 256 floats each
+// (element (r, c) at Mp[(r / 16) * 256 + c * 16 + r % 16]).  The reflector block is written twice,
+// compactly: Vr[r * 16 + c] (row-major, the A operand of C += V W') and Vt in the same tiles as
+// the panel (the A operand of W = V^T C), both with explicit unit diagonal and zeros above.
 template <int NTHR, int R>
-__device__ __forceinline__ void qr_panel_body(float* Mp, int64_t ld, float* Vr, float* Vt, int64_t ldt, float* Tg,
-                                              float* rdiag, int m) {
+__device__ __forceinline__ void qr_panel_body(float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, int m) {
     constexpr int NW = NTHR / 64;
     __shared__ float red[2][NW][NB];
     __shared__ float prow[2][NB];
@@ -118,8 +118,9 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, int64_t ld, float* Vr, 
 #pragma unroll
     for (int i = 0; i < R; ++i) {
         const int r = tid + i * NTHR;
+        const int64_t at = (int64_t)(r >> 4) * 256 + (r & 15);
 #pragma unroll
-        for (int c = 0; c < NB; ++c) P[i][c] = r < m ? Mp[(int64_t)c * ld + r] : 0.f;      // consecutive lanes, consecutive addresses
+        for (int c = 0; c < NB; ++c) P[i][c] = r < m ? Mp[at + c * 16] : 0.f;             // 16 consecutive lanes, consecutive addresses
     }
 
     // Rows at or beyond m hold zeros and stay zero, rows tid + i NTHR with i > 0 lie below every
@@ -221,8 +222,8 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, int64_t ld, float* Vr, 
                 for (int e = 0; e < 4; ++e) {
                     const int c = c4 * 4 + e;
                     v[e] = r > c ? P[i][c] : (r == c ? 1.f : 0.f);
-                    Mp[(int64_t)c * ld + r] = P[i][c];
-                    Vt[(int64_t)c * ldt + r] = v[e];
+                    Mp[(int64_t)(r >> 4) * 256 + c * 16 + (r & 15)] = P[i][c];
+                    Vt[(int64_t)(r >> 4) * 256 + c * 16 + (r & 15)] = v[e];
                 }
                 *reinterpret_cast<float4*>(Vr + (int64_t)r * NB + c4 * 4) = make_float4(v[0], v[1], v[2], v[3]);
             }
@@ -232,8 +233,8 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, int64_t ld, float* Vr, 
 
 template <int NTHR, int R>
 __global__ __launch_bounds__(NTHR)
-void qr_panel_kernel(float* Mp, int64_t ld, float* Vr, float* Vt, int64_t ldt, float* Tg, float* rdiag, int m) {
-    qr_panel_body<NTHR, R>(Mp, ld, Vr, Vt, ldt, Tg, rdiag, m);
+void qr_panel_kernel(float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, int m) {
+    qr_panel_body<NTHR, R>(Mp, Vr, Vt, Tg, rdiag, m);
 }
 
 // ------------------------------------------------------- skinny rank-16 kernels --
@@ -416,15 +417,15 @@ void rank16_update_kernel(const float* L, int64_t ldl, const float* W, int64_t l
 // and as the accumulator of C -= V W' (K = the 16 reflectors).  Wave w of 8 owns blocks
 // w, w+8, ...; the 8 partial W are added in wave order (fixed order, reproducible), then
 // W' = -op(T) W is formed once per strip.
-// Layouts, chosen so that every global access is one 16-byte load or store per lane: C is
-// column-major (Cs[c * ldc + r]: the four rows 4 g .. 4 g + 3 a lane owns are adjacent), the
-// reflectors come as Vt[i * ldt + r] for the first product and as Vr[r * 16 + i] for the second.
+// Layouts, chosen so that every global access of a wave is one contiguous kilobyte, 16 bytes per
+// lane: the strip is a column of 16 x 16 tiles (256 floats each, [column][row] inside: the four
+// rows 4 g .. 4 g + 3 a lane owns are adjacent), the reflectors come in the same tiles (Vt) for the
+// first product and as Vr[r * 16 + i] for the second.
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 template <int NBLK>
-__device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr, const float* __restrict__ Vt, int64_t ldt,
-                                                   const float* __restrict__ T, int t_transposed, float* Cs, int64_t ldc,
-                                                   int nblocks) {
+__device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr, const float* __restrict__ Vt,
+                                                   const float* __restrict__ T, int t_transposed, float* Cs, int nblocks) {
     __shared__ float Wp[8][NB][NB];
     __shared__ float Ws[NB][NB];
     __shared__ float Wn[NB][NB];
@@ -433,8 +434,8 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr,
     const int c = lane & 15, g = lane >> 4;
     if (tid < NB * NB) Ts[tid >> 4][tid & 15] = T[tid];
 
-    float* Cl = Cs + (int64_t)c * ldc + 4 * g;               // this lane's column, its first row of block 0
-    const float* Vtl = Vt + (int64_t)c * ldt + 4 * g;        // reflector c, same rows
+    float* Cl = Cs + c * 16 + 4 * g;                         // this lane's column, its first row of tile 0
+    const float* Vtl = Vt + c * 16 + 4 * g;                  // reflector c, same rows
     const float* Vrl = Vr + (int64_t)c * NB + 4 * g;         // row c of a block, reflectors 4 g ..
     // Blocks past the end are clamped to the last one for every load (a valid address, no branch) and
     // take no part: their strip registers are zero and they are not stored.  All loads of a phase are
@@ -447,7 +448,7 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr,
 #pragma unroll
     for (int b = 0; b < NBLK; ++b) {
         const int blk = wave + 8 * b;
-        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(Cl + 16 * (blk < nblocks ? blk : last));
+        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(Cl + 256 * (blk < nblocks ? blk : last));
         const bool valid = blk < nblocks;
         cr[b] = f32x4_t{valid ? v[0] : 0.f, valid ? v[1] : 0.f, valid ? v[2] : 0.f, valid ? v[3] : 0.f};
     }
@@ -459,7 +460,7 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr,
 #pragma unroll
         for (int q = 0; q < GRP; ++q) {
             const int blk = wave + 8 * (grp * GRP + q);
-            va[grp & 1][q] = *reinterpret_cast<const f32x4_t*>(Vtl + 16 * (blk < nblocks ? blk : last));
+            va[grp & 1][q] = *reinterpret_cast<const f32x4_t*>(Vtl + 256 * (blk < nblocks ? blk : last));
         }
     };
     load_vt(0);
@@ -520,16 +521,16 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr,
             cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[1], bq[1], cr[b], 0, 0, 0);
             cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[2], bq[2], cr[b], 0, 0, 0);
             cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[3], bq[3], cr[b], 0, 0, 0);
-            if (blk < nblocks) *reinterpret_cast<f32x4_t*>(Cl + 16 * blk) = cr[b];
+            if (blk < nblocks) *reinterpret_cast<f32x4_t*>(Cl + 256 * blk) = cr[b];
         }
     }
 }
 
 template <int NBLK>
 __global__ __launch_bounds__(512)
-void reflect_strip_kernel(const float* __restrict__ Vr, const float* __restrict__ Vt, int64_t ldt,
-                          const float* __restrict__ T, int t_transposed, float* C, int64_t ldc, int nblocks) {
-    reflect_strip_body<NBLK>(Vr, Vt, ldt, T, t_transposed, C + (int64_t)blockIdx.x * NB * ldc, ldc, nblocks);
+void reflect_strip_kernel(const float* __restrict__ Vr, const float* __restrict__ Vt, const float* __restrict__ T,
+                          int t_transposed, float* C, int64_t strip_stride, int nblocks) {
+    reflect_strip_body<NBLK>(Vr, Vt, T, t_transposed, C + (int64_t)blockIdx.x * strip_stride, nblocks);
 }
 
 // One launch per QR step p.  The chain of panel factorisations (one workgroup each) is the
@@ -537,17 +538,16 @@ void reflect_strip_kernel(const float* __restrict__ Vr, const float* __restrict_
 //   workgroup 0        updates the 16 columns of panel p + 1, then factorises them;
 //   the next `wide`    update the remaining trailing columns of the matrix;
 //   the last `acc`     update all columns of the accumulated transposed orthogonal factor
-//                      X <- (I - V T^T V^T) X  (X starts as the identity, ends as Q^T; like the
-//                      matrix it is stored column-major, which makes the buffer Q in row-major).
+//                      X <- (I - V T^T V^T) X  (X starts as the identity, ends as Q^T).
 // Every strip reads only V_p, T_p and its own columns; panel p + 1 writes its own columns, the
 // other pair of reflector buffers and its own T, so the workgroups of one launch never touch the
 // same data.  Waves of workgroup 0 that the panel does not use leave after the strip.
 struct QrStepArgs {
     const float* Vr; const float* Vt;    // reflector block p in both layouts (see reflect_strip_body)
     const float* T;                      // its 16 x 16 triangle
-    float* C;                            // column-major, (row c0, column c0 + 16): panel p + 1 first
-    float* X;                            // column-major, (row c0, column 0) of the accumulator
-    int64_t ld, ldt;
+    float* C;                            // tile (row block of c0, column block of c0 + 16) of the matrix: panel p + 1 first
+    float* X;                            // tile (row block of c0, column block 0) of the accumulator
+    int64_t strip_stride;                // floats between the tiles of neighbouring column blocks
     int nblocks;                         // rows / 16 of step p
     int wide, acc;                       // strip counts
     float* Vr_next; float* Vt_next; float* Tnext; float* rdiag_next;   // outputs of panel p + 1
@@ -558,13 +558,25 @@ template <int NTHR, int R, int NBLK>
 __global__ __launch_bounds__(512)
 void qr_step_kernel(QrStepArgs a) {
     const int b = blockIdx.x;
-    float* Cs = b <= a.wide ? a.C + (int64_t)b * NB * a.ld : a.X + (int64_t)(b - 1 - a.wide) * NB * a.ld;
-    reflect_strip_body<NBLK>(a.Vr, a.Vt, a.ldt, a.T, 1, Cs, a.ld, a.nblocks);
+    float* Cs = b <= a.wide ? a.C + (int64_t)b * a.strip_stride : a.X + (int64_t)(b - 1 - a.wide) * a.strip_stride;
+    reflect_strip_body<NBLK>(a.Vr, a.Vt, a.T, 1, Cs, a.nblocks);
     if (b != 0 || a.m_next <= 0) return;
     __threadfence_block();
     __syncthreads();                     // the strip's stores are visible to the whole workgroup
     if (threadIdx.x >= NTHR) return;
-    qr_panel_body<NTHR, R>(a.C + NB, a.ld, a.Vr_next, a.Vt_next, a.ldt, a.Tnext, a.rdiag_next, a.m_next);   // 16 rows further down
+    qr_panel_body<NTHR, R>(a.C + 256, a.Vr_next, a.Vt_next, a.Tnext, a.rdiag_next, a.m_next);   // one tile (16 rows) further down
+}
+
+// zeroes what lies beyond n x n of the tiled matrix M (n_pad x n_pad) and sets the tiled X to the identity
+__global__ __launch_bounds__(256)
+void qr_prepare_kernel(float* M, float* X, int n, int n_pad) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;          // index into the tiled arrays
+    if (i >= (int64_t)n_pad * n_pad) return;
+    const int nbr = n_pad >> 4;
+    const int tile = (int)(i >> 8), in = (int)(i & 255);
+    const int r = (tile % nbr) * 16 + (in & 15), c = (tile / nbr) * 16 + (in >> 4);
+    if (r >= n || c >= n) M[i] = 0.f;
+    X[i] = r == c ? 1.f : 0.f;
 }
 
 __global__ __launch_bounds__(256)
@@ -804,10 +816,10 @@ void kappa_finish_kernel(const float* xa, const float* xi, int n, float* out) {
 }
 
 template <int NTHR>
-hipError_t launch_qr_panel(int rows_per_thread, float* Mp, int64_t ld, float* Vr, float* Vt, int64_t ldt, float* Tg,
-                           float* rdiag, int m, hipStream_t s) {
+hipError_t launch_qr_panel(int rows_per_thread, float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, int m,
+                           hipStream_t s) {
     switch (rows_per_thread) {
-#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((qr_panel_kernel<NTHR, RR>), dim3(1), dim3(NTHR), 0, s, Mp, ld, Vr, Vt, ldt, Tg, rdiag, m); break;
+#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((qr_panel_kernel<NTHR, RR>), dim3(1), dim3(NTHR), 0, s, Mp, Vr, Vt, Tg, rdiag, m); break;
         GELO_CASE(1) GELO_CASE(2) GELO_CASE(3) GELO_CASE(4) GELO_CASE(5)
         GELO_CASE(6) GELO_CASE(7) GELO_CASE(8) GELO_CASE(9) GELO_CASE(10)
 #undef GELO_CASE
@@ -852,18 +864,19 @@ hipError_t vt_c(const FactorWorkspace& ws, const float* V, const float* T, int t
 }
 
 // C (rows x cols, rows and cols multiples of 16) <- (I - V op(T) V^T) C with op(T) = T^T if t_transposed
-// C (column-major, rows x cols, both multiples of 16) <- (I - V op(T) V^T) C
-hipError_t apply_block_reflector(const float* Vr, const float* Vt, int64_t ldt, const float* T, int t_transposed,
-                                 float* C, int64_t ldc, int rows, int cols, hipStream_t s) {
+// C (tiled, rows x cols, both multiples of 16; C points at the first tile, strip_stride floats between column blocks)
+// <- (I - V op(T) V^T) C
+hipError_t apply_block_reflector(const float* Vr, const float* Vt, const float* T, int t_transposed,
+                                 float* C, int64_t strip_stride, int rows, int cols, hipStream_t s) {
     if (rows <= 0 || cols <= 0) return hipSuccess;
     if (rows % NB != 0 || cols % NB != 0) return hipErrorInvalidValue;
     const int nblocks = rows / NB;
     const dim3 grid(cols / NB), block(512);
     const int per_wave = (nblocks + 7) / 8;
-    if (per_wave <= 5) hipLaunchKernelGGL(reflect_strip_kernel<5>, grid, block, 0, s, Vr, Vt, ldt, T, t_transposed, C, ldc, nblocks);
-    else if (per_wave <= 10) hipLaunchKernelGGL(reflect_strip_kernel<10>, grid, block, 0, s, Vr, Vt, ldt, T, t_transposed, C, ldc, nblocks);
-    else if (per_wave <= 20) hipLaunchKernelGGL(reflect_strip_kernel<20>, grid, block, 0, s, Vr, Vt, ldt, T, t_transposed, C, ldc, nblocks);
-    else if (per_wave <= 40) hipLaunchKernelGGL(reflect_strip_kernel<40>, grid, block, 0, s, Vr, Vt, ldt, T, t_transposed, C, ldc, nblocks);
+    if (per_wave <= 5) hipLaunchKernelGGL(reflect_strip_kernel<5>, grid, block, 0, s, Vr, Vt, T, t_transposed, C, strip_stride, nblocks);
+    else if (per_wave <= 10) hipLaunchKernelGGL(reflect_strip_kernel<10>, grid, block, 0, s, Vr, Vt, T, t_transposed, C, strip_stride, nblocks);
+    else if (per_wave <= 20) hipLaunchKernelGGL(reflect_strip_kernel<20>, grid, block, 0, s, Vr, Vt, T, t_transposed, C, strip_stride, nblocks);
+    else if (per_wave <= 40) hipLaunchKernelGGL(reflect_strip_kernel<40>, grid, block, 0, s, Vr, Vt, T, t_transposed, C, strip_stride, nblocks);
     else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -972,33 +985,38 @@ hipError_t launch_qr_step(const QrStepArgs& a, hipStream_t s) {
 
 }  // namespace
 
-hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t s) {
+hipError_t householder_qr(const FactorWorkspace& ws, int n, hipStream_t s) {
     const int n_pad = ws.n_pad;
-    const int64_t ld = ws.ld, ldt = n_pad;
-    const int panels = n_pad / NB;
+    const int nbr = n_pad / NB;                               // tile rows (= tile columns)
+    const int64_t strip_stride = (int64_t)nbr * 256;
+    const int panels = nbr;
     // block reflector p is only needed while step p runs: two compact pairs of buffers alternate
     float* Vr[2] = {ws.Vc, ws.Vc + (int64_t)n_pad * NB};
     float* Vt[2] = {ws.Vc + 2 * (int64_t)n_pad * NB, ws.Vc + 3 * (int64_t)n_pad * NB};
-    GELO_TRY(set_identity(ws.X, ld, n_pad, s));
+    {
+        const int64_t elems = (int64_t)n_pad * n_pad;
+        hipLaunchKernelGGL(qr_prepare_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, s, ws.M, ws.X, n, n_pad);
+        GELO_TRY(hipGetLastError());
+    }
     // panel 0 on its own; then one launch per step: trailing update + accumulation of Q^T with block
     // reflector p, and in the same launch the factorisation of panel p + 1
     {
         const int m = n_pad;
-        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, ld, Vr[0], Vt[0], ldt, ws.Tmat, ws.rdiag, m, s));
-        else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M, ld, Vr[0], Vt[0], ldt, ws.Tmat, ws.rdiag, m, s));
+        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, Vr[0], Vt[0], ws.Tmat, ws.rdiag, m, s));
+        else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M, Vr[0], Vt[0], ws.Tmat, ws.rdiag, m, s));
     }
     for (int p = 0; p < panels; ++p) {
         const int c0 = p * NB, m = n_pad - c0;
         const int cols = n_pad - c0 - NB;
         QrStepArgs a;
         a.Vr = Vr[p & 1]; a.Vt = Vt[p & 1]; a.T = ws.Tmat + (int64_t)p * NB * NB;
-        a.X = ws.X + c0;
-        a.ld = ld; a.ldt = ldt; a.nblocks = m / NB; a.acc = n_pad / NB;
+        a.X = ws.X + (int64_t)p * 256;                        // tile (p, 0)
+        a.strip_stride = strip_stride; a.nblocks = m / NB; a.acc = nbr;
         if (cols <= 0) {                      // last block reflector: only the accumulator is left
-            GELO_TRY(apply_block_reflector(a.Vr, a.Vt, ldt, a.T, 1, a.X, ld, m, n_pad, s));
+            GELO_TRY(apply_block_reflector(a.Vr, a.Vt, a.T, 1, a.X, strip_stride, m, n_pad, s));
             break;
         }
-        a.C = ws.M + (int64_t)(c0 + NB) * ld + c0;
+        a.C = ws.M + (int64_t)(p + 1) * strip_stride + (int64_t)p * 256;      // tile (p, p + 1)
         a.wide = cols / NB - 1;
         a.Vr_next = Vr[(p + 1) & 1]; a.Vt_next = Vt[(p + 1) & 1];
         a.Tnext = ws.Tmat + (int64_t)(p + 1) * NB * NB; a.rdiag_next = ws.rdiag + c0 + NB;
@@ -1063,8 +1081,8 @@ hipError_t kappa_estimate(const float* A, const float* Ainv, int64_t lda, int n,
                           int iterations, hipStream_t s) {
     const int64_t ld = ws.ld;
     // transposes into the (now free) factorisation buffers
-    GELO_TRY(emit_matrix(A, lda, nullptr, n, ld, nullptr, nullptr, ws.M, nullptr, s));
-    GELO_TRY(emit_matrix(Ainv, lda, nullptr, n, ld, nullptr, nullptr, ws.X, nullptr, s));
+    GELO_TRY(emit_matrix(A, lda, 0, nullptr, n, ld, nullptr, nullptr, ws.M, nullptr, s));
+    GELO_TRY(emit_matrix(Ainv, lda, 0, nullptr, n, ld, nullptr, nullptr, ws.X, nullptr, s));
     const dim3 grid((n + 3) / 4), block(256);
     float* x = ws.vec;
     float* y = ws.vec + ld;

@@ -37,11 +37,19 @@ struct PhiloxStream {
     uint32_t key0, key1;            // seed low / high
     uint32_t c1, c2, c3;            // (stream << 8 | attempt), batch id low, batch id high
 };
-// out[r * ld + c] = scale * N(0,1) for r < rows, c < cols; element e = r*cols + c is output
-// e % 4 of Philox block e / 4 (counter word 0 = block index).  With `transposed` the same element
-// goes to out[c * ld + r] (column-major storage of the same matrix).
+// The QR works on 16 x 16 tiles: a tile is 256 contiguous floats ordered [column in tile][row in
+// tile], tiles are ordered column-block major; element (r, c) of a matrix with `tile_rows` tile
+// rows sits at the index below.  A wave that owns a tile in the accumulator layout of
+// v_mfma_f32_16x16x4_f32 (lane = 16 g + c holds rows 4 g .. 4 g + 3 of column c) then reads or
+// writes it as ONE contiguous kilobyte, 16 bytes per lane.
+__host__ __device__ inline int64_t qr_tile_index(int r, int c, int tile_rows) {
+    return ((int64_t)(c >> 4) * tile_rows + (r >> 4)) * 256 + (c & 15) * 16 + (r & 15);
+}
+// out = scale * N(0,1) for r < rows, c < cols; element e = r*cols + c is output e % 4 of Philox
+// block e / 4 (counter word 0 = block index).  tiled == 0: out[r * ld + c]; tiled != 0: the same
+// element goes to out[qr_tile_index(r, c, ld)] (ld = number of tile rows).
 hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale,
-                       int transposed, hipStream_t stream);
+                       int tiled, hipStream_t stream);
 // dst[r * ldd + c] += scale * src[r * lds + c] over an rows x cols block
 hipError_t axpy_matrix(float* dst, int64_t ldd, const float* src, int64_t lds, int rows, int cols,
                        float scale, hipStream_t stream);
@@ -56,7 +64,9 @@ hipError_t make_shields(const float* G, int64_t ldg, const float* gnorm, const f
 // Writes an n x n float matrix (src, optional per-column sign flip from `rdiag` < 0) into the
 // mixing buffers: dst32 / dst16 get the matrix, dstT32 / dstT16 its transpose (any may be null).
 // Every destination has `ldd` elements per row and its columns [n, ldd) are zero-filled.
-hipError_t emit_matrix(const float* src, int64_t lds, const float* rdiag, int n, int64_t ldd,
+// src_tiled == 0: src is row-major with pitch lds; src_tiled != 0: src holds the TRANSPOSE of the
+// matrix in 16 x 16 tiles with lds tile rows (what householder_qr leaves in ws.X).
+hipError_t emit_matrix(const float* src, int64_t lds, int src_tiled, const float* rdiag, int n, int64_t ldd,
                        float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16,
                        hipStream_t stream);
 // dense float copy out[r * cols + c] = (float) src[r * ld + c]
@@ -84,11 +94,11 @@ struct FactorWorkspace {
 size_t factor_workspace_bytes(int n);
 void factor_workspace_carve(void* base, int n, FactorWorkspace* ws);
 
-// ws.M holds an n_pad x n_pad matrix (rows/cols beyond n zero) in COLUMN-major order: element
-// (r, c) at ws.M[c * ld + r] (the trailing updates work on column strips, which are then
-// contiguous in memory).  On return ws.X holds, in the usual row-major order, the orthogonal
-// factor Q of its Householder QR (identity in the padding block), and ws.rdiag the diagonal of R.
-hipError_t householder_qr(const FactorWorkspace& ws, hipStream_t stream);
+// ws.M holds an n x n matrix in 16 x 16 tiles (qr_tile_index with n_pad / 16 tile rows; what lies
+// beyond n need not be initialised).  On return ws.X holds Q^T, the transpose of the orthogonal
+// factor of its Householder QR, in the same tiled layout (identity in the padding block), and
+// ws.rdiag the diagonal of R.
+hipError_t householder_qr(const FactorWorkspace& ws, int n, hipStream_t stream);
 // ws.M holds an n_pad x n_pad matrix with an identity block in the padding.  On return ws.X holds
 // its inverse (via row-pivoted LU), *ws.flag != 0 if a zero pivot was met.
 hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t stream);

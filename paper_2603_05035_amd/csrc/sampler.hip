@@ -39,7 +39,7 @@ __device__ __forceinline__ void box_muller(uint32_t wa, uint32_t wb, float* z0, 
 }
 
 __global__ __launch_bounds__(256)
-void fill_normal_kernel(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale, int transposed) {
+void fill_normal_kernel(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale, int tiled) {
     const int64_t total = (int64_t)rows * cols;
     const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (q * 4 >= total) return;
@@ -52,7 +52,7 @@ void fill_normal_kernel(float* out, int64_t ld, int rows, int cols, PhiloxStream
     int r = (int)(e / cols), c = (int)(e % cols);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-        if (e + t < total) out[transposed ? (int64_t)c * ld + r : (int64_t)r * ld + c] = scale * z[t];
+        if (e + t < total) out[tiled ? qr_tile_index(r, c, (int)ld) : (int64_t)r * ld + c] = scale * z[t];
         if (++c == cols) { c = 0; ++r; }
     }
 }
@@ -192,7 +192,7 @@ void make_shields_kernel(const float* G, int64_t ldg, const float* gnorm, const 
 // 32 x 32 tiles through LDS so that both the matrix and its transpose are written row-contiguously.
 // Grid covers ceil(ldd/32) x ceil(ldd/32) tiles; everything outside n x n is written as zero.
 __global__ __launch_bounds__(256)
-void emit_matrix_kernel(const float* src, int64_t lds, const float* rdiag, int n, int64_t ldd,
+void emit_matrix_kernel(const float* src, int64_t lds, int src_tiled, const float* rdiag, int n, int64_t ldd,
                         float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16) {
     __shared__ float tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
@@ -201,7 +201,7 @@ void emit_matrix_kernel(const float* src, int64_t lds, const float* rdiag, int n
         const int r = r0 + i, c = c0 + tx;
         float x = 0.f;
         if (r < n && c < n) {
-            x = src[(int64_t)r * lds + c];
+            x = src_tiled ? src[qr_tile_index(c, r, (int)lds)] : src[(int64_t)r * lds + c];
             if (rdiag != nullptr && rdiag[c] < 0.f) x = -x;
         }
         tile[i][tx] = x;
@@ -236,11 +236,11 @@ void export_dense_kernel(const void* src, int64_t ld, int rows, int cols, float*
 }  // namespace
 
 hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale,
-                       int transposed, hipStream_t stream) {
+                       int tiled, hipStream_t stream) {
     const int64_t quads = ((int64_t)rows * cols + 3) / 4;
     if (quads == 0) return hipSuccess;
     hipLaunchKernelGGL(fill_normal_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
-                       out, ld, rows, cols, ps, scale, transposed);
+                       out, ld, rows, cols, ps, scale, tiled);
     return hipGetLastError();
 }
 
@@ -278,11 +278,11 @@ hipError_t make_shields(const float* G, int64_t ldg, const float* gnorm, const f
     return hipGetLastError();
 }
 
-hipError_t emit_matrix(const float* src, int64_t lds, const float* rdiag, int n, int64_t ldd,
+hipError_t emit_matrix(const float* src, int64_t lds, int src_tiled, const float* rdiag, int n, int64_t ldd,
                        float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16, hipStream_t stream) {
     const int t = (int)((ldd + 31) / 32);
     hipLaunchKernelGGL(emit_matrix_kernel, dim3(t, t), dim3(256), 0, stream,
-                       src, lds, rdiag, n, ldd, dst32, dst16, dstT32, dstT16);
+                       src, lds, src_tiled, rdiag, n, ldd, dst32, dst16, dstT32, dstT16);
     return hipGetLastError();
 }
 
