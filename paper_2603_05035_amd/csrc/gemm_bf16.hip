@@ -584,11 +584,11 @@ void gemm_bf16_skinny_kernel(Bf16Args g) {
         b_off[ct] = C::A_BYTES + rl * 128 + chunk * 16 + (s16 & 3) * 8;
     }
 
-    f32x16_t acc[2];
+    f32x16_t acc2[2][2];
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[c][v] = 0.f;
+        for (int v = 0; v < 16; ++v) { acc2[c][0][v] = 0.f; acc2[c][1][v] = 0.f; }
 
 #pragma unroll
     for (int t = 0; t < C::DIST; ++t) if (t < T) issue(t);
@@ -599,20 +599,32 @@ void gemm_bf16_skinny_kernel(Bf16Args g) {
         __builtin_amdgcn_s_barrier();                          // tile t complete for all waves; stage (t-1) % STAGES is free
         if (t + C::DIST < T) issue(t + C::DIST);
         const uint8_t* st = lds + (t % C::STAGES) * C::STAGE_BYTES;
+        // all fragments of the K step first, then the MFMAs on two accumulators per column tile (short dependent chains)
+        bf16x8_t a_frag[4], b_frag[4][2];
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            const bf16x8_t a_frag = *reinterpret_cast<const bf16x8_t*>(st + a_frag_off + (((ks * 2 + grp) ^ a_sw) * 16));
+            a_frag[ks] = *reinterpret_cast<const bf16x8_t*>(st + a_frag_off + (((ks * 2 + grp) ^ a_sw) * 16));
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct) {
                 typedef dma::s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
                 const dma::s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * 128));
                 const dma::s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * 128 + 4 * 128));
                 const dma::s16x8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                acc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both), a_frag, acc[ct], 0, 0, 0);
+                b_frag[ks][ct] = __builtin_bit_cast(bf16x8_t, both);
             }
         }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+                acc2[ct][ks & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_frag[ks][ct], a_frag[ks], acc2[ct][ks & 1], 0, 0, 0);
     }
 
+    f32x16_t acc[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[c][v] = acc2[c][0][v] + acc2[c][1][v];
     // acc[ct][v] = C[row 32 wave + lane % 32][col ct*32 + 8 (v / 4) + 4 (lane / 32) + v % 4]
     constexpr int PITCH = 144;
     __builtin_amdgcn_s_barrier();
