@@ -1,14 +1,11 @@
-// Dense factorisations the trusted side needs to build a fresh mixing matrix
-// (Section 3.2 step 1.2; Table 3's "A-gen (QR)" step; Section 3.2.1 Mitigation 1):
-//   - blocked Householder QR with explicit Q (orthogonal A),
-//   - row-pivoted blocked LU and an explicit inverse (non-orthogonal A),
-//   - a kappa_2 estimate by power iteration (the "generate and verify" check).
-// Everything is float and deterministic: reductions run in a fixed order, no atomics.
+// Blocked Householder QR with explicit Q: the orthogonal mixing matrix the trusted side draws
+// for every batch (Section 3.2 step 1.2; Table 3's "A-gen (QR)" step), and the workspace shared
+// with the LU path.  Everything is float and deterministic: reductions run in a fixed order, no
+// atomics.
 //
-// Both factorisations use column panels of width 16.  A panel is factorised by ONE workgroup
-// that keeps its rows in registers (thread t owns rows t, t+NTHR, ...), so the per-column
-// reductions cost a couple of barriers and no memory traffic.  The rank-16 updates of the
-// trailing matrix are bandwidth-bound and run on the vector ALUs.
+// Column panels are 16 wide.  A panel is factorised by ONE workgroup that keeps its rows in
+// registers (thread t owns rows t, t+NTHR, ...), so the per-column reductions cost one barrier
+// and no memory traffic; the block reflectors are applied on the matrix cores.
 #include <type_traits>
 #include <utility>
 
@@ -24,14 +21,6 @@ __device__ __forceinline__ float wave_sum(float v) {
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
     return v;
 }
-
-template <int... Is, class F>
-__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-// compile-time loop: the body sees its index as a constant, so register arrays stay in registers
-template <int N, class F>
-__device__ __forceinline__ void static_for(F&& f) { static_for_impl(std::make_integer_sequence<int, N>{}, f); }
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_mov(float v) {
@@ -237,179 +226,6 @@ void qr_panel_kernel(float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, i
     qr_panel_body<NTHR, R>(Mp, Vr, Vt, Tg, rdiag, m);
 }
 
-// ------------------------------------------------------- skinny rank-16 kernels --
-// Both work on tiles of 128 rows x 64 columns with 128 threads: thread (ct, rt) owns 4 adjacent
-// columns (one 16-byte access per row) of the 16 rows rt, rt+8, ...
-constexpr int SK_COLS = 64;
-constexpr int SK_ROWS = 128;
-constexpr int SK_THREADS = 128;
-
-// Wpart[tile][i][col] = sum over the rows r of tile blockIdx.y of V[r][i] * C[r][col]
-__global__ __launch_bounds__(SK_THREADS)
-void vt_c_partial_kernel(const float* V, int64_t ldv, const float* C, int64_t ldc, int rows, int cols,
-                         float* Wpart, int64_t ldw) {
-    __shared__ __attribute__((aligned(16))) float Vs[SK_ROWS][NB];
-    __shared__ __attribute__((aligned(16))) float red[8][NB][SK_COLS];
-    const int tid = threadIdx.x;
-    const int r0 = blockIdx.y * SK_ROWS;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {                   // 128 rows x 4 chunks of 16 bytes
-        const int id = tid + t * SK_THREADS;
-        const int r = id >> 2, c4 = id & 3;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (r0 + r < rows) v = *reinterpret_cast<const float4*>(V + (int64_t)(r0 + r) * ldv + c4 * 4);
-        *reinterpret_cast<float4*>(&Vs[r][c4 * 4]) = v;
-    }
-    __syncthreads();
-    const int ct = tid & 15, rt = tid >> 4;
-    const int col = blockIdx.x * SK_COLS + ct * 4;
-    float acc[NB][4];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) { acc[i][0] = acc[i][1] = acc[i][2] = acc[i][3] = 0.f; }
-    if (col < cols) {
-        float4 c[16];
-#pragma unroll
-        for (int ii = 0; ii < 16; ++ii) {
-            const int r = r0 + rt + 8 * ii;
-            c[ii] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r < rows) c[ii] = *reinterpret_cast<const float4*>(C + (int64_t)r * ldc + col);
-        }
-#pragma unroll
-        for (int ii = 0; ii < 16; ++ii) {
-            const float* vs = Vs[rt + 8 * ii];
-#pragma unroll
-            for (int i4 = 0; i4 < NB / 4; ++i4) {
-                const float4 v = *reinterpret_cast<const float4*>(vs + i4 * 4);
-                const float vv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    acc[i4 * 4 + e][0] = fmaf(vv[e], c[ii].x, acc[i4 * 4 + e][0]);
-                    acc[i4 * 4 + e][1] = fmaf(vv[e], c[ii].y, acc[i4 * 4 + e][1]);
-                    acc[i4 * 4 + e][2] = fmaf(vv[e], c[ii].z, acc[i4 * 4 + e][2]);
-                    acc[i4 * 4 + e][3] = fmaf(vv[e], c[ii].w, acc[i4 * 4 + e][3]);
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < NB; ++i)
-        *reinterpret_cast<float4*>(&red[rt][i][ct * 4]) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
-    __syncthreads();
-    // 16 x 64 outputs of this tile, 8 per thread, each the sum of 8 partials in a fixed order
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const int id = tid + t * SK_THREADS;        // 0..255: (i, 4-column group)
-        const int i = id >> 4, cg = id & 15;
-        const int ocol = blockIdx.x * SK_COLS + cg * 4;
-        if (ocol < cols) {
-            float4 s = *reinterpret_cast<const float4*>(&red[0][i][cg * 4]);
-#pragma unroll
-            for (int g = 1; g < 8; ++g) {
-                const float4 q = *reinterpret_cast<const float4*>(&red[g][i][cg * 4]);
-                s.x += q.x; s.y += q.y; s.z += q.z; s.w += q.w;
-            }
-            *reinterpret_cast<float4*>(Wpart + ((int64_t)blockIdx.y * NB + i) * ldw + ocol) = s;
-        }
-    }
-}
-
-// W[0:16, strip] = op(T) * sum_tile Wpart[tile][0:16, strip] for the 64-column strip blockIdx.x;
-// tiles are added in index order; op(T) = T^T if t_transposed.
-__global__ __launch_bounds__(SK_THREADS)
-void reduce_apply_kernel(const float* Wpart, int tiles, int cols, int64_t ldw, const float* T, int t_transposed,
-                         float* W) {
-    __shared__ __attribute__((aligned(16))) float Wsum[NB][SK_COLS];
-    __shared__ float Ts[NB][NB];
-    const int tid = threadIdx.x;
-    if (tid < NB) {
-#pragma unroll
-        for (int c4 = 0; c4 < NB / 4; ++c4)
-            *reinterpret_cast<float4*>(&Ts[tid][c4 * 4]) = *reinterpret_cast<const float4*>(T + tid * NB + c4 * 4);
-    }
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const int id = tid + t * SK_THREADS;
-        const int i = id >> 4, cg = id & 15;
-        const int ocol = blockIdx.x * SK_COLS + cg * 4;
-        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (ocol < cols) {
-#pragma unroll 4
-            for (int tl = 0; tl < tiles; ++tl) {
-                const float4 q = *reinterpret_cast<const float4*>(Wpart + ((int64_t)tl * NB + i) * ldw + ocol);
-                s.x += q.x; s.y += q.y; s.z += q.z; s.w += q.w;
-            }
-        }
-        *reinterpret_cast<float4*>(&Wsum[i][cg * 4]) = s;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const int id = tid + t * SK_THREADS;
-        const int i = id >> 4, cg = id & 15;
-        const int ocol = blockIdx.x * SK_COLS + cg * 4;
-        if (ocol < cols) {
-            float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-            for (int k = 0; k < NB; ++k) {
-                const float tk = t_transposed ? Ts[k][i] : Ts[i][k];       // (T^T W)[i] or (T W)[i]
-                const float4 q = *reinterpret_cast<const float4*>(&Wsum[k][cg * 4]);
-                o.x = fmaf(tk, q.x, o.x); o.y = fmaf(tk, q.y, o.y); o.z = fmaf(tk, q.z, o.z); o.w = fmaf(tk, q.w, o.w);
-            }
-            *reinterpret_cast<float4*>(W + (int64_t)i * ldw + ocol) = o;
-        }
-    }
-}
-
-// C[r][col] -= sum_i L[r][i] * W[i][col]
-__global__ __launch_bounds__(SK_THREADS)
-void rank16_update_kernel(const float* L, int64_t ldl, const float* W, int64_t ldw, float* C, int64_t ldc,
-                          int rows, int cols) {
-    __shared__ __attribute__((aligned(16))) float Ls[SK_ROWS][NB];
-    const int tid = threadIdx.x;
-    const int r0 = blockIdx.y * SK_ROWS;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int id = tid + t * SK_THREADS;
-        const int r = id >> 2, c4 = id & 3;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (r0 + r < rows) v = *reinterpret_cast<const float4*>(L + (int64_t)(r0 + r) * ldl + c4 * 4);
-        *reinterpret_cast<float4*>(&Ls[r][c4 * 4]) = v;
-    }
-    __syncthreads();
-    const int ct = tid & 15, rt = tid >> 4;
-    const int col = blockIdx.x * SK_COLS + ct * 4;
-    if (col >= cols) return;
-    float4 w[NB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) w[i] = *reinterpret_cast<const float4*>(W + (int64_t)i * ldw + col);
-    float4 c[16];
-#pragma unroll
-    for (int ii = 0; ii < 16; ++ii) {
-        const int r = r0 + rt + 8 * ii;
-        c[ii] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (r < rows) c[ii] = *reinterpret_cast<const float4*>(C + (int64_t)r * ldc + col);
-    }
-#pragma unroll
-    for (int ii = 0; ii < 16; ++ii) {
-        const int r = r0 + rt + 8 * ii;
-        const float* ls = Ls[rt + 8 * ii];
-        float4 s = c[ii];
-#pragma unroll
-        for (int i4 = 0; i4 < NB / 4; ++i4) {
-            const float4 l = *reinterpret_cast<const float4*>(ls + i4 * 4);
-            const float lv[4] = {l.x, l.y, l.z, l.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                s.x = fmaf(-lv[e], w[i4 * 4 + e].x, s.x);
-                s.y = fmaf(-lv[e], w[i4 * 4 + e].y, s.y);
-                s.z = fmaf(-lv[e], w[i4 * 4 + e].z, s.z);
-                s.w = fmaf(-lv[e], w[i4 * 4 + e].w, s.w);
-            }
-        }
-        if (r < rows) *reinterpret_cast<float4*>(C + (int64_t)r * ldc + col) = s;
-    }
-}
-
 // ------------------------------------------------- fused block-reflector update --
 // C <- C - V op(T) V^T C for a 16-column strip of C per workgroup, in ONE pass over C: the strip
 // (m x 16, m a multiple of 16) lives in registers as 16 x 16 blocks in the accumulator layout of
@@ -594,227 +410,6 @@ void pad_matrix_kernel(float* M, int64_t ld, int n, int n_pad, int identity_bloc
     if (r >= n || c >= n) M[(int64_t)r * ld + c] = (identity_block && r == c) ? 1.f : 0.f;
 }
 
-// ------------------------------------------------------------------ LU panel --
-// Row-pivoted LU of the m x 16 panel at Mp, in place (unit-lower multipliers below the diagonal).
-// piv[j] = panel-local row swapped with row j (first largest |value|).  *flag is set on a zero pivot.
-template <int NTHR, int R>
-__global__ __launch_bounds__(NTHR)
-void lu_panel_kernel(float* Mp, int64_t ld, int m, int* piv, int row_offset, int* flag) {
-    constexpr int NW = NTHR / 64;
-    __shared__ float red_v[NW];
-    __shared__ int red_i[NW];
-    __shared__ float rowbuf[2][NB];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    float P[R][NB];
-#pragma unroll
-    for (int i = 0; i < R; ++i) {
-        const int r = tid + i * NTHR;
-        if (r < m) {
-#pragma unroll
-            for (int c4 = 0; c4 < NB / 4; ++c4) {
-                const float4 v = *reinterpret_cast<const float4*>(Mp + (int64_t)r * ld + c4 * 4);
-                P[i][c4 * 4 + 0] = v.x; P[i][c4 * 4 + 1] = v.y; P[i][c4 * 4 + 2] = v.z; P[i][c4 * 4 + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < NB; ++c) P[i][c] = 0.f;
-        }
-    }
-
-    // rolled loop with the columns rotated by one per step (current column = slot 0), as in the QR panel
-#pragma unroll 1
-    for (int j = 0; j < NB; ++j) {
-        // pivot search over rows >= j: largest |value|, smallest row on ties
-        float bv = -1.f;
-        int bi = 0x7fffffff;
-#pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const int r = tid + i * NTHR;
-            if (r >= j && r < m) {
-                const float a = fabsf(P[i][0]);
-                if (a > bv) { bv = a; bi = r; }       // rows visited in increasing order per thread
-            }
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            const float ov = __shfl_xor(bv, off, 64);
-            const int oi = __shfl_xor(bi, off, 64);
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-        }
-        if (lane == 0) { red_v[wave] = bv; red_i[wave] = bi; }
-        __syncthreads();
-        bv = red_v[0]; bi = red_i[0];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) {
-            const float ov = red_v[w];
-            const int oi = red_i[w];
-            if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-        }
-        const int pr = bi < m ? bi : j;
-        // exchange rows j and pr through LDS
-        if (tid == j) {
-#pragma unroll
-            for (int c = 0; c < NB; ++c) rowbuf[0][c] = P[0][c];
-        }
-#pragma unroll
-        for (int i = 0; i < R; ++i) {
-            if (tid + i * NTHR == pr) {
-#pragma unroll
-                for (int c = 0; c < NB; ++c) rowbuf[1][c] = P[i][c];
-            }
-        }
-        __syncthreads();
-        if (pr != j) {
-            if (tid == j) {
-#pragma unroll
-                for (int c = 0; c < NB; ++c) P[0][c] = rowbuf[1][c];
-            }
-#pragma unroll
-            for (int i = 0; i < R; ++i) {
-                if (tid + i * NTHR == pr) {
-#pragma unroll
-                    for (int c = 0; c < NB; ++c) P[i][c] = rowbuf[0][c];
-                }
-            }
-        }
-        float prow[NB];
-#pragma unroll
-        for (int c = 0; c < NB; ++c) prow[c] = rowbuf[1][c];
-        if (tid == 0) piv[j] = row_offset + pr;
-        const float pivot = prow[0];
-        const int live = NB - j;
-        if (pivot != 0.f) {
-            const float inv = 1.0f / pivot;
-#pragma unroll
-            for (int i = 0; i < R; ++i) {
-                const int r = tid + i * NTHR;
-                if (r > j && r < m) {
-                    const float l = P[i][0] * inv;
-                    P[i][0] = l;
-#pragma unroll
-                    for (int c = 1; c < NB; ++c) if (c < live) P[i][c] = fmaf(-l, prow[c], P[i][c]);
-                }
-            }
-        } else if (tid == 0) {
-            *flag = 1;
-        }
-#pragma unroll
-        for (int i = 0; i < R; ++i) {
-            const float first = P[i][0];
-#pragma unroll
-            for (int c = 0; c < NB - 1; ++c) P[i][c] = P[i][c + 1];
-            P[i][NB - 1] = first;
-        }
-        __syncthreads();
-    }
-
-#pragma unroll
-    for (int i = 0; i < R; ++i) {
-        const int r = tid + i * NTHR;
-        if (r >= m) continue;
-        float* mp = Mp + (int64_t)r * ld;
-#pragma unroll
-        for (int c4 = 0; c4 < NB / 4; ++c4)
-            *reinterpret_cast<float4*>(mp + c4 * 4) = make_float4(P[i][c4 * 4], P[i][c4 * 4 + 1], P[i][c4 * 4 + 2], P[i][c4 * 4 + 3]);
-    }
-}
-
-// applies the 16 row interchanges of one panel (global rows row0 + j <-> piv[j]) to columns [cbeg, cend)
-__global__ __launch_bounds__(256)
-void swap_rows_kernel(float* M, int64_t ld, int row0, const int* piv, int cbeg, int cend) {
-    const int c = cbeg + blockIdx.x * 256 + threadIdx.x;
-    if (c >= cend) return;
-#pragma unroll 1
-    for (int j = 0; j < NB; ++j) {
-        const int p = piv[j];
-        if (p != row0 + j) {
-            const float a = M[(int64_t)(row0 + j) * ld + c];
-            const float b = M[(int64_t)p * ld + c];
-            M[(int64_t)(row0 + j) * ld + c] = b;
-            M[(int64_t)p * ld + c] = a;
-        }
-    }
-}
-
-// B[0:16, col] <- T^-1 B[0:16, col] for the 16 x 16 triangle T (row stride ldt):
-// UPPER = false: unit lower triangle; UPPER = true: upper triangle with its diagonal.
-template <bool UPPER>
-__global__ __launch_bounds__(256)
-void tri_solve_kernel(const float* T, int64_t ldt, float* B, int64_t ldb, int cols) {
-    __shared__ float Ts[NB][NB];
-    const int tid = threadIdx.x;
-    Ts[tid >> 4][tid & 15] = T[(int64_t)(tid >> 4) * ldt + (tid & 15)];
-    __syncthreads();
-    const int col = blockIdx.x * 256 + tid;
-    if (col >= cols) return;
-    float x[NB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) x[i] = B[(int64_t)i * ldb + col];
-    if (!UPPER) {
-#pragma unroll
-        for (int i = 1; i < NB; ++i)
-#pragma unroll
-            for (int k = 0; k < i; ++k) x[i] = fmaf(-Ts[i][k], x[k], x[i]);
-    } else {
-#pragma unroll
-        for (int i = NB - 1; i >= 0; --i) {
-#pragma unroll
-            for (int k = i + 1; k < NB; ++k) x[i] = fmaf(-Ts[i][k], x[k], x[i]);
-            x[i] /= Ts[i][i];
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < NB; ++i) B[(int64_t)i * ldb + col] = x[i];
-}
-
-// ------------------------------------------------------------ power iteration --
-// y[row] = (M[row, 0:n] . x) / ||x||, one wave per row
-__global__ __launch_bounds__(256)
-void matvec_unit_kernel(const float* M, int64_t ld, int n, const float* x, float* y) {
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (row >= n) return;
-    float ss = 0.f, dot = 0.f;
-    const float* mr = M + (int64_t)row * ld;
-    for (int c = lane; c < n; c += 64) {
-        const float xv = x[c];
-        ss = fmaf(xv, xv, ss);
-        dot = fmaf(mr[c], xv, dot);
-    }
-    ss = wave_sum(ss);
-    dot = wave_sum(dot);
-    if (lane == 0) y[row] = dot * rsqrtf(ss);
-}
-
-__global__ __launch_bounds__(256)
-void start_vector_kernel(float* x, int n) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) {
-        uint32_t h = (uint32_t)i * 2654435761u + 0x9E3779B9u;   // fixed pseudo-random signs and sizes
-        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
-        x[i] = ((h & 1u) ? 1.f : -1.f) * (0.5f + (float)((h >> 8) & 0xFFFF) * (1.0f / 65536.0f));
-    }
-}
-
-// out[0] = ||xa|| * ||xi||  (sigma_max estimate times 1/sigma_min estimate); out[1], out[2] the factors
-__global__ __launch_bounds__(1024)
-void kappa_finish_kernel(const float* xa, const float* xi, int n, float* out) {
-    __shared__ float ra[16], ri[16];
-    const int tid = threadIdx.x;
-    float a = 0.f, b = 0.f;
-    for (int i = tid; i < n; i += 1024) { a = fmaf(xa[i], xa[i], a); b = fmaf(xi[i], xi[i], b); }
-    a = wave_sum(a); b = wave_sum(b);
-    if ((tid & 63) == 0) { ra[tid >> 6] = a; ri[tid >> 6] = b; }
-    __syncthreads();
-    if (tid == 0) {
-        float sa = 0.f, sb = 0.f;
-        for (int w = 0; w < 16; ++w) { sa += ra[w]; sb += ri[w]; }
-        out[1] = sqrtf(sa); out[2] = sqrtf(sb);
-        out[0] = sqrtf(sa) * sqrtf(sb);
-    }
-}
-
 template <int NTHR>
 hipError_t launch_qr_panel(int rows_per_thread, float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, int m,
                            hipStream_t s) {
@@ -828,42 +423,6 @@ hipError_t launch_qr_panel(int rows_per_thread, float* Mp, float* Vr, float* Vt,
     return hipGetLastError();
 }
 
-template <int NTHR>
-hipError_t launch_lu_panel(int rows_per_thread, float* Mp, int64_t ld, int m, int* piv, int row_offset,
-                           int* flag, hipStream_t s) {
-    switch (rows_per_thread) {
-#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((lu_panel_kernel<NTHR, RR>), dim3(1), dim3(NTHR), 0, s, Mp, ld, m, piv, row_offset, flag); break;
-        GELO_CASE(1) GELO_CASE(2) GELO_CASE(3) GELO_CASE(4) GELO_CASE(5)
-#undef GELO_CASE
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-}
-
-hipError_t rank16_update(const float* L, int64_t ldl, const float* W, int64_t ldw, float* C, int64_t ldc,
-                         int rows, int cols, hipStream_t s) {
-    if (rows <= 0 || cols <= 0) return hipSuccess;
-    hipLaunchKernelGGL(rank16_update_kernel, dim3((cols + SK_COLS - 1) / SK_COLS, (rows + SK_ROWS - 1) / SK_ROWS),
-                       dim3(SK_THREADS), 0, s, L, ldl, W, ldw, C, ldc, rows, cols);
-    return hipGetLastError();
-}
-
-// W (16 x cols, row stride ws.ld) = op(T) V^T C over `rows` rows; op(T) = T^T if t_transposed
-hipError_t vt_c(const FactorWorkspace& ws, const float* V, const float* T, int t_transposed, const float* C,
-                int64_t ldc, int rows, int cols, hipStream_t s) {
-    if (rows <= 0 || cols <= 0) return hipSuccess;
-    const int chunks = (rows + SK_ROWS - 1) / SK_ROWS;
-    if (chunks > ws.wpart_chunks) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(vt_c_partial_kernel, dim3((cols + SK_COLS - 1) / SK_COLS, chunks), dim3(SK_THREADS), 0, s,
-                       V, ws.ld, C, ldc, rows, cols, ws.Wpart, ws.ld);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(reduce_apply_kernel, dim3((cols + SK_COLS - 1) / SK_COLS), dim3(SK_THREADS), 0, s,
-                       ws.Wpart, chunks, cols, ws.ld, T, t_transposed, ws.W);
-    return hipGetLastError();
-}
-
-// C (rows x cols, rows and cols multiples of 16) <- (I - V op(T) V^T) C with op(T) = T^T if t_transposed
 // C (tiled, rows x cols, both multiples of 16; C points at the first tile, strip_stride floats between column blocks)
 // <- (I - V op(T) V^T) C
 hipError_t apply_block_reflector(const float* Vr, const float* Vt, const float* T, int t_transposed,
@@ -887,31 +446,27 @@ hipError_t apply_block_reflector(const float* Vr, const float* Vt, const float* 
 
 size_t factor_workspace_bytes(int n) {
     const int64_t n_pad = round_up(n, NB), ld = round_up(n, 64);
-    const int64_t chunks = (n_pad + SK_ROWS - 1) / SK_ROWS;
-    int64_t floats = 3 * n_pad * ld + n_pad * NB + chunks * NB * ld + NB * ld + n_pad + 4 * ld + 64;
-    return (size_t)floats * sizeof(float) + (size_t)(n_pad + ld + 128) * sizeof(int) + 8192;
+    const int64_t floats = 3 * n_pad * ld + n_pad * NB + 2 * n_pad * kLuBlock + n_pad + 6 * ld + 64;
+    return (size_t)floats * sizeof(float) + (size_t)(n_pad + 256) * sizeof(int) + 8192;
 }
 
 void factor_workspace_carve(void* base, int n, FactorWorkspace* ws) {
     const int64_t n_pad = round_up(n, NB), ld = round_up(n, 64);
-    const int64_t chunks = (n_pad + SK_ROWS - 1) / SK_ROWS;
     float* p = (float*)base;
     auto take = [&](int64_t count) { float* q = p; p += round_up(count, 64); return q; };
     ws->M = take(n_pad * ld);
     ws->X = take(n_pad * ld);
     ws->Vc = take(n_pad * ld);
     ws->Tmat = take(n_pad * NB);
-    ws->Wpart = take(chunks * NB * ld);
-    ws->W = take(NB * ld);
+    ws->Dinv = take(2 * n_pad * kLuBlock);
     ws->rdiag = take(n_pad);
-    ws->vec = take(4 * ld);
+    ws->vec = take(6 * ld);
     ws->scalars = take(16);
-    ws->piv = (int*)take(n_pad);
+    ws->perm = (int*)take(n_pad);
+    ws->gat = (int*)take(128);
     ws->flag = (int*)take(16);
-    ws->counters = (int*)take(ld / SK_COLS + 1);
     ws->n_pad = (int)n_pad;
     ws->ld = ld;
-    ws->wpart_chunks = (int)chunks;
 }
 
 __global__ void zero_ints_kernel(int* p, int count) {
@@ -1024,87 +579,6 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, hipStream_t s) {
         GELO_TRY(launch_qr_step(a, s));
     }
     return hipSuccess;
-}
-
-hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t s) {
-    const int n_pad = ws.n_pad;
-    const int64_t ld = ws.ld;
-    const int panels = n_pad / NB;
-    GELO_TRY(zero_ints(ws.flag, 1, s));
-    GELO_TRY(set_identity(ws.X, ld, n_pad, s));
-    for (int p = 0; p < panels; ++p) {
-        const int c0 = p * NB, m = n_pad - c0;
-        const int64_t off = (int64_t)c0 * ld + c0;
-        if (m <= 256 * 5) GELO_TRY(launch_lu_panel<256>((m + 255) / 256, ws.M + off, ld, m, ws.piv + c0, c0, ws.flag, s));
-        else GELO_TRY(launch_lu_panel<1024>((m + 1023) / 1024, ws.M + off, ld, m, ws.piv + c0, c0, ws.flag, s));
-        // the same interchanges on the rest of the matrix and on the right-hand side (X ends up as P)
-        if (c0 > 0) {
-            hipLaunchKernelGGL(swap_rows_kernel, dim3((c0 + 255) / 256), dim3(256), 0, s, ws.M, ld, c0, ws.piv + c0, 0, c0);
-            GELO_TRY(hipGetLastError());
-        }
-        const int cols = n_pad - c0 - NB;
-        if (cols > 0) {
-            hipLaunchKernelGGL(swap_rows_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, ws.M, ld, c0, ws.piv + c0, c0 + NB, n_pad);
-            GELO_TRY(hipGetLastError());
-        }
-        hipLaunchKernelGGL(swap_rows_kernel, dim3((n_pad + 255) / 256), dim3(256), 0, s, ws.X, ld, c0, ws.piv + c0, 0, n_pad);
-        GELO_TRY(hipGetLastError());
-        if (cols > 0) {
-            float* U12 = ws.M + off + NB;
-            hipLaunchKernelGGL(tri_solve_kernel<false>, dim3((cols + 255) / 256), dim3(256), 0, s, ws.M + off, ld, U12, ld, cols);
-            GELO_TRY(hipGetLastError());
-            GELO_TRY(rank16_update(ws.M + off + (int64_t)NB * ld, ld, U12, ld, U12 + (int64_t)NB * ld, ld, m - NB, cols, s));
-        }
-    }
-    // L Y = P
-    for (int p = 0; p < panels; ++p) {
-        const int c0 = p * NB;
-        const int64_t off = (int64_t)c0 * ld + c0;
-        float* Xb = ws.X + (int64_t)c0 * ld;
-        hipLaunchKernelGGL(tri_solve_kernel<false>, dim3((n_pad + 255) / 256), dim3(256), 0, s, ws.M + off, ld, Xb, ld, n_pad);
-        GELO_TRY(hipGetLastError());
-        GELO_TRY(rank16_update(ws.M + off + (int64_t)NB * ld, ld, Xb, ld, Xb + (int64_t)NB * ld, ld, n_pad - c0 - NB, n_pad, s));
-    }
-    // U X = Y
-    for (int p = panels - 1; p >= 0; --p) {
-        const int c0 = p * NB;
-        const int64_t off = (int64_t)c0 * ld + c0;
-        float* Xb = ws.X + (int64_t)c0 * ld;
-        hipLaunchKernelGGL(tri_solve_kernel<true>, dim3((n_pad + 255) / 256), dim3(256), 0, s, ws.M + off, ld, Xb, ld, n_pad);
-        GELO_TRY(hipGetLastError());
-        GELO_TRY(rank16_update(ws.M + c0, ld, Xb, ld, ws.X, ld, c0, n_pad, s));
-    }
-    return hipSuccess;
-}
-
-hipError_t kappa_estimate(const float* A, const float* Ainv, int64_t lda, int n, const FactorWorkspace& ws,
-                          int iterations, hipStream_t s) {
-    const int64_t ld = ws.ld;
-    // transposes into the (now free) factorisation buffers
-    GELO_TRY(emit_matrix(A, lda, 0, nullptr, n, ld, nullptr, nullptr, ws.M, nullptr, s));
-    GELO_TRY(emit_matrix(Ainv, lda, 0, nullptr, n, ld, nullptr, nullptr, ws.X, nullptr, s));
-    const dim3 grid((n + 3) / 4), block(256);
-    float* x = ws.vec;
-    float* y = ws.vec + ld;
-    float* xa = ws.vec + 2 * ld;
-    float* xi = ws.vec + 3 * ld;
-    for (int op = 0; op < 2; ++op) {
-        const float* Mf = op == 0 ? A : Ainv;            // forward operator
-        const float* Mt = op == 0 ? ws.M : ws.X;         // its transpose
-        const int64_t ldf = lda;
-        float* last = op == 0 ? xa : xi;
-        hipLaunchKernelGGL(start_vector_kernel, dim3((n + 255) / 256), dim3(256), 0, s, x, n);
-        GELO_TRY(hipGetLastError());
-        for (int it = 0; it < iterations; ++it) {
-            hipLaunchKernelGGL(matvec_unit_kernel, grid, block, 0, s, Mf, ldf, n, x, y);
-            GELO_TRY(hipGetLastError());
-            float* dst = (it + 1 == iterations) ? last : x;
-            hipLaunchKernelGGL(matvec_unit_kernel, grid, block, 0, s, Mt, ld, n, y, dst);
-            GELO_TRY(hipGetLastError());
-        }
-    }
-    hipLaunchKernelGGL(kappa_finish_kernel, dim3(1), dim3(1024), 0, s, xa, xi, n, ws.scalars);
-    return hipGetLastError();
 }
 
 }  // namespace gelo

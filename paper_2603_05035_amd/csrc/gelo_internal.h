@@ -6,12 +6,24 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace gelo {
 
 constexpr int kPanel = 16;          // column-panel width of the QR / LU factorisations
-constexpr int kMaxN = 5120;         // 1024 threads x 5 register-resident rows in the panel kernels
+constexpr int kMaxN = 5120;         // 512 threads x 10 register-resident rows in the panel kernels
+constexpr int kLuBlock = 128;       // outer block width of the LU: trailing updates are GEMMs with K = 128
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+// compile-time loop: the body sees its index as a constant, so register arrays stay in registers
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(std::make_integer_sequence<int, N>{}, f); }
 
 // ---------------------------------------------------------------- GEMMs ----
 // C[M x N] = A[M x K] * B[K x N], row-major.  B is given as two row segments:
@@ -26,11 +38,13 @@ struct GemmOperands {
     void* C;        int64_t ldc;
     int M, N, K;
     bool a_zero_padded = false;   // A is readable and zero in columns [K, round_up(K, 64))
+    bool subtract = false;        // float only: C <- C - A * B instead of C <- A * B
 };
 hipError_t gemm_bf16(const GemmOperands& g, hipStream_t stream);
 hipError_t gemm_f32(const GemmOperands& g, hipStream_t stream);
 hipError_t gemm_bf16_init();        // one-time kernel attribute set-up (large dynamic LDS)
 hipError_t gemm_f32_init();
+hipError_t lu_init();
 
 // --------------------------------------------------------------- sampler ---
 struct PhiloxStream {
@@ -80,16 +94,14 @@ struct FactorWorkspace {
     float* X;        // the result being accumulated (Q, or A^-1)
     float* Vc;       // QR: two alternating pairs of compact reflector blocks (n_pad x 16 and 16 x n_pad)
     float* Tmat;     // per panel: the 16 x 16 triangle T of the block reflector I - V T V^T
-    float* Wpart;    // partial products of the skinny reductions
-    float* W;        // kPanel x ld reduced products
+    float* Dinv;     // LU: inverses of the diagonal blocks of L, then of U (pitch kLuBlock, n_pad rows each)
     float* rdiag;    // n_pad: diagonal of R
-    float* vec;      // 4 * ld floats for the power iterations
-    int*   piv;      // n_pad pivot rows
+    float* vec;      // 6 * ld floats for the power iterations
+    int*   perm;     // LU: perm[i] = row of the input that the interchanges brought to row i
+    int*   gat;      // LU: two alternating lists of 32 (destination, source) row pairs, one per panel
     int*   flag;     // singular-pivot flag
-    int*   counters; // one arrival counter per 64-column strip (zero between kernels)
     float* scalars;  // [0] kappa estimate, [1] sigma_max^2, [2] 1/sigma_min^2
     int n_pad; int64_t ld;
-    int wpart_chunks;   // row chunks Wpart can hold
 };
 size_t factor_workspace_bytes(int n);
 void factor_workspace_carve(void* base, int n, FactorWorkspace* ws);

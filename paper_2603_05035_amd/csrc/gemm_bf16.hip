@@ -744,6 +744,7 @@ hipError_t launch_dma(const GemmOperands& o, hipStream_t stream) {
 // Tiny M (decode-shaped batches) takes 128 x 128 with 4 waves so that N alone can spread the work.
 hipError_t gemm_bf16(const GemmOperands& o, hipStream_t stream) {
     if (o.M <= 0 || o.N <= 0 || o.K <= 0) return hipSuccess;
+    if (o.subtract) return hipErrorInvalidValue;       // float only
     if ((int64_t)o.M * o.lda >= (int64_t)1 << 31) return hipErrorInvalidValue;   // the generic kernel keeps 32-bit element offsets into A
     if (o.M > 128 && o.N >= 8 && (o.a_zero_padded || o.K % dma::BKS == 0)) {
         constexpr int kCus = 256;

@@ -1,6 +1,8 @@
 // float GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32), used by the
 // single-precision GELO chain (Section 3.2, eqs. 1-3): C[M x N] = A[M x K] * B[K x N],
-// all row-major, B optionally split into two row segments ([H ; S]).
+// all row-major, B optionally split into two row segments ([H ; S]); optionally C <- C - A * B.
+// A tile reads all of its B columns before it stores, so with M <= 128 the product may
+// overwrite B in place (C == B0, K == M): the LU path's multiplications by a diagonal-block inverse.
 //
 // A workgroup of 4 waves owns a 128 x 128 tile and walks K in steps of 16
 // through double-buffered LDS; a wave owns 64 x 64 as 2 x 2 accumulators.
@@ -27,6 +29,7 @@ struct F32Args {
     float* C;        int64_t ldc;
     int M, N, K;
     int tiles_m, tiles_n;
+    int subtract;              // C <- C - A B (the LU's trailing and substitution updates)
 };
 
 __global__ __launch_bounds__(NT)
@@ -136,7 +139,10 @@ void gemm_f32_kernel(F32Args g) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = m0 + wm * 64 + mt * 32 + 8 * (v >> 2) + 4 * grp + (v & 3);
-                    if (row < g.M) g.C[(int64_t)row * g.ldc + col] = acc[mt][nt][v];
+                    if (row < g.M) {
+                        float* cp = g.C + (int64_t)row * g.ldc + col;
+                        *cp = g.subtract ? *cp - acc[mt][nt][v] : acc[mt][nt][v];
+                    }
                 }
             }
         }
@@ -156,6 +162,7 @@ hipError_t gemm_f32(const GemmOperands& o, hipStream_t stream) {
     a.M = o.M; a.N = o.N; a.K = o.K;
     a.tiles_m = (o.M + BM - 1) / BM;
     a.tiles_n = (o.N + BN - 1) / BN;
+    a.subtract = o.subtract ? 1 : 0;
     hipLaunchKernelGGL(gemm_f32_kernel, dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
     return hipGetLastError();
 }
