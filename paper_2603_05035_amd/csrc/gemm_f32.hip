@@ -2,7 +2,8 @@
 // single-precision GELO chain (Section 3.2, eqs. 1-3): C[M x N] = A[M x K] * B[K x N],
 // all row-major, B optionally split into two row segments ([H ; S]); optionally C <- C - A * B.
 // A tile reads all of its B columns before it stores, so with M <= 128 the product may
-// overwrite B in place (C == B0, K == M): the LU path's multiplications by a diagonal-block inverse.
+// overwrite B in place (C == B0, K == M): the LU path's multiplications by a diagonal-block inverse
+// (those shapes take the short kernel at the end of this file, which has the same property).
 //
 // A workgroup of 4 waves owns a 128 x 128 tile and walks K in steps of 16
 // through double-buffered LDS; a wave owns 64 x 64 as 2 x 2 accumulators.
@@ -148,9 +149,88 @@ void gemm_f32_kernel(F32Args g) {
         }
 }
 
+// M <= 128 and K <= 128 (K a multiple of 16): the LU path's multiplications by the inverse of a
+// diagonal block.  One 128 x 128 tile per 128 columns would leave most of the chip idle and each
+// tile bound by the float MFMA rate of its one CU, so the tiles here are 128 x 32 (four times as
+// many workgroups, a wave owns 32 x 32), and with so few K steps both panels of the tile are
+// fetched at once (all loads in flight together) and stored to LDS behind ONE barrier.
+constexpr int SN = 32;             // tile width
+constexpr int KP = 132;            // LDS pitch of the A panel, floats (conflict-free as A_PITCH is)
+constexpr int SP = SN + 4;         // LDS pitch of the B panel
+constexpr size_t kShortLds = ((size_t)BM * KP + (size_t)BM * SP) * sizeof(float);
+
+__global__ __launch_bounds__(NT)
+void gemm_f32_short_kernel(F32Args g) {
+    extern __shared__ __attribute__((aligned(16))) float panels[];
+    float* As = panels;                 // [row][k]
+    float* Bs = panels + BM * KP;       // [k][col]
+    const int n0 = blockIdx.x * SN;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 31, grp = lane >> 5;
+    const int kc = g.K >> 2;            // 16-byte chunks per A row
+
+    f32x4_t a_st[16], b_st[4];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int id = tid + i * NT;
+        const int r = id / kc, c = id - r * kc;
+        const int row = r < g.M ? r : g.M - 1;
+        f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+        if (r < BM) v = *reinterpret_cast<const f32x4_t*>(g.A + (int64_t)row * g.lda + c * 4);
+        a_st[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = tid + i * NT;
+        const int r = id >> 3, c = id & 7;
+        const int gn = n0 + c * 4;
+        f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+        if (r < g.K && gn < g.N) v = *reinterpret_cast<const f32x4_t*>(g.B0 + (int64_t)r * g.ldb0 + gn);
+        b_st[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int id = tid + i * NT;
+        const int r = id / kc, c = id - r * kc;
+        if (r < BM) *reinterpret_cast<f32x4_t*>(&As[r * KP + c * 4]) = a_st[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int id = tid + i * NT;
+        *reinterpret_cast<f32x4_t*>(&Bs[(id >> 3) * SP + (id & 7) * 4]) = b_st[i];
+    }
+    __syncthreads();
+
+    f32x16_t acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const int k_steps = g.K >> 3;
+    for (int ks = 0; ks < k_steps; ++ks) {
+        const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(&As[(wave * 32 + j) * KP + ks * 8 + grp * 4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[e], Bs[(ks * 8 + grp * 4 + e) * SP + j], acc, 0, 0, 0);
+    }
+    const int col = n0 + j;
+    if (col < g.N) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = wave * 32 + 8 * (v >> 2) + 4 * grp + (v & 3);
+            if (row < g.M) {
+                float* cp = g.C + (int64_t)row * g.ldc + col;
+                *cp = g.subtract ? *cp - acc[v] : acc[v];
+            }
+        }
+    }
+}
+
 }  // namespace
 
-hipError_t gemm_f32_init() { return hipSuccess; }
+hipError_t gemm_f32_init() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_f32_short_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kShortLds);
+}
 
 hipError_t gemm_f32(const GemmOperands& o, hipStream_t stream) {
     if (o.M <= 0 || o.N <= 0 || o.K <= 0) return hipSuccess;
@@ -163,7 +243,10 @@ hipError_t gemm_f32(const GemmOperands& o, hipStream_t stream) {
     a.tiles_m = (o.M + BM - 1) / BM;
     a.tiles_n = (o.N + BN - 1) / BN;
     a.subtract = o.subtract ? 1 : 0;
-    hipLaunchKernelGGL(gemm_f32_kernel, dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
+    if (o.M <= BM && o.K <= 128 && o.K % 16 == 0 && o.K0 >= o.K)
+        hipLaunchKernelGGL(gemm_f32_short_kernel, dim3((o.N + SN - 1) / SN), dim3(NT), kShortLds, stream, a);
+    else
+        hipLaunchKernelGGL(gemm_f32_kernel, dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
     return hipGetLastError();
 }
 

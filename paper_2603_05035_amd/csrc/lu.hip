@@ -46,7 +46,6 @@ __device__ __forceinline__ void lu_panel_body(float* Mp, int64_t ld, int m, int 
     __shared__ unsigned long long keys[NW];
     __shared__ __attribute__((aligned(16))) float prow[NB];
     __shared__ int qlist[NB];
-    __shared__ int top_s[NB], far_pos_s[NB], far_row_s[NB];
     __shared__ int gd[32], gs[32];
     __shared__ int pos_of[kMaxN];
 
@@ -142,36 +141,33 @@ __device__ __forceinline__ void lu_panel_body(float* Mp, int64_t ld, int m, int 
     }
     if (tid < 32) { gd[tid] = -1; gs[tid] = -1; }
     __syncthreads();
-    if (tid == 0) {
-        // top_s[t]: the row now at position t < 16; rows that left the top sit at far_pos_s (always
-        // rows that started in the top 16); every other row is still where it started
-        int nf = 0;
-        for (int t = 0; t < NB; ++t) top_s[t] = t;
-        for (int j = 0; j < NB; ++j) {
-            const int q = qlist[j];
-            int pq = -1;
-            for (int t = j; t < NB; ++t) if (top_s[t] == q) pq = t;
-            if (pq < 0) for (int f = 0; f < nf; ++f) if (far_row_s[f] == q) pq = far_pos_s[f];
-            if (pq < 0) pq = q;
-            const int w = top_s[j];
-            top_s[j] = q;
+    if (wave == 0) {
+        // The 16 interchanges replayed by one wave, all state in registers: lane t < 16 carries top = the row
+        // now at position t; rows that left the top 16 (always rows that started there) sit at far positions,
+        // one (fpos, frow) pair per lane f < nf; every other row is still where it started.
+        int top = lane, fpos = -1, frow = -1, nf = 0;
+        const int qv = qlist[lane & 15];
+        static_for<NB>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            const int q = __builtin_amdgcn_readlane(qv, j);
+            const unsigned long long mt = __ballot(lane >= j && lane < NB && top == q);
+            const unsigned long long mf = __ballot(lane < nf && frow == q);
+            int pq = q;                                    // position of the pivot row before this interchange
+            if (mt) pq = __ffsll(mt) - 1;
+            else if (mf) pq = __shfl(fpos, __ffsll(mf) - 1, 64);
+            const int w = __builtin_amdgcn_readlane(top, j);
+            if (lane == j) top = q;
             if (pq < NB) {
-                top_s[pq] = pq == j ? q : w;
+                if (lane == pq && pq != j) top = w;
             } else {
-                int f = 0;
-                while (f < nf && far_pos_s[f] != pq) ++f;
-                if (f == nf) ++nf;
-                far_pos_s[f] = pq; far_row_s[f] = w;
+                const unsigned long long mp = __ballot(lane < nf && fpos == pq);
+                const int f = mp ? __ffsll(mp) - 1 : nf;
+                nf += mp ? 0 : 1;
+                if (lane == f) { fpos = pq; frow = w; }
             }
-        }
-        for (int t = 0; t < NB; ++t) {
-            pos_of[top_s[t]] = t;
-            gd[t] = row_offset + t; gs[t] = row_offset + top_s[t];
-        }
-        for (int f = 0; f < nf; ++f) {
-            pos_of[far_row_s[f]] = far_pos_s[f];
-            gd[NB + f] = row_offset + far_pos_s[f]; gs[NB + f] = row_offset + far_row_s[f];
-        }
+        });
+        if (lane < NB) { pos_of[top] = lane; gd[lane] = row_offset + lane; gs[lane] = row_offset + top; }
+        if (lane < nf) { pos_of[frow] = fpos; gd[NB + lane] = row_offset + fpos; gs[NB + lane] = row_offset + frow; }
     }
     __syncthreads();
     int pv = 0;
@@ -338,14 +334,20 @@ void lu_step_kernel(LuStepArgs a) {
 template <bool UPPER>
 __device__ __forceinline__ void tri_inverse_body(const float* T, int64_t ldt, int w, float* out, float* Ts, float* Xl) {
     const int tid = threadIdx.x;
-    for (int i = 0; i < BW; ++i) {
-        float v = i == tid ? 1.f : 0.f;
-        if (i < w && tid < w) {
-            const bool keep = UPPER ? tid >= i : tid < i;
-            const float t = T[(int64_t)i * ldt + tid];
-            v = keep ? t : v;
+#pragma unroll 1
+    for (int i0 = 0; i0 < BW; i0 += NB) {                  // 16 rows of loads in flight
+        float v[NB];
+#pragma unroll
+        for (int ii = 0; ii < NB; ++ii) {
+            const int i = i0 + ii;
+            v[ii] = (i < w && tid < w) ? T[(int64_t)i * ldt + tid] : 0.f;
         }
-        Ts[i * BW + tid] = v;
+#pragma unroll
+        for (int ii = 0; ii < NB; ++ii) {
+            const int i = i0 + ii;
+            const bool keep = i < w && tid < w && (UPPER ? tid >= i : tid < i);
+            Ts[i * BW + tid] = keep ? v[ii] : (i == tid ? 1.f : 0.f);
+        }
     }
     __syncthreads();
     constexpr int NBLK = BW / NB;
