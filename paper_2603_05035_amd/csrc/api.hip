@@ -18,7 +18,7 @@ using namespace gelo;
 
 namespace {
 constexpr float kConditionedBeta = 0.25f;
-constexpr int kKappaIterations = 64;
+constexpr int kKappaSteps = 20;          // Lanczos steps of the condition estimate
 constexpr uint32_t kStreamMixing = 0, kStreamShield = 1, kStreamPerturb = 2;
 }
 
@@ -276,7 +276,7 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
             GELO_HIP(ctx, pad_matrix(ws.M, ld, n, ws.n_pad, 1, s));
             GELO_HIP(ctx, lu_inverse(ws, s));
             GELO_HIP(ctx, emit_matrix(ws.X, ld, 0, nullptr, n, ldk, m->Ainv32, m->Ainv16, nullptr, nullptr, s));
-            GELO_HIP(ctx, kappa_estimate(m->A32, m->Ainv32, ldk, n, ws, kKappaIterations, s));
+            GELO_HIP(ctx, kappa_estimate(m->A32, m->Ainv32, ldk, n, ws, kKappaSteps, s));
             GELO_HIP(ctx, hipMemcpyAsync(m->stat + 1, ws.scalars, sizeof(float), hipMemcpyDeviceToDevice, s));
             if (kind == GELO_GAUSSIAN) {
                 // the one host synchronisation of the library: accept or redraw

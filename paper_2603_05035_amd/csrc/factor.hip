@@ -446,7 +446,7 @@ hipError_t apply_block_reflector(const float* Vr, const float* Vt, const float* 
 
 size_t factor_workspace_bytes(int n) {
     const int64_t n_pad = round_up(n, NB), ld = round_up(n, 64);
-    const int64_t floats = 3 * n_pad * ld + n_pad * NB + 2 * n_pad * kLuBlock + n_pad + 6 * ld + 64;
+    const int64_t floats = 3 * n_pad * ld + n_pad * NB + 2 * n_pad * kLuBlock + n_pad + 8 * ld + 256 + 64;
     return (size_t)floats * sizeof(float) + (size_t)(n_pad + 256) * sizeof(int) + 8192;
 }
 
@@ -460,7 +460,8 @@ void factor_workspace_carve(void* base, int n, FactorWorkspace* ws) {
     ws->Tmat = take(n_pad * NB);
     ws->Dinv = take(2 * n_pad * kLuBlock);
     ws->rdiag = take(n_pad);
-    ws->vec = take(6 * ld);
+    ws->vec = take(8 * ld);
+    ws->tri = take(128);
     ws->scalars = take(16);
     ws->perm = (int*)take(n_pad);
     ws->gat = (int*)take(128);

@@ -96,11 +96,12 @@ struct FactorWorkspace {
     float* Tmat;     // per panel: the 16 x 16 triangle T of the block reflector I - V T V^T
     float* Dinv;     // LU: inverses of the diagonal blocks of L, then of U (pitch kLuBlock, n_pad rows each)
     float* rdiag;    // n_pad: diagonal of R
-    float* vec;      // 6 * ld floats for the power iterations
+    float* vec;      // 8 * ld floats: the Lanczos vectors of the condition estimate
+    float* tri;      // its tridiagonal coefficients (2 operators x (alpha, beta) x 32)
     int*   perm;     // LU: perm[i] = row of the input that the interchanges brought to row i
     int*   gat;      // LU: two alternating lists of 32 (destination, source) row pairs, one per panel
     int*   flag;     // singular-pivot flag
-    float* scalars;  // [0] kappa estimate, [1] sigma_max^2, [2] 1/sigma_min^2
+    float* scalars;  // [0] kappa estimate, [1] sigma_max, [2] 1 / sigma_min
     int n_pad; int64_t ld;
 };
 size_t factor_workspace_bytes(int n);
@@ -114,10 +115,11 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, hipStream_t stream);
 // ws.M holds an n_pad x n_pad matrix with an identity block in the padding.  On return ws.X holds
 // its inverse (via row-pivoted LU), *ws.flag != 0 if a zero pivot was met.
 hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t stream);
-// kappa_2 estimate of the n x n matrix A (lda) with inverse Ainv by power iteration on A^T A and
-// Ainv Ainv^T; uses ws.M / ws.X as scratch for the two transposes; result in ws.scalars[0].
+// kappa_2 estimate of the n x n matrix A (lda) with inverse Ainv: sigma_max of both by `steps`
+// (at most 32) Lanczos steps on A^T A and Ainv^T Ainv; uses ws.M / ws.X as scratch for the two
+// transposes; result in ws.scalars[0].
 hipError_t kappa_estimate(const float* A, const float* Ainv, int64_t lda, int n, const FactorWorkspace& ws,
-                          int iterations, hipStream_t stream);
+                          int steps, hipStream_t stream);
 hipError_t set_identity(float* X, int64_t ld, int n_pad, hipStream_t stream);
 hipError_t zero_ints(int* p, int count, hipStream_t stream);
 // zero rows/cols [n, n_pad) of M; optionally put ones on that part of the diagonal

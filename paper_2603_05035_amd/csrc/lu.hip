@@ -1,4 +1,4 @@
-// Row-pivoted blocked LU, the explicit inverse and the kappa_2 estimate behind the non-orthogonal
+// Row-pivoted blocked LU, the explicit inverse and the kappa_2 estimate (Lanczos) behind the non-orthogonal
 // mixing matrices (Section 3.2.1, Mitigation 1: a well-conditioned non-orthogonal A, generated and
 // verified; Section 3.2 eq. 3 needs A^-1 explicitly so that un-mixing is one GEMM).
 // Everything is float and deterministic: reductions run in a fixed order, no atomics.
@@ -456,9 +456,14 @@ void iota_kernel(int* p, int count) {
     if (i < count) p[i] = i;
 }
 
-// ------------------------------------------------------------ power iteration --
-// Two matrix-vector products per launch, one wave per row: rows [0, n) give ya = Ma xa / ||xa||,
-// rows [n, 2n) give yb = Mb xb / ||xb||.
+// ------------------------------------------------------------------ Lanczos --
+// sigma_max of a matrix M from a few steps of the Lanczos recurrence on M^T M (no
+// reorthogonalisation: the largest Ritz value converges first and never overshoots).  The two
+// operators the condition number needs, A and A^-1, share every launch.
+constexpr int kLanczosMax = 32;      // coefficient slots per operator
+
+// Two matrix-vector products per launch, one wave per row: rows [0, n) give ya = Ma xa,
+// rows [n, 2n) give yb = Mb xb.
 __global__ __launch_bounds__(256)
 void matvec_pair_kernel(const float* Ma, int64_t lda, const float* xa, float* ya,
                         const float* Mb, int64_t ldb, const float* xb, float* yb, int n) {
@@ -469,44 +474,115 @@ void matvec_pair_kernel(const float* Ma, int64_t lda, const float* xa, float* ya
     row -= second ? n : 0;
     const float* mr = second ? Mb + (int64_t)row * ldb : Ma + (int64_t)row * lda;
     const float* x = second ? xb : xa;
-    float ss = 0.f, dot = 0.f;
-    for (int c = lane; c < n; c += 64) {
-        const float xv = x[c];
-        ss = fmaf(xv, xv, ss);
-        dot = fmaf(mr[c], xv, dot);
-    }
-    ss = wave_sum(ss);
+    float dot = 0.f;
+    for (int c = lane; c < n; c += 64) dot = fmaf(mr[c], x[c], dot);
     dot = wave_sum(dot);
-    if (lane == 0) (second ? yb : ya)[row] = dot * rsqrtf(ss);
+    if (lane == 0) (second ? yb : ya)[row] = dot;
 }
 
-__global__ __launch_bounds__(256)
-void start_vector_kernel(float* xa, float* xb, int n) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) {
-        uint32_t h = (uint32_t)i * 2654435761u + 0x9E3779B9u;   // fixed pseudo-random signs and sizes
-        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
-        const float v = ((h & 1u) ? 1.f : -1.f) * (0.5f + (float)((h >> 8) & 0xFFFF) * (1.0f / 65536.0f));
-        xa[i] = v; xb[i] = v;
-    }
-}
-
-// out[0] = ||xa|| * ||xi||  (sigma_max estimate times 1/sigma_min estimate); out[1], out[2] the factors
-__global__ __launch_bounds__(1024)
-void kappa_finish_kernel(const float* xa, const float* xi, int n, float* out) {
-    __shared__ float ra[16], ri[16];
-    const int tid = threadIdx.x;
-    float a = 0.f, b = 0.f;
-    for (int i = tid; i < n; i += 1024) { a = fmaf(xa[i], xa[i], a); b = fmaf(xi[i], xi[i], b); }
-    a = wave_sum(a); b = wave_sum(b);
-    if ((tid & 63) == 0) { ra[tid >> 6] = a; ri[tid >> 6] = b; }
+// sum over the 1024 threads of a workgroup, the same value in every thread, fixed order
+__device__ __forceinline__ float block_sum_1024(float v, float* red) {
+    v = wave_sum(v);
+    __syncthreads();                                   // red may still be read from the previous call
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    if (tid == 0) {
-        float sa = 0.f, sb = 0.f;
-        for (int w = 0; w < 16; ++w) { sa += ra[w]; sb += ri[w]; }
-        out[1] = sqrtf(sa); out[2] = sqrtf(sb);
-        out[0] = sqrtf(sa) * sqrtf(sb);
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) s += red[w];
+    return s;
+}
+
+constexpr int kVecPerThread = kMaxN / 1024;            // 5
+
+// Workgroup o (0: A, 1: A^-1) owns the vectors at vec + o * 4 * ld: v, v_prev, y, w.
+// step < 0: v = a fixed pseudo-random unit vector, v_prev = 0.
+// step >= 0: alpha = w . v, r = w - alpha v - beta_prev v_prev, beta = |r|, v_prev = v, v = r / beta;
+//            tri[o][0][step] = alpha, tri[o][1][step] = beta.
+__global__ __launch_bounds__(1024)
+void lanczos_vector_kernel(float* vec, int64_t ld, int n, float* tri, int step) {
+    __shared__ float red[16];
+    const int tid = threadIdx.x, o = blockIdx.x;
+    float* v = vec + (int64_t)o * 4 * ld;
+    float* vp = v + ld;
+    const float* w = v + 3 * ld;
+    float* tr = tri + o * 2 * kLanczosMax;
+    float x[kVecPerThread], xp[kVecPerThread], r[kVecPerThread];
+    if (step < 0) {
+        float ss = 0.f;
+#pragma unroll
+        for (int k = 0; k < kVecPerThread; ++k) {
+            const int i = tid + 1024 * k;
+            uint32_t h = (uint32_t)i * 2654435761u + 0x9E3779B9u;   // fixed pseudo-random signs and sizes
+            h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+            x[k] = i < n ? ((h & 1u) ? 1.f : -1.f) * (0.5f + (float)((h >> 8) & 0xFFFF) * (1.0f / 65536.0f)) : 0.f;
+            ss = fmaf(x[k], x[k], ss);
+        }
+        const float inv = rsqrtf(block_sum_1024(ss, red));
+#pragma unroll
+        for (int k = 0; k < kVecPerThread; ++k) {
+            const int i = tid + 1024 * k;
+            if (i < n) { v[i] = x[k] * inv; vp[i] = 0.f; }
+        }
+        return;
     }
+    float dot = 0.f;
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; ++k) {
+        const int i = tid + 1024 * k;
+        x[k] = i < n ? v[i] : 0.f;
+        xp[k] = i < n ? vp[i] : 0.f;
+        r[k] = i < n ? w[i] : 0.f;
+        dot = fmaf(r[k], x[k], dot);
+    }
+    const float alpha = block_sum_1024(dot, red);
+    const float beta_prev = step > 0 ? tr[kLanczosMax + step - 1] : 0.f;
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; ++k) {
+        r[k] = fmaf(-beta_prev, xp[k], fmaf(-alpha, x[k], r[k]));
+        ss = fmaf(r[k], r[k], ss);
+    }
+    const float beta = sqrtf(block_sum_1024(ss, red));
+    const float inv = beta > 0.f ? 1.0f / beta : 0.f;
+#pragma unroll
+    for (int k = 0; k < kVecPerThread; ++k) {
+        const int i = tid + 1024 * k;
+        if (i < n) { vp[i] = x[k]; v[i] = r[k] * inv; }
+    }
+    if (tid == 0) { tr[step] = alpha; tr[kLanczosMax + step] = beta; }
+}
+
+// Largest eigenvalue of the symmetric tridiagonal matrix (alpha[0..k), beta[0..k-1)) by bisection on
+// the Sturm count; out[0] = sqrt(lambda_A lambda_Ainv) = the kappa_2 estimate, out[1], out[2] its factors.
+__global__ __launch_bounds__(64)
+void lanczos_finish_kernel(const float* tri, int k, float* out) {
+    __shared__ float sig[2];
+    const int o = threadIdx.x;
+    if (o < 2) {
+        const float* al = tri + o * 2 * kLanczosMax;
+        const float* be = al + kLanczosMax;
+        float hi = 0.f;
+        for (int i = 0; i < k; ++i) {
+            const float g = fabsf(al[i]) + (i > 0 ? fabsf(be[i - 1]) : 0.f) + (i + 1 < k ? fabsf(be[i]) : 0.f);
+            hi = fmaxf(hi, g);
+        }
+        float lo = 0.f;
+        for (int it = 0; it < 48; ++it) {
+            const float mid = 0.5f * (lo + hi);
+            int below = 0;                              // eigenvalues below mid
+            float d = 1.f;
+            for (int i = 0; i < k; ++i) {
+                const float b2 = i > 0 ? be[i - 1] * be[i - 1] : 0.f;
+                d = al[i] - mid - b2 / d;
+                if (fabsf(d) < 1e-30f) d = -1e-30f;
+                below += d < 0.f;
+            }
+            if (below == k) hi = mid; else lo = mid;
+        }
+        sig[o] = sqrtf(0.5f * (lo + hi));
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { out[1] = sig[0]; out[2] = sig[1]; out[0] = sig[0] * sig[1]; }
 }
 
 #define GELO_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
@@ -647,26 +723,28 @@ hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t s) {
 }
 
 hipError_t kappa_estimate(const float* A, const float* Ainv, int64_t lda, int n, const FactorWorkspace& ws,
-                          int iterations, hipStream_t s) {
+                          int steps, hipStream_t s) {
     const int64_t ld = ws.ld;
+    if (steps < 1 || steps > kLanczosMax) return hipErrorInvalidValue;
+    if (steps > n) steps = n;
     // transposes into the (now free) factorisation buffers
     GELO_TRY(emit_matrix(A, lda, 0, nullptr, n, ld, nullptr, nullptr, ws.M, nullptr, s));
     GELO_TRY(emit_matrix(Ainv, lda, 0, nullptr, n, ld, nullptr, nullptr, ws.X, nullptr, s));
     const dim3 grid((2 * n + 3) / 4), block(256);
-    float* xa = ws.vec;            float* ya = ws.vec + ld;
-    float* xi = ws.vec + 2 * ld;   float* yi = ws.vec + 3 * ld;
-    float* la = ws.vec + 4 * ld;   float* li = ws.vec + 5 * ld;
-    hipLaunchKernelGGL(start_vector_kernel, dim3((n + 255) / 256), dim3(256), 0, s, xa, xi, n);
+    float* va = ws.vec;            float* ya = va + 2 * ld;   float* wa = va + 3 * ld;
+    float* vi = ws.vec + 4 * ld;   float* yi = vi + 2 * ld;   float* wi = vi + 3 * ld;
+    hipLaunchKernelGGL(lanczos_vector_kernel, dim3(2), dim3(1024), 0, s, ws.vec, ld, n, ws.tri, -1);
     GELO_TRY(hipGetLastError());
-    // x <- A^T (A x) and x <- Ainv^T (Ainv x), both in the same launches, vectors normalised on the way in
-    for (int it = 0; it < iterations; ++it) {
-        hipLaunchKernelGGL(matvec_pair_kernel, grid, block, 0, s, A, lda, xa, ya, Ainv, lda, xi, yi, n);
+    for (int j = 0; j < steps; ++j) {
+        // w = M^T (M v) for M = A and M = Ainv, then one step of the recurrence for both
+        hipLaunchKernelGGL(matvec_pair_kernel, grid, block, 0, s, A, lda, va, ya, Ainv, lda, vi, yi, n);
         GELO_TRY(hipGetLastError());
-        const bool last = it + 1 == iterations;
-        hipLaunchKernelGGL(matvec_pair_kernel, grid, block, 0, s, ws.M, ld, ya, last ? la : xa, ws.X, ld, yi, last ? li : xi, n);
+        hipLaunchKernelGGL(matvec_pair_kernel, grid, block, 0, s, ws.M, ld, ya, wa, ws.X, ld, yi, wi, n);
+        GELO_TRY(hipGetLastError());
+        hipLaunchKernelGGL(lanczos_vector_kernel, dim3(2), dim3(1024), 0, s, ws.vec, ld, n, ws.tri, j);
         GELO_TRY(hipGetLastError());
     }
-    hipLaunchKernelGGL(kappa_finish_kernel, dim3(1), dim3(1024), 0, s, la, li, n, ws.scalars);
+    hipLaunchKernelGGL(lanczos_finish_kernel, dim3(1), dim3(64), 0, s, ws.tri, steps, ws.scalars);
     return hipGetLastError();
 }
 
