@@ -9,9 +9,9 @@
 // factorises panel i + 1 right behind the update of its own chunk, so the chain of panels is the
 // critical path and nothing else.  The row interchanges of a panel never run one after another
 // through memory: the panel writes them as ONE gather list (at most 32 rows change place), which
-// the next launch applies to all other columns in one round trip.  After a block, its two diagonal
-// triangles are inverted (one workgroup each); U12 = L11^-1 U12 and the trailing update are float
-// GEMMs with K = 128.  The inverse then is two block substitutions (GEMMs again, the right-hand
+// the next launch applies to all other columns in one round trip.  The inverses of the block's two
+// diagonal triangles grow by one block row / column per launch beside the panel chain; after the
+// block, U12 = L11^-1 U12 and the trailing update are float GEMMs with K = 128.  The inverse then is two block substitutions (GEMMs again, the right-hand
 // side of the forward one kept triangular) and one column permutation.
 #include "gelo_internal.h"
 
@@ -50,6 +50,7 @@ __device__ __forceinline__ void lu_panel_body(float* Mp, int64_t ld, int m, int 
     __shared__ int pos_of[kMaxN];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t prow_addr = (uint32_t)(size_t)prow;       // its LDS byte address
     float P[R][NB];
     unsigned used = 0;                       // bit i: register row i is absent or already a pivot row
 #pragma unroll
@@ -96,18 +97,19 @@ __device__ __forceinline__ void lu_panel_body(float* Mp, int64_t ld, int m, int 
         const int q = none ? 0 : (int)(0xFFFFFFFFu - (unsigned)(best & 0xFFFFFFFFull));     // the pivot row
         const int q_slot = q / NTHR, q_tid = q % NTHR;
         if (tid == q_tid) {
-            // the pivot row's columns j..15 (all the update reads) go to LDS.  The empty asm hides that the
-            // stored values are loads of P: the compiler would otherwise merge the R stores into one whose
-            // address is picked at run time, and an array indexed that way stays in scratch memory.
+            // the pivot row's columns j..15 (all the update reads) go to LDS.  The stores are written as
+            // instructions: left to the compiler, the R alternatives are merged into one store whose source
+            // is picked at run time, and an array indexed that way stays in scratch memory.
             static_for<R>([&](auto ic) {
                 constexpr int i = decltype(ic)::value;
                 if (i == q_slot) {
-#pragma unroll
-                    for (int c = j; c < NB; ++c) {
-                        float v = P[i][c];
-                        asm volatile("" : "+v"(v));
-                        prow[c] = v;
-                    }
+                    static_for<NB - j>([&](auto cc) {
+                        constexpr int c = j + decltype(cc)::value;
+                        const float val = P[i][c];
+                        const uint32_t addr = prow_addr;
+                        asm volatile("ds_write_b32 %0, %1 offset:%2" :: "v"(addr), "v"(val), "n"(c * 4) : "memory");
+                    });
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 }
             });
             used |= 1u << q_slot;
@@ -147,8 +149,8 @@ __device__ __forceinline__ void lu_panel_body(float* Mp, int64_t ld, int m, int 
         // one (fpos, frow) pair per lane f < nf; every other row is still where it started.
         int top = lane, fpos = -1, frow = -1, nf = 0;
         const int qv = qlist[lane & 15];
-        static_for<NB>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
             const int q = __builtin_amdgcn_readlane(qv, j);
             const unsigned long long mt = __ballot(lane >= j && lane < NB && top == q);
             const unsigned long long mf = __ballot(lane < nf && frow == q);
@@ -165,7 +167,7 @@ __device__ __forceinline__ void lu_panel_body(float* Mp, int64_t ld, int m, int 
                 nf += mp ? 0 : 1;
                 if (lane == f) { fpos = pq; frow = w; }
             }
-        });
+        }
         if (lane < NB) { pos_of[top] = lane; gd[lane] = row_offset + lane; gs[lane] = row_offset + top; }
         if (lane < nf) { pos_of[frow] = fpos; gd[NB + lane] = row_offset + fpos; gs[NB + lane] = row_offset + frow; }
     }
@@ -202,29 +204,52 @@ void lu_panel_kernel(float* Mp, int64_t ld, int m, int row_offset, int* gat, int
 // A values are the 16 bytes L[row][4 g .. 4 g + 3].
 __device__ __forceinline__ void lu_chunk_body(float* M, int64_t ld, const int* gat, int pc, int col0, int n_pad) {
     __shared__ float L11[NB][NB + 1];
+    __shared__ float X0[NB][NB];          // the chunk's top block after the interchanges
     __shared__ float Us[NB][NB];
     __shared__ int cg[64];
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int cc = lane & 15, g = lane >> 4;
+    // nothing below the panel's top block moves any more: L11 and the first rows of L21 are fetched
+    // together with the interchange list
+    float l11 = 0.f;
     if (tid < 64) cg[tid] = gat[tid];
+    if (tid < NB * NB) l11 = M[(int64_t)(pc + (tid >> 4)) * ld + pc + (tid & 15)];
+    const int nblk = (n_pad - pc) / NB - 1;
+    constexpr int UN = 4;                                 // blocks in flight per wave
+    f32x4_t a4[2][UN], acc[2][UN];
+    auto rowbase = [&](int b) { return pc + NB + NB * (b < nblk ? b : nblk - 1); };     // clamped: a valid address, no branch
+    auto load_l = [&](int buf, int b0) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+            a4[buf][u] = *reinterpret_cast<const f32x4_t*>(M + (int64_t)(rowbase(b0 + 8 * u) + cc) * ld + pc + 4 * g);
+    };
+    auto load_c = [&](int buf, int b0) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const float* cp = M + (int64_t)(rowbase(b0 + 8 * u) + 4 * g) * ld + col0 + cc;
+            acc[buf][u] = f32x4_t{cp[0], cp[ld], cp[2 * ld], cp[3 * ld]};
+        }
+    };
+    load_l(0, wave);
     __syncthreads();
     {
         const int e = tid >> 4, c = tid & 15;             // 32 entries x 16 columns
         const int src = cg[32 + e], dst = cg[e];
         float v = 0.f;
         if (src >= 0) v = M[(int64_t)src * ld + col0 + c];
+        if (tid < NB * NB) L11[tid >> 4][tid & 15] = l11;
         __syncthreads();                                  // every row is read before any is overwritten
         if (dst >= 0) M[(int64_t)dst * ld + col0 + c] = v;
+        if (e < NB) X0[e][c] = v;                         // entries 0..15 are the rows pc .. pc + 15
     }
     __threadfence_block();
     __syncthreads();
-    if (tid < NB * NB) L11[tid >> 4][tid & 15] = M[(int64_t)(pc + (tid >> 4)) * ld + pc + (tid & 15)];
-    float x[NB];
+    load_c(0, wave);                                      // in flight while the first 16 lanes solve the top block
     if (tid < NB) {
+        float x[NB];
 #pragma unroll
-        for (int i = 0; i < NB; ++i) x[i] = M[(int64_t)(pc + i) * ld + col0 + tid];
-    }
-    __syncthreads();
-    if (tid < NB) {
+        for (int i = 0; i < NB; ++i) x[i] = X0[i][tid];
 #pragma unroll
         for (int i = 1; i < NB; ++i)
 #pragma unroll
@@ -236,35 +261,33 @@ __device__ __forceinline__ void lu_chunk_body(float* M, int64_t ld, const int* g
         }
     }
     __syncthreads();
-    const int lane = tid & 63, wave = tid >> 6;
-    const int cc = lane & 15, g = lane >> 4;
     float bq[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) bq[e] = -Us[4 * g + e][cc];
-    const int nblk = (n_pad - pc) / NB - 1;
-    constexpr int UN = 4;                                 // blocks in flight per wave
-    for (int b0 = wave; b0 < nblk; b0 += 8 * UN) {
-        f32x4_t a4[UN], acc[UN];
+    auto update = [&](auto bufc, int b0) {
+        constexpr int buf = decltype(bufc)::value;
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int b = b0 + 8 * u;
-            const int rb = pc + NB + NB * (b < nblk ? b : nblk - 1);      // clamped: a valid address, no branch
-            a4[u] = *reinterpret_cast<const f32x4_t*>(M + (int64_t)(rb + cc) * ld + pc + 4 * g);
-            const float* cp = M + (int64_t)(rb + 4 * g) * ld + col0 + cc;
-            acc[u] = f32x4_t{cp[0], cp[ld], cp[2 * ld], cp[3 * ld]};
-        }
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int b = b0 + 8 * u;
-            acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[u][0], bq[0], acc[u], 0, 0, 0);
-            acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[u][1], bq[1], acc[u], 0, 0, 0);
-            acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[u][2], bq[2], acc[u], 0, 0, 0);
-            acc[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[u][3], bq[3], acc[u], 0, 0, 0);
+            f32x4_t r = acc[buf][u];
+            r = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[buf][u][0], bq[0], r, 0, 0, 0);
+            r = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[buf][u][1], bq[1], r, 0, 0, 0);
+            r = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[buf][u][2], bq[2], r, 0, 0, 0);
+            r = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[buf][u][3], bq[3], r, 0, 0, 0);
             if (b < nblk) {
                 float* cp = M + (int64_t)(pc + NB + NB * b + 4 * g) * ld + col0 + cc;
-                cp[0] = acc[u][0]; cp[ld] = acc[u][1]; cp[2 * ld] = acc[u][2]; cp[3 * ld] = acc[u][3];
+                cp[0] = r[0]; cp[ld] = r[1]; cp[2 * ld] = r[2]; cp[3 * ld] = r[3];
             }
         }
+    };
+    // two groups per trip, so that the buffer indices are constants: the next group's loads are
+    // issued before the current group's MFMAs and stores
+    for (int b0 = wave; b0 < nblk; b0 += 16 * UN) {
+        const bool second = b0 + 8 * UN < nblk;
+        if (second) { load_l(1, b0 + 8 * UN); load_c(1, b0 + 8 * UN); }
+        update(std::integral_constant<int, 0>{}, b0);
+        if (b0 + 16 * UN < nblk) { load_l(0, b0 + 16 * UN); load_c(0, b0 + 16 * UN); }
+        if (second) update(std::integral_constant<int, 1>{}, b0 + 8 * UN);
     }
 }
 
@@ -292,129 +315,25 @@ __device__ __forceinline__ void lu_gather_body(float* M, int64_t ld, const int* 
     }
 }
 
-// One launch per panel inside an outer block (not its first panel):
-//   workgroup 0             applies the previous panel (at pc) to the next 16 columns, then factorises them;
-//   workgroups < nchunks    apply it to the other 16-column chunks of the block;
-//   the rest                apply its interchanges to every column outside [pc, block_end).
-// No two workgroups touch the same columns.
-struct LuStepArgs {
-    float* M; int64_t ld; int n_pad;
-    int pc;                   // first row / column of the previous panel
-    int block_end;            // first column behind the outer block
-    int nchunks;              // (block_end - pc - 16) / 16 >= 1
-    const int* gat_prev;      // interchanges of the previous panel
-    int* gat_next;            // written by the panel factorised here
-    int* perm; int* flag;
-};
+// ------------------------------------------ inverses of the diagonal triangles --
+// The inverses of the two 128 x 128 triangles of an outer block (L11 unit lower, U11 upper) are
+// what turns the block's triangular solves into GEMMs.  They grow with the block: once panel ib is
+// factorised, block row ib of L11^-1 and block column ib of U11^-1 depend only on finished data,
+// so two spare workgroups of the next launch compute them beside the panel chain.
+// Both results are row-major with pitch BW; entries outside the triangles are written as zeros.
 
-template <int NTHR, int R>
-__global__ __launch_bounds__(512)
-void lu_step_kernel(LuStepArgs a) {
-    const int b = blockIdx.x;
-    if (b >= a.nchunks) {
-        lu_gather_body(a.M, a.ld, a.gat_prev, b - a.nchunks, a.n_pad, a.pc, a.block_end);
-        return;
-    }
-    lu_chunk_body(a.M, a.ld, a.gat_prev, a.pc, a.pc + NB * (1 + b), a.n_pad);
-    if (b != 0) return;
-    __threadfence_block();
-    __syncthreads();                     // the chunk's stores are visible to the whole workgroup
-    if (threadIdx.x >= NTHR) return;
-    const int pn = a.pc + NB;
-    lu_panel_body<NTHR, R>(a.M + (int64_t)pn * a.ld + pn, a.ld, a.n_pad - pn, pn, a.gat_next, a.perm, a.flag);
-}
-
-// -------------------------------------------------------- triangle inverses --
-// X = T^-1 for a w x w triangle (w <= 128, row stride ldt); thread j computes column j by block
-// substitution with 16 x 16 blocks: the triangle sits in LDS (row i contiguous, read 16 bytes at a
-// time, all lanes the same address), the 16 entries of the current block row in registers, the
-// finished part of the column in LDS (Xl, read and written by its own thread only).
-// UPPER = false: unit lower triangle; true: upper with its diagonal.  Beyond w the triangle is taken
-// as the identity.  Out: row-major, pitch BW.  128 threads.
-template <bool UPPER>
-__device__ __forceinline__ void tri_inverse_body(const float* T, int64_t ldt, int w, float* out, float* Ts, float* Xl) {
-    const int tid = threadIdx.x;
-#pragma unroll 1
-    for (int i0 = 0; i0 < BW; i0 += NB) {                  // 16 rows of loads in flight
-        float v[NB];
-#pragma unroll
-        for (int ii = 0; ii < NB; ++ii) {
-            const int i = i0 + ii;
-            v[ii] = (i < w && tid < w) ? T[(int64_t)i * ldt + tid] : 0.f;
-        }
-#pragma unroll
-        for (int ii = 0; ii < NB; ++ii) {
-            const int i = i0 + ii;
-            const bool keep = i < w && tid < w && (UPPER ? tid >= i : tid < i);
-            Ts[i * BW + tid] = keep ? v[ii] : (i == tid ? 1.f : 0.f);
-        }
-    }
-    __syncthreads();
-    constexpr int NBLK = BW / NB;
-#pragma unroll 1
-    for (int s = 0; s < NBLK; ++s) {
-        const int ib = UPPER ? NBLK - 1 - s : s;
-        const float* Trow = Ts + ib * NB * BW;            // the 16 rows of this block row
-        float acc[NB];
-#pragma unroll
-        for (int ii = 0; ii < NB; ++ii) acc[ii] = ib * NB + ii == tid ? 1.f : 0.f;
-#pragma unroll 1
-        for (int t = 0; t < s; ++t) {                      // the block rows solved so far
-            const int kb = UPPER ? NBLK - 1 - t : t;
-            float xk[NB];
-#pragma unroll
-            for (int kk = 0; kk < NB; ++kk) xk[kk] = Xl[(kb * NB + kk) * BW + tid];
-#pragma unroll
-            for (int ii = 0; ii < NB; ++ii)
-#pragma unroll
-                for (int k4 = 0; k4 < NB / 4; ++k4) {
-                    const float4 tv = *reinterpret_cast<const float4*>(Trow + ii * BW + kb * NB + k4 * 4);
-                    acc[ii] = fmaf(-tv.x, xk[k4 * 4 + 0], acc[ii]);
-                    acc[ii] = fmaf(-tv.y, xk[k4 * 4 + 1], acc[ii]);
-                    acc[ii] = fmaf(-tv.z, xk[k4 * 4 + 2], acc[ii]);
-                    acc[ii] = fmaf(-tv.w, xk[k4 * 4 + 3], acc[ii]);
-                }
-        }
-        const float* Td = Trow + ib * NB;                  // the diagonal block
-        if (!UPPER) {
-#pragma unroll
-            for (int ii = 1; ii < NB; ++ii)
-#pragma unroll
-                for (int kk = 0; kk < ii; ++kk) acc[ii] = fmaf(-Td[ii * BW + kk], acc[kk], acc[ii]);
-        } else {
-#pragma unroll
-            for (int ii = NB - 1; ii >= 0; --ii) {
-#pragma unroll
-                for (int kk = ii + 1; kk < NB; ++kk) acc[ii] = fmaf(-Td[ii * BW + kk], acc[kk], acc[ii]);
-                acc[ii] /= Td[ii * BW + ii];
-            }
-        }
-#pragma unroll
-        for (int ii = 0; ii < NB; ++ii) {
-            const int i = ib * NB + ii;
-            Xl[i * BW + tid] = acc[ii];
-            if (i < w && tid < w) out[i * BW + tid] = acc[ii];
-        }
-    }
-}
-
-// After the last panel of an outer block (first column c0, width w): workgroup 0 inverts L11,
-// workgroup 1 inverts U11 (128 threads each), the others apply the last panel's interchanges to
-// every column outside the block.  The block's own columns left of that panel belong to L11, so
-// workgroup 0 moves those rows itself before it reads the triangle.
-__global__ __launch_bounds__(512)
-void lu_block_finish_kernel(float* M, int64_t ld, int n_pad, int c0, int w, const int* gat, float* Linv, float* Uinv) {
-    extern __shared__ __attribute__((aligned(16))) float Ts[];
+// Block row ib of Linv = L11^-1.  First the interchanges of panel ib are applied to the block's
+// columns left of that panel (those entries belong to L11 and nobody else touches them in this
+// launch); then thread j < 128 computes column j of the block row:
+// Linv[ib][:, j] = Lii^-1 (E[ib][:, j] - sum_{kb < ib} L[ib][kb] Linv[kb][:, j]).  512 threads.
+__device__ __forceinline__ void linv_block_row(float* M, int64_t ld, int c0, int ib, int w, const int* gat, float* Linv) {
+    __shared__ float Lr[NB][BW + 1];
     __shared__ int cg[64];
-    const int b = blockIdx.x, tid = threadIdx.x;
-    if (b >= 2) {
-        lu_gather_body(M, ld, gat, b - 2, n_pad, c0, c0 + w);
-        return;
-    }
-    if (b == 0) {
-        if (tid < 64) cg[tid] = gat[tid];
-        __syncthreads();
-        const int width = w - NB;                          // columns [c0, c0 + width), 32 list entries each
+    const int tid = threadIdx.x;
+    const int width = NB * ib;                             // columns [c0, c0 + width) lie left of panel ib
+    if (tid < 64) cg[tid] = gat[tid];
+    __syncthreads();
+    {
         float v[7];
 #pragma unroll
         for (int k = 0; k < 7; ++k) {
@@ -431,13 +350,155 @@ void lu_block_finish_kernel(float* M, int64_t ld, int n_pad, int c0, int w, cons
             const int dst = e < 32 ? cg[e] : -1;
             if (dst >= 0) M[(int64_t)dst * ld + c0 + c] = v[k];
         }
-        __threadfence_block();
-        __syncthreads();
     }
-    if (tid >= BW) return;
-    const float* T = M + (int64_t)c0 * ld + c0;
-    if (b == 0) tri_inverse_body<false>(T, ld, w, Linv, Ts, Ts + BW * BW);
-    else tri_inverse_body<true>(T, ld, w, Uinv, Ts, Ts + BW * BW);
+    __threadfence_block();
+    __syncthreads();
+    const int cols = width + NB;                           // block row ib of L11: 16 rows x cols
+    for (int id = tid; id < NB * cols; id += 512) {
+        const int ii = id / cols, k = id - ii * cols;
+        Lr[ii][k] = M[(int64_t)(c0 + width + ii) * ld + c0 + k];
+    }
+    __syncthreads();
+    if (tid >= BW || tid >= w) return;
+    const int j = tid;
+    float acc[NB];
+#pragma unroll
+    for (int ii = 0; ii < NB; ++ii) acc[ii] = width + ii == j ? 1.f : 0.f;
+    if (j < cols) {
+#pragma unroll 1
+        for (int kb = 0; kb < ib; ++kb) {
+            float xk[NB];
+#pragma unroll
+            for (int kk = 0; kk < NB; ++kk) xk[kk] = Linv[(kb * NB + kk) * BW + j];
+#pragma unroll
+            for (int ii = 0; ii < NB; ++ii)
+#pragma unroll
+                for (int kk = 0; kk < NB; ++kk) acc[ii] = fmaf(-Lr[ii][kb * NB + kk], xk[kk], acc[ii]);
+        }
+#pragma unroll
+        for (int ii = 1; ii < NB; ++ii)
+#pragma unroll
+            for (int kk = 0; kk < ii; ++kk) acc[ii] = fmaf(-Lr[ii][width + kk], acc[kk], acc[ii]);
+    }
+#pragma unroll
+    for (int ii = 0; ii < NB; ++ii) Linv[(width + ii) * BW + j] = acc[ii];
+}
+
+// Block column ib of Uinv = U11^-1: Uinv[ib][ib] = Uii^-1 and, above it,
+// Uinv[0:ib][ib] = -Uinv[0:ib][0:ib] (U[0:ib][ib] Uii^-1); zeros below.  Thread j < 128 owns row j.
+__device__ __forceinline__ void uinv_block_col(const float* M, int64_t ld, int c0, int ib, int w, float* Uinv) {
+    __shared__ float Uc[BW][NB + 1];                       // U[0 : 16 (ib + 1)][panel ib]
+    __shared__ float Dii[NB][NB + 1];
+    __shared__ float Y[BW][NB + 1];
+    const int tid = threadIdx.x;
+    const int above = NB * ib;
+    for (int id = tid; id < (above + NB) * NB; id += 512) {
+        const int r = id >> 4, c = id & 15;
+        Uc[r][c] = M[(int64_t)(c0 + r) * ld + c0 + above + c];
+    }
+    __syncthreads();
+    if (tid < NB) {                                        // column tid of Uii^-1 by back substitution
+        float x[NB];
+#pragma unroll
+        for (int i = NB - 1; i >= 0; --i) {
+            float t = i == tid ? 1.f : 0.f;
+#pragma unroll
+            for (int k = i + 1; k < NB; ++k) t = fmaf(-Uc[above + i][k], x[k], t);
+            x[i] = t / Uc[above + i][i];
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) Dii[i][tid] = x[i];
+    }
+    __syncthreads();
+    if (tid < above) {                                     // Y = U[0:ib][ib] Uii^-1, row tid
+        float y[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) y[c] = 0.f;
+#pragma unroll
+        for (int m = 0; m < NB; ++m) {
+            const float u = Uc[tid][m];
+#pragma unroll
+            for (int c = 0; c < NB; ++c) y[c] = fmaf(u, Dii[m][c], y[c]);
+        }
+#pragma unroll
+        for (int c = 0; c < NB; ++c) Y[tid][c] = y[c];
+    }
+    __syncthreads();
+    if (tid >= BW || tid >= w) return;
+    const int j = tid;
+    float z[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) z[c] = 0.f;
+    if (j < above) {
+#pragma unroll 1
+        for (int kb = j >> 4; kb < ib; ++kb) {             // row j of Uinv is zero left of its diagonal
+            float uk[NB];
+#pragma unroll
+            for (int k4 = 0; k4 < NB / 4; ++k4) {
+                const float4 t = *reinterpret_cast<const float4*>(Uinv + j * BW + kb * NB + k4 * 4);
+                uk[k4 * 4 + 0] = t.x; uk[k4 * 4 + 1] = t.y; uk[k4 * 4 + 2] = t.z; uk[k4 * 4 + 3] = t.w;
+            }
+#pragma unroll
+            for (int kk = 0; kk < NB; ++kk)
+#pragma unroll
+                for (int c = 0; c < NB; ++c) z[c] = fmaf(-uk[kk], Y[kb * NB + kk][c], z[c]);
+        }
+    } else if (j < above + NB) {
+#pragma unroll
+        for (int c = 0; c < NB; ++c) z[c] = Dii[j - above][c];
+    }
+#pragma unroll
+    for (int c4 = 0; c4 < NB / 4; ++c4)
+        *reinterpret_cast<float4*>(Uinv + j * BW + above + c4 * 4) = make_float4(z[c4 * 4], z[c4 * 4 + 1], z[c4 * 4 + 2], z[c4 * 4 + 3]);
+}
+
+// One launch per panel inside an outer block (not its first panel):
+//   workgroup 0             applies the previous panel (at pc) to the next 16 columns, then factorises them;
+//   workgroups < nchunks    apply it to the other 16-column chunks of the block;
+//   the next two            extend the inverses of the block's triangles by the previous panel's block row / column
+//                           (the first of them also moves the block's own rows left of that panel);
+//   the rest                apply its interchanges to every column outside the block.
+// No two workgroups touch the same data.
+struct LuStepArgs {
+    float* M; int64_t ld; int n_pad;
+    int c0, w;                // the outer block: first column, width
+    int pc;                   // first row / column of the previous panel
+    int nchunks;              // (c0 + w - pc - 16) / 16 >= 1
+    const int* gat_prev;      // interchanges of the previous panel
+    int* gat_next;            // written by the panel factorised here
+    int* perm; int* flag;
+    float* Linv; float* Uinv; // inverses of this block's triangles (pitch BW)
+};
+
+template <int NTHR, int R>
+__global__ __launch_bounds__(512)
+void lu_step_kernel(LuStepArgs a) {
+    const int b = blockIdx.x;
+    if (b >= a.nchunks) {
+        const int ib = (a.pc - a.c0) / NB;
+        if (b == a.nchunks) linv_block_row(a.M, a.ld, a.c0, ib, a.w, a.gat_prev, a.Linv);
+        else if (b == a.nchunks + 1) uinv_block_col(a.M, a.ld, a.c0, ib, a.w, a.Uinv);
+        else lu_gather_body(a.M, a.ld, a.gat_prev, b - a.nchunks - 2, a.n_pad, a.c0, a.c0 + a.w);
+        return;
+    }
+    lu_chunk_body(a.M, a.ld, a.gat_prev, a.pc, a.pc + NB * (1 + b), a.n_pad);
+    if (b != 0) return;
+    __threadfence_block();
+    __syncthreads();                     // the chunk's stores are visible to the whole workgroup
+    if (threadIdx.x >= NTHR) return;
+    const int pn = a.pc + NB;
+    lu_panel_body<NTHR, R>(a.M + (int64_t)pn * a.ld + pn, a.ld, a.n_pad - pn, pn, a.gat_next, a.perm, a.flag);
+}
+
+// After the last panel of an outer block: the last block row / column of the two inverses
+// (workgroups 0 and 1), and that panel's interchanges on every column outside the block.
+__global__ __launch_bounds__(512)
+void lu_block_finish_kernel(float* M, int64_t ld, int n_pad, int c0, int w, const int* gat, float* Linv, float* Uinv) {
+    const int b = blockIdx.x;
+    const int ib = w / NB - 1;
+    if (b == 0) linv_block_row(M, ld, c0, ib, w, gat, Linv);
+    else if (b == 1) uinv_block_col(M, ld, c0, ib, w, Uinv);
+    else lu_gather_body(M, ld, gat, b - 2, n_pad, c0, c0 + w);
 }
 
 // X[r, perm[c]] <- X[r, c]: one row per workgroup, through LDS
@@ -552,37 +613,45 @@ void lanczos_vector_kernel(float* vec, int64_t ld, int n, float* tri, int step) 
     if (tid == 0) { tr[step] = alpha; tr[kLanczosMax + step] = beta; }
 }
 
-// Largest eigenvalue of the symmetric tridiagonal matrix (alpha[0..k), beta[0..k-1)) by bisection on
-// the Sturm count; out[0] = sqrt(lambda_A lambda_Ainv) = the kappa_2 estimate, out[1], out[2] its factors.
+// Largest eigenvalue of the symmetric tridiagonal matrix (alpha[0..k), beta[0..k-1)) by sectioning on
+// the Sturm count: one wave, lanes 0..31 work on A, lanes 32..63 on A^-1; each round every lane counts
+// the eigenvalues below its own trial value (32 trial values per bracket), and the bracket shrinks to
+// the interval between the last trial with an eigenvalue at or above it and the first one above all.
+// out[0] = sqrt(lambda_A lambda_Ainv) = the kappa_2 estimate, out[1], out[2] its factors.
 __global__ __launch_bounds__(64)
 void lanczos_finish_kernel(const float* tri, int k, float* out) {
-    __shared__ float sig[2];
-    const int o = threadIdx.x;
-    if (o < 2) {
-        const float* al = tri + o * 2 * kLanczosMax;
-        const float* be = al + kLanczosMax;
-        float hi = 0.f;
-        for (int i = 0; i < k; ++i) {
-            const float g = fabsf(al[i]) + (i > 0 ? fabsf(be[i - 1]) : 0.f) + (i + 1 < k ? fabsf(be[i]) : 0.f);
-            hi = fmaxf(hi, g);
-        }
-        float lo = 0.f;
-        for (int it = 0; it < 48; ++it) {
-            const float mid = 0.5f * (lo + hi);
-            int below = 0;                              // eigenvalues below mid
-            float d = 1.f;
-            for (int i = 0; i < k; ++i) {
-                const float b2 = i > 0 ? be[i - 1] * be[i - 1] : 0.f;
-                d = al[i] - mid - b2 / d;
-                if (fabsf(d) < 1e-30f) d = -1e-30f;
-                below += d < 0.f;
-            }
-            if (below == k) hi = mid; else lo = mid;
-        }
-        sig[o] = sqrtf(0.5f * (lo + hi));
-    }
+    __shared__ float co[2 * 2 * kLanczosMax];
+    const int lane = threadIdx.x, o = lane >> 5, l = lane & 31;
+    co[lane] = tri[lane]; co[lane + 64] = tri[lane + 64];
     __syncthreads();
-    if (threadIdx.x == 0) { out[1] = sig[0]; out[2] = sig[1]; out[0] = sig[0] * sig[1]; }
+    const float* al = co + o * 2 * kLanczosMax;
+    const float* be = al + kLanczosMax;
+    float hi = 0.f;
+    for (int i = 0; i < k; ++i) {
+        const float gsh = fabsf(al[i]) + (i > 0 ? fabsf(be[i - 1]) : 0.f) + (i + 1 < k ? fabsf(be[i]) : 0.f);
+        hi = fmaxf(hi, gsh);
+    }
+    float lo = 0.f;
+    for (int round = 0; round < 6; ++round) {
+        const float step = (hi - lo) * (1.0f / 32.0f);
+        const float x = lo + step * (float)(l + 1);        // l = 31: the current upper end
+        int below = 0;                                     // eigenvalues below x
+        float d = 1.f;
+        for (int i = 0; i < k; ++i) {
+            const float b2 = i > 0 ? be[i - 1] * be[i - 1] : 0.f;
+            d = al[i] - x - b2 * __builtin_amdgcn_rcpf(d);
+            if (fabsf(d) < 1e-30f) d = -1e-30f;
+            below += d < 0.f;
+        }
+        const unsigned long long all = __ballot(below == k);
+        const unsigned half = (unsigned)(all >> (32 * o));  // this operator's lanes
+        const int first = half ? __ffs(half) - 1 : 31;      // first trial above every eigenvalue
+        hi = lo + step * (float)(first + 1);
+        lo = lo + step * (float)first;
+    }
+    const float sigma = sqrtf(0.5f * (lo + hi));
+    const float s0 = __shfl(sigma, 0, 64), s1 = __shfl(sigma, 32, 64);
+    if (lane == 0) { out[1] = s0; out[2] = s1; out[0] = s0 * s1; }
 }
 
 #define GELO_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
@@ -616,7 +685,7 @@ hipError_t launch_lu_panel(float* Mp, int64_t ld, int m, int row_offset, int* ga
 
 hipError_t launch_lu_step(const LuStepArgs& a, hipStream_t s) {
     const int m = a.n_pad - a.pc - NB;                    // rows of the panel factorised in this launch
-    const dim3 grid(a.nchunks + (a.n_pad + 127) / 128);
+    const dim3 grid(a.nchunks + 2 + (a.n_pad + 127) / 128);
 #define GELO_CASE(NT, RR) hipLaunchKernelGGL((lu_step_kernel<NT, RR>), grid, dim3(512), 0, s, a); break;
     if (m <= 1024) {
         switch ((m + 255) / 256) {
@@ -655,14 +724,9 @@ hipError_t gemm(const float* A, int64_t lda, const float* B, int64_t ldb, float*
     return gemm_f32(g, s);
 }
 
-constexpr size_t kTriangleLds = 2 * (size_t)BW * BW * sizeof(float);      // the triangle and its inverse
-
 }  // namespace
 
-hipError_t lu_init() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(lu_block_finish_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kTriangleLds);
-}
+hipError_t lu_init() { return hipSuccess; }
 
 hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t s) {
     const int n_pad = ws.n_pad;
@@ -684,15 +748,16 @@ hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t s) {
         GELO_TRY(launch_lu_panel(M + (int64_t)c0 * ld + c0, ld, n_pad - c0, c0, ws.gat + 64 * (panel & 1), ws.perm, ws.flag, s));
         for (int pc = c0; pc + NB < block_end; pc += NB) {
             LuStepArgs a;
-            a.M = M; a.ld = ld; a.n_pad = n_pad; a.pc = pc; a.block_end = block_end;
+            a.M = M; a.ld = ld; a.n_pad = n_pad; a.c0 = c0; a.w = w; a.pc = pc;
             a.nchunks = (block_end - pc - NB) / NB;
+            a.Linv = Linv + (int64_t)c0 * BW; a.Uinv = Uinv + (int64_t)c0 * BW;
             a.gat_prev = ws.gat + 64 * (panel & 1);
             a.gat_next = ws.gat + 64 * ((panel + 1) & 1);
             a.perm = ws.perm; a.flag = ws.flag;
             GELO_TRY(launch_lu_step(a, s));
             ++panel;
         }
-        hipLaunchKernelGGL(lu_block_finish_kernel, dim3(2 + (n_pad + 127) / 128), dim3(512), kTriangleLds, s,
+        hipLaunchKernelGGL(lu_block_finish_kernel, dim3(2 + (n_pad + 127) / 128), dim3(512), 0, s,
                            M, ld, n_pad, c0, w, ws.gat + 64 * (panel & 1), Linv + (int64_t)c0 * BW, Uinv + (int64_t)c0 * BW);
         GELO_TRY(hipGetLastError());
         ++panel;
