@@ -108,11 +108,11 @@ def write_traffic_record(workload: str, fetch_csv: str, write_csv: str) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=25)
     ap.add_argument("--workload", default="llama7b_bf16_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--pipeline", type=int, default=8, help="mixing matrices drawn ahead on side streams")
+    ap.add_argument("--pipeline", type=int, default=24, help="mixing matrices drawn ahead on side streams")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run a plain elementwise copy of known size (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--write-traffic-record", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),

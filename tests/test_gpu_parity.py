@@ -264,6 +264,26 @@ def test_conditioned_matrix_construction(ctx):
     assert np.linalg.norm(f64(A).T @ f64(A) - np.eye(n)) / math.sqrt(n) > 0.2     # Gram matrices are masked
 
 
+@pytest.mark.parametrize("n", [16, 130, 928, 1100, 2070])
+def test_pivoted_lu_inverse_across_block_boundaries(ctx, n):
+    """The explicit inverse behind the non-orthogonal kinds, at sizes that cross the boundaries of the
+    blocked LU (a single panel; a 128-column outer block plus a short one; eight column windows; panels of
+    more than 1024 and of more than 2048 rows): A^-1 against the float64 inverse of the SAME matrix, the
+    residual of the product, and the condition estimate against numpy's."""
+    for kind, cond_max in ((g.GELO_CONDITIONED, 0.0), (g.GELO_GAUSSIAN, 1e12)):
+        if kind == g.GELO_GAUSSIAN and n > 1000:
+            continue          # kappa ~ n: the float inverse itself is then too inexact to pin the estimate to 5%
+        m = g.gelo_sample_mixing(ctx, kind, n, 0, 64, g.GELO_F32, cond_max, 1, batch_id=7100 + 2 * n + (kind == g.GELO_GAUSSIAN))
+        A, A_inv, _, _, kappa = g.gelo_mixing_export(ctx, m, n, 0, 64)
+        g.gelo_mixing_free(ctx, m)
+        A, A_inv = f64(A), f64(A_inv)
+        kappa_ref = np.linalg.cond(A)
+        assert abs(kappa - kappa_ref) / kappa_ref < 0.05
+        # float LU + substitution: error ~ n eps32 kappa (eps32 = 2^-24)
+        assert o.rel_frobenius(A_inv, np.linalg.inv(A)) < max(n, 64) * 2.0 ** -24 * kappa_ref
+        assert np.linalg.norm(A @ A_inv - np.eye(n)) / math.sqrt(n) < max(n, 64) * 2.0 ** -24 * kappa_ref
+
+
 # ------------------------------------------------------------ full-size configs --
 def full_size(ctx, name, layer=0):
     w = wl.WORKLOADS[name]
