@@ -6,8 +6,9 @@ sits in HBM: draw a fresh mixing matrix A (Philox + Householder QR, or LU for th
 non-orthogonal kinds), build the shield rows, mix U = A[H;S], project Y = U W, unmix
 Z = A^-1 Y.  Prints ONE JSON line:
   value      whole-step throughput: algorithmic FLOP of the step (chain + A generation) / time
-  roofline   the dominant kernel (the projection GEMM) against the MFMA peak of its dtype,
-             timed with events on the stream it runs on
+  roofline   the dominant kernel (the projection GEMM) against the MFMA peak of its dtype (against
+             HBM bandwidth for decode-shaped batches of at most 128 rows), timed with events on
+             the stream it runs on
   cpu_baseline  the fp64 CPU oracle timed on the host cores on a bounded sample
 plus per-stage times, the chain-only rate with A already sampled, and the overhead against a
 plain H W GEMM run through the same kernel.
@@ -273,6 +274,15 @@ def main() -> int:
                      "peak": peak, "unit": "TFLOP/s", "frac": f_proj / t_proj / 1e12 / peak, "traffic": None,
                      "avg_launch_us": t_proj * 1e6},
     }
+
+    if n <= 128:
+        # decode-shaped batches: the projection streams W once and does almost no arithmetic per byte
+        # (about 2 n FLOP per byte of W), so it is bound by HBM, not by the matrix cores
+        esz = 2 if w.dtype == "bf16" else 4
+        b_proj = float(esz) * (n * d + d * p + n * p)
+        result["roofline"] = {"kernel": "gemm (project Y = U W), skinny path", "bound": "hbm",
+                              "achieved": b_proj / t_proj / 1e9, "peak": 8000.0, "unit": "GB/s",
+                              "frac": b_proj / t_proj / 1e9 / 8000.0, "traffic": None, "avg_launch_us": t_proj * 1e6}
 
     # HBM traffic of the projection GEMM from the committed rocprofv3 counter runs; only valid for the
     # kernel source those runs were taken on
