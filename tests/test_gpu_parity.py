@@ -135,6 +135,34 @@ def test_orthogonal_mixing_matrix_at_the_largest_n(ctx):
     assert np.linalg.norm(np.tril(R, -1)) / np.linalg.norm(R) < 20 * (10.0 * n) * 2.0 ** -24 / math.sqrt(n) + 1e-5
 
 
+def test_conditioned_inverse_at_the_largest_n(ctx):
+    """n = GELO_MAX_N through the pivoted LU: ten register rows per thread in the panels, forty column
+    windows, forty outer blocks.  A^-1 is pinned by what defines it (both products give the identity to
+    float rounding times n), the condition estimate by the bounds of the construction
+    (singular values within 1 +- 2 * 0.25 up to fluctuations) and by ||A||_2 ||A^-1||_2 from a few
+    float64 power iterations on the exported matrices."""
+    n = g.GELO_MAX_N
+    m = g.gelo_sample_mixing(ctx, g.GELO_CONDITIONED, n, 0, 64, g.GELO_F32, 0.0, 1, batch_id=778)
+    A, A_inv, _, _, kappa = g.gelo_mixing_export(ctx, m, n, 0, 64, want_shields=False)
+    g.gelo_mixing_free(ctx, m)
+    Ad, Bd = A.double().cuda(), A_inv.double().cuda()
+    eye = torch.eye(n, dtype=torch.float64, device="cuda")
+    bound = n * 2.0 ** -24 * 4.0
+    assert (Ad @ Bd - eye).norm().item() / math.sqrt(n) < bound
+    assert (Bd @ Ad - eye).norm().item() / math.sqrt(n) < bound
+
+    def sigma_max(Mx):
+        x = torch.ones(n, dtype=torch.float64, device="cuda")
+        for _ in range(200):
+            x = Mx.t() @ (Mx @ x)
+            x = x / x.norm()
+        return (Mx @ x).norm().item()
+
+    kappa_ref = sigma_max(Ad) * sigma_max(Bd)
+    assert 1.5 < kappa < 4.0
+    assert abs(kappa - kappa_ref) / kappa_ref < 0.05
+
+
 def test_fresh_per_batch_and_deterministic(ctx):
     c2 = g.gelo_create(0, 0xC0FFEE, allow_batch_reuse=True)
     try:
