@@ -5,11 +5,12 @@
 // overwrite B in place (C == B0, K == M): the LU path's multiplications by a diagonal-block inverse
 // (those shapes take the short kernel at the end of this file, which has the same property).
 //
-// A workgroup of 4 waves owns a 128 x 128 tile and walks K in steps of 16
-// through double-buffered LDS; a wave owns 64 x 64 as 2 x 2 accumulators.
-// A lane reads four consecutive k of its A row with one 16-byte LDS read and
-// spends them on four successive MFMAs; the matching B values are single
-// dwords, contiguous across lanes.
+// A workgroup of 4 waves owns a 128 x 128 or 128 x 192 tile (whichever fills whole rounds of
+// the chip's CUs better) and walks K in steps of 32 through double-buffered LDS; a wave owns
+// 64 rows x half the tile's columns.  A lane reads four consecutive k of its A row with one
+// 16-byte LDS read and spends them on four successive MFMAs; the matching B values are single
+// dwords, contiguous across lanes; the fragments of the next 8 k are read while the MFMAs of the
+// current 8 run.
 #include "gelo_internal.h"
 
 namespace gelo {
@@ -18,10 +19,9 @@ namespace {
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128, BN = 128, BK = 16;
+constexpr int BM = 128, BK = 32;
 constexpr int NT = 256;
-constexpr int A_PITCH = BK + 4;    // floats: 80-byte rows, conflict-free 16-byte reads down a column of rows
-constexpr int B_PITCH = BN + 4;
+constexpr int A_PITCH = BK + 4;    // floats: 144-byte rows, conflict-free 16-byte reads down a column of rows
 
 struct F32Args {
     const float* A;  int64_t lda;
@@ -33,8 +33,14 @@ struct F32Args {
     int subtract;              // C <- C - A B (the LU's trailing and substitution updates)
 };
 
+// BN = 128 or 192: the tile width is picked per shape so that the tile count fills whole rounds of the chip's CUs
+template <int BN>
 __global__ __launch_bounds__(NT)
 void gemm_f32_kernel(F32Args g) {
+    constexpr int B_PITCH = BN + 4;
+    constexpr int NTN = BN / 64;                 // 32-column MFMA blocks per wave
+    constexpr int BCH = BN / 4;                  // 16-byte chunks per B row
+    constexpr int BLD = BK * BCH / NT;           // B chunks per thread and K step
     __shared__ __attribute__((aligned(16))) float As[2][BM * A_PITCH];
     __shared__ __attribute__((aligned(16))) float Bs[2][BK * B_PITCH];
 
@@ -54,15 +60,21 @@ void gemm_f32_kernel(F32Args g) {
     const int KA = (g.K + 3) & ~3;
     const int k_tiles = (g.K + BK - 1) / BK;
 
-    f32x4_t a_stage[2], b_stage[2];
+    // the arguments the loads need, by value (scalar registers)
+    const float* B0 = g.B0;
+    const float* B1 = g.B1;
+    const int64_t ldb0 = g.ldb0, ldb1 = g.ldb1;
+    const int K0 = g.K0, Kd = g.K, Nd = g.N;
+
+    f32x4_t a_stage[4], b_stage[BLD];
 
     auto load_global = [&](int kt) {
         const int k0 = kt * BK;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 4; ++i) {
             const int id = tid + i * NT;
-            {   // A: 128 rows x 4 chunks
-                const int r = id >> 2, c = id & 3;
+            {   // A: 128 rows x 8 chunks
+                const int r = id >> 3, c = id & 7;
                 int row = m0 + r;
                 row = row < g.M ? row : g.M - 1;
                 const int gk = k0 + c * 4;
@@ -70,14 +82,35 @@ void gemm_f32_kernel(F32Args g) {
                 if (gk < KA) v = *reinterpret_cast<const f32x4_t*>(g.A + (int64_t)row * g.lda + gk);
                 a_stage[i] = v;
             }
-            {   // B: 16 rows x 32 chunks
-                const int r = id >> 5, c = id & 31;
-                const int gk = k0 + r, gn = n0 + c * 4;
+        }
+        // B: 32 rows x BN / 4 chunks.  A K step that lies in one row segment of B (the common case) takes its
+        // base pointer from scalar registers; picking B0 or B1 per lane makes the compiler fetch the pointer
+        // itself from the argument block with a vector load, one exposed memory latency per chunk.
+        const bool seg0 = k0 + BK <= K0, seg1 = k0 >= K0;
+        if (seg0 || seg1) {
+            const float* base = seg0 ? B0 + (int64_t)k0 * ldb0 : B1 + (int64_t)(k0 - K0) * ldb1;
+            const int64_t ldb = seg0 ? ldb0 : ldb1;
+#pragma unroll
+            for (int i = 0; i < BLD; ++i) {
+                const int id = tid + i * NT;
+                const int r = id / BCH, c = id - r * BCH;
+                const int gn = n0 + c * 4;
                 f32x4_t v = {0.f, 0.f, 0.f, 0.f};
-                if (gk < g.K && gn < g.N) {
-                    const float* p = gk < g.K0 ? g.B0 + (int64_t)gk * g.ldb0 + gn
-                                               : g.B1 + (int64_t)(gk - g.K0) * g.ldb1 + gn;
-                    v = *reinterpret_cast<const f32x4_t*>(p);
+                if (k0 + r < Kd && gn < Nd) v = *reinterpret_cast<const f32x4_t*>(base + (int64_t)r * ldb + gn);
+                b_stage[i] = v;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < BLD; ++i) {
+                const int id = tid + i * NT;
+                const int r = id / BCH, c = id - r * BCH;
+                const int gk = k0 + r, gn = n0 + c * 4;
+                const bool first = gk < K0;
+                const int64_t off = first ? (int64_t)gk * ldb0 : (int64_t)(gk - K0) * ldb1;
+                f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+                if (gk < Kd && gn < Nd) {
+                    if (first) v = *reinterpret_cast<const f32x4_t*>(B0 + off + gn);
+                    else v = *reinterpret_cast<const f32x4_t*>(B1 + off + gn);
                 }
                 b_stage[i] = v;
             }
@@ -85,18 +118,23 @@ void gemm_f32_kernel(F32Args g) {
     };
     auto store_lds = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < 4; ++i) {
             const int id = tid + i * NT;
-            *reinterpret_cast<f32x4_t*>(&As[buf][(id >> 2) * A_PITCH + (id & 3) * 4]) = a_stage[i];
-            *reinterpret_cast<f32x4_t*>(&Bs[buf][(id >> 5) * B_PITCH + (id & 31) * 4]) = b_stage[i];
+            *reinterpret_cast<f32x4_t*>(&As[buf][(id >> 3) * A_PITCH + (id & 7) * 4]) = a_stage[i];
+        }
+#pragma unroll
+        for (int i = 0; i < BLD; ++i) {
+            const int id = tid + i * NT;
+            const int r = id / BCH, c = id - r * BCH;
+            *reinterpret_cast<f32x4_t*>(&Bs[buf][r * B_PITCH + c * 4]) = b_stage[i];
         }
     };
 
-    f32x16_t acc[2][2];
+    f32x16_t acc[2][NTN];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NTN; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
@@ -107,25 +145,32 @@ void gemm_f32_kernel(F32Args g) {
     for (int kt = 0; kt < k_tiles; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < k_tiles) load_global(kt + 1);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            f32x4_t a4[2];
+        // fragments of sub-step ks + 1 are read while the 16 MFMAs of sub-step ks run
+        f32x4_t a4[2][2];
+        float b1[2][4][NTN];
+        auto load_frags = [&](int fb, int ks) {
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
-                a4[mt] = *reinterpret_cast<const f32x4_t*>(
+                a4[fb][mt] = *reinterpret_cast<const f32x4_t*>(
                     &As[buf][(wm * 64 + mt * 32 + j) * A_PITCH + ks * 8 + grp * 4]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float b1[2];
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    b1[nt] = Bs[buf][(ks * 8 + grp * 4 + e) * B_PITCH + wn * 64 + nt * 32 + j];
+                for (int nt = 0; nt < NTN; ++nt)
+                    b1[fb][e][nt] = Bs[buf][(ks * 8 + grp * 4 + e) * B_PITCH + wn * (BN / 2) + nt * 32 + j];
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < BK / 8; ++ks) {
+            const int fb = ks & 1;
+            if (ks + 1 < BK / 8) load_frags(fb ^ 1, ks + 1);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[mt][e], b1[nt], acc[mt][nt], 0, 0, 0);
-            }
+                    for (int nt = 0; nt < NTN; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[fb][mt][e], b1[fb][e][nt], acc[mt][nt], 0, 0, 0);
         }
         if (kt + 1 < k_tiles) store_lds(buf ^ 1);
         __syncthreads();
@@ -134,8 +179,8 @@ void gemm_f32_kernel(F32Args g) {
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int col = n0 + wn * 64 + nt * 32 + j;
+        for (int nt = 0; nt < NTN; ++nt) {
+            const int col = n0 + wn * (BN / 2) + nt * 32 + j;
             if (col < g.N) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -241,12 +286,24 @@ hipError_t gemm_f32(const GemmOperands& o, hipStream_t stream) {
     a.C = (float*)o.C;         a.ldc = o.ldc;
     a.M = o.M; a.N = o.N; a.K = o.K;
     a.tiles_m = (o.M + BM - 1) / BM;
-    a.tiles_n = (o.N + BN - 1) / BN;
     a.subtract = o.subtract ? 1 : 0;
-    if (o.M <= BM && o.K <= 128 && o.K % 16 == 0 && o.K0 >= o.K)
-        hipLaunchKernelGGL(gemm_f32_short_kernel, dim3((o.N + SN - 1) / SN), dim3(NT), kShortLds, stream, a);
-    else
-        hipLaunchKernelGGL(gemm_f32_kernel, dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
+    if (o.M <= BM && o.K <= 128 && o.K % 16 == 0 && o.K0 >= o.K) {
+        a.tiles_n = (o.N + SN - 1) / SN;
+        hipLaunchKernelGGL(gemm_f32_short_kernel, dim3(a.tiles_n), dim3(NT), kShortLds, stream, a);
+        return hipGetLastError();
+    }
+    // tile width: the one whose tile count wastes less of the last round over the chip's 256 CUs
+    // (cost = rounds x tile width; e.g. 512 x 12288: 384 tiles of 128 = two rounds, 256 tiles of 192 = one)
+    constexpr int kCus = 256;
+    const int t128 = a.tiles_m * ((o.N + 127) / 128), t192 = a.tiles_m * ((o.N + 191) / 192);
+    const int64_t cost128 = (int64_t)((t128 + kCus - 1) / kCus) * 128, cost192 = (int64_t)((t192 + kCus - 1) / kCus) * 192;
+    if (cost192 < cost128) {
+        a.tiles_n = (o.N + 191) / 192;
+        hipLaunchKernelGGL(gemm_f32_kernel<192>, dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
+    } else {
+        a.tiles_n = (o.N + 127) / 128;
+        hipLaunchKernelGGL(gemm_f32_kernel<128>, dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
+    }
     return hipGetLastError();
 }
 
