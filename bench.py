@@ -123,7 +123,7 @@ def main() -> int:
     if args.write_traffic_record:
         return write_traffic_record(args.workload, *args.write_traffic_record)
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        print("bench.py: this library runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np

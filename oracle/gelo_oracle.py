@@ -218,8 +218,9 @@ def sample_conditioned(seed, batch_id, n, beta=CONDITIONED_BETA):
     orthogonal matrix of `sample_orthogonal`, G2 an independent Gaussian.
     ||G2/sqrt(n)||_2 ~ 2, so the singular values stay within about
     [1-2 beta, 1+2 beta]: kappa of a few, inside the paper's "kappa < 100"
-    advice, while A^T A != I.  (The construction is this build's reading; the
-    paper asks for a well-conditioned general A without saying how to get one.)
+    advice, while A^T A != I.  (The construction is a reading of this
+    implementation; the paper asks for a well-conditioned general A without saying
+    how to get one.)
     Returns (A, A^-1, kappa)."""
     Q, _ = sample_orthogonal(seed, batch_id, n)
     G2 = gaussian_matrix(seed, batch_id, STREAM_PERTURB, 0, n, n)

@@ -1,6 +1,6 @@
 """Error behaviour of the C ABI: argument errors come back synchronously as status codes with
 a message, nothing is enqueued, and no kernel ever sees an invalid shape.  (A context needs a
-device, so these run on the GPU machine; none of them launches a kernel that could fault.)"""
+device, so these need a GPU; none of them launches a kernel that could fault.)"""
 import pytest
 import torch
 
