@@ -48,25 +48,38 @@ __device__ __forceinline__ void lu_panel_body(float* Mp, int64_t ld, int m, int 
     __shared__ int qlist[NB];
     __shared__ int gd[32], gs[32];
     __shared__ int pos_of[kMaxN];
+    __shared__ __attribute__((aligned(16))) float stage[NW][64 * (NB + 4)];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t prow_addr = (uint32_t)(size_t)prow;       // its LDS byte address
     float P[R][NB];
     unsigned used = 0;                       // bit i: register row i is absent or already a pivot row
+    // A thread owns whole rows (64 bytes of the row-major matrix each), but a load in which every lane
+    // reads a different row touches 64 cache lines.  So the 64 rows of a wave travel through an LDS
+    // stage: four lanes read one row together (16 lines per load), then every lane picks up its row.
+    constexpr int SP = NB + 4;               // stage pitch, floats
+    float* st = stage[wave];
+    const int srow = lane >> 2, schunk = (lane & 3) * 4;
 #pragma unroll
     for (int i = 0; i < R; ++i) {
-        const int r = tid + i * NTHR;
-        if (r < m) {
+        const int base = i * NTHR + 64 * wave;
+        float4 v[4];
 #pragma unroll
-            for (int c4 = 0; c4 < NB / 4; ++c4) {
-                const float4 v = *reinterpret_cast<const float4*>(Mp + (int64_t)r * ld + c4 * 4);
-                P[i][c4 * 4 + 0] = v.x; P[i][c4 * 4 + 1] = v.y; P[i][c4 * 4 + 2] = v.z; P[i][c4 * 4 + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < NB; ++c) P[i][c] = 0.f;
-            used |= 1u << i;
+        for (int q = 0; q < 4; ++q) {
+            const int rr = base + 16 * q + srow;
+            v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (rr < m) v[q] = *reinterpret_cast<const float4*>(Mp + (int64_t)rr * ld + schunk);
         }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<float4*>(&st[(16 * q + srow) * SP + schunk]) = v[q];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int c4 = 0; c4 < NB / 4; ++c4) {
+            const float4 x = *reinterpret_cast<const float4*>(&st[lane * SP + c4 * 4]);
+            P[i][c4 * 4 + 0] = x.x; P[i][c4 * 4 + 1] = x.y; P[i][c4 * 4 + 2] = x.z; P[i][c4 * 4 + 3] = x.w;
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (base + lane >= m) used |= 1u << i;
     }
 
     static_for<NB>([&](auto jc) {
@@ -180,13 +193,19 @@ __device__ __forceinline__ void lu_panel_body(float* Mp, int64_t ld, int m, int 
     __syncthreads();
     if (tid < 32 && gd[tid] >= 0) perm[gd[tid]] = pv;
 #pragma unroll
-    for (int i = 0; i < R; ++i) {
-        const int r = tid + i * NTHR;
-        if (r >= m) continue;
-        float* mp = Mp + (int64_t)pos_of[r] * ld;
+    for (int i = 0; i < R; ++i) {            // back through the stage, every row to its new position
+        const int base = i * NTHR + 64 * wave;
 #pragma unroll
         for (int c4 = 0; c4 < NB / 4; ++c4)
-            *reinterpret_cast<float4*>(mp + c4 * 4) = make_float4(P[i][c4 * 4], P[i][c4 * 4 + 1], P[i][c4 * 4 + 2], P[i][c4 * 4 + 3]);
+            *reinterpret_cast<float4*>(&st[lane * SP + c4 * 4]) = make_float4(P[i][c4 * 4], P[i][c4 * 4 + 1], P[i][c4 * 4 + 2], P[i][c4 * 4 + 3]);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int rr = base + 16 * q + srow;
+            const float4 x = *reinterpret_cast<const float4*>(&st[(16 * q + srow) * SP + schunk]);
+            if (rr < m) *reinterpret_cast<float4*>(Mp + (int64_t)pos_of[rr] * ld + schunk) = x;
+        }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
