@@ -5,12 +5,11 @@
 // overwrite B in place (C == B0, K == M): the LU path's multiplications by a diagonal-block inverse
 // (those shapes take the short kernel at the end of this file, which has the same property).
 //
-// A workgroup of 4 waves owns a 128 x 128 or 128 x 192 tile (whichever fills whole rounds of
-// the chip's CUs better) and walks K in steps of 32 through double-buffered LDS; a wave owns
-// 64 rows x half the tile's columns.  A lane reads four consecutive k of its A row with one
-// 16-byte LDS read and spends them on four successive MFMAs; the matching B values are single
-// dwords, contiguous across lanes; the fragments of the next 8 k are read while the MFMAs of the
-// current 8 run.
+// A workgroup of 4 waves owns a 128 x 96, 128 x 128 or 128 x 192 tile (whichever fills whole
+// rounds of the chip's CUs best) and walks K in steps of 32 through double-buffered LDS.  A lane
+// reads four consecutive k of its A row with one 16-byte LDS read and spends them on four
+// successive MFMAs; the matching B values are single dwords, contiguous across lanes; the
+// fragments of the next 8 k are read while the MFMAs of the current 8 run.
 #include "gelo_internal.h"
 
 namespace gelo {
@@ -33,12 +32,17 @@ struct F32Args {
     int subtract;              // C <- C - A B (the LU's trailing and substitution updates)
 };
 
-// BN = 128 or 192: the tile width is picked per shape so that the tile count fills whole rounds of the chip's CUs
-template <int BN>
+// BN = 96, 128 or 192: the tile width is picked per shape so that the tile count fills whole rounds of the chip's CUs.
+// WAVES_M x (4 / WAVES_M) waves: 2 x 2 for the wide tiles, 4 x 1 (a wave owns 32 rows x 96 columns) for the narrow one,
+// whose LDS footprint lets two workgroups share a CU and cover each other's barrier and LDS-store phases.
+template <int BN, int WAVES_M>
 __global__ __launch_bounds__(NT)
 void gemm_f32_kernel(F32Args g) {
     constexpr int B_PITCH = BN + 4;
-    constexpr int NTN = BN / 64;                 // 32-column MFMA blocks per wave
+    constexpr int WAVES_N = 4 / WAVES_M;
+    constexpr int WROWS = BM / WAVES_M, WCOLS = BN / WAVES_N;
+    constexpr int MTM = WROWS / 32;              // 32-row MFMA blocks per wave
+    constexpr int NTN = WCOLS / 32;              // 32-column MFMA blocks per wave
     constexpr int BCH = BN / 4;                  // 16-byte chunks per B row
     constexpr int BLD = BK * BCH / NT;           // B chunks per thread and K step
     __shared__ __attribute__((aligned(16))) float As[2][BM * A_PITCH];
@@ -55,7 +59,7 @@ void gemm_f32_kernel(F32Args g) {
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int j = lane & 31, grp = lane >> 5;
     const int KA = (g.K + 3) & ~3;
     const int k_tiles = (g.K + BK - 1) / BK;
@@ -130,9 +134,9 @@ void gemm_f32_kernel(F32Args g) {
         }
     };
 
-    f32x16_t acc[2][NTN];
+    f32x16_t acc[MTM][NTN];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < MTM; ++a)
 #pragma unroll
         for (int b = 0; b < NTN; ++b)
 #pragma unroll
@@ -146,18 +150,18 @@ void gemm_f32_kernel(F32Args g) {
         const int buf = kt & 1;
         if (kt + 1 < k_tiles) load_global(kt + 1);
         // fragments of sub-step ks + 1 are read while the 16 MFMAs of sub-step ks run
-        f32x4_t a4[2][2];
+        f32x4_t a4[2][MTM];
         float b1[2][4][NTN];
         auto load_frags = [&](int fb, int ks) {
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+            for (int mt = 0; mt < MTM; ++mt)
                 a4[fb][mt] = *reinterpret_cast<const f32x4_t*>(
-                    &As[buf][(wm * 64 + mt * 32 + j) * A_PITCH + ks * 8 + grp * 4]);
+                    &As[buf][(wm * WROWS + mt * 32 + j) * A_PITCH + ks * 8 + grp * 4]);
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll
                 for (int nt = 0; nt < NTN; ++nt)
-                    b1[fb][e][nt] = Bs[buf][(ks * 8 + grp * 4 + e) * B_PITCH + wn * (BN / 2) + nt * 32 + j];
+                    b1[fb][e][nt] = Bs[buf][(ks * 8 + grp * 4 + e) * B_PITCH + wn * WCOLS + nt * 32 + j];
         };
         load_frags(0, 0);
 #pragma unroll
@@ -167,7 +171,7 @@ void gemm_f32_kernel(F32Args g) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
+                for (int mt = 0; mt < MTM; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < NTN; ++nt)
                         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[fb][mt][e], b1[fb][e][nt], acc[mt][nt], 0, 0, 0);
@@ -177,14 +181,14 @@ void gemm_f32_kernel(F32Args g) {
     }
 
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int mt = 0; mt < MTM; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NTN; ++nt) {
-            const int col = n0 + wn * (BN / 2) + nt * 32 + j;
+            const int col = n0 + wn * WCOLS + nt * 32 + j;
             if (col < g.N) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int row = m0 + wm * 64 + mt * 32 + 8 * (v >> 2) + 4 * grp + (v & 3);
+                    const int row = m0 + wm * WROWS + mt * 32 + 8 * (v >> 2) + 4 * grp + (v & 3);
                     if (row < g.M) {
                         float* cp = g.C + (int64_t)row * g.ldc + col;
                         *cp = g.subtract ? *cp - acc[mt][nt][v] : acc[mt][nt][v];
@@ -292,17 +296,22 @@ hipError_t gemm_f32(const GemmOperands& o, hipStream_t stream) {
         hipLaunchKernelGGL(gemm_f32_short_kernel, dim3(a.tiles_n), dim3(NT), kShortLds, stream, a);
         return hipGetLastError();
     }
-    // tile width: the one whose tile count wastes less of the last round over the chip's 256 CUs
-    // (cost = rounds x tile width; e.g. 512 x 12288: 384 tiles of 128 = two rounds, 256 tiles of 192 = one)
+    // Tile width.  Large K: 128 x 96 tiles, two workgroups per CU (cost: rounds of 512 tiles), unless a wider
+    // tile wastes less of its last round over the 256 CUs; short K (the LU's updates, bound by the
+    // read-modify-write of C): the wide tiles only.
     constexpr int kCus = 256;
-    const int t128 = a.tiles_m * ((o.N + 127) / 128), t192 = a.tiles_m * ((o.N + 191) / 192);
-    const int64_t cost128 = (int64_t)((t128 + kCus - 1) / kCus) * 128, cost192 = (int64_t)((t192 + kCus - 1) / kCus) * 192;
-    if (cost192 < cost128) {
+    auto tiles = [&](int bn) { return a.tiles_m * ((o.N + bn - 1) / bn); };
+    const int64_t cost96 = (int64_t)((tiles(96) + 2 * kCus - 1) / (2 * kCus)) * 2 * 96 * 85 / 100;      // measured: 15% faster per flop
+    const int64_t cost128 = (int64_t)((tiles(128) + kCus - 1) / kCus) * 128, cost192 = (int64_t)((tiles(192) + kCus - 1) / kCus) * 192;
+    if (o.K >= 512 && cost96 <= cost128 && cost96 <= cost192) {
+        a.tiles_n = (o.N + 95) / 96;
+        hipLaunchKernelGGL((gemm_f32_kernel<96, 4>), dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
+    } else if (cost192 < cost128) {
         a.tiles_n = (o.N + 191) / 192;
-        hipLaunchKernelGGL(gemm_f32_kernel<192>, dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
+        hipLaunchKernelGGL((gemm_f32_kernel<192, 2>), dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
     } else {
         a.tiles_n = (o.N + 127) / 128;
-        hipLaunchKernelGGL(gemm_f32_kernel<128>, dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
+        hipLaunchKernelGGL((gemm_f32_kernel<128, 2>), dim3(a.tiles_m * a.tiles_n), dim3(NT), 0, stream, a);
     }
     return hipGetLastError();
 }
