@@ -468,6 +468,28 @@ def test_project_bf16_fast_path_edges(ctx, M, K, N, ldy_extra):
         assert torch.all(parent[:, N:] == 3.0)
 
 
+@pytest.mark.parametrize("M,K,N,ldy_extra", [
+    (512, 256, 12288, 0),      # 128 x 192 tiles (one round of the CUs)
+    (500, 1024, 6152, 8),      # 128 x 96 tiles, ragged in M and N
+    (300, 640, 1000, 0),       # 128 x 128 tiles, ragged
+    (100, 64, 200, 8),         # M, K <= 128: the 128 x 32 kernel
+    (128, 128, 96, 0),         # its largest shape
+    (37, 24, 48, 0),           # K not a multiple of 16: the general kernel on a tiny shape
+])
+def test_project_f32_tile_variants(ctx, M, K, N, ldy_extra):
+    """Every tile shape of the float GEMM, at sizes that leave ragged last tiles."""
+    rng = np.random.default_rng(M * 11 + N)
+    U = dev(rng.standard_normal((M, K)).astype(np.float32), "f32")
+    W = dev((0.05 * rng.standard_normal((K, N))).astype(np.float32), "f32")
+    parent = torch.full((M, N + ldy_extra), 3.0, dtype=torch.float32, device="cuda")
+    Y = parent[:, :N]
+    g.gelo_project(ctx, U, W, Y)
+    torch.cuda.synchronize()
+    assert o.rel_frobenius(f64(Y), o.project(f64(U), f64(W))) < TOL_STAGE["f32"]
+    if ldy_extra:
+        assert torch.all(parent[:, N:] == 3.0)
+
+
 def test_sampling_ahead_on_side_streams_matches_one_stream():
     """The mixing matrix does not depend on the data, so it may be drawn ahead on another stream and
     context while earlier batches run; the chain then waits for it through the mixing object.  The
