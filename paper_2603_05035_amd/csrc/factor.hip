@@ -246,7 +246,8 @@ __device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr,
     __shared__ float Ws[NB][NB];
     __shared__ float Wn[NB][NB];
     __shared__ float Ts[NB][NB];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wave index as a scalar: block numbers and their clamped offsets then live in scalar registers
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
     if (tid < NB * NB) Ts[tid >> 4][tid & 15] = T[tid];
 
