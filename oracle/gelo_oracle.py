@@ -40,6 +40,8 @@ _PHILOX_W1 = np.uint64(0xBB67AE85)
 STREAM_MIXING = 0        # Gaussian G that A is built from
 STREAM_SHIELD = 1        # Gaussian directions of the shield rows
 STREAM_PERTURB = 2       # second Gaussian of the conditioned non-orthogonal A
+STREAM_STRUCT_PERM = 3   # sort keys of the permutations of the structured orthogonal A
+STREAM_STRUCT_SIGN = 4   # its sign flips
 
 
 def philox4x32_10(counter, key):
@@ -229,6 +231,94 @@ def sample_conditioned(seed, batch_id, n, beta=CONDITIONED_BETA):
 
 
 # --------------------------------------------------------------------------
+# Structured orthogonal A.  The paper's Conclusion lists "faster constructions
+# for fresh, well-conditioned mixing (e.g. structured orthogonal transforms)" as
+# future work and gives no construction; the one below is this implementation's:
+#   A = P_R (B D_{R-1} P_{R-1}) ... (B D_1 P_1) (B D_0 P_0)
+# with P_r random row permutations, D_r random sign flips and B the normalised
+# Walsh-Hadamard transform on blocks of rows.  Every factor is orthogonal, so
+# A^-1 = A^T; applying A costs O(n log n) per column instead of O(n^2).
+# --------------------------------------------------------------------------
+STRUCTURED_ROUNDS = 3
+
+
+def philox_words(seed, batch_id, stream, sub, count):
+    """`count` raw 32-bit words: word i is output i mod 4 of Philox block i div 4, block q drawn with
+    counter (q, stream<<8 | sub, batch_id low, batch_id high) and key (seed low, seed high)."""
+    q = np.arange((count + 3) // 4, dtype=np.uint64)
+    c1 = np.uint64(((int(stream) & 0xFFFFFF) << 8) | (int(sub) & 0xFF))
+    c2 = np.uint64(int(batch_id) & 0xFFFFFFFF)
+    c3 = np.uint64((int(batch_id) >> 32) & 0xFFFFFFFF)
+    key = (int(seed) & 0xFFFFFFFF, (int(seed) >> 32) & 0xFFFFFFFF)
+    return np.stack(philox4x32_10((q, c1, c2, c3), key), axis=1).reshape(-1)[:count]
+
+
+def walsh_hadamard(m):
+    """Sylvester's m x m matrix of +-1 (m a power of two): H_1 = [1], H_2m = [[H_m, H_m], [H_m, -H_m]]."""
+    if m < 1 or m & (m - 1):
+        raise ValueError("power of two expected")
+    Hm = np.ones((1, 1))
+    while Hm.shape[0] < m:
+        Hm = np.block([[Hm, Hm], [Hm, -Hm]])
+    return Hm
+
+
+def hadamard_blocks(n):
+    """The powers of two of the binary expansion of n, largest first: the row blocks of B.
+    (n = 2150 -> 2048, 64, 32, 4, 2.)"""
+    return [1 << b for b in range(int(n).bit_length() - 1, -1, -1) if (n >> b) & 1]
+
+
+def block_hadamard(n):
+    """B: block-diagonal n x n matrix, one block H_m / sqrt(m) per entry of hadamard_blocks(n), in that order."""
+    B = np.zeros((n, n))
+    at = 0
+    for m in hadamard_blocks(n):
+        B[at:at + m, at:at + m] = walsh_hadamard(m) / math.sqrt(m)
+        at += m
+    return B
+
+
+def permutation_from_keys(keys):
+    """The permutation that sorts (key, index) pairs in ascending order: entry j is the index of the
+    j-th smallest key, equal keys in index order."""
+    return np.argsort(np.asarray(keys, dtype=np.uint32), kind="stable")
+
+
+def structured_tables(seed, batch_id, n, rounds=STRUCTURED_ROUNDS):
+    """The random draws behind one structured A: `rounds + 1` permutations (each from n Philox words
+    used as sort keys, stream STREAM_STRUCT_PERM, sub-stream = its number) and `rounds` sign vectors
+    (top bit of the words of stream STREAM_STRUCT_SIGN set -> -1)."""
+    perms = np.stack([permutation_from_keys(philox_words(seed, batch_id, STREAM_STRUCT_PERM, r, n))
+                      for r in range(rounds + 1)])
+    signs = np.stack([np.where(philox_words(seed, batch_id, STREAM_STRUCT_SIGN, r, n) >> np.uint32(31), -1.0, 1.0)
+                      for r in range(rounds)]) if rounds > 0 else np.zeros((0, n))
+    return perms, signs
+
+
+def structured_matrix(perms, signs):
+    """Dense A = P_R (B D_{R-1} P_{R-1}) ... (B D_0 P_0) from its factors, each written out as a matrix:
+    (P_r x)[j] = x[perms[r][j]], D_r = diag(signs[r])."""
+    perms = np.asarray(perms)
+    n = perms.shape[1]
+    rounds = perms.shape[0] - 1
+    B = block_hadamard(n)
+    eye = np.eye(n)
+    A = eye
+    for r in range(rounds):
+        P = eye[perms[r]]                       # row j of P picks x[perms[r][j]]
+        D = np.diag(np.asarray(signs[r], dtype=np.float64))
+        A = B @ (D @ (P @ A))
+    return eye[perms[rounds]] @ A
+
+
+def sample_structured(seed, batch_id, n, rounds=STRUCTURED_ROUNDS):
+    """Fresh structured orthogonal A for one batch; returns (A, A^-1 = A^T)."""
+    A = structured_matrix(*structured_tables(seed, batch_id, n, rounds))
+    return A, A.T.copy()
+
+
+# --------------------------------------------------------------------------
 # Shield rows (Section 3.2.1, Mitigation 2, eqs. 7-9).
 # --------------------------------------------------------------------------
 NORM_MEDIAN = 0
@@ -288,6 +378,7 @@ def plain_projection(H, W):
 KIND_ORTHOGONAL = 0
 KIND_GAUSSIAN = 1
 KIND_CONDITIONED = 2
+KIND_STRUCTURED = 3
 
 
 def sample_mixing(kind, seed, batch_id, n, cond_max=1e3, max_attempts=64):
@@ -301,6 +392,9 @@ def sample_mixing(kind, seed, batch_id, n, cond_max=1e3, max_attempts=64):
     if kind == KIND_CONDITIONED:
         A, A_inv, kappa = sample_conditioned(seed, batch_id, n)
         return A, A_inv, {"attempt": 0, "kappa": kappa}
+    if kind == KIND_STRUCTURED:
+        A, A_inv = sample_structured(seed, batch_id, n)
+        return A, A_inv, {"attempt": 0, "kappa": 1.0}
     raise ValueError("unknown kind")
 
 
