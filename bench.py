@@ -26,11 +26,21 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}          # MI355X dense matrix peaks
-KIND_NAME = {0: "orthogonal", 1: "gaussian", 2: "conditioned"}
+KIND_NAME = {0: "orthogonal", 1: "gaussian", 2: "conditioned", 3: "structured"}
+
+
+STRUCTURED_ROUNDS = 3
+
+
+def butterfly_adds(n):
+    """additions of one block Walsh-Hadamard transform of a column: m log2 m per block of the binary expansion"""
+    return float(sum((1 << b) * b for b in range(n.bit_length()) if (n >> b) & 1))
 
 
 def chain_flops(w):
     n, nd, d, p = w.n, w.n_data, w.d, w.p
+    if w.kind == 3:      # structured A: mix and unmix are butterflies, only the projection is a product
+        return 2.0 * n * d * p + STRUCTURED_ROUNDS * butterfly_adds(n) * (d + p)
     return 2.0 * n * n * d + 2.0 * n * d * p + 2.0 * nd * n * p
 
 
@@ -38,7 +48,7 @@ def gen_flops(w, attempts=1):
     n = float(w.n)
     qr = 8.0 / 3.0 * n ** 3            # Householder QR with explicit Q
     lu = 2.0 * n ** 3                  # LU + explicit inverse
-    return {0: qr, 1: lu * attempts, 2: qr + lu}[w.kind]
+    return {0: qr, 1: lu * attempts, 2: qr + lu, 3: 0.0}[w.kind]   # structured: sorting keys, no arithmetic to count
 
 
 CAL_ELEMS = 1 << 28                                   # fp32 elements of the calibration copy: 1 GiB read, 1 GiB written
@@ -322,7 +332,9 @@ def main() -> int:
         t_cpu = time.perf_counter() - t0
         ns = rows + ks
         f_chain_s = 2.0 * ns * ns * d + 2.0 * ns * d * p + 2.0 * rows * ns * p
-        f_gen_s = {0: 8.0 / 3.0, 1: 2.0 * (ref["info"]["attempt"] + 1), 2: 8.0 / 3.0 + 2.0}[w.kind] * float(ns) ** 3
+        if w.kind == 3:
+            f_chain_s = 2.0 * ns * d * p + STRUCTURED_ROUNDS * butterfly_adds(ns) * (d + p)
+        f_gen_s = {0: 8.0 / 3.0, 1: 2.0 * (ref["info"]["attempt"] + 1), 2: 8.0 / 3.0 + 2.0, 3: 0.0}[w.kind] * float(ns) ** 3
         result["cpu_baseline"] = {
             "value": (f_chain_s + f_gen_s) / t_cpu / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
             "seconds": t_cpu,

@@ -64,8 +64,17 @@ typedef enum { GELO_F32 = 0, GELO_BF16 = 1 } gelo_dtype;
 /* How A is drawn (Section 3.2 step 1.2; Section 3.2.1).
  *  ORTHOGONAL   A = Q diag(sign r_ii) from the Householder QR of a Philox Gaussian; A^-1 = A^T.
  *  GAUSSIAN     A = G/sqrt(n); redrawn until kappa_2(A) <= cond_max; A^-1 from a pivoted LU.
- *  CONDITIONED  A = Q + 0.25 G2/sqrt(n): dense, A^T A != I, kappa of a few; A^-1 from a pivoted LU. */
-typedef enum { GELO_ORTHOGONAL = 0, GELO_GAUSSIAN = 1, GELO_CONDITIONED = 2 } gelo_kind;
+ *  CONDITIONED  A = Q + 0.25 G2/sqrt(n): dense, A^T A != I, kappa of a few; A^-1 from a pivoted LU.
+ *  STRUCTURED   A = P_3 (B D_2 P_2)(B D_1 P_1)(B D_0 P_0): Philox-drawn row permutations P_r and sign
+ *               flips D_r around B, the normalised Walsh-Hadamard transform on the row blocks of the
+ *               binary expansion of n.  Orthogonal (A^-1 = A^T), never formed: mix and unmix apply it in
+ *               O(n log n) per column and drawing it costs O(n^2 / 64) comparisons.  The "structured
+ *               orthogonal transforms" the paper's Conclusion proposes for cheaper fresh mixing, in a
+ *               construction of this library's own.  It leaks what every orthogonal A leaks
+ *               (Section 3.2.1 eqs. 5-6: U^T U = H^T H, the spectrum of H H^T) and comes from a finite
+ *               family, 4 permutations and 3 n sign bits; its resistance to the attacks of Section 4 has
+ *               not been measured by anyone.  gelo_mixing_export builds the dense A for inspection. */
+typedef enum { GELO_ORTHOGONAL = 0, GELO_GAUSSIAN = 1, GELO_CONDITIONED = 2, GELO_STRUCTURED = 3 } gelo_kind;
 
 /* Row-norm statistic of H that the shield rows are scaled by. */
 typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;

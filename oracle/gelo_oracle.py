@@ -312,6 +312,29 @@ def structured_matrix(perms, signs):
     return eye[perms[rounds]] @ A
 
 
+def structured_apply(perms, signs, X, transposed=False):
+    """A X (or A^T X) for an n x m matrix X, factor by factor in the order of the definition, without
+    forming A: A^T = P_0^T D_0 B P_1^T D_1 B ... B P_R^T  (B is symmetric, (P^T x)[perm[j]] = x[j])."""
+    perms = np.asarray(perms)
+    X = np.array(X, dtype=np.float64, copy=True)
+    n = perms.shape[1]
+    rounds = perms.shape[0] - 1
+    B = block_hadamard(n)
+    if not transposed:
+        for r in range(rounds):
+            X = B @ (np.asarray(signs[r], dtype=np.float64)[:, None] * X[perms[r]])
+        return X[perms[rounds]]
+    out = np.empty_like(X)
+    out[perms[rounds]] = X
+    X = out
+    for r in range(rounds - 1, -1, -1):
+        X = np.asarray(signs[r], dtype=np.float64)[:, None] * (B @ X)
+        out = np.empty_like(X)
+        out[perms[r]] = X
+        X = out
+    return X
+
+
 def sample_structured(seed, batch_id, n, rounds=STRUCTURED_ROUNDS):
     """Fresh structured orthogonal A for one batch; returns (A, A^-1 = A^T)."""
     A = structured_matrix(*structured_tables(seed, batch_id, n, rounds))

@@ -12,7 +12,7 @@ from ctypes import (POINTER, byref, c_char_p, c_double, c_float, c_int, c_int64,
 import torch
 
 GELO_F32, GELO_BF16 = 0, 1
-GELO_ORTHOGONAL, GELO_GAUSSIAN, GELO_CONDITIONED = 0, 1, 2
+GELO_ORTHOGONAL, GELO_GAUSSIAN, GELO_CONDITIONED, GELO_STRUCTURED = 0, 1, 2, 3
 GELO_NORM_MEDIAN, GELO_NORM_MEAN = 0, 1
 GELO_OK = 0
 STATUS_NAMES = ["GELO_OK", "GELO_EINVAL", "GELO_ESHAPE", "GELO_EDTYPE", "GELO_EALIGN", "GELO_ENOMEM",
@@ -171,13 +171,15 @@ def gelo_qkv_forward(ctx, kind: int, H: torch.Tensor, W: torch.Tensor, Z: torch.
     return Z
 
 
-def gelo_mixing_export(ctx, mixing, n: int, k_shield: int, d: int, want_shields: bool = True, stream=None):
-    """Test hook: (A, A_inv, S, attempt, kappa) with A, A_inv, S float32 GPU tensors."""
-    A = torch.empty((n, n), dtype=torch.float32, device="cuda")
-    A_inv = torch.empty((n, n), dtype=torch.float32, device="cuda")
+def gelo_mixing_export(ctx, mixing, n: int, k_shield: int, d: int, want_shields: bool = True,
+                       want_matrices: bool = True, stream=None):
+    """Test hook: (A, A_inv, S, attempt, kappa) with A, A_inv, S float32 GPU tensors (None where not asked for)."""
+    A = torch.empty((n, n), dtype=torch.float32, device="cuda") if want_matrices else None
+    A_inv = torch.empty((n, n), dtype=torch.float32, device="cuda") if want_matrices else None
     S = torch.empty((k_shield, d), dtype=torch.float32, device="cuda") if (want_shields and k_shield > 0) else None
     attempt, kappa = c_int(-1), c_float(0.0)
     _check(ctx, load_library().gelo_mixing_export(
-        ctx, mixing, c_void_p(A.data_ptr()), c_void_p(A_inv.data_ptr()),
+        ctx, mixing, c_void_p(A.data_ptr()) if A is not None else None,
+        c_void_p(A_inv.data_ptr()) if A_inv is not None else None,
         c_void_p(S.data_ptr()) if S is not None else None, byref(attempt), byref(kappa), _stream(stream)))
     return A, A_inv, S, attempt.value, kappa.value

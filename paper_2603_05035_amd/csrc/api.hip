@@ -27,8 +27,10 @@ struct gelo_mixing {
     int64_t ldk;                 // leading dimension of A / A^-1 (n rounded up to 64), zero padded
     void* block;                 // one device allocation holding everything below
     size_t block_bytes;
-    float* A32; float* Ainv32;
+    float* A32; float* Ainv32;   // dense kinds only
     uint16_t* A16; uint16_t* Ainv16;
+    uint32_t* table;             // STRUCTURED only: its permutations and sign flips, nothing dense is kept
+    bool structured;
     float* GS;                   // k x d shield directions
     float* gsnorm;               // k
     void* S;                     // k x d shield rows in the compute dtype
@@ -93,18 +95,20 @@ gelo_status grow(gelo_ctx* ctx, void** buf, size_t* have, size_t need) {
     return GELO_OK;
 }
 
-gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, gelo_mixing** out) {
+gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, bool structured, gelo_mixing** out) {
     for (gelo_mixing* m : ctx->pool) {
-        if (!m->in_use && m->n_data == n_data && m->k == k && m->d == d && m->dtype == dtype) { *out = m; return GELO_OK; }
+        if (!m->in_use && m->n_data == n_data && m->k == k && m->d == d && m->dtype == dtype && m->structured == structured) { *out = m; return GELO_OK; }
     }
     gelo_mixing* m = new (std::nothrow) gelo_mixing();
     if (!m) return fail(ctx, GELO_ENOMEM, "host allocation failed");
-    m->n_data = n_data; m->k = k; m->n = n_data + k; m->d = d; m->dtype = dtype;
+    m->n_data = n_data; m->k = k; m->n = n_data + k; m->d = d; m->dtype = dtype; m->structured = structured;
     m->ldk = round_up(m->n, 64);
-    const size_t mat32 = up256((size_t)m->n * m->ldk * 4), mat16 = up256((size_t)m->n * m->ldk * 2);
+    const size_t mat32 = structured ? 0 : up256((size_t)m->n * m->ldk * 4);
+    const size_t mat16 = structured ? 0 : up256((size_t)m->n * m->ldk * 2);
+    const size_t tab = structured ? up256((size_t)(kStructuredRounds + 1) * m->n * 4) : 0;
     const size_t gs = up256((size_t)(k > 0 ? k : 1) * d * 4), s = up256((size_t)(k > 0 ? k : 1) * d * elem_size(dtype));
     const size_t small = up256((size_t)(k + 1) * 4) + up256((size_t)n_data * 4) + 256;
-    m->block_bytes = 2 * mat32 + (dtype == GELO_BF16 ? 2 * mat16 : 0) + gs + s + small;
+    m->block_bytes = 2 * mat32 + (dtype == GELO_BF16 ? 2 * mat16 : 0) + tab + gs + s + small;
     hipError_t e = hipMalloc(&m->block, m->block_bytes);
     if (e != hipSuccess) { delete m; return fail(ctx, GELO_ENOMEM, "hipMalloc(%zu) failed: %s", m->block_bytes, hipGetErrorString(e)); }
     char* p = (char*)m->block;
@@ -112,6 +116,7 @@ gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, g
     m->Ainv32 = (float*)p; p += mat32;
     m->A16 = m->Ainv16 = nullptr;
     if (dtype == GELO_BF16) { m->A16 = (uint16_t*)p; p += mat16; m->Ainv16 = (uint16_t*)p; p += mat16; }
+    m->table = (uint32_t*)p; p += tab;
     m->GS = (float*)p; p += gs;
     m->S = p; p += s;
     m->gsnorm = (float*)p; p += up256((size_t)(k + 1) * 4);
@@ -181,7 +186,8 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
     ctx->host_scalars = nullptr; ctx->host_flag = nullptr;
     if (hipHostMalloc((void**)&ctx->host_scalars, 64, hipHostMallocDefault) != hipSuccess) { delete ctx; return GELO_ENOMEM; }
     ctx->host_flag = (int*)(ctx->host_scalars + 8);
-    if (gemm_bf16_init() != hipSuccess || gemm_f32_init() != hipSuccess || lu_init() != hipSuccess) {
+    if (gemm_bf16_init() != hipSuccess || gemm_f32_init() != hipSuccess || lu_init() != hipSuccess ||
+        structured_init() != hipSuccess) {
         hipHostFree(ctx->host_scalars); delete ctx; return GELO_EHIP;
     }
     *out = ctx;
@@ -212,13 +218,16 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
     if (!ctx) return GELO_EINVAL;
     if (!out) return fail(ctx, GELO_EINVAL, "out is NULL");
     *out = nullptr;
-    if (kind != GELO_ORTHOGONAL && kind != GELO_GAUSSIAN && kind != GELO_CONDITIONED) return fail(ctx, GELO_EINVAL, "unknown kind %d", (int)kind);
+    if (kind != GELO_ORTHOGONAL && kind != GELO_GAUSSIAN && kind != GELO_CONDITIONED && kind != GELO_STRUCTURED)
+        return fail(ctx, GELO_EINVAL, "unknown kind %d", (int)kind);
     if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
     if (n_data < 1 || k_shield < 0 || d < 1) return fail(ctx, GELO_EINVAL, "n_data=%d k_shield=%d d=%d", n_data, k_shield, d);
     if (d % 8 != 0) return fail(ctx, GELO_EALIGN, "d=%d is not a multiple of 8", d);
     const int64_t n64 = (int64_t)n_data + k_shield;
     if (n64 > GELO_MAX_N) return fail(ctx, GELO_ESHAPE, "n = n_data + k_shield = %lld exceeds GELO_MAX_N = %d", (long long)n64, GELO_MAX_N);
     const int n = (int)n64;
+    if (kind == GELO_STRUCTURED && n > structured_max_rows())
+        return fail(ctx, GELO_ESHAPE, "n = %d exceeds what one workgroup's LDS holds for the structured kind (%d)", n, structured_max_rows());
     if (kind == GELO_GAUSSIAN) {
         if (!(cond_max >= 1.0)) return fail(ctx, GELO_EINVAL, "cond_max=%g must be >= 1", cond_max);
         if (max_attempts < 1 || max_attempts > GELO_MAX_ATTEMPTS) return fail(ctx, GELO_EINVAL, "max_attempts=%d outside 1..%d", max_attempts, GELO_MAX_ATTEMPTS);
@@ -228,12 +237,16 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
 
     GELO_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
-    gelo_status st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, factor_workspace_bytes(n));
-    if (st != GELO_OK) return st;
-    FactorWorkspace ws;
-    factor_workspace_carve(ctx->factor_ws, n, &ws);
+    const bool structured = kind == GELO_STRUCTURED;
+    gelo_status st = GELO_OK;
+    FactorWorkspace ws = {};
+    if (!structured) {
+        st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, factor_workspace_bytes(n));
+        if (st != GELO_OK) return st;
+        factor_workspace_carve(ctx->factor_ws, n, &ws);
+    }
     gelo_mixing* m = nullptr;
-    st = acquire_mixing(ctx, n_data, k_shield, d, dtype, &m);
+    st = acquire_mixing(ctx, n_data, k_shield, d, dtype, structured, &m);
     if (st != GELO_OK) return st;
     if (m->last_stream != nullptr || m->mixed) GELO_HIP(ctx, hipStreamWaitEvent(s, m->released, 0));
 
@@ -251,7 +264,9 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
         return e;
     };
 
-    if (kind == GELO_ORTHOGONAL) {
+    if (structured) {
+        GELO_HIP(ctx, structured_tables(m->table, n, kStructuredRounds, ps, s));
+    } else if (kind == GELO_ORTHOGONAL) {
         GELO_HIP(ctx, orthogonal_into_X());
         // A = Q diag(sign r_ii); A^-1 = A^T
         GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s));
@@ -327,6 +342,16 @@ gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh,
         GELO_HIP(ctx, norm_statistic(m->rownorm, m->n_data, (int)stat, m->stat, s));
         GELO_HIP(ctx, make_shields(m->GS, m->d, m->gsnorm, m->stat, shield_scale, m->k, m->d, m->S, bf, m->d, s));
     }
+    if (m->structured) {
+        StructuredOperands o;
+        o.in0 = H; o.ld0 = ldh; o.rows0 = m->n_data;
+        o.in1 = m->S; o.ld1 = m->d;
+        o.out = U; o.ldo = ldu; o.rows_out = m->n;
+        o.table = m->table; o.n = m->n; o.ncols = m->d; o.rounds = kStructuredRounds; o.transposed = false;
+        GELO_HIP(ctx, structured_apply(o, bf, s));
+        m->mixed = true; m->last_stream = s;
+        return GELO_OK;
+    }
     GemmOperands g;
     g.A = bf ? (const void*)m->A16 : (const void*)m->A32; g.lda = m->ldk;
     g.B0 = H; g.ldb0 = ldh; g.K0 = m->n_data;
@@ -375,6 +400,16 @@ gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* m, int p, const void* Y, int6
     hipStream_t s = (hipStream_t)stream;
     if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
     const bool bf = m->dtype == GELO_BF16;
+    if (m->structured) {
+        StructuredOperands o;
+        o.in0 = Y; o.ld0 = ldy; o.rows0 = m->n;
+        o.in1 = nullptr; o.ld1 = 0;
+        o.out = Z; o.ldo = ldz; o.rows_out = m->n_data;      // the shield rows of A^T Y are never stored
+        o.table = m->table; o.n = m->n; o.ncols = p; o.rounds = kStructuredRounds; o.transposed = true;
+        GELO_HIP(ctx, structured_apply(o, bf, s));
+        m->consumed = true; m->last_stream = s;
+        return GELO_OK;
+    }
     GemmOperands g;
     g.A = bf ? (const void*)m->Ainv16 : (const void*)m->Ainv32; g.lda = m->ldk;   // rows 0..n_data-1 of A^-1
     g.B0 = Y; g.ldb0 = ldy; g.K0 = m->n;
@@ -435,8 +470,29 @@ gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* m, float* A, fl
     GELO_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
     if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
-    if (A) GELO_HIP(ctx, export_dense(m->A32, 0, m->ldk, m->n, m->n, A, s));
-    if (A_inv) GELO_HIP(ctx, export_dense(m->Ainv32, 0, m->ldk, m->n, m->n, A_inv, s));
+    if (m->structured && (A || A_inv)) {
+        // the dense matrices exist only here: A = (the transform applied to the identity), in float
+        const int64_t ldn = round_up(m->n, 8);
+        const size_t mat = up256((size_t)m->n * ldn * 4);
+        gelo_status st = grow(ctx, &ctx->chain_ws, &ctx->chain_ws_bytes, 2 * mat);
+        if (st != GELO_OK) return st;
+        float* eye = (float*)ctx->chain_ws;
+        float* res = (float*)((char*)ctx->chain_ws + mat);
+        GELO_HIP(ctx, set_identity(eye, ldn, m->n, s));
+        for (int t = 0; t < 2; ++t) {
+            float* dst = t == 0 ? A : A_inv;
+            if (!dst) continue;
+            StructuredOperands o;
+            o.in0 = eye; o.ld0 = ldn; o.rows0 = m->n; o.in1 = nullptr; o.ld1 = 0;
+            o.out = res; o.ldo = ldn; o.rows_out = m->n;
+            o.table = m->table; o.n = m->n; o.ncols = (int)ldn; o.rounds = kStructuredRounds; o.transposed = t == 1;
+            GELO_HIP(ctx, structured_apply(o, 0, s));
+            GELO_HIP(ctx, export_dense(res, 0, ldn, m->n, m->n, dst, s));
+        }
+    } else {
+        if (A) GELO_HIP(ctx, export_dense(m->A32, 0, m->ldk, m->n, m->n, A, s));
+        if (A_inv) GELO_HIP(ctx, export_dense(m->Ainv32, 0, m->ldk, m->n, m->n, A_inv, s));
+    }
     if (S && m->k > 0) GELO_HIP(ctx, export_dense(m->S, m->dtype == GELO_BF16, m->d, m->k, m->d, S, s));
     if (attempt) *attempt = m->attempt;
     if (kappa) {

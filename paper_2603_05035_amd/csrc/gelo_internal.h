@@ -51,6 +51,23 @@ struct PhiloxStream {
     uint32_t key0, key1;            // seed low / high
     uint32_t c1, c2, c3;            // (stream << 8 | attempt), batch id low, batch id high
 };
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies
+// and a word permutation, key advanced by Weyl constants between rounds.
+__device__ __forceinline__ void philox4x32_10(uint32_t& c0, uint32_t& c1, uint32_t& c2, uint32_t& c3,
+                                              uint32_t k0, uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+}
 // The QR works on 16 x 16 tiles: a tile is 256 contiguous floats ordered [column in tile][row in
 // tile], tiles are ordered column-block major; element (r, c) of a matrix with `tile_rows` tile
 // rows sits at the index below.  A wave that owns a tile in the accumulator layout of
@@ -86,6 +103,28 @@ hipError_t emit_matrix(const float* src, int64_t lds, int src_tiled, const float
 // dense float copy out[r * cols + c] = (float) src[r * ld + c]
 hipError_t export_dense(const void* src, int is_bf16, int64_t ld, int rows, int cols, float* out,
                         hipStream_t stream);
+
+// ------------------------------------------------- structured orthogonal A --
+constexpr int kStructuredRounds = 3;
+// table[(rounds + 1) x n]: the permutations (low 31 bits) and sign flips (top bit) of one structured
+// A = P_R (B D_{R-1} P_{R-1}) ... (B D_0 P_0), drawn from the Philox streams of (seed, batch id) in ps
+// (ps.c1 is not used: the streams are fixed).
+hipError_t structured_tables(uint32_t* table, int n, int rounds, PhiloxStream ps, hipStream_t stream);
+// out = A x (transposed == 0) or A^T x (transposed != 0) for the n x ncols operand x whose rows
+// [0, rows0) come from in0 and rows [rows0, n) from in1 (may be null when rows0 == n); result rows
+// >= rows_out are dropped.  float or bf16 throughout; ncols a multiple of 4 and every row start
+// 16-byte (float) / 8-byte (bf16) aligned; n <= structured_max_rows().
+struct StructuredOperands {
+    const void* in0; int64_t ld0; int rows0;
+    const void* in1; int64_t ld1;
+    void* out; int64_t ldo; int rows_out;
+    const uint32_t* table;
+    int n, ncols, rounds;
+    bool transposed;
+};
+hipError_t structured_apply(const StructuredOperands& o, int is_bf16, hipStream_t stream);
+hipError_t structured_init();
+int structured_max_rows();
 
 // --------------------------------------------------------- factorisations --
 // Workspace for one n_pad x ld float problem (n_pad = round_up(n, kPanel), ld = round_up(n, 64)).

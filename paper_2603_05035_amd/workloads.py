@@ -19,6 +19,7 @@ import numpy as np
 KIND_ORTHOGONAL = 0
 KIND_GAUSSIAN = 1
 KIND_CONDITIONED = 2
+KIND_STRUCTURED = 3
 
 
 @dataclass(frozen=True)
@@ -61,6 +62,10 @@ WORKLOADS = {
     # p = d and a fresh A of its own (the method offloads every linear projection Q, K, V and O)
     "llama7b_bf16_oproj": Workload("llama7b_bf16_oproj", "bf16", 2048, 102, 4096, 4096,
                                    KIND_ORTHOGONAL, 8, 0xC5),
+    # the prefill batch again with the structured orthogonal A (permutations, sign flips and block
+    # Walsh-Hadamard rounds: nothing to factorise, mix and unmix in O(n log n) per column)
+    "llama7b_bf16_prefill_structured": Workload("llama7b_bf16_prefill_structured", "bf16", 2048, 102, 4096, 12288,
+                                                KIND_STRUCTURED, 8, 0xC6),
 }
 
 

@@ -149,3 +149,13 @@ def test_chain_identity_and_gram_leak_with_structured_a():
     assert o.rel_frobenius(out["U"].T @ out["U"], H.T @ H + S.T @ S) < 1e-13          # eq. 9: orthogonal A
     U0 = o.mix(o.sample_structured(3, 0, 48)[0], H)
     assert o.rel_frobenius(U0.T @ U0, H.T @ H) < 1e-13                                # eq. 5: the Gram leak stays
+
+
+def test_structured_apply_equals_the_dense_matrix():
+    rng = np.random.default_rng(12)
+    for n in (3, 22, 150):
+        perms, signs = o.structured_tables(seed=9, batch_id=n, n=n)
+        A = o.structured_matrix(perms, signs)
+        X = rng.standard_normal((n, 7))
+        assert np.abs(o.structured_apply(perms, signs, X) - A @ X).max() < 1e-13
+        assert np.abs(o.structured_apply(perms, signs, X, transposed=True) - A.T @ X).max() < 1e-13
