@@ -32,7 +32,11 @@ void structured_tables_kernel(uint32_t* table, int n, int rounds, PhiloxStream p
     for (int q = tid; q * 4 < n; q += 256) {
         uint32_t c0 = (uint32_t)q, c1 = (kStreamPerm << 8) | (uint32_t)b, c2 = ps.c2, c3 = ps.c3;
         philox4x32_10(c0, c1, c2, c3, ps.key0, ps.key1);
-        keys[4 * q] = c0; keys[4 * q + 1] = c1; keys[4 * q + 2] = c2; keys[4 * q + 3] = c3;
+        // past the end: the largest key, so that with its index >= n such a pair is above every real one
+        keys[4 * q] = c0;
+        keys[4 * q + 1] = 4 * q + 1 < n ? c1 : 0xFFFFFFFFu;
+        keys[4 * q + 2] = 4 * q + 2 < n ? c2 : 0xFFFFFFFFu;
+        keys[4 * q + 3] = 4 * q + 3 < n ? c3 : 0xFFFFFFFFu;
     }
     __syncthreads();
     const int slot = tid & 63, part = tid >> 6;
@@ -43,8 +47,10 @@ void structured_tables_kernel(uint32_t* table, int n, int rounds, PhiloxStream p
         const uint4* keys4 = reinterpret_cast<const uint4*>(keys);
         const int quads = (n + 3) / 4, chunk = (quads + 3) / 4;
         const int lo = part * chunk, hi = min(quads, lo + chunk);
-        auto is_below = [&](uint32_t kk, int k) { return (k < n && (kk < ki || (kk == ki && k < i))) ? 1 : 0; };
-#pragma unroll 4
+        // (key, index) pairs compared as 64-bit numbers: no branch on equal keys
+        const uint64_t mine = ((uint64_t)ki << 32) | (uint32_t)i;
+        auto is_below = [&](uint32_t kk, int k) { return ((((uint64_t)kk << 32) | (uint32_t)k) < mine) ? 1 : 0; };
+#pragma unroll 8
         for (int qd = lo; qd < hi; ++qd) {                   // every lane reads the same four keys: a broadcast
             const uint4 kk = keys4[qd];
             below += is_below(kk.x, 4 * qd) + is_below(kk.y, 4 * qd + 1) + is_below(kk.z, 4 * qd + 2) + is_below(kk.w, 4 * qd + 3);
@@ -92,10 +98,10 @@ __device__ __forceinline__ float4 scaled(float4 v, float s) { return make_float4
 __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 __device__ __forceinline__ float4 sub4(float4 a, float4 b) { return make_float4(a.x - b.x, a.y - b.y, a.z - b.z, a.w - b.w); }
 
-__device__ __forceinline__ uint32_t bf16_round(float f) {           // round to nearest even, NaN kept quiet
-    const uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    bf16x2_t v = {(__bf16)lo, (__bf16)hi};                  // round to nearest even
+    return __builtin_bit_cast(uint32_t, v);
 }
 
 template <typename T>
@@ -110,18 +116,37 @@ __device__ __forceinline__ float4 load_quad<uint16_t>(const uint16_t* p) {
 }
 __device__ __forceinline__ void store_quad(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 __device__ __forceinline__ void store_quad(uint16_t* p, float4 v) {
-    uint2 o;
-    o.x = bf16_round(v.x) | (bf16_round(v.y) << 16);
-    o.y = bf16_round(v.z) | (bf16_round(v.w) << 16);
-    *reinterpret_cast<uint2*>(p) = o;
+    *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(v.x, v.y), pack_bf16x2(v.z, v.w));
 }
 
-// One pass of the block Walsh-Hadamard transform: the NS butterfly stages s0 .. s0 + NS - 1 (stage s
-// pairs rows 2^s apart and applies to a row only while s is below its block's exponent).  A work item
-// is one quad of columns of the 2^NS rows base + j 2^s0.  If their common aligned range of 2^(s0+NS)
-// rows lies in one block, every stage applies to every row (the usual case: registers, one LDS read
-// and write per row); otherwise the item straddles smaller blocks at the end of the strip and goes
-// stage by stage over LDS, each pair predicated on its rows' exponent.
+// NS butterfly stages s0 .. s0 + NS - 1 on the 2^NS rows first + j 2^s0 of quad column q, which the
+// caller knows to lie in one block of at least 2^(s0 + NS) rows: registers, one LDS read and one
+// write per row.
+template <int QW, int NS>
+__device__ __forceinline__ void butterfly_rows(float4* X, int first, int s0, int q) {
+    constexpr int RW = 1 << NS;
+    float4 v[RW];
+#pragma unroll
+    for (int j = 0; j < RW; ++j) v[j] = X[lds_row(first + (j << s0)) * QW + q];
+#pragma unroll
+    for (int k = 0; k < NS; ++k)
+#pragma unroll
+        for (int j = 0; j < RW; ++j)
+            if (!(j & (1 << k))) {
+                const float4 a = v[j], c = v[j | (1 << k)];
+                v[j] = add4(a, c);
+                v[j | (1 << k)] = sub4(a, c);
+            }
+#pragma unroll
+    for (int j = 0; j < RW; ++j) X[lds_row(first + (j << s0)) * QW + q] = v[j];
+}
+
+// One pass of the block Walsh-Hadamard transform: stages s0 .. s0 + NS - 1 (stage s pairs rows 2^s
+// apart and applies to a row only while s is below its block's exponent).  A work item is one quad
+// of columns of the 2^NS rows base + j 2^s0.  Usually their aligned range of 2^(s0 + NS) rows lies
+// in one block and the item is one butterfly.  At the end of the strip it straddles smaller blocks:
+// then it is cut, block by block, into the shorter butterflies each block still needs in this pass
+// (blocks come in decreasing size, so every piece starts at a multiple of its own length).
 template <int QW, int NS>
 __device__ __forceinline__ void hadamard_pass(float4* X, int n, int s0) {
     constexpr int RW = 1 << NS;
@@ -134,45 +159,19 @@ __device__ __forceinline__ void hadamard_pass(float4* X, int n, int s0) {
         const int base = ((gi >> s0) << (s0 + NS)) | (gi & ((1 << s0) - 1));
         if (base >= n) continue;
         if (block_exponent(base, n) >= s0 + NS) {
-            float4 v[RW];
-#pragma unroll
-            for (int j = 0; j < RW; ++j) v[j] = X[lds_row(base + (j << s0)) * QW + q];
-#pragma unroll
-            for (int k = 0; k < NS; ++k)
-#pragma unroll
-                for (int j = 0; j < RW; ++j)
-                    if (!(j & (1 << k))) {
-                        const float4 a = v[j], c = v[j | (1 << k)];
-                        v[j] = add4(a, c);
-                        v[j | (1 << k)] = sub4(a, c);
-                    }
-#pragma unroll
-            for (int j = 0; j < RW; ++j) X[lds_row(base + (j << s0)) * QW + q] = v[j];
-        } else {
+            butterfly_rows<QW, NS>(X, base, s0, q);
+            continue;
+        }
 #pragma unroll 1
-            for (int k = 0; k < NS; ++k) {
-                const int s = s0 + k;
-                float4 lo[RW / 2], hi[RW / 2];
-                bool on[RW / 2];
-#pragma unroll
-                for (int h = 0; h < RW / 2; ++h) {           // h-th row with bit k of j clear
-                    const int j = ((h >> k) << (k + 1)) | (h & ((1 << k) - 1));
-                    const int r = base + (j << s0);
-                    on[h] = r < n && s < block_exponent(r < n ? r : base, n);   // then r + 2^s lies in the same block
-                    const int ra = on[h] ? r : base;         // a valid row either way; its value is dropped when off
-                    lo[h] = X[lds_row(ra) * QW + q];
-                    hi[h] = X[lds_row(on[h] ? ra + (1 << s) : base) * QW + q];
-                }
-#pragma unroll
-                for (int h = 0; h < RW / 2; ++h) {
-                    const int j = ((h >> k) << (k + 1)) | (h & ((1 << k) - 1));
-                    const int r = base + (j << s0);
-                    if (on[h]) {
-                        X[lds_row(r) * QW + q] = add4(lo[h], hi[h]);
-                        X[lds_row(r + (1 << s)) * QW + q] = sub4(lo[h], hi[h]);
-                    }
-                }
-            }
+        for (int j0 = 0; j0 < RW;) {
+            const int first = base + (j0 << s0);
+            if (first >= n) break;
+            const int ns = block_exponent(first, n) - s0;    // stages this block still needs; below NS here
+            if (ns <= 0) break;                              // and no later block needs any
+            if (NS > 3 && ns == 3) butterfly_rows<QW, 3>(X, first, s0, q);
+            else if (NS > 2 && ns == 2) butterfly_rows<QW, 2>(X, first, s0, q);
+            else butterfly_rows<QW, 1>(X, first, s0, q);
+            j0 += 1 << ns;
         }
     }
 }
@@ -194,13 +193,16 @@ __device__ __forceinline__ void block_hadamard(float4* X, int n) {
     }
 }
 
-constexpr int kMaxItems = 20;      // quads per thread: a strip has at most 512 x 20 of them (160 KB of LDS)
+constexpr int kMaxQuads = 20;      // quads per thread: a strip has at most 512 x 20 of them (160 KB of LDS)
 
 // T: float or uint16_t (bf16 bits).  CW columns per workgroup, 512 threads, n x CW floats of LDS.
+// In the permutations between the rounds a thread owns whole rows of the strip (rows tid, tid + 512, ...):
+// one table entry, one sign, one scale and one pair of row addresses serve all the columns of a row.
 template <typename T, int CW>
 __global__ __launch_bounds__(512)
 void structured_apply_kernel(StructuredArgs a) {
     constexpr int QW = CW / 4;
+    constexpr int RP = kMaxQuads / QW;                       // rows per thread at most
     extern __shared__ float4 X[];
     const int tid = threadIdx.x, n = a.n, R = a.rounds;
     // consecutive strips go to consecutive workgroups of ONE accelerator die (workgroups are dealt
@@ -209,35 +211,38 @@ void structured_apply_kernel(StructuredArgs a) {
     const int strip = (blockIdx.x & 7) * per_die + (blockIdx.x >> 3);
     if (strip >= nstrips) return;
     const int col0 = strip * CW;
+    const int quads = min(QW, (a.ncols - col0) / 4);         // a ragged last strip has fewer
     const int total = n * QW;
     const uint32_t* tab_in = a.table + (int64_t)(a.inverse ? R : 0) * n;
     const uint32_t* tab_out = a.table + (int64_t)(a.inverse ? 0 : R) * n;
 
     // ---- load: forward x[j] = sign_0[j] in[perm_0[j]];  transposed x[perm_R[j]] = in[j]
-    // (unrolled over the thread's items so that its table reads, then its operand loads, overlap)
+    // Here and in the store a work item is one quad of one row, quads of a row on neighbouring lanes:
+    // a wave's access touches 16 rows, not 64.  Unrolled over the thread's items so that its table
+    // reads, then its operand loads, overlap.
     {
-        uint32_t entry[kMaxItems];
+        uint32_t entry[kMaxQuads];
 #pragma unroll
-        for (int it = 0; it < kMaxItems; ++it) {
+        for (int it = 0; it < kMaxQuads; ++it) {
             const int t = tid + 512 * it;
             entry[it] = t < total ? tab_in[t / QW] : 0u;
         }
-        float4 v[kMaxItems];
+        float4 v[kMaxQuads];
 #pragma unroll
-        for (int it = 0; it < kMaxItems; ++it) {
+        for (int it = 0; it < kMaxQuads; ++it) {
             const int t = tid + 512 * it;
             const int q = t % QW, j = t / QW;
-            if (t < total && col0 + 4 * q < a.ncols) {
+            if (t < total && q < quads) {
                 const int src = a.inverse ? j : (int)(entry[it] & ~kSignBit);
                 const T* row = src < a.rows0 ? (const T*)a.in0 + (int64_t)src * a.ld0 : (const T*)a.in1 + (int64_t)(src - a.rows0) * a.ld1;
                 v[it] = load_quad<T>(row + col0 + 4 * q);
             }
         }
 #pragma unroll
-        for (int it = 0; it < kMaxItems; ++it) {
+        for (int it = 0; it < kMaxQuads; ++it) {
             const int t = tid + 512 * it;
             const int q = t % QW, j = t / QW;
-            if (t < total && col0 + 4 * q < a.ncols) {
+            if (t < total && q < quads) {
                 const int dst = a.inverse ? (int)(entry[it] & ~kSignBit) : j;
                 X[lds_row(dst) * QW + q] = scaled(v[it], (entry[it] & kSignBit) ? -1.f : 1.f);
             }
@@ -251,44 +256,50 @@ void structured_apply_kernel(StructuredArgs a) {
         block_hadamard<QW>(X, n);
         if (r == R) break;
         const uint32_t* tab = a.table + (int64_t)(a.inverse ? R - r : r) * n;
-        float4 held[kMaxItems];
+        float4 held[RP][QW];
+        int where[RP];                                       // LDS row each held row goes to
 #pragma unroll
-        for (int it = 0; it < kMaxItems; ++it) {
-            const int t = tid + 512 * it;
-            if (t < total) {
-                const int q = t % QW, j = t / QW;
+        for (int it = 0; it < RP; ++it) {
+            const int j = tid + 512 * it;
+            if (j < n) {
                 const uint32_t entry = tab[j];
-                const int src = a.inverse ? j : (int)(entry & ~kSignBit);
+                const int other = (int)(entry & ~kSignBit);
+                const int src = a.inverse ? j : other, dst = a.inverse ? other : j;
                 const float s = block_scale(block_exponent(src, n));
-                held[it] = scaled(X[lds_row(src) * QW + q], (entry & kSignBit) ? -s : s);
+                const float f = (entry & kSignBit) ? -s : s;
+                const float4* xr = X + lds_row(src) * QW;
+#pragma unroll
+                for (int q = 0; q < QW; ++q) held[it][q] = scaled(xr[q], f);
+                where[it] = lds_row(dst) * QW;
             }
         }
         __syncthreads();                                     // every row is read before any is overwritten
 #pragma unroll
-        for (int it = 0; it < kMaxItems; ++it) {
-            const int t = tid + 512 * it;
-            if (t < total) {
-                const int q = t % QW, j = t / QW;
-                const int dst = a.inverse ? (int)(tab[j] & ~kSignBit) : j;
-                X[lds_row(dst) * QW + q] = held[it];
+        for (int it = 0; it < RP; ++it)
+            if (tid + 512 * it < n) {
+#pragma unroll
+                for (int q = 0; q < QW; ++q) X[where[it] + q] = held[it][q];
             }
-        }
         __syncthreads();
     }
 
     // ---- store: forward out[j] = x[perm_R[j]];  transposed out[perm_0[j]] = sign_0[j] x[j]
     {
-        uint32_t entry[kMaxItems];
+        // index arithmetic redone from an opaque copy of the thread number: values shared with the load
+        // phase would otherwise stay in registers across the whole kernel and spill
+        int tid_s = tid;
+        asm volatile("" : "+v"(tid_s));
+        uint32_t entry[kMaxQuads];
 #pragma unroll
-        for (int it = 0; it < kMaxItems; ++it) {
-            const int t = tid + 512 * it;
+        for (int it = 0; it < kMaxQuads; ++it) {
+            const int t = tid_s + 512 * it;
             entry[it] = t < total ? tab_out[t / QW] : 0u;
         }
 #pragma unroll
-        for (int it = 0; it < kMaxItems; ++it) {
-            const int t = tid + 512 * it;
+        for (int it = 0; it < kMaxQuads; ++it) {
+            const int t = tid_s + 512 * it;
             const int q = t % QW, j = t / QW;
-            if (t >= total || col0 + 4 * q >= a.ncols) continue;
+            if (t >= total || q >= quads) continue;
             const int other = (int)(entry[it] & ~kSignBit);
             const int src = a.inverse ? j : other, dst = a.inverse ? other : j;
             if (dst >= a.rows_out) continue;
@@ -314,6 +325,9 @@ hipError_t launch_apply(const StructuredArgs& a, size_t lds, hipStream_t s) {
     return hipGetLastError();
 }
 
+// 16 columns per workgroup while n rows of them fit in LDS (2560 rows), 8 beyond that.  (Half-size
+// workgroups, two per CU, so that one's loads overlap the other's butterflies, were 8% slower: the
+// kernel is bound by vector-ALU issue, not by its memory phases.)
 template <typename T>
 hipError_t dispatch_apply(const StructuredArgs& a, hipStream_t s) {
     const size_t rows_pad = (size_t)round_up(a.n, 16);
