@@ -203,6 +203,7 @@ __global__ __launch_bounds__(512)
 void structured_apply_kernel(StructuredArgs a) {
     constexpr int QW = CW / 4;
     constexpr int RP = kMaxQuads / QW;                       // rows per thread at most
+    static_assert(RP >= 1, "strip too wide for one row per thread");
     extern __shared__ float4 X[];
     const int tid = threadIdx.x, n = a.n, R = a.rounds;
     // consecutive strips go to consecutive workgroups of ONE accelerator die (workgroups are dealt
@@ -327,10 +328,13 @@ hipError_t launch_apply(const StructuredArgs& a, size_t lds, hipStream_t s) {
 
 // 16 columns per workgroup while n rows of them fit in LDS (2560 rows), 8 beyond that.  (Half-size
 // workgroups, two per CU, so that one's loads overlap the other's butterflies, were 8% slower: the
-// kernel is bound by vector-ALU issue, not by its memory phases.)
+// kernel is bound by vector-ALU issue, not by its memory phases.)  Short strips (decode-shaped
+// batches of at most 512 rows) take 64 columns: a workgroup's fixed cost - a dozen barriers and four
+// dependent trips to memory - is then paid by 64 instead of 256 or 768 workgroups.
 template <typename T>
 hipError_t dispatch_apply(const StructuredArgs& a, hipStream_t s) {
     const size_t rows_pad = (size_t)round_up(a.n, 16);
+    if (a.n <= 512 && a.ncols >= 2048) return launch_apply<T, 64>(a, rows_pad * 256, s);
     if (rows_pad * 64 <= (size_t)g_lds_cap) return launch_apply<T, 16>(a, rows_pad * 64, s);
     if (rows_pad * 32 <= (size_t)g_lds_cap) return launch_apply<T, 8>(a, rows_pad * 32, s);
     return hipErrorInvalidValue;
@@ -346,6 +350,8 @@ hipError_t structured_init() {
     if (e != hipSuccess) return e;
     g_lds_cap = cap < 160 * 1024 ? cap : 160 * 1024;
     if (g_lds_cap < 64 * 1024) return hipErrorInvalidDevice;
+    if ((e = allow_lds<float, 64>()) != hipSuccess) return e;
+    if ((e = allow_lds<uint16_t, 64>()) != hipSuccess) return e;
     if ((e = allow_lds<float, 16>()) != hipSuccess) return e;
     if ((e = allow_lds<float, 8>()) != hipSuccess) return e;
     if ((e = allow_lds<uint16_t, 16>()) != hipSuccess) return e;

@@ -66,6 +66,11 @@ WORKLOADS = {
     # Walsh-Hadamard rounds: nothing to factorise, mix and unmix in O(n log n) per column)
     "llama7b_bf16_prefill_structured": Workload("llama7b_bf16_prefill_structured", "bf16", 2048, 102, 4096, 12288,
                                                 KIND_STRUCTURED, 8, 0xC6),
+    # ... the 4096 + 205 row layer of the sweep and the decode-shaped batch, same kind
+    "sweep_bf16_structured": Workload("sweep_bf16_structured", "bf16", 4096, 205, 4096, 12288,
+                                      KIND_STRUCTURED, 8, 0xC7),
+    "decode_bf16_structured": Workload("decode_bf16_structured", "bf16", 64, 4, 4096, 12288,
+                                       KIND_STRUCTURED, 8, 0xC8),
 }
 
 

@@ -92,13 +92,14 @@ def run_chain(ctx, dtype, H32, W32, k, batch_id, scale=10.0):
 
 CASES = [("f32", 16, 2, 64, 192), ("bf16", 16, 2, 64, 192), ("f32", 1, 0, 8, 8), ("bf16", 2, 1, 8, 16),
          ("f32", 300, 15, 256, 520), ("bf16", 300, 15, 264, 520), ("f32", 1031, 0, 72, 40),
-         ("bf16", 2048, 102, 512, 776), ("bf16", 4096, 205, 256, 264), ("f32", 5000, 120, 64, 72)]
+         ("bf16", 2048, 102, 512, 776), ("bf16", 4096, 205, 256, 264), ("f32", 5000, 120, 64, 72),
+         ("bf16", 200, 10, 2056, 2072), ("f32", 500, 12, 2048, 2056)]      # short strips: 64 columns per workgroup
 
 
 @pytest.mark.parametrize("dtype,nd,k,d,p", CASES)
 def test_chain_stagewise_and_end_to_end(ctx, dtype, nd, k, d, p):
-    """Ragged strips (widths that are not multiples of 16), both strip widths (16 and 8 columns per
-    workgroup), blocks of every size in the binary expansion of n, with and without shield rows."""
+    """Ragged strips (widths that are not multiples of the strip width), all strip widths (64, 16 and 8
+    columns per workgroup), blocks of every size in the binary expansion of n, with and without shield rows."""
     H32 = wl.make_hidden(nd, d, 77 + nd, min(4, d))
     W32 = wl.make_weight(d, p, 78 + nd)
     bid = 5000 + nd * 3 + (dtype == "bf16")
@@ -116,13 +117,14 @@ def test_chain_stagewise_and_end_to_end(ctx, dtype, nd, k, d, p):
         assert o.rel_frobenius(U.T @ U, H.T @ H + S.T @ S) < 10 * tol
 
 
-def test_full_size_bf16_prefill_structured(ctx):
-    """The prefill shape of the headline workload (2048 + 102 rows, d = 4096, p = 12288) in the launch
-    configuration the benchmark times: every stage against the oracle on sampled columns (the transform
-    acts on columns independently), the whole result by a random projection."""
-    w = wl.WORKLOADS["llama7b_bf16_prefill_structured"]
+@pytest.mark.parametrize("name", ["llama7b_bf16_prefill_structured", "sweep_bf16_structured", "decode_bf16_structured"])
+def test_full_size_structured_workloads(ctx, name):
+    """The benchmark's structured workloads at full size (d = 4096, p = 12288; 2048 + 102, 4096 + 205 and
+    64 + 4 rows) in the launch configuration it times: every stage against the oracle on sampled columns
+    (the transform acts on columns independently), the whole result by a random projection."""
+    w = wl.WORKLOADS[name]
     H32, W32 = wl.make_inputs(w)
-    bid = 4242
+    bid = 4242 + w.n
     r = run_chain(ctx, "bf16", H32, W32, w.k_shield, bid)
     H, W, S = f64(r["H"]), f64(r["W"]), f64(r["S"])
     U, Y, Z = f64(r["U"]), f64(r["Y"]), f64(r["Z"])
