@@ -294,6 +294,21 @@ def main() -> int:
                               "achieved": b_proj / t_proj / 1e9, "peak": 8000.0, "unit": "GB/s",
                               "frac": b_proj / t_proj / 1e9 / 8000.0, "traffic": None, "avg_launch_us": t_proj * 1e6}
 
+    if w.kind == 3:
+        # The second kernel of a structured step: the transform behind unmix (one launch, timed by the stage
+        # events above).  Its butterflies are plain float additions on the vector ALUs; the peak is what
+        # 256 CUs x 64 lanes x 2.4 GHz can issue when every instruction is a useful, unpacked addition.
+        esz = 2 if w.dtype == "bf16" else 4
+        t_un = stage["unmix"] * 1e-3
+        adds = STRUCTURED_ROUNDS * butterfly_adds(n) * p
+        bytes_un = float(esz) * (n * p + nd * p)
+        alu_peak = 256 * 64 * 2.4e9 / 1e12
+        result["transform"] = {"kernel": "structured_apply (unmix Z = A^T Y, shield rows dropped)", "bound": "alu",
+                               "achieved": adds / t_un / 1e12, "peak": alu_peak, "unit": "Tadd/s",
+                               "frac": adds / t_un / 1e12 / alu_peak,
+                               "hbm_GBps": bytes_un / t_un / 1e9, "hbm_frac": bytes_un / t_un / 1e9 / 8000.0,
+                               "launch_us": t_un * 1e6}
+
     # HBM traffic of the projection GEMM from the committed rocprofv3 counter runs; only valid for the
     # kernel source those runs were taken on
     try:

@@ -24,6 +24,8 @@ def mixed(kind, H, k=0, scale=10.0, seed=1, bid=3):
     n = H.shape[0] + k
     if kind == "orthogonal":
         A = o.sample_orthogonal(seed, bid, n)[0]
+    elif kind == "structured":
+        A = o.sample_structured(seed, bid, n)[0]
     elif kind == "conditioned":
         A = o.sample_conditioned(seed, bid, n)[0]
     else:
@@ -64,9 +66,12 @@ def test_similarity_spectrum_against_singular_values():
 
 
 # ------------------------------------------------------------- Section 3.2.1, eqs. 5, 6 and 9 --
-def test_orthogonal_mixing_leaks_covariance_and_similarity_spectrum():
+@pytest.mark.parametrize("kind", ["orthogonal", "structured"])
+def test_orthogonal_mixing_leaks_covariance_and_similarity_spectrum(kind):
+    """any orthogonal A, the Haar one from the QR or the structured one from permutations, signs and
+    Walsh-Hadamard blocks"""
     H = laplace_sources()
-    U, _ = mixed("orthogonal", H)
+    U, _ = mixed(kind, H)
     assert lk.covariance_leak(U, H) < 1e-12          # eq. 5: U^T U = H^T H
     assert lk.spectrum_leak(U, H) < 1e-12            # eq. 6: U U^T is similar to H H^T
 
@@ -103,7 +108,7 @@ def test_fastica_separates_a_known_two_source_mixture():
     assert cos.min() > 0.995
 
 
-@pytest.mark.parametrize("kind,k", [("orthogonal", 0), ("conditioned", 0), ("gaussian", 0), ("orthogonal", 2)])
+@pytest.mark.parametrize("kind,k", [("orthogonal", 0), ("conditioned", 0), ("gaussian", 0), ("orthogonal", 2), ("structured", 0)])
 def test_ideal_independent_sources_are_recovered_whatever_the_mixing(kind, k):
     """What the mitigations do NOT claim: when the rows of H are independent and heavy-tailed (nothing
     like hidden states), FastICA recovers them from U up to order, sign and scale for every kind of A,
