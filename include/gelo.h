@@ -94,8 +94,12 @@ const char* gelo_status_string(gelo_status s);
 /* Trusted side, Section 3.2 step 1.2.  Draws the secrets of batch `batch_id`: A (n x n,
  * n = n_data + k_shield), its inverse, and k_shield Gaussian shield directions of width d.
  * A pure function of (seed, batch_id, kind, n, k_shield, d).  cond_max and max_attempts
- * (1..GELO_MAX_ATTEMPTS) are used by GELO_GAUSSIAN only, which reads one scalar back per
- * attempt (the only host synchronisation in the library).  n <= GELO_MAX_N, n_data >= 1,
+ * (1..GELO_MAX_ATTEMPTS) are used by GELO_GAUSSIAN only: it factorises up to four consecutive
+ * attempts side by side on streams of its own (n <= 1024; one at a time beyond), reads their
+ * condition estimates back (the only host synchronisation in the library) and returns the first
+ * acceptable attempt in order, so the result does not depend on how many ran at once.
+ * n <= GELO_MAX_N (for GELO_STRUCTURED also n rows x 8 floats must fit in one workgroup's LDS:
+ * the same 5120 on this chip), n_data >= 1,
  * k_shield >= 0, d a multiple of 8.  *out is owned by the library: release it with
  * gelo_mixing_free (which recycles its device memory inside the context). */
 gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d,

@@ -20,6 +20,12 @@ namespace {
 constexpr float kConditionedBeta = 0.25f;
 constexpr int kKappaSteps = 20;          // Lanczos steps of the condition estimate
 constexpr uint32_t kStreamMixing = 0, kStreamShield = 1, kStreamPerturb = 2;
+// GAUSSIAN draws are accepted or rejected by their condition number, and a draw's chain of small
+// launches leaves most of the chip idle: up to kLanes consecutive attempts are factorised side by
+// side on library-owned streams, each in a workspace of its own, and the first acceptable one in
+// attempt order wins - the same matrix a one-at-a-time loop would return.
+constexpr int kLanes = 4;
+constexpr int kLanesMaxN = 1024;        // beyond this the rule is infeasible anyway and the buffers get large
 }
 
 struct gelo_mixing {
@@ -53,9 +59,14 @@ struct gelo_ctx {
     std::string err;
     void* factor_ws; size_t factor_ws_bytes;
     void* chain_ws;  size_t chain_ws_bytes;
-    float* host_scalars;         // pinned: kappa read-back
+    float* host_scalars;         // pinned: kappa read-back, one slot per lane
     int* host_flag;
     std::vector<gelo_mixing*> pool;
+    hipStream_t lane_stream[kLanes];   // created on the first GAUSSIAN draw
+    hipEvent_t lane_fork, lane_done[kLanes];
+    hipEvent_t lane_join;              // the winner's copies out of `cand` (on the caller's stream) are done
+    bool lanes_ready, join_pending;
+    void* cand; size_t cand_bytes;     // per lane: candidate A, A^-1 (float, and bf16 copies)
 };
 
 namespace {
@@ -133,6 +144,18 @@ gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, b
     return GELO_OK;
 }
 
+gelo_status ensure_lanes(gelo_ctx* ctx) {
+    if (ctx->lanes_ready) return GELO_OK;
+    GELO_HIP(ctx, hipEventCreateWithFlags(&ctx->lane_fork, hipEventDisableTiming));
+    GELO_HIP(ctx, hipEventCreateWithFlags(&ctx->lane_join, hipEventDisableTiming));
+    for (int i = 0; i < kLanes; ++i) {
+        GELO_HIP(ctx, hipStreamCreateWithFlags(&ctx->lane_stream[i], hipStreamNonBlocking));
+        GELO_HIP(ctx, hipEventCreateWithFlags(&ctx->lane_done[i], hipEventDisableTiming));
+    }
+    ctx->lanes_ready = true;
+    return GELO_OK;
+}
+
 bool owns(const gelo_ctx* ctx, const gelo_mixing* m) {
     for (const gelo_mixing* q : ctx->pool) if (q == m) return true;
     return false;
@@ -184,6 +207,7 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
     ctx->device = device; ctx->seed = seed; ctx->allow_reuse = allow_batch_reuse != 0;
     ctx->factor_ws = ctx->chain_ws = nullptr; ctx->factor_ws_bytes = ctx->chain_ws_bytes = 0;
     ctx->host_scalars = nullptr; ctx->host_flag = nullptr;
+    ctx->lanes_ready = false; ctx->join_pending = false; ctx->cand = nullptr; ctx->cand_bytes = 0;
     if (hipHostMalloc((void**)&ctx->host_scalars, 64, hipHostMallocDefault) != hipSuccess) { delete ctx; return GELO_ENOMEM; }
     ctx->host_flag = (int*)(ctx->host_scalars + 8);
     if (gemm_bf16_init() != hipSuccess || gemm_f32_init() != hipSuccess || lu_init() != hipSuccess ||
@@ -203,6 +227,11 @@ gelo_status gelo_destroy(gelo_ctx* ctx) {
         hipFree(m->block);
         delete m;
     }
+    if (ctx->lanes_ready) {
+        (void)hipEventDestroy(ctx->lane_fork); (void)hipEventDestroy(ctx->lane_join);
+        for (int i = 0; i < kLanes; ++i) { (void)hipStreamDestroy(ctx->lane_stream[i]); (void)hipEventDestroy(ctx->lane_done[i]); }
+    }
+    if (ctx->cand) (void)hipFree(ctx->cand);
     if (ctx->factor_ws) (void)hipFree(ctx->factor_ws);
     if (ctx->chain_ws) (void)hipFree(ctx->chain_ws);
     if (ctx->host_scalars) (void)hipHostFree(ctx->host_scalars);
@@ -240,8 +269,10 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
     const bool structured = kind == GELO_STRUCTURED;
     gelo_status st = GELO_OK;
     FactorWorkspace ws = {};
+    const int lanes = (kind == GELO_GAUSSIAN && n <= kLanesMaxN) ? (max_attempts < kLanes ? max_attempts : kLanes) : 1;
+    const size_t ws_bytes = up256(factor_workspace_bytes(n));
     if (!structured) {
-        st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, factor_workspace_bytes(n));
+        st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, ws_bytes * lanes);
         if (st != GELO_OK) return st;
         factor_workspace_carve(ctx->factor_ws, n, &ws);
     }
@@ -270,44 +301,87 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
         GELO_HIP(ctx, orthogonal_into_X());
         // A = Q diag(sign r_ii); A^-1 = A^T
         GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s));
+    } else if (kind == GELO_CONDITIONED) {
+        GELO_HIP(ctx, orthogonal_into_X());
+        GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, nullptr, nullptr, nullptr, s));
+        ps.c1 = kStreamPerturb << 8;
+        GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f, 0, s));
+        GELO_HIP(ctx, axpy_matrix(m->A32, ldk, ws.M, ld, n, n, kConditionedBeta / std::sqrt((float)n), s));
+        GELO_HIP(ctx, emit_matrix(m->A32, ldk, 0, nullptr, n, ld, ws.M, nullptr, nullptr, nullptr, s));
+        if (bf) GELO_HIP(ctx, emit_matrix(m->A32, ldk, 0, nullptr, n, ldk, nullptr, m->A16, nullptr, nullptr, s));
+        GELO_HIP(ctx, pad_matrix(ws.M, ld, n, ws.n_pad, 1, s));
+        GELO_HIP(ctx, lu_inverse(ws, s));
+        GELO_HIP(ctx, emit_matrix(ws.X, ld, 0, nullptr, n, ldk, m->Ainv32, m->Ainv16, nullptr, nullptr, s));
+        GELO_HIP(ctx, kappa_estimate(m->A32, m->Ainv32, ldk, n, ws, kKappaSteps, s));
+        GELO_HIP(ctx, hipMemcpyAsync(m->stat + 1, ws.scalars, sizeof(float), hipMemcpyDeviceToDevice, s));
+        m->kappa = -1.0f;                                     // stays on the device until someone asks
     } else {
-        bool accepted = false;
-        const int attempts = kind == GELO_GAUSSIAN ? max_attempts : 1;
-        bool singular_last = false;
-        for (int attempt = 0; attempt < attempts && !accepted; ++attempt) {
-            if (kind == GELO_GAUSSIAN) {
-                ps.c1 = (kStreamMixing << 8) | (uint32_t)attempt;
-                GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f / std::sqrt((float)n), 0, s));
-                GELO_HIP(ctx, emit_matrix(ws.M, ld, 0, nullptr, n, ldk, m->A32, m->A16, nullptr, nullptr, s));
-            } else {
-                GELO_HIP(ctx, orthogonal_into_X());
-                GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, nullptr, nullptr, nullptr, s));
-                ps.c1 = kStreamPerturb << 8;
-                GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f, 0, s));
-                GELO_HIP(ctx, axpy_matrix(m->A32, ldk, ws.M, ld, n, n, kConditionedBeta / std::sqrt((float)n), s));
-                GELO_HIP(ctx, emit_matrix(m->A32, ldk, 0, nullptr, n, ld, ws.M, nullptr, nullptr, nullptr, s));
-                if (bf) GELO_HIP(ctx, emit_matrix(m->A32, ldk, 0, nullptr, n, ldk, nullptr, m->A16, nullptr, nullptr, s));
+        // GAUSSIAN: groups of `lanes` consecutive attempts side by side; the host reads every lane's
+        // kappa and singular flag (the library's only host synchronisation) and takes the first
+        // acceptable attempt in order.
+        const size_t mat32 = up256((size_t)n * ldk * 4), mat16 = bf ? up256((size_t)n * ldk * 2) : 0;
+        const size_t lane_cand = 2 * mat32 + 2 * mat16;
+        if (lanes > 1) {
+            st = grow(ctx, &ctx->cand, &ctx->cand_bytes, lane_cand * lanes);
+            if (st == GELO_OK) st = ensure_lanes(ctx);
+            if (st != GELO_OK) return st;
+        }
+        bool accepted = false, singular_last = false;
+        for (int base = 0; base < max_attempts && !accepted; base += lanes) {
+            const int count = max_attempts - base < lanes ? max_attempts - base : lanes;
+            if (lanes > 1) GELO_HIP(ctx, hipEventRecord(ctx->lane_fork, s));
+            FactorWorkspace lw[kLanes];
+            float* cA32[kLanes]; float* cAi32[kLanes]; uint16_t* cA16[kLanes]; uint16_t* cAi16[kLanes];
+            for (int i = 0; i < count; ++i) {
+                hipStream_t ls = lanes > 1 ? ctx->lane_stream[i] : s;
+                if (lanes > 1) {
+                    GELO_HIP(ctx, hipStreamWaitEvent(ls, ctx->lane_fork, 0));
+                    if (ctx->join_pending) GELO_HIP(ctx, hipStreamWaitEvent(ls, ctx->lane_join, 0));   // an earlier call may still be copying
+                    factor_workspace_carve((char*)ctx->factor_ws + ws_bytes * i, n, &lw[i]);
+                    char* c = (char*)ctx->cand + lane_cand * i;
+                    cA32[i] = (float*)c; cAi32[i] = (float*)(c + mat32);
+                    cA16[i] = bf ? (uint16_t*)(c + 2 * mat32) : nullptr;
+                    cAi16[i] = bf ? (uint16_t*)(c + 2 * mat32 + mat16) : nullptr;
+                } else {
+                    lw[i] = ws; cA32[i] = m->A32; cAi32[i] = m->Ainv32; cA16[i] = m->A16; cAi16[i] = m->Ainv16;
+                }
+                ps.c1 = (kStreamMixing << 8) | (uint32_t)(base + i);
+                GELO_HIP(ctx, fill_normal(lw[i].M, ld, n, n, ps, 1.0f / std::sqrt((float)n), 0, ls));
+                GELO_HIP(ctx, emit_matrix(lw[i].M, ld, 0, nullptr, n, ldk, cA32[i], cA16[i], nullptr, nullptr, ls));
+                GELO_HIP(ctx, pad_matrix(lw[i].M, ld, n, lw[i].n_pad, 1, ls));
+                GELO_HIP(ctx, lu_inverse(lw[i], ls));
+                GELO_HIP(ctx, emit_matrix(lw[i].X, ld, 0, nullptr, n, ldk, cAi32[i], cAi16[i], nullptr, nullptr, ls));
+                GELO_HIP(ctx, kappa_estimate(cA32[i], cAi32[i], ldk, n, lw[i], kKappaSteps, ls));
+                GELO_HIP(ctx, hipMemcpyAsync(ctx->host_scalars + i, lw[i].scalars, sizeof(float), hipMemcpyDeviceToHost, ls));
+                GELO_HIP(ctx, hipMemcpyAsync(ctx->host_flag + i, lw[i].flag, sizeof(int), hipMemcpyDeviceToHost, ls));
+                if (lanes > 1) GELO_HIP(ctx, hipEventRecord(ctx->lane_done[i], ls));
             }
-            GELO_HIP(ctx, pad_matrix(ws.M, ld, n, ws.n_pad, 1, s));
-            GELO_HIP(ctx, lu_inverse(ws, s));
-            GELO_HIP(ctx, emit_matrix(ws.X, ld, 0, nullptr, n, ldk, m->Ainv32, m->Ainv16, nullptr, nullptr, s));
-            GELO_HIP(ctx, kappa_estimate(m->A32, m->Ainv32, ldk, n, ws, kKappaSteps, s));
-            GELO_HIP(ctx, hipMemcpyAsync(m->stat + 1, ws.scalars, sizeof(float), hipMemcpyDeviceToDevice, s));
-            if (kind == GELO_GAUSSIAN) {
-                // the one host synchronisation of the library: accept or redraw
-                GELO_HIP(ctx, hipMemcpyAsync(ctx->host_scalars, ws.scalars, sizeof(float), hipMemcpyDeviceToHost, s));
-                GELO_HIP(ctx, hipMemcpyAsync(ctx->host_flag, ws.flag, sizeof(int), hipMemcpyDeviceToHost, s));
-                GELO_HIP(ctx, hipStreamSynchronize(s));
-                singular_last = *ctx->host_flag != 0;
-                const float kappa = ctx->host_scalars[0];
-                if (!singular_last && kappa <= (float)cond_max) { accepted = true; m->attempt = attempt; m->kappa = kappa; }
+            if (lanes > 1) {
+                for (int i = 0; i < count; ++i) GELO_HIP(ctx, hipEventSynchronize(ctx->lane_done[i]));
             } else {
-                accepted = true; m->kappa = -1.0f;
+                GELO_HIP(ctx, hipStreamSynchronize(s));
+            }
+            for (int i = 0; i < count && !accepted; ++i) {
+                singular_last = ctx->host_flag[i] != 0;
+                const float kappa = ctx->host_scalars[i];
+                if (singular_last || !(kappa <= (float)cond_max)) continue;
+                accepted = true; m->attempt = base + i; m->kappa = kappa;
+                GELO_HIP(ctx, hipMemcpyAsync(m->stat + 1, lw[i].scalars, sizeof(float), hipMemcpyDeviceToDevice, s));
+                if (lanes > 1) {      // every lane has finished: plain copies on the caller's stream
+                    GELO_HIP(ctx, hipMemcpyAsync(m->A32, cA32[i], (size_t)n * ldk * 4, hipMemcpyDeviceToDevice, s));
+                    GELO_HIP(ctx, hipMemcpyAsync(m->Ainv32, cAi32[i], (size_t)n * ldk * 4, hipMemcpyDeviceToDevice, s));
+                    if (bf) {
+                        GELO_HIP(ctx, hipMemcpyAsync(m->A16, cA16[i], (size_t)n * ldk * 2, hipMemcpyDeviceToDevice, s));
+                        GELO_HIP(ctx, hipMemcpyAsync(m->Ainv16, cAi16[i], (size_t)n * ldk * 2, hipMemcpyDeviceToDevice, s));
+                    }
+                    GELO_HIP(ctx, hipEventRecord(ctx->lane_join, s));
+                    ctx->join_pending = true;
+                }
             }
         }
         if (!accepted) {
-            if (singular_last) return fail(ctx, GELO_ESINGULAR, "zero pivot in the last of %d draws", attempts);
-            return fail(ctx, GELO_ECOND, "no draw with kappa <= %g within %d attempts", cond_max, attempts);
+            if (singular_last) return fail(ctx, GELO_ESINGULAR, "zero pivot in the last of %d draws", max_attempts);
+            return fail(ctx, GELO_ECOND, "no draw with kappa <= %g within %d attempts", cond_max, max_attempts);
         }
     }
     if (k_shield > 0) {
