@@ -62,6 +62,13 @@ WORKLOADS = {
     # p = d and a fresh A of its own (the method offloads every linear projection Q, K, V and O)
     "llama7b_bf16_oproj": Workload("llama7b_bf16_oproj", "bf16", 2048, 102, 4096, 4096,
                                    KIND_ORTHOGONAL, 8, 0xC5),
+    # beyond Q/K/V/O: the MLP projections of the same model (the paper's Conclusion lists them as the next
+    # layers to offload; Llama-2-7B: hidden 4096, intermediate 11008).  Gate and up share their input and
+    # are fused like Q|K|V (p = 2 x 11008); down maps 11008 back to 4096.
+    "llama7b_bf16_mlp_gate_up": Workload("llama7b_bf16_mlp_gate_up", "bf16", 2048, 102, 4096, 22016,
+                                         KIND_STRUCTURED, 8, 0xC9),
+    "llama7b_bf16_mlp_down": Workload("llama7b_bf16_mlp_down", "bf16", 2048, 102, 11008, 4096,
+                                      KIND_STRUCTURED, 8, 0xCA),
     # the prefill batch again with the structured orthogonal A (permutations, sign flips and block
     # Walsh-Hadamard rounds: nothing to factorise, mix and unmix in O(n log n) per column)
     "llama7b_bf16_prefill_structured": Workload("llama7b_bf16_prefill_structured", "bf16", 2048, 102, 4096, 12288,

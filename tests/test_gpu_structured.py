@@ -117,14 +117,15 @@ def test_chain_stagewise_and_end_to_end(ctx, dtype, nd, k, d, p):
         assert o.rel_frobenius(U.T @ U, H.T @ H + S.T @ S) < 10 * tol
 
 
-@pytest.mark.parametrize("name", ["llama7b_bf16_prefill_structured", "sweep_bf16_structured", "decode_bf16_structured"])
+@pytest.mark.parametrize("name", ["llama7b_bf16_prefill_structured", "sweep_bf16_structured", "decode_bf16_structured",
+                                  "llama7b_bf16_mlp_gate_up", "llama7b_bf16_mlp_down"])
 def test_full_size_structured_workloads(ctx, name):
-    """The benchmark's structured workloads at full size (d = 4096, p = 12288; 2048 + 102, 4096 + 205 and
-    64 + 4 rows) in the launch configuration it times: every stage against the oracle on sampled columns
+    """The benchmark's structured workloads at full size (d = 4096, p = 12288 with 2048 + 102, 4096 + 205 and
+    64 + 4 rows; the two MLP projections 4096 -> 22016 and 11008 -> 4096) in the launch configuration it times: every stage against the oracle on sampled columns
     (the transform acts on columns independently), the whole result by a random projection."""
     w = wl.WORKLOADS[name]
     H32, W32 = wl.make_inputs(w)
-    bid = 4242 + w.n
+    bid = 4242 + w.seed * 10000
     r = run_chain(ctx, "bf16", H32, W32, w.k_shield, bid)
     H, W, S = f64(r["H"]), f64(r["W"]), f64(r["S"])
     U, Y, Z = f64(r["U"]), f64(r["Y"]), f64(r["Z"])
