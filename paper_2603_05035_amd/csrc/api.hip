@@ -41,7 +41,7 @@ struct gelo_mixing {
     float* gsnorm;               // k
     void* S;                     // k x d shield rows in the compute dtype
     float* rownorm;              // n_data
-    float* stat;                 // [0] row-norm statistic of H, [1] kappa estimate
+    float* stat;                 // [1] kappa estimate, [2..3] row-norm statistic of H as two halves (see norm_statistic)
     int attempt;
     float kappa;                 // host copy (GAUSSIAN); < 0: still only on the device
     bool in_use, mixed, consumed;
@@ -413,8 +413,8 @@ gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh,
     const bool bf = m->dtype == GELO_BF16;
     if (m->k > 0) {
         GELO_HIP(ctx, row_norms(H, bf, ldh, m->n_data, m->d, m->rownorm, s));
-        GELO_HIP(ctx, norm_statistic(m->rownorm, m->n_data, (int)stat, m->stat, s));
-        GELO_HIP(ctx, make_shields(m->GS, m->d, m->gsnorm, m->stat, shield_scale, m->k, m->d, m->S, bf, m->d, s));
+        GELO_HIP(ctx, norm_statistic(m->rownorm, m->n_data, (int)stat, m->stat + 2, s));
+        GELO_HIP(ctx, make_shields(m->GS, m->d, m->gsnorm, m->stat + 2, shield_scale, m->k, m->d, m->S, bf, m->d, s));
     }
     if (m->structured) {
         StructuredOperands o;

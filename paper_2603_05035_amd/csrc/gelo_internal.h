@@ -87,9 +87,10 @@ hipError_t axpy_matrix(float* dst, int64_t ldd, const float* src, int64_t lds, i
 // norms[r] = || X[r, 0:cols] ||_2, X float or bf16
 hipError_t row_norms(const void* X, int is_bf16, int64_t ld, int rows, int cols, float* norms,
                      hipStream_t stream);
-// *out = median (stat 0; even count: mean of the two middle values) or mean (stat 1) of v[0:count]
+// out[0], out[1] = the two middle elements of v[0:count] (stat 0: their mean is the median; the same
+// element twice when count is odd) or twice its mean (stat 1); consumers take 0.5 (out[0] + out[1])
 hipError_t norm_statistic(const float* v, int count, int stat, float* out, hipStream_t stream);
-// S[i, :] = G[i, :] * (scale * *stat / gnorm[i]), written as float or bf16 (lds elements per row)
+// S[i, :] = G[i, :] * (scale * 0.5 (stat[0] + stat[1]) / gnorm[i]), written as float or bf16 (lds elements per row)
 hipError_t make_shields(const float* G, int64_t ldg, const float* gnorm, const float* stat, float scale,
                         int k, int d, void* S, int is_bf16, int64_t lds, hipStream_t stream);
 // Writes an n x n float matrix (src, optional per-column sign flip from `rdiag` < 0) into the

@@ -85,77 +85,57 @@ void row_norms_kernel(const void* X, int64_t ld, int rows, int cols, float* norm
     if (lane == 0) norms[row] = sqrtf(s);
 }
 
-// The value of 0-based rank `rank` among keys[0:count] (LDS), by radix selection from the most
-// significant byte down: four passes of a 256-bin histogram, each narrowing the candidates to
-// one bin.  Exact (it returns one of the keys).  All 1024 threads call it; hist / pick are LDS.
-__device__ uint32_t select_rank(const uint32_t* keys, int count, int rank, uint32_t* hist, uint32_t* pick) {
+// Mean of v[0:count]: single workgroup, tree sum in a fixed order.
+__global__ __launch_bounds__(1024)
+void mean_kernel(const float* v, int count, float* out) {
+    __shared__ float buf[1024];
     const int tid = threadIdx.x;
-    uint32_t prefix = 0, mask = 0;
-    for (int pass = 3; pass >= 0; --pass) {
-        const int shift = 8 * pass;
-        if (tid < 256) hist[tid] = 0;
+    float s = 0.f;
+    for (int i = tid; i < count; i += 1024) s += v[i];
+    buf[tid] = s;
+    __syncthreads();
+    for (int half = 512; half > 0; half >>= 1) {
+        if (tid < half) buf[tid] += buf[tid + half];
         __syncthreads();
-        for (int i = tid; i < count; i += 1024) {
-            const uint32_t k = keys[i];
-            if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (tid < 64) {
-            // lane l owns bins 4 l .. 4 l + 3; inclusive scan over the wave finds the bin holding `rank`
-            const uint32_t h0 = hist[4 * tid], h1 = hist[4 * tid + 1], h2 = hist[4 * tid + 2], h3 = hist[4 * tid + 3];
-            const uint32_t mine = h0 + h1 + h2 + h3;
-            uint32_t incl = mine;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const uint32_t up = __shfl_up(incl, off, 64);
-                if (tid >= off) incl += up;
-            }
-            const uint32_t before = incl - mine;
-            if ((uint32_t)rank >= before && (uint32_t)rank < incl) {
-                uint32_t r = (uint32_t)rank - before, bin = 4 * tid;
-                if (r >= h0) { r -= h0; ++bin; if (r >= h1) { r -= h1; ++bin; if (r >= h2) { r -= h2; ++bin; } } }
-                pick[0] = bin; pick[1] = r;
-            }
-        }
-        __syncthreads();
-        prefix |= pick[0] << shift;
-        mask |= 255u << shift;
-        rank = (int)pick[1];
-        __syncthreads();                    // pick is rewritten in the next pass
     }
-    return prefix;
+    if (tid == 0) { out[0] = buf[0] / (float)count; out[1] = out[0]; }
 }
 
-// Single workgroup.  Median: the middle element(s) by radix selection on the bit patterns (row
-// norms are non-negative floats, whose order is that of their bits).  Mean: tree sum in a fixed order.
-__global__ __launch_bounds__(1024)
-void norm_statistic_kernel(const float* v, int count, int stat, float* out) {
-    extern __shared__ float buf[];          // max(count, 1024) floats
-    __shared__ uint32_t hist[256];
-    __shared__ uint32_t pick[2];
+// Median of v[0:count] (non-negative floats, whose order is that of their bit patterns) as its two
+// middle elements: out[0] = element of rank (count - 1) / 2, out[1] = element of rank count / 2 (the
+// same element when count is odd); the median is their mean.  Every element finds its rank by
+// counting the (value, index) pairs below its own - count^2 comparisons spread over count / 64
+// workgroups - and the two that hit the middle ranks write themselves out: no sorting, no atomics,
+// and exactly one writer per slot.
+__global__ __launch_bounds__(256)
+void median_parts_kernel(const float* v, int count, float* out) {
+    extern __shared__ __align__(16) uint32_t keys[];        // count rounded up to 4; the padding holds the largest key
+    __shared__ int part_count[4][64];
     const int tid = threadIdx.x;
-    if (stat == 1) {
-        float s = 0.f;
-        for (int i = tid; i < count; i += 1024) s += v[i];
-        buf[tid] = s;
-        __syncthreads();
-        for (int half = 512; half > 0; half >>= 1) {
-            if (tid < half) buf[tid] += buf[tid + half];
-            __syncthreads();
-        }
-        if (tid == 0) *out = buf[0] / (float)count;
-        return;
-    }
-    uint32_t* keys = reinterpret_cast<uint32_t*>(buf);
-    for (int i = tid; i < count; i += 1024) keys[i] = __float_as_uint(v[i]);
+    const int padded = (count + 3) & ~3;
+    for (int i = tid; i < padded; i += 256) keys[i] = i < count ? __float_as_uint(v[i]) : 0xFFFFFFFFu;
     __syncthreads();
-    const uint32_t hi = select_rank(keys, count, count >> 1, hist, pick);
-    float m = __uint_as_float(hi);
-    if ((count & 1) == 0) {
-        const uint32_t lo = select_rank(keys, count, (count >> 1) - 1, hist, pick);
-        m = 0.5f * (__uint_as_float(lo) + m);
+    const int slot = tid & 63, part = tid >> 6;
+    const int i = blockIdx.x * 64 + slot;
+    int below = 0;
+    if (i < count) {
+        const uint4* keys4 = reinterpret_cast<const uint4*>(keys);
+        const int quads = padded / 4, chunk = (quads + 3) / 4;
+        const int lo = part * chunk, hi = min(quads, lo + chunk);
+        const uint64_t mine = ((uint64_t)keys[i] << 32) | (uint32_t)i;
+        auto is_below = [&](uint32_t kk, int k) { return ((((uint64_t)kk << 32) | (uint32_t)k) < mine) ? 1 : 0; };
+#pragma unroll 8
+        for (int qd = lo; qd < hi; ++qd) {
+            const uint4 kk = keys4[qd];
+            below += is_below(kk.x, 4 * qd) + is_below(kk.y, 4 * qd + 1) + is_below(kk.z, 4 * qd + 2) + is_below(kk.w, 4 * qd + 3);
+        }
     }
-    if (tid == 0) *out = m;
+    part_count[part][slot] = below;
+    __syncthreads();
+    if (part != 0 || i >= count) return;
+    const int rank = part_count[0][slot] + part_count[1][slot] + part_count[2][slot] + part_count[3][slot];
+    if (rank == (count - 1) / 2) out[0] = __uint_as_float(keys[i]);
+    if (rank == count / 2) out[1] = __uint_as_float(keys[i]);
 }
 
 template <bool BF16>
@@ -165,7 +145,7 @@ void make_shields_kernel(const float* G, int64_t ldg, const float* gnorm, const 
     const int i = blockIdx.y;
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= d) return;
-    const float f = scale * (*stat) / gnorm[i];
+    const float f = scale * (0.5f * (stat[0] + stat[1])) / gnorm[i];
     const float x = G[(int64_t)i * ldg + c] * f;
     if (BF16) ((__bf16*)S)[(int64_t)i * lds + c] = (__bf16)x;
     else ((float*)S)[(int64_t)i * lds + c] = x;
@@ -245,9 +225,9 @@ hipError_t row_norms(const void* X, int is_bf16, int64_t ld, int rows, int cols,
 
 hipError_t norm_statistic(const float* v, int count, int stat, float* out, hipStream_t stream) {
     if (count <= 0) return hipErrorInvalidValue;
-    const size_t floats = count > 1024 ? (size_t)count : 1024;
-    hipLaunchKernelGGL(norm_statistic_kernel, dim3(1), dim3(1024), floats * sizeof(float), stream,
-                       v, count, stat, out);
+    if (stat == 1) hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, stream, v, count, out);
+    else hipLaunchKernelGGL(median_parts_kernel, dim3((count + 63) / 64), dim3(256), (size_t)((count + 3) & ~3) * sizeof(uint32_t),
+                            stream, v, count, out);
     return hipGetLastError();
 }
 
