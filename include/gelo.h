@@ -136,7 +136,9 @@ gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, in
 /* Test hook: copies the secrets of a mixing object to caller DEVICE buffers (any may be NULL):
  * A and A_inv as float n x n (dense), S as float k_shield x d (dense; valid after gelo_mix).
  * attempt / kappa are HOST pointers: the accepted attempt number and the library's estimate of
- * kappa_2(A) (1 for ORTHOGONAL). */
+ * kappa_2(A) (1 for ORTHOGONAL and STRUCTURED).  A STRUCTURED object holds no matrix: A and A_inv
+ * are built here by transforming the identity, in the context workspace that gelo_qkv_forward also
+ * uses for U / Y when they are not passed in - do not run the two at the same time on one context. */
 gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* mixing, float* A, float* A_inv,
                                float* S, int* attempt, float* kappa, void* stream);
 
