@@ -98,8 +98,8 @@ const char* gelo_status_string(gelo_status s);
  * attempts side by side on streams of its own (n <= 1024; one at a time beyond), reads their
  * condition estimates back (the only host synchronisation in the library) and returns the first
  * acceptable attempt in order, so the result does not depend on how many ran at once.
- * n <= GELO_MAX_N (for GELO_STRUCTURED also n rows x 8 floats must fit in one workgroup's LDS:
- * the same 5120 on this chip), n_data >= 1,
+ * n <= GELO_MAX_N (GELO_STRUCTURED keeps 4 columns of all n rows in one workgroup's LDS at least,
+ * which allows more rows than that on this chip), n_data >= 1,
  * k_shield >= 0, d a multiple of 8.  *out is owned by the library: release it with
  * gelo_mixing_free (which recycles its device memory inside the context). */
 gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d,

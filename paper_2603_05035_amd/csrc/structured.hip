@@ -80,10 +80,14 @@ struct StructuredArgs {
     int n, ncols, rounds, inverse;
 };
 
-// Row r of the strip sits at LDS row r ^ ((r >> 4) & 15): a permutation inside every aligned group
-// of 16 rows that makes each butterfly pass free of bank conflicts, whichever row bits its lanes
-// run over (a thread reads rows that differ in four bits; its neighbours differ in the others).
-__device__ __forceinline__ int lds_row(int r) { return r ^ ((r >> 4) & 15); }
+// Row r of the strip sits at LDS row r + r / 16: one empty row after every 16.  Without it the first
+// butterfly pass, whose neighbouring lanes hold neighbouring groups of 16 rows, would put them all on
+// the same banks; with it every pass is free of bank conflicts, and the LDS rows of a butterfly
+// first + j 2^s0 are the first one plus offsets that depend on j and s0 only (lds_offset): one
+// address per item, the rest scalar.
+__device__ __forceinline__ int lds_row(int r) { return r + (r >> 4); }
+__device__ __forceinline__ int lds_offset(int j, int s0) { return (j << s0) + ((j << s0) >> 4); }
+inline size_t lds_rows(int n) { const size_t p = (size_t)round_up(n, 16); return p + p / 16; }
 
 // exponent of the block of row r < n: the highest bit in which r and n differ (there n has a one:
 // r lies in the block that this bit of n stands for)
@@ -120,14 +124,15 @@ __device__ __forceinline__ void store_quad(uint16_t* p, float4 v) {
 }
 
 // NS butterfly stages s0 .. s0 + NS - 1 on the 2^NS rows first + j 2^s0 of quad column q, which the
-// caller knows to lie in one block of at least 2^(s0 + NS) rows: registers, one LDS read and one
-// write per row.
+// caller knows to lie in one block of at least 2^(s0 + NS) rows (so bits s0 .. s0 + NS - 1 of `first`
+// are zero, which is what makes lds_offset exact): registers, one LDS read and one write per row.
 template <int QW, int NS>
 __device__ __forceinline__ void butterfly_rows(float4* X, int first, int s0, int q) {
     constexpr int RW = 1 << NS;
+    float4* x0 = X + lds_row(first) * QW + q;
     float4 v[RW];
 #pragma unroll
-    for (int j = 0; j < RW; ++j) v[j] = X[lds_row(first + (j << s0)) * QW + q];
+    for (int j = 0; j < RW; ++j) v[j] = x0[lds_offset(j, s0) * QW];
 #pragma unroll
     for (int k = 0; k < NS; ++k)
 #pragma unroll
@@ -138,7 +143,7 @@ __device__ __forceinline__ void butterfly_rows(float4* X, int first, int s0, int
                 v[j | (1 << k)] = sub4(a, c);
             }
 #pragma unroll
-    for (int j = 0; j < RW; ++j) X[lds_row(first + (j << s0)) * QW + q] = v[j];
+    for (int j = 0; j < RW; ++j) x0[lds_offset(j, s0) * QW] = v[j];
 }
 
 // One pass of the block Walsh-Hadamard transform: stages s0 .. s0 + NS - 1 (stage s pairs rows 2^s
@@ -193,9 +198,9 @@ __device__ __forceinline__ void block_hadamard(float4* X, int n) {
     }
 }
 
-constexpr int kMaxQuads = 20;      // quads per thread: a strip has at most 512 x 20 of them (160 KB of LDS)
+constexpr int kMaxQuads = 20;      // quads per thread: a strip has fewer than 512 x 20 of them (160 KB of LDS)
 
-// T: float or uint16_t (bf16 bits).  CW columns per workgroup, 512 threads, n x CW floats of LDS.
+// T: float or uint16_t (bf16 bits).  CW columns per workgroup, 512 threads, lds_rows(n) x CW floats of LDS.
 // In the permutations between the rounds a thread owns whole rows of the strip (rows tid, tid + 512, ...):
 // one table entry, one sign, one scale and one pair of row addresses serve all the columns of a row.
 template <typename T, int CW>
@@ -326,17 +331,18 @@ hipError_t launch_apply(const StructuredArgs& a, size_t lds, hipStream_t s) {
     return hipGetLastError();
 }
 
-// 16 columns per workgroup while n rows of them fit in LDS (2560 rows), 8 beyond that.  (Half-size
+// 16 columns per workgroup while the strip fits in LDS (2400 rows), then 8 (4816 rows), then 4.  (Half-size
 // workgroups, two per CU, so that one's loads overlap the other's butterflies, were 8% slower: the
 // kernel is bound by vector-ALU issue, not by its memory phases.)  Short strips (decode-shaped
 // batches of at most 512 rows) take 64 columns: a workgroup's fixed cost - a dozen barriers and four
 // dependent trips to memory - is then paid by 64 instead of 256 or 768 workgroups.
 template <typename T>
 hipError_t dispatch_apply(const StructuredArgs& a, hipStream_t s) {
-    const size_t rows_pad = (size_t)round_up(a.n, 16);
-    if (a.n <= 512 && a.ncols >= 2048) return launch_apply<T, 64>(a, rows_pad * 256, s);
-    if (rows_pad * 64 <= (size_t)g_lds_cap) return launch_apply<T, 16>(a, rows_pad * 64, s);
-    if (rows_pad * 32 <= (size_t)g_lds_cap) return launch_apply<T, 8>(a, rows_pad * 32, s);
+    const size_t rows = lds_rows(a.n);
+    if (a.n <= 512 && a.ncols >= 2048) return launch_apply<T, 64>(a, rows * 256, s);
+    if (rows * 64 <= (size_t)g_lds_cap) return launch_apply<T, 16>(a, rows * 64, s);
+    if (rows * 32 <= (size_t)g_lds_cap) return launch_apply<T, 8>(a, rows * 32, s);
+    if (rows * 16 <= (size_t)g_lds_cap) return launch_apply<T, 4>(a, rows * 16, s);
     return hipErrorInvalidValue;
 }
 
@@ -354,11 +360,13 @@ hipError_t structured_init() {
     if ((e = allow_lds<uint16_t, 64>()) != hipSuccess) return e;
     if ((e = allow_lds<float, 16>()) != hipSuccess) return e;
     if ((e = allow_lds<float, 8>()) != hipSuccess) return e;
+    if ((e = allow_lds<float, 4>()) != hipSuccess) return e;
     if ((e = allow_lds<uint16_t, 16>()) != hipSuccess) return e;
-    return allow_lds<uint16_t, 8>();
+    if ((e = allow_lds<uint16_t, 8>()) != hipSuccess) return e;
+    return allow_lds<uint16_t, 4>();
 }
 
-int structured_max_rows() { return g_lds_cap / 32 / 16 * 16; }   // 8 columns of floats per row at least
+int structured_max_rows() { return g_lds_cap / 16 / 17 * 16; }   // 4 columns of floats per row, one padding row per 16
 
 hipError_t structured_tables(uint32_t* table, int n, int rounds, PhiloxStream ps, hipStream_t s) {
     const size_t lds = (size_t)round_up(n, 4) * sizeof(uint32_t);
