@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <new>
 #include <string>
 #include <unordered_set>
@@ -67,6 +68,13 @@ struct gelo_ctx {
     hipEvent_t lane_join;              // the winner's copies out of `cand` (on the caller's stream) are done
     bool lanes_ready, join_pending;
     void* cand; size_t cand_bytes;     // per lane: candidate A, A^-1 (float, and bf16 copies)
+    // Everything of an attempt behind the Gaussian fill (about 125 launches that depend on nothing but
+    // the lane's buffers) is captured once per lane into a graph and replayed: the host then spends one
+    // launch instead of 125 per attempt, which is what lets four lanes really run side by side.
+    hipGraphExec_t lane_graph[kLanes];
+    bool lane_graph_ok[kLanes];
+    int graph_n; bool graph_bf; void* graph_ws; void* graph_cand;   // what the graphs were captured for
+    bool use_graphs;                   // off when GELO_EAGER_ATTEMPTS is set in the environment (tests compare the two)
 };
 
 namespace {
@@ -144,6 +152,13 @@ gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, b
     return GELO_OK;
 }
 
+void drop_lane_graphs(gelo_ctx* ctx) {
+    for (int i = 0; i < kLanes; ++i) {
+        if (ctx->lane_graph_ok[i]) (void)hipGraphExecDestroy(ctx->lane_graph[i]);
+        ctx->lane_graph_ok[i] = false;
+    }
+}
+
 gelo_status ensure_lanes(gelo_ctx* ctx) {
     if (ctx->lanes_ready) return GELO_OK;
     GELO_HIP(ctx, hipEventCreateWithFlags(&ctx->lane_fork, hipEventDisableTiming));
@@ -208,6 +223,9 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
     ctx->factor_ws = ctx->chain_ws = nullptr; ctx->factor_ws_bytes = ctx->chain_ws_bytes = 0;
     ctx->host_scalars = nullptr; ctx->host_flag = nullptr;
     ctx->lanes_ready = false; ctx->join_pending = false; ctx->cand = nullptr; ctx->cand_bytes = 0;
+    for (int i = 0; i < kLanes; ++i) ctx->lane_graph_ok[i] = false;
+    ctx->graph_n = 0; ctx->graph_bf = false; ctx->graph_ws = ctx->graph_cand = nullptr;
+    ctx->use_graphs = std::getenv("GELO_EAGER_ATTEMPTS") == nullptr;
     if (hipHostMalloc((void**)&ctx->host_scalars, 64, hipHostMallocDefault) != hipSuccess) { delete ctx; return GELO_ENOMEM; }
     ctx->host_flag = (int*)(ctx->host_scalars + 8);
     if (gemm_bf16_init() != hipSuccess || gemm_f32_init() != hipSuccess || lu_init() != hipSuccess ||
@@ -227,6 +245,7 @@ gelo_status gelo_destroy(gelo_ctx* ctx) {
         hipFree(m->block);
         delete m;
     }
+    drop_lane_graphs(ctx);
     if (ctx->lanes_ready) {
         (void)hipEventDestroy(ctx->lane_fork); (void)hipEventDestroy(ctx->lane_join);
         for (int i = 0; i < kLanes; ++i) { (void)hipStreamDestroy(ctx->lane_stream[i]); (void)hipEventDestroy(ctx->lane_done[i]); }
@@ -325,6 +344,10 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
             st = grow(ctx, &ctx->cand, &ctx->cand_bytes, lane_cand * lanes);
             if (st == GELO_OK) st = ensure_lanes(ctx);
             if (st != GELO_OK) return st;
+            if (ctx->graph_n != n || ctx->graph_bf != bf || ctx->graph_ws != ctx->factor_ws || ctx->graph_cand != ctx->cand) {
+                drop_lane_graphs(ctx);      // captured for other buffers or another size
+                ctx->graph_n = n; ctx->graph_bf = bf; ctx->graph_ws = ctx->factor_ws; ctx->graph_cand = ctx->cand;
+            }
         }
         bool accepted = false, singular_last = false;
         for (int base = 0; base < max_attempts && !accepted; base += lanes) {
@@ -347,13 +370,36 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
                 }
                 ps.c1 = (kStreamMixing << 8) | (uint32_t)(base + i);
                 GELO_HIP(ctx, fill_normal(lw[i].M, ld, n, n, ps, 1.0f / std::sqrt((float)n), 0, ls));
-                GELO_HIP(ctx, emit_matrix(lw[i].M, ld, 0, nullptr, n, ldk, cA32[i], cA16[i], nullptr, nullptr, ls));
-                GELO_HIP(ctx, pad_matrix(lw[i].M, ld, n, lw[i].n_pad, 1, ls));
-                GELO_HIP(ctx, lu_inverse(lw[i], ls));
-                GELO_HIP(ctx, emit_matrix(lw[i].X, ld, 0, nullptr, n, ldk, cAi32[i], cAi16[i], nullptr, nullptr, ls));
-                GELO_HIP(ctx, kappa_estimate(cA32[i], cAi32[i], ldk, n, lw[i], kKappaSteps, ls));
-                GELO_HIP(ctx, hipMemcpyAsync(ctx->host_scalars + i, lw[i].scalars, sizeof(float), hipMemcpyDeviceToHost, ls));
-                GELO_HIP(ctx, hipMemcpyAsync(ctx->host_flag + i, lw[i].flag, sizeof(int), hipMemcpyDeviceToHost, ls));
+                // everything behind the fill: the same launches for every attempt of this lane
+                auto factorise = [&]() -> hipError_t {
+                    hipError_t e = emit_matrix(lw[i].M, ld, 0, nullptr, n, ldk, cA32[i], cA16[i], nullptr, nullptr, ls);
+                    if (e == hipSuccess) e = pad_matrix(lw[i].M, ld, n, lw[i].n_pad, 1, ls);
+                    if (e == hipSuccess) e = lu_inverse(lw[i], ls);
+                    if (e == hipSuccess) e = emit_matrix(lw[i].X, ld, 0, nullptr, n, ldk, cAi32[i], cAi16[i], nullptr, nullptr, ls);
+                    if (e == hipSuccess) e = kappa_estimate(cA32[i], cAi32[i], ldk, n, lw[i], kKappaSteps, ls);
+                    if (e == hipSuccess) e = hipMemcpyAsync(ctx->host_scalars + i, lw[i].scalars, sizeof(float), hipMemcpyDeviceToHost, ls);
+                    if (e == hipSuccess) e = hipMemcpyAsync(ctx->host_flag + i, lw[i].flag, sizeof(int), hipMemcpyDeviceToHost, ls);
+                    return e;
+                };
+                if (lanes > 1 && ctx->use_graphs) {
+                    if (!ctx->lane_graph_ok[i]) {
+                        GELO_HIP(ctx, hipStreamBeginCapture(ls, hipStreamCaptureModeRelaxed));
+                        const hipError_t e_body = factorise();
+                        hipGraph_t graph = nullptr;
+                        const hipError_t e_end = hipStreamEndCapture(ls, &graph);      // also ends a failed capture
+                        if (e_body != hipSuccess || e_end != hipSuccess || !graph) {
+                            if (graph) (void)hipGraphDestroy(graph);
+                            return hip_fail(ctx, e_body != hipSuccess ? e_body : e_end, "capturing an attempt");
+                        }
+                        const hipError_t e_inst = hipGraphInstantiate(&ctx->lane_graph[i], graph, nullptr, nullptr, 0);
+                        (void)hipGraphDestroy(graph);
+                        if (e_inst != hipSuccess) return hip_fail(ctx, e_inst, "hipGraphInstantiate");
+                        ctx->lane_graph_ok[i] = true;
+                    }
+                    GELO_HIP(ctx, hipGraphLaunch(ctx->lane_graph[i], ls));
+                } else {
+                    GELO_HIP(ctx, factorise());
+                }
                 if (lanes > 1) GELO_HIP(ctx, hipEventRecord(ctx->lane_done[i], ls));
             }
             if (lanes > 1) {

@@ -543,3 +543,37 @@ def test_sampling_ahead_on_side_streams_matches_one_stream():
     for za, zb in zip(a, b):
         assert torch.equal(za, zb)
         assert o.rel_frobenius(f64(zb), ref) < TOL_END["bf16"]
+
+
+def test_gaussian_attempts_replayed_from_a_graph_equal_eager_launches(monkeypatch):
+    """Beyond the first call a GAUSSIAN attempt is a replay of launches captured per lane.  Two contexts with
+    the same seed, one of them told to launch everything eagerly: the accepted attempt, kappa, A and A^-1
+    must agree bit for bit on every batch, first use and replays alike, with other work of the library
+    (a whole chain of another kind, a draw of another size that invalidates the captured graphs) in between."""
+    n, d = 200, 64
+    monkeypatch.setenv("GELO_EAGER_ATTEMPTS", "1")
+    eager = g.gelo_create(0, 0xFACE, allow_batch_reuse=False)
+    monkeypatch.delenv("GELO_EAGER_ATTEMPTS")
+    replay = g.gelo_create(0, 0xFACE, allow_batch_reuse=False)
+    H, W = dev(wl.make_hidden(48, d, 3, 2), "f32"), dev(wl.make_weight(d, 40, 4), "f32")
+    Z = torch.empty((48, 40), dtype=torch.float32, device="cuda")
+    try:
+        for bid in range(6):
+            size = n if bid != 3 else 136                  # another size once: the graphs are captured again
+            out = []
+            for c in (eager, replay):
+                m = g.gelo_sample_mixing(c, g.GELO_GAUSSIAN, size, 0, d, g.GELO_F32, 600.0 + 100.0 * bid, 64, batch_id=bid)
+                A, A_inv, _, attempt, kappa = g.gelo_mixing_export(c, m, size, 0, d)
+                torch.cuda.synchronize()
+                g.gelo_mixing_free(c, m)
+                out.append((A.clone(), A_inv.clone(), attempt, kappa))
+                g.gelo_qkv_forward(c, g.GELO_ORTHOGONAL, H, W, Z, k_shield=2, batch_id=100 + bid)   # eager work in between
+                torch.cuda.synchronize()
+            assert out[0][2] == out[1][2] and out[0][3] == out[1][3], (bid, out[0][2:], out[1][2:])
+            assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1])
+            A64 = f64(out[1][0])
+            assert np.linalg.cond(A64) <= (600.0 + 100.0 * bid) * 1.05
+            assert np.linalg.norm(A64 @ f64(out[1][1]) - np.eye(size)) / math.sqrt(size) < 1e-3
+    finally:
+        g.gelo_destroy(eager)
+        g.gelo_destroy(replay)
