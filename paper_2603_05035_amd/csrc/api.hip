@@ -381,21 +381,26 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
                     if (e == hipSuccess) e = hipMemcpyAsync(ctx->host_flag + i, lw[i].flag, sizeof(int), hipMemcpyDeviceToHost, ls);
                     return e;
                 };
-                if (lanes > 1 && ctx->use_graphs) {
-                    if (!ctx->lane_graph_ok[i]) {
-                        GELO_HIP(ctx, hipStreamBeginCapture(ls, hipStreamCaptureModeRelaxed));
+                if (lanes > 1 && ctx->use_graphs && !ctx->lane_graph_ok[i]) {
+                    // a capture records and runs nothing; if the runtime refuses any part of it, this
+                    // context goes back to launching every attempt kernel by kernel
+                    hipGraph_t graph = nullptr;
+                    bool ok = hipStreamBeginCapture(ls, hipStreamCaptureModeRelaxed) == hipSuccess;
+                    if (ok) {
                         const hipError_t e_body = factorise();
-                        hipGraph_t graph = nullptr;
                         const hipError_t e_end = hipStreamEndCapture(ls, &graph);      // also ends a failed capture
-                        if (e_body != hipSuccess || e_end != hipSuccess || !graph) {
-                            if (graph) (void)hipGraphDestroy(graph);
-                            return hip_fail(ctx, e_body != hipSuccess ? e_body : e_end, "capturing an attempt");
-                        }
-                        const hipError_t e_inst = hipGraphInstantiate(&ctx->lane_graph[i], graph, nullptr, nullptr, 0);
-                        (void)hipGraphDestroy(graph);
-                        if (e_inst != hipSuccess) return hip_fail(ctx, e_inst, "hipGraphInstantiate");
-                        ctx->lane_graph_ok[i] = true;
+                        ok = e_body == hipSuccess && e_end == hipSuccess && graph != nullptr;
                     }
+                    if (ok) ok = hipGraphInstantiate(&ctx->lane_graph[i], graph, nullptr, nullptr, 0) == hipSuccess;
+                    if (graph) (void)hipGraphDestroy(graph);
+                    if (ok) {
+                        ctx->lane_graph_ok[i] = true;
+                    } else {
+                        (void)hipGetLastError();
+                        ctx->use_graphs = false;
+                    }
+                }
+                if (lanes > 1 && ctx->use_graphs && ctx->lane_graph_ok[i]) {
                     GELO_HIP(ctx, hipGraphLaunch(ctx->lane_graph[i], ls));
                 } else {
                     GELO_HIP(ctx, factorise());
