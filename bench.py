@@ -294,6 +294,18 @@ def main() -> int:
                               "achieved": b_proj / t_proj / 1e9, "peak": 8000.0, "unit": "GB/s",
                               "frac": b_proj / t_proj / 1e9 / 8000.0, "traffic": None, "avg_launch_us": t_proj * 1e6}
 
+    if n <= 128:
+        # HBM rate of the two small-n mixing calls of a decode-shaped batch (algorithmic bytes of eq. 1 / eq. 3:
+        # every operand read once, the result written once; the stage times include the shield kernels of mix)
+        esz = 2 if w.dtype == "bf16" else 4
+        a_bytes = 0.0 if w.kind == 3 else float(esz) * n * n            # the structured kind reads tables, not a matrix
+        b_mix = a_bytes + float(esz) * (nd * d + k * d + n * d)
+        b_unmix = (a_bytes * nd / n) + float(esz) * (n * p + nd * p)
+        result["small_n_mixing"] = {"mix_GBps": b_mix / (stage["mix"] * 1e-3) / 1e9, "mix_us": stage["mix"] * 1e3,
+                                    "unmix_GBps": b_unmix / (stage["unmix"] * 1e-3) / 1e9, "unmix_us": stage["unmix"] * 1e3,
+                                    "peak_GBps": 8000.0,
+                                    "note": "both calls move about a megabyte and are bound by launch latency, not by HBM"}
+
     if w.kind == 3:
         # The second kernel of a structured step: the transform behind unmix (one launch, timed by the stage
         # events above).  Its butterflies are plain float additions on the vector ALUs; the peak is what
