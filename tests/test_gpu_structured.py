@@ -162,3 +162,28 @@ def test_structured_kind_rejects_what_it_cannot_hold(ctx):
     with pytest.raises(g.GeloError) as e:
         g.gelo_sample_mixing(ctx, g.GELO_STRUCTURED, 5120, 1, 64, g.GELO_F32, 0.0, 1, batch_id=1)
     assert g.STATUS_NAMES[e.value.status] == "GELO_ESHAPE"
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_strided_operands(ctx, dtype):
+    """Leading dimensions larger than the width (views into bigger buffers): the transform must keep to
+    its columns on the way in and on the way out, and the rows the unmix drops must stay unwritten."""
+    nd, k, d, p = 70, 4, 72, 136
+    td = TORCH_DTYPE[dtype]
+    big_h = torch.zeros((nd, d + 24), dtype=td, device="cuda")
+    H = big_h[:, :d]
+    H.copy_(torch.from_numpy(wl.make_hidden(nd, d, 9, 0)).to(td))
+    W = dev(wl.make_weight(d, p, 9), dtype)
+    U = torch.full((nd + k, d + 8), 7.0, dtype=td, device="cuda")[:, :d]
+    Y = torch.full((nd + k, p + 16), 7.0, dtype=td, device="cuda")[:, :p]
+    Zbuf = torch.full((nd + k, p + 8), 7.0, dtype=td, device="cuda")        # k rows more than the unmix writes
+    Z = Zbuf[:nd, :p]
+    m = g.gelo_sample_mixing(ctx, g.GELO_STRUCTURED, nd, k, d, CODE[dtype], 0.0, 1, batch_id=8001 + (dtype == "bf16"))
+    g.gelo_mix(ctx, m, H, U)
+    g.gelo_project(ctx, U, W, Y)
+    g.gelo_unmix(ctx, m, Y, Z)
+    torch.cuda.synchronize()
+    g.gelo_mixing_free(ctx, m)
+    assert o.rel_frobenius(f64(Z), o.plain_projection(f64(H), f64(W))) < TOL_END[dtype]
+    assert torch.all(U._base[:, d:] == 7.0) and torch.all(Y._base[:, p:] == 7.0)
+    assert torch.all(Zbuf[:, p:] == 7.0) and torch.all(Zbuf[nd:, :] == 7.0)      # shield rows are never stored
