@@ -437,8 +437,7 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
     }
     if (k_shield > 0) {
         ps.c1 = kStreamShield << 8;
-        GELO_HIP(ctx, fill_normal(m->GS, d, k_shield, d, ps, 1.0f, 0, s));
-        GELO_HIP(ctx, row_norms(m->GS, 0, d, k_shield, d, m->gsnorm, s));
+        GELO_HIP(ctx, shield_directions(m->GS, k_shield, d, ps, m->gsnorm, s));
     }
     GELO_HIP(ctx, hipEventRecord(m->ready, s));
     m->in_use = true; m->mixed = false; m->consumed = false; m->batch_id = batch_id;

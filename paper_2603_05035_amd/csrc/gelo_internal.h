@@ -81,6 +81,8 @@ __host__ __device__ inline int64_t qr_tile_index(int r, int c, int tile_rows) {
 // element goes to out[qr_tile_index(r, c, ld)] (ld = number of tile rows).
 hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale,
                        int tiled, hipStream_t stream);
+// GS[k x d] (pitch d) = N(0,1) with fill_normal's element order, gsnorm[i] = || GS[i, :] ||_2; d % 8 == 0
+hipError_t shield_directions(float* GS, int k, int d, PhiloxStream ps, float* gsnorm, hipStream_t stream);
 // dst[r * ldd + c] += scale * src[r * lds + c] over an rows x cols block
 hipError_t axpy_matrix(float* dst, int64_t ldd, const float* src, int64_t lds, int rows, int cols,
                        float scale, hipStream_t stream);

@@ -39,6 +39,31 @@ void fill_normal_kernel(float* out, int64_t ld, int rows, int cols, PhiloxStream
     }
 }
 
+// The k x d shield directions (row-major, pitch d, the same element-to-Philox-word map as
+// fill_normal_kernel) and their norms in one launch: one workgroup per row, partial sums of squares
+// added in a fixed order (lanes by halving, then the four waves in turn).
+__global__ __launch_bounds__(256)
+void shield_directions_kernel(float* GS, int d, PhiloxStream ps, float* gsnorm) {
+    __shared__ float wave_part[4];
+    const int i = blockIdx.x, tid = threadIdx.x;
+    const int quads = d / 4;                                  // d is a multiple of 8
+    float ss = 0.f;
+    for (int ql = tid; ql < quads; ql += 256) {
+        uint32_t c0 = (uint32_t)(i * quads + ql), c1 = ps.c1, c2 = ps.c2, c3 = ps.c3;
+        philox4x32_10(c0, c1, c2, c3, ps.key0, ps.key1);
+        float4 z;
+        box_muller(c0, c1, &z.x, &z.y);
+        box_muller(c2, c3, &z.z, &z.w);
+        *reinterpret_cast<float4*>(GS + (int64_t)i * d + 4 * ql) = z;
+        ss = fmaf(z.x, z.x, ss); ss = fmaf(z.y, z.y, ss); ss = fmaf(z.z, z.z, ss); ss = fmaf(z.w, z.w, ss);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if ((tid & 63) == 0) wave_part[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) gsnorm[i] = sqrtf(((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3]);
+}
+
 __global__ __launch_bounds__(256)
 void axpy_matrix_kernel(float* dst, int64_t ldd, const float* src, int64_t lds, int rows, int cols, float scale) {
     const int c = blockIdx.x * 256 + threadIdx.x;
@@ -203,6 +228,12 @@ hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream 
     if (quads == 0) return hipSuccess;
     hipLaunchKernelGGL(fill_normal_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
                        out, ld, rows, cols, ps, scale, tiled);
+    return hipGetLastError();
+}
+
+hipError_t shield_directions(float* GS, int k, int d, PhiloxStream ps, float* gsnorm, hipStream_t stream) {
+    if (k <= 0) return hipSuccess;
+    hipLaunchKernelGGL(shield_directions_kernel, dim3(k), dim3(256), 0, stream, GS, d, ps, gsnorm);
     return hipGetLastError();
 }
 
