@@ -49,3 +49,17 @@ def test_product_sources_do_not_reach_for_the_oracle():
             if f.endswith((".py", ".hip", ".h")) and f != "workloads.py":   # the shared input generator may mention it
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"(import|from)\s+oracle|gelo_oracle", text), f
+
+
+def test_enumerators_agree_between_header_binding_and_workloads():
+    """the numbers behind gelo_kind / gelo_dtype / gelo_norm_stat as the header spells them"""
+    from paper_2603_05035_amd import workloads as wl
+    text = open(os.path.join(ROOT, "include", "gelo.h")).read()
+    values = {name: int(v) for name, v in re.findall(r"\b(GELO_[A-Z0-9_]+)\s*=\s*(\d+)", text)}
+    for name in ("GELO_ORTHOGONAL", "GELO_GAUSSIAN", "GELO_CONDITIONED", "GELO_STRUCTURED", "GELO_F32", "GELO_BF16",
+                 "GELO_NORM_MEDIAN", "GELO_NORM_MEAN", "GELO_OK"):
+        assert getattr(binding, name) == values[name], name
+    assert (wl.KIND_ORTHOGONAL, wl.KIND_GAUSSIAN, wl.KIND_CONDITIONED, wl.KIND_STRUCTURED) == (
+        values["GELO_ORTHOGONAL"], values["GELO_GAUSSIAN"], values["GELO_CONDITIONED"], values["GELO_STRUCTURED"])
+    assert binding.STATUS_NAMES[values["GELO_ESHAPE"]] == "GELO_ESHAPE" and binding.STATUS_NAMES[values["GELO_EHIP"]] == "GELO_EHIP"
+    assert int(re.search(r"#define GELO_MAX_N (\d+)", text).group(1)) == binding.GELO_MAX_N
