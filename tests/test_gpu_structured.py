@@ -53,11 +53,12 @@ def test_dense_matrix_of_the_tables_matches_oracle(ctx, n_data, k):
     assert np.linalg.norm(f64(A) @ f64(A_inv) - np.eye(n)) / math.sqrt(n) < 1e-5
 
 
-@pytest.mark.parametrize("n_data,k", [(4096, 205), (5000, 120)])
+@pytest.mark.parametrize("n_data,k", [(2400, 0), (2401, 0), (4096, 205), (4816, 0), (4817, 0), (5000, 120)])
 def test_tables_at_the_narrow_strip_widths(ctx, n_data, k):
-    """Beyond 2560 rows a workgroup keeps 8 instead of 16 columns of the strip in LDS; at n = GELO_MAX_N
-    that takes all 160 KB of it.  The dense oracle matrix would cost minutes here: sampled columns of A
-    and A^T through the oracle's factor-by-factor transform, and orthogonality of the exported pair."""
+    """A workgroup keeps 16 columns of the strip in LDS up to 2400 rows (all 160 KB of it then), 8 up to 4816,
+    4 beyond, up to n = GELO_MAX_N: both sides of each boundary.  The dense oracle matrix would cost minutes
+    here: sampled columns of A and A^T through the oracle's factor-by-factor transform, and orthogonality of
+    the exported pair."""
     n = n_data + k
     bid = 51 + n
     m = g.gelo_sample_mixing(ctx, g.GELO_STRUCTURED, n_data, k, 64, g.GELO_F32, 0.0, 1, batch_id=bid)

@@ -159,3 +159,12 @@ def test_structured_apply_equals_the_dense_matrix():
         X = rng.standard_normal((n, 7))
         assert np.abs(o.structured_apply(perms, signs, X) - A @ X).max() < 1e-13
         assert np.abs(o.structured_apply(perms, signs, X, transposed=True) - A.T @ X).max() < 1e-13
+
+
+def test_bench_counts_the_butterflies_of_the_blocks():
+    """bench.py prices a structured step by its additions: m log2 m per block of the binary expansion"""
+    import bench
+    assert bench.butterfly_adds(2150) == 2048 * 11 + 64 * 6 + 32 * 5 + 4 * 2 + 2 * 1
+    assert bench.butterfly_adds(4096) == 4096 * 12 and bench.butterfly_adds(1) == 0
+    for n in (3, 70, 2150):
+        assert bench.butterfly_adds(n) == sum(m * int(math.log2(m)) for m in o.hadamard_blocks(n))
