@@ -1,8 +1,8 @@
 """Numerical stability of the offloaded projection under storage formats (the paper's Conclusion lists
 BF16 / FP16 / FP8 / INT8 as open; Table 1 only says the method is exact up to floating point).
 First the rounding functions are pinned by the formats' definitions; then the study: what the
-shield rows and the outlier channels do to the error of an 8-bit projection.  The figures are this
-build's, on synthetic hidden states (parity unpinned against the paper: it reports none)."""
+shield rows and the outlier channels do to the error of an 8-bit projection.  The figures are measured
+here, on synthetic hidden states (parity unpinned against the paper: it reports none)."""
 import math
 
 import numpy as np
