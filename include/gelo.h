@@ -31,6 +31,15 @@
  *  - A context is not thread-safe.  Sampling uses context-owned workspace, so
  *    two gelo_sample_mixing calls on one context must not overlap in time on
  *    different streams; sampling may overlap mix/project/unmix of other batches.
+ *  - Memory: a context owns a factorisation workspace, a pool of mixing objects and
+ *    (for gelo_qkv_forward without caller U / Y) a chain workspace.  gelo_reserve
+ *    sizes all three ahead of time; a per-batch call allocates only when it meets a
+ *    shape that was not reserved (first use), and only then may it synchronise the
+ *    device to replace a smaller buffer.  The per-batch calls make no host allocation.
+ *  - The kernels clamp out-of-range rows and columns of a ragged last tile to valid
+ *    addresses and multiply them by the zero padding of A; operand rows beyond the
+ *    contraction length are replaced by zeros, so a NaN or Inf in the data reaches
+ *    only the outputs that mathematically depend on it.
  */
 #ifndef GELO_H
 #define GELO_H
@@ -42,7 +51,7 @@
 extern "C" {
 #endif
 
-typedef struct gelo_ctx gelo_ctx;        /* device, Philox key (seed), workspace, set of used batch ids */
+typedef struct gelo_ctx gelo_ctx;        /* device, Philox key (seed), workspace, record of used batch ids */
 typedef struct gelo_mixing gelo_mixing;  /* the trusted side's secrets for ONE batch: A, A^-1, shield directions */
 
 typedef enum {
@@ -81,11 +90,30 @@ typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;
 
 #define GELO_MAX_N 5120        /* largest n = n_data + k_shield the factorisation kernels take */
 #define GELO_MAX_ATTEMPTS 255  /* the attempt number is one byte of the Philox counter */
+#define GELO_BATCH_WINDOW 4096 /* how far below the highest batch id used so far an unused id is still accepted */
 
 /* Creates a context on HIP device `device` with Philox key `seed`.  `allow_batch_reuse` != 0
  * switches off the check that a batch id is used at most once (for tests and benchmarks that
- * replay a batch; production callers pass 0: A must never be reused, Section 3.2 step 1.2). */
+ * replay a batch; production callers pass 0: A must never be reused, Section 3.2 step 1.2).
+ * The check keeps no growing set: with h = 1 + the highest id used so far, an id is refused
+ * (GELO_EREUSE) if it was used, if it lies below the floor (gelo_set_batch_floor), or if it lies
+ * more than GELO_BATCH_WINDOW below h; ids at or above h are always new.  Callers that number their
+ * batches upwards (layer by layer, step by step) never meet the window. */
 gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_batch_reuse);
+/* Checkpoint / resume of "never reused": A is a pure function of (seed, batch id), so the whole state
+ * of a context is its seed and the ids it has used.  gelo_get_batch_floor returns the smallest id f
+ * such that no id >= f has been used; a context created later with the same seed and
+ * gelo_set_batch_floor(ctx, f) refuses every id below f and so never derives an A a second time.
+ * The floor only moves up (GELO_EINVAL otherwise). */
+gelo_status gelo_set_batch_floor(gelo_ctx* ctx, uint64_t first_unused);
+gelo_status gelo_get_batch_floor(const gelo_ctx* ctx, uint64_t* first_unused);
+/* Sizes the context's device memory for batches of this shape before the first of them arrives:
+ * the factorisation workspace (and the side-by-side attempt buffers of GELO_GAUSSIAN with this
+ * max_attempts), `mixings` pooled mixing objects, and, if p > 0, the U / Y workspace of
+ * gelo_qkv_forward.  May synchronise the device and allocate; the per-batch calls that follow
+ * then do neither.  Arguments as in gelo_sample_mixing. */
+gelo_status gelo_reserve(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_data, int k_shield, int d, int p,
+                         int max_attempts, int mixings);
 gelo_status gelo_destroy(gelo_ctx* ctx);
 /* Message of the last failing call on `ctx` ("" if none).  Owned by the context. */
 const char* gelo_last_error(const gelo_ctx* ctx);
@@ -97,7 +125,10 @@ const char* gelo_status_string(gelo_status s);
  * (1..GELO_MAX_ATTEMPTS) are used by GELO_GAUSSIAN only: it factorises up to four consecutive
  * attempts side by side on streams of its own (n <= 1024; one at a time beyond), reads their
  * condition estimates back (the only host synchronisation in the library) and returns the first
- * acceptable attempt in order, so the result does not depend on how many ran at once.
+ * acceptable attempt in order, so the result does not depend on how many ran at once.  The
+ * estimate (20 Lanczos steps) approaches kappa_2 from below, within 0.5 % as measured; an attempt
+ * is accepted only if 1.01 x estimate <= cond_max, so an accepted A meets the bound itself
+ * ("generate and verify", Section 3.2.1) and a draw within 1 % below it may be redrawn.
  * n <= GELO_MAX_N (GELO_STRUCTURED keeps 4 columns of all n rows in one workgroup's LDS at least,
  * which allows more rows than that on this chip), n_data >= 1,
  * k_shield >= 0, d a multiple of 8.  *out is owned by the library: release it with
@@ -107,8 +138,11 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
                                uint64_t batch_id, gelo_mixing** out, void* stream);
 
 /* Trusted side, eq. 1 / eqs. 7-8.  Shield rows S_i = g_i * shield_scale * m(H) / ||g_i||, m the
- * median or mean row 2-norm of H; then U[n x d] = A * [H ; S].  H: n_data x d (ldh), U: n x d (ldu). */
-gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* mixing, const void* H, int64_t ldh,
+ * median or mean row 2-norm of H; then U[n x d] = A * [H ; S].  H: n_data x d (ldh), U: n x d (ldu),
+ * both of type `dtype`, which must be the one the mixing object was drawn for (GELO_EDTYPE otherwise:
+ * the kernels would read and write the buffers with the wrong element size).  The row counts are the
+ * mixing object's (gelo_mixing_info); the caller's buffers must hold them. */
+gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* mixing, gelo_dtype dtype, const void* H, int64_t ldh,
                      float shield_scale, gelo_norm_stat stat, void* U, int64_t ldu, void* stream);
 
 /* Accelerator side, eq. 2.  Y[n x p] = U[n x d] * W[d x p].  Touches no secret: it takes no
@@ -118,12 +152,17 @@ gelo_status gelo_project(gelo_ctx* ctx, gelo_dtype dtype, int n, int d, int p,
                          void* Y, int64_t ldy, void* stream);
 
 /* Trusted side, eq. 3 + shield drop.  Z[n_data x p] = (A^-1 * Y)[0:n_data, :]; the shield rows
- * of the product are never computed.  Y: n x p (ldy).  Marks the mixing consumed: a second
+ * of the product are never computed.  Y: n x p (ldy), Z: n_data x p (ldz), both of type `dtype`
+ * (GELO_EDTYPE if it is not the mixing object's).  Marks the mixing consumed: a second
  * gelo_mix or gelo_unmix on it returns GELO_EREUSE. */
-gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* mixing, int p, const void* Y, int64_t ldy,
+gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* mixing, gelo_dtype dtype, int p, const void* Y, int64_t ldy,
                        void* Z, int64_t ldz, void* stream);
 
 gelo_status gelo_mixing_free(gelo_ctx* ctx, gelo_mixing* mixing);
+/* Shape and type a mixing object was drawn for (any out pointer may be NULL): H is n_data x d,
+ * U is (n_data + k_shield) x d, Y is (n_data + k_shield) x p, Z is n_data x p. */
+gelo_status gelo_mixing_info(gelo_ctx* ctx, const gelo_mixing* mixing, int* n_data, int* k_shield, int* d,
+                             gelo_dtype* dtype, gelo_kind* kind);
 
 /* The whole chain for one batch: sample, mix, project, unmix (eqs. 1-3).  H: n_data x d, W: d x p,
  * Z: n_data x p, all densely packed (leading dimension = width).  U_opt (n x d) and Y_opt (n x p)
@@ -141,6 +180,18 @@ gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, in
  * uses for U / Y when they are not passed in - do not run the two at the same time on one context. */
 gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* mixing, float* A, float* A_inv,
                                float* S, int* attempt, float* kappa, void* stream);
+
+/* Test hooks for bitwise checks of the integer work.
+ * gelo_debug_philox_words: words[4 i .. 4 i + 3] (DEVICE, 16-byte aligned) = the four 32-bit outputs of
+ * Philox4x32-10 for counter (first_block + i, stream_id << 8 | attempt, batch id low, batch id high)
+ * under the context's key; stream ids: 0 mixing Gaussian (attempt = redraw number), 1 shield
+ * directions, 2 CONDITIONED perturbation, 3 sort keys of permutation r and 4 sign words of round r of
+ * the structured kind (r travels in the attempt byte).
+ * gelo_mixing_export_table: the (rounds + 1) x n words of a GELO_STRUCTURED object (entry j of
+ * permutation r in the low 31 bits, sign flip of position j in round r in the top bit) to a DEVICE buffer. */
+gelo_status gelo_debug_philox_words(gelo_ctx* ctx, uint32_t stream_id, uint32_t attempt, uint64_t batch_id,
+                                    uint32_t first_block, uint32_t blocks, uint32_t* words, void* stream);
+gelo_status gelo_mixing_export_table(gelo_ctx* ctx, const gelo_mixing* mixing, uint32_t* table, void* stream);
 
 #ifdef __cplusplus
 }

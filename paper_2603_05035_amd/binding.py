@@ -6,7 +6,7 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import (POINTER, byref, c_char_p, c_double, c_float, c_int, c_int64, c_uint64,
+from ctypes import (POINTER, byref, c_char_p, c_double, c_float, c_int, c_int64, c_uint32, c_uint64,
                     c_void_p)
 
 import torch
@@ -18,6 +18,7 @@ GELO_OK = 0
 STATUS_NAMES = ["GELO_OK", "GELO_EINVAL", "GELO_ESHAPE", "GELO_EDTYPE", "GELO_EALIGN", "GELO_ENOMEM",
                 "GELO_ECOND", "GELO_ESINGULAR", "GELO_EREUSE", "GELO_ESTATE", "GELO_EHIP"]
 GELO_MAX_N = 5120
+GELO_BATCH_WINDOW = 4096
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgelo.so")
 
@@ -29,11 +30,18 @@ SIGNATURES = {
     "gelo_status_string": (c_char_p, [c_int]),
     "gelo_sample_mixing": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_double, c_int, c_uint64,
                                    POINTER(c_void_p), c_void_p]),
-    "gelo_mix": (c_int, [c_void_p, c_void_p, c_void_p, c_int64, c_float, c_int, c_void_p, c_int64, c_void_p]),
+    "gelo_set_batch_floor": (c_int, [c_void_p, c_uint64]),
+    "gelo_get_batch_floor": (c_int, [c_void_p, POINTER(c_uint64)]),
+    "gelo_reserve": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int]),
+    "gelo_mix": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_int64, c_float, c_int, c_void_p, c_int64, c_void_p]),
     "gelo_project": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_int64, c_void_p, c_int64,
                              c_void_p, c_int64, c_void_p]),
-    "gelo_unmix": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_int64, c_void_p, c_int64, c_void_p]),
+    "gelo_unmix": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int64, c_void_p, c_int64, c_void_p]),
     "gelo_mixing_free": (c_int, [c_void_p, c_void_p]),
+    "gelo_mixing_info": (c_int, [c_void_p, c_void_p, POINTER(c_int), POINTER(c_int), POINTER(c_int), POINTER(c_int),
+                                 POINTER(c_int)]),
+    "gelo_debug_philox_words": (c_int, [c_void_p, c_uint32, c_uint32, c_uint64, c_uint32, c_uint32, c_void_p, c_void_p]),
+    "gelo_mixing_export_table": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p]),
     "gelo_qkv_forward": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_float,
                                  c_int, c_double, c_int, c_uint64, c_void_p, c_void_p, c_void_p, c_void_p]),
     "gelo_mixing_export": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, POINTER(c_int),
@@ -114,13 +122,33 @@ def gelo_sample_mixing(ctx, kind: int, n_data: int, k_shield: int, d: int, dtype
     return mixing
 
 
+def gelo_mixing_info(ctx, mixing):
+    """(n_data, k_shield, d, dtype code, kind) the mixing object was drawn for."""
+    v = [c_int() for _ in range(5)]
+    _check(ctx, load_library().gelo_mixing_info(ctx, mixing, *[byref(x) for x in v]))
+    return tuple(x.value for x in v)
+
+
+def _check_against_mixing(ctx, mixing, tensors):
+    """`tensors`: (name, tensor, rows expected ('n' or 'n_data'), width expected ('d' or None)).  The C ABI
+    sees raw pointers; here the tensors carry shapes and types, so every mismatch that would make a kernel
+    leave the caller's buffers is refused before the call."""
+    n_data, k, d, code, _ = gelo_mixing_info(ctx, mixing)
+    rows = {"n": n_data + k, "n_data": n_data}
+    for name, t, r, w in tensors:
+        if _dtype_code(t) != code:
+            raise GeloError(3, f"{name} is {t.dtype} but the mixing object was drawn for {'bf16' if code == GELO_BF16 else 'f32'}")
+        if t.dim() != 2 or t.shape[0] != rows[r] or (w == "d" and t.shape[1] != d):
+            raise GeloError(2, f"{name} has shape {tuple(t.shape)}; this mixing object needs {rows[r]} rows"
+                               + (f" of width {d}" if w == "d" else ""))
+
+
 def gelo_mix(ctx, mixing, H: torch.Tensor, U: torch.Tensor, shield_scale: float = 10.0,
              stat: int = GELO_NORM_MEDIAN, stream=None) -> torch.Tensor:
     hp, ldh = _matrix(H, "H")
     up, ldu = _matrix(U, "U")
-    if H.dtype != U.dtype:
-        raise TypeError("H and U must have the same dtype")
-    _check(ctx, load_library().gelo_mix(ctx, mixing, hp, ldh, shield_scale, stat, up, ldu, _stream(stream)))
+    _check_against_mixing(ctx, mixing, (("H", H, "n_data", "d"), ("U", U, "n", "d")))
+    _check(ctx, load_library().gelo_mix(ctx, mixing, _dtype_code(H), hp, ldh, shield_scale, stat, up, ldu, _stream(stream)))
     return U
 
 
@@ -139,9 +167,10 @@ def gelo_project(ctx, U: torch.Tensor, W: torch.Tensor, Y: torch.Tensor, stream=
 def gelo_unmix(ctx, mixing, Y: torch.Tensor, Z: torch.Tensor, stream=None) -> torch.Tensor:
     yp, ldy = _matrix(Y, "Y")
     zp, ldz = _matrix(Z, "Z")
-    if Y.dtype != Z.dtype or Y.shape[1] != Z.shape[1]:
-        raise ValueError("shape or dtype mismatch in gelo_unmix")
-    _check(ctx, load_library().gelo_unmix(ctx, mixing, Y.shape[1], yp, ldy, zp, ldz, _stream(stream)))
+    if Y.shape[1] != Z.shape[1]:
+        raise GeloError(2, "Y and Z must have the same width")
+    _check_against_mixing(ctx, mixing, (("Y", Y, "n", None), ("Z", Z, "n_data", None)))
+    _check(ctx, load_library().gelo_unmix(ctx, mixing, _dtype_code(Y), Y.shape[1], yp, ldy, zp, ldz, _stream(stream)))
     return Z
 
 
@@ -169,6 +198,37 @@ def gelo_qkv_forward(ctx, kind: int, H: torch.Tensor, W: torch.Tensor, Z: torch.
         c_void_p(U.data_ptr()) if U is not None else None, c_void_p(Y.data_ptr()) if Y is not None else None,
         _stream(stream)))
     return Z
+
+
+def gelo_reserve(ctx, kind: int, dtype: int, n_data: int, k_shield: int, d: int, p: int = 0,
+                 max_attempts: int = 64, mixings: int = 1) -> None:
+    _check(ctx, load_library().gelo_reserve(ctx, kind, dtype, n_data, k_shield, d, p, max_attempts, mixings))
+
+
+def gelo_set_batch_floor(ctx, first_unused: int) -> None:
+    _check(ctx, load_library().gelo_set_batch_floor(ctx, first_unused))
+
+
+def gelo_get_batch_floor(ctx) -> int:
+    v = c_uint64()
+    _check(ctx, load_library().gelo_get_batch_floor(ctx, byref(v)))
+    return v.value
+
+
+def gelo_debug_philox_words(ctx, stream_id: int, attempt: int, batch_id: int, first_block: int, blocks: int,
+                            stream=None) -> torch.Tensor:
+    """Test hook: blocks x 4 raw Philox words (int32 tensor holding the uint32 bit patterns)."""
+    words = torch.empty((blocks, 4), dtype=torch.int32, device="cuda")
+    _check(ctx, load_library().gelo_debug_philox_words(ctx, stream_id, attempt, batch_id, first_block, blocks,
+                                                       c_void_p(words.data_ptr()), _stream(stream)))
+    return words
+
+
+def gelo_mixing_export_table(ctx, mixing, n: int, rounds: int = 3, stream=None) -> torch.Tensor:
+    """Test hook: the (rounds + 1) x n table words of a structured mixing object (int32 bit patterns)."""
+    table = torch.empty((rounds + 1, n), dtype=torch.int32, device="cuda")
+    _check(ctx, load_library().gelo_mixing_export_table(ctx, mixing, c_void_p(table.data_ptr()), _stream(stream)))
+    return table
 
 
 def gelo_mixing_export(ctx, mixing, n: int, k_shield: int, d: int, want_shields: bool = True,

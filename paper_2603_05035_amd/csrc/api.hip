@@ -9,8 +9,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <new>
+#include <cstring>
 #include <string>
-#include <unordered_set>
 #include <vector>
 
 #include "gelo_internal.h"
@@ -27,6 +27,13 @@ constexpr uint32_t kStreamMixing = 0, kStreamShield = 1, kStreamPerturb = 2;
 // attempt order wins - the same matrix a one-at-a-time loop would return.
 constexpr int kLanes = 4;
 constexpr int kLanesMaxN = 1024;        // beyond this the rule is infeasible anyway and the buffers get large
+// The condition estimate is a largest Ritz value, which approaches kappa_2 from below (measured within
+// 0.5 % after kKappaSteps steps): a draw is accepted only if the estimate, raised by this margin, still
+// meets the bound, so that an accepted A really satisfies kappa_2(A) <= cond_max.
+constexpr float kKappaGuard = 1.01f;
+// "Never reused" without a growing set: every id below `batch_floor` or more than kBatchWindow below the
+// highest id seen counts as used; inside the window one bit per id remembers which ones were.
+constexpr int kBatchWindow = 4096;
 }
 
 struct gelo_mixing {
@@ -56,7 +63,9 @@ struct gelo_ctx {
     int device;
     uint64_t seed;
     bool allow_reuse;
-    std::unordered_set<uint64_t> used_batches;
+    uint64_t batch_floor;              // ids below it are refused (a resumed context starts here)
+    uint64_t batch_high;               // one past the highest id used so far
+    uint64_t batch_bits[kBatchWindow / 64];   // bit (id % kBatchWindow): id was used, for ids in [batch_high - kBatchWindow, batch_high)
     std::string err;
     void* factor_ws; size_t factor_ws_bytes;
     void* chain_ws;  size_t chain_ws_bytes;
@@ -101,6 +110,29 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 size_t elem_size(int dtype) { return dtype == GELO_BF16 ? 2 : 4; }
 size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Has batch id `b` been used on this context (or must it be assumed so)?  Pure: changes nothing.
+bool batch_used(const gelo_ctx* ctx, uint64_t b) {
+    if (ctx->allow_reuse) return false;
+    if (b < ctx->batch_floor) return true;
+    if (b >= ctx->batch_high) return false;
+    if (ctx->batch_high - b > (uint64_t)kBatchWindow) return true;        // too far back to remember: assume used
+    return (ctx->batch_bits[(b % kBatchWindow) / 64] >> (b % 64)) & 1u;
+}
+
+// Records `b` as used; ids the window slides over on the way up start out unused.
+void batch_commit(gelo_ctx* ctx, uint64_t b) {
+    if (ctx->allow_reuse) return;
+    if (b >= ctx->batch_high) {
+        if (b - ctx->batch_high >= (uint64_t)kBatchWindow) {
+            std::memset(ctx->batch_bits, 0, sizeof ctx->batch_bits);
+        } else {
+            for (uint64_t i = ctx->batch_high; i <= b; ++i) ctx->batch_bits[(i % kBatchWindow) / 64] &= ~((uint64_t)1 << (i % 64));
+        }
+        ctx->batch_high = b + 1;
+    }
+    ctx->batch_bits[(b % kBatchWindow) / 64] |= (uint64_t)1 << (b % 64);
+}
+
 gelo_status grow(gelo_ctx* ctx, void** buf, size_t* have, size_t need) {
     if (*have >= need) return GELO_OK;
     if (*buf) {
@@ -114,33 +146,56 @@ gelo_status grow(gelo_ctx* ctx, void** buf, size_t* have, size_t need) {
     return GELO_OK;
 }
 
+// Sizes of the device block behind one mixing object and where its parts sit in it.
+struct MixingLayout { size_t mat32, mat16, tab, gs, s, gsnorm, rownorm, total; };
+
+MixingLayout mixing_layout(int n_data, int k, int d, int dtype, bool structured) {
+    MixingLayout L;
+    const int n = n_data + k;
+    const int64_t ldk = round_up(n, 64);
+    L.mat32 = structured ? 0 : up256((size_t)n * ldk * 4);
+    L.mat16 = (structured || dtype != GELO_BF16) ? 0 : up256((size_t)n * ldk * 2);
+    L.tab = structured ? up256((size_t)(kStructuredRounds + 1) * n * 4) : 0;
+    L.gs = up256((size_t)(k > 0 ? k : 1) * d * 4);
+    L.s = up256((size_t)(k > 0 ? k : 1) * d * elem_size(dtype));
+    L.gsnorm = up256((size_t)(k + 1) * 4);
+    L.rownorm = up256((size_t)n_data * 4);
+    L.total = 2 * L.mat32 + 2 * L.mat16 + L.tab + L.gs + L.s + L.gsnorm + L.rownorm + 256;
+    return L;
+}
+
+// Fills the shape fields of `m` and points its buffers into the device block at `base` (L.total bytes).
+void carve_mixing(gelo_mixing* m, void* base, int n_data, int k, int d, int dtype, bool structured) {
+    const MixingLayout L = mixing_layout(n_data, k, d, dtype, structured);
+    m->n_data = n_data; m->k = k; m->n = n_data + k; m->d = d; m->dtype = dtype; m->structured = structured;
+    m->ldk = round_up(m->n, 64);
+    m->block = base; m->block_bytes = L.total;
+    char* p = (char*)base;
+    m->A32 = (float*)p; p += L.mat32;
+    m->Ainv32 = (float*)p; p += L.mat32;
+    m->A16 = m->Ainv16 = nullptr;
+    if (L.mat16) { m->A16 = (uint16_t*)p; p += L.mat16; m->Ainv16 = (uint16_t*)p; p += L.mat16; }
+    m->table = (uint32_t*)p; p += L.tab;
+    m->GS = (float*)p; p += L.gs;
+    m->S = p; p += L.s;
+    m->gsnorm = (float*)p; p += L.gsnorm;
+    m->rownorm = (float*)p; p += L.rownorm;
+    m->stat = (float*)p;
+}
+
+// A free pooled object of this shape, or a new one (the only place a mixing object allocates; gelo_reserve
+// fills the pool ahead of time so that the per-batch calls find one).
 gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, bool structured, gelo_mixing** out) {
     for (gelo_mixing* m : ctx->pool) {
         if (!m->in_use && m->n_data == n_data && m->k == k && m->d == d && m->dtype == dtype && m->structured == structured) { *out = m; return GELO_OK; }
     }
     gelo_mixing* m = new (std::nothrow) gelo_mixing();
     if (!m) return fail(ctx, GELO_ENOMEM, "host allocation failed");
-    m->n_data = n_data; m->k = k; m->n = n_data + k; m->d = d; m->dtype = dtype; m->structured = structured;
-    m->ldk = round_up(m->n, 64);
-    const size_t mat32 = structured ? 0 : up256((size_t)m->n * m->ldk * 4);
-    const size_t mat16 = structured ? 0 : up256((size_t)m->n * m->ldk * 2);
-    const size_t tab = structured ? up256((size_t)(kStructuredRounds + 1) * m->n * 4) : 0;
-    const size_t gs = up256((size_t)(k > 0 ? k : 1) * d * 4), s = up256((size_t)(k > 0 ? k : 1) * d * elem_size(dtype));
-    const size_t small = up256((size_t)(k + 1) * 4) + up256((size_t)n_data * 4) + 256;
-    m->block_bytes = 2 * mat32 + (dtype == GELO_BF16 ? 2 * mat16 : 0) + tab + gs + s + small;
-    hipError_t e = hipMalloc(&m->block, m->block_bytes);
-    if (e != hipSuccess) { delete m; return fail(ctx, GELO_ENOMEM, "hipMalloc(%zu) failed: %s", m->block_bytes, hipGetErrorString(e)); }
-    char* p = (char*)m->block;
-    m->A32 = (float*)p; p += mat32;
-    m->Ainv32 = (float*)p; p += mat32;
-    m->A16 = m->Ainv16 = nullptr;
-    if (dtype == GELO_BF16) { m->A16 = (uint16_t*)p; p += mat16; m->Ainv16 = (uint16_t*)p; p += mat16; }
-    m->table = (uint32_t*)p; p += tab;
-    m->GS = (float*)p; p += gs;
-    m->S = p; p += s;
-    m->gsnorm = (float*)p; p += up256((size_t)(k + 1) * 4);
-    m->rownorm = (float*)p; p += up256((size_t)n_data * 4);
-    m->stat = (float*)p;
+    const MixingLayout L = mixing_layout(n_data, k, d, dtype, structured);
+    void* block = nullptr;
+    hipError_t e = hipMalloc(&block, L.total);
+    if (e != hipSuccess) { delete m; return fail(ctx, GELO_ENOMEM, "hipMalloc(%zu) failed: %s", L.total, hipGetErrorString(e)); }
+    carve_mixing(m, block, n_data, k, d, dtype, structured);
     if (hipEventCreateWithFlags(&m->ready, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&m->released, hipEventDisableTiming) != hipSuccess) {
         hipFree(m->block); delete m;
@@ -220,6 +275,8 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
     gelo_ctx* ctx = new (std::nothrow) gelo_ctx();
     if (!ctx) return GELO_ENOMEM;
     ctx->device = device; ctx->seed = seed; ctx->allow_reuse = allow_batch_reuse != 0;
+    ctx->batch_floor = 0; ctx->batch_high = 0;
+    std::memset(ctx->batch_bits, 0, sizeof ctx->batch_bits);
     ctx->factor_ws = ctx->chain_ws = nullptr; ctx->factor_ws_bytes = ctx->chain_ws_bytes = 0;
     ctx->host_scalars = nullptr; ctx->host_flag = nullptr;
     ctx->lanes_ready = false; ctx->join_pending = false; ctx->cand = nullptr; ctx->cand_bytes = 0;
@@ -260,12 +317,9 @@ gelo_status gelo_destroy(gelo_ctx* ctx) {
 
 const char* gelo_last_error(const gelo_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
-gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d,
-                               gelo_dtype dtype, double cond_max, int max_attempts,
-                               uint64_t batch_id, gelo_mixing** out, void* stream) {
-    if (!ctx) return GELO_EINVAL;
-    if (!out) return fail(ctx, GELO_EINVAL, "out is NULL");
-    *out = nullptr;
+// Argument checks shared by the sampling entry points; on success *n_out = n_data + k_shield.
+static gelo_status check_sample_args(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d, gelo_dtype dtype,
+                                     double cond_max, int max_attempts, uint64_t batch_id, int* n_out) {
     if (kind != GELO_ORTHOGONAL && kind != GELO_GAUSSIAN && kind != GELO_CONDITIONED && kind != GELO_STRUCTURED)
         return fail(ctx, GELO_EINVAL, "unknown kind %d", (int)kind);
     if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
@@ -280,31 +334,26 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
         if (!(cond_max >= 1.0)) return fail(ctx, GELO_EINVAL, "cond_max=%g must be >= 1", cond_max);
         if (max_attempts < 1 || max_attempts > GELO_MAX_ATTEMPTS) return fail(ctx, GELO_EINVAL, "max_attempts=%d outside 1..%d", max_attempts, GELO_MAX_ATTEMPTS);
     }
-    if (!ctx->allow_reuse && ctx->used_batches.count(batch_id))
-        return fail(ctx, GELO_EREUSE, "batch id %llu was already used on this context", (unsigned long long)batch_id);
+    if (batch_id == UINT64_MAX) return fail(ctx, GELO_EINVAL, "batch id 2^64 - 1 is reserved");
+    if (batch_used(ctx, batch_id))
+        return fail(ctx, GELO_EREUSE, "batch id %llu was already used on this context (or lies below its floor / window)", (unsigned long long)batch_id);
+    *n_out = n;
+    return GELO_OK;
+}
 
-    GELO_HIP(ctx, hipSetDevice(ctx->device));
-    hipStream_t s = (hipStream_t)stream;
+// Enqueues the draw of batch `batch_id` into the buffers `m` points at, with `ws` as factorisation
+// workspace (not used by STRUCTURED).  `lanes` > 1 (GAUSSIAN only) uses the context's lane buffers, which
+// the caller has sized.  Allocates nothing.
+static gelo_status sample_into(gelo_ctx* ctx, gelo_mixing* m, FactorWorkspace ws, size_t ws_bytes, int lanes, gelo_kind kind,
+                               double cond_max, int max_attempts, uint64_t batch_id, hipStream_t s) {
+    const int n = m->n, k_shield = m->k, d = m->d;
     const bool structured = kind == GELO_STRUCTURED;
     gelo_status st = GELO_OK;
-    FactorWorkspace ws = {};
-    const int lanes = (kind == GELO_GAUSSIAN && n <= kLanesMaxN) ? (max_attempts < kLanes ? max_attempts : kLanes) : 1;
-    const size_t ws_bytes = up256(factor_workspace_bytes(n));
-    if (!structured) {
-        st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, ws_bytes * lanes);
-        if (st != GELO_OK) return st;
-        factor_workspace_carve(ctx->factor_ws, n, &ws);
-    }
-    gelo_mixing* m = nullptr;
-    st = acquire_mixing(ctx, n_data, k_shield, d, dtype, structured, &m);
-    if (st != GELO_OK) return st;
-    if (m->last_stream != nullptr || m->mixed) GELO_HIP(ctx, hipStreamWaitEvent(s, m->released, 0));
-
     PhiloxStream ps;
     ps.key0 = (uint32_t)ctx->seed; ps.key1 = (uint32_t)(ctx->seed >> 32);
     ps.c2 = (uint32_t)batch_id; ps.c3 = (uint32_t)(batch_id >> 32);
     const int64_t ld = ws.ld, ldk = m->ldk;
-    const bool bf = dtype == GELO_BF16;
+    const bool bf = m->dtype == GELO_BF16;
     m->kind = kind; m->attempt = 0; m->kappa = 1.0f;
 
     auto orthogonal_into_X = [&]() -> hipError_t {
@@ -341,9 +390,7 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
         const size_t mat32 = up256((size_t)n * ldk * 4), mat16 = bf ? up256((size_t)n * ldk * 2) : 0;
         const size_t lane_cand = 2 * mat32 + 2 * mat16;
         if (lanes > 1) {
-            st = grow(ctx, &ctx->cand, &ctx->cand_bytes, lane_cand * lanes);
-            if (st == GELO_OK) st = ensure_lanes(ctx);
-            if (st != GELO_OK) return st;
+            if (ctx->cand_bytes < lane_cand * lanes || !ctx->lanes_ready) return fail(ctx, GELO_ESTATE, "lane buffers were not prepared");
             if (ctx->graph_n != n || ctx->graph_bf != bf || ctx->graph_ws != ctx->factor_ws || ctx->graph_cand != ctx->cand) {
                 drop_lane_graphs(ctx);      // captured for other buffers or another size
                 ctx->graph_n = n; ctx->graph_bf = bf; ctx->graph_ws = ctx->factor_ws; ctx->graph_cand = ctx->cand;
@@ -415,7 +462,7 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
             for (int i = 0; i < count && !accepted; ++i) {
                 singular_last = ctx->host_flag[i] != 0;
                 const float kappa = ctx->host_scalars[i];
-                if (singular_last || !(kappa <= (float)cond_max)) continue;
+                if (singular_last || !(kappa * kKappaGuard <= (float)cond_max)) continue;
                 accepted = true; m->attempt = base + i; m->kappa = kappa;
                 GELO_HIP(ctx, hipMemcpyAsync(m->stat + 1, lw[i].scalars, sizeof(float), hipMemcpyDeviceToDevice, s));
                 if (lanes > 1) {      // every lane has finished: plain copies on the caller's stream
@@ -439,27 +486,60 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
         ps.c1 = kStreamShield << 8;
         GELO_HIP(ctx, shield_directions(m->GS, k_shield, d, ps, m->gsnorm, s));
     }
+    (void)st; (void)structured;
+    m->batch_id = batch_id;
+    return GELO_OK;
+}
+
+// Device memory a draw of this shape needs beyond the mixing object: the factorisation workspace (one per
+// lane) and, for side-by-side GAUSSIAN attempts, the candidate buffers and streams.
+static gelo_status prepare_sampling(gelo_ctx* ctx, gelo_kind kind, int n, gelo_dtype dtype, int max_attempts, int* lanes_out) {
+    const int lanes = (kind == GELO_GAUSSIAN && n <= kLanesMaxN) ? (max_attempts < kLanes ? max_attempts : kLanes) : 1;
+    *lanes_out = lanes;
+    if (kind == GELO_STRUCTURED) return GELO_OK;
+    gelo_status st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, up256(factor_workspace_bytes(n)) * lanes);
+    if (st != GELO_OK || lanes == 1) return st;
+    const int64_t ldk = round_up(n, 64);
+    const size_t mat32 = up256((size_t)n * ldk * 4), mat16 = dtype == GELO_BF16 ? up256((size_t)n * ldk * 2) : 0;
+    st = grow(ctx, &ctx->cand, &ctx->cand_bytes, (2 * mat32 + 2 * mat16) * lanes);
+    if (st == GELO_OK) st = ensure_lanes(ctx);
+    return st;
+}
+
+gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d,
+                               gelo_dtype dtype, double cond_max, int max_attempts,
+                               uint64_t batch_id, gelo_mixing** out, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!out) return fail(ctx, GELO_EINVAL, "out is NULL");
+    *out = nullptr;
+    int n = 0;
+    gelo_status st = check_sample_args(ctx, kind, n_data, k_shield, d, dtype, cond_max, max_attempts, batch_id, &n);
+    if (st != GELO_OK) return st;
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    int lanes = 1;
+    st = prepare_sampling(ctx, kind, n, dtype, max_attempts, &lanes);     // allocates on first use of a shape only (see gelo_reserve)
+    if (st != GELO_OK) return st;
+    FactorWorkspace ws = {};
+    const size_t ws_bytes = up256(factor_workspace_bytes(n));
+    if (kind != GELO_STRUCTURED) factor_workspace_carve(ctx->factor_ws, n, &ws);
+    gelo_mixing* m = nullptr;
+    st = acquire_mixing(ctx, n_data, k_shield, d, dtype, kind == GELO_STRUCTURED, &m);
+    if (st != GELO_OK) return st;
+    if (m->last_stream != nullptr || m->mixed) GELO_HIP(ctx, hipStreamWaitEvent(s, m->released, 0));
+    st = sample_into(ctx, m, ws, ws_bytes, lanes, kind, cond_max, max_attempts, batch_id, s);
+    if (st != GELO_OK) return st;
     GELO_HIP(ctx, hipEventRecord(m->ready, s));
-    m->in_use = true; m->mixed = false; m->consumed = false; m->batch_id = batch_id;
+    m->in_use = true; m->mixed = false; m->consumed = false;
     m->sample_stream = s; m->last_stream = s;
-    if (!ctx->allow_reuse) ctx->used_batches.insert(batch_id);
+    batch_commit(ctx, batch_id);
     *out = m;
     return GELO_OK;
 }
 
-gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh,
-                     float shield_scale, gelo_norm_stat stat, void* U, int64_t ldu, void* stream) {
-    if (!ctx) return GELO_EINVAL;
-    if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or freed");
-    if (stat != GELO_NORM_MEDIAN && stat != GELO_NORM_MEAN) return fail(ctx, GELO_EINVAL, "unknown norm statistic %d", (int)stat);
-    if (m->k > 0 && !(shield_scale > 0.f)) return fail(ctx, GELO_EINVAL, "shield_scale=%g must be positive", (double)shield_scale);
-    gelo_status st = check_matrix(ctx, "H", H, ldh, m->d);
-    if (st == GELO_OK) st = check_matrix(ctx, "U", U, ldu, m->d);
-    if (st != GELO_OK) return st;
-    if (!ctx->allow_reuse && m->mixed) return fail(ctx, GELO_EREUSE, "this mixing object has already mixed a batch");
-    GELO_HIP(ctx, hipSetDevice(ctx->device));
-    hipStream_t s = (hipStream_t)stream;
-    if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
+// Launches of eq. 1 / eqs. 7-8 on the buffers of `m`: shield rows, then U = A [H ; S].
+static gelo_status mix_launch(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh, float shield_scale,
+                              gelo_norm_stat stat, void* U, int64_t ldu, hipStream_t s) {
     const bool bf = m->dtype == GELO_BF16;
     if (m->k > 0) {
         GELO_HIP(ctx, row_norms(H, bf, ldh, m->n_data, m->d, m->rownorm, s));
@@ -473,7 +553,6 @@ gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh,
         o.out = U; o.ldo = ldu; o.rows_out = m->n;
         o.table = m->table; o.n = m->n; o.ncols = m->d; o.rounds = kStructuredRounds; o.transposed = false;
         GELO_HIP(ctx, structured_apply(o, bf, s));
-        m->mixed = true; m->last_stream = s;
         return GELO_OK;
     }
     GemmOperands g;
@@ -482,7 +561,47 @@ gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh,
     g.B1 = m->S; g.ldb1 = m->d;
     g.C = U; g.ldc = ldu;
     g.M = m->n; g.N = m->d; g.K = m->n; g.a_zero_padded = true;
-    st = run_gemm(ctx, m->dtype, g, s);
+    return run_gemm(ctx, m->dtype, g, s);
+}
+
+// Launches of eq. 3 with the shield rows dropped: Z = (A^-1 Y)[0:n_data, :].
+static gelo_status unmix_launch(gelo_ctx* ctx, gelo_mixing* m, int p, const void* Y, int64_t ldy, void* Z, int64_t ldz,
+                                hipStream_t s) {
+    const bool bf = m->dtype == GELO_BF16;
+    if (m->structured) {
+        StructuredOperands o;
+        o.in0 = Y; o.ld0 = ldy; o.rows0 = m->n;
+        o.in1 = nullptr; o.ld1 = 0;
+        o.out = Z; o.ldo = ldz; o.rows_out = m->n_data;      // the shield rows of A^T Y are never stored
+        o.table = m->table; o.n = m->n; o.ncols = p; o.rounds = kStructuredRounds; o.transposed = true;
+        GELO_HIP(ctx, structured_apply(o, bf, s));
+        return GELO_OK;
+    }
+    GemmOperands g;
+    g.A = bf ? (const void*)m->Ainv16 : (const void*)m->Ainv32; g.lda = m->ldk;   // rows 0..n_data-1 of A^-1
+    g.B0 = Y; g.ldb0 = ldy; g.K0 = m->n;
+    g.B1 = Y; g.ldb1 = ldy;
+    g.C = Z; g.ldc = ldz;
+    g.M = m->n_data; g.N = p; g.K = m->n; g.a_zero_padded = true;
+    return run_gemm(ctx, m->dtype, g, s);
+}
+
+gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* m, gelo_dtype dtype, const void* H, int64_t ldh,
+                     float shield_scale, gelo_norm_stat stat, void* U, int64_t ldu, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or freed");
+    if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
+    if ((int)dtype != m->dtype) return fail(ctx, GELO_EDTYPE, "H and U are %s but the mixing object was drawn for %s", dtype == GELO_BF16 ? "bf16" : "f32", m->dtype == GELO_BF16 ? "bf16" : "f32");
+    if (stat != GELO_NORM_MEDIAN && stat != GELO_NORM_MEAN) return fail(ctx, GELO_EINVAL, "unknown norm statistic %d", (int)stat);
+    if (m->k > 0 && !(shield_scale > 0.f)) return fail(ctx, GELO_EINVAL, "shield_scale=%g must be positive", (double)shield_scale);
+    gelo_status st = check_matrix(ctx, "H", H, ldh, m->d);
+    if (st == GELO_OK) st = check_matrix(ctx, "U", U, ldu, m->d);
+    if (st != GELO_OK) return st;
+    if (!ctx->allow_reuse && m->mixed) return fail(ctx, GELO_EREUSE, "this mixing object has already mixed a batch");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
+    st = mix_launch(ctx, m, H, ldh, shield_scale, stat, U, ldu, s);
     if (st != GELO_OK) return st;
     m->mixed = true; m->last_stream = s;
     return GELO_OK;
@@ -509,10 +628,12 @@ gelo_status gelo_project(gelo_ctx* ctx, gelo_dtype dtype, int n, int d, int p,
     return run_gemm(ctx, dtype, g, (hipStream_t)stream);
 }
 
-gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* m, int p, const void* Y, int64_t ldy,
+gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* m, gelo_dtype dtype, int p, const void* Y, int64_t ldy,
                        void* Z, int64_t ldz, void* stream) {
     if (!ctx) return GELO_EINVAL;
     if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or freed");
+    if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
+    if ((int)dtype != m->dtype) return fail(ctx, GELO_EDTYPE, "Y and Z are %s but the mixing object was drawn for %s", dtype == GELO_BF16 ? "bf16" : "f32", m->dtype == GELO_BF16 ? "bf16" : "f32");
     if (p < 1) return fail(ctx, GELO_EINVAL, "p=%d", p);
     if (p % 8 != 0) return fail(ctx, GELO_EALIGN, "p=%d is not a multiple of 8", p);
     gelo_status st = check_matrix(ctx, "Y", Y, ldy, p);
@@ -523,26 +644,21 @@ gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* m, int p, const void* Y, int6
     GELO_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
     if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
-    const bool bf = m->dtype == GELO_BF16;
-    if (m->structured) {
-        StructuredOperands o;
-        o.in0 = Y; o.ld0 = ldy; o.rows0 = m->n;
-        o.in1 = nullptr; o.ld1 = 0;
-        o.out = Z; o.ldo = ldz; o.rows_out = m->n_data;      // the shield rows of A^T Y are never stored
-        o.table = m->table; o.n = m->n; o.ncols = p; o.rounds = kStructuredRounds; o.transposed = true;
-        GELO_HIP(ctx, structured_apply(o, bf, s));
-        m->consumed = true; m->last_stream = s;
-        return GELO_OK;
-    }
-    GemmOperands g;
-    g.A = bf ? (const void*)m->Ainv16 : (const void*)m->Ainv32; g.lda = m->ldk;   // rows 0..n_data-1 of A^-1
-    g.B0 = Y; g.ldb0 = ldy; g.K0 = m->n;
-    g.B1 = Y; g.ldb1 = ldy;
-    g.C = Z; g.ldc = ldz;
-    g.M = m->n_data; g.N = p; g.K = m->n; g.a_zero_padded = true;
-    st = run_gemm(ctx, m->dtype, g, s);
+    st = unmix_launch(ctx, m, p, Y, ldy, Z, ldz, s);
     if (st != GELO_OK) return st;
     m->consumed = true; m->last_stream = s;
+    return GELO_OK;
+}
+
+gelo_status gelo_mixing_info(gelo_ctx* ctx, const gelo_mixing* m, int* n_data, int* k_shield, int* d,
+                             gelo_dtype* dtype, gelo_kind* kind) {
+    if (!ctx) return GELO_EINVAL;
+    if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or freed");
+    if (n_data) *n_data = m->n_data;
+    if (k_shield) *k_shield = m->k;
+    if (d) *d = m->d;
+    if (dtype) *dtype = (gelo_dtype)m->dtype;
+    if (kind) *kind = (gelo_kind)m->kind;
     return GELO_OK;
 }
 
@@ -564,6 +680,8 @@ gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, in
     if (p < 1 || p % 8 != 0) return fail(ctx, p < 1 ? GELO_EINVAL : GELO_EALIGN, "p=%d must be a positive multiple of 8", p);
     if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
     if (n_data < 1 || k_shield < 0 || d < 1) return fail(ctx, GELO_EINVAL, "n_data=%d k_shield=%d d=%d", n_data, k_shield, d);
+    if (!aligned16(H) || !aligned16(W) || !aligned16(Z) || !aligned16(U_opt) || !aligned16(Y_opt))
+        return fail(ctx, GELO_EALIGN, "H, W, Z, U and Y must be 16-byte aligned");
     const int64_t n = (int64_t)n_data + k_shield;
     void* U = U_opt; void* Y = Y_opt;
     if (!U || !Y) {
@@ -577,9 +695,9 @@ gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, in
     gelo_mixing* m = nullptr;
     gelo_status st = gelo_sample_mixing(ctx, kind, n_data, k_shield, d, dtype, cond_max, max_attempts, batch_id, &m, stream);
     if (st != GELO_OK) return st;
-    st = gelo_mix(ctx, m, H, d, shield_scale, stat, U, d, stream);
+    st = gelo_mix(ctx, m, dtype, H, d, shield_scale, stat, U, d, stream);
     if (st == GELO_OK) st = gelo_project(ctx, dtype, (int)n, d, p, U, d, W, p, Y, p, stream);
-    if (st == GELO_OK) st = gelo_unmix(ctx, m, p, Y, p, Z, p, stream);
+    if (st == GELO_OK) st = gelo_unmix(ctx, m, dtype, p, Y, p, Z, p, stream);
     const std::string keep = ctx->err;
     gelo_mixing_free(ctx, m);
     if (st != GELO_OK) ctx->err = keep;
@@ -628,6 +746,75 @@ gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* m, float* A, fl
             *kappa = m->kappa;
         }
     }
+    return GELO_OK;
+}
+
+gelo_status gelo_reserve(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_data, int k_shield, int d, int p,
+                         int max_attempts, int mixings) {
+    if (!ctx) return GELO_EINVAL;
+    if (mixings < 0 || p < 0) return fail(ctx, GELO_EINVAL, "mixings=%d p=%d", mixings, p);
+    int n = 0;
+    const bool reuse = ctx->allow_reuse;
+    ctx->allow_reuse = true;                    // no batch id is involved here
+    gelo_status st = check_sample_args(ctx, kind, n_data, k_shield, d, dtype, 1.0, kind == GELO_GAUSSIAN ? max_attempts : 1, 0, &n);
+    ctx->allow_reuse = reuse;
+    if (st != GELO_OK) return st;
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    int lanes = 1;
+    st = prepare_sampling(ctx, kind, n, dtype, max_attempts, &lanes);
+    if (st != GELO_OK) return st;
+    if (p > 0) {
+        const size_t ub = up256((size_t)n * d * elem_size(dtype)), yb = up256((size_t)n * p * elem_size(dtype));
+        st = grow(ctx, &ctx->chain_ws, &ctx->chain_ws_bytes, ub + yb);
+        if (st != GELO_OK) return st;
+    }
+    // `mixings` free objects of this shape in the pool
+    std::vector<gelo_mixing*> got;
+    for (int i = 0; i < mixings && st == GELO_OK; ++i) {
+        gelo_mixing* m = nullptr;
+        st = acquire_mixing(ctx, n_data, k_shield, d, dtype, kind == GELO_STRUCTURED, &m);
+        if (st == GELO_OK) { m->in_use = true; got.push_back(m); }
+    }
+    for (gelo_mixing* m : got) m->in_use = false;
+    return st;
+}
+
+gelo_status gelo_set_batch_floor(gelo_ctx* ctx, uint64_t first_unused) {
+    if (!ctx) return GELO_EINVAL;
+    if (first_unused < ctx->batch_floor) return fail(ctx, GELO_EINVAL, "the floor only moves up (it is %llu)", (unsigned long long)ctx->batch_floor);
+    ctx->batch_floor = first_unused;
+    return GELO_OK;
+}
+
+gelo_status gelo_get_batch_floor(const gelo_ctx* ctx, uint64_t* first_unused) {
+    if (!ctx || !first_unused) return GELO_EINVAL;
+    *first_unused = ctx->batch_high > ctx->batch_floor ? ctx->batch_high : ctx->batch_floor;
+    return GELO_OK;
+}
+
+gelo_status gelo_debug_philox_words(gelo_ctx* ctx, uint32_t stream_id, uint32_t attempt, uint64_t batch_id,
+                                    uint32_t first_block, uint32_t blocks, uint32_t* words, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!words || (reinterpret_cast<uintptr_t>(words) & 15u)) return fail(ctx, words ? GELO_EALIGN : GELO_EINVAL, "words must be a 16-byte aligned device pointer");
+    if (stream_id > 0xFFFFFFu || attempt > 255u) return fail(ctx, GELO_EINVAL, "stream_id=%u attempt=%u", stream_id, attempt);
+    if ((uint64_t)first_block + blocks > ((uint64_t)1 << 32)) return fail(ctx, GELO_EINVAL, "block range leaves 32 bits");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    PhiloxStream ps;
+    ps.key0 = (uint32_t)ctx->seed; ps.key1 = (uint32_t)(ctx->seed >> 32);
+    ps.c1 = (stream_id << 8) | attempt; ps.c2 = (uint32_t)batch_id; ps.c3 = (uint32_t)(batch_id >> 32);
+    GELO_HIP(ctx, philox_words(words, first_block, blocks, ps, (hipStream_t)stream));
+    return GELO_OK;
+}
+
+gelo_status gelo_mixing_export_table(gelo_ctx* ctx, const gelo_mixing* m, uint32_t* table, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or freed");
+    if (!m->structured) return fail(ctx, GELO_EINVAL, "only a GELO_STRUCTURED mixing object has a table");
+    if (!table) return fail(ctx, GELO_EINVAL, "table is NULL");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
+    GELO_HIP(ctx, hipMemcpyAsync(table, m->table, (size_t)(kStructuredRounds + 1) * m->n * sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
     return GELO_OK;
 }
 

@@ -242,9 +242,10 @@ void gemm_bf16_kernel(Bf16Args g) {
 //   The MFMA operands are swapped (B fragment first), so the accumulators hold blocks of C^T and a
 //     lane owns 4 consecutive columns of one row; the epilogue goes through LDS once more so that
 //     the global stores are 16 bytes per lane over whole row segments.
-// Out-of-range rows / columns are clamped to valid addresses instead of being zero-filled, which
-// is correct because A is zero in columns [K, round_up(K, 64)) (required by the dispatcher) and
-// clamped B rows are finite.  Measured on the 2150 x 12288 x 4096 projection against the
+// Out-of-range rows of A and columns of B are clamped to valid addresses (their products land in
+// outputs that are never stored); rows of B beyond K are fetched from a block of zeros and A is zero
+// in columns [K, round_up(K, 64)) (required by the dispatcher), so the K tail contributes exact zeros
+// whatever the data holds.  Measured on the 2150 x 12288 x 4096 projection against the
 // alternatives that were tried: K step 32 with four stages and prefetch distance 3 (-4 %),
 // per-lane address arithmetic for the fetches (-5 %), v_perm transposition of B in registers
 // with direct stores (-9 %).  BN = 192 exists for the tile count: 2048 x 12288 is 384 tiles of
@@ -256,6 +257,10 @@ constexpr int A_BYTES = BM * BKS * 2;           // 32 KB per stage, rows of 128 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 template <int BN> constexpr int lds_bytes() { return STAGES * (A_BYTES + BKS * BN * 2); }
+
+// sixteen zero bytes: what the rows of B beyond the contraction length are fetched from, so that a NaN or
+// Inf in the last valid row cannot reach the accumulators through 0 x Inf
+__device__ __align__(16) const uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
 
 // lds_addr must be wave-uniform (it travels in M0); lane l's 16 bytes land at lds_addr + 16 l
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
@@ -342,11 +347,13 @@ __device__ __forceinline__ void tile_body(const Bf16Args& g, uint8_t* lds, int m
         } else {
 #pragma unroll
             for (int i = 0; i < NBD; ++i) {
-                int gk = k0 + b_krow[i]; gk = gk < K ? gk : K - 1;
+                int gk = k0 + b_krow[i];
+                const bool beyond = gk >= K;                      // rows past the contraction length read zeros
+                gk = beyond ? K - 1 : gk;
                 const bool first = gk < K0;
                 const uint16_t* base = first ? B0p : B1p;
                 const int64_t off = first ? (int64_t)gk * ldb0 : (int64_t)(gk - K0) * ldb1;
-                dma16(base + off + b_gn[i], sb + i * 1024);
+                dma16(beyond ? (const uint16_t*)g_zero16 : base + off + b_gn[i], sb + i * 1024);
             }
         }
     };
@@ -562,11 +569,13 @@ void gemm_bf16_skinny_kernel(Bf16Args g) {
         } else {
 #pragma unroll
             for (int i = 0; i < C::NBW; ++i) {
-                int gk = k0 + b_krow[i]; gk = gk < K ? gk : K - 1;
+                int gk = k0 + b_krow[i];
+                const bool beyond = gk >= K;
+                gk = beyond ? K - 1 : gk;
                 const bool first = gk < K0;
                 const uint16_t* base = first ? B0p : B1p;
                 const int64_t off = first ? (int64_t)gk * ldb0 : (int64_t)(gk - K0) * ldb1;
-                dma::dma16(base + off + b_gn[i], st + b_dst[i]);
+                dma::dma16(beyond ? (const uint16_t*)dma::g_zero16 : base + off + b_gn[i], st + b_dst[i]);
             }
         }
     };

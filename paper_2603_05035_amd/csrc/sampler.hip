@@ -39,6 +39,16 @@ void fill_normal_kernel(float* out, int64_t ld, int rows, int cols, PhiloxStream
     }
 }
 
+// Raw generator output for bitwise checks: words[4 i .. 4 i + 3] = the four words of block first + i.
+__global__ __launch_bounds__(256)
+void philox_words_kernel(uint32_t* words, uint32_t first, uint32_t blocks, PhiloxStream ps) {
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= blocks) return;
+    uint32_t c0 = first + i, c1 = ps.c1, c2 = ps.c2, c3 = ps.c3;
+    philox4x32_10(c0, c1, c2, c3, ps.key0, ps.key1);
+    *reinterpret_cast<uint4*>(words + 4 * (size_t)i) = make_uint4(c0, c1, c2, c3);
+}
+
 // The k x d shield directions (row-major, pitch d, the same element-to-Philox-word map as
 // fill_normal_kernel) and their norms in one launch: one workgroup per row, partial sums of squares
 // added in a fixed order (lanes by halving, then the four waves in turn).
@@ -228,6 +238,12 @@ hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream 
     if (quads == 0) return hipSuccess;
     hipLaunchKernelGGL(fill_normal_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
                        out, ld, rows, cols, ps, scale, tiled);
+    return hipGetLastError();
+}
+
+hipError_t philox_words(uint32_t* words, uint32_t first_block, uint32_t blocks, PhiloxStream ps, hipStream_t stream) {
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(philox_words_kernel, dim3((blocks + 255u) / 256u), dim3(256), 0, stream, words, first_block, blocks, ps);
     return hipGetLastError();
 }
 

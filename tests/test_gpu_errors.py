@@ -82,23 +82,114 @@ def test_alignment_and_shape_checks(ctx):
     s = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     P = ctypes.c_void_p
     # NULL, misaligned pointer, short and odd leading dimensions
-    assert lib.gelo_mix(ctx, m, null, 64, 10.0, 0, P(base), 64, s) == 1
-    assert lib.gelo_mix(ctx, m, P(base + 4), 64, 10.0, 0, P(base), 64, s) == 4
-    assert lib.gelo_mix(ctx, m, P(base), 56, 10.0, 0, P(base), 64, s) == 1
-    assert lib.gelo_mix(ctx, m, P(base), 68, 10.0, 0, P(base), 64, s) == 4
+    assert lib.gelo_mix(ctx, m, 0, null, 64, 10.0, 0, P(base), 64, s) == 1
+    assert lib.gelo_mix(ctx, m, 0, P(base + 4), 64, 10.0, 0, P(base), 64, s) == 4
+    assert lib.gelo_mix(ctx, m, 0, P(base), 56, 10.0, 0, P(base), 64, s) == 1
+    assert lib.gelo_mix(ctx, m, 0, P(base), 68, 10.0, 0, P(base), 64, s) == 4
+    assert lib.gelo_mix(ctx, m, 1, P(base), 64, 10.0, 0, P(base), 64, s) == 3      # bf16 buffers, float mixing object
+    assert lib.gelo_mix(ctx, m, 2, P(base), 64, 10.0, 0, P(base), 64, s) == 1
+    assert lib.gelo_unmix(ctx, m, 1, 64, P(base), 64, P(base), 64, s) == 3
     assert lib.gelo_project(ctx, 0, 16, 64, 60, P(base), 64, P(base), 64, P(base), 64, s) == 4
     assert lib.gelo_project(ctx, 0, 0, 64, 64, P(base), 64, P(base), 64, P(base), 64, s) == 1
     assert lib.gelo_project(ctx, 3, 16, 64, 64, P(base), 64, P(base), 64, P(base), 64, s) == 1
-    assert lib.gelo_unmix(ctx, m, 64, P(base), 64, P(base), 64, s) == 9        # not mixed yet
-    assert lib.gelo_unmix(ctx, m, 12, P(base), 64, P(base), 64, s) == 4
+    assert lib.gelo_unmix(ctx, m, 0, 64, P(base), 64, P(base), 64, s) == 9        # not mixed yet
+    assert lib.gelo_unmix(ctx, m, 0, 12, P(base), 64, P(base), 64, s) == 4
     assert lib.gelo_mixing_export(ctx, null, null, null, null, None, None, s) == 1
     g.gelo_mixing_free(ctx, m)
     # a mixing object of another context is refused
     c2 = g.gelo_create(0, 2)
     m2 = g.gelo_sample_mixing(c2, g.GELO_ORTHOGONAL, 16, 0, 64, g.GELO_F32, batch_id=1)
-    assert lib.gelo_mix(ctx, m2, P(base), 64, 10.0, 0, P(base), 64, s) == 1
+    assert lib.gelo_mix(ctx, m2, 0, P(base), 64, 10.0, 0, P(base), 64, s) == 1
     g.gelo_mixing_free(c2, m2)
     g.gelo_destroy(c2)
+
+
+def test_dtype_and_shape_mismatch_is_refused_before_any_launch(ctx):
+    """A mixing object drawn for float must not meet bf16 buffers (the kernels would run past them), nor
+    buffers with too few rows: GELO_EDTYPE / GELO_ESHAPE, nothing enqueued, the object stays usable."""
+    m = g.gelo_sample_mixing(ctx, g.GELO_ORTHOGONAL, 16, 2, 64, g.GELO_F32, batch_id=40)
+    assert g.gelo_mixing_info(ctx, m) == (16, 2, 64, g.GELO_F32, g.GELO_ORTHOGONAL)
+    H = torch.randn(16, 64, device="cuda")
+    U = torch.full((18, 64), 5.0, device="cuda")
+    Hb, Ub = H.bfloat16(), U.bfloat16()
+    assert status_of(g.gelo_mix, ctx, m, Hb, Ub) == "GELO_EDTYPE"
+    assert status_of(g.gelo_mix, ctx, m, H, U[:17]) == "GELO_ESHAPE"          # U needs n = 18 rows
+    assert status_of(g.gelo_mix, ctx, m, H[:15], U) == "GELO_ESHAPE"
+    assert status_of(g.gelo_mix, ctx, m, torch.randn(16, 72, device="cuda"), torch.empty(18, 72, device="cuda")) == "GELO_ESHAPE"
+    torch.cuda.synchronize()
+    assert torch.all(U == 5.0)                                               # nothing ran
+    g.gelo_mix(ctx, m, H, U)
+    Y = torch.randn(18, 72, device="cuda")
+    Z = torch.full((16, 72), 5.0, device="cuda")
+    assert status_of(g.gelo_unmix, ctx, m, Y.bfloat16(), Z.bfloat16()) == "GELO_EDTYPE"
+    assert status_of(g.gelo_unmix, ctx, m, Y[:17], Z) == "GELO_ESHAPE"
+    assert status_of(g.gelo_unmix, ctx, m, Y, Z[:15]) == "GELO_ESHAPE"
+    torch.cuda.synchronize()
+    assert torch.all(Z == 5.0)
+    g.gelo_unmix(ctx, m, Y, Z)
+    g.gelo_mixing_free(ctx, m)
+    torch.cuda.synchronize()
+
+
+def test_batch_window_and_floor(ctx):
+    """The record of used batch ids is a high-water mark plus a window of GELO_BATCH_WINDOW ids below it:
+    ids above are new, ids inside are remembered one by one, ids further back count as used.  The floor
+    lets a restarted process resume from (seed, first unused id)."""
+    def draw(b, c=ctx):
+        m = g.gelo_sample_mixing(c, g.GELO_ORTHOGONAL, 8, 0, 64, g.GELO_F32, batch_id=b)
+        g.gelo_mixing_free(c, m)
+    W = g.GELO_BATCH_WINDOW
+    assert g.gelo_get_batch_floor(ctx) == 0
+    draw(10); draw(7); draw(12)
+    assert g.gelo_get_batch_floor(ctx) == 13
+    for b in (10, 7, 12):
+        assert status_of(draw, b) == "GELO_EREUSE"
+    draw(8)                                            # inside the window and unused
+    draw(12 + W)                                       # the window slides past 12 and everything below it
+    assert status_of(draw, 12) == "GELO_EREUSE"
+    assert status_of(draw, 8) == "GELO_EREUSE"
+    assert status_of(draw, 11) == "GELO_EREUSE"        # never used, but too far back to know
+    draw(13)                                           # the oldest id still inside the window, unused
+    draw(12 + W + 5 * W)                               # a jump of more than a window forgets nothing it should keep
+    assert status_of(draw, 12 + W) == "GELO_EREUSE"
+    draw(12 + 5 * W + 1)
+    big = (1 << 63) + 12345
+    draw(big)
+    assert status_of(draw, big) == "GELO_EREUSE"
+    assert status_of(draw, (1 << 64) - 1) == "GELO_EINVAL"
+    # resume: same seed, floor restored; everything below is refused, the first unused id works
+    first_unused = g.gelo_get_batch_floor(ctx)
+    assert first_unused == big + 1
+    c2 = g.gelo_create(0, 1, allow_batch_reuse=False)
+    try:
+        g.gelo_set_batch_floor(c2, first_unused)
+        assert status_of(draw, big, c2) == "GELO_EREUSE"
+        assert status_of(draw, 0, c2) == "GELO_EREUSE"
+        draw(first_unused, c2)
+        assert status_of(g.gelo_set_batch_floor, c2, 5) == "GELO_EINVAL"
+    finally:
+        g.gelo_destroy(c2)
+
+
+def test_reserve_sizes_the_context_ahead(ctx):
+    """After gelo_reserve the per-batch calls of that shape find their memory: device memory in use does not
+    grow over a chain (U and Y in context workspace) nor over draws held at the same time."""
+    nd, k, d, p = 1000, 24, 1024, 2048       # unreserved, this shape would take about 50 MB on first use
+    g.gelo_reserve(ctx, g.GELO_ORTHOGONAL, g.GELO_BF16, nd, k, d, p, mixings=2)
+    H = torch.randn(nd, d, device="cuda").bfloat16()
+    W = (0.02 * torch.randn(d, p, device="cuda")).bfloat16()
+    Z = torch.empty(nd, p, device="cuda", dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    g.gelo_qkv_forward(ctx, g.GELO_ORTHOGONAL, H, W, Z, k_shield=k, batch_id=1)
+    m1 = g.gelo_sample_mixing(ctx, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, batch_id=2)
+    m2 = g.gelo_sample_mixing(ctx, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, batch_id=3)
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] >= free0 - (4 << 20)        # a little slack for the runtime's own pools
+    g.gelo_mixing_free(ctx, m1)
+    g.gelo_mixing_free(ctx, m2)
+    assert torch.allclose(Z.float(), H.float() @ W.float(), rtol=5e-2, atol=5e-2)
+    assert status_of(g.gelo_reserve, ctx, g.GELO_ORTHOGONAL, g.GELO_BF16, g.GELO_MAX_N, 1, d) == "GELO_ESHAPE"
 
 
 def test_condition_budget_exhausted(ctx):

@@ -29,8 +29,10 @@ def f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float64).cpu().numpy()
 
 
-@pytest.fixture(scope="module")
+@pytest.fixture()
 def ctx():
+    """a context per test: batch ids need not rise from one test to the next (a context refuses ids that
+    fall more than GELO_BATCH_WINDOW below the highest one it has seen)"""
     c = g.gelo_create(0, 0xC0FFEE, allow_batch_reuse=False)
     yield c
     g.gelo_destroy(c)
@@ -98,6 +100,65 @@ def test_gaussian_source_matches_oracle(ctx, n):
     G = o.gaussian_matrix(0xC0FFEE, 1000 + n, o.STREAM_MIXING, 0, n, n) / math.sqrt(n)
     assert np.abs(f64(A) - G).max() < 4e-6 / math.sqrt(n) * 6 + 1e-7
     assert o.rel_frobenius(f64(A), G) < 2e-7
+
+
+def u32(t: torch.Tensor) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("stream_id,attempt,batch_id,first,blocks", [
+    (0, 0, 0, 0, 1 << 18),                        # 2^20 words of the mixing stream from the start of a batch
+    (0, 3, (7 << 32) | 0xFFFFFFFF, 0xFFFFF000, 4096),   # a redraw, a 64-bit batch id, the top of the block range
+    (1, 0, 123456789, 1000, 5000),                # shield directions
+    (2, 0, 9, 0, 300), (3, 2, 9, 0, 300), (4, 1, 9, 17, 300),
+])
+def test_philox_words_are_bit_exact(ctx, stream_id, attempt, batch_id, first, blocks):
+    """Integer work is held bit for bit: the raw words of the library's generator against the oracle's
+    Philox4x32-10 for the same key and counters."""
+    words = u32(g.gelo_debug_philox_words(ctx, stream_id, attempt, batch_id, first, blocks))
+    idx = np.arange(blocks, dtype=np.uint64) + np.uint64(first)
+    assert int(idx[-1]) < 1 << 32
+    ref = np.stack(o.philox4x32_10((idx, (stream_id << 8) | attempt, batch_id & 0xFFFFFFFF, batch_id >> 32),
+                                   (0xC0FFEE & 0xFFFFFFFF, 0xC0FFEE >> 32)), axis=1)
+    assert words.shape == ref.shape and np.array_equal(words, ref)
+
+
+def test_gaussian_uniforms_use_the_pinned_words(ctx):
+    """The Gaussian source consumes exactly those words: A = G / sqrt(n) recomputed from the exported raw
+    words through the oracle's Box-Muller agrees with the library's float Box-Muller to float rounding
+    (a flipped low bit of a word that reaches the uniform would move it by 2^-23 and pass this bound,
+    which is why the words themselves are compared bitwise above)."""
+    n = 150
+    m = g.gelo_sample_mixing(ctx, g.GELO_GAUSSIAN, n, 0, 64, g.GELO_F32, 1e9, 4, batch_id=77)
+    A, _, _, attempt, _ = g.gelo_mixing_export(ctx, m, n, 0, 64)
+    g.gelo_mixing_free(ctx, m)
+    assert attempt == 0
+    blocks = (n * n + 3) // 4
+    words = u32(g.gelo_debug_philox_words(ctx, 0, 0, 77, 0, blocks))
+    z0, z1 = o.box_muller(words[:, 0], words[:, 1])
+    z2, z3 = o.box_muller(words[:, 2], words[:, 3])
+    G = np.stack([z0, z1, z2, z3], axis=1).reshape(-1)[:n * n].reshape(n, n) / math.sqrt(n)
+    assert o.rel_frobenius(f64(A), G) < 2e-7
+
+
+def test_condition_bound_is_verified_with_a_guard_band(ctx):
+    """Section 3.2.1 asks to generate and verify: the condition estimate approaches kappa_2 from below,
+    so an attempt is accepted only if 1.01 x estimate <= cond_max.  Pinned on one draw whose kappa_2 is
+    known from the float64 SVD: a bound 0.3 % above kappa rejects it, a bound 3 % above accepts it."""
+    n, bid = 96, 4242
+    Gm = o.gaussian_matrix(0xC0FFEE, bid, o.STREAM_MIXING, 0, n, n) / math.sqrt(n)
+    kappa = np.linalg.cond(Gm)
+    c2 = g.gelo_create(0, 0xC0FFEE, allow_batch_reuse=True)
+    try:
+        with pytest.raises(g.GeloError) as e:
+            g.gelo_sample_mixing(c2, g.GELO_GAUSSIAN, n, 0, 64, g.GELO_F32, kappa * 1.003, 1, batch_id=bid)
+        assert g.STATUS_NAMES[e.value.status] == "GELO_ECOND"
+        m = g.gelo_sample_mixing(c2, g.GELO_GAUSSIAN, n, 0, 64, g.GELO_F32, kappa * 1.03, 1, batch_id=bid)
+        _, _, _, attempt, kappa_gpu = g.gelo_mixing_export(c2, m, n, 0, 64)
+        g.gelo_mixing_free(c2, m)
+        assert attempt == 0 and abs(kappa_gpu - kappa) / kappa < 0.005 and kappa_gpu * 1.01 <= kappa * 1.03
+    finally:
+        g.gelo_destroy(c2)
 
 
 @pytest.mark.parametrize("n_data,k", [(16, 2), (1, 0), (1, 1), (15, 0), (16, 0), (17, 3), (130, 20), (300, 0),
@@ -222,20 +283,21 @@ def test_chain_stagewise_and_end_to_end(ctx, kind, dtype, nd, k, d, p):
     H32 = wl.make_hidden(nd, d, seed=nd * 3 + d, outlier_channels=8 if d >= 200 else 0)
     W32 = wl.make_weight(d, p, seed=p + d)
     bid = 4000 + nd * 13 + k + d + (1 << 20) * kind + (1 << 24) * (dtype == "bf16")
-    cond_max = 1e4 if kind == g.GELO_GAUSSIAN else 1e3
-    r = run_chain(ctx, kind, dtype, H32, W32, k, bid, cond_max=cond_max)
+    r = run_chain(ctx, kind, dtype, H32, W32, k, bid, cond_max=1e3)
     n = nd + k
     A = f64(r["A"])
     assert np.linalg.norm(A @ f64(r["A_inv"]) - np.eye(n)) / math.sqrt(n) < (2e-6 if kind == g.GELO_ORTHOGONAL else 2e-6 * max(r["kappa"], 1.0) * 10)
-    if kind == g.GELO_GAUSSIAN and dtype == "bf16":
-        pytest.skip("bf16 with an ill-conditioned A is outside the contract")
     if kind == g.GELO_GAUSSIAN:
-        # stage errors are amplified by kappa(A) in the unmix; hold the end-to-end contract only
+        # kappa_2(A) <= 1e3 as in the float config, and the contract bound as written.  Only the unmix
+        # stage gets a factor: A^-1 Y cancels (the entries of A^-1 are large, the result is not), so the
+        # product's own condition number || |A^-1| |Y| || / || A^-1 Y || is an order of magnitude above
+        # that of the other two products, and float accumulation errs in proportion to it.
         H, W = f64(r["H"]), f64(r["W"])
+        assert r["kappa"] <= 1e3
         assert o.rel_frobenius(f64(r["U"]), o.mix(A, H)) < TOL_STAGE[dtype]
         assert o.rel_frobenius(f64(r["Y"]), o.project(f64(r["U"]), W)) < TOL_STAGE[dtype]
         assert o.rel_frobenius(f64(r["Z"]), o.unmix(f64(r["A_inv"]), f64(r["Y"]), nd)) < TOL_STAGE[dtype] * 10
-        assert o.rel_frobenius(f64(r["Z"]), o.plain_projection(H, W)) < TOL_END[dtype] * max(1.0, r["kappa"] / 100)
+        assert o.rel_frobenius(f64(r["Z"]), o.plain_projection(H, W)) < TOL_END[dtype]
     else:
         stagewise_check(r, dtype, nd, k)
 
@@ -374,22 +436,70 @@ def test_full_size_sweep_layers(ctx, name, layer):
         assert r["kappa"] < 100.0
 
 
-def test_sweep_layers_by_freivalds(ctx):
-    """More layers of the sweep than the full oracle can afford: Z r == H (W r) for a random r."""
-    w = wl.WORKLOADS["sweep_bf16_cond"]
-    rng = np.random.default_rng(5)
-    for layer in (2, 3):
-        name = "sweep_bf16_orth" if layer % 2 == 0 else "sweep_bf16_cond"
-        wk = wl.WORKLOADS[name]
+def freivalds(Z, H, W, rvec):
+    """|| Z r - H (W r) || / || H (W r) || in float64: O(n d + d p) instead of the full product"""
+    lhs = (Z.double() @ rvec).cpu().numpy()
+    rhs = (H.double() @ (W.double() @ rvec)).cpu().numpy()
+    return np.linalg.norm(lhs - rhs) / np.linalg.norm(rhs)
+
+
+def test_prefill_sweep_all_32_layers(ctx):
+    """The 32-layer prefill sweep as the config states it: 4096 rows per layer, fresh inputs, weights and A
+    per layer, even layers ORTHOGONAL with 205 shield rows (n = 4301), odd layers CONDITIONED without
+    shields, batch id = layer.  Every layer by Freivalds' check (Z r against H (W r) in float64 for a random
+    r); layers 0 and 1 also against the full float64 product."""
+    gen = torch.Generator(device="cpu").manual_seed(5)
+    worst = 0.0
+    for layer in range(32):
+        wk = wl.WORKLOADS["sweep_bf16_orth" if layer % 2 == 0 else "sweep_bf16_cond"]
         H32, W32 = wl.make_inputs(wk, layer)
         H, W = dev(H32, "bf16"), dev(W32, "bf16")
         Z = torch.empty((wk.n_data, wk.p), dtype=torch.bfloat16, device="cuda")
-        g.gelo_qkv_forward(ctx, wk.kind, H, W, Z, k_shield=wk.k_shield, batch_id=9500 + layer)
+        g.gelo_qkv_forward(ctx, wk.kind, H, W, Z, k_shield=wk.k_shield, batch_id=layer)
         torch.cuda.synchronize()
-        rvec = rng.standard_normal(wk.p)
-        lhs = f64(Z) @ rvec
-        rhs = f64(H) @ (f64(W) @ rvec)
-        assert np.linalg.norm(lhs - rhs) / np.linalg.norm(rhs) < TOL_END["bf16"]
+        rvec = torch.randn(wk.p, generator=gen, dtype=torch.float64).cuda()
+        err = freivalds(Z, H, W, rvec)
+        worst = max(worst, err)
+        assert err < TOL_END["bf16"], (layer, err)
+        if layer < 2:
+            assert o.rel_frobenius(f64(Z), o.plain_projection(f64(H), f64(W))) < TOL_END["bf16"]
+        print(f"sweep layer {layer:2d} ({'orthogonal + 205 shields' if layer % 2 == 0 else 'conditioned'}): Freivalds error {err:.2e}", flush=True)
+    print("worst layer", worst)
+
+
+def test_decode_sweep_one_full_step(ctx):
+    """One step of the decode-shaped config: 32 layers, 64 tokens + 4 shield rows each, a fresh orthogonal
+    68 x 68 A per layer-step with batch id = step * 32 + layer, 32 resident weights.  Every layer-step by
+    Freivalds' check; layers 0 and 31 against the full float64 product, and their A against the oracle's
+    Householder QR of the oracle's own Gaussian for that batch id."""
+    wk = wl.WORKLOADS["decode_bf16"]
+    step = 5
+    gen = torch.Generator(device="cpu").manual_seed(6)
+    weights = [dev(wl.make_weight(wk.d, wk.p, wk.seed * 1000 + layer), "bf16") for layer in range(32)]
+    for layer in range(32):
+        bid = step * 32 + layer
+        H = dev(wl.make_hidden(wk.n_data, wk.d, wk.seed * 1000 + 64 * step + layer, wk.outlier_channels), "bf16")
+        W = weights[layer]
+        if layer in (0, 31):
+            m = g.gelo_sample_mixing(ctx, wk.kind, wk.n_data, wk.k_shield, wk.d, g.GELO_BF16, 0.0, 1, batch_id=bid)
+            U = torch.empty((wk.n, wk.d), dtype=torch.bfloat16, device="cuda")
+            Y = torch.empty((wk.n, wk.p), dtype=torch.bfloat16, device="cuda")
+            Z = torch.empty((wk.n_data, wk.p), dtype=torch.bfloat16, device="cuda")
+            g.gelo_mix(ctx, m, H, U)
+            g.gelo_project(ctx, U, W, Y)
+            A, _, _, _, _ = g.gelo_mixing_export(ctx, m, wk.n, wk.k_shield, wk.d, want_shields=False)
+            g.gelo_unmix(ctx, m, Y, Z)
+            torch.cuda.synchronize()
+            g.gelo_mixing_free(ctx, m)
+            check_orthogonal_A(f64(A), 0xC0FFEE, bid, wk.n, compare_elements=True)
+            assert o.rel_frobenius(f64(Z), o.plain_projection(f64(H), f64(W))) < TOL_END["bf16"]
+        else:
+            Z = torch.empty((wk.n_data, wk.p), dtype=torch.bfloat16, device="cuda")
+            g.gelo_qkv_forward(ctx, wk.kind, H, W, Z, k_shield=wk.k_shield, batch_id=bid)
+            torch.cuda.synchronize()
+        rvec = torch.randn(wk.p, generator=gen, dtype=torch.float64).cuda()
+        err = freivalds(Z, H, W, rvec)
+        assert err < TOL_END["bf16"], (layer, err)
 
 
 def test_qkv_forward_equals_the_four_calls(ctx):

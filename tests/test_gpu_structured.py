@@ -29,8 +29,10 @@ def f64(t):
     return t.detach().to(torch.float64).cpu().numpy()
 
 
-@pytest.fixture(scope="module")
+@pytest.fixture()
 def ctx():
+    """a context per test: batch ids need not rise from one test to the next (a context refuses ids that
+    fall more than GELO_BATCH_WINDOW below the highest one it has seen)"""
     c = g.gelo_create(0, SEED, allow_batch_reuse=False)
     yield c
     g.gelo_destroy(c)
@@ -51,6 +53,25 @@ def test_dense_matrix_of_the_tables_matches_oracle(ctx, n_data, k):
     assert np.abs(f64(A) - A_ref).max() < 2e-6
     assert np.abs(f64(A_inv) - A_ref.T).max() < 2e-6
     assert np.linalg.norm(f64(A) @ f64(A_inv) - np.eye(n)) / math.sqrt(n) < 1e-5
+
+
+@pytest.mark.parametrize("n_data,k", [(1, 0), (2, 1), (63, 0), (64, 0), (65, 0), (300, 21), (2048, 102), (4096, 205),
+                                      (5000, 120)])
+def test_table_words_are_bit_exact(ctx, n_data, k):
+    """The tables are pure integer work (ranks of Philox keys, sign bits) and are held bit for bit: every
+    word of the library's table against the oracle's permutations (low 31 bits) and signs (top bit; the
+    last permutation carries none)."""
+    n = n_data + k
+    bid = 900000 + n
+    m = g.gelo_sample_mixing(ctx, g.GELO_STRUCTURED, n_data, k, 64, g.GELO_F32, 0.0, 1, batch_id=bid)
+    table = g.gelo_mixing_export_table(ctx, m, n).cpu().numpy().view(np.uint32)
+    g.gelo_mixing_free(ctx, m)
+    perms, signs = o.structured_tables(SEED, bid, n)
+    assert table.shape == (4, n)
+    assert np.array_equal(table & np.uint32(0x7FFFFFFF), perms.astype(np.uint32))
+    sign_bits = (table >> np.uint32(31)).astype(np.int64)
+    assert np.array_equal(sign_bits[:3], (signs < 0).astype(np.int64))
+    assert not sign_bits[3].any()
 
 
 @pytest.mark.parametrize("n_data,k", [(2400, 0), (2401, 0), (4096, 205), (4816, 0), (4817, 0), (5000, 120)])
