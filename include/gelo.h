@@ -91,6 +91,8 @@ typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;
 #define GELO_MAX_N 5120        /* largest n = n_data + k_shield the factorisation kernels take */
 #define GELO_MAX_ATTEMPTS 255  /* the attempt number is one byte of the Philox counter */
 #define GELO_BATCH_WINDOW 4096 /* how far below the highest batch id used so far an unused id is still accepted */
+#define GELO_STATIC_MAX_N 128  /* largest n gelo_qkv_forward_static takes */
+#define GELO_STATIC_SCRATCH_BYTES (3u << 20)   /* size of its static device buffer, held per GPU until the process ends */
 
 /* Creates a context on HIP device `device` with Philox key `seed`.  `allow_batch_reuse` != 0
  * switches off the check that a batch id is used at most once (for tests and benchmarks that
@@ -171,6 +173,21 @@ gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, in
                              int d, int p, const void* H, const void* W, float shield_scale,
                              gelo_norm_stat stat, double cond_max, int max_attempts, uint64_t batch_id,
                              void* Z, void* U_opt, void* Y_opt, void* stream);
+
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): gelo_qkv_forward for one decode-shaped batch with every intermediate of the
+ * trusted side (A, A^-1, the factorisation workspace, shield directions and rows) in a static device
+ * buffer of GELO_STATIC_SCRATCH_BYTES that each GPU the library runs on holds until the process ends.
+ * Calls no hipMalloc / hipFree and creates no stream, event or pooled object.  n = n_data + k_shield
+ * <= GELO_STATIC_MAX_N, and the batch's buffers (about 0.6 MB at n = 128 plus 10 bytes (bf16) or
+ * 12 bytes (float) per element of the k_shield x d shield block) must fit the static buffer:
+ * GELO_ESHAPE otherwise.  kind: GELO_ORTHOGONAL, GELO_CONDITIONED or GELO_STRUCTURED.  U (n x d) and
+ * Y (n x p) are required; H, W, Z, U, Y densely packed as in gelo_qkv_forward.  All calls on one GPU
+ * share the one buffer, whatever their context or stream: calls that overlap in time on a GPU race;
+ * issue them on one stream or order them yourself.  Same results, bit for bit, as gelo_qkv_forward. */
+gelo_status gelo_qkv_forward_static(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_data, int k_shield,
+                                    int d, int p, const void* H, const void* W, float shield_scale,
+                                    gelo_norm_stat stat, uint64_t batch_id, void* Z, void* U, void* Y, void* stream);
 
 /* Test hook: copies the secrets of a mixing object to caller DEVICE buffers (any may be NULL):
  * A and A_inv as float n x n (dense), S as float k_shield x d (dense; valid after gelo_mix).

@@ -19,6 +19,8 @@ STATUS_NAMES = ["GELO_OK", "GELO_EINVAL", "GELO_ESHAPE", "GELO_EDTYPE", "GELO_EA
                 "GELO_ECOND", "GELO_ESINGULAR", "GELO_EREUSE", "GELO_ESTATE", "GELO_EHIP"]
 GELO_MAX_N = 5120
 GELO_BATCH_WINDOW = 4096
+GELO_STATIC_MAX_N = 128
+GELO_STATIC_SCRATCH_BYTES = 3 << 20
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgelo.so")
 
@@ -40,6 +42,8 @@ SIGNATURES = {
     "gelo_mixing_free": (c_int, [c_void_p, c_void_p]),
     "gelo_mixing_info": (c_int, [c_void_p, c_void_p, POINTER(c_int), POINTER(c_int), POINTER(c_int), POINTER(c_int),
                                  POINTER(c_int)]),
+    "gelo_qkv_forward_static": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_float,
+                                        c_int, c_uint64, c_void_p, c_void_p, c_void_p, c_void_p]),
     "gelo_debug_philox_words": (c_int, [c_void_p, c_uint32, c_uint32, c_uint64, c_uint32, c_uint32, c_void_p, c_void_p]),
     "gelo_mixing_export_table": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p]),
     "gelo_qkv_forward": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_float,
@@ -196,6 +200,25 @@ def gelo_qkv_forward(ctx, kind: int, H: torch.Tensor, W: torch.Tensor, Z: torch.
         ctx, kind, _dtype_code(H), n_data, k_shield, d, p, c_void_p(H.data_ptr()), c_void_p(W.data_ptr()),
         shield_scale, stat, cond_max, max_attempts, batch_id, c_void_p(Z.data_ptr()),
         c_void_p(U.data_ptr()) if U is not None else None, c_void_p(Y.data_ptr()) if Y is not None else None,
+        _stream(stream)))
+    return Z
+
+
+def gelo_qkv_forward_static(ctx, kind: int, H: torch.Tensor, W: torch.Tensor, Z: torch.Tensor, U: torch.Tensor,
+                            Y: torch.Tensor, k_shield: int = 0, shield_scale: float = 10.0,
+                            stat: int = GELO_NORM_MEDIAN, batch_id: int = 0, stream=None) -> torch.Tensor:
+    """The chain for one decode-shaped batch through the entry point that allocates nothing."""
+    for name, t in (("H", H), ("W", W), ("Z", Z), ("U", U), ("Y", Y)):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != H.dtype:
+            raise ValueError(f"{name} must be a contiguous GPU tensor of H's dtype")
+    n_data, d = H.shape
+    p = W.shape[1]
+    n = n_data + k_shield
+    if W.shape[0] != d or tuple(Z.shape) != (n_data, p) or tuple(U.shape) != (n, d) or tuple(Y.shape) != (n, p):
+        raise ValueError("shape mismatch in gelo_qkv_forward_static")
+    _check(ctx, load_library().gelo_qkv_forward_static(
+        ctx, kind, _dtype_code(H), n_data, k_shield, d, p, c_void_p(H.data_ptr()), c_void_p(W.data_ptr()),
+        shield_scale, stat, batch_id, c_void_p(Z.data_ptr()), c_void_p(U.data_ptr()), c_void_p(Y.data_ptr()),
         _stream(stream)))
     return Z
 

@@ -34,6 +34,18 @@ constexpr float kKappaGuard = 1.01f;
 // "Never reused" without a growing set: every id below `batch_floor` or more than kBatchWindow below the
 // highest id seen counts as used; inside the window one bit per id remembers which ones were.
 constexpr int kBatchWindow = 4096;
+
+// Scratch of the entry point that allocates nothing (gelo_qkv_forward_static): the mixing matrices, the
+// factorisation workspace and the shield buffers of one decode-shaped batch.  Host code never uses this
+// name as an address: gelo_create asks the runtime for the array's device address, per device.
+constexpr size_t kStaticScratchBytes = (size_t)3 << 20;
+constexpr int kStaticMaxDevices = 16;
+}
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+void* g_scratch_ptr[kStaticMaxDevices] = {};
 }
 
 struct gelo_mixing {
@@ -66,6 +78,7 @@ struct gelo_ctx {
     uint64_t batch_floor;              // ids below it are refused (a resumed context starts here)
     uint64_t batch_high;               // one past the highest id used so far
     uint64_t batch_bits[kBatchWindow / 64];   // bit (id % kBatchWindow): id was used, for ids in [batch_high - kBatchWindow, batch_high)
+    void* static_scratch;              // device address of `scratch` on this context's device
     std::string err;
     void* factor_ws; size_t factor_ws_bytes;
     void* chain_ws;  size_t chain_ws_bytes;
@@ -277,6 +290,14 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
     ctx->device = device; ctx->seed = seed; ctx->allow_reuse = allow_batch_reuse != 0;
     ctx->batch_floor = 0; ctx->batch_high = 0;
     std::memset(ctx->batch_bits, 0, sizeof ctx->batch_bits);
+    // the device address of the static scratch array, asked for once per device with that device current
+    ctx->static_scratch = device < kStaticMaxDevices ? g_scratch_ptr[device] : nullptr;
+    if (!ctx->static_scratch) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { delete ctx; return GELO_EHIP; }
+        ctx->static_scratch = ptr;
+        if (device < kStaticMaxDevices) g_scratch_ptr[device] = ptr;
+    }
     ctx->factor_ws = ctx->chain_ws = nullptr; ctx->factor_ws_bytes = ctx->chain_ws_bytes = 0;
     ctx->host_scalars = nullptr; ctx->host_flag = nullptr;
     ctx->lanes_ready = false; ctx->join_pending = false; ctx->cand = nullptr; ctx->cand_bytes = 0;
@@ -747,6 +768,43 @@ gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* m, float* A, fl
         }
     }
     return GELO_OK;
+}
+
+gelo_status gelo_qkv_forward_static(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_data, int k_shield,
+                                    int d, int p, const void* H, const void* W, float shield_scale,
+                                    gelo_norm_stat stat, uint64_t batch_id, void* Z, void* U, void* Y, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!H || !W || !Z || !U || !Y) return fail(ctx, GELO_EINVAL, "H, W, Z, U and Y must not be NULL");
+    if (!aligned16(H) || !aligned16(W) || !aligned16(Z) || !aligned16(U) || !aligned16(Y))
+        return fail(ctx, GELO_EALIGN, "H, W, Z, U and Y must be 16-byte aligned");
+    if (p < 1 || p % 8 != 0) return fail(ctx, p < 1 ? GELO_EINVAL : GELO_EALIGN, "p=%d must be a positive multiple of 8", p);
+    if (kind == GELO_GAUSSIAN) return fail(ctx, GELO_EINVAL, "GELO_GAUSSIAN reads condition estimates back and uses buffers of its own: not available without allocation");
+    if (stat != GELO_NORM_MEDIAN && stat != GELO_NORM_MEAN) return fail(ctx, GELO_EINVAL, "unknown norm statistic %d", (int)stat);
+    if (k_shield > 0 && !(shield_scale > 0.f)) return fail(ctx, GELO_EINVAL, "shield_scale=%g must be positive", (double)shield_scale);
+    int n = 0;
+    gelo_status st = check_sample_args(ctx, kind, n_data, k_shield, d, dtype, 1.0, 1, batch_id, &n);
+    if (st != GELO_OK) return st;
+    const bool structured = kind == GELO_STRUCTURED;
+    if (n > GELO_STATIC_MAX_N) return fail(ctx, GELO_ESHAPE, "n = %d exceeds GELO_STATIC_MAX_N = %d", n, GELO_STATIC_MAX_N);
+    const MixingLayout L = mixing_layout(n_data, k_shield, d, dtype, structured);
+    const size_t ws_bytes = structured ? 0 : up256(factor_workspace_bytes(n));
+    if (L.total + ws_bytes > kStaticScratchBytes)
+        return fail(ctx, GELO_ESHAPE, "this batch needs %zu bytes of scratch, the static buffer holds %zu (n <= %d, and k_shield * d bounded by it)",
+                    L.total + ws_bytes, kStaticScratchBytes, GELO_STATIC_MAX_N);
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    // the mixing object of this call lives on the host stack and points into the static device array
+    gelo_mixing local = {};
+    char* base = (char*)ctx->static_scratch;
+    carve_mixing(&local, base, n_data, k_shield, d, dtype, structured);
+    FactorWorkspace ws = {};
+    if (!structured) factor_workspace_carve(base + up256(L.total), n, &ws);
+    st = sample_into(ctx, &local, ws, ws_bytes, 1, kind, 1.0, 1, batch_id, s);
+    if (st == GELO_OK) batch_commit(ctx, batch_id);
+    if (st == GELO_OK) st = mix_launch(ctx, &local, H, d, shield_scale, stat, U, d, s);
+    if (st == GELO_OK) st = gelo_project(ctx, dtype, n, d, p, U, d, W, p, Y, p, stream);
+    if (st == GELO_OK) st = unmix_launch(ctx, &local, p, Y, p, Z, p, s);
+    return st;
 }
 
 gelo_status gelo_reserve(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_data, int k_shield, int d, int p,

@@ -192,6 +192,33 @@ def test_reserve_sizes_the_context_ahead(ctx):
     assert status_of(g.gelo_reserve, ctx, g.GELO_ORTHOGONAL, g.GELO_BF16, g.GELO_MAX_N, 1, d) == "GELO_ESHAPE"
 
 
+def test_static_entry_point_argument_checks(ctx):
+    H = torch.randn(64, 64, device="cuda")
+    W = torch.randn(64, 72, device="cuda")
+    Z = torch.empty(64, 72, device="cuda")
+    S = g.gelo_qkv_forward_static
+    def bufs(n, d=64, p=72):
+        return torch.empty(n, d, device="cuda"), torch.empty(n, p, device="cuda")
+    U, Y = bufs(68)
+    assert status_of(S, ctx, g.GELO_GAUSSIAN, H, W, Z, U, Y, k_shield=4, batch_id=1) == "GELO_EINVAL"
+    Hbig = torch.randn(g.GELO_STATIC_MAX_N, 64, device="cuda")
+    Zbig = torch.empty(g.GELO_STATIC_MAX_N, 72, device="cuda")
+    U2, Y2 = bufs(g.GELO_STATIC_MAX_N + 1)
+    assert status_of(S, ctx, g.GELO_ORTHOGONAL, Hbig, W, Zbig, U2, Y2, k_shield=1, batch_id=1) == "GELO_ESHAPE"
+    # the shield block alone would not fit the static buffer: 64 x 16384 floats and their rows
+    d = 16384
+    Hw = torch.randn(64, d, device="cuda")
+    Ww = torch.randn(d, 8, device="cuda")
+    U3, Y3 = torch.empty(128, d, device="cuda"), torch.empty(128, 8, device="cuda")
+    assert status_of(S, ctx, g.GELO_ORTHOGONAL, Hw, Ww, torch.empty(64, 8, device="cuda"), U3, Y3, k_shield=64, batch_id=1) == "GELO_ESHAPE"
+    assert b"static buffer" in g.load_library().gelo_last_error(ctx)
+    # none of the refused calls consumed the batch id
+    S(ctx, g.GELO_ORTHOGONAL, H, W, Z, U, Y, k_shield=4, batch_id=1)
+    assert status_of(S, ctx, g.GELO_ORTHOGONAL, H, W, Z, U, Y, k_shield=4, batch_id=1) == "GELO_EREUSE"
+    torch.cuda.synchronize()
+    assert torch.allclose(Z, H @ W, rtol=1e-3, atol=1e-3)
+
+
 def test_condition_budget_exhausted(ctx):
     # kappa <= 1.5 never happens for a Gaussian draw: every attempt is rejected, status ECOND
     assert status_of(g.gelo_sample_mixing, ctx, g.GELO_GAUSSIAN, 64, 0, 64, g.GELO_F32, 1.5, 3, 30) == "GELO_ECOND"
