@@ -56,82 +56,215 @@ SRC_PATH = os.path.join(ROOT, "paper_2603_05035_amd", "csrc", "gemm_bf16.hip")
 TRAFFIC_PATH = os.path.join(ROOT, "profiles", "gemm_project_traffic.json")
 
 
-def write_traffic_record(workload: str, fetch_csv: str, write_csv: str) -> int:
-    """HBM bytes per launch of the projection GEMM from two counter runs.
+# Workloads made of several chains per step.  A step of "llama7b_bf16_layer" is one layer's two offloaded
+# projections (Fig. 1: Q, K, V and O all go through the protocol): fused QKV on the hidden states, then O on
+# the attention output (a second synthetic activation stands in), each with a fresh A of its own.  A step of
+# "prefill_sweep_bf16" is the 32-layer prefill sweep (4096 rows per layer, even layers ORTHOGONAL + 205
+# shields, odd layers CONDITIONED, fresh H, W and A per layer).  A step of "decode_sweep_bf16" is one decode
+# step through 32 layers (64 tokens + 4 shields, a fresh 68 x 68 A per layer-step, 32 resident weights); the
+# config's 128 steps are the default step count.
+COMPOSITE = {
+    "llama7b_bf16_layer": ["llama7b_bf16_prefill", "llama7b_bf16_oproj"],
+    "prefill_sweep_bf16": ["sweep_bf16_orth" if l % 2 == 0 else "sweep_bf16_cond" for l in range(32)],
+    "decode_sweep_bf16": ["decode_bf16"] * 32,
+}
 
-    FETCH_SIZE and WRITE_SIZE are reported in KiB per dispatch.  Each is scaled by the factor that maps
-    what the same counter reads for the calibration copy (a plain elementwise kernel that reads and
-    writes CAL_ELEMS fp32 values) onto that kernel's known byte count.
-    """
-    import csv
-    import hashlib
-    import re
-    from paper_2603_05035_amd import workloads as wl
-    w = wl.WORKLOADS[workload]
-    def read(path, counter):
-        # the projection is the GEMM launch bench.py issues most often (its isolated timing loop): of the
-        # (kernel, grid) pairs of the direct-to-LDS GEMM kernels, the one with the most dispatches
-        groups, cal = {}, []
-        for row in csv.DictReader(open(path, newline="")):
-            if row["Counter_Name"] != counter:
-                continue
-            name, grid, val = row["Kernel_Name"], int(row["Grid_Size"]), float(row["Counter_Value"])
-            if "gemm_bf16_dma" in name:
-                groups.setdefault((name, grid), []).append(val)
-            elif "elementwise_kernel" in name and "Mul" in name and grid >= CAL_ELEMS // 64:
-                cal.append(val)
-        if not groups or not cal:
-            raise SystemExit(f"{path}: {len(groups)} GEMM launch shapes, {len(cal)} calibration launches with {counter}")
-        key = max(groups, key=lambda k: len(groups[k]))
-        gemm = groups[key]
-        return sum(gemm) / len(gemm), sum(cal) / len(cal), len(gemm), len(cal), key
 
-    known = CAL_ELEMS * 4.0
-    f_gemm, f_cal, nf, ncf, key = read(fetch_csv, "FETCH_SIZE")
-    w_gemm, w_cal, nw, ncw, key_w = read(write_csv, "WRITE_SIZE")
-    if key != key_w:
-        raise SystemExit(f"the two runs disagree on the projection launch: {key} vs {key_w}")
-    fetch_factor, write_factor = known / (f_cal * 1024.0), known / (w_cal * 1024.0)
-    fetch_b, write_b = f_gemm * 1024.0 * fetch_factor, w_gemm * 1024.0 * write_factor
-    rec = {
-        "workload": w.name,
-        "kernel": re.search(r"gemm_bf16_dma\w*(<\d+>)?", key[0]).group(0) + " (project Y = U W)", "grid_threads": key[1],
-        "kernel_source_sha1": hashlib.sha1(open(SRC_PATH, "rb").read()).hexdigest(),
-        "traffic_bytes_per_launch": fetch_b + write_b,
-        "fetch_bytes_per_launch": fetch_b, "write_bytes_per_launch": write_b,
-        "algorithmic_bytes_per_launch": 2.0 * (w.n * w.d + w.d * w.p + w.n * w.p),
-        "raw_KiB": {"FETCH_SIZE": f_gemm, "WRITE_SIZE": w_gemm, "FETCH_SIZE_copy": f_cal, "WRITE_SIZE_copy": w_cal},
-        "calibration": {"copy_bytes_each_way": known, "fetch_factor": fetch_factor, "write_factor": write_factor},
-        "launches_averaged": {"projection": [nf, nw], "copy": [ncf, ncw]},
-        "commands": ["rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dir> -o fetch -- "
-                     "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --traffic-calibration",
-                     "rocprofv3 --pmc WRITE_SIZE --output-format csv -d <dir> -o write -- "
-                     "python3 bench.py --steps 2 --warmup 1 --no-cpu-baseline --traffic-calibration",
-                     "python3 bench.py --write-traffic-record <fetch>_counter_collection.csv <write>_counter_collection.csv"],
+def run_composite(args, torch, np, g, wl):
+    name = args.workload
+    parts = [wl.WORKLOADS[x] for x in COMPOSITE[name]]
+    L = len(parts)
+    K = args.steps if args.steps_given else {"llama7b_bf16_layer": 50, "prefill_sweep_bf16": 2, "decode_sweep_bf16": 128}[name]
+    Wm = args.warmup if args.warmup_given else {"llama7b_bf16_layer": 10, "prefill_sweep_bf16": 1, "decode_sweep_bf16": 8}[name]
+    dt = torch.bfloat16
+    # inputs resident in HBM: one weight per layer; hidden states per layer (the decode sweep reuses its 32
+    # hidden-state buffers across steps: the chain does not look at the values)
+    Hs, Ws = [], []
+    for l, w in enumerate(parts):
+        H32 = wl.make_hidden(w.n_data, w.d, w.seed * 1000 + l, w.outlier_channels)
+        Hs.append(torch.from_numpy(H32).to(dt).cuda())
+        Ws.append(torch.from_numpy(wl.make_weight(w.d, w.p, w.seed * 1000 + l)).to(dt).cuda())
+    nmax = max(w.n for w in parts); pmax = max(w.p for w in parts); dmax = max(w.d for w in parts)
+    U = torch.empty((nmax * dmax,), dtype=dt, device="cuda")
+    Y = torch.empty((nmax * pmax,), dtype=dt, device="cuda")
+    Z = torch.empty((max(w.n_data for w in parts) * pmax,), dtype=dt, device="cuda")
+    def views(w):
+        return (U[:w.n * w.d].view(w.n, w.d), Y[:w.n * w.p].view(w.n, w.p), Z[:w.n_data * w.p].view(w.n_data, w.p))
+
+    depth = args.pipeline
+    side = [torch.cuda.Stream() for _ in range(depth)]
+    ctxs = [g.gelo_create(0, 0xBE00 + i, allow_batch_reuse=False) for i in range(depth)]
+    for c in ctxs:                                   # sizes known ahead: nothing allocates inside the timed region
+        for w in {(w.kind, w.n_data, w.k_shield, w.d): w for w in parts}.values():
+            g.gelo_reserve(c, w.kind, g.GELO_BF16, w.n_data, w.k_shield, w.d, 0, 64, 1)
+    ring = [None] * depth
+    counter = [0]                                    # chains issued so far; batch id = step * L + layer
+
+    def draw(slot, idx):
+        w = parts[idx % L]
+        ring[slot] = (g.gelo_sample_mixing(ctxs[slot], w.kind, w.n_data, w.k_shield, w.d, g.GELO_BF16, w.cond_max, 64,
+                                           idx, stream=side[slot]), idx)
+
+    def chain(i):
+        slot = i % depth
+        m, idx = ring[slot]
+        l = idx % L
+        w = parts[l]
+        u, y, z = views(w)
+        g.gelo_mix(ctxs[slot], m, Hs[l], u, w.shield_scale)
+        g.gelo_project(ctxs[slot], u, Ws[l], y)
+        g.gelo_unmix(ctxs[slot], m, y, z)
+        g.gelo_mixing_free(ctxs[slot], m)
+        draw(slot, idx + depth)
+
+    for slot in range(depth):
+        draw(slot, slot)
+    i = 0
+    for _ in range(Wm * L):
+        chain(i); i += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K * L):
+        chain(i); i += 1
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / K
+    for slot in range(depth):
+        g.gelo_mixing_free(ctxs[slot], ring[slot][0])
+
+    # serial: the same chains through gelo_qkv_forward on one stream, nothing overlapped
+    ctx = ctxs[0]
+    base = (i + depth + 1 + L) // L * L
+    Ks = max(1, min(K, 8))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for j in range(Ks * L):
+        w = parts[j % L]
+        u, y, z = views(w)
+        g.gelo_qkv_forward(ctx, w.kind, Hs[j % L], Ws[j % L], z, k_shield=w.k_shield, shield_scale=w.shield_scale,
+                           cond_max=w.cond_max, batch_id=base + j, U=u, Y=y)
+    torch.cuda.synchronize()
+    t_serial = (time.perf_counter() - t0) / Ks
+
+    # the plain projections of one step through the same kernel, and per-layer stage times of the first layers
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+    for l in range(L):
+        g.gelo_project(ctx, Hs[l], Ws[l], views(parts[l])[2])
+    torch.cuda.synchronize()
+    a, b = ev(), ev()
+    a.record()
+    for _ in range(3):
+        for l in range(L):
+            g.gelo_project(ctx, Hs[l], Ws[l], views(parts[l])[2])
+    b.record()
+    torch.cuda.synchronize()
+    t_plain = a.elapsed_time(b) / 3 * 1e-3
+    stages = []
+    bid = base + Ks * L + L
+    for l in range(min(L, 2)):
+        w = parts[l]
+        u, y, z = views(w)
+        acc = {"sample": 0.0, "mix": 0.0, "project": 0.0, "unmix": 0.0}
+        reps = 5
+        for r in range(reps):
+            e = [ev() for _ in range(5)]
+            e[0].record()
+            m = g.gelo_sample_mixing(ctx, w.kind, w.n_data, w.k_shield, w.d, g.GELO_BF16, w.cond_max, 64, bid); bid += 1
+            e[1].record(); g.gelo_mix(ctx, m, Hs[l], u, w.shield_scale)
+            e[2].record(); g.gelo_project(ctx, u, Ws[l], y)
+            e[3].record(); g.gelo_unmix(ctx, m, y, z)
+            e[4].record(); torch.cuda.synchronize()
+            g.gelo_mixing_free(ctx, m)
+            for q, key in enumerate(("sample", "mix", "project", "unmix")):
+                acc[key] += e[q].elapsed_time(e[q + 1]) / reps
+        stages.append({"layer": l, "workload": w.name, **{k2: round(v, 4) for k2, v in acc.items()}})
+    # the projection of layer 0 alone, for the roofline of the dominant kernel
+    w0 = parts[0]
+    u0, y0, _ = views(w0)
+    for _ in range(20):
+        g.gelo_project(ctx, u0, Ws[0], y0)
+    torch.cuda.synchronize()
+    pairs = []
+    for _ in range(50):
+        a, b = ev(), ev(); a.record(); g.gelo_project(ctx, u0, Ws[0], y0); b.record(); pairs.append((a, b))
+    torch.cuda.synchronize()
+    t_proj = sum(x.elapsed_time(y_) for x, y_ in pairs) / len(pairs) * 1e-3
+    for c in ctxs:
+        g.gelo_destroy(c)
+
+    f_chain = sum(chain_flops(w) for w in parts)
+    f_gen = sum(gen_flops(w) for w in parts)
+    f_plain = sum(2.0 * w.n_data * w.d * w.p for w in parts)
+    peak = PEAK_TFLOPS["bf16"]
+    decode = parts[0].n <= 128
+    result = {
+        "metric": "GELO QKV-forward TFLOP/s (whole step: A generation + shields + mix + project + unmix)",
+        "value": (f_chain + f_gen) / t_step / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": name, "chains_per_step": L, "parts": sorted({w.name for w in parts}),
+                   "step": {"llama7b_bf16_layer": "one layer: fused QKV projection, then O projection, a fresh A each",
+                            "prefill_sweep_bf16": "one 32-layer prefill sweep (4096 rows per layer; even layers orthogonal + 205 shields, odd layers conditioned)",
+                            "decode_sweep_bf16": "one decode step through 32 layers (64 tokens + 4 shields, fresh 68 x 68 A per layer-step)"}[name]},
+        "pipeline": {"depth": depth, "serial_ms_per_step": t_serial * 1e3, "serial_steps_timed": Ks,
+                     "note": "A for the next chains is drawn on side streams while the chains run; every timed chain draws one A and consumes one"},
+        "us_per_chain": t_step / L * 1e6, "serial_us_per_chain": t_serial / L * 1e6,
+        "frac_of_mfma_peak_whole_step": (f_chain + f_gen) / t_step / 1e12 / peak,
+        "plain_ms_per_step": t_plain * 1e3,
+        "overhead_vs_plain_gemm_pct": {"whole_step": (t_step / t_plain - 1.0) * 100.0, "whole_step_serial": (t_serial / t_plain - 1.0) * 100.0,
+                                       "flop_ratio_floor": (f_chain / f_plain - 1.0) * 100.0},
+        "useful_tflops": f_plain / t_step / 1e12,
+        "stage_ms_first_layers": stages,
     }
-    with open(TRAFFIC_PATH, "w") as f:
-        json.dump(rec, f, indent=1)
-        f.write("\n")
-    print(json.dumps(rec))
+    if decode:
+        b_proj = 2.0 * (w0.n * w0.d + w0.d * w0.p + w0.n * w0.p)
+        result["roofline"] = {"kernel": "gemm (project Y = U W), skinny path", "bound": "hbm", "achieved": b_proj / t_proj / 1e9,
+                              "peak": 8000.0, "unit": "GB/s", "frac": b_proj / t_proj / 1e9 / 8000.0, "traffic": None,
+                              "avg_launch_us": t_proj * 1e6}
+        result["w_stream_floor_us_per_chain"] = 2.0 * w0.d * w0.p / 8e12 * 1e6
+    else:
+        f_proj = 2.0 * w0.n * w0.d * w0.p
+        result["roofline"] = {"kernel": "gemm (project Y = U W) of the step's first chain", "bound": "mfma", "achieved": f_proj / t_proj / 1e12,
+                              "peak": peak, "unit": "TFLOP/s", "frac": f_proj / t_proj / 1e12 / peak, "traffic": None,
+                              "avg_launch_us": t_proj * 1e6}
+    if not args.no_cpu_baseline:
+        from oracle import gelo_oracle as oracle
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([t.get("num_threads", 1) for t in threadpool_info()] or [os.cpu_count() or 1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        # bounded sample: the first chain of the step on at most 1024 of its rows
+        rows = min(w0.n_data, 1024)
+        ks = w0.k_shield if rows == w0.n_data else int(round(0.05 * rows)) if w0.k_shield > 0 else 0
+        H64, W64 = Hs[0][:rows].double().cpu().numpy(), Ws[0].double().cpu().numpy()
+        t0 = time.perf_counter()
+        ref = oracle.qkv_forward(w0.kind, w0.seed, 0, H64, W64, k_shield=ks, shield_scale=w0.shield_scale, cond_max=w0.cond_max)
+        t_cpu = time.perf_counter() - t0
+        ns = rows + ks
+        f_s = 2.0 * ns * ns * w0.d + 2.0 * ns * w0.d * w0.p + 2.0 * rows * ns * w0.p + 8.0 / 3.0 * float(ns) ** 3
+        result["cpu_baseline"] = {"value": f_s / t_cpu / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle", "seconds": t_cpu,
+                                  "sample": f"one fp64 oracle chain (sampling + QR + shields + mix + project + unmix) of the step's first "
+                                            f"projection on {rows} data rows + {ks} shield rows (d={w0.d}, p={w0.p})",
+                                  "check_rel_err_vs_plain": float(np.linalg.norm(ref["Z"] - H64 @ W64) / np.linalg.norm(H64 @ W64))}
+    print(json.dumps(result))
     return 0
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=25)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="llama7b_bf16_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pipeline", type=int, default=24, help="mixing matrices drawn ahead on side streams")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run a plain elementwise copy of known size (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--write-traffic-record", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
-                    help="no GPU work: turn the counter_collection.csv files of two rocprofv3 --pmc runs of "
-                         "'bench.py --traffic-calibration' (FETCH_SIZE, then WRITE_SIZE) into profiles/gemm_project_traffic.json")
     args = ap.parse_args()
-    if args.write_traffic_record:
-        return write_traffic_record(args.workload, *args.write_traffic_record)
+    args.steps_given, args.warmup_given = args.steps is not None, args.warmup is not None
+    args.steps = 50 if args.steps is None else args.steps
+    args.warmup = 25 if args.warmup is None else args.warmup
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this library runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
@@ -144,6 +277,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.workload in COMPOSITE:
+        return run_composite(args, torch, np, g, wl)
     w = wl.WORKLOADS[args.workload]
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     H32, W32 = wl.make_inputs(w)
@@ -285,6 +420,17 @@ def main() -> int:
                      "avg_launch_us": t_proj * 1e6},
     }
 
+    if w.kind in (0, 1, 2):
+        # A generation against the float matrix peak: the factorisations' trailing updates run on the float MFMA
+        # path; their panels are bound by the latency of one workgroup, which is what keeps the fraction low
+        t_gen = stage["sample"] * 1e-3
+        result["a_gen"] = {"kernel": {0: "Philox + Householder QR with explicit Q", 1: "Philox + pivoted LU + inverse + condition estimate (per accepted draw)",
+                                      2: "Householder QR + pivoted LU + inverse + condition estimate"}[w.kind],
+                           "bound": "mfma", "flop": f_gen, "ms": t_gen * 1e3, "achieved": f_gen / t_gen / 1e12, "peak": PEAK_TFLOPS["f32"],
+                           "unit": "TFLOP/s", "frac": f_gen / t_gen / 1e12 / PEAK_TFLOPS["f32"],
+                           "pipelined_ms_per_draw": t_step * 1e3,
+                           "note": "one draw alone on one stream; pipelined_ms_per_draw bounds it from above when draws of other batches overlap"}
+
     if n <= 128:
         # decode-shaped batches: the projection streams W once and does almost no arithmetic per byte
         # (about 2 n FLOP per byte of W), so it is bound by HBM, not by the matrix cores
@@ -329,6 +475,8 @@ def main() -> int:
         src = open(SRC_PATH, "rb").read()
         if rec.get("workload") == w.name and rec.get("kernel_source_sha1") == hashlib.sha1(src).hexdigest():
             result["roofline"]["traffic"] = rec["traffic_bytes_per_launch"]
+            result["roofline"]["traffic_source"] = ("profiles/gemm_project_traffic.json: counters taken in an earlier run on this "
+                                                   "kernel source (matched by its SHA-1), not measured in this run")
     except Exception:
         pass
 

@@ -91,7 +91,8 @@ typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;
 #define GELO_MAX_N 5120        /* largest n = n_data + k_shield the factorisation kernels take */
 #define GELO_MAX_ATTEMPTS 255  /* the attempt number is one byte of the Philox counter */
 #define GELO_BATCH_WINDOW 4096 /* how far below the highest batch id used so far an unused id is still accepted */
-#define GELO_STATIC_MAX_N 128  /* largest n gelo_qkv_forward_static takes */
+#define GELO_STATIC_MAX_N 128  /* largest n gelo_qkv_forward_static and gelo_sample_mixing_batch take */
+#define GELO_MAX_BATCH_DRAW 48 /* mixing objects one gelo_sample_mixing_batch call draws */
 #define GELO_STATIC_SCRATCH_BYTES (3u << 20)   /* size of its static device buffer, held per GPU until the process ends */
 
 /* Creates a context on HIP device `device` with Philox key `seed`.  `allow_batch_reuse` != 0
@@ -139,6 +140,15 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
                                gelo_dtype dtype, double cond_max, int max_attempts,
                                uint64_t batch_id, gelo_mixing** out, void* stream);
 
+/* Trusted side, Section 3.2 step 1.2 for decode-shaped batches: `count` mixing objects (1..GELO_MAX_BATCH_DRAW)
+ * for batch ids first_batch_id .. first_batch_id + count - 1, all of one shape, drawn by ONE launch (a fresh
+ * A per layer-step costs more in launch latency than in work at this size, and A does not depend on the data:
+ * a decode step's worth is drawn ahead at once).  GELO_ORTHOGONAL only, n = n_data + k_shield <=
+ * GELO_STATIC_MAX_N (GELO_ESHAPE beyond).  Object i is what gelo_sample_mixing returns for its batch id, bit
+ * for bit.  out: HOST array of `count` pointers; on an error nothing is drawn and no id is consumed. */
+gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d, gelo_dtype dtype,
+                                     uint64_t first_batch_id, int count, gelo_mixing** out, void* stream);
+
 /* Trusted side, eq. 1 / eqs. 7-8.  Shield rows S_i = g_i * shield_scale * m(H) / ||g_i||, m the
  * median or mean row 2-norm of H; then U[n x d] = A * [H ; S].  H: n_data x d (ldh), U: n x d (ldu),
  * both of type `dtype`, which must be the one the mixing object was drawn for (GELO_EDTYPE otherwise:
@@ -161,6 +171,11 @@ gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* mixing, gelo_dtype dtype, int
                        void* Z, int64_t ldz, void* stream);
 
 gelo_status gelo_mixing_free(gelo_ctx* ctx, gelo_mixing* mixing);
+/* gelo_mix, gelo_project and gelo_unmix (eqs. 1-3) for a mixing object drawn earlier, in one call: H (n_data x d),
+ * W (d x p), Z (n_data x p), U (n x d) and Y (n x p) densely packed, all of type `dtype`; U and Y are required (they
+ * are the observable messages).  The latency-bound decode path spends one host call per layer-step this way. */
+gelo_status gelo_chain(gelo_ctx* ctx, gelo_mixing* mixing, gelo_dtype dtype, int p, const void* H, const void* W,
+                       float shield_scale, gelo_norm_stat stat, void* Z, void* U, void* Y, void* stream);
 /* Shape and type a mixing object was drawn for (any out pointer may be NULL): H is n_data x d,
  * U is (n_data + k_shield) x d, Y is (n_data + k_shield) x p, Z is n_data x p. */
 gelo_status gelo_mixing_info(gelo_ctx* ctx, const gelo_mixing* mixing, int* n_data, int* k_shield, int* d,

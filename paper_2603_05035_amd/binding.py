@@ -20,6 +20,7 @@ STATUS_NAMES = ["GELO_OK", "GELO_EINVAL", "GELO_ESHAPE", "GELO_EDTYPE", "GELO_EA
 GELO_MAX_N = 5120
 GELO_BATCH_WINDOW = 4096
 GELO_STATIC_MAX_N = 128
+GELO_MAX_BATCH_DRAW = 48
 GELO_STATIC_SCRATCH_BYTES = 3 << 20
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgelo.so")
@@ -35,6 +36,9 @@ SIGNATURES = {
     "gelo_set_batch_floor": (c_int, [c_void_p, c_uint64]),
     "gelo_get_batch_floor": (c_int, [c_void_p, POINTER(c_uint64)]),
     "gelo_reserve": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int]),
+    "gelo_sample_mixing_batch": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_uint64, c_int, POINTER(c_void_p), c_void_p]),
+    "gelo_chain": (c_int, [c_void_p, c_void_p, c_int, c_int, c_void_p, c_void_p, c_float, c_int, c_void_p, c_void_p, c_void_p,
+                           c_void_p]),
     "gelo_mix": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_int64, c_float, c_int, c_void_p, c_int64, c_void_p]),
     "gelo_project": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_int64, c_void_p, c_int64,
                              c_void_p, c_int64, c_void_p]),
@@ -124,6 +128,31 @@ def gelo_sample_mixing(ctx, kind: int, n_data: int, k_shield: int, d: int, dtype
     _check(ctx, load_library().gelo_sample_mixing(ctx, kind, n_data, k_shield, d, dtype, cond_max, max_attempts,
                                                   batch_id, byref(mixing), _stream(stream)))
     return mixing
+
+
+def gelo_sample_mixing_batch(ctx, kind: int, n_data: int, k_shield: int, d: int, dtype: int, first_batch_id: int,
+                             count: int, stream=None):
+    """`count` mixing objects for consecutive batch ids from one launch (decode-shaped batches)."""
+    arr = (c_void_p * count)()
+    _check(ctx, load_library().gelo_sample_mixing_batch(ctx, kind, n_data, k_shield, d, dtype, first_batch_id, count,
+                                                        arr, _stream(stream)))
+    return [c_void_p(arr[i]) for i in range(count)]
+
+
+def gelo_chain(ctx, mixing, H: torch.Tensor, W: torch.Tensor, Z: torch.Tensor, U: torch.Tensor, Y: torch.Tensor,
+               shield_scale: float = 10.0, stat: int = GELO_NORM_MEDIAN, stream=None) -> torch.Tensor:
+    """mix + project + unmix for a mixing object drawn earlier, one call."""
+    for name, t in (("H", H), ("W", W), ("Z", Z), ("U", U), ("Y", Y)):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != H.dtype:
+            raise ValueError(f"{name} must be a contiguous GPU tensor of H's dtype")
+    p = W.shape[1]
+    if W.shape[0] != H.shape[1] or Y.shape[1] != p or Z.shape[1] != p:
+        raise GeloError(2, "W, Y and Z do not fit together")
+    _check_against_mixing(ctx, mixing, (("H", H, "n_data", "d"), ("U", U, "n", "d"), ("Y", Y, "n", None), ("Z", Z, "n_data", None)))
+    _check(ctx, load_library().gelo_chain(ctx, mixing, _dtype_code(H), p, c_void_p(H.data_ptr()), c_void_p(W.data_ptr()),
+                                          shield_scale, stat, c_void_p(Z.data_ptr()), c_void_p(U.data_ptr()),
+                                          c_void_p(Y.data_ptr()), _stream(stream)))
+    return Z
 
 
 def gelo_mixing_info(ctx, mixing):

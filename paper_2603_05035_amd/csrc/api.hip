@@ -196,6 +196,14 @@ void carve_mixing(gelo_mixing* m, void* base, int n_data, int k, int d, int dtyp
     m->stat = (float*)p;
 }
 
+// Where the buffers a batched small draw fills sit inside a mixing object's block (the same for every object of a shape).
+void small_targets_layout(const gelo_mixing* m, SmallSampleTargets* t) {
+    const char* base = (const char*)m->block;
+    t->off_A32 = (const char*)m->A32 - base; t->off_Ainv32 = (const char*)m->Ainv32 - base;
+    t->off_A16 = m->A16 ? (const char*)m->A16 - base : -1; t->off_Ainv16 = m->Ainv16 ? (const char*)m->Ainv16 - base : -1;
+    t->off_GS = (const char*)m->GS - base; t->off_gsnorm = (const char*)m->gsnorm - base;
+}
+
 // A free pooled object of this shape, or a new one (the only place a mixing object allocates; gelo_reserve
 // fills the pool ahead of time so that the per-batch calls find one).
 gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, bool structured, gelo_mixing** out) {
@@ -307,7 +315,7 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
     if (hipHostMalloc((void**)&ctx->host_scalars, 64, hipHostMallocDefault) != hipSuccess) { delete ctx; return GELO_ENOMEM; }
     ctx->host_flag = (int*)(ctx->host_scalars + 8);
     if (gemm_bf16_init() != hipSuccess || gemm_f32_init() != hipSuccess || lu_init() != hipSuccess ||
-        structured_init() != hipSuccess) {
+        structured_init() != hipSuccess || small_init() != hipSuccess) {
         hipHostFree(ctx->host_scalars); delete ctx; return GELO_EHIP;
     }
     *out = ctx;
@@ -384,6 +392,16 @@ static gelo_status sample_into(gelo_ctx* ctx, gelo_mixing* m, FactorWorkspace ws
         return e;
     };
 
+    if (kind == GELO_ORTHOGONAL && n <= kSmallMaxN) {
+        // decode-shaped: Gaussian, QR, both matrices and the shield directions from one launch
+        SmallSampleTargets t;
+        small_targets_layout(m, &t);
+        t.block[0] = m->block;
+        ps.c1 = kStreamMixing << 8;
+        GELO_HIP(ctx, small_sample(t, 1, batch_id, ps, kStreamShield << 8, n, k_shield, d, ldk, s));
+        m->batch_id = batch_id;
+        return GELO_OK;
+    }
     if (structured) {
         GELO_HIP(ctx, structured_tables(m->table, n, kStructuredRounds, ps, s));
     } else if (kind == GELO_ORTHOGONAL) {
@@ -562,6 +580,13 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
 static gelo_status mix_launch(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh, float shield_scale,
                               gelo_norm_stat stat, void* U, int64_t ldu, hipStream_t s) {
     const bool bf = m->dtype == GELO_BF16;
+    if (bf && !m->structured && m->n <= kSmallMaxN) {
+        // decode-shaped: row norms, then statistic + shield rows + product in one launch
+        if (m->k > 0) GELO_HIP(ctx, row_norms(H, 1, ldh, m->n_data, m->d, m->rownorm, s));
+        GELO_HIP(ctx, small_mix(m->A16, m->ldk, (const uint16_t*)H, ldh, m->GS, m->gsnorm, m->rownorm, (int)stat, shield_scale,
+                                m->n_data, m->k, m->d, (uint16_t*)m->S, (uint16_t*)U, ldu, s));
+        return GELO_OK;
+    }
     if (m->k > 0) {
         GELO_HIP(ctx, row_norms(H, bf, ldh, m->n_data, m->d, m->rownorm, s));
         GELO_HIP(ctx, norm_statistic(m->rownorm, m->n_data, (int)stat, m->stat + 2, s));
@@ -681,6 +706,73 @@ gelo_status gelo_mixing_info(gelo_ctx* ctx, const gelo_mixing* m, int* n_data, i
     if (dtype) *dtype = (gelo_dtype)m->dtype;
     if (kind) *kind = (gelo_kind)m->kind;
     return GELO_OK;
+}
+
+gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d, gelo_dtype dtype,
+                                     uint64_t first_batch_id, int count, gelo_mixing** out, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!out) return fail(ctx, GELO_EINVAL, "out is NULL");
+    if (count < 1 || count > GELO_MAX_BATCH_DRAW) return fail(ctx, GELO_EINVAL, "count=%d outside 1..%d", count, GELO_MAX_BATCH_DRAW);
+    for (int i = 0; i < count; ++i) out[i] = nullptr;
+    if (kind != GELO_ORTHOGONAL) return fail(ctx, GELO_EINVAL, "batched draws exist for GELO_ORTHOGONAL only");
+    if (first_batch_id > UINT64_MAX - (uint64_t)count) return fail(ctx, GELO_EINVAL, "batch ids leave 64 bits");
+    int n = 0;
+    for (int i = 0; i < count; ++i) {
+        gelo_status st = check_sample_args(ctx, kind, n_data, k_shield, d, dtype, 1.0, 1, first_batch_id + (uint64_t)i, &n);
+        if (st != GELO_OK) return st;
+    }
+    if (n > GELO_STATIC_MAX_N) return fail(ctx, GELO_ESHAPE, "batched draws take n <= %d (n = %d)", GELO_STATIC_MAX_N, n);
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    SmallSampleTargets t;
+    gelo_mixing* got[GELO_MAX_BATCH_DRAW];
+    int have = 0;
+    gelo_status st = GELO_OK;
+    for (int i = 0; i < count && st == GELO_OK; ++i) {
+        gelo_mixing* m = nullptr;
+        st = acquire_mixing(ctx, n_data, k_shield, d, dtype, false, &m);
+        if (st != GELO_OK) break;
+        if (m->last_stream != nullptr || m->mixed) {
+            hipError_t e = hipStreamWaitEvent(s, m->released, 0);
+            if (e != hipSuccess) { st = hip_fail(ctx, e, "hipStreamWaitEvent"); break; }
+        }
+        m->in_use = true;                        // so that the next acquire takes another object
+        got[have++] = m;
+        t.block[i] = m->block;
+    }
+    if (st == GELO_OK) {
+        small_targets_layout(got[0], &t);
+        PhiloxStream ps;
+        ps.key0 = (uint32_t)ctx->seed; ps.key1 = (uint32_t)(ctx->seed >> 32);
+        ps.c1 = kStreamMixing << 8; ps.c2 = ps.c3 = 0;
+        hipError_t e = small_sample(t, count, first_batch_id, ps, kStreamShield << 8, n, k_shield, d, got[0]->ldk, s);
+        if (e != hipSuccess) st = hip_fail(ctx, e, "small_sample");
+    }
+    if (st != GELO_OK) {
+        for (int i = 0; i < have; ++i) got[i]->in_use = false;
+        return st;
+    }
+    for (int i = 0; i < count; ++i) {
+        gelo_mixing* m = got[i];
+        m->kind = kind; m->attempt = 0; m->kappa = 1.0f; m->batch_id = first_batch_id + (uint64_t)i;
+        m->mixed = false; m->consumed = false; m->sample_stream = s; m->last_stream = s;
+        hipError_t e = hipEventRecord(m->ready, s);
+        if (e != hipSuccess) return hip_fail(ctx, e, "hipEventRecord");
+        batch_commit(ctx, m->batch_id);
+        out[i] = m;
+    }
+    return GELO_OK;
+}
+
+gelo_status gelo_chain(gelo_ctx* ctx, gelo_mixing* m, gelo_dtype dtype, int p, const void* H, const void* W, float shield_scale,
+                       gelo_norm_stat stat, void* Z, void* U, void* Y, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!m || !owns(ctx, m) || !m->in_use) return fail(ctx, GELO_EINVAL, "mixing object is NULL, foreign or freed");
+    if (!U || !Y) return fail(ctx, GELO_EINVAL, "U and Y must not be NULL");
+    gelo_status st = gelo_mix(ctx, m, dtype, H, m->d, shield_scale, stat, U, m->d, stream);
+    if (st == GELO_OK) st = gelo_project(ctx, dtype, m->n, m->d, p, U, m->d, W, p, Y, p, stream);
+    if (st == GELO_OK) st = gelo_unmix(ctx, m, dtype, p, Y, p, Z, p, stream);
+    return st;
 }
 
 gelo_status gelo_mixing_free(gelo_ctx* ctx, gelo_mixing* m) {

@@ -68,6 +68,40 @@ __device__ __forceinline__ void philox4x32_10(uint32_t& c0, uint32_t& c1, uint32
         k1 += 0xBB67AE85u;
     }
 }
+// top 23 bits of a word -> (2 m + 1) 2^-24: exact in float, strictly inside (0, 1)
+__device__ __forceinline__ float uniform_open01(uint32_t w) {
+    return (float)(2u * (w >> 9) + 1u) * 5.9604644775390625e-08f;
+}
+// Box-Muller: two N(0, 1) values from two words
+__device__ __forceinline__ void box_muller(uint32_t wa, uint32_t wb, float* z0, float* z1) {
+    const float radius = sqrtf(-2.0f * logf(uniform_open01(wa)));
+    float s, c;
+    sincospif(2.0f * uniform_open01(wb), &s, &c);
+    *z0 = radius * c;
+    *z1 = radius * s;
+}
+// Row i of the k x d shield directions (row-major, pitch d, element e = i d + c is output e % 4 of Philox block
+// e / 4) and its norm, by one 256-thread workgroup; wave_part: 4 floats of LDS.  Partial sums of squares are
+// added in a fixed order (lanes by halving, then the four waves in turn).
+__device__ __forceinline__ void shield_direction_row(float* GS, int d, int i, PhiloxStream ps, float* gsnorm, float* wave_part) {
+    const int tid = threadIdx.x;
+    const int quads = d / 4;                                  // d is a multiple of 8
+    float ss = 0.f;
+    for (int ql = tid; ql < quads; ql += 256) {
+        uint32_t c0 = (uint32_t)(i * quads + ql), c1 = ps.c1, c2 = ps.c2, c3 = ps.c3;
+        philox4x32_10(c0, c1, c2, c3, ps.key0, ps.key1);
+        float4 z;
+        box_muller(c0, c1, &z.x, &z.y);
+        box_muller(c2, c3, &z.z, &z.w);
+        *reinterpret_cast<float4*>(GS + (int64_t)i * d + 4 * ql) = z;
+        ss = fmaf(z.x, z.x, ss); ss = fmaf(z.y, z.y, ss); ss = fmaf(z.z, z.z, ss); ss = fmaf(z.w, z.w, ss);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if ((tid & 63) == 0) wave_part[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) gsnorm[i] = sqrtf(((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3]);
+}
 // The QR works on 16 x 16 tiles: a tile is 256 contiguous floats ordered [column in tile][row in
 // tile], tiles are ordered column-block major; element (r, c) of a matrix with `tile_rows` tile
 // rows sits at the index below.  A wave that owns a tile in the accumulator layout of
@@ -108,6 +142,27 @@ hipError_t emit_matrix(const float* src, int64_t lds, int src_tiled, const float
 // dense float copy out[r * cols + c] = (float) src[r * ld + c]
 hipError_t export_dense(const void* src, int is_bf16, int64_t ld, int rows, int cols, float* out,
                         hipStream_t stream);
+
+// ------------------------------------------- decode-shaped batches (n <= 128) --
+constexpr int kSmallMaxN = 128;      // one workgroup holds [G | I] (n x 2 n floats) in LDS up to this n
+constexpr int kSmallMaxBatch = 48;   // mixing objects one launch of small_sample draws
+// Buffers of the mixing objects a batched draw fills, all of one shape: the same offsets into each block.
+struct SmallSampleTargets {
+    void* block[kSmallMaxBatch];
+    int64_t off_A32, off_Ainv32, off_A16, off_Ainv16, off_GS, off_gsnorm;    // off_A16 < 0: no bf16 copies
+};
+// For item i < count: batch id = first_batch + i; A = Q diag(sign r_ii) of the Householder QR of its n x n Philox
+// Gaussian (stream c1 of ps; ps.c2 / ps.c3 are ignored), written with its transpose (float, and bf16 if wanted;
+// ldk elements per row, zero beyond column n), and the k x d shield directions with their norms (stream c1_shield).
+// One launch: a workgroup per matrix and one per shield row.  n <= kSmallMaxN, count <= kSmallMaxBatch.
+hipError_t small_sample(const SmallSampleTargets& t, int count, uint64_t first_batch, PhiloxStream ps, uint32_t c1_shield,
+                        int n, int k, int d, int64_t ldk, hipStream_t stream);
+hipError_t small_init();
+// bf16, n <= kSmallMaxN: shield rows and U = A [H ; S] in one launch.  rownorm: the n_data row norms of H (ignored
+// when k == 0); stat_kind 0 median / 1 mean; S (k x d bf16, pitch d) is written too.  d % 8 == 0.
+hipError_t small_mix(const uint16_t* A16, int64_t ldk, const uint16_t* H, int64_t ldh, const float* GS, const float* gsnorm,
+                     const float* rownorm, int stat_kind, float shield_scale, int n_data, int k, int d,
+                     uint16_t* S, uint16_t* U, int64_t ldu, hipStream_t stream);
 
 // ------------------------------------------------- structured orthogonal A --
 constexpr int kStructuredRounds = 3;

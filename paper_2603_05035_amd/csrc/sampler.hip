@@ -7,19 +7,6 @@
 namespace gelo {
 namespace {
 
-// top 23 bits -> (2m + 1) 2^-24, exact in float, strictly inside (0, 1)
-__device__ __forceinline__ float uniform_open01(uint32_t w) {
-    return (float)(2u * (w >> 9) + 1u) * 5.9604644775390625e-08f;
-}
-
-__device__ __forceinline__ void box_muller(uint32_t wa, uint32_t wb, float* z0, float* z1) {
-    const float radius = sqrtf(-2.0f * logf(uniform_open01(wa)));
-    float s, c;
-    sincospif(2.0f * uniform_open01(wb), &s, &c);
-    *z0 = radius * c;
-    *z1 = radius * s;
-}
-
 __global__ __launch_bounds__(256)
 void fill_normal_kernel(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale, int tiled) {
     const int64_t total = (int64_t)rows * cols;
@@ -55,23 +42,7 @@ void philox_words_kernel(uint32_t* words, uint32_t first, uint32_t blocks, Philo
 __global__ __launch_bounds__(256)
 void shield_directions_kernel(float* GS, int d, PhiloxStream ps, float* gsnorm) {
     __shared__ float wave_part[4];
-    const int i = blockIdx.x, tid = threadIdx.x;
-    const int quads = d / 4;                                  // d is a multiple of 8
-    float ss = 0.f;
-    for (int ql = tid; ql < quads; ql += 256) {
-        uint32_t c0 = (uint32_t)(i * quads + ql), c1 = ps.c1, c2 = ps.c2, c3 = ps.c3;
-        philox4x32_10(c0, c1, c2, c3, ps.key0, ps.key1);
-        float4 z;
-        box_muller(c0, c1, &z.x, &z.y);
-        box_muller(c2, c3, &z.z, &z.w);
-        *reinterpret_cast<float4*>(GS + (int64_t)i * d + 4 * ql) = z;
-        ss = fmaf(z.x, z.x, ss); ss = fmaf(z.y, z.y, ss); ss = fmaf(z.z, z.z, ss); ss = fmaf(z.w, z.w, ss);
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
-    if ((tid & 63) == 0) wave_part[tid >> 6] = ss;
-    __syncthreads();
-    if (tid == 0) gsnorm[i] = sqrtf(((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3]);
+    shield_direction_row(GS, d, blockIdx.x, ps, gsnorm, wave_part);
 }
 
 __global__ __launch_bounds__(256)

@@ -161,8 +161,9 @@ def test_condition_bound_is_verified_with_a_guard_band(ctx):
         g.gelo_destroy(c2)
 
 
-@pytest.mark.parametrize("n_data,k", [(16, 2), (1, 0), (1, 1), (15, 0), (16, 0), (17, 3), (130, 20), (300, 0),
-                                      (1000, 30), (1300, 11)])
+@pytest.mark.parametrize("n_data,k", [(16, 2), (1, 0), (1, 1), (2, 0), (3, 1), (15, 0), (16, 0), (17, 3), (64, 4), (70, 1),
+                                      (100, 27), (120, 8),          # up to n = 128: one workgroup, matrix in LDS
+                                      (125, 4), (130, 20), (300, 0), (1000, 30), (1300, 11)])
 def test_orthogonal_mixing_matrix(ctx, n_data, k):
     n = n_data + k
     bid = 2000 + n * 7 + k
@@ -222,6 +223,71 @@ def test_conditioned_inverse_at_the_largest_n(ctx):
     kappa_ref = sigma_max(Ad) * sigma_max(Bd)
     assert 1.5 < kappa < 4.0
     assert abs(kappa - kappa_ref) / kappa_ref < 0.05
+
+
+def test_batched_draw_equals_single_draws(ctx):
+    """A decode step's mixing objects from one launch: object i is, bit for bit, what gelo_sample_mixing returns for
+    batch id first + i - A, A^-1, and (through a mix of the same H) the shield rows and U."""
+    nd, k, d = 64, 4, 512
+    first, count = 640, 32
+    H = dev(wl.make_hidden(nd, d, 77, 4), "bf16")
+    single = g.gelo_create(0, 0xC0FFEE, allow_batch_reuse=False)
+    try:
+        ms = g.gelo_sample_mixing_batch(ctx, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, first, count)
+        assert len(ms) == count
+        for i in (0, 1, 17, 31):
+            m1 = g.gelo_sample_mixing(single, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=first + i)
+            U0 = torch.empty((nd + k, d), dtype=torch.bfloat16, device="cuda")
+            U1 = torch.empty_like(U0)
+            g.gelo_mix(ctx, ms[i], H, U0)
+            g.gelo_mix(single, m1, H, U1)
+            A0, Ai0, S0, _, _ = g.gelo_mixing_export(ctx, ms[i], nd + k, k, d)
+            A1, Ai1, S1, _, _ = g.gelo_mixing_export(single, m1, nd + k, k, d)
+            torch.cuda.synchronize()
+            assert torch.equal(A0, A1) and torch.equal(Ai0, Ai1) and torch.equal(S0, S1) and torch.equal(U0, U1)
+            g.gelo_mixing_free(single, m1)
+            if i == 17:
+                check_orthogonal_A(f64(A0), 0xC0FFEE, first + i, nd + k, compare_elements=True)
+        for m in ms:
+            g.gelo_mixing_free(ctx, m)
+        # the ids of the batch are consumed, one by one
+        with pytest.raises(g.GeloError) as e:
+            g.gelo_sample_mixing(ctx, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=first + 5)
+        assert g.STATUS_NAMES[e.value.status] == "GELO_EREUSE"
+        with pytest.raises(g.GeloError) as e:
+            g.gelo_sample_mixing_batch(ctx, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, first + count - 1, 4)
+        assert g.STATUS_NAMES[e.value.status] == "GELO_EREUSE"
+        with pytest.raises(g.GeloError) as e:
+            g.gelo_sample_mixing_batch(ctx, g.GELO_ORTHOGONAL, 200, 0, d, g.GELO_BF16, 5000, 4)
+        assert g.STATUS_NAMES[e.value.status] == "GELO_ESHAPE"
+    finally:
+        g.gelo_destroy(single)
+
+
+def test_chain_call_equals_the_three_calls(ctx):
+    nd, k, d, p = 64, 4, 4096, 12288
+    H = dev(wl.make_hidden(nd, d, 5, 8), "bf16")
+    W = dev(wl.make_weight(d, p, 6), "bf16")
+    c2 = g.gelo_create(0, 0xC0FFEE, allow_batch_reuse=False)
+    try:
+        out = []
+        for c, fused in ((ctx, True), (c2, False)):
+            m = g.gelo_sample_mixing(c, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=3)
+            U = torch.empty((nd + k, d), dtype=torch.bfloat16, device="cuda")
+            Y = torch.empty((nd + k, p), dtype=torch.bfloat16, device="cuda")
+            Z = torch.empty((nd, p), dtype=torch.bfloat16, device="cuda")
+            if fused:
+                g.gelo_chain(c, m, H, W, Z, U, Y)
+            else:
+                g.gelo_mix(c, m, H, U); g.gelo_project(c, U, W, Y); g.gelo_unmix(c, m, Y, Z)
+            torch.cuda.synchronize()
+            g.gelo_mixing_free(c, m)
+            out.append((U, Y, Z))
+        for a, b in zip(*out):
+            assert torch.equal(a, b)
+        assert o.rel_frobenius(f64(out[0][2]), o.plain_projection(f64(H), f64(W))) < TOL_END["bf16"]
+    finally:
+        g.gelo_destroy(c2)
 
 
 def test_fresh_per_batch_and_deterministic(ctx):
