@@ -92,44 +92,85 @@ def run_composite(args, torch, np, g, wl):
         return (U[:w.n * w.d].view(w.n, w.d), Y[:w.n * w.p].view(w.n, w.p), Z[:w.n_data * w.p].view(w.n_data, w.p))
 
     depth = args.pipeline
-    side = [torch.cuda.Stream() for _ in range(depth)]
-    ctxs = [g.gelo_create(0, 0xBE00 + i, allow_batch_reuse=False) for i in range(depth)]
-    for c in ctxs:                                   # sizes known ahead: nothing allocates inside the timed region
-        for w in {(w.kind, w.n_data, w.k_shield, w.d): w for w in parts}.values():
-            g.gelo_reserve(c, w.kind, g.GELO_BF16, w.n_data, w.k_shield, w.d, 0, 64, 1)
-    ring = [None] * depth
-    counter = [0]                                    # chains issued so far; batch id = step * L + layer
+    decode = parts[0].n <= 128
+    if decode:
+        # Decode step: the mixing objects of a whole step (one per layer) come from ONE launch on a side stream, a step
+        # ahead of the chains that consume them; a chain is one host call (mix + project + unmix).
+        depth = 2
+        side = [torch.cuda.Stream() for _ in range(depth)]
+        ctxs = [g.gelo_create(0, 0xBE00 + i, allow_batch_reuse=False) for i in range(depth)]
+        w0 = parts[0]
+        for c in ctxs:
+            g.gelo_reserve(c, w0.kind, g.GELO_BF16, w0.n_data, w0.k_shield, w0.d, 0, 64, L)
+        ring = [None] * depth
 
-    def draw(slot, idx):
-        w = parts[idx % L]
-        ring[slot] = (g.gelo_sample_mixing(ctxs[slot], w.kind, w.n_data, w.k_shield, w.d, g.GELO_BF16, w.cond_max, 64,
-                                           idx, stream=side[slot]), idx)
+        def draw_step(step):
+            slot = step % depth
+            ring[slot] = g.gelo_sample_mixing_batch(ctxs[slot], w0.kind, w0.n_data, w0.k_shield, w0.d, g.GELO_BF16,
+                                                    step * L, L, stream=side[slot])
 
-    def chain(i):
-        slot = i % depth
-        m, idx = ring[slot]
-        l = idx % L
-        w = parts[l]
-        u, y, z = views(w)
-        g.gelo_mix(ctxs[slot], m, Hs[l], u, w.shield_scale)
-        g.gelo_project(ctxs[slot], u, Ws[l], y)
-        g.gelo_unmix(ctxs[slot], m, y, z)
-        g.gelo_mixing_free(ctxs[slot], m)
-        draw(slot, idx + depth)
+        def run_step(step):
+            slot = step % depth
+            ms = ring[slot]
+            u, y, z = views(w0)
+            for l in range(L):
+                g.gelo_chain(ctxs[slot], ms[l], Hs[l], Ws[l], z, u, y, w0.shield_scale)
+                g.gelo_mixing_free(ctxs[slot], ms[l])
+            draw_step(step + depth)
 
-    for slot in range(depth):
-        draw(slot, slot)
-    i = 0
-    for _ in range(Wm * L):
-        chain(i); i += 1
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(K * L):
-        chain(i); i += 1
-    torch.cuda.synchronize()
-    t_step = (time.perf_counter() - t0) / K
-    for slot in range(depth):
-        g.gelo_mixing_free(ctxs[slot], ring[slot][0])
+        for st_ in range(depth):
+            draw_step(st_)
+        step = 0
+        for _ in range(Wm):
+            run_step(step); step += 1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            run_step(step); step += 1
+        torch.cuda.synchronize()
+        t_step = (time.perf_counter() - t0) / K
+        for slot in range(depth):
+            for m in ring[slot]:
+                g.gelo_mixing_free(ctxs[slot], m)
+        i = (step + depth) * L
+    else:
+        side = [torch.cuda.Stream() for _ in range(depth)]
+        ctxs = [g.gelo_create(0, 0xBE00 + i, allow_batch_reuse=False) for i in range(depth)]
+        for c in ctxs:                                   # sizes known ahead: nothing allocates inside the timed region
+            for w in {(w.kind, w.n_data, w.k_shield, w.d): w for w in parts}.values():
+                g.gelo_reserve(c, w.kind, g.GELO_BF16, w.n_data, w.k_shield, w.d, 0, 64, 1)
+        ring = [None] * depth
+
+        def draw(slot, idx):
+            w = parts[idx % L]
+            ring[slot] = (g.gelo_sample_mixing(ctxs[slot], w.kind, w.n_data, w.k_shield, w.d, g.GELO_BF16, w.cond_max, 64,
+                                               idx, stream=side[slot]), idx)
+
+        def chain(i):
+            slot = i % depth
+            m, idx = ring[slot]
+            l = idx % L
+            w = parts[l]
+            u, y, z = views(w)
+            g.gelo_mix(ctxs[slot], m, Hs[l], u, w.shield_scale)
+            g.gelo_project(ctxs[slot], u, Ws[l], y)
+            g.gelo_unmix(ctxs[slot], m, y, z)
+            g.gelo_mixing_free(ctxs[slot], m)
+            draw(slot, idx + depth)
+
+        for slot in range(depth):
+            draw(slot, slot)
+        i = 0
+        for _ in range(Wm * L):
+            chain(i); i += 1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K * L):
+            chain(i); i += 1
+        torch.cuda.synchronize()
+        t_step = (time.perf_counter() - t0) / K
+        for slot in range(depth):
+            g.gelo_mixing_free(ctxs[slot], ring[slot][0])
 
     # serial: the same chains through gelo_qkv_forward on one stream, nothing overlapped
     ctx = ctxs[0]
@@ -196,7 +237,6 @@ def run_composite(args, torch, np, g, wl):
     f_gen = sum(gen_flops(w) for w in parts)
     f_plain = sum(2.0 * w.n_data * w.d * w.p for w in parts)
     peak = PEAK_TFLOPS["bf16"]
-    decode = parts[0].n <= 128
     result = {
         "metric": "GELO QKV-forward TFLOP/s (whole step: A generation + shields + mix + project + unmix)",
         "value": (f_chain + f_gen) / t_step / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -222,6 +262,14 @@ def run_composite(args, torch, np, g, wl):
                               "peak": 8000.0, "unit": "GB/s", "frac": b_proj / t_proj / 1e9 / 8000.0, "traffic": None,
                               "avg_launch_us": t_proj * 1e6}
         result["w_stream_floor_us_per_chain"] = 2.0 * w0.d * w0.p / 8e12 * 1e6
+        # HBM rate of the two small-n mixing calls (algorithmic bytes of eq. 1 / eq. 3: operands read once, result written once)
+        st0 = stages[0]
+        b_mix = 2.0 * (w0.n * w0.n + w0.n_data * w0.d + w0.k_shield * w0.d + w0.n * w0.d)
+        b_unmix = 2.0 * (w0.n_data * w0.n + w0.n * w0.p + w0.n_data * w0.p)
+        result["small_n_mixing"] = {"sample_us": st0["sample"] * 1e3, "mix_us": st0["mix"] * 1e3, "unmix_us": st0["unmix"] * 1e3,
+                                    "mix_GBps": b_mix / (st0["mix"] * 1e-3) / 1e9, "unmix_GBps": b_unmix / (st0["unmix"] * 1e-3) / 1e9,
+                                    "peak_GBps": 8000.0,
+                                    "note": "one draw alone costs sample_us; a decode step draws its 32 in one launch, a step ahead"}
     else:
         f_proj = 2.0 * w0.n * w0.d * w0.p
         result["roofline"] = {"kernel": "gemm (project Y = U W) of the step's first chain", "bound": "mfma", "achieved": f_proj / t_proj / 1e12,

@@ -70,7 +70,8 @@ void row_norms_kernel(const void* X, int64_t ld, int rows, int cols, float* norm
     float s = 0.f;
     if (BF16) {
         const uint16_t* p = (const uint16_t*)X + (int64_t)row * ld;
-        for (int c = lane * 8; c < cols; c += 64 * 8) {
+#pragma unroll 8
+        for (int c = lane * 8; c < cols; c += 64 * 8) {          // unrolled: the loads of eight steps fly together
             const uint4 v = *reinterpret_cast<const uint4*>(p + c);
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -82,6 +83,7 @@ void row_norms_kernel(const void* X, int64_t ld, int rows, int cols, float* norm
         }
     } else {
         const float* p = (const float*)X + (int64_t)row * ld;
+#pragma unroll 8
         for (int c = lane * 4; c < cols; c += 64 * 4) {
             const float4 v = *reinterpret_cast<const float4*>(p + c);
             s = fmaf(v.x, v.x, s); s = fmaf(v.y, v.y, s); s = fmaf(v.z, v.z, s); s = fmaf(v.w, v.w, s);

@@ -86,41 +86,59 @@ void small_sample_kernel(SmallSampleArgs a) {
             const float alpha = piv[j];
             const float top = mine[j];
             const int r0 = (j + 1) & ~3;
-            float s = 0.f, q = 0.f;
-            for (int r = r0; r < n; r += 4) {
-                f32x4_t x = *reinterpret_cast<const f32x4_t*>(piv + r);
+            // four independent partial sums each, and the loop unrolled: a lone wave per SIMD has nothing else to hide
+            // the LDS latency behind
+            f32x4_t sp = {0.f, 0.f, 0.f, 0.f}, qp = {0.f, 0.f, 0.f, 0.f};
+            {
+                // only the first chunk can reach above the tail
+                f32x4_t x = *reinterpret_cast<const f32x4_t*>(piv + r0);
+                const f32x4_t y = *reinterpret_cast<const f32x4_t*>(mine + r0);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float xt = r0 + t > j ? x[t] : 0.f;
+                    sp[t] = xt * y[t];
+                    qp[t] = xt * xt;
+                }
+            }
+#pragma unroll 4
+            for (int r = r0 + 4; r < n; r += 4) {
+                const f32x4_t x = *reinterpret_cast<const f32x4_t*>(piv + r);
                 const f32x4_t y = *reinterpret_cast<const f32x4_t*>(mine + r);
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const float xt = r + t > j ? x[t] : 0.f;           // only the first chunk can reach above the tail
-                    s = fmaf(xt, y[t], s);
-                    q = fmaf(xt, xt, q);
+                    sp[t] = fmaf(x[t], y[t], sp[t]);
+                    qp[t] = fmaf(x[t], x[t], qp[t]);
                 }
             }
+            const float s = (sp[0] + sp[1]) + (sp[2] + sp[3]);
+            const float q = (qp[0] + qp[1]) + (qp[2] + qp[3]);
             // beta = -sign(alpha) sqrt(alpha^2 + |x|^2), tau = (beta - alpha) / beta, v = x / (alpha - beta) below a
             // unit entry; a zero tail gives the identity (tau = 0)
             const bool tail = q > 0.f;
-            const float nrm = sqrtf(fmaf(alpha, alpha, q));
+            const float nrm = __builtin_amdgcn_sqrtf(fmaf(alpha, alpha, q));
             const float beta = tail ? -copysignf(nrm, alpha) : alpha;
-            const float tau = tail ? (beta - alpha) / beta : 0.f;
-            const float scale = tail ? 1.0f / (alpha - beta) : 0.f;
+            const float tau = tail ? (beta - alpha) * __builtin_amdgcn_rcpf(beta) : 0.f;      // hardware reciprocals (1 ulp), as in the
+            const float scale = tail ? __builtin_amdgcn_rcpf(alpha - beta) : 0.f;             // panel kernel of the blocked QR
             const float w = fmaf(scale, s, top);                       // v^T (column c)
             const float tw = tau * w;
             mine[j] = top - tw;
             const float f = tw * scale;
-            for (int r = r0; r < n; r += 4) {
+            {
+                const f32x4_t x = *reinterpret_cast<const f32x4_t*>(piv + r0);
+                f32x4_t y = *reinterpret_cast<const f32x4_t*>(mine + r0);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) y[t] = r0 + t > j ? fmaf(-f, x[t], y[t]) : y[t];
+                *reinterpret_cast<f32x4_t*>(mine + r0) = y;
+            }
+#pragma unroll 4
+            for (int r = r0 + 4; r < n; r += 4) {
                 const f32x4_t x = *reinterpret_cast<const f32x4_t*>(piv + r);
                 f32x4_t y = *reinterpret_cast<const f32x4_t*>(mine + r);
 #pragma unroll
-                for (int t = 0; t < 4; ++t) y[t] = r + t > j ? fmaf(-f, x[t], y[t]) : y[t];
+                for (int t = 0; t < 4; ++t) y[t] = fmaf(-f, x[t], y[t]);
                 *reinterpret_cast<f32x4_t*>(mine + r) = y;
             }
-        } else if (c == j) {
-            // the diagonal of R: this column's own reflector turns (alpha, x) into (beta, 0)
-            const float alpha = mine[j];
-            float q = 0.f;
-            for (int r = j + 1; r < n; ++r) q = fmaf(mine[r], mine[r], q);
-            rdiag[j] = q > 0.f ? -copysignf(sqrtf(fmaf(alpha, alpha, q)), alpha) : alpha;
+            if (c == j + 1) rdiag[j] = beta;                           // the diagonal of R: (alpha, x) becomes (beta, 0)
         }
         __syncthreads();
     }
@@ -175,21 +193,52 @@ void small_mix_kernel(SmallMixArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = a.n_data + a.k, c0 = blockIdx.x * MIX_BN;
     const int kp = (n + 15) & ~15;
+    const int j = lane & 31, grp = lane >> 5;
+
+    // Every load from memory is issued before anything waits: the kernel is a chain of a few dependent steps, and
+    // one memory latency per step would be most of its run time.
+    const float my_norm = (a.k > 0 && tid < a.n_data) ? a.rownorm[tid] : 0.f;
+    const float my_gsnorm = tid < a.k ? a.gsnorm[tid] : 1.f;
+    constexpr int HR = kSmallMaxN * (MIX_BN / 8) / 256;          // 16-byte chunks of H per thread: at most 4
+    u32x4_t hreg[HR];
+#pragma unroll
+    for (int it = 0; it < HR; ++it) {
+        const int i = tid + it * 256;
+        const int r = i >> 3, col = c0 + (i & 7) * 8;
+        hreg[it] = u32x4_t{0u, 0u, 0u, 0u};
+        if (r < a.n_data && col < a.d) hreg[it] = *reinterpret_cast<const u32x4_t*>(a.H + (int64_t)r * a.ldh + col);
+    }
+    constexpr int GR = 4;                                        // shield values per thread held in registers (k <= 16)
+    float gsv[GR];
+#pragma unroll
+    for (int it = 0; it < GR; ++it) {
+        const int i = tid + it * 256;
+        const int r = i / MIX_BN, col = c0 + (i - r * MIX_BN);
+        gsv[it] = (r < a.k && col < a.d) ? a.GS[(int64_t)r * a.d + col] : 0.f;
+    }
+    bf16x8_t af[kSmallMaxN / 16];
+    {
+        int arow = wave * 32 + j; arow = arow < n ? arow : n - 1;
+        const uint16_t* ap = a.A16 + (int64_t)arow * a.ldk + grp * 8;
+#pragma unroll
+        for (int ks = 0; ks < kSmallMaxN / 16; ++ks)
+            if (ks * 16 < kp && wave * 32 < n) af[ks] = *reinterpret_cast<const bf16x8_t*>(ap + ks * 16);
+    }
 
     if (a.k > 0) {
-        if (tid < a.n_data) norms[tid] = a.rownorm[tid];
+        if (tid < a.n_data) norms[tid] = my_norm;
         __syncthreads();
         if (a.stat_kind == 0) {
             // median by rank: every value counts the (value, index) pairs below it; the two of middle rank meet in the mean
             if (tid < a.n_data) {
-                const uint32_t mine = __float_as_uint(norms[tid]);
+                const uint32_t mine = __float_as_uint(my_norm);
                 int below = 0;
                 for (int i = 0; i < a.n_data; ++i) {
                     const uint32_t o = __float_as_uint(norms[i]);
                     below += (o < mine || (o == mine && i < tid)) ? 1 : 0;
                 }
-                if (below == (a.n_data - 1) / 2) factor[0] = norms[tid];
-                if (below == a.n_data / 2) factor[1] = norms[tid];
+                if (below == (a.n_data - 1) / 2) factor[0] = my_norm;
+                if (below == a.n_data / 2) factor[1] = my_norm;
             }
             __syncthreads();
             if (tid == 0) stat_s = 0.5f * (factor[0] + factor[1]);
@@ -201,27 +250,31 @@ void small_mix_kernel(SmallMixArgs a) {
         __syncthreads();
         const float m = stat_s;
         __syncthreads();
-        if (tid < a.k) factor[tid] = a.shield_scale * m / a.gsnorm[tid];
+        if (tid < a.k) factor[tid] = a.shield_scale * m / my_gsnorm;
     }
     // zero the K padding of the tile, then fill it: rows of H as 16-byte chunks of 8 columns, shield rows scaled on the way
     for (int i = tid; i < MIX_BN * (MIX_KP / 2); i += 256) reinterpret_cast<uint32_t*>(Bt)[i] = 0u;
     __syncthreads();
-    for (int i = tid; i < a.n_data * (MIX_BN / 8); i += 256) {
-        const int r = i >> 3, ch = i & 7;
-        int col = c0 + ch * 8;
-        if (col >= a.d) continue;                               // d is a multiple of 8: a chunk is inside or outside
-        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(a.H + (int64_t)r * a.ldh + col);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            Bt[(ch * 8 + 2 * t) * MIX_KP + r] = (uint16_t)(v[t] & 0xFFFFu);
-            Bt[(ch * 8 + 2 * t + 1) * MIX_KP + r] = (uint16_t)(v[t] >> 16);
+    for (int it = 0; it < HR; ++it) {
+        const int i = tid + it * 256;
+        const int r = i >> 3, ch = i & 7;
+        if (r < a.n_data && c0 + ch * 8 < a.d) {                 // d is a multiple of 8: a chunk is inside or outside
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                Bt[(ch * 8 + 2 * t) * MIX_KP + r] = (uint16_t)(hreg[it][t] & 0xFFFFu);
+                Bt[(ch * 8 + 2 * t + 1) * MIX_KP + r] = (uint16_t)(hreg[it][t] >> 16);
+            }
         }
     }
-    for (int i = tid; i < a.k * MIX_BN; i += 256) {
+    for (int i = tid, it = 0; i < a.k * MIX_BN; i += 256, ++it) {
         const int r = i / MIX_BN, cc = i - r * MIX_BN;
         const int col = c0 + cc;
         if (col >= a.d) continue;
-        const __bf16 h = (__bf16)(a.GS[(int64_t)r * a.d + col] * factor[r]);
+        float gsx;
+        switch (it) { case 0: gsx = gsv[0]; break; case 1: gsx = gsv[1]; break; case 2: gsx = gsv[2]; break; case 3: gsx = gsv[3]; break;
+                      default: gsx = a.GS[(int64_t)r * a.d + col]; }
+        const __bf16 h = (__bf16)(gsx * factor[r]);
         const uint16_t bits = __builtin_bit_cast(uint16_t, h);
         a.S[(int64_t)r * a.d + col] = bits;
         Bt[cc * MIX_KP + a.n_data + r] = bits;
@@ -230,20 +283,19 @@ void small_mix_kernel(SmallMixArgs a) {
     if (wave * 32 >= n) return;
     // v_mfma_f32_32x32x16_bf16: lane l supplies row l % 32 of A and column l % 32 of B, contraction values
     // 8 (l / 32) .. + 7; it receives column l % 32, rows 8 (v / 4) + 4 (l / 32) + v % 4
-    const int j = lane & 31, grp = lane >> 5;
-    int arow = wave * 32 + j; arow = arow < n ? arow : n - 1;
-    const uint16_t* ap = a.A16 + (int64_t)arow * a.ldk + grp * 8;
     f32x16_t acc[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
-    for (int ks = 0; ks < kp; ks += 16) {
-        const bf16x8_t af = *reinterpret_cast<const bf16x8_t*>(ap + ks);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const bf16x8_t bf = *reinterpret_cast<const bf16x8_t*>(Bt + (t * 32 + j) * MIX_KP + ks + grp * 8);
-            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc[t], 0, 0, 0);
+    for (int ks = 0; ks < kSmallMaxN / 16; ++ks) {
+        if (ks * 16 < kp) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const bf16x8_t bf = *reinterpret_cast<const bf16x8_t*>(Bt + (t * 32 + j) * MIX_KP + ks * 16 + grp * 8);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks], bf, acc[t], 0, 0, 0);
+            }
         }
     }
 #pragma unroll
