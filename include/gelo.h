@@ -163,6 +163,22 @@ gelo_status gelo_project(gelo_ctx* ctx, gelo_dtype dtype, int n, int d, int p,
                          const void* U, int64_t ldu, const void* W, int64_t ldw,
                          void* Y, int64_t ldy, void* stream);
 
+/* Accelerator side, eq. 2 with both operands stored as 8-bit floats (OCP FP8 E4M3, the "FP8 / INT8 quantized
+ * numerics" of the paper's Conclusion): twice the matrix rate of the bf16 projection.  The weight is public and
+ * static, so it is prepared once: gelo_prepare_weight_fp8 writes into the caller's DEVICE buffer Wq
+ * (gelo_fp8_weight_bytes(d, p) bytes, 16-byte aligned) the codes of W^T (p x d bytes: code of
+ * W[k][j] * 448 / max_k |W[k][j]| at byte j d + k, round to nearest even, saturating at 448), padded to a
+ * multiple of 256 bytes, then the p column scales max_k |W[k][j]| / 448 as floats.  gelo_project_fp8 quantises
+ * U (bf16, n x d) per row the same way into context workspace (allocated on first use of a size), multiplies
+ * on the matrix cores with float accumulation and writes Y[i][j] = acc * su[i] * sw[j] as bf16.  d a multiple
+ * of 128 (GELO_ESHAPE otherwise), p a multiple of 8.  The rounding of U and W to 3 fraction bits (relative
+ * error 2^-4 per element at worst) reaches Z = A^-1 Y at about 4e-2 to 7e-2 relative Frobenius error with
+ * shield rows in the batch: this call does NOT meet the 2e-2 bound of the bf16 chain; mix and unmix stay bf16. */
+gelo_status gelo_fp8_weight_bytes(int d, int p, size_t* bytes);
+gelo_status gelo_prepare_weight_fp8(gelo_ctx* ctx, int d, int p, const void* W, int64_t ldw, void* Wq, void* stream);
+gelo_status gelo_project_fp8(gelo_ctx* ctx, int n, int d, int p, const void* U, int64_t ldu, const void* Wq,
+                             void* Y, int64_t ldy, void* stream);
+
 /* Trusted side, eq. 3 + shield drop.  Z[n_data x p] = (A^-1 * Y)[0:n_data, :]; the shield rows
  * of the product are never computed.  Y: n x p (ldy), Z: n_data x p (ldz), both of type `dtype`
  * (GELO_EDTYPE if it is not the mixing object's).  Marks the mixing consumed: a second
@@ -224,6 +240,10 @@ gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* mixing, float* 
 gelo_status gelo_debug_philox_words(gelo_ctx* ctx, uint32_t stream_id, uint32_t attempt, uint64_t batch_id,
                                     uint32_t first_block, uint32_t blocks, uint32_t* words, void* stream);
 gelo_status gelo_mixing_export_table(gelo_ctx* ctx, const gelo_mixing* mixing, uint32_t* table, void* stream);
+/* Test hook: the row quantisation gelo_project_fp8 applies to U, into caller DEVICE buffers: codes n x d bytes
+ * (16-byte aligned), scales n floats. */
+gelo_status gelo_debug_quantize_rows_fp8(gelo_ctx* ctx, int n, int d, const void* U, int64_t ldu, uint8_t* codes,
+                                         float* scales, void* stream);
 
 #ifdef __cplusplus
 }

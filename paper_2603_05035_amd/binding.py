@@ -48,6 +48,10 @@ SIGNATURES = {
                                  POINTER(c_int)]),
     "gelo_qkv_forward_static": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_float,
                                         c_int, c_uint64, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "gelo_fp8_weight_bytes": (c_int, [c_int, c_int, POINTER(ctypes.c_size_t)]),
+    "gelo_prepare_weight_fp8": (c_int, [c_void_p, c_int, c_int, c_void_p, c_int64, c_void_p, c_void_p]),
+    "gelo_project_fp8": (c_int, [c_void_p, c_int, c_int, c_int, c_void_p, c_int64, c_void_p, c_void_p, c_int64, c_void_p]),
+    "gelo_debug_quantize_rows_fp8": (c_int, [c_void_p, c_int, c_int, c_void_p, c_int64, c_void_p, c_void_p, c_void_p]),
     "gelo_debug_philox_words": (c_int, [c_void_p, c_uint32, c_uint32, c_uint64, c_uint32, c_uint32, c_void_p, c_void_p]),
     "gelo_mixing_export_table": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p]),
     "gelo_qkv_forward": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_float,
@@ -265,6 +269,48 @@ def gelo_get_batch_floor(ctx) -> int:
     v = c_uint64()
     _check(ctx, load_library().gelo_get_batch_floor(ctx, byref(v)))
     return v.value
+
+
+def gelo_fp8_weight_bytes(d: int, p: int) -> int:
+    v = ctypes.c_size_t()
+    st = load_library().gelo_fp8_weight_bytes(d, p, byref(v))
+    if st != GELO_OK:
+        raise GeloError(st, "gelo_fp8_weight_bytes")
+    return v.value
+
+
+def gelo_prepare_weight_fp8(ctx, W: torch.Tensor, stream=None) -> torch.Tensor:
+    """The FP8 form of a bf16 weight (d x p): a uint8 device buffer holding the codes of W^T and the column scales."""
+    if W.dtype != torch.bfloat16:
+        raise TypeError("the 8-bit projection takes a bf16 weight")
+    wp, ldw = _matrix(W, "W")
+    d, p = W.shape
+    Wq = torch.empty(gelo_fp8_weight_bytes(d, p), dtype=torch.uint8, device="cuda")
+    _check(ctx, load_library().gelo_prepare_weight_fp8(ctx, d, p, wp, ldw, c_void_p(Wq.data_ptr()), _stream(stream)))
+    return Wq
+
+
+def gelo_project_fp8(ctx, U: torch.Tensor, Wq: torch.Tensor, p: int, Y: torch.Tensor, stream=None) -> torch.Tensor:
+    up, ldu = _matrix(U, "U")
+    yp, ldy = _matrix(Y, "Y")
+    n, d = U.shape
+    if U.dtype != torch.bfloat16 or Y.dtype != torch.bfloat16 or tuple(Y.shape) != (n, p):
+        raise ValueError("U and Y must be bf16, Y n x p")
+    if Wq.dtype != torch.uint8 or Wq.numel() != gelo_fp8_weight_bytes(d, p):
+        raise GeloError(2, "Wq is not the prepared form of a d x p weight")
+    _check(ctx, load_library().gelo_project_fp8(ctx, n, d, p, up, ldu, c_void_p(Wq.data_ptr()), yp, ldy, _stream(stream)))
+    return Y
+
+
+def gelo_debug_quantize_rows_fp8(ctx, U: torch.Tensor, stream=None):
+    """Test hook: (codes n x d uint8, scales n float32) of the row quantisation of U."""
+    up, ldu = _matrix(U, "U")
+    n, d = U.shape
+    codes = torch.empty((n, d), dtype=torch.uint8, device="cuda")
+    scales = torch.empty((n,), dtype=torch.float32, device="cuda")
+    _check(ctx, load_library().gelo_debug_quantize_rows_fp8(ctx, n, d, up, ldu, c_void_p(codes.data_ptr()),
+                                                            c_void_p(scales.data_ptr()), _stream(stream)))
+    return codes, scales
 
 
 def gelo_debug_philox_words(ctx, stream_id: int, attempt: int, batch_id: int, first_block: int, blocks: int,

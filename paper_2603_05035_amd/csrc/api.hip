@@ -82,6 +82,7 @@ struct gelo_ctx {
     std::string err;
     void* factor_ws; size_t factor_ws_bytes;
     void* chain_ws;  size_t chain_ws_bytes;
+    void* quant_ws;  size_t quant_ws_bytes;    // FP8 projection: codes and row scales of the current U
     float* host_scalars;         // pinned: kappa read-back, one slot per lane
     int* host_flag;
     std::vector<gelo_mixing*> pool;
@@ -307,6 +308,7 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
         if (device < kStaticMaxDevices) g_scratch_ptr[device] = ptr;
     }
     ctx->factor_ws = ctx->chain_ws = nullptr; ctx->factor_ws_bytes = ctx->chain_ws_bytes = 0;
+    ctx->quant_ws = nullptr; ctx->quant_ws_bytes = 0;
     ctx->host_scalars = nullptr; ctx->host_flag = nullptr;
     ctx->lanes_ready = false; ctx->join_pending = false; ctx->cand = nullptr; ctx->cand_bytes = 0;
     for (int i = 0; i < kLanes; ++i) ctx->lane_graph_ok[i] = false;
@@ -315,7 +317,7 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
     if (hipHostMalloc((void**)&ctx->host_scalars, 64, hipHostMallocDefault) != hipSuccess) { delete ctx; return GELO_ENOMEM; }
     ctx->host_flag = (int*)(ctx->host_scalars + 8);
     if (gemm_bf16_init() != hipSuccess || gemm_f32_init() != hipSuccess || lu_init() != hipSuccess ||
-        structured_init() != hipSuccess || small_init() != hipSuccess) {
+        structured_init() != hipSuccess || small_init() != hipSuccess || gemm_fp8_init() != hipSuccess) {
         hipHostFree(ctx->host_scalars); delete ctx; return GELO_EHIP;
     }
     *out = ctx;
@@ -339,6 +341,7 @@ gelo_status gelo_destroy(gelo_ctx* ctx) {
     if (ctx->cand) (void)hipFree(ctx->cand);
     if (ctx->factor_ws) (void)hipFree(ctx->factor_ws);
     if (ctx->chain_ws) (void)hipFree(ctx->chain_ws);
+    if (ctx->quant_ws) (void)hipFree(ctx->quant_ws);
     if (ctx->host_scalars) (void)hipHostFree(ctx->host_scalars);
     delete ctx;
     return GELO_OK;
@@ -965,6 +968,67 @@ gelo_status gelo_mixing_export_table(gelo_ctx* ctx, const gelo_mixing* m, uint32
     hipStream_t s = (hipStream_t)stream;
     if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
     GELO_HIP(ctx, hipMemcpyAsync(table, m->table, (size_t)(kStructuredRounds + 1) * m->n * sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
+    return GELO_OK;
+}
+
+gelo_status gelo_fp8_weight_bytes(int d, int p, size_t* bytes) {
+    if (!bytes || d < 1 || p < 1) return GELO_EINVAL;
+    *bytes = up256((size_t)p * d) + (size_t)p * sizeof(float);
+    return GELO_OK;
+}
+
+static gelo_status check_fp8_shape(gelo_ctx* ctx, int d, int p) {
+    if (d < 1 || p < 1) return fail(ctx, GELO_EINVAL, "d=%d p=%d", d, p);
+    if (d % 128 != 0) return fail(ctx, GELO_ESHAPE, "the 8-bit projection takes d a multiple of 128 (d = %d)", d);
+    if (p % 8 != 0) return fail(ctx, GELO_EALIGN, "p=%d is not a multiple of 8", p);
+    return GELO_OK;
+}
+
+gelo_status gelo_prepare_weight_fp8(gelo_ctx* ctx, int d, int p, const void* W, int64_t ldw, void* Wq, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    gelo_status st = check_fp8_shape(ctx, d, p);
+    if (st == GELO_OK) st = check_matrix(ctx, "W", W, ldw, p);
+    if (st != GELO_OK) return st;
+    if (!Wq || !aligned16(Wq)) return fail(ctx, Wq ? GELO_EALIGN : GELO_EINVAL, "Wq must be a 16-byte aligned device buffer");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    uint8_t* codes = (uint8_t*)Wq;
+    float* scale = (float*)(codes + up256((size_t)p * d));
+    GELO_HIP(ctx, quantize_weight_e4m3(W, ldw, d, p, codes, scale, (hipStream_t)stream));
+    return GELO_OK;
+}
+
+gelo_status gelo_project_fp8(gelo_ctx* ctx, int n, int d, int p, const void* U, int64_t ldu, const void* Wq,
+                             void* Y, int64_t ldy, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (n < 1) return fail(ctx, GELO_EINVAL, "n=%d", n);
+    gelo_status st = check_fp8_shape(ctx, d, p);
+    if (st == GELO_OK) st = check_matrix(ctx, "U", U, ldu, d);
+    if (st == GELO_OK) st = check_matrix(ctx, "Y", Y, ldy, p);
+    if (st != GELO_OK) return st;
+    if (!Wq || !aligned16(Wq)) return fail(ctx, Wq ? GELO_EALIGN : GELO_EINVAL, "Wq must be a 16-byte aligned device buffer");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    const size_t code_bytes = up256((size_t)n * d);
+    st = grow(ctx, &ctx->quant_ws, &ctx->quant_ws_bytes, code_bytes + up256((size_t)n * sizeof(float)));
+    if (st != GELO_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t* ucodes = (uint8_t*)ctx->quant_ws;
+    float* uscale = (float*)(ucodes + code_bytes);
+    const uint8_t* wcodes = (const uint8_t*)Wq;
+    const float* wscale = (const float*)(wcodes + up256((size_t)p * d));
+    GELO_HIP(ctx, quantize_rows_e4m3(U, ldu, n, d, ucodes, d, uscale, s));
+    GELO_HIP(ctx, gemm_fp8(ucodes, d, uscale, wcodes, d, wscale, Y, ldy, n, p, d, s));
+    return GELO_OK;
+}
+
+gelo_status gelo_debug_quantize_rows_fp8(gelo_ctx* ctx, int n, int d, const void* U, int64_t ldu, uint8_t* codes,
+                                         float* scales, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (n < 1 || d < 8 || d % 8 != 0) return fail(ctx, GELO_EINVAL, "n=%d d=%d", n, d);
+    gelo_status st = check_matrix(ctx, "U", U, ldu, d);
+    if (st != GELO_OK) return st;
+    if (!codes || !scales || !aligned16(codes)) return fail(ctx, GELO_EINVAL, "codes (16-byte aligned) and scales must be device buffers");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    GELO_HIP(ctx, quantize_rows_e4m3(U, ldu, n, d, codes, d, scales, (hipStream_t)stream));
     return GELO_OK;
 }
 

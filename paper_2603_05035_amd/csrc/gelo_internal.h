@@ -46,6 +46,18 @@ hipError_t gemm_bf16_init();        // one-time kernel attribute set-up (large d
 hipError_t gemm_f32_init();
 hipError_t lu_init();
 
+// 8-bit float projection (OCP FP8 E4M3 operands, float accumulation, bf16 result) --------------------------
+// codes[r][c] = e4m3(X[r][c] * 448 / max_c |X[r][c]|) (ldq bytes per row), scale[r] = max / 448 (1 for a zero row); X bf16
+hipError_t quantize_rows_e4m3(const void* X, int64_t ld, int rows, int cols, uint8_t* codes, int64_t ldq, float* scale,
+                              hipStream_t stream);
+// W (d x p bf16) -> codes[j][k] (p x d, the transpose) with one scale per column j of W; d a multiple of 128
+hipError_t quantize_weight_e4m3(const void* W, int64_t ldw, int d, int p, uint8_t* codes, float* scale, hipStream_t stream);
+// C[M x N] (bf16) = (A[M x K] . B[N x K]^T) * sa[i] * sb[j]; codes row-major with lda / ldb bytes per row (multiples of
+// 16, at least K), K a multiple of 128, N a multiple of 8; sb 16-byte aligned
+hipError_t gemm_fp8(const uint8_t* A, int64_t lda, const float* sa, const uint8_t* B, int64_t ldb, const float* sb,
+                    void* C, int64_t ldc, int M, int N, int K, hipStream_t stream);
+hipError_t gemm_fp8_init();
+
 // --------------------------------------------------------------- sampler ---
 struct PhiloxStream {
     uint32_t key0, key1;            // seed low / high
