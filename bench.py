@@ -311,8 +311,8 @@ def main() -> int:
                     help="also run a plain elementwise copy of known size (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     args.steps_given, args.warmup_given = args.steps is not None, args.warmup is not None
-    args.steps = 50 if args.steps is None else args.steps
-    args.warmup = 25 if args.warmup is None else args.warmup
+    args.steps = 48 if args.steps is None else args.steps
+    args.warmup = 16 if args.warmup is None else args.warmup
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this library runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
@@ -360,29 +360,61 @@ def main() -> int:
     # ---- whole step, pipelined: A does not depend on H, so the trusted side draws the mixing matrices
     # of the next batches on side streams (one context = one workspace per stream) while the chain of
     # the current batch runs.  Every timed step still generates one fresh A and consumes one.
-    depth = args.pipeline
     main = torch.cuda.current_stream()
-    side = [torch.cuda.Stream() for _ in range(depth)]
-    ctxs = [g.gelo_create(0, w.seed + 1 + i, allow_batch_reuse=False) for i in range(depth)]
-    ring = [None] * depth
     bid = [0]
+    if w.kind == g.GELO_ORTHOGONAL:
+        # batched draws: `group` matrices per call (their factorisations share every launch), `rings` groups alive:
+        # one being consumed while the others are drawn on side streams.  The group size divides K and W, so the
+        # timed region issues exactly K draws and K chains.
+        group = next(b for b in (16, 12, 8, 6, 5, 4, 3, 2, 1) if K % b == 0 and Wm % b == 0 and b <= max(1, args.pipeline))
+        rings = 3
+        depth = group * rings
+        side = [torch.cuda.Stream() for _ in range(rings)]
+        ctxs = [g.gelo_create(0, w.seed + 1 + i, allow_batch_reuse=False) for i in range(rings)]
+        for c in ctxs:
+            g.gelo_reserve(c, w.kind, code, nd, k, d, p, 1, group)     # nothing allocates inside the timed region
+        ring = [None] * rings
 
-    def draw(slot):
+        def draw_group(r):
+            ring[r] = g.gelo_sample_mixing_batch(ctxs[r], w.kind, nd, k, d, code, bid[0], group, stream=side[r])
+            bid[0] += group
 
-        ring[slot] = g.gelo_sample_mixing(ctxs[slot], w.kind, nd, k, d, code, w.cond_max, 64, bid[0], stream=side[slot])
-        bid[0] += 1
+        def pstep(i):
+            r, j = (i // group) % rings, i % group
+            m = ring[r][j]
+            g.gelo_mix(ctxs[r], m, H, U, w.shield_scale)             # waits for the draw through the object's event
+            g.gelo_project(ctxs[r], U, W, Y)
+            g.gelo_unmix(ctxs[r], m, Y, Z)
+            g.gelo_mixing_free(ctxs[r], m)
+            if j == group - 1:
+                draw_group(r)                                       # the group's next `group` batches
 
-    def pstep(i):
-        slot = i % depth
-        m = ring[slot]
-        g.gelo_mix(ctxs[slot], m, H, U, w.shield_scale)          # waits for the draw through the object's event
-        g.gelo_project(ctxs[slot], U, W, Y)
-        g.gelo_unmix(ctxs[slot], m, Y, Z)
-        g.gelo_mixing_free(ctxs[slot], m)
-        draw(slot)                                              # refill the slot for batch i + depth
+        for r in range(rings):
+            draw_group(r)
+        leftovers = lambda: [(ctxs[r], m) for r in range(rings) for m in ring[r]]
+    else:
+        group = 1
+        depth = args.pipeline
+        side = [torch.cuda.Stream() for _ in range(depth)]
+        ctxs = [g.gelo_create(0, w.seed + 1 + i, allow_batch_reuse=False) for i in range(depth)]
+        ring = [None] * depth
 
-    for slot in range(depth):
-        draw(slot)
+        def draw(slot):
+            ring[slot] = g.gelo_sample_mixing(ctxs[slot], w.kind, nd, k, d, code, w.cond_max, 64, bid[0], stream=side[slot])
+            bid[0] += 1
+
+        def pstep(i):
+            slot = i % depth
+            m = ring[slot]
+            g.gelo_mix(ctxs[slot], m, H, U, w.shield_scale)          # waits for the draw through the object's event
+            g.gelo_project(ctxs[slot], U, W, Y)
+            g.gelo_unmix(ctxs[slot], m, Y, Z)
+            g.gelo_mixing_free(ctxs[slot], m)
+            draw(slot)                                              # refill the slot for batch i + depth
+
+        for slot in range(depth):
+            draw(slot)
+        leftovers = lambda: [(ctxs[slot], ring[slot]) for slot in range(depth)]
     for i in range(Wm):
         pstep(i)
     torch.cuda.synchronize()
@@ -391,8 +423,8 @@ def main() -> int:
         pstep(i)
     torch.cuda.synchronize()                  # exactly K draws and K chains were issued and have finished in the region
     t_step = (time.perf_counter() - t0) / K
-    for slot in range(depth):
-        g.gelo_mixing_free(ctxs[slot], ring[slot])
+    for c, m in leftovers():
+        g.gelo_mixing_free(c, m)
     for c in ctxs:
         g.gelo_destroy(c)
 
@@ -447,8 +479,9 @@ def main() -> int:
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": t_step * 1e3,
-        "pipeline": {"depth": depth, "note": "A for the next batches is drawn on side streams while the chain runs; "
-                     "each timed step draws one A and consumes one",
+        "pipeline": {"depth": depth, "draws_per_call": group,
+                     "note": "A for the next batches is drawn on side streams while the chain runs (ORTHOGONAL: draws_per_call "
+                             "matrices per batched call, their factorisations side by side); each timed step draws one A and consumes one",
                      "serial_ms_per_step": t_serial * 1e3, "serial_tflops": (f_chain + f_gen) / t_serial / 1e12},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",

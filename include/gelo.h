@@ -91,7 +91,7 @@ typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;
 #define GELO_MAX_N 5120        /* largest n = n_data + k_shield the factorisation kernels take */
 #define GELO_MAX_ATTEMPTS 255  /* the attempt number is one byte of the Philox counter */
 #define GELO_BATCH_WINDOW 4096 /* how far below the highest batch id used so far an unused id is still accepted */
-#define GELO_STATIC_MAX_N 128  /* largest n gelo_qkv_forward_static and gelo_sample_mixing_batch take */
+#define GELO_STATIC_MAX_N 128  /* largest n gelo_qkv_forward_static takes (and one-launch batched draws) */
 #define GELO_MAX_BATCH_DRAW 48 /* mixing objects one gelo_sample_mixing_batch call draws */
 #define GELO_STATIC_SCRATCH_BYTES (3u << 20)   /* size of its static device buffer, held per GPU until the process ends */
 
@@ -140,12 +140,16 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
                                gelo_dtype dtype, double cond_max, int max_attempts,
                                uint64_t batch_id, gelo_mixing** out, void* stream);
 
-/* Trusted side, Section 3.2 step 1.2 for decode-shaped batches: `count` mixing objects (1..GELO_MAX_BATCH_DRAW)
- * for batch ids first_batch_id .. first_batch_id + count - 1, all of one shape, drawn by ONE launch (a fresh
- * A per layer-step costs more in launch latency than in work at this size, and A does not depend on the data:
- * a decode step's worth is drawn ahead at once).  GELO_ORTHOGONAL only, n = n_data + k_shield <=
- * GELO_STATIC_MAX_N (GELO_ESHAPE beyond).  Object i is what gelo_sample_mixing returns for its batch id, bit
- * for bit.  out: HOST array of `count` pointers; on an error nothing is drawn and no id is consumed. */
+/* Trusted side, Section 3.2 step 1.2, many batches at once: `count` mixing objects (1..GELO_MAX_BATCH_DRAW) for
+ * batch ids first_batch_id .. first_batch_id + count - 1, all of one shape.  A does not depend on the data, so
+ * a decode step's worth, or the next few prefill batches, can be drawn ahead together.  GELO_ORTHOGONAL only.
+ *  n <= GELO_STATIC_MAX_N  ONE launch draws all of them (at this size a fresh A per layer-step costs more in
+ *                          launch latency than in work);
+ *  larger n                up to 16 factorisations (fewer where 16 workspaces would exceed 4 GiB) share every
+ *                          launch of the Householder QR, each in a workspace of its own (the chain of panel factorisations leaves most of the chip idle when one
+ *                          matrix is factorised alone; side by side the strips of all of them fill it).
+ * Object i is what gelo_sample_mixing returns for its batch id, bit for bit.  out: HOST array of `count`
+ * pointers; on an argument error nothing is drawn and no id is consumed. */
 gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d, gelo_dtype dtype,
                                      uint64_t first_batch_id, int count, gelo_mixing** out, void* stream);
 

@@ -26,6 +26,15 @@ constexpr uint32_t kStreamMixing = 0, kStreamShield = 1, kStreamPerturb = 2;
 // side on library-owned streams, each in a workspace of its own, and the first acceptable one in
 // attempt order wins - the same matrix a one-at-a-time loop would return.
 constexpr int kLanes = 4;
+constexpr int kQrSideBySide = 16;       // batched ORTHOGONAL draws: factorisations that share each launch, at most
+constexpr size_t kQrSideBytes = (size_t)4 << 30;   // ... and no more of them than fit this much workspace
+// how many factorisations of an n x n matrix a batched draw of `count` runs side by side
+static int qr_side_by_side(int count, size_t ws_bytes) {
+    int side = count < kQrSideBySide ? count : kQrSideBySide;
+    const size_t fit = kQrSideBytes / ws_bytes;
+    if ((size_t)side > fit) side = fit < 1 ? 1 : (int)fit;
+    return side;
+}
 constexpr int kLanesMaxN = 1024;        // beyond this the rule is infeasible anyway and the buffers get large
 // The condition estimate is a largest Ritz value, which approaches kappa_2 from below (measured within
 // 0.5 % after kKappaSteps steps): a draw is accepted only if the estimate, raised by this margin, still
@@ -391,7 +400,7 @@ static gelo_status sample_into(gelo_ctx* ctx, gelo_mixing* m, FactorWorkspace ws
     auto orthogonal_into_X = [&]() -> hipError_t {
         ps.c1 = kStreamMixing << 8;
         hipError_t e = fill_normal(ws.M, ws.n_pad / 16, n, n, ps, 1.0f, 1, s);     // straight into the QR's tiles
-        if (e == hipSuccess) e = householder_qr(ws, n, s);
+        if (e == hipSuccess) e = householder_qr(ws, n, 1, 0, s);
         return e;
     };
 
@@ -724,13 +733,17 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
         gelo_status st = check_sample_args(ctx, kind, n_data, k_shield, d, dtype, 1.0, 1, first_batch_id + (uint64_t)i, &n);
         if (st != GELO_OK) return st;
     }
-    if (n > GELO_STATIC_MAX_N) return fail(ctx, GELO_ESHAPE, "batched draws take n <= %d (n = %d)", GELO_STATIC_MAX_N, n);
     GELO_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
+    const bool small = n <= kSmallMaxN;
+    // larger matrices: up to kQrSideBySide factorisations share every launch, each in a workspace of its own
+    const size_t ws_bytes = up256(factor_workspace_bytes(n));
+    const int side = qr_side_by_side(count, ws_bytes);
+    gelo_status st = small ? GELO_OK : grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, ws_bytes * side);
+    if (st != GELO_OK) return st;
     SmallSampleTargets t;
     gelo_mixing* got[GELO_MAX_BATCH_DRAW];
     int have = 0;
-    gelo_status st = GELO_OK;
     for (int i = 0; i < count && st == GELO_OK; ++i) {
         gelo_mixing* m = nullptr;
         st = acquire_mixing(ctx, n_data, k_shield, d, dtype, false, &m);
@@ -743,13 +756,36 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
         got[have++] = m;
         t.block[i] = m->block;
     }
-    if (st == GELO_OK) {
+    PhiloxStream ps;
+    ps.key0 = (uint32_t)ctx->seed; ps.key1 = (uint32_t)(ctx->seed >> 32);
+    ps.c1 = kStreamMixing << 8; ps.c2 = ps.c3 = 0;
+    if (st == GELO_OK && small) {
         small_targets_layout(got[0], &t);
-        PhiloxStream ps;
-        ps.key0 = (uint32_t)ctx->seed; ps.key1 = (uint32_t)(ctx->seed >> 32);
-        ps.c1 = kStreamMixing << 8; ps.c2 = ps.c3 = 0;
         hipError_t e = small_sample(t, count, first_batch_id, ps, kStreamShield << 8, n, k_shield, d, got[0]->ldk, s);
         if (e != hipSuccess) st = hip_fail(ctx, e, "small_sample");
+    }
+    for (int base = 0; st == GELO_OK && !small && base < count; base += side) {
+        const int c = count - base < side ? count - base : side;
+        FactorWorkspace lw[kQrSideBySide];
+        hipError_t e = hipSuccess;
+        for (int i = 0; i < c && e == hipSuccess; ++i) {
+            factor_workspace_carve((char*)ctx->factor_ws + ws_bytes * i, n, &lw[i]);
+            const uint64_t id = first_batch_id + (uint64_t)(base + i);
+            ps.c1 = kStreamMixing << 8; ps.c2 = (uint32_t)id; ps.c3 = (uint32_t)(id >> 32);
+            e = fill_normal(lw[i].M, lw[i].n_pad / 16, n, n, ps, 1.0f, 1, s);      // straight into the QR's tiles
+        }
+        if (e == hipSuccess) e = householder_qr(lw[0], n, c, (int64_t)(ws_bytes / sizeof(float)), s);
+        for (int i = 0; i < c && e == hipSuccess; ++i) {
+            gelo_mixing* m = got[base + i];
+            const uint64_t id = first_batch_id + (uint64_t)(base + i);
+            // A = Q diag(sign r_ii); A^-1 = A^T
+            e = emit_matrix(lw[i].X, lw[i].n_pad / 16, 1, lw[i].rdiag, n, m->ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s);
+            if (e == hipSuccess && k_shield > 0) {
+                ps.c1 = kStreamShield << 8; ps.c2 = (uint32_t)id; ps.c3 = (uint32_t)(id >> 32);
+                e = shield_directions(m->GS, k_shield, d, ps, m->gsnorm, s);
+            }
+        }
+        if (e != hipSuccess) st = hip_fail(ctx, e, "batched orthogonal draw");
     }
     if (st != GELO_OK) {
         for (int i = 0; i < have; ++i) got[i]->in_use = false;
@@ -916,6 +952,12 @@ gelo_status gelo_reserve(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_
     int lanes = 1;
     st = prepare_sampling(ctx, kind, n, dtype, max_attempts, &lanes);
     if (st != GELO_OK) return st;
+    if (kind == GELO_ORTHOGONAL && n > kSmallMaxN && mixings > 1) {
+        // a batched draw of `mixings` matrices factorises up to kQrSideBySide of them side by side
+        const int side = qr_side_by_side(mixings, up256(factor_workspace_bytes(n)));
+        st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, up256(factor_workspace_bytes(n)) * side);
+        if (st != GELO_OK) return st;
+    }
     if (p > 0) {
         const size_t ub = up256((size_t)n * d * elem_size(dtype)), yb = up256((size_t)n * p * elem_size(dtype));
         st = grow(ctx, &ctx->chain_ws, &ctx->chain_ws_bytes, ub + yb);

@@ -222,8 +222,9 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, float* Vr, float* Vt, f
 
 template <int NTHR, int R>
 __global__ __launch_bounds__(NTHR)
-void qr_panel_kernel(float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, int m) {
-    qr_panel_body<NTHR, R>(Mp, Vr, Vt, Tg, rdiag, m);
+void qr_panel_kernel(float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, int m, int64_t batch_stride) {
+    const int64_t off = (int64_t)blockIdx.y * batch_stride;
+    qr_panel_body<NTHR, R>(Mp + off, Vr + off, Vt + off, Tg + off, rdiag + off, m);
 }
 
 // ------------------------------------------------- fused block-reflector update --
@@ -239,156 +240,250 @@ void qr_panel_kernel(float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, i
 // first product and as Vr[r * 16 + i] for the second.
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
-template <int NBLK>
-__device__ __forceinline__ void reflect_strip_body(const float* __restrict__ Vr, const float* __restrict__ Vt,
-                                                   const float* __restrict__ T, int t_transposed, float* Cs, int nblocks) {
-    __shared__ float Wp[8][NB][NB];
-    __shared__ float Ws[NB][NB];
-    __shared__ float Wn[NB][NB];
+// One block reflector I - V op(T) V^T as a strip sees it: V in both layouts, its triangle, and `shift`, the
+// number of 16-row blocks by which its first row lies below the strip's first row (a strip that applies several
+// reflectors of a block of panels in one pass starts at the oldest one's first row).
+struct Reflector { const float* Vr; const float* Vt; const float* T; int shift; };
+// (the pointers are those of the first matrix of a batch; `off` below is the distance to this workgroup's matrix)
+
+// strips per workgroup where a finished block of panels is applied: two where the registers allow it
+constexpr int strips_per_workgroup(int NBLK) { return NBLK == 20 ? 2 : 1; }
+constexpr int kMaxDelay = 4;             // most reflectors one strip pass applies (panels per block of the delayed update)
+
+// a tile of zeros: what a strip block reads in place of a reflector block that does not exist for it
+__device__ __attribute__((aligned(1024))) float g_zero_tile[256];
+
+// NS = 1 or 2 neighbouring 16-column strips per workgroup (`strips` of them exist: the second may be missing at the
+// end of a range; the tiles of neighbouring strips lie `strip_stride` floats apart).  With two strips every
+// reflector block a wave fetches feeds twice the matrix instructions: the reflectors come from the L2, whose
+// bandwidth all strips of a launch share, and at one strip per workgroup that bandwidth - not the matrix
+// cores - bounds a launch.  Each strip's arithmetic is the same whichever way the strips are paired.
+template <int NBLK, int NS>
+__device__ __forceinline__ void reflect_strip_body(const Reflector* refl, int count, int64_t off, int t_transposed, float* Cs,
+                                                   int64_t strip_stride, int strips, int nblocks) {
+    constexpr int NC = NB * NS;                              // columns per workgroup
+    __shared__ float Wp[8][NB][NC];
+    __shared__ float Ws[NB][NC];
+    __shared__ float Wn[NB][NC];
     __shared__ float Ts[NB][NB];
-    // the wave index as a scalar: block numbers and their clamped offsets then live in scalar registers
+    // the wave index as a scalar: block numbers and their offsets then live in scalar registers
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
-    if (tid < NB * NB) Ts[tid >> 4][tid & 15] = T[tid];
 
     float* Cl = Cs + c * 16 + 4 * g;                         // this lane's column, its first row of tile 0
-    const float* Vtl = Vt + c * 16 + 4 * g;                  // reflector c, same rows
-    const float* Vrl = Vr + (int64_t)c * NB + 4 * g;         // row c of a block, reflectors 4 g ..
-    // Blocks past the end are clamped to the last one for every load (a valid address, no branch) and
-    // take no part: their strip registers are zero and they are not stored.  All loads of a phase are
-    // issued ahead of the MFMAs that use them, in groups of GRP blocks, double-buffered: a load
-    // consumed right behind its issue would expose one memory latency per block.
-    constexpr int GRP = 5, NG = NBLK / GRP;
-    static_assert(NBLK % GRP == 0, "blocks per wave must be a multiple of the load group");
+    // Blocks past the end take no part: their strip registers are zero, they meet the zero tile instead of a
+    // reflector block (so they are still zero when the next reflector of a block of panels comes), and they are
+    // not stored; their loads are clamped to the last block (a valid address, no branch).  A missing second
+    // strip is all zeros and not stored either.
     const int last = nblocks - 1;
-    f32x4_t cr[NBLK];
+    f32x4_t cr[NS][NBLK];
 #pragma unroll
-    for (int b = 0; b < NBLK; ++b) {
-        const int blk = wave + 8 * b;
-        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(Cl + 256 * (blk < nblocks ? blk : last));
-        const bool valid = blk < nblocks;
-        cr[b] = f32x4_t{valid ? v[0] : 0.f, valid ? v[1] : 0.f, valid ? v[2] : 0.f, valid ? v[3] : 0.f};
-    }
-    // W_partial[i][col] = sum over this wave's rows of V[r][i] C[r][col]; MFMA (b, v) contracts the four
-    // rows 16 blk + 4 kk + v (kk = lane / 16): A = V[row][lane % 16], B = the strip register itself
-    f32x4_t w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
-    f32x4_t va[2][GRP];
-    auto load_vt = [&](int grp) {
+    for (int st = 0; st < NS; ++st) {
+        const bool have = st < strips;
+        const float* Csl = Cl + (have ? st * strip_stride : 0);
 #pragma unroll
-        for (int q = 0; q < GRP; ++q) {
-            const int blk = wave + 8 * (grp * GRP + q);
-            va[grp & 1][q] = *reinterpret_cast<const f32x4_t*>(Vtl + 256 * (blk < nblocks ? blk : last));
-        }
-    };
-    load_vt(0);
-#pragma unroll
-    for (int grp = 0; grp < NG; ++grp) {
-        if (grp + 1 < NG) load_vt(grp + 1);
-#pragma unroll
-        for (int q = 0; q < GRP; ++q) {
-            const int b = grp * GRP + q;
-            const f32x4_t a = va[grp & 1][q];
-            w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[b][0], w0, 0, 0, 0);
-            w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], cr[b][1], w1, 0, 0, 0);
-            w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], cr[b][2], w0, 0, 0, 0);
-            w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], cr[b][3], w1, 0, 0, 0);
-        }
-    }
-    // the reflector rows of the second product do not depend on W: fetch the first group before the barriers
-    auto load_vr = [&](int grp) {
-#pragma unroll
-        for (int q = 0; q < GRP; ++q) {
-            const int blk = wave + 8 * (grp * GRP + q);
-            va[grp & 1][q] = *reinterpret_cast<const f32x4_t*>(Vrl + (int64_t)(16 * (blk < nblocks ? blk : last)) * NB);
-        }
-    };
-    load_vr(0);
-#pragma unroll
-    for (int v = 0; v < 4; ++v) Wp[wave][4 * g + v][c] = w0[v] + w1[v];      // accumulator row 4 g + v, column c
-    __syncthreads();
-    if (tid < NB * NB) {
-        const int i = tid >> 4, cc = tid & 15;
-        float sum = Wp[0][i][cc];
-#pragma unroll
-        for (int w = 1; w < 8; ++w) sum += Wp[w][i][cc];
-        Ws[i][cc] = sum;
-    }
-    __syncthreads();
-    if (tid < NB * NB) {
-        const int i = tid >> 4, cc = tid & 15;
-        float o = 0.f;
-#pragma unroll
-        for (int k = 0; k < NB; ++k) o = fmaf(t_transposed ? Ts[k][i] : Ts[i][k], Ws[k][cc], o);
-        Wn[i][cc] = -o;
-    }
-    __syncthreads();
-    // C_block += V_block W': MFMA q contracts reflectors 4 kk + q; A = V[16 blk + lane % 16][4 kk + q]
-    float bq[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) bq[q] = Wn[4 * g + q][c];
-#pragma unroll
-    for (int grp = 0; grp < NG; ++grp) {
-        if (grp + 1 < NG) load_vr(grp + 1);
-#pragma unroll
-        for (int q = 0; q < GRP; ++q) {
-            const int b = grp * GRP + q;
+        for (int b = 0; b < NBLK; ++b) {
             const int blk = wave + 8 * b;
-            const f32x4_t a4 = va[grp & 1][q];
-            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[0], bq[0], cr[b], 0, 0, 0);
-            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[1], bq[1], cr[b], 0, 0, 0);
-            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[2], bq[2], cr[b], 0, 0, 0);
-            cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[3], bq[3], cr[b], 0, 0, 0);
-            if (blk < nblocks) *reinterpret_cast<f32x4_t*>(Cl + 256 * blk) = cr[b];
+            const f32x4_t v = *reinterpret_cast<const f32x4_t*>(Csl + 256 * (blk < nblocks ? blk : last));
+            const bool valid = have && blk < nblocks;
+            cr[st][b] = f32x4_t{valid ? v[0] : 0.f, valid ? v[1] : 0.f, valid ? v[2] : 0.f, valid ? v[3] : 0.f};
+        }
+    }
+    // The reflector operands stream through two register groups of GRP blocks.  Per reflector there are 2 NG
+    // groups, first those of the tiled layout (W = V^T C), then those of the row layout (C += V W'); group j
+    // uses register group j % 2, and as soon as a group has been consumed the group two places further on -
+    // of the next reflector, if this one has no more - is requested into the same registers.  Two groups are
+    // always on their way, across the barriers and from one reflector to the next: a load consumed right behind
+    // its issue would expose one memory latency per group.
+    constexpr int GRP = (NBLK == 20 && NS == 1) ? 10 : 5, NG = NBLK / GRP;
+    static_assert(NBLK % GRP == 0, "blocks per wave must be a multiple of the load group");
+    f32x4_t va[2][GRP];
+    const float* zero_l = g_zero_tile + c * 16 + 4 * g;
+    auto request = [&](const Reflector& R, auto jc) {
+        constexpr int j = decltype(jc)::value, phase = j / NG, grp = j % NG;
+        // Vt: reflector c, this lane's four rows of the block; Vr: row c of the block, reflectors 4 g ..
+        const float* base = (phase == 0 ? R.Vt : R.Vr) + off + c * 16 + 4 * g;
+#pragma unroll
+        for (int k = 0; k < GRP; ++k) {
+            const int blk = wave + 8 * (grp * GRP + k), vb = blk - R.shift;      // strip block blk meets reflector block blk - shift
+            const float* src = (vb >= 0 && blk <= last) ? base + 256 * vb : zero_l;
+            va[j & 1][k] = *reinterpret_cast<const f32x4_t*>(src);
+        }
+    };
+    // the triangle of a reflector is fetched one reflector ahead (needed behind its second barrier only), so that
+    // no wait for it ever stands between a request and the products that use older requests
+    float t_next = tid < NB * NB ? refl[0].T[off + tid] : 0.f;
+    request(refl[0], std::integral_constant<int, 0>{});
+    request(refl[0], std::integral_constant<int, 1>{});
+    // (the loop over the reflectors is unrolled: the waits for the requests then count exactly what is outstanding)
+    static_for<kMaxDelay>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        if (q >= count) return;
+        const Reflector R = refl[q];
+        const bool more = q + 1 < count;
+        const Reflector Rn = more ? refl[q + 1] : R;
+        auto request_behind = [&](auto jc) {                  // the group two places behind group j
+            constexpr int j = decltype(jc)::value;
+            if constexpr (j + 2 < 2 * NG) request(R, std::integral_constant<int, j + 2>{});
+            else if (more) request(Rn, std::integral_constant<int, j + 2 - 2 * NG>{});
+        };
+        const float t_mine = t_next;
+        // W_partial[i][col] = sum over this wave's rows of V[r][i] C[r][col]; MFMA (b, v) contracts the four
+        // rows 16 blk + 4 kk + v (kk = lane / 16): A = V[row][lane % 16], B = the strip register itself.
+        f32x4_t w0[NS], w1[NS];
+#pragma unroll
+        for (int st = 0; st < NS; ++st) { w0[st] = f32x4_t{0.f, 0.f, 0.f, 0.f}; w1[st] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
+        static_for<NG>([&](auto gc) {
+            constexpr int grp = decltype(gc)::value;
+#pragma unroll
+            for (int k = 0; k < GRP; ++k) {
+                const int b = grp * GRP + k;
+                const f32x4_t a = va[grp & 1][k];
+#pragma unroll
+                for (int st = 0; st < NS; ++st) {
+                    w0[st] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[st][b][0], w0[st], 0, 0, 0);
+                    w1[st] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], cr[st][b][1], w1[st], 0, 0, 0);
+                }
+#pragma unroll
+                for (int st = 0; st < NS; ++st) {
+                    w0[st] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], cr[st][b][2], w0[st], 0, 0, 0);
+                    w1[st] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], cr[st][b][3], w1[st], 0, 0, 0);
+                }
+            }
+            request_behind(gc);
+        });
+        if (tid < NB * NB) Ts[tid >> 4][tid & 15] = t_mine;
+        if (more && tid < NB * NB) t_next = Rn.T[off + tid];
+#pragma unroll
+        for (int st = 0; st < NS; ++st)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Wp[wave][4 * g + v][st * NB + c] = w0[st][v] + w1[st][v];     // accumulator row 4 g + v, column c
+        __syncthreads();
+        if (tid < NB * NC) {
+            const int i = tid / NC, cc = tid % NC;
+            float sum = Wp[0][i][cc];
+#pragma unroll
+            for (int w = 1; w < 8; ++w) sum += Wp[w][i][cc];
+            Ws[i][cc] = sum;
+        }
+        __syncthreads();
+        if (tid < NB * NC) {
+            const int i = tid / NC, cc = tid % NC;
+            float o = 0.f;
+#pragma unroll
+            for (int k = 0; k < NB; ++k) o = fmaf(t_transposed ? Ts[k][i] : Ts[i][k], Ws[k][cc], o);
+            Wn[i][cc] = -o;
+        }
+        __syncthreads();
+        // C_block += V_block W': MFMA k contracts reflectors 4 kk + k; A = V[16 blk + lane % 16][4 kk + k]
+        float bq[NS][4];
+#pragma unroll
+        for (int st = 0; st < NS; ++st)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) bq[st][k] = Wn[4 * g + k][st * NB + c];
+        static_for<NG>([&](auto gc) {
+            constexpr int grp = decltype(gc)::value, j = NG + grp;
+#pragma unroll
+            for (int k = 0; k < GRP; ++k) {
+                const int b = grp * GRP + k;
+                const f32x4_t a4 = va[j & 1][k];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                    for (int st = 0; st < NS; ++st)
+                        cr[st][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[kk], bq[st][kk], cr[st][b], 0, 0, 0);
+            }
+            request_behind(std::integral_constant<int, j>{});
+        });
+        // The LDS arrays serve the next reflector too: Ts and Wp were last read before the third barrier above, Wn
+        // (read into bq right behind it) is rewritten only behind the next reflector's second barrier.
+    });
+#pragma unroll
+    for (int st = 0; st < NS; ++st) {
+        if (st < strips) {
+            float* Csl = Cl + st * strip_stride;
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                const int blk = wave + 8 * b;
+                if (blk < nblocks) *reinterpret_cast<f32x4_t*>(Csl + 256 * blk) = cr[st][b];
+            }
         }
     }
 }
 
-template <int NBLK>
-__global__ __launch_bounds__(512)
-void reflect_strip_kernel(const float* __restrict__ Vr, const float* __restrict__ Vt, const float* __restrict__ T,
-                          int t_transposed, float* C, int64_t strip_stride, int nblocks) {
-    reflect_strip_body<NBLK>(Vr, Vt, T, t_transposed, C + (int64_t)blockIdx.x * strip_stride, nblocks);
-}
-
-// One launch per QR step p.  The chain of panel factorisations (one workgroup each) is the
-// critical path, so the launch that applies block reflector p also factorises panel p + 1:
-//   workgroup 0        updates the 16 columns of panel p + 1, then factorises them;
-//   the next `wide`    update the remaining trailing columns of the matrix;
-//   the last `acc`     update all columns of the accumulated transposed orthogonal factor
-//                      X <- (I - V T^T V^T) X  (X starts as the identity, ends as Q^T).
-// Every strip reads only V_p, T_p and its own columns; panel p + 1 writes its own columns, the
-// other pair of reflector buffers and its own T, so the workgroups of one launch never touch the
-// same data.  Waves of workgroup 0 that the panel does not use leave after the strip.
+// One launch per QR step p.  The chain of panel factorisations (one workgroup each) is the critical path, so
+// the launch that follows the factorisation of panel p also factorises panel p + 1.  Panels come in blocks of
+// D (delayed update): inside a block only the block's own columns see each new reflector at once; everything
+// outside it - the rest of the matrix and the accumulated transposed orthogonal factor X (starts as the
+// identity, ends as Q^T) - is read and written ONCE per block, by strips that apply the block's D reflectors in
+// a row while they hold their columns in registers.  That divides the memory traffic of the factorisation,
+// which is what bounds several factorisations running side by side, by almost D.
+//   workgroup 0          updates the 16 columns of panel p + 1 - with reflector p alone inside a block, with the
+//                        whole finished block when panel p + 1 starts a new one - then factorises them;
+//   `inner` workgroups   (inside a block) apply reflector p to the block's later panels;
+//   `outer` + `acc`      (a block has just been finished) apply its reflectors to the columns beyond panel
+//                        p + 1 and to all columns of X.
+// Every strip reads only reflectors and its own columns; panel p + 1 writes its own columns, reflector buffers
+// no strip of this launch reads, and its own T: the workgroups of one launch never touch the same data.  Waves
+// of workgroup 0 that the panel does not use leave after the strip.
 struct QrStepArgs {
-    const float* Vr; const float* Vt;    // reflector block p in both layouts (see reflect_strip_body)
-    const float* T;                      // its 16 x 16 triangle
-    float* C;                            // tile (row block of c0, column block of c0 + 16) of the matrix: panel p + 1 first
-    float* X;                            // tile (row block of c0, column block 0) of the accumulator
+    Reflector refl[kMaxDelay];           // the current block's reflectors so far; shift = position in the block
+    int pending;                         // how many of them (the newest is refl[pending - 1], reflector p)
+    int block_done;                      // panel p is the last of its block (or of the matrix)
+    float* C0;                           // the columns of panel p + 1: tile (first row block, column block p + 1)
+    float* Cin;                          // tile (row block p, column block p + 2): `inner` strips from here
+    float* Cout;                         // tile (row block of the block's first panel, column block p + 2): `outer` strips
+    float* X;                            // tile (row block of the block's first panel, column block 0): `acc` strips
     int64_t strip_stride;                // floats between the tiles of neighbouring column blocks
-    int nblocks;                         // rows / 16 of step p
-    int wide, acc;                       // strip counts
+    int nb_single, nb_block;             // rows / 16 below the first row of reflector p / of the block's first reflector
+    int inner, outer, acc;               // strip counts
     float* Vr_next; float* Vt_next; float* Tnext; float* rdiag_next;   // outputs of panel p + 1
     int m_next;                          // its row count (0: no further panel)
+    int64_t batch_stride;                // floats from one matrix's workspace to the next one's (grid y = matrix)
 };
 
 template <int NTHR, int R, int NBLK>
-__global__ __launch_bounds__(512)
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(NBLK >= 20 ? 2 : 4, NBLK >= 20 ? 2 : 4)))
 void qr_step_kernel(QrStepArgs a) {
     const int b = blockIdx.x;
-    float* Cs = b <= a.wide ? a.C + (int64_t)b * a.strip_stride : a.X + (int64_t)(b - 1 - a.wide) * a.strip_stride;
-    reflect_strip_body<NBLK>(a.Vr, a.Vt, a.T, 1, Cs, a.nblocks);
-    if (b != 0 || a.m_next <= 0) return;
-    __threadfence_block();
-    __syncthreads();                     // the strip's stores are visible to the whole workgroup
-    if (threadIdx.x >= NTHR) return;
-    qr_panel_body<NTHR, R>(a.C + 256, a.Vr_next, a.Vt_next, a.Tnext, a.rdiag_next, a.m_next);   // one tile (16 rows) further down
+    const int64_t off = (int64_t)blockIdx.y * a.batch_stride;
+    const Reflector* newest = a.refl + (a.pending - 1);
+    if (b == 0) {
+        if (a.m_next <= 0) return;
+        if (a.block_done) reflect_strip_body<NBLK, 1>(a.refl, a.pending, off, 1, a.C0 + off, 0, 1, a.nb_block);
+        else {
+            Reflector single = *newest; single.shift = 0;
+            reflect_strip_body<NBLK, 1>(&single, 1, off, 1, a.C0 + off, 0, 1, a.nb_single);
+        }
+        __threadfence_block();
+        __syncthreads();                 // the strip's stores are visible to the whole workgroup
+        if (threadIdx.x >= NTHR) return;
+        // the panel starts one tile (16 rows) below reflector p's first row
+        float* Mp = a.C0 + off + 256 * (a.block_done ? a.pending : 1);
+        qr_panel_body<NTHR, R>(Mp, a.Vr_next + off, a.Vt_next + off, a.Tnext + off, a.rdiag_next + off, a.m_next);
+        return;
+    }
+    if (b <= a.inner) {
+        Reflector single = *newest; single.shift = 0;
+        reflect_strip_body<NBLK, 1>(&single, 1, off, 1, a.Cin + off + (int64_t)(b - 1) * a.strip_stride, 0, 1, a.nb_single);
+        return;
+    }
+    // the strips behind the block and those of X, NS neighbours per workgroup
+    constexpr int NS = strips_per_workgroup(NBLK);
+    const int outer_wgs = (a.outer + NS - 1) / NS;
+    int idx = b - 1 - a.inner, range = a.outer;
+    float* Cs = a.Cout;
+    if (idx >= outer_wgs) { idx -= outer_wgs; range = a.acc; Cs = a.X; }
+    const int first = idx * NS, strips = range - first < NS ? range - first : NS;
+    reflect_strip_body<NBLK, NS>(a.refl, a.pending, off, 1, Cs + off + (int64_t)first * a.strip_stride, a.strip_stride, strips, a.nb_block);
 }
 
 // zeroes what lies beyond n x n of the tiled matrix M (n_pad x n_pad) and sets the tiled X to the identity
 __global__ __launch_bounds__(256)
-void qr_prepare_kernel(float* M, float* X, int n, int n_pad) {
+void qr_prepare_kernel(float* M, float* X, int n, int n_pad, int64_t batch_stride) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;          // index into the tiled arrays
     if (i >= (int64_t)n_pad * n_pad) return;
+    M += (int64_t)blockIdx.y * batch_stride; X += (int64_t)blockIdx.y * batch_stride;
     const int nbr = n_pad >> 4;
     const int tile = (int)(i >> 8), in = (int)(i & 255);
     const int r = (tile % nbr) * 16 + (in & 15), c = (tile / nbr) * 16 + (in >> 4);
@@ -413,31 +508,14 @@ void pad_matrix_kernel(float* M, int64_t ld, int n, int n_pad, int identity_bloc
 
 template <int NTHR>
 hipError_t launch_qr_panel(int rows_per_thread, float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, int m,
-                           hipStream_t s) {
+                           int count, int64_t batch_stride, hipStream_t s) {
     switch (rows_per_thread) {
-#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((qr_panel_kernel<NTHR, RR>), dim3(1), dim3(NTHR), 0, s, Mp, Vr, Vt, Tg, rdiag, m); break;
+#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((qr_panel_kernel<NTHR, RR>), dim3(1, count), dim3(NTHR), 0, s, Mp, Vr, Vt, Tg, rdiag, m, batch_stride); break;
         GELO_CASE(1) GELO_CASE(2) GELO_CASE(3) GELO_CASE(4) GELO_CASE(5)
         GELO_CASE(6) GELO_CASE(7) GELO_CASE(8) GELO_CASE(9) GELO_CASE(10)
 #undef GELO_CASE
         default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
-}
-
-// C (tiled, rows x cols, both multiples of 16; C points at the first tile, strip_stride floats between column blocks)
-// <- (I - V op(T) V^T) C
-hipError_t apply_block_reflector(const float* Vr, const float* Vt, const float* T, int t_transposed,
-                                 float* C, int64_t strip_stride, int rows, int cols, hipStream_t s) {
-    if (rows <= 0 || cols <= 0) return hipSuccess;
-    if (rows % NB != 0 || cols % NB != 0) return hipErrorInvalidValue;
-    const int nblocks = rows / NB;
-    const dim3 grid(cols / NB), block(512);
-    const int per_wave = (nblocks + 7) / 8;
-    if (per_wave <= 5) hipLaunchKernelGGL(reflect_strip_kernel<5>, grid, block, 0, s, Vr, Vt, T, t_transposed, C, strip_stride, nblocks);
-    else if (per_wave <= 10) hipLaunchKernelGGL(reflect_strip_kernel<10>, grid, block, 0, s, Vr, Vt, T, t_transposed, C, strip_stride, nblocks);
-    else if (per_wave <= 20) hipLaunchKernelGGL(reflect_strip_kernel<20>, grid, block, 0, s, Vr, Vt, T, t_transposed, C, strip_stride, nblocks);
-    else if (per_wave <= 40) hipLaunchKernelGGL(reflect_strip_kernel<40>, grid, block, 0, s, Vr, Vt, T, t_transposed, C, strip_stride, nblocks);
-    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
@@ -495,90 +573,108 @@ hipError_t pad_matrix(float* M, int64_t ld, int n, int n_pad, int identity_block
 namespace {
 
 template <int NTHR, int R, int NBLK>
-hipError_t launch_qr_step_t(const QrStepArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK>), dim3(1 + a.wide + a.acc), dim3(512), 0, s, a);
+hipError_t launch_qr_step_t(const QrStepArgs& a, int count, hipStream_t s) {
+    constexpr int NS = strips_per_workgroup(NBLK);
+    const int wgs = 1 + a.inner + (a.outer + NS - 1) / NS + (a.acc + NS - 1) / NS;
+    hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK>), dim3(wgs, count), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 
-// Can a panel with R rows per thread (NTHR threads) meet strips with NBLK blocks per wave (PREV: the
-// next smaller strip variant)?  The next panel has 16 (nblocks - 1) rows, so only a few pairs occur.
+// Can a panel with R rows per thread (NTHR threads) meet strips with NBLK blocks per wave (PREV: the next
+// smaller strip variant)?  The next panel has 16 (nb_single - 1) rows and the longest strip of the launch
+// nb_single .. nb_single + kMaxDelay - 1 blocks, so only a few pairs occur.
 constexpr bool qr_step_pair_occurs(int NTHR, int R, int NBLK, int PREV) {
-    const int min_nb = (R - 1) * NTHR / NB + 2, max_nb = R * NTHR / NB + 1;
+    const int min_nb = (R - 1) * NTHR / NB + 2, max_nb = R * NTHR / NB + 1 + (kMaxDelay - 1);
     return (min_nb + 7) / 8 <= NBLK && (max_nb + 7) / 8 > PREV;
 }
 
 template <int NTHR, int R>
-hipError_t launch_qr_step_r(int per_wave, const QrStepArgs& a, hipStream_t s) {
-    if (per_wave <= 5) { if constexpr (qr_step_pair_occurs(NTHR, R, 5, 0)) return launch_qr_step_t<NTHR, R, 5>(a, s); }
-    else if (per_wave <= 10) { if constexpr (qr_step_pair_occurs(NTHR, R, 10, 5)) return launch_qr_step_t<NTHR, R, 10>(a, s); }
-    else if (per_wave <= 20) { if constexpr (qr_step_pair_occurs(NTHR, R, 20, 10)) return launch_qr_step_t<NTHR, R, 20>(a, s); }
-    else if (per_wave <= 40) { if constexpr (qr_step_pair_occurs(NTHR, R, 40, 20)) return launch_qr_step_t<NTHR, R, 40>(a, s); }
+hipError_t launch_qr_step_r(int per_wave, const QrStepArgs& a, int count, hipStream_t s) {
+    if (per_wave <= 5) { if constexpr (qr_step_pair_occurs(NTHR, R, 5, 0)) return launch_qr_step_t<NTHR, R, 5>(a, count, s); }
+    else if (per_wave <= 10) { if constexpr (qr_step_pair_occurs(NTHR, R, 10, 5)) return launch_qr_step_t<NTHR, R, 10>(a, count, s); }
+    else if (per_wave <= 20) { if constexpr (qr_step_pair_occurs(NTHR, R, 20, 10)) return launch_qr_step_t<NTHR, R, 20>(a, count, s); }
+    else if (per_wave <= 40) { if constexpr (qr_step_pair_occurs(NTHR, R, 40, 20)) return launch_qr_step_t<NTHR, R, 40>(a, count, s); }
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_qr_step(const QrStepArgs& a, hipStream_t s) {
-    const int per_wave = (a.nblocks + 7) / 8;
+hipError_t launch_qr_step(const QrStepArgs& a, int count, hipStream_t s) {
+    const int longest = a.block_done ? a.nb_block : a.nb_single;
+    const int per_wave = (longest + 7) / 8;
     const int m = a.m_next;
     if (m <= 1024) {
         switch ((m + 255) / 256) {
-            case 0: case 1: return launch_qr_step_r<256, 1>(per_wave, a, s);
-            case 2: return launch_qr_step_r<256, 2>(per_wave, a, s);
-            case 3: return launch_qr_step_r<256, 3>(per_wave, a, s);
-            default: return launch_qr_step_r<256, 4>(per_wave, a, s);
+            case 0: case 1: return launch_qr_step_r<256, 1>(per_wave, a, count, s);
+            case 2: return launch_qr_step_r<256, 2>(per_wave, a, count, s);
+            case 3: return launch_qr_step_r<256, 3>(per_wave, a, count, s);
+            default: return launch_qr_step_r<256, 4>(per_wave, a, count, s);
         }
     }
     switch ((m + 511) / 512) {
-        case 3: return launch_qr_step_r<512, 3>(per_wave, a, s);
-        case 4: return launch_qr_step_r<512, 4>(per_wave, a, s);
-        case 5: return launch_qr_step_r<512, 5>(per_wave, a, s);
-        case 6: return launch_qr_step_r<512, 6>(per_wave, a, s);
-        case 7: return launch_qr_step_r<512, 7>(per_wave, a, s);
-        case 8: return launch_qr_step_r<512, 8>(per_wave, a, s);
-        case 9: return launch_qr_step_r<512, 9>(per_wave, a, s);
-        case 10: return launch_qr_step_r<512, 10>(per_wave, a, s);
+        case 3: return launch_qr_step_r<512, 3>(per_wave, a, count, s);
+        case 4: return launch_qr_step_r<512, 4>(per_wave, a, count, s);
+        case 5: return launch_qr_step_r<512, 5>(per_wave, a, count, s);
+        case 6: return launch_qr_step_r<512, 6>(per_wave, a, count, s);
+        case 7: return launch_qr_step_r<512, 7>(per_wave, a, count, s);
+        case 8: return launch_qr_step_r<512, 8>(per_wave, a, count, s);
+        case 9: return launch_qr_step_r<512, 9>(per_wave, a, count, s);
+        case 10: return launch_qr_step_r<512, 10>(per_wave, a, count, s);
         default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
-hipError_t householder_qr(const FactorWorkspace& ws, int n, hipStream_t s) {
+hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t batch_stride, hipStream_t s) {
+    if (count < 1 || count > 65535) return hipErrorInvalidValue;
     const int n_pad = ws.n_pad;
     const int nbr = n_pad / NB;                               // tile rows (= tile columns)
     const int64_t strip_stride = (int64_t)nbr * 256;
     const int panels = nbr;
-    // block reflector p is only needed while step p runs: two compact pairs of buffers alternate
-    float* Vr[2] = {ws.Vc, ws.Vc + (int64_t)n_pad * NB};
-    float* Vt[2] = {ws.Vc + 2 * (int64_t)n_pad * NB, ws.Vc + 3 * (int64_t)n_pad * NB};
+    // Panels per block of the delayed update; the reflectors of two blocks are alive at a time (the finished
+    // block is being applied while the next one's first panel is written), each n_pad x 16 in two layouts, all
+    // inside the n_pad x ld floats of ws.Vc.
+    const int D = ws.ld >= 64 * kMaxDelay ? kMaxDelay : (ws.ld >= 128 ? 2 : 1);
+    const int sets = 2 * D;
+    const int64_t set_floats = (int64_t)n_pad * NB;
+    auto Vr_of = [&](int p) { return ws.Vc + (int64_t)(p % sets) * set_floats; };
+    auto Vt_of = [&](int p) { return ws.Vc + (int64_t)(sets + p % sets) * set_floats; };
     {
         const int64_t elems = (int64_t)n_pad * n_pad;
-        hipLaunchKernelGGL(qr_prepare_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, s, ws.M, ws.X, n, n_pad);
+        hipLaunchKernelGGL(qr_prepare_kernel, dim3((unsigned)((elems + 255) / 256), count), dim3(256), 0, s, ws.M, ws.X, n, n_pad, batch_stride);
         GELO_TRY(hipGetLastError());
     }
-    // panel 0 on its own; then one launch per step: trailing update + accumulation of Q^T with block
-    // reflector p, and in the same launch the factorisation of panel p + 1
+    // panel 0 on its own; then one launch per step
     {
         const int m = n_pad;
-        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, Vr[0], Vt[0], ws.Tmat, ws.rdiag, m, s));
-        else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M, Vr[0], Vt[0], ws.Tmat, ws.rdiag, m, s));
+        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, Vr_of(0), Vt_of(0), ws.Tmat, ws.rdiag, m, count, batch_stride, s));
+        else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M, Vr_of(0), Vt_of(0), ws.Tmat, ws.rdiag, m, count, batch_stride, s));
     }
     for (int p = 0; p < panels; ++p) {
-        const int c0 = p * NB, m = n_pad - c0;
-        const int cols = n_pad - c0 - NB;
+        const int p0 = p / D * D, i = p - p0;                 // first panel of p's block, p's position in it
+        const bool last = p + 1 == panels;
+        const int block_end = p0 + D < panels ? p0 + D : panels;     // one past the block's last panel
         QrStepArgs a;
-        a.Vr = Vr[p & 1]; a.Vt = Vt[p & 1]; a.T = ws.Tmat + (int64_t)p * NB * NB;
-        a.X = ws.X + (int64_t)p * 256;                        // tile (p, 0)
-        a.strip_stride = strip_stride; a.nblocks = m / NB; a.acc = nbr;
-        if (cols <= 0) {                      // last block reflector: only the accumulator is left
-            GELO_TRY(apply_block_reflector(a.Vr, a.Vt, a.T, 1, a.X, strip_stride, m, n_pad, s));
-            break;
+        a.pending = i + 1;
+        for (int q = 0; q <= i; ++q) {
+            a.refl[q].Vr = Vr_of(p0 + q); a.refl[q].Vt = Vt_of(p0 + q);
+            a.refl[q].T = ws.Tmat + (int64_t)(p0 + q) * NB * NB; a.refl[q].shift = q;
         }
-        a.C = ws.M + (int64_t)(p + 1) * strip_stride + (int64_t)p * 256;      // tile (p, p + 1)
-        a.wide = cols / NB - 1;
-        a.Vr_next = Vr[(p + 1) & 1]; a.Vt_next = Vt[(p + 1) & 1];
-        a.Tnext = ws.Tmat + (int64_t)(p + 1) * NB * NB; a.rdiag_next = ws.rdiag + c0 + NB;
-        a.m_next = m - NB;
-        GELO_TRY(launch_qr_step(a, s));
+        a.block_done = (p + 1 == block_end) ? 1 : 0;
+        a.strip_stride = strip_stride;
+        a.nb_single = nbr - p; a.nb_block = nbr - p0;
+        const int first_row_block = a.block_done ? p0 : p;    // where workgroup 0's strip starts
+        a.C0 = last ? ws.M : ws.M + (int64_t)(p + 1) * strip_stride + (int64_t)first_row_block * 256;
+        a.Cin = ws.M + (int64_t)(p + 2 < nbr ? p + 2 : 0) * strip_stride + (int64_t)p * 256;
+        a.Cout = ws.M + (int64_t)(p + 2 < nbr ? p + 2 : 0) * strip_stride + (int64_t)p0 * 256;
+        a.X = ws.X + (int64_t)p0 * 256;                       // tile (p0, 0)
+        a.inner = a.block_done ? 0 : block_end - (p + 2);     // the block's panels behind p + 1
+        a.outer = (a.block_done && p + 2 < nbr) ? nbr - (p + 2) : 0;
+        a.acc = a.block_done ? nbr : 0;
+        a.Vr_next = Vr_of(p + 1); a.Vt_next = Vt_of(p + 1);
+        a.Tnext = ws.Tmat + (int64_t)(p + 1) * NB * NB; a.rdiag_next = ws.rdiag + (p + 1) * NB;
+        a.m_next = last ? 0 : n_pad - (p + 1) * NB;
+        a.batch_stride = batch_stride;
+        GELO_TRY(launch_qr_step(a, count, s));
     }
     return hipSuccess;
 }

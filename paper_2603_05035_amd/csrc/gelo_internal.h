@@ -221,8 +221,9 @@ void factor_workspace_carve(void* base, int n, FactorWorkspace* ws);
 // ws.M holds an n x n matrix in 16 x 16 tiles (qr_tile_index with n_pad / 16 tile rows; what lies
 // beyond n need not be initialised).  On return ws.X holds Q^T, the transpose of the orthogonal
 // factor of its Householder QR, in the same tiled layout (identity in the padding block), and
-// ws.rdiag the diagonal of R.
-hipError_t householder_qr(const FactorWorkspace& ws, int n, hipStream_t stream);
+// ws.rdiag the diagonal of R.  `count` > 1 factorises that many matrices side by side in the same launches (grid y):
+// matrix i's workspace is the one carved at `batch_stride` floats times i behind ws's (same n for all).
+hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t batch_stride, hipStream_t stream);
 // ws.M holds an n_pad x n_pad matrix with an identity block in the padding.  On return ws.X holds
 // its inverse (via row-pivoted LU), *ws.flag != 0 if a zero pivot was met.
 hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t stream);

@@ -258,8 +258,44 @@ def test_batched_draw_equals_single_draws(ctx):
             g.gelo_sample_mixing_batch(ctx, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, first + count - 1, 4)
         assert g.STATUS_NAMES[e.value.status] == "GELO_EREUSE"
         with pytest.raises(g.GeloError) as e:
-            g.gelo_sample_mixing_batch(ctx, g.GELO_ORTHOGONAL, 200, 0, d, g.GELO_BF16, 5000, 4)
-        assert g.STATUS_NAMES[e.value.status] == "GELO_ESHAPE"
+            g.gelo_sample_mixing_batch(ctx, g.GELO_GAUSSIAN, nd, k, d, g.GELO_BF16, 5000, 4)
+        assert g.STATUS_NAMES[e.value.status] == "GELO_EINVAL"
+    finally:
+        g.gelo_destroy(single)
+
+
+@pytest.mark.parametrize("nd,k,d,count,picks", [(290, 10, 256, 3, (0, 2)), (129, 0, 64, 19, (0, 15, 16, 18)),
+                                                (2048, 102, 4096, 10, (0, 7, 9))])
+def test_batched_draw_of_large_matrices_equals_single_draws(ctx, nd, k, d, count, picks):
+    """Beyond the one-launch size the factorisations of a batched draw share their launches, sixteen at a time
+    (count = 19: a full group and a ragged one).  Object i is still, bit for bit, the single draw of its batch id;
+    one of them is compared with the oracle's A as well."""
+    first = 900
+    n = nd + k
+    single = g.gelo_create(0, 0xC0FFEE, allow_batch_reuse=False)
+    try:
+        ms = g.gelo_sample_mixing_batch(ctx, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, first, count)
+        assert len(ms) == count
+        for i in picks:
+            m1 = g.gelo_sample_mixing(single, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=first + i)
+            H = dev(wl.make_hidden(nd, d, 78, 4), "bf16")
+            U0 = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+            U1 = torch.empty_like(U0)
+            g.gelo_mix(ctx, ms[i], H, U0)
+            g.gelo_mix(single, m1, H, U1)
+            A0, Ai0, S0, _, _ = g.gelo_mixing_export(ctx, ms[i], n, k, d)
+            A1, Ai1, S1, _, _ = g.gelo_mixing_export(single, m1, n, k, d)
+            torch.cuda.synchronize()
+            assert torch.equal(A0, A1) and torch.equal(Ai0, Ai1), f"object {i}"
+            assert (k == 0 or torch.equal(S0, S1)) and torch.equal(U0, U1), f"object {i}: shield rows or product differ"
+            g.gelo_mixing_free(single, m1)
+            if i == picks[-1] and n <= 400:
+                check_orthogonal_A(f64(A0), 0xC0FFEE, first + i, n, compare_elements=True)
+        for m in ms:
+            g.gelo_mixing_free(ctx, m)
+        with pytest.raises(g.GeloError) as e:
+            g.gelo_sample_mixing(ctx, g.GELO_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=first + count - 1)
+        assert g.STATUS_NAMES[e.value.status] == "GELO_EREUSE"
     finally:
         g.gelo_destroy(single)
 
