@@ -74,8 +74,8 @@ def run_composite(args, torch, np, g, wl):
     name = args.workload
     parts = [wl.WORKLOADS[x] for x in COMPOSITE[name]]
     L = len(parts)
-    K = args.steps if args.steps_given else {"llama7b_bf16_layer": 50, "prefill_sweep_bf16": 2, "decode_sweep_bf16": 128}[name]
-    Wm = args.warmup if args.warmup_given else {"llama7b_bf16_layer": 10, "prefill_sweep_bf16": 1, "decode_sweep_bf16": 8}[name]
+    K = args.steps if args.steps_given else {"llama7b_bf16_layer": 48, "prefill_sweep_bf16": 2, "decode_sweep_bf16": 128}[name]
+    Wm = args.warmup if args.warmup_given else {"llama7b_bf16_layer": 16, "prefill_sweep_bf16": 1, "decode_sweep_bf16": 8}[name]
     dt = torch.bfloat16
     # inputs resident in HBM: one weight per layer; hidden states per layer (the decode sweep reuses its 32
     # hidden-state buffers across steps: the chain does not look at the values)
@@ -133,6 +133,53 @@ def run_composite(args, torch, np, g, wl):
             for m in ring[slot]:
                 g.gelo_mixing_free(ctxs[slot], m)
         i = (step + depth) * L
+    elif all(w.kind == g.GELO_ORTHOGONAL and (w.n_data, w.k_shield, w.d) == (parts[0].n_data, parts[0].k_shield, parts[0].d)
+             for w in parts):
+        # every chain takes an ORTHOGONAL A of one shape: batched draws (`group` matrices per call, their factorisations
+        # side by side) on side streams, `rings` groups alive - one being consumed while the others are drawn
+        w0 = parts[0]
+        group = next(b for b in (16, 12, 8, 6, 4, 2, 1) if (K * L) % b == 0 and (Wm * L) % b == 0)
+        rings = 3
+        depth = group * rings
+        side = [torch.cuda.Stream() for _ in range(rings)]
+        ctxs = [g.gelo_create(0, 0xBE00 + i, allow_batch_reuse=False) for i in range(rings)]
+        for c in ctxs:                                   # sizes known ahead: nothing allocates inside the timed region
+            g.gelo_reserve(c, w0.kind, g.GELO_BF16, w0.n_data, w0.k_shield, w0.d, 0, 1, group)
+        ring = [None] * rings
+        nxt = [0]
+
+        def draw_group(r):
+            ring[r] = g.gelo_sample_mixing_batch(ctxs[r], w0.kind, w0.n_data, w0.k_shield, w0.d, g.GELO_BF16, nxt[0], group,
+                                                 stream=side[r])
+            nxt[0] += group
+
+        def chain(i):
+            r, j, l = (i // group) % rings, i % group, i % L
+            w = parts[l]
+            m = ring[r][j]
+            u, y, z = views(w)
+            g.gelo_mix(ctxs[r], m, Hs[l], u, w.shield_scale)
+            g.gelo_project(ctxs[r], u, Ws[l], y)
+            g.gelo_unmix(ctxs[r], m, y, z)
+            g.gelo_mixing_free(ctxs[r], m)
+            if j == group - 1:
+                draw_group(r)
+
+        for r in range(rings):
+            draw_group(r)
+        i = 0
+        for _ in range(Wm * L):
+            chain(i); i += 1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K * L):
+            chain(i); i += 1
+        torch.cuda.synchronize()
+        t_step = (time.perf_counter() - t0) / K
+        for r in range(rings):
+            for m in ring[r]:
+                g.gelo_mixing_free(ctxs[r], m)
+        i = nxt[0]
     else:
         side = [torch.cuda.Stream() for _ in range(depth)]
         ctxs = [g.gelo_create(0, 0xBE00 + i, allow_batch_reuse=False) for i in range(depth)]
