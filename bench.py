@@ -353,13 +353,14 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="llama7b_bf16_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--draw-batch", type=int, default=32, help="ORTHOGONAL: mixing matrices per batched draw (its factorisations run side by side)")
     ap.add_argument("--pipeline", type=int, default=24, help="mixing matrices drawn ahead on side streams")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run a plain elementwise copy of known size (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     args.steps_given, args.warmup_given = args.steps is not None, args.warmup is not None
-    args.steps = 48 if args.steps is None else args.steps
-    args.warmup = 16 if args.warmup is None else args.warmup
+    args.steps = 64 if args.steps is None else args.steps
+    args.warmup = 32 if args.warmup is None else args.warmup
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this library runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         return 2
@@ -413,7 +414,7 @@ def main() -> int:
         # batched draws: `group` matrices per call (their factorisations share every launch), `rings` groups alive:
         # one being consumed while the others are drawn on side streams.  The group size divides K and W, so the
         # timed region issues exactly K draws and K chains.
-        group = next(b for b in (16, 12, 8, 6, 5, 4, 3, 2, 1) if K % b == 0 and Wm % b == 0 and b <= max(1, args.pipeline))
+        group = next(b for b in (32, 24, 16, 12, 8, 6, 5, 4, 3, 2, 1) if K % b == 0 and Wm % b == 0 and b <= max(1, args.draw_batch))
         rings = 3
         depth = group * rings
         side = [torch.cuda.Stream() for _ in range(rings)]

@@ -145,7 +145,7 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
  * a decode step's worth, or the next few prefill batches, can be drawn ahead together.  GELO_ORTHOGONAL only.
  *  n <= GELO_STATIC_MAX_N  ONE launch draws all of them (at this size a fresh A per layer-step costs more in
  *                          launch latency than in work);
- *  larger n                up to 16 factorisations (fewer where 16 workspaces would exceed 4 GiB) share every
+ *  larger n                up to 32 factorisations (fewer where 32 workspaces would exceed 4 GiB) share every
  *                          launch of the Householder QR, each in a workspace of its own (the chain of panel factorisations leaves most of the chip idle when one
  *                          matrix is factorised alone; side by side the strips of all of them fill it).
  * Object i is what gelo_sample_mixing returns for its batch id, bit for bit.  out: HOST array of `count`

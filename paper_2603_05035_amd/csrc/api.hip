@@ -26,7 +26,7 @@ constexpr uint32_t kStreamMixing = 0, kStreamShield = 1, kStreamPerturb = 2;
 // side on library-owned streams, each in a workspace of its own, and the first acceptable one in
 // attempt order wins - the same matrix a one-at-a-time loop would return.
 constexpr int kLanes = 4;
-constexpr int kQrSideBySide = 16;       // batched ORTHOGONAL draws: factorisations that share each launch, at most
+constexpr int kQrSideBySide = 32;       // batched ORTHOGONAL draws: factorisations that share each launch, at most
 constexpr size_t kQrSideBytes = (size_t)4 << 30;   // ... and no more of them than fit this much workspace
 // how many factorisations of an n x n matrix a batched draw of `count` runs side by side
 static int qr_side_by_side(int count, size_t ws_bytes) {

@@ -264,11 +264,11 @@ def test_batched_draw_equals_single_draws(ctx):
         g.gelo_destroy(single)
 
 
-@pytest.mark.parametrize("nd,k,d,count,picks", [(290, 10, 256, 3, (0, 2)), (129, 0, 64, 19, (0, 15, 16, 18)),
+@pytest.mark.parametrize("nd,k,d,count,picks", [(290, 10, 256, 3, (0, 2)), (129, 0, 64, 37, (0, 31, 32, 36)),
                                                 (2048, 102, 4096, 10, (0, 7, 9))])
 def test_batched_draw_of_large_matrices_equals_single_draws(ctx, nd, k, d, count, picks):
-    """Beyond the one-launch size the factorisations of a batched draw share their launches, sixteen at a time
-    (count = 19: a full group and a ragged one).  Object i is still, bit for bit, the single draw of its batch id;
+    """Beyond the one-launch size the factorisations of a batched draw share their launches, 32 at a time
+    (count = 37: a full group and a ragged one).  Object i is still, bit for bit, the single draw of its batch id;
     one of them is compared with the oracle's A as well."""
     first = 900
     n = nd + k
