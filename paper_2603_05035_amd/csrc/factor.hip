@@ -76,8 +76,8 @@ __device__ __forceinline__ float lane_value(float v) {
 }
 
 // ------------------------------------------------------------------ QR panel --
-// Factorises the m x 16 panel at Mp (row stride ld) in place (R on and above the diagonal,
-// reflector tails below, as in LAPACK), and writes for the block reflector I - V T V^T:
+// Factorises the m x 16 panel at Mp (read only; R on and above the diagonal and the reflector tails below, as
+// in LAPACK, exist in registers only) and writes for the block reflector I - V T V^T:
 // Vc = V with explicit unit diagonal and zeros above (m x 16, row stride ld), T (16 x 16,
 // dense row-major at Tg) and rdiag[0:16] = diag(R).  Reflector j: beta = -sign(alpha) ||x||,
 // tau = (beta - alpha)/beta, v = x / (alpha - beta) below the diagonal; a zero tail gets tau = 0.
@@ -199,7 +199,8 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, float* Vr, float* Vt, f
                 make_float4(Trow[c4 * 4], Trow[c4 * 4 + 1], Trow[c4 * 4 + 2], Trow[c4 * 4 + 3]);
     }
 
-    // write back the factored panel and the clean reflector block
+    // write the clean reflector block in its two layouts (the factored panel itself - R and the reflector tails -
+    // is not stored: nobody reads these columns again, the diagonal of R went to rdiag)
 #pragma unroll
     for (int i = 0; i < R; ++i) {
         const int r = tid + i * NTHR;
@@ -211,7 +212,6 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, float* Vr, float* Vt, f
                 for (int e = 0; e < 4; ++e) {
                     const int c = c4 * 4 + e;
                     v[e] = r > c ? P[i][c] : (r == c ? 1.f : 0.f);
-                    Mp[(int64_t)(r >> 4) * 256 + c * 16 + (r & 15)] = P[i][c];
                     Vt[(int64_t)(r >> 4) * 256 + c * 16 + (r & 15)] = v[e];
                 }
                 *reinterpret_cast<float4*>(Vr + (int64_t)r * NB + c4 * 4) = make_float4(v[0], v[1], v[2], v[3]);
@@ -246,8 +246,7 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 struct Reflector { const float* Vr; const float* Vt; const float* T; int shift; };
 // (the pointers are those of the first matrix of a batch; `off` below is the distance to this workgroup's matrix)
 
-// strips per workgroup where a finished block of panels is applied: two where the registers allow it
-constexpr int strips_per_workgroup(int NBLK) { return NBLK == 20 ? 2 : 1; }
+constexpr int kPanelRows256 = 2560;      // panels of up to this many rows are factorised by 256 threads, longer ones by 512
 constexpr int kMaxDelay = 4;             // most reflectors one strip pass applies (panels per block of the delayed update)
 
 // a tile of zeros: what a strip block reads in place of a reflector block that does not exist for it
@@ -418,9 +417,10 @@ __device__ __forceinline__ void reflect_strip_body(const Reflector* refl, int co
 // identity, ends as Q^T) - is read and written ONCE per block, by strips that apply the block's D reflectors in
 // a row while they hold their columns in registers.  That divides the memory traffic of the factorisation,
 // which is what bounds several factorisations running side by side, by almost D.
-//   workgroup 0          updates the 16 columns of panel p + 1 - with reflector p alone inside a block, with the
-//                        whole finished block when panel p + 1 starts a new one - then factorises them;
-//   `inner` workgroups   (inside a block) apply reflector p to the block's later panels;
+//   workgroup 0          applies reflector p to the 16 columns of panel p + 1, then factorises them;
+//   `inner` workgroups   (inside a block) apply reflector p to the block's later panels and to the first panel
+//                        of the next block: its columns then lack only the newest reflector when workgroup 0
+//                        gets to them, as everywhere else on the chain;
 //   `outer` + `acc`      (a block has just been finished) apply its reflectors to the columns beyond panel
 //                        p + 1 and to all columns of X.
 // Every strip reads only reflectors and its own columns; panel p + 1 writes its own columns, reflector buffers
@@ -430,7 +430,7 @@ struct QrStepArgs {
     Reflector refl[kMaxDelay];           // the current block's reflectors so far; shift = position in the block
     int pending;                         // how many of them (the newest is refl[pending - 1], reflector p)
     int block_done;                      // panel p is the last of its block (or of the matrix)
-    float* C0;                           // the columns of panel p + 1: tile (first row block, column block p + 1)
+    float* C0;                           // the columns of panel p + 1: tile (row block p, column block p + 1)
     float* Cin;                          // tile (row block p, column block p + 2): `inner` strips from here
     float* Cout;                         // tile (row block of the block's first panel, column block p + 2): `outer` strips
     float* X;                            // tile (row block of the block's first panel, column block 0): `acc` strips
@@ -442,7 +442,7 @@ struct QrStepArgs {
     int64_t batch_stride;                // floats from one matrix's workspace to the next one's (grid y = matrix)
 };
 
-template <int NTHR, int R, int NBLK>
+template <int NTHR, int R, int NBLK, int NS>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(NBLK >= 20 ? 2 : 4, NBLK >= 20 ? 2 : 4)))
 void qr_step_kernel(QrStepArgs a) {
     const int b = blockIdx.x;
@@ -450,8 +450,7 @@ void qr_step_kernel(QrStepArgs a) {
     const Reflector* newest = a.refl + (a.pending - 1);
     if (b == 0) {
         if (a.m_next <= 0) return;
-        if (a.block_done) reflect_strip_body<NBLK, 1>(a.refl, a.pending, off, 1, a.C0 + off, 0, 1, a.nb_block);
-        else {
+        {
             Reflector single = *newest; single.shift = 0;
             reflect_strip_body<NBLK, 1>(&single, 1, off, 1, a.C0 + off, 0, 1, a.nb_single);
         }
@@ -459,7 +458,7 @@ void qr_step_kernel(QrStepArgs a) {
         __syncthreads();                 // the strip's stores are visible to the whole workgroup
         if (threadIdx.x >= NTHR) return;
         // the panel starts one tile (16 rows) below reflector p's first row
-        float* Mp = a.C0 + off + 256 * (a.block_done ? a.pending : 1);
+        float* Mp = a.C0 + off + 256;
         qr_panel_body<NTHR, R>(Mp, a.Vr_next + off, a.Vt_next + off, a.Tnext + off, a.rdiag_next + off, a.m_next);
         return;
     }
@@ -469,7 +468,6 @@ void qr_step_kernel(QrStepArgs a) {
         return;
     }
     // the strips behind the block and those of X, NS neighbours per workgroup
-    constexpr int NS = strips_per_workgroup(NBLK);
     const int outer_wgs = (a.outer + NS - 1) / NS;
     int idx = b - 1 - a.inner, range = a.outer;
     float* Cs = a.Cout;
@@ -574,9 +572,18 @@ namespace {
 
 template <int NTHR, int R, int NBLK>
 hipError_t launch_qr_step_t(const QrStepArgs& a, int count, hipStream_t s) {
-    constexpr int NS = strips_per_workgroup(NBLK);
-    const int wgs = 1 + a.inner + (a.outer + NS - 1) / NS + (a.acc + NS - 1) / NS;
-    hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK>), dim3(wgs, count), dim3(512), 0, s, a);
+    // Strips per workgroup where a finished block of panels is applied.  Two (where the registers allow it) take
+    // 8 time units against 5 for one strip; what decides is how many times the launch fills the 256 compute
+    // units either way: many strips (several matrices side by side) favour pairs, one matrix's few strips
+    // singles that all run at once.
+    if constexpr (NBLK == 20) {
+        const int64_t singles = a.outer + a.acc, pairs = (a.outer + 1) / 2 + (a.acc + 1) / 2;
+        if (singles > 0 && (count * pairs + 255) / 256 * 8 < (count * singles + 255) / 256 * 5) {
+            hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK, 2>), dim3((unsigned)(1 + a.inner + pairs), count), dim3(512), 0, s, a);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK, 1>), dim3(1 + a.inner + a.outer + a.acc, count), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 
@@ -601,18 +608,23 @@ hipError_t launch_qr_step(const QrStepArgs& a, int count, hipStream_t s) {
     const int longest = a.block_done ? a.nb_block : a.nb_single;
     const int per_wave = (longest + 7) / 8;
     const int m = a.m_next;
-    if (m <= 1024) {
+    // The per-column work of a panel that does not grow with its rows (reduction, broadcast, the scalar chain)
+    // is done by every wave: four waves, one per SIMD, with more rows each beat eight up to kPanelRows256 rows.
+    if (m <= kPanelRows256) {
         switch ((m + 255) / 256) {
             case 0: case 1: return launch_qr_step_r<256, 1>(per_wave, a, count, s);
             case 2: return launch_qr_step_r<256, 2>(per_wave, a, count, s);
             case 3: return launch_qr_step_r<256, 3>(per_wave, a, count, s);
-            default: return launch_qr_step_r<256, 4>(per_wave, a, count, s);
+            case 4: return launch_qr_step_r<256, 4>(per_wave, a, count, s);
+            case 5: return launch_qr_step_r<256, 5>(per_wave, a, count, s);
+            case 6: return launch_qr_step_r<256, 6>(per_wave, a, count, s);
+            case 7: return launch_qr_step_r<256, 7>(per_wave, a, count, s);
+            case 8: return launch_qr_step_r<256, 8>(per_wave, a, count, s);
+            case 9: return launch_qr_step_r<256, 9>(per_wave, a, count, s);
+            default: return launch_qr_step_r<256, 10>(per_wave, a, count, s);
         }
     }
     switch ((m + 511) / 512) {
-        case 3: return launch_qr_step_r<512, 3>(per_wave, a, count, s);
-        case 4: return launch_qr_step_r<512, 4>(per_wave, a, count, s);
-        case 5: return launch_qr_step_r<512, 5>(per_wave, a, count, s);
         case 6: return launch_qr_step_r<512, 6>(per_wave, a, count, s);
         case 7: return launch_qr_step_r<512, 7>(per_wave, a, count, s);
         case 8: return launch_qr_step_r<512, 8>(per_wave, a, count, s);
@@ -646,7 +658,7 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
     // panel 0 on its own; then one launch per step
     {
         const int m = n_pad;
-        if (m <= 1024) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, Vr_of(0), Vt_of(0), ws.Tmat, ws.rdiag, m, count, batch_stride, s));
+        if (m <= kPanelRows256) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, Vr_of(0), Vt_of(0), ws.Tmat, ws.rdiag, m, count, batch_stride, s));
         else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M, Vr_of(0), Vt_of(0), ws.Tmat, ws.rdiag, m, count, batch_stride, s));
     }
     for (int p = 0; p < panels; ++p) {
@@ -662,12 +674,12 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
         a.block_done = (p + 1 == block_end) ? 1 : 0;
         a.strip_stride = strip_stride;
         a.nb_single = nbr - p; a.nb_block = nbr - p0;
-        const int first_row_block = a.block_done ? p0 : p;    // where workgroup 0's strip starts
-        a.C0 = last ? ws.M : ws.M + (int64_t)(p + 1) * strip_stride + (int64_t)first_row_block * 256;
+        a.C0 = last ? ws.M : ws.M + (int64_t)(p + 1) * strip_stride + (int64_t)p * 256;
         a.Cin = ws.M + (int64_t)(p + 2 < nbr ? p + 2 : 0) * strip_stride + (int64_t)p * 256;
         a.Cout = ws.M + (int64_t)(p + 2 < nbr ? p + 2 : 0) * strip_stride + (int64_t)p0 * 256;
         a.X = ws.X + (int64_t)p0 * 256;                       // tile (p0, 0)
-        a.inner = a.block_done ? 0 : block_end - (p + 2);     // the block's panels behind p + 1
+        // the block's panels behind p + 1 and the first panel of the next block
+        a.inner = a.block_done ? 0 : (block_end < nbr ? block_end : nbr - 1) - (p + 1);
         a.outer = (a.block_done && p + 2 < nbr) ? nbr - (p + 2) : 0;
         a.acc = a.block_done ? nbr : 0;
         a.Vr_next = Vr_of(p + 1); a.Vt_next = Vt_of(p + 1);
