@@ -244,6 +244,17 @@ gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* mixing, float* 
 gelo_status gelo_debug_philox_words(gelo_ctx* ctx, uint32_t stream_id, uint32_t attempt, uint64_t batch_id,
                                     uint32_t first_block, uint32_t blocks, uint32_t* words, void* stream);
 gelo_status gelo_mixing_export_table(gelo_ctx* ctx, const gelo_mixing* mixing, uint32_t* table, void* stream);
+/* Measurement aid (for the caller that reports a kernel against the matrix-core peak, as Section 4.2 style
+ * "fraction of peak" figures do): what the matrix cores of this device deliver when every wave issues nothing
+ * but independent matrix instructions from registers - v_mfma_f32_32x32x16_bf16 (fp8 = 0) or
+ * v_mfma_f32_32x32x64_f8f6f4 on E4M3 (fp8 = 1), eight accumulator tiles per wave, two waves per SIMD, as in a K
+ * step of the projection kernels; no memory traffic.  Runs one warm-up launch and `launches` (1..1000) timed
+ * launches of `iters` (1..2^20) loop passes each on `stream`, WAITS for them, and returns the mean time of one
+ * launch (HOST double) and the floating-point operations one launch executes (HOST double).  Uses the static
+ * scratch buffer of gelo_qkv_forward_static: do not overlap the two on one GPU. */
+gelo_status gelo_measure_matrix_rate(gelo_ctx* ctx, int fp8, int iters, int launches, double* seconds, double* flop,
+                                     void* stream);
+
 /* Test hook: the row quantisation gelo_project_fp8 applies to U, into caller DEVICE buffers: codes n x d bytes
  * (16-byte aligned), scales n floats. */
 gelo_status gelo_debug_quantize_rows_fp8(gelo_ctx* ctx, int n, int d, const void* U, int64_t ldu, uint8_t* codes,

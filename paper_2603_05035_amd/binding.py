@@ -52,6 +52,7 @@ SIGNATURES = {
     "gelo_prepare_weight_fp8": (c_int, [c_void_p, c_int, c_int, c_void_p, c_int64, c_void_p, c_void_p]),
     "gelo_project_fp8": (c_int, [c_void_p, c_int, c_int, c_int, c_void_p, c_int64, c_void_p, c_void_p, c_int64, c_void_p]),
     "gelo_debug_quantize_rows_fp8": (c_int, [c_void_p, c_int, c_int, c_void_p, c_int64, c_void_p, c_void_p, c_void_p]),
+    "gelo_measure_matrix_rate": (c_int, [c_void_p, c_int, c_int, c_int, POINTER(c_double), POINTER(c_double), c_void_p]),
     "gelo_debug_philox_words": (c_int, [c_void_p, c_uint32, c_uint32, c_uint64, c_uint32, c_uint32, c_void_p, c_void_p]),
     "gelo_mixing_export_table": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p]),
     "gelo_qkv_forward": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p, c_void_p, c_float,
@@ -311,6 +312,14 @@ def gelo_debug_quantize_rows_fp8(ctx, U: torch.Tensor, stream=None):
     _check(ctx, load_library().gelo_debug_quantize_rows_fp8(ctx, n, d, up, ldu, c_void_p(codes.data_ptr()),
                                                             c_void_p(scales.data_ptr()), _stream(stream)))
     return codes, scales
+
+
+def gelo_measure_matrix_rate(ctx, fp8: bool, iters: int = 2000, launches: int = 5, stream=None):
+    """(seconds per launch, FLOP per launch) of the matrix-instruction-only kernel; waits for it."""
+    sec, flop = c_double(0.0), c_double(0.0)
+    _check(ctx, load_library().gelo_measure_matrix_rate(ctx, 1 if fp8 else 0, iters, launches, byref(sec), byref(flop),
+                                                        _stream(stream)))
+    return sec.value, flop.value
 
 
 def gelo_debug_philox_words(ctx, stream_id: int, attempt: int, batch_id: int, first_block: int, blocks: int,

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libgelo.so")
-SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_f32.hip", "sampler.hip", "factor.hip", "lu.hip", "structured.hip", "small.hip", "gemm_fp8.hip"]
+SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_f32.hip", "sampler.hip", "factor.hip", "lu.hip", "structured.hip", "small.hip", "gemm_fp8.hip", "calibrate.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -1074,4 +1074,31 @@ gelo_status gelo_debug_quantize_rows_fp8(gelo_ctx* ctx, int n, int d, const void
     return GELO_OK;
 }
 
+gelo_status gelo_measure_matrix_rate(gelo_ctx* ctx, int fp8, int iters, int launches, double* seconds, double* flop, void* stream) {
+    if (!ctx) return GELO_EINVAL;
+    if (!seconds || !flop) return fail(ctx, GELO_EINVAL, "seconds and flop must not be NULL");
+    if (iters < 1 || iters > (1 << 20) || launches < 1 || launches > 1000 || (fp8 != 0 && fp8 != 1))
+        return fail(ctx, GELO_EINVAL, "fp8=%d iters=%d launches=%d", fp8, iters, launches);
+    if (!ctx->static_scratch || matrix_rate_scratch_bytes() > kStaticScratchBytes) return fail(ctx, GELO_ESTATE, "no scratch buffer on this device");
+    GELO_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    GELO_HIP(ctx, hipEventCreate(&e0));
+    hipError_t e = hipEventCreate(&e1);
+    double f = 0.0;
+    if (e == hipSuccess) e = matrix_rate_launch(fp8, iters, (float*)ctx->static_scratch, &f, s);      // clocks settle under the load
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int i = 0; i < launches && e == hipSuccess; ++i) e = matrix_rate_launch(fp8, iters, (float*)ctx->static_scratch, &f, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return hip_fail(ctx, e, "matrix rate measurement");
+    *seconds = (double)ms * 1e-3 / launches;
+    *flop = f;
+    return GELO_OK;
+}
+
 }  // extern "C"

@@ -128,6 +128,9 @@ __host__ __device__ inline int64_t qr_tile_index(int r, int c, int tile_rows) {
 hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale,
                        int tiled, hipStream_t stream);
 // words[4 i .. 4 i + 3] = the four output words of Philox block first_block + i (counter word 0), 16-byte aligned
+// calibrate.hip: matrix instructions from registers only (0: bf16 32x32x16, 1: E4M3 32x32x64)
+size_t matrix_rate_scratch_bytes();
+hipError_t matrix_rate_launch(int fp8, int iters, float* scratch, double* flop, hipStream_t stream);
 hipError_t philox_words(uint32_t* words, uint32_t first_block, uint32_t blocks, PhiloxStream ps, hipStream_t stream);
 // GS[k x d] (pitch d) = N(0,1) with fill_normal's element order, gsnorm[i] = || GS[i, :] ||_2; d % 8 == 0
 hipError_t shield_directions(float* GS, int k, int d, PhiloxStream ps, float* gsnorm, hipStream_t stream);

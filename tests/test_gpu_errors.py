@@ -225,3 +225,14 @@ def test_condition_budget_exhausted(ctx):
     # the failed call consumed nothing: the batch id can still be used
     m = g.gelo_sample_mixing(ctx, g.GELO_GAUSSIAN, 64, 0, 64, g.GELO_F32, 1e6, 3, 30)
     g.gelo_mixing_free(ctx, m)
+
+
+def test_matrix_rate_measurement(ctx):
+    """The measurement aid: a plausible rate for both instruction kinds (between a fifth of the published peak and
+    the peak itself), the stated operation count, and argument checks."""
+    for fp8, peak in ((False, 2.5e15), (True, 5.0e15)):
+        sec, flop = g.gelo_measure_matrix_rate(ctx, fp8, iters=500, launches=3)
+        assert flop == 2.0 * 32 * 32 * (64 if fp8 else 16) * 32 * 500 * 8 * 256
+        assert 0.2 * peak < flop / sec <= 1.02 * peak, (fp8, flop / sec)
+    assert status_of(g.gelo_measure_matrix_rate, ctx, False, 0, 3) == "GELO_EINVAL"
+    assert status_of(g.gelo_measure_matrix_rate, ctx, False, 10, 0) == "GELO_EINVAL"
