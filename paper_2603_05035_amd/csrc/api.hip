@@ -326,7 +326,8 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
     if (hipHostMalloc((void**)&ctx->host_scalars, 64, hipHostMallocDefault) != hipSuccess) { delete ctx; return GELO_ENOMEM; }
     ctx->host_flag = (int*)(ctx->host_scalars + 8);
     if (gemm_bf16_init() != hipSuccess || gemm_f32_init() != hipSuccess || lu_init() != hipSuccess ||
-        structured_init() != hipSuccess || small_init() != hipSuccess || gemm_fp8_init() != hipSuccess) {
+        structured_init() != hipSuccess || small_init() != hipSuccess || gemm_fp8_init() != hipSuccess ||
+        factor_init() != hipSuccess || sampler_init() != hipSuccess) {
         hipHostFree(ctx->host_scalars); delete ctx; return GELO_EHIP;
     }
     *out = ctx;

@@ -246,25 +246,24 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 struct Reflector { const float* Vr; const float* Vt; const float* T; int shift; };
 // (the pointers are those of the first matrix of a batch; `off` below is the distance to this workgroup's matrix)
 
-constexpr int kPanelRows256 = 2560;      // panels of up to this many rows are factorised by 256 threads, longer ones by 512
+constexpr int kBulkFromCount = 2;         // from this many factorisations side by side the block strips get launches of their own
+constexpr int kPanelRows256 = 1024;      // panels of up to this many rows are factorised by 256 threads, longer ones by 512
 constexpr int kMaxDelay = 4;             // most reflectors one strip pass applies (panels per block of the delayed update)
 
 // a tile of zeros: what a strip block reads in place of a reflector block that does not exist for it
 __device__ __attribute__((aligned(1024))) float g_zero_tile[256];
 
-// NS = 1 or 2 neighbouring 16-column strips per workgroup (`strips` of them exist: the second may be missing at the
-// end of a range; the tiles of neighbouring strips lie `strip_stride` floats apart).  With two strips every
-// reflector block a wave fetches feeds twice the matrix instructions: the reflectors come from the L2, whose
-// bandwidth all strips of a launch share, and at one strip per workgroup that bandwidth - not the matrix
-// cores - bounds a launch.  Each strip's arithmetic is the same whichever way the strips are paired.
+// NS neighbouring 16-column strips per workgroup (`strips` of them exist: the last may be missing at the end of a
+// range; the tiles of neighbouring strips lie `strip_stride` floats apart).  With two strips every reflector block a
+// wave fetches feeds twice the matrix instructions, at twice the registers; measured equal to two one-strip
+// workgroups per compute unit (reflect_strip_lds_body), which is what the launches of many matrices use, so only
+// NS = 1 is instantiated at present.  Each strip's arithmetic is the same whichever way strips are grouped.
 template <int NBLK, int NS>
-__device__ __forceinline__ void reflect_strip_body(const Reflector* refl, int count, int64_t off, int t_transposed, float* Cs,
+__device__ __forceinline__ void reflect_strip_body(const Reflector* refl, int count, int64_t off, float* Cs,
                                                    int64_t strip_stride, int strips, int nblocks) {
     constexpr int NC = NB * NS;                              // columns per workgroup
-    __shared__ float Wp[8][NB][NC];
-    __shared__ float Ws[NB][NC];
-    __shared__ float Wn[NB][NC];
-    __shared__ float Ts[NB][NB];
+    __shared__ float Wp[2][8][NB][NC];                       // the waves' partial W, alternating between reflectors
+    __shared__ float Ts[2][NB][NB];
     // the wave index as a scalar: block numbers and their offsets then live in scalar registers
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
@@ -338,6 +337,7 @@ __device__ __forceinline__ void reflect_strip_body(const Reflector* refl, int co
             for (int k = 0; k < GRP; ++k) {
                 const int b = grp * GRP + k;
                 const f32x4_t a = va[grp & 1][k];
+                if (wave + 8 * b > last) continue;            // a block past the end (wave-uniform): nothing to add
 #pragma unroll
                 for (int st = 0; st < NS; ++st) {
                     w0[st] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[st][b][0], w0[st], 0, 0, 0);
@@ -351,41 +351,45 @@ __device__ __forceinline__ void reflect_strip_body(const Reflector* refl, int co
             }
             request_behind(gc);
         });
-        if (tid < NB * NB) Ts[tid >> 4][tid & 15] = t_mine;
+        if (tid < NB * NB) Ts[q & 1][tid >> 4][tid & 15] = t_mine;
         if (more && tid < NB * NB) t_next = Rn.T[off + tid];
 #pragma unroll
         for (int st = 0; st < NS; ++st)
 #pragma unroll
-            for (int v = 0; v < 4; ++v) Wp[wave][4 * g + v][st * NB + c] = w0[st][v] + w1[st][v];     // accumulator row 4 g + v, column c
+            for (int v = 0; v < 4; ++v) Wp[q & 1][wave][4 * g + v][st * NB + c] = w0[st][v] + w1[st][v];     // accumulator row 4 g + v, column c
         __syncthreads();
-        if (tid < NB * NC) {
-            const int i = tid / NC, cc = tid % NC;
-            float sum = Wp[0][i][cc];
-#pragma unroll
-            for (int w = 1; w < 8; ++w) sum += Wp[w][i][cc];
-            Ws[i][cc] = sum;
-        }
-        __syncthreads();
-        if (tid < NB * NC) {
-            const int i = tid / NC, cc = tid % NC;
-            float o = 0.f;
-#pragma unroll
-            for (int k = 0; k < NB; ++k) o = fmaf(t_transposed ? Ts[k][i] : Ts[i][k], Ws[k][cc], o);
-            Wn[i][cc] = -o;
-        }
-        __syncthreads();
+        // ONE barrier per reflector: every wave adds the eight partial W (in wave order) for the entries it needs as
+        // an operand and forms W' = -T^T W itself, on the matrix cores: step s contracts reflectors 4 s + kk,
+        // A = T[4 s + kk][lane % 16], B = W[4 s + kk][lane % 16]; the result arrives in the accumulator layout,
+        // which is the operand layout of the second product.  (The partial sums and the triangle alternate between
+        // two buffers: a wave may be a whole reflector ahead of another one that is still reading.)
         // C_block += V_block W': MFMA k contracts reflectors 4 kk + k; A = V[16 blk + lane % 16][4 kk + k]
         float bq[NS][4];
+        {
+            float ta[4];
 #pragma unroll
-        for (int st = 0; st < NS; ++st)
+            for (int sx = 0; sx < 4; ++sx) ta[sx] = Ts[q & 1][4 * sx + g][c];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) bq[st][k] = Wn[4 * g + k][st * NB + c];
+            for (int st = 0; st < NS; ++st) {
+                f32x4_t wn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int sx = 0; sx < 4; ++sx) {
+                    float sum = Wp[q & 1][0][4 * sx + g][st * NB + c];
+#pragma unroll
+                    for (int w = 1; w < 8; ++w) sum += Wp[q & 1][w][4 * sx + g][st * NB + c];
+                    wn = __builtin_amdgcn_mfma_f32_16x16x4f32(ta[sx], sum, wn, 0, 0, 0);
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k) bq[st][k] = -wn[k];
+            }
+        }
         static_for<NG>([&](auto gc) {
             constexpr int grp = decltype(gc)::value, j = NG + grp;
 #pragma unroll
             for (int k = 0; k < GRP; ++k) {
                 const int b = grp * GRP + k;
                 const f32x4_t a4 = va[j & 1][k];
+                if (wave + 8 * b > last) continue;
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
@@ -394,8 +398,6 @@ __device__ __forceinline__ void reflect_strip_body(const Reflector* refl, int co
             }
             request_behind(std::integral_constant<int, j>{});
         });
-        // The LDS arrays serve the next reflector too: Ts and Wp were last read before the third barrier above, Wn
-        // (read into bq right behind it) is rewritten only behind the next reflector's second barrier.
     });
 #pragma unroll
     for (int st = 0; st < NS; ++st) {
@@ -408,6 +410,169 @@ __device__ __forceinline__ void reflect_strip_body(const Reflector* refl, int co
             }
         }
     }
+}
+
+// The same strip for launches that hold nothing but strips (several factorisations side by side: see
+// householder_qr).  There the strips' own phases - read the strip, matrix instructions, write it - must overlap
+// BETWEEN workgroups of a compute unit, which takes two workgroups per unit, that is at most 128 registers per
+// lane.  So the reflector blocks do not pass through registers: each wave fetches them straight into a small
+// ring in LDS (direct-to-LDS loads; a block is one contiguous kilobyte in either layout, and lane l's 16 bytes
+// land at 16 l, which is where it reads them back as the instruction's operand).  One 16-column strip per
+// workgroup, arithmetic and summation order exactly those of reflect_strip_body.
+__device__ __forceinline__ void fetch_block_to_lds(const void* gptr, uint32_t lds_addr) {      // lds_addr wave-uniform (travels in M0)
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" :: "v"(gptr), "s"(lds_addr) : "memory", "m0");
+}
+template <int N> __device__ __forceinline__ void wait_fetches() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+
+template <int NBLK>
+__device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, int count, int64_t off, float* Cs, int nblocks) {
+    constexpr int GRP = NBLK % 2 == 0 ? 2 : 1, NG = NBLK / GRP;      // blocks per fetch group, groups per product
+    constexpr int DEPTH = 2;                                         // ring slots per wave: groups on their way or in use
+    __shared__ __attribute__((aligned(1024))) float ring[8][DEPTH][GRP][256];
+    __shared__ float Wp[2][8][NB][NB];
+    __shared__ float Ts[2][NB][NB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, g = lane >> 4;
+    float* Cl = Cs + c * 16 + 4 * g;
+    const int last = nblocks - 1;
+    f32x4_t cr[NBLK];
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        const int blk = wave + 8 * b;
+        // the strip passes through once: keep it out of the way of the reflectors, which every strip of the matrix re-reads from L2
+        const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(Cl + 256 * (blk < nblocks ? blk : last)));
+        const bool valid = blk < nblocks;
+        cr[b] = f32x4_t{valid ? v[0] : 0.f, valid ? v[1] : 0.f, valid ? v[2] : 0.f, valid ? v[3] : 0.f};
+    }
+    const uint32_t ring_addr = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)&ring[wave][0][0][0]);
+    const float* mine = &ring[wave][0][0][0] + lane * 4;                 // this lane's operand inside a block
+    const float* zero_l = g_zero_tile + c * 16 + 4 * g;
+    // Group j of reflector q (first the NG groups of the tiled layout, then the NG of the row layout) is number
+    // u = 2 NG q + j of the strip and goes to ring slot u % DEPTH.  Before a wave waits for group u it requests group
+    // u + DEPTH - 1 into the slot that group u - 1 has just left: DEPTH - 1 groups are on their way while one is
+    // in use, across the barriers and from one reflector to the next.
+    auto request = [&](const Reflector& R, auto uc) {
+        constexpr int u = decltype(uc)::value, j = u % (2 * NG), phase = j / NG, grp = j % NG;
+        const float* base = (phase == 0 ? R.Vt : R.Vr) + off + c * 16 + 4 * g;
+#pragma unroll
+        for (int k = 0; k < GRP; ++k) {
+            const int blk = wave + 8 * (grp * GRP + k), vb = blk - R.shift;
+            const float* src = (vb >= 0 && blk <= last) ? base + 256 * vb : zero_l;
+            fetch_block_to_lds(src, ring_addr + (uint32_t)(((u % DEPTH) * GRP + k) * 1024));
+        }
+    };
+    float t_next = tid < NB * NB ? refl[0].T[off + tid] : 0.f;
+    static_for<DEPTH - 1>([&](auto uc) { request(refl[0], uc); });      // 2 NG >= DEPTH - 1: all of reflector 0
+    static_for<kMaxDelay>([&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        if (q >= count) return;
+        const Reflector R = refl[q];
+        const bool more = q + 1 < count;
+        const Reflector Rn = more ? refl[q + 1] : R;
+        // Group j has landed once no more fetches are counted than those of the groups requested behind it (the
+        // counter runs in issue order; any other load of this wave in between only makes the wait longer).  Behind
+        // it are the next DEPTH - 1 groups - those of them that exist: the last reflector has no successor.
+        auto arrived = [&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            constexpr int here = (2 * NG - 1 - j) < (DEPTH - 1) ? (2 * NG - 1 - j) : (DEPTH - 1);      // behind it, same reflector
+            if (more) wait_fetches<(DEPTH - 1) * GRP>(); else wait_fetches<here * GRP>();
+        };
+        auto request_ahead = [&](auto jc) {                   // the group DEPTH - 1 places on, into the slot consumed last
+            constexpr int j = decltype(jc)::value, nj = j + DEPTH - 1;
+            if constexpr (nj < 2 * NG) request(R, std::integral_constant<int, 2 * NG * q + nj>{});
+            else if (more) request(Rn, std::integral_constant<int, 2 * NG * q + nj>{});
+        };
+        const float t_mine = t_next;
+        f32x4_t w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
+        static_for<NG>([&](auto gc) {
+            constexpr int grp = decltype(gc)::value;
+            request_ahead(gc);
+            arrived(gc);
+#pragma unroll
+            for (int k = 0; k < GRP; ++k) {
+                const int b = grp * GRP + k;
+                if (wave + 8 * b > last) continue;            // a block past the end (wave-uniform): its fetch was the zero tile
+                const f32x4_t a = *reinterpret_cast<const f32x4_t*>(mine + (((2 * NG * q + grp) % DEPTH) * GRP + k) * 256);
+                w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[b][0], w0, 0, 0, 0);
+                w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], cr[b][1], w1, 0, 0, 0);
+                w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], cr[b][2], w0, 0, 0, 0);
+                w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], cr[b][3], w1, 0, 0, 0);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the operands are in registers before their ring slot is refilled
+        });
+        if (tid < NB * NB) Ts[q & 1][tid >> 4][tid & 15] = t_mine;
+        if (more && tid < NB * NB) t_next = Rn.T[off + tid];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Wp[q & 1][wave][4 * g + v][c] = w0[v] + w1[v];
+        __syncthreads();
+        float bq[4];                                          // W' = -T^T W, formed by every wave (see reflect_strip_body)
+        {
+            f32x4_t wn = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sx = 0; sx < 4; ++sx) {
+                float sum = Wp[q & 1][0][4 * sx + g][c];
+#pragma unroll
+                for (int w = 1; w < 8; ++w) sum += Wp[q & 1][w][4 * sx + g][c];
+                wn = __builtin_amdgcn_mfma_f32_16x16x4f32(Ts[q & 1][4 * sx + g][c], sum, wn, 0, 0, 0);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) bq[k] = -wn[k];
+        }
+        static_for<NG>([&](auto gc) {
+            constexpr int grp = decltype(gc)::value, j = NG + grp;
+            request_ahead(std::integral_constant<int, j>{});
+            arrived(std::integral_constant<int, j>{});
+#pragma unroll
+            for (int k = 0; k < GRP; ++k) {
+                const int b = grp * GRP + k;
+                if (wave + 8 * b > last) continue;
+                const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(mine + (((2 * NG * q + j) % DEPTH) * GRP + k) * 256);
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[kk], bq[kk], cr[b], 0, 0, 0);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        });
+    });
+#pragma unroll
+    for (int b = 0; b < NBLK; ++b) {
+        const int blk = wave + 8 * b;
+        if (blk < nblocks) __builtin_nontemporal_store(cr[b], reinterpret_cast<f32x4_t*>(Cl + 256 * blk));
+    }
+}
+
+// A finished block of panels applied to everything behind it and to X, for `count` matrices: `outer` strips from
+// Cout, `acc` strips from X, one per workgroup.  Which workgroup takes which strip of which matrix is chosen for the
+// L2s: workgroups are dealt to the 8 accelerator dies in turn (die = workgroup number mod 8), every strip of a matrix
+// reads that matrix's reflectors (1.1 MB for a block of four) and a die's L2 holds 4 MB - so a die works through
+// whole matrices one after the other (matrices die, die + 8, ...; with fewer than 8 matrices the dies that share a
+// matrix split its strips) instead of meeting all `count` sets of reflectors at once.
+struct QrBulkArgs {
+    Reflector refl[kMaxDelay]; int pending;
+    float* Cout; float* X; int outer, acc;
+    int64_t strip_stride; int nb_block; int64_t batch_stride; int count;
+};
+// workgroups per die that the deal needs
+inline int qr_bulk_slots(int strips, int count) {
+    if (count >= 8) return (count + 7) / 8 * strips;
+    const int dies = 8 / count;                              // the fewest dies any matrix gets
+    return (strips + dies - 1) / dies;
+}
+
+template <int NBLK>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void qr_bulk_kernel(QrBulkArgs a) {
+    const int die = blockIdx.x & 7, slot = blockIdx.x >> 3, strips = a.outer + a.acc;
+    int matrix, b;
+    if (a.count >= 8) { matrix = die + 8 * (slot / strips); b = slot % strips; }
+    else {
+        matrix = die % a.count;
+        const int sharing = (8 - matrix + a.count - 1) / a.count;       // dies with die % count == matrix
+        b = slot * sharing + die / a.count;
+    }
+    if (matrix >= a.count || b >= strips) return;
+    const int64_t off = (int64_t)matrix * a.batch_stride;
+    float* Cs = b < a.outer ? a.Cout + (int64_t)b * a.strip_stride : a.X + (int64_t)(b - a.outer) * a.strip_stride;
+    reflect_strip_lds_body<NBLK>(a.refl, a.pending, off, Cs + off, a.nb_block);
 }
 
 // One launch per QR step p.  The chain of panel factorisations (one workgroup each) is the critical path, so
@@ -443,7 +608,7 @@ struct QrStepArgs {
 };
 
 template <int NTHR, int R, int NBLK, int NS>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(NBLK >= 20 ? 2 : 4, NBLK >= 20 ? 2 : 4)))
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(NBLK >= 10 ? 2 : 4, NBLK >= 10 ? 2 : 4)))
 void qr_step_kernel(QrStepArgs a) {
     const int b = blockIdx.x;
     const int64_t off = (int64_t)blockIdx.y * a.batch_stride;
@@ -452,7 +617,7 @@ void qr_step_kernel(QrStepArgs a) {
         if (a.m_next <= 0) return;
         {
             Reflector single = *newest; single.shift = 0;
-            reflect_strip_body<NBLK, 1>(&single, 1, off, 1, a.C0 + off, 0, 1, a.nb_single);
+            reflect_strip_body<NBLK, 1>(&single, 1, off, a.C0 + off, 0, 1, a.nb_single);
         }
         __threadfence_block();
         __syncthreads();                 // the strip's stores are visible to the whole workgroup
@@ -464,7 +629,7 @@ void qr_step_kernel(QrStepArgs a) {
     }
     if (b <= a.inner) {
         Reflector single = *newest; single.shift = 0;
-        reflect_strip_body<NBLK, 1>(&single, 1, off, 1, a.Cin + off + (int64_t)(b - 1) * a.strip_stride, 0, 1, a.nb_single);
+        reflect_strip_body<NBLK, 1>(&single, 1, off, a.Cin + off + (int64_t)(b - 1) * a.strip_stride, 0, 1, a.nb_single);
         return;
     }
     // the strips behind the block and those of X, NS neighbours per workgroup
@@ -473,7 +638,7 @@ void qr_step_kernel(QrStepArgs a) {
     float* Cs = a.Cout;
     if (idx >= outer_wgs) { idx -= outer_wgs; range = a.acc; Cs = a.X; }
     const int first = idx * NS, strips = range - first < NS ? range - first : NS;
-    reflect_strip_body<NBLK, NS>(a.refl, a.pending, off, 1, Cs + off + (int64_t)first * a.strip_stride, a.strip_stride, strips, a.nb_block);
+    reflect_strip_body<NBLK, NS>(a.refl, a.pending, off, Cs + off + (int64_t)first * a.strip_stride, a.strip_stride, strips, a.nb_block);
 }
 
 // zeroes what lies beyond n x n of the tiled matrix M (n_pad x n_pad) and sets the tiled X to the identity
@@ -572,17 +737,6 @@ namespace {
 
 template <int NTHR, int R, int NBLK>
 hipError_t launch_qr_step_t(const QrStepArgs& a, int count, hipStream_t s) {
-    // Strips per workgroup where a finished block of panels is applied.  Two (where the registers allow it) take
-    // 8 time units against 5 for one strip; what decides is how many times the launch fills the 256 compute
-    // units either way: many strips (several matrices side by side) favour pairs, one matrix's few strips
-    // singles that all run at once.
-    if constexpr (NBLK == 20) {
-        const int64_t singles = a.outer + a.acc, pairs = (a.outer + 1) / 2 + (a.acc + 1) / 2;
-        if (singles > 0 && (count * pairs + 255) / 256 * 8 < (count * singles + 255) / 256 * 5) {
-            hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK, 2>), dim3((unsigned)(1 + a.inner + pairs), count), dim3(512), 0, s, a);
-            return hipGetLastError();
-        }
-    }
     hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK, 1>), dim3(1 + a.inner + a.outer + a.acc, count), dim3(512), 0, s, a);
     return hipGetLastError();
 }
@@ -604,27 +758,40 @@ hipError_t launch_qr_step_r(int per_wave, const QrStepArgs& a, int count, hipStr
     return hipErrorInvalidValue;
 }
 
+template <int NBLK>
+hipError_t launch_qr_bulk_t(const QrBulkArgs& b, int count, hipStream_t s) {
+    hipLaunchKernelGGL((qr_bulk_kernel<NBLK>), dim3(8 * qr_bulk_slots(b.outer + b.acc, count)), dim3(512), 0, s, b);
+    return hipGetLastError();
+}
+
+// strips of at most 160 blocks only (20 per wave: what fits 128 registers)
+constexpr int kBulkMaxBlocks = 160;
+hipError_t launch_qr_bulk(const QrBulkArgs& b, int count, hipStream_t s) {
+    const int per_wave = (b.nb_block + 7) / 8;
+    if (per_wave <= 5) return launch_qr_bulk_t<5>(b, count, s);
+    if (per_wave <= 10) return launch_qr_bulk_t<10>(b, count, s);
+    if (per_wave <= 20) return launch_qr_bulk_t<20>(b, count, s);
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_qr_step(const QrStepArgs& a, int count, hipStream_t s) {
-    const int longest = a.block_done ? a.nb_block : a.nb_single;
+    const int longest = (a.block_done && a.outer + a.acc > 0) ? a.nb_block : a.nb_single;
     const int per_wave = (longest + 7) / 8;
     const int m = a.m_next;
-    // The per-column work of a panel that does not grow with its rows (reduction, broadcast, the scalar chain)
-    // is done by every wave: four waves, one per SIMD, with more rows each beat eight up to kPanelRows256 rows.
+    // (256 or 512 threads per panel made no difference at 2150 rows: what a column costs beyond its rows -
+    // reduction, broadcast, the scalar chain - is latency, not issue slots)
     if (m <= kPanelRows256) {
         switch ((m + 255) / 256) {
             case 0: case 1: return launch_qr_step_r<256, 1>(per_wave, a, count, s);
             case 2: return launch_qr_step_r<256, 2>(per_wave, a, count, s);
             case 3: return launch_qr_step_r<256, 3>(per_wave, a, count, s);
-            case 4: return launch_qr_step_r<256, 4>(per_wave, a, count, s);
-            case 5: return launch_qr_step_r<256, 5>(per_wave, a, count, s);
-            case 6: return launch_qr_step_r<256, 6>(per_wave, a, count, s);
-            case 7: return launch_qr_step_r<256, 7>(per_wave, a, count, s);
-            case 8: return launch_qr_step_r<256, 8>(per_wave, a, count, s);
-            case 9: return launch_qr_step_r<256, 9>(per_wave, a, count, s);
-            default: return launch_qr_step_r<256, 10>(per_wave, a, count, s);
+            default: return launch_qr_step_r<256, 4>(per_wave, a, count, s);
         }
     }
     switch ((m + 511) / 512) {
+        case 3: return launch_qr_step_r<512, 3>(per_wave, a, count, s);
+        case 4: return launch_qr_step_r<512, 4>(per_wave, a, count, s);
+        case 5: return launch_qr_step_r<512, 5>(per_wave, a, count, s);
         case 6: return launch_qr_step_r<512, 6>(per_wave, a, count, s);
         case 7: return launch_qr_step_r<512, 7>(per_wave, a, count, s);
         case 8: return launch_qr_step_r<512, 8>(per_wave, a, count, s);
@@ -686,9 +853,29 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
         a.Tnext = ws.Tmat + (int64_t)(p + 1) * NB * NB; a.rdiag_next = ws.rdiag + (p + 1) * NB;
         a.m_next = last ? 0 : n_pad - (p + 1) * NB;
         a.batch_stride = batch_stride;
+        // Several matrices side by side: the strips that apply a finished block get a launch of their own (two
+        // workgroups per compute unit, which the panel's registers rule out in the step kernel).  One matrix
+        // alone keeps them beside workgroup 0: there the launch count and the chain of panels are what matters.
+        // Either way every column sees the same arithmetic.
+        if (count >= kBulkFromCount && a.block_done && a.outer + a.acc > 0 && a.nb_block <= kBulkMaxBlocks) {
+            QrBulkArgs b;
+            for (int q = 0; q < kMaxDelay; ++q) b.refl[q] = a.refl[q < a.pending ? q : 0];
+            b.pending = a.pending; b.Cout = a.Cout; b.X = a.X; b.outer = a.outer; b.acc = a.acc;
+            b.strip_stride = strip_stride; b.nb_block = a.nb_block; b.batch_stride = batch_stride; b.count = count;
+            GELO_TRY(launch_qr_bulk(b, count, s));
+            a.outer = a.acc = 0;
+            if (last) continue;                               // no panel left: the step launch would be empty
+        }
         GELO_TRY(launch_qr_step(a, count, s));
     }
     return hipSuccess;
+}
+
+// Brings this file's code onto the device (the runtime loads a code object on its first use, which allocates
+// device memory): contexts do this when they are created, so that no later call does.
+hipError_t factor_init() {
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&qr_prepare_kernel));
 }
 
 }  // namespace gelo

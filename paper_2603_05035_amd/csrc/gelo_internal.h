@@ -45,6 +45,8 @@ hipError_t gemm_f32(const GemmOperands& g, hipStream_t stream);
 hipError_t gemm_bf16_init();        // one-time kernel attribute set-up (large dynamic LDS)
 hipError_t gemm_f32_init();
 hipError_t lu_init();
+hipError_t factor_init();
+hipError_t sampler_init();
 
 // 8-bit float projection (OCP FP8 E4M3 operands, float accumulation, bf16 result) --------------------------
 // codes[r][c] = e4m3(X[r][c] * 448 / max_c |X[r][c]|) (ldq bytes per row), scale[r] = max / 448 (1 for a zero row); X bf16

@@ -745,7 +745,10 @@ hipError_t gemm(const float* A, int64_t lda, const float* B, int64_t ldb, float*
 
 }  // namespace
 
-hipError_t lu_init() { return hipSuccess; }
+hipError_t lu_init() {         // brings this file's code onto the device (see factor_init)
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&permute_columns_kernel));
+}
 
 hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t s) {
     const int n_pad = ws.n_pad;

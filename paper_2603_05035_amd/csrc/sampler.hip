@@ -277,4 +277,9 @@ hipError_t export_dense(const void* src, int is_bf16, int64_t ld, int rows, int 
     return hipGetLastError();
 }
 
+hipError_t sampler_init() {    // brings this file's code onto the device (see factor_init)
+    hipFuncAttributes attr;
+    return hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&fill_normal_kernel));
+}
+
 }  // namespace gelo
