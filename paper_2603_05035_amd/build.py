@@ -39,5 +39,37 @@ def build(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def build_sanitized(verbose: bool = False) -> str:
+    """Host-side sanitizer target: api.hip's HOST code (argument checks, context and mixing-object life cycle)
+    compiled with AddressSanitizer + UndefinedBehaviorSanitizer, linked with the other, uninstrumented objects of
+    `build()` into libgelo_hostsan.so, plus the driver tests/host_sanitize/lifecycle.cpp -> lifecycle_hostsan (both beside libgelo.so).
+    The GPU code is not instrumented.  Call build() first."""
+    obj_dir = os.path.join(HERE, "_build")
+    root = os.path.dirname(HERE)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    api_obj = os.path.join(obj_dir, "api_hostsan.o")
+    lib = os.path.join(HERE, "libgelo_hostsan.so")           # beside libgelo.so: what a GPU box receives
+    exe = os.path.join(HERE, "lifecycle_hostsan")
+    cmds = [
+        [HIPCC, *FLAGS, *san, "-c", os.path.join(CSRC, "api.hip"), "-o", api_obj],
+        [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize", api_obj,
+         *[os.path.join(obj_dir, src.replace(".hip", ".o")) for src in SOURCES if src != "api.hip"], "-o", lib],
+        [HIPCC, "-x", "c++", "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize", "-fno-omit-frame-pointer",
+         "-I", os.path.join(root, "include"), "-I", "/opt/rocm/include", "-D__HIP_PLATFORM_AMD__",
+         os.path.join(root, "tests", "host_sanitize", "lifecycle.cpp"), "-L", HERE, "-lgelo_hostsan", "-L", "/opt/rocm/lib", "-lamdhip64",
+         "-Wl,-rpath,$ORIGIN", "-Wl,-rpath,/opt/rocm/lib", "-o", exe],
+    ]
+    for cmd in cmds:
+        proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l)
+        if proc.returncode != 0 or (verbose and out.strip()):
+            sys.stderr.write(out + "\n")
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc failed (host sanitizer target)")
+    return exe
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    if "--sanitize" in sys.argv:
+        print(build_sanitized(verbose=True))
