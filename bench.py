@@ -590,6 +590,26 @@ def main() -> int:
                            "unit": "TFLOP/s", "frac": f_gen / t_gen / 1e12 / PEAK_TFLOPS["f32"],
                            "pipelined_ms_per_draw": t_step * 1e3,
                            "note": "one draw alone on one stream; pipelined_ms_per_draw bounds it from above when draws of other batches overlap"}
+        if w.kind == g.GELO_ORTHOGONAL and n > 128:
+            # the same factorisation as throughput work: `group` draws in one batched call (side by side in the same
+            # launches), nothing else on the GPU
+            bctx = g.gelo_create(0, w.seed + 77, allow_batch_reuse=False)
+            g.gelo_reserve(bctx, w.kind, code, nd, k, d, 0, 1, group)
+            tb = []
+            for rep in range(3):
+                e0, e1 = ev(), ev()
+                e0.record()
+                ms_ = g.gelo_sample_mixing_batch(bctx, w.kind, nd, k, d, code, rep * group, group)
+                e1.record()
+                torch.cuda.synchronize()
+                tb.append(e0.elapsed_time(e1) * 1e-3)
+                for m_ in ms_:
+                    g.gelo_mixing_free(bctx, m_)
+            g.gelo_destroy(bctx)
+            t_b = min(tb[1:]) / group
+            result["a_gen"]["batched"] = {"draws_per_call": group, "ms_per_draw": t_b * 1e3, "achieved": f_gen / t_b / 1e12,
+                                          "frac": f_gen / t_b / 1e12 / PEAK_TFLOPS["f32"],
+                                          "note": "gelo_sample_mixing_batch alone on the GPU: the chain of panels is shared, the strips of all matrices fill the chip"}
 
     if n <= 128:
         # decode-shaped batches: the projection streams W once and does almost no arithmetic per byte
