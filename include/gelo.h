@@ -93,7 +93,7 @@ typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;
 #define GELO_BATCH_WINDOW 4096 /* how far below the highest batch id used so far an unused id is still accepted */
 #define GELO_STATIC_MAX_N 128  /* largest n gelo_qkv_forward_static takes (and one-launch batched draws) */
 #define GELO_MAX_BATCH_DRAW 48 /* mixing objects one gelo_sample_mixing_batch call draws */
-#define GELO_STATIC_SCRATCH_BYTES (3u << 20)   /* size of its static device buffer, held per GPU until the process ends */
+#define GELO_STATIC_SCRATCH_BYTES (16u << 20)   /* size of its static device buffer, held per GPU until the process ends */
 
 /* Creates a context on HIP device `device` with Philox key `seed`.  `allow_batch_reuse` != 0
  * switches off the check that a batch id is used at most once (for tests and benchmarks that
@@ -162,7 +162,10 @@ gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* mixing, gelo_dtype dtype, const
                      float shield_scale, gelo_norm_stat stat, void* U, int64_t ldu, void* stream);
 
 /* Accelerator side, eq. 2.  Y[n x p] = U[n x d] * W[d x p].  Touches no secret: it takes no
- * mixing object.  Also serves as the plain baseline H*W (pass H as U, n = n_data). */
+ * mixing object.  Also serves as the plain baseline H*W (pass H as U, n = n_data).  A bf16 product
+ * of at most 96 rows whose width leaves most of the chip idle (p < 8192) cuts d over workgroups and
+ * keeps their float partial sums in a context workspace (gelo_reserve with p sizes it): two such
+ * calls on one context must not overlap in time on different streams. */
 gelo_status gelo_project(gelo_ctx* ctx, gelo_dtype dtype, int n, int d, int p,
                          const void* U, int64_t ldu, const void* W, int64_t ldw,
                          void* Y, int64_t ldy, void* stream);
@@ -219,7 +222,10 @@ gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, in
  * GELO_ESHAPE otherwise.  kind: GELO_ORTHOGONAL, GELO_CONDITIONED or GELO_STRUCTURED.  U (n x d) and
  * Y (n x p) are required; H, W, Z, U, Y densely packed as in gelo_qkv_forward.  All calls on one GPU
  * share the one buffer, whatever their context or stream: calls that overlap in time on a GPU race;
- * issue them on one stream or order them yourself.  Same results, bit for bit, as gelo_qkv_forward. */
+ * issue them on one stream or order them yourself.  Same results, bit for bit, as gelo_qkv_forward
+ * (a projection that cuts K over workgroups keeps its float partial sums in the static buffer too;
+ * only if they do not fit behind the batch's buffers is K left whole, and Y then differs from
+ * gelo_qkv_forward's in the order of summation: never for n x p up to 68 x 12288). */
 gelo_status gelo_qkv_forward_static(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_data, int k_shield,
                                     int d, int p, const void* H, const void* W, float shield_scale,
                                     gelo_norm_stat stat, uint64_t batch_id, void* Z, void* U, void* Y, void* stream);

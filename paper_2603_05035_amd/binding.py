@@ -21,7 +21,7 @@ GELO_MAX_N = 5120
 GELO_BATCH_WINDOW = 4096
 GELO_STATIC_MAX_N = 128
 GELO_MAX_BATCH_DRAW = 48
-GELO_STATIC_SCRATCH_BYTES = 3 << 20
+GELO_STATIC_SCRATCH_BYTES = 16 << 20
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgelo.so")
 

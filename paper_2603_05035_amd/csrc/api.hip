@@ -47,7 +47,7 @@ constexpr int kBatchWindow = 4096;
 // Scratch of the entry point that allocates nothing (gelo_qkv_forward_static): the mixing matrices, the
 // factorisation workspace and the shield buffers of one decode-shaped batch.  Host code never uses this
 // name as an address: gelo_create asks the runtime for the array's device address, per device.
-constexpr size_t kStaticScratchBytes = (size_t)3 << 20;
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
 constexpr int kStaticMaxDevices = 16;
 }
 
@@ -92,6 +92,7 @@ struct gelo_ctx {
     void* factor_ws; size_t factor_ws_bytes;
     void* chain_ws;  size_t chain_ws_bytes;
     void* quant_ws;  size_t quant_ws_bytes;    // FP8 projection: codes and row scales of the current U
+    void* project_ws; size_t project_ws_bytes; // bf16 projection of at most 128 rows: float partial sums of the K slices
     float* host_scalars;         // pinned: kappa read-back, one slot per lane
     int* host_flag;
     std::vector<gelo_mixing*> pool;
@@ -318,6 +319,7 @@ gelo_status gelo_create(gelo_ctx** out, int device, uint64_t seed, int allow_bat
     }
     ctx->factor_ws = ctx->chain_ws = nullptr; ctx->factor_ws_bytes = ctx->chain_ws_bytes = 0;
     ctx->quant_ws = nullptr; ctx->quant_ws_bytes = 0;
+    ctx->project_ws = nullptr; ctx->project_ws_bytes = 0;
     ctx->host_scalars = nullptr; ctx->host_flag = nullptr;
     ctx->lanes_ready = false; ctx->join_pending = false; ctx->cand = nullptr; ctx->cand_bytes = 0;
     for (int i = 0; i < kLanes; ++i) ctx->lane_graph_ok[i] = false;
@@ -352,6 +354,7 @@ gelo_status gelo_destroy(gelo_ctx* ctx) {
     if (ctx->factor_ws) (void)hipFree(ctx->factor_ws);
     if (ctx->chain_ws) (void)hipFree(ctx->chain_ws);
     if (ctx->quant_ws) (void)hipFree(ctx->quant_ws);
+    if (ctx->project_ws) (void)hipFree(ctx->project_ws);
     if (ctx->host_scalars) (void)hipHostFree(ctx->host_scalars);
     delete ctx;
     return GELO_OK;
@@ -666,6 +669,24 @@ gelo_status gelo_mix(gelo_ctx* ctx, gelo_mixing* m, gelo_dtype dtype, const void
     return GELO_OK;
 }
 
+// Eq. 2 with a caller-chosen workspace for the partial sums of a decode-shaped product (NULL: none, the product then
+// runs without cutting K); allocates nothing.
+static gelo_status project_launch(gelo_ctx* ctx, gelo_dtype dtype, int n, int d, int p, const void* U, int64_t ldu,
+                                  const void* W, int64_t ldw, void* Y, int64_t ldy, void* ws, size_t ws_bytes, hipStream_t s) {
+    GemmOperands g;
+    g.A = U; g.lda = ldu;
+    g.B0 = W; g.ldb0 = ldw; g.K0 = d;
+    g.B1 = W; g.ldb1 = ldw;
+    g.C = Y; g.ldc = ldy;
+    g.M = n; g.N = p; g.K = d;
+    g.splitk_ws = ws; g.splitk_ws_bytes = ws_bytes;
+    return run_gemm(ctx, dtype, g, s);
+}
+
+static size_t project_ws_need(gelo_dtype dtype, int n, int d, int p) {
+    return dtype == GELO_BF16 ? gemm_bf16_skinny_ws_bytes(n, p, d) : 0;
+}
+
 gelo_status gelo_project(gelo_ctx* ctx, gelo_dtype dtype, int n, int d, int p,
                          const void* U, int64_t ldu, const void* W, int64_t ldw,
                          void* Y, int64_t ldy, void* stream) {
@@ -678,13 +699,13 @@ gelo_status gelo_project(gelo_ctx* ctx, gelo_dtype dtype, int n, int d, int p,
     if (st == GELO_OK) st = check_matrix(ctx, "Y", Y, ldy, p);
     if (st != GELO_OK) return st;
     GELO_HIP(ctx, hipSetDevice(ctx->device));
-    GemmOperands g;
-    g.A = U; g.lda = ldu;
-    g.B0 = W; g.ldb0 = ldw; g.K0 = d;
-    g.B1 = W; g.ldb1 = ldw;
-    g.C = Y; g.ldc = ldy;
-    g.M = n; g.N = p; g.K = d;
-    return run_gemm(ctx, dtype, g, (hipStream_t)stream);
+    const size_t need = project_ws_need(dtype, n, d, p);
+    if (need > 0) {
+        st = grow(ctx, &ctx->project_ws, &ctx->project_ws_bytes, need);
+        if (st != GELO_OK) return st;
+    }
+    return project_launch(ctx, dtype, n, d, p, U, ldu, W, ldw, Y, ldy, need > 0 ? ctx->project_ws : nullptr, need > 0 ? ctx->project_ws_bytes : 0,
+                          (hipStream_t)stream);
 }
 
 gelo_status gelo_unmix(gelo_ctx* ctx, gelo_mixing* m, gelo_dtype dtype, int p, const void* Y, int64_t ldy,
@@ -934,7 +955,11 @@ gelo_status gelo_qkv_forward_static(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dt
     st = sample_into(ctx, &local, ws, ws_bytes, 1, kind, 1.0, 1, batch_id, s);
     if (st == GELO_OK) batch_commit(ctx, batch_id);
     if (st == GELO_OK) st = mix_launch(ctx, &local, H, d, shield_scale, stat, U, d, s);
-    if (st == GELO_OK) st = gelo_project(ctx, dtype, n, d, p, U, d, W, p, Y, p, stream);
+    // partial sums of the projection: behind the batch's buffers if the static array still holds them (else K is not cut)
+    const size_t used = up256(L.total) + ws_bytes;
+    const size_t need = project_ws_need(dtype, n, d, p);
+    const bool fits = need > 0 && used + need <= kStaticScratchBytes;
+    if (st == GELO_OK) st = project_launch(ctx, dtype, n, d, p, U, d, W, p, Y, p, fits ? base + used : nullptr, fits ? need : 0, s);
     if (st == GELO_OK) st = unmix_launch(ctx, &local, p, Y, p, Z, p, s);
     return st;
 }
@@ -962,6 +987,9 @@ gelo_status gelo_reserve(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_
     if (p > 0) {
         const size_t ub = up256((size_t)n * d * elem_size(dtype)), yb = up256((size_t)n * p * elem_size(dtype));
         st = grow(ctx, &ctx->chain_ws, &ctx->chain_ws_bytes, ub + yb);
+        if (st != GELO_OK) return st;
+        const size_t need = project_ws_need(dtype, n, d, p);
+        if (need > 0) st = grow(ctx, &ctx->project_ws, &ctx->project_ws_bytes, need);
         if (st != GELO_OK) return st;
     }
     // `mixings` free objects of this shape in the pool

@@ -39,7 +39,12 @@ struct GemmOperands {
     int M, N, K;
     bool a_zero_padded = false;   // A is readable and zero in columns [K, round_up(K, 64))
     bool subtract = false;        // float only: C <- C - A * B instead of C <- A * B
+    void* splitk_ws = nullptr;    // bf16, M <= 128: float workspace for a launch that cuts K over workgroups (optional;
+    size_t splitk_ws_bytes = 0;   //   at least gemm_bf16_skinny_ws_bytes(M, N, K), 16-byte aligned)
 };
+size_t gemm_bf16_skinny_ws_bytes(int M, int N, int K);    // 0: such a launch is not used for this shape
+int gemm_bf16_skinny_slices(int M, int N, int K);
+int64_t gemm_bf16_skinny_ldp(int N);
 hipError_t gemm_bf16(const GemmOperands& g, hipStream_t stream);
 hipError_t gemm_f32(const GemmOperands& g, hipStream_t stream);
 hipError_t gemm_bf16_init();        // one-time kernel attribute set-up (large dynamic LDS)

@@ -22,6 +22,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;
 constexpr int WN = 128;
@@ -499,43 +500,74 @@ void gemm_bf16_dma_mixed_kernel(Bf16Args g) {
 }  // namespace dma
 
 // ---------------------------------------------------------------------------------------------
-// Skinny path (M <= 128: decode-shaped batches).  The product is bound by streaming B once, so every
-// workgroup takes ALL rows and only 64 columns (192 workgroups for 12288 columns), and its 64-column
-// panel of B runs through a deep ring of LDS stages (up to 8 K steps of 64 in flight) filled by the
-// same direct-to-LDS loads as the fast path.  Wave w owns rows 32 w .. 32 w + 31: it fetches and reads
-// only its own rows of A, so only the B part of a stage needs the barrier.  Same transposing reads,
-// swapped MFMA operands and LDS epilogue as the fast path.  Measured at 68 x 12288 x 4096: 32 us
-// against 65 us for the 128 x 128 generic tile.
+// Skinny path (M <= 128: decode-shaped batches).  The product is bound by streaming B once.  A
+// workgroup takes ALL rows and BN = 32 NCT columns; K steps of 64 run through a ring of LDS stages
+// filled by the same direct-to-LDS loads as the fast path (whole 128-byte lines of A and B).  The
+// CONTRACTION of a K step is split over the four waves: wave w multiplies rows 16 w .. 16 w + 15 of
+// B's stage with the matching 32 bytes of every row of A, so nothing is read from LDS twice (with the
+// rows split over the waves instead, every wave read all of B and the reads took as long as the
+// fetches).  One barrier per K step; the fragments of step t + 1 are read while the matrix
+// instructions of step t run.  Rows of A beyond M are not fetched (their lanes are masked; what the
+// matrix cores make of the stale LDS words lands in rows that are never stored).  The four partial
+// sums meet in LDS after the loop and are added in wave order.
+//
+// Two shapes of launch.  Measured on MI355X, one CU streams at most 26 - 28 GB/s from HBM whatever
+// the depth of its ring (3 to 13 stages made no difference, nor did a panel-contiguous copy of B),
+// and every byte of A a CU fetches (all of A, once per workgroup) counts against the same limit:
+// 68 x 12288 x 4096 took 30 us on 192 workgroups of 64 columns, 20 us with 8 rows.
+//  - NCT = 2 (64 columns), all of K per workgroup: no workspace, any shape.
+//  - NCT = 6 (192 columns = three whole 128-byte lines per row of B), K cut into `slices` ranges of
+//    K steps so that columns x slices fills the chip: every CU streams its share of B and only
+//    1 / slices of A.  The workgroups write float partial sums; a second small kernel adds them in
+//    slice order (fixed order, no atomics) and rounds to bf16.
 namespace skinny {
 
-constexpr int BN = 64, BKS = 64;
+constexpr int BKS = 64, NWAVES = 4, KW = BKS / NWAVES;
+constexpr int EPI_COLS = 64, EPI_PITCH = EPI_COLS + 4;           // floats; 272-byte rows: 16-byte writes of 16 rows hit distinct banks
 
-template <int NW> struct Cfg {
-    static constexpr int A_BYTES = NW * 32 * 128;
-    static constexpr int B_BYTES = BKS * BN * 2;                 // 8 KB, rows of 128 B
-    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int NBW = (8 + NW - 1) / NW;                // B fetches per wave and K step
-    static constexpr int PER_TILE = 4 + NBW;
-    static constexpr int STAGES_LDS = (152 * 1024) / STAGE_BYTES;    // what fits in LDS
-    static constexpr int STAGES_CNT = 63 / PER_TILE + 1;             // a wave can count 63 fetches in flight
+template <int RT, int NCT> struct Cfg {                          // RT = row tiles of 32, NCT = column tiles of 32
+    static constexpr int BN = 32 * NCT;
+    static constexpr int ROWB = BN * 2, CPR = ROWB / 16;         // bytes / 16-byte chunks per row of B's stage
+    static constexpr int NBD = BKS * ROWB / 1024 / NWAVES;       // B fetches per wave and K step
+    static constexpr int PER = RT + NBD;                         // fetches per wave and K step
+    static constexpr int A_BYTES = RT * 32 * 128;
+    static constexpr int STAGE_BYTES = A_BYTES + BKS * ROWB;
+    static constexpr int STAGES_LDS = (156 * 1024) / STAGE_BYTES;              // what fits in LDS
+    static constexpr int STAGES_CNT = 63 / PER + 1;                            // a wave can count 63 fetches in flight
     static constexpr int STAGES = STAGES_LDS < STAGES_CNT ? (STAGES_LDS < 8 ? STAGES_LDS : 8) : (STAGES_CNT < 8 ? STAGES_CNT : 8);
     static constexpr int DIST = STAGES - 1;
+    static constexpr int EPI_BYTES = NWAVES * RT * 32 * EPI_PITCH * 4;
+    static constexpr int LDS_BYTES = STAGES * STAGE_BYTES > EPI_BYTES ? STAGES * STAGE_BYTES : EPI_BYTES;
+    static_assert(DIST >= 2, "the ring must hold the step being read, the next one and one in flight");
+    static_assert(BKS * ROWB % (1024 * NWAVES) == 0 && NCT % 2 == 0, "stage / wave mismatch");
 };
+
+// position (in 16-byte chunks) of chunk c of B row r inside the row: rows r + 2, r + 3 of a transposing read are
+// rotated by 64 bytes (for 128-byte rows: their halves swap), which puts the four rows of a read on distinct banks
+template <int CPR> __device__ __forceinline__ int chunk_pos(int r, int c) { const int p = c + 4 * ((r >> 1) & 1); return p >= CPR ? p - CPR : p; }
+template <int CPR> __device__ __forceinline__ int chunk_of_pos(int r, int pos) { const int c = pos - 4 * ((r >> 1) & 1); return c < 0 ? c + CPR : c; }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 template <int PER, int MAXL> __device__ __forceinline__ void wait_later(int later) {
-    // allow `later` (<= MAXL) younger tiles of PER fetches each to stay in flight
+    // allow `later` (<= MAXL) younger K steps of PER fetches each to stay in flight
     if constexpr (MAXL == 0) { wait_vmcnt<0>(); }
     else { if (later >= MAXL) wait_vmcnt<PER * MAXL>(); else wait_later<PER, MAXL - 1>(later); }
 }
 
-template <int NW>
-__global__ __launch_bounds__(NW * 64)
-void gemm_bf16_skinny_kernel(Bf16Args g) {
-    using C = Cfg<NW>;
+struct SkinnyArgs {
+    Bf16Args g;
+    float* partial;             // SPLIT: slices x M x ldp floats
+    int64_t ldp;
+    int slices;
+};
+
+template <int RT, int NCT, bool SPLIT>
+__global__ __launch_bounds__(NWAVES * 64)
+void gemm_bf16_skinny_kernel(SkinnyArgs sa) {
+    using C = Cfg<RT, NCT>;
+    const Bf16Args& g = sa.g;
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)lds);
-    const int n0 = blockIdx.x * BN;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -546,140 +578,207 @@ void gemm_bf16_skinny_kernel(Bf16Args g) {
         return (int64_t)(((uint64_t)hi << 32) | lo);
     };
     const int K = uni32(g.K), K0 = uni32(g.K0);
-    const int T = (K + BKS - 1) / BKS;
+    const int T_all = (K + BKS - 1) / BKS;
+    // consecutive workgroups take the slices of one column group: the workgroups of one XCD (every eighth) then share
+    // few slices of A in their L2
+    const int slices = SPLIT ? uni32(sa.slices) : 1;
+    const int slice = SPLIT ? (int)(blockIdx.x % (unsigned)slices) : 0;
+    const int n0 = (SPLIT ? (int)(blockIdx.x / (unsigned)slices) : (int)blockIdx.x) * C::BN;
+    const int t_first = SPLIT ? (int)((int64_t)T_all * slice / slices) : 0;
+    const int T = (SPLIT ? (int)((int64_t)T_all * (slice + 1) / slices) : T_all) - t_first;       // K steps of this workgroup
     const int64_t ldb0 = uni64(g.ldb0), ldb1 = uni64(g.ldb1);
     const uint16_t* B0p = (const uint16_t*)uni64((int64_t)g.B0);
     const uint16_t* B1p = (const uint16_t*)uni64((int64_t)g.B1);
 
-    // A: wave w fetches (and later reads) only its own 32 rows; B: the 8 blocks of 8 rows are dealt to the waves
-    const uint16_t* a_src[4];
+    // A: the 4 RT blocks of 8 rows x 128 bytes are dealt to the waves (wave w: blocks w, w + 4, ...); chunk c of row r
+    // lands at position c ^ swizzle(r).  Lanes of rows beyond M stay off, except lane 0, so that every fetch is issued
+    // and counted.
+    const uint16_t* a_src[RT];
+    bool a_on[RT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = wave * 32 + i * 8 + (lane >> 3), cp = lane & 7;
+    for (int i = 0; i < RT; ++i) {
+        const int row = (wave + 4 * i) * 8 + (lane >> 3), cp = lane & 7;
         const int c = cp ^ ((row ^ (row >> 3)) & 7);
-        const int grow = row < g.M ? row : g.M - 1;
-        a_src[i] = g.A + (int64_t)grow * g.lda + c * 8;
+        a_on[i] = row < g.M || lane == 0;
+        a_src[i] = g.A + (int64_t)(row < g.M ? row : 0) * g.lda + c * 8;
     }
-    const uint16_t* b0_src[C::NBW];
-    const uint16_t* b1_src[C::NBW];
-    int b_krow[C::NBW], b_gn[C::NBW];
-    uint32_t b_dst[C::NBW];
+    // B: the stage's 16-byte units in order, NBD kilobytes per wave
+    const uint16_t* b0_src[C::NBD];
+    const uint16_t* b1_src[C::NBD];
+    int b_krow[C::NBD], b_gn[C::NBD];
 #pragma unroll
-    for (int i = 0; i < C::NBW; ++i) {
-        int blk = wave * C::NBW + i; blk = blk < 8 ? blk : 7;    // a surplus fetch repeats block 7 (same data, same place)
-        const int br = blk * 8 + (lane >> 3), cpos = lane & 7;
-        const int bc = cpos ^ (((br >> 1) & 1) << 2);           // rows r+2, r+3 of a transposing read swap their 64-byte halves
+    for (int i = 0; i < C::NBD; ++i) {
+        const int e = (wave * C::NBD + i) * 64 + lane;
+        const int br = e / C::CPR, cpos = e - br * C::CPR;
+        const int bc = chunk_of_pos<C::CPR>(br, cpos);
         int gn = n0 + bc * 8; gn = gn < g.N ? gn : g.N - 8;
         b_krow[i] = br; b_gn[i] = gn;
-        b_dst[i] = __builtin_amdgcn_readfirstlane(C::A_BYTES + blk * 1024);
         b0_src[i] = B0p + (int64_t)br * ldb0 + gn;
         b1_src[i] = B1p + (int64_t)(br - K0) * ldb1 + gn;
     }
 
-    auto issue = [&](int t) {
-        const int k0 = t * BKS;
-        const uint32_t st = lds_base + (t % C::STAGES) * C::STAGE_BYTES;
+    auto issue = [&](int t, int slot) {                          // t counts this workgroup's K steps
+        const int k0 = (t_first + t) * BKS;
+        const uint32_t st = lds_base + slot * C::STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dma::dma16(a_src[i] + k0, st + (wave * 4 + i) * 1024);
+        for (int i = 0; i < RT; ++i) {
+            if ((wave + 4 * i) * 8 + 8 <= g.M) dma::dma16(a_src[i] + k0, st + (wave + 4 * i) * 1024);       // wave-uniform: a whole block
+            else if (a_on[i]) dma::dma16(a_src[i] + k0, st + (wave + 4 * i) * 1024);
+        }
+        const uint32_t sb = st + C::A_BYTES + wave * C::NBD * 1024;
         if (k0 + BKS <= K0) {
             const int64_t off = (int64_t)k0 * ldb0;
 #pragma unroll
-            for (int i = 0; i < C::NBW; ++i) dma::dma16(b0_src[i] + off, st + b_dst[i]);
+            for (int i = 0; i < C::NBD; ++i) dma::dma16(b0_src[i] + off, sb + i * 1024);
         } else if (k0 >= K0 && k0 + BKS <= K) {
             const int64_t off = (int64_t)k0 * ldb1;
 #pragma unroll
-            for (int i = 0; i < C::NBW; ++i) dma::dma16(b1_src[i] + off, st + b_dst[i]);
+            for (int i = 0; i < C::NBD; ++i) dma::dma16(b1_src[i] + off, sb + i * 1024);
         } else {
 #pragma unroll
-            for (int i = 0; i < C::NBW; ++i) {
+            for (int i = 0; i < C::NBD; ++i) {
                 int gk = k0 + b_krow[i];
-                const bool beyond = gk >= K;
+                const bool beyond = gk >= K;                      // rows past the contraction length read zeros
                 gk = beyond ? K - 1 : gk;
                 const bool first = gk < K0;
                 const uint16_t* base = first ? B0p : B1p;
                 const int64_t off = first ? (int64_t)gk * ldb0 : (int64_t)(gk - K0) * ldb1;
-                dma::dma16(beyond ? (const uint16_t*)dma::g_zero16 : base + off + b_gn[i], st + b_dst[i]);
+                dma::dma16(beyond ? (const uint16_t*)dma::g_zero16 : base + off + b_gn[i], sb + i * 1024);
             }
         }
     };
 
-    const int a_row = wave * 32 + j;
-    const int a_sw = (a_row ^ (a_row >> 3)) & 7;
-    const uint32_t a_frag_off = a_row * 128;
-    const int s16 = lane & 15, G = lane >> 4;
-    const int kg = G >> 1, nh = G & 1;
-    const int rl = kg * 8 + (s16 >> 2);
-    uint32_t b_off[2];
+    // fragment addresses inside a stage: the wave's 16 contraction rows
+    uint32_t a_off[RT];
 #pragma unroll
-    for (int ct = 0; ct < 2; ++ct) {
-        const int chunk = (ct * 4 + nh * 2) ^ (((rl >> 1) & 1) << 2);
-        b_off[ct] = C::A_BYTES + rl * 128 + chunk * 16 + (s16 & 3) * 8;
+    for (int i = 0; i < RT; ++i) {
+        const int row = i * 32 + j;
+        a_off[i] = row * 128 + (((wave * 2 + grp) ^ ((row ^ (row >> 3)) & 7)) * 16);
+    }
+    const int s16 = lane & 15, nh = (lane >> 4) & 1;
+    const int rl = wave * KW + grp * 8 + (s16 >> 2);             // row of the first transposing read; the second is 4 below
+    uint32_t b_off[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+        b_off[ct] = C::A_BYTES + rl * C::ROWB + chunk_pos<C::CPR>(rl, ct * 4 + nh * 2) * 16 + (s16 & 3) * 8;
+    struct Frags { bf16x8_t a[RT], b[NCT]; };
+    auto read_frags = [&](int slot, Frags& f) {
+        const uint8_t* st = lds + slot * C::STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < RT; ++i) f.a[i] = *reinterpret_cast<const bf16x8_t*>(st + a_off[i]);
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            typedef dma::s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
+            const dma::s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct]));
+            const dma::s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + 4 * C::ROWB));
+            const dma::s16x8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            f.b[ct] = __builtin_bit_cast(bf16x8_t, both);
+        }
+    };
+
+    f32x16_t acc[RT][NCT];
+#pragma unroll
+    for (int i = 0; i < RT; ++i)
+#pragma unroll
+        for (int c = 0; c < NCT; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][c][v] = 0.f;
+
+    int slot_issue = 0, slot_read = 0;
+    auto next_slot = [](int s) { return s + 1 == C::STAGES ? 0 : s + 1; };
+#pragma unroll
+    for (int t = 0; t < C::DIST; ++t) if (t < T) { issue(t, slot_issue); slot_issue = next_slot(slot_issue); }
+
+    Frags cur, nxt;
+    if (T > 0) {
+        const int later = (T - 1) < (C::DIST - 1) ? (T - 1) : (C::DIST - 1);
+        wait_later<C::PER, C::DIST - 1>(later);
+        __builtin_amdgcn_s_barrier();                          // step 0 has landed for every wave
+        read_frags(slot_read, cur); slot_read = next_slot(slot_read);
+    }
+    // step t: behind the barrier step t + 1 has landed for every wave and nobody reads the slot of step t - 1 any
+    // more: refill that slot, start reading step t + 1, multiply step t
+    for (int t = 0; t < T; ++t) {
+        if (t + 1 < T) {
+            const int left = T - 2 - t;
+            wait_later<C::PER, C::DIST - 2>(left < C::DIST - 2 ? left : C::DIST - 2);
+        }
+        __builtin_amdgcn_s_barrier();
+        if (t + C::DIST < T) { issue(t + C::DIST, slot_issue); slot_issue = next_slot(slot_issue); }
+        nxt = cur;
+        if (t + 1 < T) { read_frags(slot_read, nxt); slot_read = next_slot(slot_read); }
+#pragma unroll
+        for (int i = 0; i < RT; ++i)
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct)
+                acc[i][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[ct], cur.a[i], acc[i][ct], 0, 0, 0);
+        cur = nxt;
     }
 
-    f32x16_t acc2[2][2];
+    // acc[i][ct][v] = partial C[row 32 i + lane % 32][col ct*32 + 8 (v / 4) + 4 (lane / 32) + v % 4] over the wave's share of K.
+    // 64 columns at a time: every wave lays its share down, then all threads add the four in wave order.
+    float* ep = reinterpret_cast<float*>(lds) + wave * (RT * 32 * EPI_PITCH);
+    const float* all = reinterpret_cast<const float*>(lds);
+    const int rr = tid >> 3, cc = tid & 7;
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int cp = 0; cp < NCT / 2; ++cp) {
+        __syncthreads();                                       // the ring (first pass) or the previous pass is no longer read
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { acc2[c][0][v] = 0.f; acc2[c][1][v] = 0.f; }
-
+        for (int i = 0; i < RT; ++i)
 #pragma unroll
-    for (int t = 0; t < C::DIST; ++t) if (t < T) issue(t);
-
-    for (int t = 0; t < T; ++t) {
-        const int later = (T - 1 - t) < (C::DIST - 1) ? (T - 1 - t) : (C::DIST - 1);
-        wait_later<C::PER_TILE, C::DIST - 1>(later);
-        __builtin_amdgcn_s_barrier();                          // tile t complete for all waves; stage (t-1) % STAGES is free
-        if (t + C::DIST < T) issue(t + C::DIST);
-        const uint8_t* st = lds + (t % C::STAGES) * C::STAGE_BYTES;
-        // all fragments of the K step first, then the MFMAs on two accumulators per column tile (short dependent chains)
-        bf16x8_t a_frag[4], b_frag[4][2];
+            for (int c2 = 0; c2 < 2; ++c2)
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            a_frag[ks] = *reinterpret_cast<const bf16x8_t*>(st + a_frag_off + (((ks * 2 + grp) ^ a_sw) * 16));
+                for (int q = 0; q < 4; ++q) {
+                    const f32x16_t& a = acc[i][cp * 2 + c2];
+                    const f32x4_t v = {a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+                    *reinterpret_cast<f32x4_t*>(ep + (i * 32 + j) * EPI_PITCH + c2 * 32 + 8 * q + 4 * grp) = v;
+                }
+        __syncthreads();
+        const int col = n0 + cp * EPI_COLS + cc * 8;
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
-                typedef dma::s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
-                const dma::s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * 128));
-                const dma::s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(st + b_off[ct] + ks * 16 * 128 + 4 * 128));
-                const dma::s16x8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                b_frag[ks][ct] = __builtin_bit_cast(bf16x8_t, both);
+        for (int it = 0; it < RT; ++it) {
+            const int row = it * 32 + rr;
+            f32x4_t s0 = *reinterpret_cast<const f32x4_t*>(all + row * EPI_PITCH + cc * 8);
+            f32x4_t s1 = *reinterpret_cast<const f32x4_t*>(all + row * EPI_PITCH + cc * 8 + 4);
+#pragma unroll
+            for (int w = 1; w < NWAVES; ++w) {                   // fixed order: wave 0 + wave 1 + wave 2 + wave 3
+                s0 += *reinterpret_cast<const f32x4_t*>(all + (w * RT * 32 + row) * EPI_PITCH + cc * 8);
+                s1 += *reinterpret_cast<const f32x4_t*>(all + (w * RT * 32 + row) * EPI_PITCH + cc * 8 + 4);
+            }
+            if (row < g.M && col < g.N) {
+                if (SPLIT) {
+                    float* dst = sa.partial + ((int64_t)slice * g.M + row) * sa.ldp + col;
+                    *reinterpret_cast<f32x4_t*>(dst) = s0;
+                    *reinterpret_cast<f32x4_t*>(dst + 4) = s1;
+                } else {
+                    u32x4_t out;
+                    out[0] = pack_bf16x2(s0[0], s0[1]); out[1] = pack_bf16x2(s0[2], s0[3]);
+                    out[2] = pack_bf16x2(s1[0], s1[1]); out[3] = pack_bf16x2(s1[2], s1[3]);
+                    *reinterpret_cast<u32x4_t*>(g.C + (int64_t)row * g.ldc + col) = out;
+                }
             }
         }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int ct = 0; ct < 2; ++ct)
-                acc2[ct][ks & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b_frag[ks][ct], a_frag[ks], acc2[ct][ks & 1], 0, 0, 0);
     }
+}
 
-    f32x16_t acc[2];
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[c][v] = acc2[c][0][v] + acc2[c][1][v];
-    // acc[ct][v] = C[row 32 wave + lane % 32][col ct*32 + 8 (v / 4) + 4 (lane / 32) + v % 4]
-    constexpr int PITCH = 144;
-    __builtin_amdgcn_s_barrier();
-    uint8_t* patch = lds + wave * (32 * PITCH);
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            u32x2_t out;
-            out[0] = pack_bf16x2(acc[ct][4 * q], acc[ct][4 * q + 1]);
-            out[1] = pack_bf16x2(acc[ct][4 * q + 2], acc[ct][4 * q + 3]);
-            *reinterpret_cast<u32x2_t*>(patch + j * PITCH + (ct * 32 + 8 * q + 4 * grp) * 2) = out;
-        }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    const int rr = lane >> 3, cc = lane & 7;
-    const int col = n0 + cc * 8;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int r = it * 8 + rr;
-        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(patch + r * PITCH + cc * 16);
-        const int row = wave * 32 + r;
-        if (row < g.M && col < g.N) *reinterpret_cast<u32x4_t*>(g.C + (int64_t)row * g.ldc + col) = v;
+// C[row][col .. col + 7] = bf16(partial[0] + partial[1] + ... in slice order); one thread per 8 columns
+__global__ __launch_bounds__(256)
+void skinny_reduce_kernel(const float* __restrict__ partial, int64_t ldp, int slices, int M, int N, uint16_t* __restrict__ Cout, int64_t ldc) {
+    const int chunks = N >> 3;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (int64_t)M * chunks) return;
+    const int row = (int)(id / chunks), col = (int)(id - (int64_t)row * chunks) * 8;
+    const float* src = partial + (int64_t)row * ldp + col;
+    f32x4_t s0 = *reinterpret_cast<const f32x4_t*>(src), s1 = *reinterpret_cast<const f32x4_t*>(src + 4);
+    for (int s = 1; s < slices; ++s) {
+        const float* q = src + (int64_t)s * M * ldp;
+        s0 += *reinterpret_cast<const f32x4_t*>(q);
+        s1 += *reinterpret_cast<const f32x4_t*>(q + 4);
     }
+    u32x4_t out;
+    out[0] = pack_bf16x2(s0[0], s0[1]); out[1] = pack_bf16x2(s0[2], s0[3]);
+    out[2] = pack_bf16x2(s1[0], s1[1]); out[3] = pack_bf16x2(s1[2], s1[3]);
+    *reinterpret_cast<u32x4_t*>(Cout + (int64_t)row * ldc + col) = out;
 }
 
 }  // namespace skinny
@@ -712,20 +811,57 @@ hipError_t allow_big_lds() {
 
 }  // namespace
 
-namespace {
-
-template <int NW>
-hipError_t allow_skinny_lds() {
-    using C = skinny::Cfg<NW>;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&skinny::gemm_bf16_skinny_kernel<NW>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, C::STAGES * C::STAGE_BYTES);
+// Split launch of the skinny path: how many ranges of K steps a column group of 192 is cut into so that
+// groups x slices comes close to the chip's 256 CUs (1: not worth it), and the float workspace it needs.
+int gemm_bf16_skinny_slices(int M, int N, int K) {
+    // Measured: with 128 or more column groups of 64 the launch that keeps all of K in a workgroup is as fast (68 x
+    // 12288 x 4096: 30 us either way; 68 x 4096 x 4096: 28 -> 20 us; 68 x 4096 x 11008: 70 -> 29 us); beyond three
+    // row tiles the 192-column accumulators no longer fit the registers.
+    if (M > 96 || N < 192 || (N + 63) / 64 > 128) return 1;
+    const int groups = (N + 191) / 192;
+    const int T = (K + 63) / 64;
+    int slices = 256 / groups;
+    if (slices > T / 4) slices = T / 4;                  // at least four K steps per slice
+    return slices < 2 ? 1 : slices;
+}
+int64_t gemm_bf16_skinny_ldp(int N) { return ((int64_t)N + 7) & ~(int64_t)7; }
+size_t gemm_bf16_skinny_ws_bytes(int M, int N, int K) {
+    const int slices = gemm_bf16_skinny_slices(M, N, K);
+    return slices > 1 ? (size_t)slices * M * gemm_bf16_skinny_ldp(N) * sizeof(float) : 0;
 }
 
-template <int NW>
+namespace {
+
+template <int RT, int NCT, bool SPLIT>
+hipError_t allow_skinny_lds() {
+    using C = skinny::Cfg<RT, NCT>;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&skinny::gemm_bf16_skinny_kernel<RT, NCT, SPLIT>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES);
+}
+
+template <int RT>
 hipError_t launch_skinny(const Bf16Args& a, hipStream_t stream) {
-    using C = skinny::Cfg<NW>;
-    hipLaunchKernelGGL(skinny::gemm_bf16_skinny_kernel<NW>, dim3((a.N + skinny::BN - 1) / skinny::BN), dim3(NW * 64),
-                       (size_t)C::STAGES * C::STAGE_BYTES, stream, a);
+    using C = skinny::Cfg<RT, 2>;
+    skinny::SkinnyArgs sa{a, nullptr, 0, 1};
+    hipLaunchKernelGGL((skinny::gemm_bf16_skinny_kernel<RT, 2, false>), dim3((a.N + C::BN - 1) / C::BN), dim3(skinny::NWAVES * 64),
+                       (size_t)C::LDS_BYTES, stream, sa);
+    return hipGetLastError();
+}
+
+// column groups of 192 x `slices` ranges of K steps, partial sums in `ws`, then the reduction
+template <int RT>
+hipError_t launch_skinny_split(const Bf16Args& a, int slices, float* ws, hipStream_t stream) {
+    using C = skinny::Cfg<RT, 6>;
+    const int groups = (a.N + C::BN - 1) / C::BN;
+    const int64_t ldp = gemm_bf16_skinny_ldp(a.N);
+    skinny::SkinnyArgs sa{a, ws, ldp, slices};
+    hipLaunchKernelGGL((skinny::gemm_bf16_skinny_kernel<RT, 6, true>), dim3(groups * slices), dim3(skinny::NWAVES * 64),
+                       (size_t)C::LDS_BYTES, stream, sa);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t items = (int64_t)a.M * (a.N >> 3);
+    hipLaunchKernelGGL(skinny::skinny_reduce_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, stream,
+                       (const float*)ws, ldp, slices, a.M, a.N, a.C, a.ldc);
     return hipGetLastError();
 }
 
@@ -743,10 +879,13 @@ hipError_t gemm_bf16_init() {
     if (e != hipSuccess) return e;
     e = allow_big_lds<256, 256, 64>();
     if (e != hipSuccess) return e;
-    e = allow_skinny_lds<1>();
-    if (e == hipSuccess) e = allow_skinny_lds<2>();
-    if (e == hipSuccess) e = allow_skinny_lds<3>();
-    if (e == hipSuccess) e = allow_skinny_lds<4>();
+    e = allow_skinny_lds<1, 2, false>();
+    if (e == hipSuccess) e = allow_skinny_lds<2, 2, false>();
+    if (e == hipSuccess) e = allow_skinny_lds<3, 2, false>();
+    if (e == hipSuccess) e = allow_skinny_lds<4, 2, false>();
+    if (e == hipSuccess) e = allow_skinny_lds<1, 6, true>();
+    if (e == hipSuccess) e = allow_skinny_lds<2, 6, true>();
+    if (e == hipSuccess) e = allow_skinny_lds<3, 6, true>();
     if (e != hipSuccess) return e;
     return allow_big_lds<128, 128, 32>();
 }
@@ -819,7 +958,16 @@ hipError_t gemm_bf16(const GemmOperands& o, hipStream_t stream) {
         a.B1 = (const uint16_t*)o.B1; a.ldb1 = o.ldb1;
         a.C = (uint16_t*)o.C;         a.ldc = o.ldc;
         a.M = o.M; a.N = o.N; a.K = o.K;
-        a.tiles_m = 1; a.tiles_n = (o.N + skinny::BN - 1) / skinny::BN;
+        a.tiles_m = 1; a.tiles_n = (o.N + 63) / 64;
+        const int slices = gemm_bf16_skinny_slices(o.M, o.N, o.K);
+        if (slices > 1 && o.N % 8 == 0 && o.splitk_ws && o.splitk_ws_bytes >= gemm_bf16_skinny_ws_bytes(o.M, o.N, o.K)) {
+            float* ws = (float*)o.splitk_ws;
+            switch ((o.M + 31) / 32) {
+                case 1: return launch_skinny_split<1>(a, slices, ws, stream);
+                case 2: return launch_skinny_split<2>(a, slices, ws, stream);
+                default: return launch_skinny_split<3>(a, slices, ws, stream);
+            }
+        }
         switch ((o.M + 31) / 32) {
             case 1: return launch_skinny<1>(a, stream);
             case 2: return launch_skinny<2>(a, stream);

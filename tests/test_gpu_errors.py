@@ -205,8 +205,8 @@ def test_static_entry_point_argument_checks(ctx):
     Zbig = torch.empty(g.GELO_STATIC_MAX_N, 72, device="cuda")
     U2, Y2 = bufs(g.GELO_STATIC_MAX_N + 1)
     assert status_of(S, ctx, g.GELO_ORTHOGONAL, Hbig, W, Zbig, U2, Y2, k_shield=1, batch_id=1) == "GELO_ESHAPE"
-    # the shield block alone would not fit the static buffer: 64 x 16384 floats and their rows
-    d = 16384
+    # the shield block alone would not fit the static buffer: 64 x 32768 floats and their rows
+    d = 32768
     Hw = torch.randn(64, d, device="cuda")
     Ww = torch.randn(d, 8, device="cuda")
     U3, Y3 = torch.empty(128, d, device="cuda"), torch.empty(128, 8, device="cuda")

@@ -663,7 +663,13 @@ def test_strided_operands(ctx):
     (129, 64, 8, 0),           # the narrowest legal output
     (700, 4096, 520, 8),       # long K (64 K steps), three row tiles with a ragged last one
     (1, 64, 8, 0), (33, 128, 520, 8), (97, 1024, 72, 0), (128, 640, 136, 16),   # the skinny kernel with 1, 2, 4, 4 waves
-    (68, 64, 200, 0),          # 3 waves, a single K step
+    (68, 64, 200, 0),          # 3 row tiles, a single K step
+    # the skinny launch that cuts K over workgroups (192-column groups x slices of K steps, float partial sums):
+    (97, 1024, 776, 8),        # 5 column groups (the last one 8 columns wide) x 4 slices, padded output rows
+    (8, 512, 200, 0),          # 2 groups x 2 slices, one row tile
+    (96, 2112, 392, 0),        # 33 K steps over 8 slices (4 or 5 steps each), three full row tiles
+    (128, 2112, 392, 0),       # four row tiles: K is not cut
+    (68, 4096, 4096, 0),       # the decode-shaped O projection: 22 groups x 11 slices
 ])
 def test_project_bf16_fast_path_edges(ctx, M, K, N, ldy_extra):
     """The direct-to-LDS bf16 kernels (both tile widths, and the skinny one for M <= 128) at shapes whose
