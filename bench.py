@@ -101,7 +101,7 @@ def run_composite(args, torch, np, g, wl):
         ctxs = [g.gelo_create(0, 0xBE00 + i, allow_batch_reuse=False) for i in range(depth)]
         w0 = parts[0]
         for c in ctxs:
-            g.gelo_reserve(c, w0.kind, g.GELO_BF16, w0.n_data, w0.k_shield, w0.d, 0, 64, L)
+            g.gelo_reserve(c, w0.kind, g.GELO_BF16, w0.n_data, w0.k_shield, w0.d, w0.p, 64, L)
         ring = [None] * depth
 
         def draw_step(step):
@@ -373,6 +373,12 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    # The interpreter's cyclic garbage collector stays off while the bench runs: a full collection over the
+    # modules loaded above takes about 40 ms of host time, fell into the timed loop of the decode sweep
+    # (a one-off stall worth 12 us per layer-step over 128 steps) and measures nothing of the library.
+    import gc
+    gc.collect()
+    gc.disable()
     if args.workload in COMPOSITE:
         return run_composite(args, torch, np, g, wl)
     w = wl.WORKLOADS[args.workload]
