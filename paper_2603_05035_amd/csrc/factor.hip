@@ -243,7 +243,9 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 // One block reflector I - V op(T) V^T as a strip sees it: V in both layouts, its triangle, and `shift`, the
 // number of 16-row blocks by which its first row lies below the strip's first row (a strip that applies several
 // reflectors of a block of panels in one pass starts at the oldest one's first row).
-struct Reflector { const float* Vr; const float* Vt; const float* T; int shift; };
+struct Reflector { const float* Vr; const float* Vt; const float* T; int shift; int plain_t; };
+// plain_t: op(T) = T (the reflector itself, I - V T V^T: what forming Q applies) instead of T^T (its transpose: what
+// the factorisation applies to the columns behind it); honoured by reflect_strip_lds_body only
 // (the pointers are those of the first matrix of a batch; `off` below is the distance to this workgroup's matrix)
 
 constexpr int kBulkFromCount = 2;         // from this many factorisations side by side the block strips get launches of their own
@@ -351,7 +353,7 @@ __device__ __forceinline__ void reflect_strip_body(const Reflector* refl, int co
             }
             request_behind(gc);
         });
-        if (tid < NB * NB) Ts[q & 1][tid >> 4][tid & 15] = t_mine;
+        if (tid < NB * NB) { if (R.plain_t) Ts[q & 1][tid & 15][tid >> 4] = t_mine; else Ts[q & 1][tid >> 4][tid & 15] = t_mine; }
         if (more && tid < NB * NB) t_next = Rn.T[off + tid];
 #pragma unroll
         for (int st = 0; st < NS; ++st)
@@ -500,7 +502,7 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
             }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the operands are in registers before their ring slot is refilled
         });
-        if (tid < NB * NB) Ts[q & 1][tid >> 4][tid & 15] = t_mine;
+        if (tid < NB * NB) { if (R.plain_t) Ts[q & 1][tid & 15][tid >> 4] = t_mine; else Ts[q & 1][tid >> 4][tid & 15] = t_mine; }
         if (more && tid < NB * NB) t_next = Rn.T[off + tid];
 #pragma unroll
         for (int v = 0; v < 4; ++v) Wp[q & 1][wave][4 * g + v][c] = w0[v] + w1[v];
@@ -813,10 +815,16 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
     // block is being applied while the next one's first panel is written), each n_pad x 16 in two layouts, all
     // inside the n_pad x ld floats of ws.Vc.
     const int D = ws.ld >= 64 * kMaxDelay ? kMaxDelay : (ws.ld >= 128 ? 2 : 1);
-    const int sets = 2 * D;
+    // Every panel's reflector block is kept until the end: the row-major copies side by side in ws.Vc (n_pad x 16 each,
+    // n_pad x n_pad in all), the tiled copies IN PLACE of the panels they came from (a factored panel is dead: nobody
+    // reads those columns of M again, and the panel kernel has all its rows in registers before it writes).
     const int64_t set_floats = (int64_t)n_pad * NB;
-    auto Vr_of = [&](int p) { return ws.Vc + (int64_t)(p % sets) * set_floats; };
-    auto Vt_of = [&](int p) { return ws.Vc + (int64_t)(sets + p % sets) * set_floats; };
+    auto Vr_of = [&](int p) { return ws.Vc + (int64_t)p * set_floats; };
+    auto Vt_of = [&](int p) { return ws.M + (int64_t)p * strip_stride + (int64_t)p * 256; };
+    // Q is formed AFTER the factorisation, last block first (householder_qr_leaves_q): block b then only meets the
+    // columns from its own first one on - the rest of H_b+1 ... H_N is still the identity there - which is
+    // 4/3 n^3 operations instead of the 2 n^3 of carrying Q^T along with the factorisation.
+    const bool backward = householder_qr_leaves_q(n);
     {
         const int64_t elems = (int64_t)n_pad * n_pad;
         hipLaunchKernelGGL(qr_prepare_kernel, dim3((unsigned)((elems + 255) / 256), count), dim3(256), 0, s, ws.M, ws.X, n, n_pad, batch_stride);
@@ -836,7 +844,7 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
         a.pending = i + 1;
         for (int q = 0; q <= i; ++q) {
             a.refl[q].Vr = Vr_of(p0 + q); a.refl[q].Vt = Vt_of(p0 + q);
-            a.refl[q].T = ws.Tmat + (int64_t)(p0 + q) * NB * NB; a.refl[q].shift = q;
+            a.refl[q].T = ws.Tmat + (int64_t)(p0 + q) * NB * NB; a.refl[q].shift = q; a.refl[q].plain_t = 0;
         }
         a.block_done = (p + 1 == block_end) ? 1 : 0;
         a.strip_stride = strip_stride;
@@ -848,7 +856,7 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
         // the block's panels behind p + 1 and the first panel of the next block
         a.inner = a.block_done ? 0 : (block_end < nbr ? block_end : nbr - 1) - (p + 1);
         a.outer = (a.block_done && p + 2 < nbr) ? nbr - (p + 2) : 0;
-        a.acc = a.block_done ? nbr : 0;
+        a.acc = (a.block_done && !backward) ? nbr : 0;
         a.Vr_next = Vr_of(p + 1); a.Vt_next = Vt_of(p + 1);
         a.Tnext = ws.Tmat + (int64_t)(p + 1) * NB * NB; a.rdiag_next = ws.rdiag + (p + 1) * NB;
         a.m_next = last ? 0 : n_pad - (p + 1) * NB;
@@ -868,8 +876,29 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
         }
         GELO_TRY(launch_qr_step(a, count, s));
     }
+    if (backward) {
+        // X = I so far.  Block by block from the last: X[p0:, p0:] <- H_p0 (H_p0+1 (... X[p0:, p0:])), one 16-column
+        // strip per workgroup, the block's reflectors newest first, each as I - V T V^T.
+        for (int p0 = (panels - 1) / D * D; p0 >= 0; p0 -= D) {
+            const int pend = panels - p0 < D ? panels - p0 : D;
+            QrBulkArgs b;
+            for (int q = 0; q < kMaxDelay; ++q) {
+                const int src = q < pend ? pend - 1 - q : 0;
+                b.refl[q].Vr = Vr_of(p0 + src); b.refl[q].Vt = Vt_of(p0 + src);
+                b.refl[q].T = ws.Tmat + (int64_t)(p0 + src) * NB * NB; b.refl[q].shift = src; b.refl[q].plain_t = 1;
+            }
+            b.pending = pend; b.Cout = ws.X; b.X = ws.X + (int64_t)p0 * strip_stride + (int64_t)p0 * 256;
+            b.outer = 0; b.acc = nbr - p0;
+            b.strip_stride = strip_stride; b.nb_block = nbr - p0; b.batch_stride = batch_stride; b.count = count;
+            GELO_TRY(launch_qr_bulk(b, count, s));
+        }
+    }
     return hipSuccess;
 }
+
+// Forming Q behind the factorisation uses the strip kernel that keeps a strip of at most 160 blocks in 128
+// registers; longer columns keep the accumulation of Q^T inside the factorisation.  Depends on n alone.
+bool householder_qr_leaves_q(int n) { return (int)(round_up(n, NB) / NB) <= kBulkMaxBlocks; }
 
 // Brings this file's code onto the device (the runtime loads a code object on its first use, which allocates
 // device memory): contexts do this when they are created, so that no later call does.
