@@ -423,10 +423,10 @@ static gelo_status sample_into(gelo_ctx* ctx, gelo_mixing* m, FactorWorkspace ws
     } else if (kind == GELO_ORTHOGONAL) {
         GELO_HIP(ctx, orthogonal_into_X());
         // A = Q diag(sign r_ii); A^-1 = A^T
-        GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, householder_qr_leaves_q(n) ? 2 : 1, ws.rdiag, n, ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s));
+        GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s));
     } else if (kind == GELO_CONDITIONED) {
         GELO_HIP(ctx, orthogonal_into_X());
-        GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, householder_qr_leaves_q(n) ? 2 : 1, ws.rdiag, n, ldk, m->A32, nullptr, nullptr, nullptr, s));
+        GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, nullptr, nullptr, nullptr, s));
         ps.c1 = kStreamPerturb << 8;
         GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f, 0, s));
         GELO_HIP(ctx, axpy_matrix(m->A32, ldk, ws.M, ld, n, n, kConditionedBeta / std::sqrt((float)n), s));
@@ -801,7 +801,7 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
             gelo_mixing* m = got[base + i];
             const uint64_t id = first_batch_id + (uint64_t)(base + i);
             // A = Q diag(sign r_ii); A^-1 = A^T
-            e = emit_matrix(lw[i].X, lw[i].n_pad / 16, householder_qr_leaves_q(n) ? 2 : 1, lw[i].rdiag, n, m->ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s);
+            e = emit_matrix(lw[i].X, lw[i].n_pad / 16, 1, lw[i].rdiag, n, m->ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s);
             if (e == hipSuccess && k_shield > 0) {
                 ps.c1 = kStreamShield << 8; ps.c2 = (uint32_t)id; ps.c3 = (uint32_t)(id >> 32);
                 e = shield_directions(m->GS, k_shield, d, ps, m->gsnorm, s);

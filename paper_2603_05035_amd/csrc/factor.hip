@@ -542,8 +542,8 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
     }
 }
 
-// A finished block of panels applied to everything behind it and to X, for `count` matrices: `outer` strips from
-// Cout, `acc` strips from X, one per workgroup.  Which workgroup takes which strip of which matrix is chosen for the
+// A block of panels applied to `outer` strips from Cout (the factorisation: the columns behind a finished block)
+// or to `acc` strips from X (forming Q), for `count` matrices, one strip per workgroup.  Which workgroup takes which strip of which matrix is chosen for the
 // L2s: workgroups are dealt to the 8 accelerator dies in turn (die = workgroup number mod 8), every strip of a matrix
 // reads that matrix's reflectors (1.1 MB for a block of four) and a die's L2 holds 4 MB - so a die works through
 // whole matrices one after the other (matrices die, die + 8, ...; with fewer than 8 matrices the dies that share a
@@ -577,22 +577,30 @@ void qr_bulk_kernel(QrBulkArgs a) {
     reflect_strip_lds_body<NBLK>(a.refl, a.pending, off, Cs + off, a.nb_block);
 }
 
+// Strips of more than 160 blocks (columns of more than 2560 rows) do not fit the 128 registers of qr_bulk_kernel:
+// the same pass with the strip and the reflector groups in registers (reflect_strip_body), one workgroup per
+// compute unit; grid x = strip of X, grid y = matrix.
+template <int NBLK>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void qr_long_strips_kernel(QrBulkArgs a) {
+    const int64_t off = (int64_t)blockIdx.y * a.batch_stride;
+    reflect_strip_body<NBLK, 1>(a.refl, a.pending, off, a.X + off + (int64_t)blockIdx.x * a.strip_stride, a.strip_stride, 1, a.nb_block);
+}
+
 // One launch per QR step p.  The chain of panel factorisations (one workgroup each) is the critical path, so
 // the launch that follows the factorisation of panel p also factorises panel p + 1.  Panels come in blocks of
-// D (delayed update): inside a block only the block's own columns see each new reflector at once; everything
-// outside it - the rest of the matrix and the accumulated transposed orthogonal factor X (starts as the
-// identity, ends as Q^T) - is read and written ONCE per block, by strips that apply the block's D reflectors in
-// a row while they hold their columns in registers.  That divides the memory traffic of the factorisation,
-// which is what bounds several factorisations running side by side, by almost D.
+// D (delayed update): inside a block only the block's own columns see each new reflector at once; the rest of
+// the matrix is read and written ONCE per block, by strips that apply the block's D reflectors in a row while
+// they hold their columns in registers.  That divides the memory traffic of the factorisation, which is what
+// bounds several factorisations running side by side, by almost D.
 //   workgroup 0          applies reflector p to the 16 columns of panel p + 1, then factorises them;
 //   `inner` workgroups   (inside a block) apply reflector p to the block's later panels and to the first panel
 //                        of the next block: its columns then lack only the newest reflector when workgroup 0
 //                        gets to them, as everywhere else on the chain;
-//   `outer` + `acc`      (a block has just been finished) apply its reflectors to the columns beyond panel
-//                        p + 1 and to all columns of X.
+//   `outer`              (a block has just been finished) apply its reflectors to the columns beyond panel p + 1.
 // Every strip reads only reflectors and its own columns; panel p + 1 writes its own columns, reflector buffers
 // no strip of this launch reads, and its own T: the workgroups of one launch never touch the same data.  Waves
-// of workgroup 0 that the panel does not use leave after the strip.
+// of workgroup 0 that the panel does not use leave after the strip.  Q is formed afterwards (householder_qr).
 struct QrStepArgs {
     Reflector refl[kMaxDelay];           // the current block's reflectors so far; shift = position in the block
     int pending;                         // how many of them (the newest is refl[pending - 1], reflector p)
@@ -600,10 +608,9 @@ struct QrStepArgs {
     float* C0;                           // the columns of panel p + 1: tile (row block p, column block p + 1)
     float* Cin;                          // tile (row block p, column block p + 2): `inner` strips from here
     float* Cout;                         // tile (row block of the block's first panel, column block p + 2): `outer` strips
-    float* X;                            // tile (row block of the block's first panel, column block 0): `acc` strips
     int64_t strip_stride;                // floats between the tiles of neighbouring column blocks
     int nb_single, nb_block;             // rows / 16 below the first row of reflector p / of the block's first reflector
-    int inner, outer, acc;               // strip counts
+    int inner, outer;                    // strip counts
     float* Vr_next; float* Vt_next; float* Tnext; float* rdiag_next;   // outputs of panel p + 1
     int m_next;                          // its row count (0: no further panel)
     int64_t batch_stride;                // floats from one matrix's workspace to the next one's (grid y = matrix)
@@ -634,13 +641,9 @@ void qr_step_kernel(QrStepArgs a) {
         reflect_strip_body<NBLK, 1>(&single, 1, off, a.Cin + off + (int64_t)(b - 1) * a.strip_stride, 0, 1, a.nb_single);
         return;
     }
-    // the strips behind the block and those of X, NS neighbours per workgroup
-    const int outer_wgs = (a.outer + NS - 1) / NS;
-    int idx = b - 1 - a.inner, range = a.outer;
-    float* Cs = a.Cout;
-    if (idx >= outer_wgs) { idx -= outer_wgs; range = a.acc; Cs = a.X; }
-    const int first = idx * NS, strips = range - first < NS ? range - first : NS;
-    reflect_strip_body<NBLK, NS>(a.refl, a.pending, off, Cs + off + (int64_t)first * a.strip_stride, a.strip_stride, strips, a.nb_block);
+    // the strips behind the block, NS neighbours per workgroup
+    const int first = (b - 1 - a.inner) * NS, strips = a.outer - first < NS ? a.outer - first : NS;
+    reflect_strip_body<NBLK, NS>(a.refl, a.pending, off, a.Cout + off + (int64_t)first * a.strip_stride, a.strip_stride, strips, a.nb_block);
 }
 
 // zeroes what lies beyond n x n of the tiled matrix M (n_pad x n_pad) and sets the tiled X to the identity
@@ -739,7 +742,7 @@ namespace {
 
 template <int NTHR, int R, int NBLK>
 hipError_t launch_qr_step_t(const QrStepArgs& a, int count, hipStream_t s) {
-    hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK, 1>), dim3(1 + a.inner + a.outer + a.acc, count), dim3(512), 0, s, a);
+    hipLaunchKernelGGL((qr_step_kernel<NTHR, R, NBLK, 1>), dim3(1 + a.inner + a.outer, count), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 
@@ -773,11 +776,15 @@ hipError_t launch_qr_bulk(const QrBulkArgs& b, int count, hipStream_t s) {
     if (per_wave <= 5) return launch_qr_bulk_t<5>(b, count, s);
     if (per_wave <= 10) return launch_qr_bulk_t<10>(b, count, s);
     if (per_wave <= 20) return launch_qr_bulk_t<20>(b, count, s);
+    if (per_wave <= 40 && b.outer == 0) {
+        hipLaunchKernelGGL((qr_long_strips_kernel<40>), dim3(b.acc, count), dim3(512), 0, s, b);
+        return hipGetLastError();
+    }
     return hipErrorInvalidValue;
 }
 
 hipError_t launch_qr_step(const QrStepArgs& a, int count, hipStream_t s) {
-    const int longest = (a.block_done && a.outer + a.acc > 0) ? a.nb_block : a.nb_single;
+    const int longest = (a.block_done && a.outer > 0) ? a.nb_block : a.nb_single;
     const int per_wave = (longest + 7) / 8;
     const int m = a.m_next;
     // (256 or 512 threads per panel made no difference at 2150 rows: what a column costs beyond its rows -
@@ -821,10 +828,9 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
     const int64_t set_floats = (int64_t)n_pad * NB;
     auto Vr_of = [&](int p) { return ws.Vc + (int64_t)p * set_floats; };
     auto Vt_of = [&](int p) { return ws.M + (int64_t)p * strip_stride + (int64_t)p * 256; };
-    // Q is formed AFTER the factorisation, last block first (householder_qr_leaves_q): block b then only meets the
-    // columns from its own first one on - the rest of H_b+1 ... H_N is still the identity there - which is
-    // 4/3 n^3 operations instead of the 2 n^3 of carrying Q^T along with the factorisation.
-    const bool backward = householder_qr_leaves_q(n);
+    // Q is formed AFTER the factorisation, last block first: block b then only meets the columns from its own first
+    // one on - the rest of H_b+1 ... H_N is still the identity there - which is 4/3 n^3 operations instead of the
+    // 2 n^3 of carrying Q^T along with the factorisation.
     {
         const int64_t elems = (int64_t)n_pad * n_pad;
         hipLaunchKernelGGL(qr_prepare_kernel, dim3((unsigned)((elems + 255) / 256), count), dim3(256), 0, s, ws.M, ws.X, n, n_pad, batch_stride);
@@ -852,11 +858,9 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
         a.C0 = last ? ws.M : ws.M + (int64_t)(p + 1) * strip_stride + (int64_t)p * 256;
         a.Cin = ws.M + (int64_t)(p + 2 < nbr ? p + 2 : 0) * strip_stride + (int64_t)p * 256;
         a.Cout = ws.M + (int64_t)(p + 2 < nbr ? p + 2 : 0) * strip_stride + (int64_t)p0 * 256;
-        a.X = ws.X + (int64_t)p0 * 256;                       // tile (p0, 0)
         // the block's panels behind p + 1 and the first panel of the next block
         a.inner = a.block_done ? 0 : (block_end < nbr ? block_end : nbr - 1) - (p + 1);
         a.outer = (a.block_done && p + 2 < nbr) ? nbr - (p + 2) : 0;
-        a.acc = (a.block_done && !backward) ? nbr : 0;
         a.Vr_next = Vr_of(p + 1); a.Vt_next = Vt_of(p + 1);
         a.Tnext = ws.Tmat + (int64_t)(p + 1) * NB * NB; a.rdiag_next = ws.rdiag + (p + 1) * NB;
         a.m_next = last ? 0 : n_pad - (p + 1) * NB;
@@ -865,18 +869,18 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
         // workgroups per compute unit, which the panel's registers rule out in the step kernel).  One matrix
         // alone keeps them beside workgroup 0: there the launch count and the chain of panels are what matters.
         // Either way every column sees the same arithmetic.
-        if (count >= kBulkFromCount && a.block_done && a.outer + a.acc > 0 && a.nb_block <= kBulkMaxBlocks) {
+        if (count >= kBulkFromCount && a.block_done && a.outer > 0 && a.nb_block <= kBulkMaxBlocks) {
             QrBulkArgs b;
             for (int q = 0; q < kMaxDelay; ++q) b.refl[q] = a.refl[q < a.pending ? q : 0];
-            b.pending = a.pending; b.Cout = a.Cout; b.X = a.X; b.outer = a.outer; b.acc = a.acc;
+            b.pending = a.pending; b.Cout = a.Cout; b.X = a.Cout; b.outer = a.outer; b.acc = 0;
             b.strip_stride = strip_stride; b.nb_block = a.nb_block; b.batch_stride = batch_stride; b.count = count;
             GELO_TRY(launch_qr_bulk(b, count, s));
-            a.outer = a.acc = 0;
+            a.outer = 0;
             if (last) continue;                               // no panel left: the step launch would be empty
         }
         GELO_TRY(launch_qr_step(a, count, s));
     }
-    if (backward) {
+    {
         // X = I so far.  Block by block from the last: X[p0:, p0:] <- H_p0 (H_p0+1 (... X[p0:, p0:])), one 16-column
         // strip per workgroup, the block's reflectors newest first, each as I - V T V^T.
         for (int p0 = (panels - 1) / D * D; p0 >= 0; p0 -= D) {
@@ -896,9 +900,6 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
     return hipSuccess;
 }
 
-// Forming Q behind the factorisation uses the strip kernel that keeps a strip of at most 160 blocks in 128
-// registers; longer columns keep the accumulation of Q^T inside the factorisation.  Depends on n alone.
-bool householder_qr_leaves_q(int n) { return (int)(round_up(n, NB) / NB) <= kBulkMaxBlocks; }
 
 // Brings this file's code onto the device (the runtime loads a code object on its first use, which allocates
 // device memory): contexts do this when they are created, so that no later call does.

@@ -156,9 +156,8 @@ hipError_t make_shields(const float* G, int64_t ldg, const float* gnorm, const f
 // Writes an n x n float matrix (src, optional per-column sign flip from `rdiag` < 0) into the
 // mixing buffers: dst32 / dst16 get the matrix, dstT32 / dstT16 its transpose (any may be null).
 // Every destination has `ldd` elements per row and its columns [n, ldd) are zero-filled.
-// src_tiled == 0: src is row-major with pitch lds; src_tiled == 1: src holds the TRANSPOSE of the
-// matrix in 16 x 16 tiles with lds tile rows, src_tiled == 2: the matrix itself in such tiles (the two
-// forms householder_qr leaves in ws.X, see householder_qr_leaves_q).
+// src_tiled == 0: src is row-major with pitch lds; src_tiled != 0: src holds the matrix in 16 x 16
+// tiles with lds tile rows (what householder_qr leaves in ws.X).
 hipError_t emit_matrix(const float* src, int64_t lds, int src_tiled, const float* rdiag, int n, int64_t ldd,
                        float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16,
                        hipStream_t stream);
@@ -231,14 +230,10 @@ void factor_workspace_carve(void* base, int n, FactorWorkspace* ws);
 
 // ws.M holds an n x n matrix in 16 x 16 tiles (qr_tile_index with n_pad / 16 tile rows; what lies
 // beyond n need not be initialised).  On return ws.X holds the orthogonal factor Q of its Householder
-// QR or its transpose (householder_qr_leaves_q), in the same tiled layout (identity in the padding block), ws.M
-// and ws.Vc the reflectors, and
+// QR in the same tiled layout (identity in the padding block), ws.M and ws.Vc the reflectors, and
 // ws.rdiag the diagonal of R.  `count` > 1 factorises that many matrices side by side in the same launches (grid y):
 // matrix i's workspace is the one carved at `batch_stride` floats times i behind ws's (same n for all).
 hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t batch_stride, hipStream_t stream);
-// true: householder_qr leaves Q itself in ws.X for this n (formed after the factorisation), not Q^T; pass
-// src_tiled = 2 instead of 1 to emit_matrix then
-bool householder_qr_leaves_q(int n);
 // ws.M holds an n_pad x n_pad matrix with an identity block in the padding.  On return ws.X holds
 // its inverse (via row-pivoted LU), *ws.flag != 0 if a zero pivot was met.
 hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t stream);

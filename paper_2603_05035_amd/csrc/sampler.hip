@@ -171,7 +171,7 @@ void emit_matrix_kernel(const float* src, int64_t lds, int src_tiled, const floa
         const int r = r0 + i, c = c0 + tx;
         float x = 0.f;
         if (r < n && c < n) {
-            x = src_tiled == 1 ? src[qr_tile_index(c, r, (int)lds)] : src_tiled == 2 ? src[qr_tile_index(r, c, (int)lds)] : src[(int64_t)r * lds + c];
+            x = src_tiled ? src[qr_tile_index(r, c, (int)lds)] : src[(int64_t)r * lds + c];
             if (rdiag != nullptr && rdiag[c] < 0.f) x = -x;
         }
         tile[i][tx] = x;
