@@ -772,10 +772,22 @@ hipError_t launch_qr_bulk_t(const QrBulkArgs& b, int count, hipStream_t s) {
 // strips of at most 160 blocks only (20 per wave: what fits 128 registers)
 constexpr int kBulkMaxBlocks = 160;
 hipError_t launch_qr_bulk(const QrBulkArgs& b, int count, hipStream_t s) {
+    // blocks per wave in steps of two: a strip kernel sized for 20 blocks spends a third more time on a strip of 11
+    // than one sized for 12 (it still requests and waits for the blocks that do not exist)
     const int per_wave = (b.nb_block + 7) / 8;
-    if (per_wave <= 5) return launch_qr_bulk_t<5>(b, count, s);
-    if (per_wave <= 10) return launch_qr_bulk_t<10>(b, count, s);
-    if (per_wave <= 20) return launch_qr_bulk_t<20>(b, count, s);
+    switch ((per_wave + 1) / 2) {
+        case 0: case 1: return launch_qr_bulk_t<2>(b, count, s);
+        case 2: return launch_qr_bulk_t<4>(b, count, s);
+        case 3: return launch_qr_bulk_t<6>(b, count, s);
+        case 4: return launch_qr_bulk_t<8>(b, count, s);
+        case 5: return launch_qr_bulk_t<10>(b, count, s);
+        case 6: return launch_qr_bulk_t<12>(b, count, s);
+        case 7: return launch_qr_bulk_t<14>(b, count, s);
+        case 8: return launch_qr_bulk_t<16>(b, count, s);
+        case 9: return launch_qr_bulk_t<18>(b, count, s);
+        case 10: return launch_qr_bulk_t<20>(b, count, s);
+        default: break;
+    }
     if (per_wave <= 40 && b.outer == 0) {
         hipLaunchKernelGGL((qr_long_strips_kernel<40>), dim3(b.acc, count), dim3(512), 0, s, b);
         return hipGetLastError();
