@@ -179,7 +179,7 @@ MixingLayout mixing_layout(int n_data, int k, int d, int dtype, bool structured)
     const int64_t ldk = round_up(n, 64);
     L.mat32 = structured ? 0 : up256((size_t)n * ldk * 4);
     L.mat16 = (structured || dtype != GELO_BF16) ? 0 : up256((size_t)n * ldk * 2);
-    L.tab = structured ? up256((size_t)(kStructuredRounds + 1) * n * 4) : 0;
+    L.tab = structured ? up256(structured_table_words(n, kStructuredRounds) * 4) : 0;
     L.gs = up256((size_t)(k > 0 ? k : 1) * d * 4);
     L.s = up256((size_t)(k > 0 ? k : 1) * d * elem_size(dtype));
     L.gsnorm = up256((size_t)(k + 1) * 4);
@@ -1038,7 +1038,9 @@ gelo_status gelo_mixing_export_table(gelo_ctx* ctx, const gelo_mixing* m, uint32
     GELO_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
     if (s != m->sample_stream) GELO_HIP(ctx, hipStreamWaitEvent(s, m->ready, 0));
-    GELO_HIP(ctx, hipMemcpyAsync(table, m->table, (size_t)(kStructuredRounds + 1) * m->n * sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
+    // the library's tables start on 16-byte boundaries; the caller's are packed
+    GELO_HIP(ctx, hipMemcpy2DAsync(table, (size_t)m->n * sizeof(uint32_t), m->table, (size_t)round_up(m->n, 4) * sizeof(uint32_t),
+                                   (size_t)m->n * sizeof(uint32_t), kStructuredRounds + 1, hipMemcpyDeviceToDevice, s));
     return GELO_OK;
 }
 

@@ -188,10 +188,13 @@ hipError_t small_mix(const uint16_t* A16, int64_t ldk, const uint16_t* H, int64_
 
 // ------------------------------------------------- structured orthogonal A --
 constexpr int kStructuredRounds = 3;
-// table[(rounds + 1) x n]: the permutations (low 31 bits) and sign flips (top bit) of one structured
+// table: the rounds + 1 permutations (low 31 bits) and sign flips (top bit) of one structured
 // A = P_R (B D_{R-1} P_{R-1}) ... (B D_0 P_0), drawn from the Philox streams of (seed, batch id) in ps
-// (ps.c1 is not used: the streams are fixed).
+// (ps.c1 is not used: the streams are fixed), each in round_up(n, 4) words, and behind them the rounds + 1
+// inverse permutations with the same signs (what the transposed transform gathers by):
+// structured_table_words(n, rounds) words in all.
 hipError_t structured_tables(uint32_t* table, int n, int rounds, PhiloxStream ps, hipStream_t stream);
+size_t structured_table_words(int n, int rounds);
 // out = A x (transposed == 0) or A^T x (transposed != 0) for the n x ncols operand x whose rows
 // [0, rows0) come from in0 and rows [rows0, n) from in1 (may be null when rows0 == n); result rows
 // >= rows_out are dropped.  float or bf16 throughout; ncols a multiple of 4 and every row start

@@ -74,10 +74,10 @@ def test_table_words_are_bit_exact(ctx, n_data, k):
     assert not sign_bits[3].any()
 
 
-@pytest.mark.parametrize("n_data,k", [(2400, 0), (2401, 0), (4096, 205), (4816, 0), (4817, 0), (5000, 120)])
+@pytest.mark.parametrize("n_data,k", [(2272, 0), (2273, 0), (4096, 205), (4304, 0), (4305, 0), (5000, 120)])
 def test_tables_at_the_narrow_strip_widths(ctx, n_data, k):
-    """A workgroup keeps 16 columns of the strip in LDS up to 2400 rows (all 160 KB of it then), 8 up to 4816,
-    4 beyond, up to n = GELO_MAX_N: both sides of each boundary.  The dense oracle matrix would cost minutes
+    """A workgroup keeps 16 columns of the strip (and one table) in LDS up to 2272 rows (all 160 KB of it then),
+    8 up to 4304, 4 beyond, up to n = GELO_MAX_N: both sides of each boundary.  The dense oracle matrix would cost minutes
     here: sampled columns of A and A^T through the oracle's factor-by-factor transform, and orthogonality of
     the exported pair."""
     n = n_data + k
