@@ -26,6 +26,54 @@ void fill_normal_kernel(float* out, int64_t ld, int rows, int cols, PhiloxStream
     }
 }
 
+// The same values into the QR's 16 x 16 tiles (qr_tile_index).  Element e = r cols + c is output e % 4 of
+// Philox block e / 4, so a block's four values are neighbours in a ROW while a tile keeps a COLUMN's 16 rows
+// together: written straight from the registers every store of a wave would touch 64 cache lines.  A workgroup
+// instead takes 16 rows x 256 columns, computes the blocks that cover each of its row segments (one more per
+// row than the segment holds when its ends fall inside blocks), sets the values down in LDS and writes the 16
+// tiles out as they lie in memory, 16 bytes per lane.
+__global__ __launch_bounds__(256)
+void fill_normal_tiled_kernel(float* out, int tile_rows, int rows, int cols, PhiloxStream ps, float scale) {
+    constexpr int CW = 256, PITCH = CW + 1, PER_ROW = CW / 4 + 1;
+    __shared__ float tile[16 * PITCH];
+    const int tid = threadIdx.x;
+    const int r0 = blockIdx.y * 16, c0 = blockIdx.x * CW;
+    const int width = min(CW, cols - c0);
+    for (int idx = tid; idx < 16 * PER_ROW; idx += 256) {
+        const int ri = idx / PER_ROW, bi = idx - ri * PER_ROW;
+        const int r = r0 + ri;
+        if (r >= rows) break;
+        const uint32_t e_first = (uint32_t)r * (uint32_t)cols + (uint32_t)c0, e_last = e_first + (uint32_t)width - 1u;
+        const uint32_t b = e_first / 4u + (uint32_t)bi;
+        if (4u * b > e_last) continue;
+        uint32_t w0 = b, w1 = ps.c1, w2 = ps.c2, w3 = ps.c3;
+        philox4x32_10(w0, w1, w2, w3, ps.key0, ps.key1);
+        float z[4];
+        box_muller(w0, w1, &z[0], &z[1]);
+        box_muller(w2, w3, &z[2], &z[3]);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t e = 4u * b + (uint32_t)t;
+            if (e >= e_first && e <= e_last) tile[ri * PITCH + (int)(e - e_first)] = scale * z[t];
+        }
+    }
+    __syncthreads();
+    // float4 item: rows 4 g .. 4 g + 3 of column c of the strip (16 bytes of a tile: index (c & 15) * 16 + 4 g)
+    for (int it = tid; it < CW * 4; it += 256) {
+        const int c = it >> 2, g = it & 3;
+        if (c >= width) continue;
+        float* dst = out + qr_tile_index(r0 + 4 * g, c0 + c, tile_rows);
+        const float* src = tile + (4 * g) * PITCH + c;
+        if (r0 + 4 * g + 3 < rows) {
+            *reinterpret_cast<float4*>(dst) = make_float4(src[0], src[PITCH], src[2 * PITCH], src[3 * PITCH]);
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (r0 + 4 * g + t < rows) dst[t] = src[t * PITCH];
+        }
+    }
+}
+
 // Raw generator output for bitwise checks: words[4 i .. 4 i + 3] = the four words of block first + i.
 __global__ __launch_bounds__(256)
 void philox_words_kernel(uint32_t* words, uint32_t first, uint32_t blocks, PhiloxStream ps) {
@@ -209,6 +257,11 @@ hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream 
                        int tiled, hipStream_t stream) {
     const int64_t quads = ((int64_t)rows * cols + 3) / 4;
     if (quads == 0) return hipSuccess;
+    if (tiled && (int64_t)rows * cols < ((int64_t)1 << 32)) {
+        hipLaunchKernelGGL(fill_normal_tiled_kernel, dim3((cols + 255) / 256, (rows + 15) / 16), dim3(256), 0, stream,
+                           out, (int)ld, rows, cols, ps, scale);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(fill_normal_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
                        out, ld, rows, cols, ps, scale, tiled);
     return hipGetLastError();
