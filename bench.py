@@ -138,7 +138,7 @@ def run_composite(args, torch, np, g, wl):
         # every chain takes an ORTHOGONAL A of one shape: batched draws (`group` matrices per call, their factorisations
         # side by side) on side streams, `rings` groups alive - one being consumed while the others are drawn
         w0 = parts[0]
-        group = next(b for b in (16, 12, 8, 6, 4, 2, 1) if (K * L) % b == 0 and (Wm * L) % b == 0)
+        group = next(b for b in range(min(32, K * L), 0, -1) if (K * L) % b == 0)   # divides the timed chains: exactly K L draws fall into them
         rings = 3
         depth = group * rings
         side = [torch.cuda.Stream() for _ in range(rings)]
@@ -162,6 +162,7 @@ def run_composite(args, torch, np, g, wl):
             g.gelo_project(ctxs[r], u, Ws[l], y)
             g.gelo_unmix(ctxs[r], m, y, z)
             g.gelo_mixing_free(ctxs[r], m)
+            ring[r][j] = None
             if j == group - 1:
                 draw_group(r)
 
@@ -178,7 +179,8 @@ def run_composite(args, torch, np, g, wl):
         t_step = (time.perf_counter() - t0) / K
         for r in range(rings):
             for m in ring[r]:
-                g.gelo_mixing_free(ctxs[r], m)
+                if m is not None:
+                    g.gelo_mixing_free(ctxs[r], m)
         i = nxt[0]
     else:
         side = [torch.cuda.Stream() for _ in range(depth)]
@@ -418,9 +420,10 @@ def main() -> int:
     bid = [0]
     if w.kind == g.GELO_ORTHOGONAL:
         # batched draws: `group` matrices per call (their factorisations share every launch), `rings` groups alive:
-        # one being consumed while the others are drawn on side streams.  The group size divides K and W, so the
-        # timed region issues exactly K draws and K chains.
-        group = next(b for b in (32, 24, 16, 12, 8, 6, 5, 4, 3, 2, 1) if K % b == 0 and Wm % b == 0 and b <= max(1, args.draw_batch))
+        # one being consumed while the others are drawn on side streams.  A group is drawn at every step whose
+        # number is group - 1 modulo the group size; the group size divides K, so ANY K consecutive steps - the
+        # timed region, whatever the warm-up count - issue exactly K / group draw calls = K draws, and K chains.
+        group = next(b for b in range(min(max(1, args.draw_batch), K), 0, -1) if K % b == 0)
         rings = 3
         depth = group * rings
         side = [torch.cuda.Stream() for _ in range(rings)]
@@ -440,12 +443,13 @@ def main() -> int:
             g.gelo_project(ctxs[r], U, W, Y)
             g.gelo_unmix(ctxs[r], m, Y, Z)
             g.gelo_mixing_free(ctxs[r], m)
+            ring[r][j] = None
             if j == group - 1:
                 draw_group(r)                                       # the group's next `group` batches
 
         for r in range(rings):
             draw_group(r)
-        leftovers = lambda: [(ctxs[r], m) for r in range(rings) for m in ring[r]]
+        leftovers = lambda: [(ctxs[r], m) for r in range(rings) for m in ring[r] if m is not None]
     else:
         group = 1
         depth = args.pipeline
