@@ -547,7 +547,10 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
 // L2s: workgroups are dealt to the 8 accelerator dies in turn (die = workgroup number mod 8), every strip of a matrix
 // reads that matrix's reflectors (1.1 MB for a block of four) and a die's L2 holds 4 MB - so a die works through
 // whole matrices one after the other (matrices die, die + 8, ...; with fewer than 8 matrices the dies that share a
-// matrix split its strips) instead of meeting all `count` sets of reflectors at once.
+// matrix split its strips) instead of meeting all `count` sets of reflectors at once.  A count that is not a
+// multiple of 8 is dealt in two parts: whole rounds of 8 matrices, one per die, then the remaining count % 8
+// matrices with their strips split over the dies that share each (20 matrices: two rounds, then 4 matrices on two
+// dies each - a die works off 2.5 matrices' strips, not 3).
 struct QrBulkArgs {
     Reflector refl[kMaxDelay]; int pending;
     float* Cout; float* X; int outer, acc;
@@ -555,21 +558,28 @@ struct QrBulkArgs {
 };
 // workgroups per die that the deal needs
 inline int qr_bulk_slots(int strips, int count) {
-    if (count >= 8) return (count + 7) / 8 * strips;
-    const int dies = 8 / count;                              // the fewest dies any matrix gets
-    return (strips + dies - 1) / dies;
+    const int rounds = count / 8, rest = count % 8;
+    int slots = rounds * strips;
+    if (rest > 0) {
+        const int dies = 8 / rest;                           // the fewest dies any of the remaining matrices gets
+        slots += (strips + dies - 1) / dies;
+    }
+    return slots;
 }
 
 template <int NBLK>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void qr_bulk_kernel(QrBulkArgs a) {
     const int die = blockIdx.x & 7, slot = blockIdx.x >> 3, strips = a.outer + a.acc;
+    const int rounds = a.count >> 3, rest = a.count & 7;
     int matrix, b;
-    if (a.count >= 8) { matrix = die + 8 * (slot / strips); b = slot % strips; }
+    if (slot < rounds * strips) { matrix = die + 8 * (slot / strips); b = slot % strips; }
     else {
-        matrix = die % a.count;
-        const int sharing = (8 - matrix + a.count - 1) / a.count;       // dies with die % count == matrix
-        b = slot * sharing + die / a.count;
+        if (rest == 0) return;
+        const int mr = die % rest;
+        const int sharing = (8 - mr + rest - 1) / rest;      // dies with die % rest == mr
+        matrix = 8 * rounds + mr;
+        b = (slot - rounds * strips) * sharing + die / rest;
     }
     if (matrix >= a.count || b >= strips) return;
     const int64_t off = (int64_t)matrix * a.batch_stride;
