@@ -163,10 +163,10 @@ def run_composite(args, torch, np, g, wl):
             g.gelo_unmix(ctxs[r], m, y, z)
             g.gelo_mixing_free(ctxs[r], m)
             ring[r][j] = None
-            if j == group - 1:
-                draw_group(r)
+            if j == (Wm * L) % group:                        # the timed region opens with a draw (as in main)
+                draw_group((r + rings - 1) % rings)
 
-        for r in range(rings):
+        for r in range(rings - 1):
             draw_group(r)
         i = 0
         for _ in range(Wm * L):
@@ -178,7 +178,7 @@ def run_composite(args, torch, np, g, wl):
         torch.cuda.synchronize()
         t_step = (time.perf_counter() - t0) / K
         for r in range(rings):
-            for m in ring[r]:
+            for m in (ring[r] or []):
                 if m is not None:
                     g.gelo_mixing_free(ctxs[r], m)
         i = nxt[0]
@@ -421,8 +421,9 @@ def main() -> int:
     if w.kind == g.GELO_ORTHOGONAL:
         # batched draws: `group` matrices per call (their factorisations share every launch), `rings` groups alive:
         # one being consumed while the others are drawn on side streams.  A group is drawn at every step whose
-        # number is group - 1 modulo the group size; the group size divides K, so ANY K consecutive steps - the
-        # timed region, whatever the warm-up count - issue exactly K / group draw calls = K draws, and K chains.
+        # number is the warm-up count modulo the group size (so the first timed step issues one: a short timed
+        # region then overlaps its draws with its chains as a long one does); the group size divides K, so ANY K
+        # consecutive steps - the timed region - issue exactly K / group draw calls = K draws, and K chains.
         group = next(b for b in range(min(max(1, args.draw_batch), K), 0, -1) if K % b == 0)
         rings = 3
         depth = group * rings
@@ -444,12 +445,12 @@ def main() -> int:
             g.gelo_unmix(ctxs[r], m, Y, Z)
             g.gelo_mixing_free(ctxs[r], m)
             ring[r][j] = None
-            if j == group - 1:
-                draw_group(r)                                       # the group's next `group` batches
+            if j == Wm % group:                                     # the timed region opens with a draw and overlaps it whole
+                draw_group((r + rings - 1) % rings)                 # the group consumed before this one is replaced
 
-        for r in range(rings):
+        for r in range(rings - 1):                                  # two groups ahead; the third is drawn at step Wm % group
             draw_group(r)
-        leftovers = lambda: [(ctxs[r], m) for r in range(rings) for m in ring[r] if m is not None]
+        leftovers = lambda: [(ctxs[r], m) for r in range(rings) for m in (ring[r] or []) if m is not None]
     else:
         group = 1
         depth = args.pipeline
