@@ -160,23 +160,26 @@ void mean_kernel(const float* v, int count, float* out) {
 // Median of v[0:count] (non-negative floats, whose order is that of their bit patterns) as its two
 // middle elements: out[0] = element of rank (count - 1) / 2, out[1] = element of rank count / 2 (the
 // same element when count is odd); the median is their mean.  Every element finds its rank by
-// counting the (value, index) pairs below its own - count^2 comparisons spread over count / 64
+// counting the (value, index) pairs below its own - count^2 comparisons spread over count / 16
 // workgroups - and the two that hit the middle ranks write themselves out: no sorting, no atomics,
 // and exactly one writer per slot.
 __global__ __launch_bounds__(256)
 void median_parts_kernel(const float* v, int count, float* out) {
+    // 16 elements per workgroup, each counted by 16 threads over a sixteenth of the keys: the count is a chain of
+    // dependent compare-and-add steps, so its length per thread, not the number of workgroups, sets the time
+    constexpr int EL = 16, PARTS = 256 / EL;
     extern __shared__ __align__(16) uint32_t keys[];        // count rounded up to 4; the padding holds the largest key
-    __shared__ int part_count[4][64];
+    __shared__ int part_count[PARTS][EL];
     const int tid = threadIdx.x;
     const int padded = (count + 3) & ~3;
     for (int i = tid; i < padded; i += 256) keys[i] = i < count ? __float_as_uint(v[i]) : 0xFFFFFFFFu;
     __syncthreads();
-    const int slot = tid & 63, part = tid >> 6;
-    const int i = blockIdx.x * 64 + slot;
+    const int slot = tid % EL, part = tid / EL;
+    const int i = blockIdx.x * EL + slot;
     int below = 0;
     if (i < count) {
         const uint4* keys4 = reinterpret_cast<const uint4*>(keys);
-        const int quads = padded / 4, chunk = (quads + 3) / 4;
+        const int quads = padded / 4, chunk = (quads + PARTS - 1) / PARTS;
         const int lo = part * chunk, hi = min(quads, lo + chunk);
         const uint64_t mine = ((uint64_t)keys[i] << 32) | (uint32_t)i;
         auto is_below = [&](uint32_t kk, int k) { return ((((uint64_t)kk << 32) | (uint32_t)k) < mine) ? 1 : 0; };
@@ -189,7 +192,9 @@ void median_parts_kernel(const float* v, int count, float* out) {
     part_count[part][slot] = below;
     __syncthreads();
     if (part != 0 || i >= count) return;
-    const int rank = part_count[0][slot] + part_count[1][slot] + part_count[2][slot] + part_count[3][slot];
+    int rank = 0;
+#pragma unroll
+    for (int q = 0; q < PARTS; ++q) rank += part_count[q][slot];
     if (rank == (count - 1) / 2) out[0] = __uint_as_float(keys[i]);
     if (rank == count / 2) out[1] = __uint_as_float(keys[i]);
 }
@@ -299,7 +304,7 @@ hipError_t row_norms(const void* X, int is_bf16, int64_t ld, int rows, int cols,
 hipError_t norm_statistic(const float* v, int count, int stat, float* out, hipStream_t stream) {
     if (count <= 0) return hipErrorInvalidValue;
     if (stat == 1) hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(1024), 0, stream, v, count, out);
-    else hipLaunchKernelGGL(median_parts_kernel, dim3((count + 63) / 64), dim3(256), (size_t)((count + 3) & ~3) * sizeof(uint32_t),
+    else hipLaunchKernelGGL(median_parts_kernel, dim3((count + 15) / 16), dim3(256), (size_t)((count + 3) & ~3) * sizeof(uint32_t),
                             stream, v, count, out);
     return hipGetLastError();
 }
