@@ -42,6 +42,7 @@ STREAM_SHIELD = 1        # Gaussian directions of the shield rows
 STREAM_PERTURB = 2       # second Gaussian of the conditioned non-orthogonal A
 STREAM_STRUCT_PERM = 3   # sort keys of the permutations of the structured orthogonal A
 STREAM_STRUCT_SIGN = 4   # its sign flips
+STREAM_BLOCK = 5         # Gaussians of the diagonal blocks of the block-diagonal orthogonal A (sub-stream = block)
 
 
 def philox4x32_10(counter, key):
@@ -342,6 +343,45 @@ def sample_structured(seed, batch_id, n, rounds=STRUCTURED_ROUNDS):
 
 
 # --------------------------------------------------------------------------
+# Block-diagonal orthogonal A: the mixed rows are cut into blocks of at most
+# BLOCK_ROWS rows and each block is mixed by a dense orthogonal matrix of its
+# own (a Householder QR of its own Gaussian, as in the paper's A-gen step).
+# The paper does not describe it; it is the cheaper-fresh-A direction of its
+# Conclusion taken the other way from the structured transform: mixing cost
+# O(n b (d + p)) instead of O(n^2 (d + p)), at the price that rows only mix
+# inside their block.  Every block takes its share of the shield rows.
+# --------------------------------------------------------------------------
+BLOCK_ROWS = 256
+
+
+def block_layout(n_data, k, block=BLOCK_ROWS):
+    """How the n = n_data + k mixed rows are cut: a list of (row0, rows, data0, data_rows, shield0, shield_rows).
+    Block i owns mixed rows [row0, row0 + rows), rows = min(block, n - row0); of the rows up to a cut r, floor(k r / n)
+    are shield rows and the rest data rows, so every block gets shield rows in proportion to its size."""
+    n = n_data + k
+    cuts = list(range(0, n, block)) + [n]
+    out = []
+    for i in range(len(cuts) - 1):
+        r0, r1 = cuts[i], cuts[i + 1]
+        s0, s1 = (k * r0) // n, (k * r1) // n
+        out.append((r0, r1 - r0, r0 - s0, (r1 - s1) - (r0 - s0), s0, s1 - s0))
+    return out
+
+
+def sample_block_orthogonal(seed, batch_id, n_data, k, block=BLOCK_ROWS):
+    """The dense n x n matrix that acts on the stacked rows [H; S] (data rows first, shield rows last): mixed rows
+    [row0, row0 + rows) = A_i [H[data0 : data0 + data_rows]; S[shield0 : shield0 + shield_rows]] with A_i the
+    orthogonal factor (positive-diagonal R) of the block's own Gaussian.  Returns (A, A^-1 = A^T)."""
+    n = n_data + k
+    A = np.zeros((n, n), dtype=np.float64)
+    for i, (r0, rows, d0, dn, s0, sn) in enumerate(block_layout(n_data, k, block)):
+        Ai = orthogonal_from_gaussian(gaussian_matrix(seed, batch_id, STREAM_BLOCK, i, rows, rows))
+        A[r0:r0 + rows, d0:d0 + dn] = Ai[:, :dn]
+        A[r0:r0 + rows, n_data + s0:n_data + s0 + sn] = Ai[:, dn:]
+    return A, A.T.copy()
+
+
+# --------------------------------------------------------------------------
 # Shield rows (Section 3.2.1, Mitigation 2, eqs. 7-9).
 # --------------------------------------------------------------------------
 NORM_MEDIAN = 0
@@ -402,6 +442,7 @@ KIND_ORTHOGONAL = 0
 KIND_GAUSSIAN = 1
 KIND_CONDITIONED = 2
 KIND_STRUCTURED = 3
+KIND_BLOCK_ORTHOGONAL = 4
 
 
 def sample_mixing(kind, seed, batch_id, n, cond_max=1e3, max_attempts=64):
@@ -427,7 +468,11 @@ def qkv_forward(kind, seed, batch_id, H, W, k_shield=0, shield_scale=10.0,
     H = np.asarray(H, dtype=np.float64)
     n_data, d = H.shape
     n = n_data + k_shield
-    A, A_inv, info = sample_mixing(kind, seed, batch_id, n, cond_max, max_attempts)
+    if kind == KIND_BLOCK_ORTHOGONAL:                      # its blocks depend on how n splits into data and shield rows
+        A, A_inv = sample_block_orthogonal(seed, batch_id, n_data, k_shield)
+        info = {"attempt": 0, "kappa": 1.0}
+    else:
+        A, A_inv, info = sample_mixing(kind, seed, batch_id, n, cond_max, max_attempts)
     S = shield_rows(H, sample_shield_directions(seed, batch_id, k_shield, d), shield_scale, stat)
     U = mix(A, H, S)
     Y = project(U, W)
