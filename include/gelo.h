@@ -82,8 +82,19 @@ typedef enum { GELO_F32 = 0, GELO_BF16 = 1 } gelo_dtype;
  *               construction of this library's own.  It leaks what every orthogonal A leaks
  *               (Section 3.2.1 eqs. 5-6: U^T U = H^T H, the spectrum of H H^T) and comes from a finite
  *               family, 4 permutations and 3 n sign bits; its resistance to the attacks of Section 4 has
- *               not been measured by anyone.  gelo_mixing_export builds the dense A for inspection. */
-typedef enum { GELO_ORTHOGONAL = 0, GELO_GAUSSIAN = 1, GELO_CONDITIONED = 2, GELO_STRUCTURED = 3 } gelo_kind;
+ *               not been measured by anyone.  gelo_mixing_export builds the dense A for inspection.
+ *  BLOCK_ORTHOGONAL  the mixed rows are cut into blocks of at most GELO_BLOCK_ROWS rows and each block is
+ *               mixed by a dense orthogonal matrix of its own (the ORTHOGONAL construction on the block's own
+ *               Philox Gaussian): rows [r0, r0 + rows) of U = A_i [H[d0 : d0 + dn]; S[s0 : s0 + sn]], where
+ *               of the rows up to a cut r floor(k_shield r / n) are shield rows, so every block gets its
+ *               share of them.  A^-1 = A^T.  Mixing costs O(n GELO_BLOCK_ROWS (d + p)) instead of
+ *               O(n^2 (d + p)) and drawing it O(n GELO_BLOCK_ROWS^2): the other route to the cheaper fresh
+ *               mixing the paper's Conclusion asks for.  What it gives up: rows mix only inside their block
+ *               (a block's U^T U is the Gram matrix of ITS rows of [H; S], so the leak of eq. 5 is per block,
+ *               244 rows at a time here instead of all n_data), which the paper does not analyse.
+ *               gelo_mixing_export builds the dense n x n matrix that acts on the stacked [H; S]. */
+typedef enum { GELO_ORTHOGONAL = 0, GELO_GAUSSIAN = 1, GELO_CONDITIONED = 2, GELO_STRUCTURED = 3,
+               GELO_BLOCK_ORTHOGONAL = 4 } gelo_kind;
 
 /* Row-norm statistic of H that the shield rows are scaled by. */
 typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;
@@ -93,6 +104,7 @@ typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;
 #define GELO_BATCH_WINDOW 4096 /* how far below the highest batch id used so far an unused id is still accepted */
 #define GELO_STATIC_MAX_N 128  /* largest n gelo_qkv_forward_static takes (and one-launch batched draws) */
 #define GELO_MAX_BATCH_DRAW 48 /* mixing objects one gelo_sample_mixing_batch call draws */
+#define GELO_BLOCK_ROWS 256    /* mixed rows per block of a GELO_BLOCK_ORTHOGONAL A */
 #define GELO_STATIC_SCRATCH_BYTES (16u << 20)   /* size of its static device buffer, held per GPU until the process ends */
 
 /* Creates a context on HIP device `device` with Philox key `seed`.  `allow_batch_reuse` != 0
@@ -219,7 +231,7 @@ gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, in
  * Calls no hipMalloc / hipFree and creates no stream, event or pooled object.  n = n_data + k_shield
  * <= GELO_STATIC_MAX_N, and the batch's buffers (about 0.6 MB at n = 128 plus 10 bytes (bf16) or
  * 12 bytes (float) per element of the k_shield x d shield block) must fit the static buffer:
- * GELO_ESHAPE otherwise.  kind: GELO_ORTHOGONAL, GELO_CONDITIONED or GELO_STRUCTURED.  U (n x d) and
+ * GELO_ESHAPE otherwise.  kind: GELO_ORTHOGONAL, GELO_CONDITIONED, GELO_STRUCTURED or GELO_BLOCK_ORTHOGONAL.  U (n x d) and
  * Y (n x p) are required; H, W, Z, U, Y densely packed as in gelo_qkv_forward.  All calls on one GPU
  * share the one buffer, whatever their context or stream: calls that overlap in time on a GPU race;
  * issue them on one stream or order them yourself.  Same results, bit for bit, as gelo_qkv_forward

@@ -20,7 +20,7 @@ using namespace gelo;
 namespace {
 constexpr float kConditionedBeta = 0.25f;
 constexpr int kKappaSteps = 20;          // Lanczos steps of the condition estimate
-constexpr uint32_t kStreamMixing = 0, kStreamShield = 1, kStreamPerturb = 2;
+constexpr uint32_t kStreamMixing = 0, kStreamShield = 1, kStreamPerturb = 2, kStreamBlock = 5;   // (3, 4: the structured kind)
 // GAUSSIAN draws are accepted or rejected by their condition number, and a draw's chain of small
 // launches leaves most of the chip idle: up to kLanes consecutive attempts are factorised side by
 // side on library-owned streams, each in a workspace of its own, and the first acceptable one in
@@ -66,6 +66,7 @@ struct gelo_mixing {
     uint16_t* A16; uint16_t* Ainv16;
     uint32_t* table;             // STRUCTURED only: its permutations and sign flips, nothing dense is kept
     bool structured;
+    bool blocked;                // BLOCK_ORTHOGONAL: A32 ... Ainv16 hold the blocks one below the other, GELO_BLOCK_ROWS columns wide
     float* GS;                   // k x d shield directions
     float* gsnorm;               // k
     void* S;                     // k x d shield rows in the compute dtype
@@ -173,10 +174,16 @@ gelo_status grow(gelo_ctx* ctx, void** buf, size_t* have, size_t need) {
 // Sizes of the device block behind one mixing object and where its parts sit in it.
 struct MixingLayout { size_t mat32, mat16, tab, gs, s, gsnorm, rownorm, total; };
 
-MixingLayout mixing_layout(int n_data, int k, int d, int dtype, bool structured) {
+enum MixingForm { kDense = 0, kStructuredForm = 1, kBlocked = 2 };
+inline MixingForm form_of(gelo_kind kind) {
+    return kind == GELO_STRUCTURED ? kStructuredForm : kind == GELO_BLOCK_ORTHOGONAL ? kBlocked : kDense;
+}
+
+MixingLayout mixing_layout(int n_data, int k, int d, int dtype, MixingForm form) {
     MixingLayout L;
+    const bool structured = form == kStructuredForm;
     const int n = n_data + k;
-    const int64_t ldk = round_up(n, 64);
+    const int64_t ldk = form == kBlocked ? GELO_BLOCK_ROWS : round_up(n, 64);
     L.mat32 = structured ? 0 : up256((size_t)n * ldk * 4);
     L.mat16 = (structured || dtype != GELO_BF16) ? 0 : up256((size_t)n * ldk * 2);
     L.tab = structured ? up256(structured_table_words(n, kStructuredRounds) * 4) : 0;
@@ -189,10 +196,11 @@ MixingLayout mixing_layout(int n_data, int k, int d, int dtype, bool structured)
 }
 
 // Fills the shape fields of `m` and points its buffers into the device block at `base` (L.total bytes).
-void carve_mixing(gelo_mixing* m, void* base, int n_data, int k, int d, int dtype, bool structured) {
-    const MixingLayout L = mixing_layout(n_data, k, d, dtype, structured);
-    m->n_data = n_data; m->k = k; m->n = n_data + k; m->d = d; m->dtype = dtype; m->structured = structured;
-    m->ldk = round_up(m->n, 64);
+void carve_mixing(gelo_mixing* m, void* base, int n_data, int k, int d, int dtype, MixingForm form) {
+    const MixingLayout L = mixing_layout(n_data, k, d, dtype, form);
+    m->n_data = n_data; m->k = k; m->n = n_data + k; m->d = d; m->dtype = dtype;
+    m->structured = form == kStructuredForm; m->blocked = form == kBlocked;
+    m->ldk = form == kBlocked ? GELO_BLOCK_ROWS : round_up(m->n, 64);
     m->block = base; m->block_bytes = L.total;
     char* p = (char*)base;
     m->A32 = (float*)p; p += L.mat32;
@@ -217,17 +225,18 @@ void small_targets_layout(const gelo_mixing* m, SmallSampleTargets* t) {
 
 // A free pooled object of this shape, or a new one (the only place a mixing object allocates; gelo_reserve
 // fills the pool ahead of time so that the per-batch calls find one).
-gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, bool structured, gelo_mixing** out) {
+gelo_status acquire_mixing(gelo_ctx* ctx, int n_data, int k, int d, int dtype, MixingForm form, gelo_mixing** out) {
     for (gelo_mixing* m : ctx->pool) {
-        if (!m->in_use && m->n_data == n_data && m->k == k && m->d == d && m->dtype == dtype && m->structured == structured) { *out = m; return GELO_OK; }
+        if (!m->in_use && m->n_data == n_data && m->k == k && m->d == d && m->dtype == dtype &&
+            m->structured == (form == kStructuredForm) && m->blocked == (form == kBlocked)) { *out = m; return GELO_OK; }
     }
     gelo_mixing* m = new (std::nothrow) gelo_mixing();
     if (!m) return fail(ctx, GELO_ENOMEM, "host allocation failed");
-    const MixingLayout L = mixing_layout(n_data, k, d, dtype, structured);
+    const MixingLayout L = mixing_layout(n_data, k, d, dtype, form);
     void* block = nullptr;
     hipError_t e = hipMalloc(&block, L.total);
     if (e != hipSuccess) { delete m; return fail(ctx, GELO_ENOMEM, "hipMalloc(%zu) failed: %s", L.total, hipGetErrorString(e)); }
-    carve_mixing(m, block, n_data, k, d, dtype, structured);
+    carve_mixing(m, block, n_data, k, d, dtype, form);
     if (hipEventCreateWithFlags(&m->ready, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&m->released, hipEventDisableTiming) != hipSuccess) {
         hipFree(m->block); delete m;
@@ -362,10 +371,31 @@ gelo_status gelo_destroy(gelo_ctx* ctx) {
 
 const char* gelo_last_error(const gelo_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
+// BLOCK_ORTHOGONAL: block i owns mixed rows [row0, row0 + rows), rows = min(GELO_BLOCK_ROWS, n - row0), mixes data rows
+// [data0, data0 + data_rows) with shield rows [shield0, shield0 + shield_rows); of the rows up to a cut r,
+// floor(k r / n) are shield rows.
+struct BlockPiece { int row0, rows, data0, data_rows, shield0, shield_rows; };
+static int block_count(int n) { return (n + GELO_BLOCK_ROWS - 1) / GELO_BLOCK_ROWS; }
+static BlockPiece block_piece(int n_data, int k, int i) {
+    const int n = n_data + k;
+    const int r0 = i * GELO_BLOCK_ROWS, r1 = r0 + GELO_BLOCK_ROWS < n ? r0 + GELO_BLOCK_ROWS : n;
+    const int s0 = (int)((int64_t)k * r0 / n), s1 = (int)((int64_t)k * r1 / n);
+    BlockPiece b;
+    b.row0 = r0; b.rows = r1 - r0; b.shield0 = s0; b.shield_rows = s1 - s0;
+    b.data0 = r0 - s0; b.data_rows = b.rows - b.shield_rows;
+    return b;
+}
+// factorisation workspaces of all blocks, one behind the other: the full blocks first (they share their launches)
+static size_t block_workspace_bytes(int n) {
+    const int full = n / GELO_BLOCK_ROWS, rest = n % GELO_BLOCK_ROWS;
+    return (size_t)full * up256(factor_workspace_bytes(GELO_BLOCK_ROWS)) + (rest ? up256(factor_workspace_bytes(rest)) : 0);
+}
+
 // Argument checks shared by the sampling entry points; on success *n_out = n_data + k_shield.
 static gelo_status check_sample_args(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d, gelo_dtype dtype,
                                      double cond_max, int max_attempts, uint64_t batch_id, int* n_out) {
-    if (kind != GELO_ORTHOGONAL && kind != GELO_GAUSSIAN && kind != GELO_CONDITIONED && kind != GELO_STRUCTURED)
+    if (kind != GELO_ORTHOGONAL && kind != GELO_GAUSSIAN && kind != GELO_CONDITIONED && kind != GELO_STRUCTURED &&
+        kind != GELO_BLOCK_ORTHOGONAL)
         return fail(ctx, GELO_EINVAL, "unknown kind %d", (int)kind);
     if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
     if (n_data < 1 || k_shield < 0 || d < 1) return fail(ctx, GELO_EINVAL, "n_data=%d k_shield=%d d=%d", n_data, k_shield, d);
@@ -420,6 +450,39 @@ static gelo_status sample_into(gelo_ctx* ctx, gelo_mixing* m, FactorWorkspace ws
     }
     if (structured) {
         GELO_HIP(ctx, structured_tables(m->table, n, kStructuredRounds, ps, s));
+    } else if (kind == GELO_BLOCK_ORTHOGONAL) {
+        // ws.M is the start of the blocks' workspaces here (block_workspace_bytes): the full blocks, whose
+        // factorisations share their launches, then the last, shorter one
+        constexpr int B = GELO_BLOCK_ROWS;
+        char* base = (char*)ws.M;
+        const int full = n / B, rest = n % B;
+        const size_t wb = up256(factor_workspace_bytes(B));
+        auto emit_block = [&](const FactorWorkspace& w, int i, int rows) {
+            const int64_t at = (int64_t)i * B * ldk;
+            return emit_matrix(w.X, w.n_pad / 16, 1, w.rdiag, rows, ldk, m->A32 + at, m->A16 ? m->A16 + at : nullptr,
+                               m->Ainv32 + at, m->Ainv16 ? m->Ainv16 + at : nullptr, s);
+        };
+        FactorWorkspace w;
+        for (int i = 0; i < full; ++i) {
+            factor_workspace_carve(base + wb * i, B, &w);
+            ps.c1 = (kStreamBlock << 8) | (uint32_t)i;
+            GELO_HIP(ctx, fill_normal(w.M, w.n_pad / 16, B, B, ps, 1.0f, 1, s));
+        }
+        if (full > 0) {
+            factor_workspace_carve(base, B, &w);
+            GELO_HIP(ctx, householder_qr(w, B, full, (int64_t)(wb / sizeof(float)), s));
+        }
+        for (int i = 0; i < full; ++i) {
+            factor_workspace_carve(base + wb * i, B, &w);
+            GELO_HIP(ctx, emit_block(w, i, B));
+        }
+        if (rest > 0) {
+            factor_workspace_carve(base + wb * full, rest, &w);
+            ps.c1 = (kStreamBlock << 8) | (uint32_t)full;
+            GELO_HIP(ctx, fill_normal(w.M, w.n_pad / 16, rest, rest, ps, 1.0f, 1, s));
+            GELO_HIP(ctx, householder_qr(w, rest, 1, 0, s));
+            GELO_HIP(ctx, emit_block(w, full, rest));
+        }
     } else if (kind == GELO_ORTHOGONAL) {
         GELO_HIP(ctx, orthogonal_into_X());
         // A = Q diag(sign r_ii); A^-1 = A^T
@@ -552,6 +615,7 @@ static gelo_status prepare_sampling(gelo_ctx* ctx, gelo_kind kind, int n, gelo_d
     const int lanes = (kind == GELO_GAUSSIAN && n <= kLanesMaxN) ? (max_attempts < kLanes ? max_attempts : kLanes) : 1;
     *lanes_out = lanes;
     if (kind == GELO_STRUCTURED) return GELO_OK;
+    if (kind == GELO_BLOCK_ORTHOGONAL) return grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, block_workspace_bytes(n));
     gelo_status st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, up256(factor_workspace_bytes(n)) * lanes);
     if (st != GELO_OK || lanes == 1) return st;
     const int64_t ldk = round_up(n, 64);
@@ -577,9 +641,10 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
     if (st != GELO_OK) return st;
     FactorWorkspace ws = {};
     const size_t ws_bytes = up256(factor_workspace_bytes(n));
-    if (kind != GELO_STRUCTURED) factor_workspace_carve(ctx->factor_ws, n, &ws);
+    if (kind == GELO_BLOCK_ORTHOGONAL) ws.M = (float*)ctx->factor_ws;      // sample_into carves the blocks' workspaces from here
+    else if (kind != GELO_STRUCTURED) factor_workspace_carve(ctx->factor_ws, n, &ws);
     gelo_mixing* m = nullptr;
-    st = acquire_mixing(ctx, n_data, k_shield, d, dtype, kind == GELO_STRUCTURED, &m);
+    st = acquire_mixing(ctx, n_data, k_shield, d, dtype, form_of(kind), &m);
     if (st != GELO_OK) return st;
     if (m->last_stream != nullptr || m->mixed) GELO_HIP(ctx, hipStreamWaitEvent(s, m->released, 0));
     st = sample_into(ctx, m, ws, ws_bytes, lanes, kind, cond_max, max_attempts, batch_id, s);
@@ -596,7 +661,7 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
 static gelo_status mix_launch(gelo_ctx* ctx, gelo_mixing* m, const void* H, int64_t ldh, float shield_scale,
                               gelo_norm_stat stat, void* U, int64_t ldu, hipStream_t s) {
     const bool bf = m->dtype == GELO_BF16;
-    if (bf && !m->structured && m->n <= kSmallMaxN) {
+    if (bf && !m->structured && !m->blocked && m->n <= kSmallMaxN) {
         // decode-shaped: row norms, then statistic + shield rows + product in one launch
         if (m->k > 0) GELO_HIP(ctx, row_norms(H, 1, ldh, m->n_data, m->d, m->rownorm, s));
         GELO_HIP(ctx, small_mix(m->A16, m->ldk, (const uint16_t*)H, ldh, m->GS, m->gsnorm, m->rownorm, (int)stat, shield_scale,
@@ -615,6 +680,22 @@ static gelo_status mix_launch(gelo_ctx* ctx, gelo_mixing* m, const void* H, int6
         o.out = U; o.ldo = ldu; o.rows_out = m->n;
         o.table = m->table; o.n = m->n; o.ncols = m->d; o.rounds = kStructuredRounds; o.transposed = false;
         GELO_HIP(ctx, structured_apply(o, bf, s));
+        return GELO_OK;
+    }
+    if (m->blocked) {
+        // block i: rows [row0, row0 + rows) of U = A_i [its data rows of H; its shield rows]
+        const size_t es = elem_size(m->dtype);
+        for (int i = 0; i < block_count(m->n); ++i) {
+            const BlockPiece b = block_piece(m->n_data, m->k, i);
+            GemmOperands g;
+            g.A = bf ? (const void*)(m->A16 + (int64_t)b.row0 * m->ldk) : (const void*)(m->A32 + (int64_t)b.row0 * m->ldk); g.lda = m->ldk;
+            g.B0 = (const char*)H + (int64_t)b.data0 * ldh * es; g.ldb0 = ldh; g.K0 = b.data_rows;
+            g.B1 = b.shield_rows > 0 ? (const void*)((const char*)m->S + (int64_t)b.shield0 * m->d * es) : g.B0; g.ldb1 = b.shield_rows > 0 ? m->d : ldh;
+            g.C = (char*)U + (int64_t)b.row0 * ldu * es; g.ldc = ldu;
+            g.M = b.rows; g.N = m->d; g.K = b.rows; g.a_zero_padded = true;
+            const gelo_status st = run_gemm(ctx, m->dtype, g, s);
+            if (st != GELO_OK) return st;
+        }
         return GELO_OK;
     }
     GemmOperands g;
@@ -637,6 +718,23 @@ static gelo_status unmix_launch(gelo_ctx* ctx, gelo_mixing* m, int p, const void
         o.out = Z; o.ldo = ldz; o.rows_out = m->n_data;      // the shield rows of A^T Y are never stored
         o.table = m->table; o.n = m->n; o.ncols = p; o.rounds = kStructuredRounds; o.transposed = true;
         GELO_HIP(ctx, structured_apply(o, bf, s));
+        return GELO_OK;
+    }
+    if (m->blocked) {
+        // block i: its data rows of Z = (the first data_rows rows of A_i^T) x rows [row0, row0 + rows) of Y
+        const size_t es = elem_size(m->dtype);
+        for (int i = 0; i < block_count(m->n); ++i) {
+            const BlockPiece b = block_piece(m->n_data, m->k, i);
+            if (b.data_rows == 0) continue;
+            GemmOperands g;
+            g.A = bf ? (const void*)(m->Ainv16 + (int64_t)b.row0 * m->ldk) : (const void*)(m->Ainv32 + (int64_t)b.row0 * m->ldk); g.lda = m->ldk;
+            g.B0 = (const char*)Y + (int64_t)b.row0 * ldy * es; g.ldb0 = ldy; g.K0 = b.rows;
+            g.B1 = g.B0; g.ldb1 = ldy;
+            g.C = (char*)Z + (int64_t)b.data0 * ldz * es; g.ldc = ldz;
+            g.M = b.data_rows; g.N = p; g.K = b.rows; g.a_zero_padded = true;
+            const gelo_status st = run_gemm(ctx, m->dtype, g, s);
+            if (st != GELO_OK) return st;
+        }
         return GELO_OK;
     }
     GemmOperands g;
@@ -768,7 +866,7 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
     int have = 0;
     for (int i = 0; i < count && st == GELO_OK; ++i) {
         gelo_mixing* m = nullptr;
-        st = acquire_mixing(ctx, n_data, k_shield, d, dtype, false, &m);
+        st = acquire_mixing(ctx, n_data, k_shield, d, dtype, kDense, &m);
         if (st != GELO_OK) break;
         if (m->last_stream != nullptr || m->mixed) {
             hipError_t e = hipStreamWaitEvent(s, m->released, 0);
@@ -905,6 +1003,26 @@ gelo_status gelo_mixing_export(gelo_ctx* ctx, const gelo_mixing* m, float* A, fl
             GELO_HIP(ctx, structured_apply(o, 0, s));
             GELO_HIP(ctx, export_dense(res, 0, ldn, m->n, m->n, dst, s));
         }
+    } else if (m->blocked) {
+        // the dense n x n matrix that acts on the stacked [H; S]: block i's columns are its data rows' and,
+        // behind column n_data, its shield rows'; A^-1 is the transpose
+        const size_t row = (size_t)m->n * sizeof(float);
+        if (A) GELO_HIP(ctx, hipMemsetAsync(A, 0, row * m->n, s));
+        if (A_inv) GELO_HIP(ctx, hipMemsetAsync(A_inv, 0, row * m->n, s));
+        for (int i = 0; i < block_count(m->n); ++i) {
+            const BlockPiece b = block_piece(m->n_data, m->k, i);
+            const float* Ai = m->A32 + (int64_t)b.row0 * m->ldk;
+            const float* Ti = m->Ainv32 + (int64_t)b.row0 * m->ldk;
+            const size_t pitch = (size_t)m->ldk * sizeof(float);
+            if (A && b.data_rows > 0)
+                GELO_HIP(ctx, hipMemcpy2DAsync(A + (int64_t)b.row0 * m->n + b.data0, row, Ai, pitch, b.data_rows * sizeof(float), b.rows, hipMemcpyDeviceToDevice, s));
+            if (A && b.shield_rows > 0)
+                GELO_HIP(ctx, hipMemcpy2DAsync(A + (int64_t)b.row0 * m->n + m->n_data + b.shield0, row, Ai + b.data_rows, pitch, b.shield_rows * sizeof(float), b.rows, hipMemcpyDeviceToDevice, s));
+            if (A_inv && b.data_rows > 0)
+                GELO_HIP(ctx, hipMemcpy2DAsync(A_inv + (int64_t)b.data0 * m->n + b.row0, row, Ti, pitch, b.rows * sizeof(float), b.data_rows, hipMemcpyDeviceToDevice, s));
+            if (A_inv && b.shield_rows > 0)
+                GELO_HIP(ctx, hipMemcpy2DAsync(A_inv + (int64_t)(m->n_data + b.shield0) * m->n + b.row0, row, Ti + (int64_t)b.data_rows * m->ldk, pitch, b.rows * sizeof(float), b.shield_rows, hipMemcpyDeviceToDevice, s));
+        }
     } else {
         if (A) GELO_HIP(ctx, export_dense(m->A32, 0, m->ldk, m->n, m->n, A, s));
         if (A_inv) GELO_HIP(ctx, export_dense(m->Ainv32, 0, m->ldk, m->n, m->n, A_inv, s));
@@ -939,8 +1057,8 @@ gelo_status gelo_qkv_forward_static(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dt
     if (st != GELO_OK) return st;
     const bool structured = kind == GELO_STRUCTURED;
     if (n > GELO_STATIC_MAX_N) return fail(ctx, GELO_ESHAPE, "n = %d exceeds GELO_STATIC_MAX_N = %d", n, GELO_STATIC_MAX_N);
-    const MixingLayout L = mixing_layout(n_data, k_shield, d, dtype, structured);
-    const size_t ws_bytes = structured ? 0 : up256(factor_workspace_bytes(n));
+    const MixingLayout L = mixing_layout(n_data, k_shield, d, dtype, form_of(kind));
+    const size_t ws_bytes = structured ? 0 : kind == GELO_BLOCK_ORTHOGONAL ? block_workspace_bytes(n) : up256(factor_workspace_bytes(n));
     if (L.total + ws_bytes > kStaticScratchBytes)
         return fail(ctx, GELO_ESHAPE, "this batch needs %zu bytes of scratch, the static buffer holds %zu (n <= %d, and k_shield * d bounded by it)",
                     L.total + ws_bytes, kStaticScratchBytes, GELO_STATIC_MAX_N);
@@ -949,9 +1067,10 @@ gelo_status gelo_qkv_forward_static(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dt
     // the mixing object of this call lives on the host stack and points into the static device array
     gelo_mixing local = {};
     char* base = (char*)ctx->static_scratch;
-    carve_mixing(&local, base, n_data, k_shield, d, dtype, structured);
+    carve_mixing(&local, base, n_data, k_shield, d, dtype, form_of(kind));
     FactorWorkspace ws = {};
-    if (!structured) factor_workspace_carve(base + up256(L.total), n, &ws);
+    if (kind == GELO_BLOCK_ORTHOGONAL) ws.M = (float*)(base + up256(L.total));      // sample_into carves the blocks' workspaces from here
+    else if (!structured) factor_workspace_carve(base + up256(L.total), n, &ws);
     st = sample_into(ctx, &local, ws, ws_bytes, 1, kind, 1.0, 1, batch_id, s);
     if (st == GELO_OK) batch_commit(ctx, batch_id);
     if (st == GELO_OK) st = mix_launch(ctx, &local, H, d, shield_scale, stat, U, d, s);
@@ -996,7 +1115,7 @@ gelo_status gelo_reserve(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_
     std::vector<gelo_mixing*> got;
     for (int i = 0; i < mixings && st == GELO_OK; ++i) {
         gelo_mixing* m = nullptr;
-        st = acquire_mixing(ctx, n_data, k_shield, d, dtype, kind == GELO_STRUCTURED, &m);
+        st = acquire_mixing(ctx, n_data, k_shield, d, dtype, form_of(kind), &m);
         if (st == GELO_OK) { m->in_use = true; got.push_back(m); }
     }
     for (gelo_mixing* m : got) m->in_use = false;

@@ -20,6 +20,7 @@ KIND_ORTHOGONAL = 0
 KIND_GAUSSIAN = 1
 KIND_CONDITIONED = 2
 KIND_STRUCTURED = 3
+KIND_BLOCK_ORTHOGONAL = 4
 
 
 @dataclass(frozen=True)
@@ -76,6 +77,11 @@ WORKLOADS = {
     # ... the 4096 + 205 row layer of the sweep and the decode-shaped batch, same kind
     "sweep_bf16_structured": Workload("sweep_bf16_structured", "bf16", 4096, 205, 4096, 12288,
                                       KIND_STRUCTURED, 8, 0xC7),
+    # ... and with the block-diagonal orthogonal A (dense orthogonal mixing inside blocks of 256 mixed rows)
+    "llama7b_bf16_prefill_blocks": Workload("llama7b_bf16_prefill_blocks", "bf16", 2048, 102, 4096, 12288,
+                                            KIND_BLOCK_ORTHOGONAL, 8, 0xCB),
+    "sweep_bf16_blocks": Workload("sweep_bf16_blocks", "bf16", 4096, 205, 4096, 12288,
+                                  KIND_BLOCK_ORTHOGONAL, 8, 0xCC),
     "decode_bf16_structured": Workload("decode_bf16_structured", "bf16", 64, 4, 4096, 12288,
                                        KIND_STRUCTURED, 8, 0xC8),
 }

@@ -1,0 +1,144 @@
+"""GPU parity of the block-diagonal orthogonal kind (GELO_BLOCK_ORTHOGONAL): the dense matrix the library
+exports must be the oracle's (every block THE orthogonal factor of its own Gaussian, in its own rows and
+columns, zeros elsewhere), mix and unmix stage by stage on the library's own secrets, and eq. 4 end to end at
+the contract's bounds (1e-4 f32 / 2e-2 bf16)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import gelo_oracle as o
+from paper_2603_05035_amd import binding as g
+from paper_2603_05035_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0xB10C
+TOL_END = {"f32": 1e-4, "bf16": 2e-2}
+TOL_STAGE = {"f32": 1e-5, "bf16": 4e-3}
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+CODE = {"f32": g.GELO_F32, "bf16": g.GELO_BF16}
+
+
+def dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(TORCH_DTYPE[dtype]).cuda()
+
+
+def f64(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+@pytest.fixture()
+def ctx():
+    c = g.gelo_create(0, SEED, allow_batch_reuse=False)
+    yield c
+    g.gelo_destroy(c)
+
+
+@pytest.mark.parametrize("n_data,k", [(1, 0), (12, 2), (100, 5), (256, 0), (257, 0), (300, 15), (500, 12), (1000, 50)])
+def test_exported_matrix_is_the_oracles(ctx, n_data, k):
+    """One block, exact blocks, a last block of a single row, ragged blocks with shields shared out: every
+    block against the oracle's QR of the same Gaussian (element-wise, at the sensitivity of a float QR), the zero
+    pattern exactly, A^-1 = A^T exactly."""
+    n = n_data + k
+    bid = 10 + n
+    m = g.gelo_sample_mixing(ctx, g.GELO_BLOCK_ORTHOGONAL, n_data, k, 64, g.GELO_F32, 0.0, 1, batch_id=bid)
+    A, A_inv, _, attempt, kappa = g.gelo_mixing_export(ctx, m, n, k, 64, want_shields=False)
+    assert g.gelo_mixing_info(ctx, m)[:3] == (n_data, k, 64)
+    g.gelo_mixing_free(ctx, m)
+    A, A_inv = f64(A), f64(A_inv)
+    assert attempt == 0 and kappa == 1.0
+    assert np.array_equal(A_inv, A.T)
+    assert np.linalg.norm(A.T @ A - np.eye(n)) / math.sqrt(n) < 1e-5
+    A_ref, _ = o.sample_block_orthogonal(SEED, bid, n_data, k)
+    assert np.all(A[A_ref == 0.0] == 0.0)                    # nothing outside the blocks
+    eps = 2.0 ** -24
+    for i, (r0, rows, d0, dn, s0, sn) in enumerate(o.block_layout(n_data, k)):
+        cols = list(range(d0, d0 + dn)) + list(range(n_data + s0, n_data + s0 + sn))
+        blk, ref = A[np.ix_(range(r0, r0 + rows), cols)], A_ref[np.ix_(range(r0, r0 + rows), cols)]
+        kappa_G = np.linalg.cond(o.gaussian_matrix(SEED, bid, o.STREAM_BLOCK, i, rows, rows))
+        assert o.rel_frobenius(blk, ref) < 10 * kappa_G * eps + 1e-6, f"block {i}"
+
+
+CASES = [("f32", 12, 2, 64, 72), ("bf16", 12, 2, 64, 72), ("f32", 300, 15, 256, 520), ("bf16", 300, 15, 264, 520),
+         ("f32", 257, 0, 72, 40), ("bf16", 1000, 50, 512, 776), ("f32", 700, 35, 128, 264)]
+
+
+@pytest.mark.parametrize("dtype,nd,k,d,p", CASES)
+def test_chain_stagewise_and_end_to_end(ctx, dtype, nd, k, d, p):
+    H32 = wl.make_hidden(nd, d, 5, min(8, d // 8))
+    W32 = wl.make_weight(d, p, 5)
+    H, W = dev(H32, dtype), dev(W32, dtype)
+    n = nd + k
+    m = g.gelo_sample_mixing(ctx, g.GELO_BLOCK_ORTHOGONAL, nd, k, d, CODE[dtype], 0.0, 1, batch_id=77)
+    U = torch.empty((n, d), dtype=H.dtype, device="cuda")
+    Y = torch.empty((n, p), dtype=H.dtype, device="cuda")
+    Z = torch.full((nd, p), float("nan"), dtype=H.dtype, device="cuda")
+    g.gelo_mix(ctx, m, H, U, 10.0)
+    g.gelo_project(ctx, U, W, Y)
+    A, A_inv, S, _, _ = g.gelo_mixing_export(ctx, m, n, k, d)
+    g.gelo_unmix(ctx, m, Y, Z)
+    torch.cuda.synchronize()
+    g.gelo_mixing_free(ctx, m)
+    Hd, Wd = f64(H), f64(W)
+    A64, Ai64 = f64(A), f64(A_inv)
+    if dtype == "bf16":                                   # the kernels consume A rounded once to bf16
+        A64, Ai64 = f64(A.to(torch.bfloat16)), f64(A_inv.to(torch.bfloat16))
+    S64 = f64(S) if k > 0 else None
+    tol = TOL_STAGE[dtype]
+    assert o.rel_frobenius(f64(U), o.mix(A64, Hd, S64)) < tol
+    assert o.rel_frobenius(f64(Y), o.project(f64(U), Wd)) < tol
+    assert o.rel_frobenius(f64(Z), o.unmix(Ai64, f64(Y), nd)) < tol
+    assert o.rel_frobenius(f64(Z), o.plain_projection(Hd, Wd)) < TOL_END[dtype]          # eq. 4
+    if k > 0:                                             # shield rows: exact norm 10 x median row norm
+        norms = np.linalg.norm(S64, axis=1)
+        med = np.median(np.linalg.norm(Hd, axis=1))
+        assert np.abs(norms / (10.0 * med) - 1.0).max() < (1e-5 if dtype == "f32" else 4e-3)
+
+
+@pytest.mark.parametrize("name", ["llama7b_bf16_prefill_blocks", "sweep_bf16_blocks"])
+def test_full_size_workloads(ctx, name):
+    """The bench workloads at full size, in one call: eq. 4 on sampled rows (the oracle computes them one by one)
+    and Freivalds on everything."""
+    w = wl.WORKLOADS[name]
+    H32, W32 = wl.make_inputs(w)
+    H, W = dev(H32, w.dtype), dev(W32, w.dtype)
+    Z = torch.full((w.n_data, w.p), float("nan"), dtype=H.dtype, device="cuda")
+    g.gelo_qkv_forward(ctx, w.kind, H, W, Z, k_shield=w.k_shield, shield_scale=w.shield_scale, batch_id=3)
+    torch.cuda.synchronize()
+    Hd, Wd, Zd = f64(H), f64(W), f64(Z)
+    rows = np.random.default_rng(9).choice(w.n_data, size=48, replace=False)
+    ref = Hd[rows] @ Wd
+    assert np.linalg.norm(Zd[rows] - ref) / np.linalg.norm(ref) < TOL_END[w.dtype]
+    r = np.random.default_rng(10).standard_normal(w.p)
+    lhs, rhs = Zd @ r, Hd @ (Wd @ r)
+    assert np.linalg.norm(lhs - rhs) / np.linalg.norm(rhs) < TOL_END[w.dtype]
+    assert np.isfinite(Zd).all()
+
+
+def test_static_entry_point_and_fresh_blocks(ctx):
+    nd, k, d, p = 100, 6, 128, 136
+    H = dev(wl.make_hidden(nd, d, 3, 4), "bf16")
+    W = dev(wl.make_weight(d, p, 3), "bf16")
+    Z0 = torch.empty((nd, p), dtype=H.dtype, device="cuda")
+    Z1 = torch.empty_like(Z0)
+    U = torch.empty((nd + k, d), dtype=H.dtype, device="cuda")
+    Y = torch.empty((nd + k, p), dtype=H.dtype, device="cuda")
+    other = g.gelo_create(0, SEED, allow_batch_reuse=False)
+    try:
+        g.gelo_qkv_forward(ctx, g.GELO_BLOCK_ORTHOGONAL, H, W, Z0, k_shield=k, batch_id=5)
+        g.gelo_qkv_forward_static(other, g.GELO_BLOCK_ORTHOGONAL, H, W, Z1, U, Y, k_shield=k, batch_id=5)
+        torch.cuda.synchronize()
+        assert torch.equal(Z0, Z1)
+    finally:
+        g.gelo_destroy(other)
+    mats = []
+    for bid in (8, 9):
+        m = g.gelo_sample_mixing(ctx, g.GELO_BLOCK_ORTHOGONAL, 300, 15, 64, g.GELO_F32, 0.0, 1, batch_id=bid)
+        mats.append(g.gelo_mixing_export(ctx, m, 315, 15, 64, want_shields=False)[0])
+        g.gelo_mixing_free(ctx, m)
+    assert (mats[0] - mats[1]).abs().max() > 0.05
+    with pytest.raises(g.GeloError) as e:
+        g.gelo_sample_mixing_batch(ctx, g.GELO_BLOCK_ORTHOGONAL, 300, 15, 64, g.GELO_BF16, 20, 2)
+    assert g.STATUS_NAMES[e.value.status] == "GELO_EINVAL"
