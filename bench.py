@@ -26,7 +26,16 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}          # MI355X dense matrix peaks
-KIND_NAME = {0: "orthogonal", 1: "gaussian", 2: "conditioned", 3: "structured"}
+KIND_NAME = {0: "orthogonal", 1: "gaussian", 2: "conditioned", 3: "structured", 4: "block_orthogonal"}
+BLOCK_ROWS = 256
+
+
+def block_rows(n_data, k):
+    """(mixed rows, data rows) of every block of the block-diagonal orthogonal kind (the library's layout restated:
+    blocks of BLOCK_ROWS mixed rows; of the rows up to a cut r, floor(k r / n) are shield rows)"""
+    n = n_data + k
+    cuts = list(range(0, n, BLOCK_ROWS)) + [n]
+    return [(r1 - r0, (r1 - k * r1 // n) - (r0 - k * r0 // n)) for r0, r1 in zip(cuts[:-1], cuts[1:])]
 
 
 STRUCTURED_ROUNDS = 3
@@ -41,6 +50,8 @@ def chain_flops(w):
     n, nd, d, p = w.n, w.n_data, w.d, w.p
     if w.kind == 3:      # structured A: mix and unmix are butterflies, only the projection is a product
         return 2.0 * n * d * p + STRUCTURED_ROUNDS * butterfly_adds(n) * (d + p)
+    if w.kind == 4:      # block-diagonal A: mix and unmix block by block
+        return 2.0 * n * d * p + sum(2.0 * r * r * d + 2.0 * dr * r * p for r, dr in block_rows(nd, w.k_shield))
     return 2.0 * n * n * d + 2.0 * n * d * p + 2.0 * nd * n * p
 
 
@@ -48,6 +59,8 @@ def gen_flops(w, attempts=1):
     n = float(w.n)
     qr = 8.0 / 3.0 * n ** 3            # Householder QR with explicit Q
     lu = 2.0 * n ** 3                  # LU + explicit inverse
+    if w.kind == 4:
+        return sum(8.0 / 3.0 * float(r) ** 3 for r, _ in block_rows(w.n_data, w.k_shield))
     return {0: qr, 1: lu * attempts, 2: qr + lu, 3: 0.0}[w.kind]   # structured: sorting keys, no arithmetic to count
 
 
@@ -700,7 +713,10 @@ def main() -> int:
         f_chain_s = 2.0 * ns * ns * d + 2.0 * ns * d * p + 2.0 * rows * ns * p
         if w.kind == 3:
             f_chain_s = 2.0 * ns * d * p + STRUCTURED_ROUNDS * butterfly_adds(ns) * (d + p)
-        f_gen_s = {0: 8.0 / 3.0, 1: 2.0 * (ref["info"]["attempt"] + 1), 2: 8.0 / 3.0 + 2.0, 3: 0.0}[w.kind] * float(ns) ** 3
+        f_gen_s = {0: 8.0 / 3.0, 1: 2.0 * (ref["info"]["attempt"] + 1), 2: 8.0 / 3.0 + 2.0, 3: 0.0, 4: 0.0}[w.kind] * float(ns) ** 3
+        if w.kind == 4:
+            f_chain_s = 2.0 * ns * d * p + sum(2.0 * r * r * d + 2.0 * dr * r * p for r, dr in block_rows(rows, ks))
+            f_gen_s = sum(8.0 / 3.0 * float(r) ** 3 for r, _ in block_rows(rows, ks))
         result["cpu_baseline"] = {
             "value": (f_chain_s + f_gen_s) / t_cpu / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
             "seconds": t_cpu,

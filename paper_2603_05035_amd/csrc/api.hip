@@ -278,6 +278,21 @@ gelo_status run_gemm(gelo_ctx* ctx, int dtype, const GemmOperands& g, hipStream_
     return GELO_OK;
 }
 
+// The products of a block-diagonal mix or unmix: bf16 in one launch, float one product at a time.
+gelo_status run_gemm_blocks(gelo_ctx* ctx, int dtype, const GemmOperands* ops, int count, hipStream_t s) {
+    if (count == 0) return GELO_OK;
+    if (dtype == GELO_BF16) {
+        const hipError_t e = gemm_bf16_batched(ops, count, s);
+        if (e != hipSuccess) return hip_fail(ctx, e, "batched GEMM launch");
+        return GELO_OK;
+    }
+    for (int i = 0; i < count; ++i) {
+        const gelo_status st = run_gemm(ctx, dtype, ops[i], s);
+        if (st != GELO_OK) return st;
+    }
+    return GELO_OK;
+}
+
 gelo_status check_matrix(gelo_ctx* ctx, const char* name, const void* p, int64_t ld, int cols) {
     if (!p) return fail(ctx, GELO_EINVAL, "%s is NULL", name);
     if (!aligned16(p)) return fail(ctx, GELO_EALIGN, "%s is not 16-byte aligned", name);
@@ -376,6 +391,7 @@ const char* gelo_last_error(const gelo_ctx* ctx) { return ctx ? ctx->err.c_str()
 // floor(k r / n) are shield rows.
 struct BlockPiece { int row0, rows, data0, data_rows, shield0, shield_rows; };
 static int block_count(int n) { return (n + GELO_BLOCK_ROWS - 1) / GELO_BLOCK_ROWS; }
+static_assert((GELO_MAX_N + GELO_BLOCK_ROWS - 1) / GELO_BLOCK_ROWS <= kGemmBatchMax, "one batched launch takes all blocks");
 static BlockPiece block_piece(int n_data, int k, int i) {
     const int n = n_data + k;
     const int r0 = i * GELO_BLOCK_ROWS, r1 = r0 + GELO_BLOCK_ROWS < n ? r0 + GELO_BLOCK_ROWS : n;
@@ -685,18 +701,18 @@ static gelo_status mix_launch(gelo_ctx* ctx, gelo_mixing* m, const void* H, int6
     if (m->blocked) {
         // block i: rows [row0, row0 + rows) of U = A_i [its data rows of H; its shield rows]
         const size_t es = elem_size(m->dtype);
-        for (int i = 0; i < block_count(m->n); ++i) {
+        GemmOperands ops[kGemmBatchMax];
+        const int nb = block_count(m->n);
+        for (int i = 0; i < nb; ++i) {
             const BlockPiece b = block_piece(m->n_data, m->k, i);
-            GemmOperands g;
+            GemmOperands& g = ops[i];
             g.A = bf ? (const void*)(m->A16 + (int64_t)b.row0 * m->ldk) : (const void*)(m->A32 + (int64_t)b.row0 * m->ldk); g.lda = m->ldk;
             g.B0 = (const char*)H + (int64_t)b.data0 * ldh * es; g.ldb0 = ldh; g.K0 = b.data_rows;
             g.B1 = b.shield_rows > 0 ? (const void*)((const char*)m->S + (int64_t)b.shield0 * m->d * es) : g.B0; g.ldb1 = b.shield_rows > 0 ? m->d : ldh;
             g.C = (char*)U + (int64_t)b.row0 * ldu * es; g.ldc = ldu;
             g.M = b.rows; g.N = m->d; g.K = b.rows; g.a_zero_padded = true;
-            const gelo_status st = run_gemm(ctx, m->dtype, g, s);
-            if (st != GELO_OK) return st;
         }
-        return GELO_OK;
+        return run_gemm_blocks(ctx, m->dtype, ops, nb, s);
     }
     GemmOperands g;
     g.A = bf ? (const void*)m->A16 : (const void*)m->A32; g.lda = m->ldk;
@@ -723,19 +739,19 @@ static gelo_status unmix_launch(gelo_ctx* ctx, gelo_mixing* m, int p, const void
     if (m->blocked) {
         // block i: its data rows of Z = (the first data_rows rows of A_i^T) x rows [row0, row0 + rows) of Y
         const size_t es = elem_size(m->dtype);
+        GemmOperands ops[kGemmBatchMax];
+        int nb = 0;
         for (int i = 0; i < block_count(m->n); ++i) {
             const BlockPiece b = block_piece(m->n_data, m->k, i);
             if (b.data_rows == 0) continue;
-            GemmOperands g;
+            GemmOperands& g = ops[nb++];
             g.A = bf ? (const void*)(m->Ainv16 + (int64_t)b.row0 * m->ldk) : (const void*)(m->Ainv32 + (int64_t)b.row0 * m->ldk); g.lda = m->ldk;
             g.B0 = (const char*)Y + (int64_t)b.row0 * ldy * es; g.ldb0 = ldy; g.K0 = b.rows;
             g.B1 = g.B0; g.ldb1 = ldy;
             g.C = (char*)Z + (int64_t)b.data0 * ldz * es; g.ldc = ldz;
             g.M = b.data_rows; g.N = p; g.K = b.rows; g.a_zero_padded = true;
-            const gelo_status st = run_gemm(ctx, m->dtype, g, s);
-            if (st != GELO_OK) return st;
         }
-        return GELO_OK;
+        return run_gemm_blocks(ctx, m->dtype, ops, nb, s);
     }
     GemmOperands g;
     g.A = bf ? (const void*)m->Ainv16 : (const void*)m->Ainv32; g.lda = m->ldk;   // rows 0..n_data-1 of A^-1

@@ -46,6 +46,11 @@ size_t gemm_bf16_skinny_ws_bytes(int M, int N, int K);    // 0: such a launch is
 int gemm_bf16_skinny_slices(int M, int N, int K);
 int64_t gemm_bf16_skinny_ldp(int N);
 hipError_t gemm_bf16(const GemmOperands& g, hipStream_t stream);
+// `count` (1..kGemmBatchMax) independent bf16 products in ONE launch (grid y = product): the blocks of a block-diagonal
+// mix or unmix.  Every product needs what the fast path of gemm_bf16 needs (N >= 8 and a multiple of 8, A zero-padded
+// or K a multiple of 64) and M <= 256 (one tile row); all share N.  hipErrorInvalidValue otherwise.
+constexpr int kGemmBatchMax = 20;
+hipError_t gemm_bf16_batched(const GemmOperands* g, int count, hipStream_t stream);
 hipError_t gemm_f32(const GemmOperands& g, hipStream_t stream);
 hipError_t gemm_bf16_init();        // one-time kernel attribute set-up (large dynamic LDS)
 hipError_t gemm_f32_init();

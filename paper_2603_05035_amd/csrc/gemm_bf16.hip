@@ -497,6 +497,21 @@ void gemm_bf16_dma_mixed_kernel(Bf16Args g) {
     }
 }
 
+// Several independent products of at most one tile row each in one launch: grid y picks the product (its
+// arguments travel by value), grid x its tile.
+struct Bf16Batch { Bf16Args g[kGemmBatchMax]; };
+
+template <int BN>
+__global__ __launch_bounds__(512)
+void gemm_bf16_dma_batched_kernel(Bf16Batch b) {
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    const Bf16Args& g = b.g[blockIdx.y];
+    if ((int)blockIdx.x >= g.tiles_m * g.tiles_n) return;
+    int tm, tn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, &tm, &tn);
+    tile_body<BN>(g, lds, tm * BM, tn * BN);
+}
+
 }  // namespace dma
 
 // ---------------------------------------------------------------------------------------------
@@ -877,6 +892,12 @@ hipError_t gemm_bf16_init() {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dma::gemm_bf16_dma_mixed_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, dma::lds_bytes<256>());
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dma::gemm_bf16_dma_batched_kernel<256>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, dma::lds_bytes<256>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dma::gemm_bf16_dma_batched_kernel<192>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, dma::lds_bytes<192>());
+    if (e != hipSuccess) return e;
     e = allow_big_lds<256, 256, 64>();
     if (e != hipSuccess) return e;
     e = allow_skinny_lds<1, 2, false>();
@@ -976,6 +997,38 @@ hipError_t gemm_bf16(const GemmOperands& o, hipStream_t stream) {
         }
     }
     return launch<128, 128, 32>(o, stream);
+}
+
+// One launch for all the products of a block-diagonal mix or unmix.  The tile width is the one with the shorter
+// schedule on the chip's CUs over ALL products (a 192-wide tile costs 0.87 of a 256-wide one).
+hipError_t gemm_bf16_batched(const GemmOperands* ops, int count, hipStream_t stream) {
+    if (count < 1 || count > kGemmBatchMax) return hipErrorInvalidValue;
+    const int N = ops[0].N;
+    for (int i = 0; i < count; ++i) {
+        const GemmOperands& o = ops[i];
+        if (o.M < 1 || o.M > dma::BM || o.K < 1 || o.N != N || N < 8 || N % 8 != 0 || o.subtract) return hipErrorInvalidValue;
+        if (!(o.a_zero_padded || o.K % dma::BKS == 0)) return hipErrorInvalidValue;
+    }
+    constexpr int kCus = 256;
+    const int64_t t256 = (int64_t)count * ((N + 255) / 256), t192 = (int64_t)count * ((N + 191) / 192);
+    const bool narrow = 0.87 * (double)((t192 + kCus - 1) / kCus) < (double)((t256 + kCus - 1) / kCus);
+    const int BN = narrow ? 192 : 256;
+    dma::Bf16Batch b;
+    for (int i = 0; i < count; ++i) {
+        const GemmOperands& o = ops[i];
+        Bf16Args& a = b.g[i];
+        a.A = (const uint16_t*)o.A;   a.lda = o.lda;
+        a.B0 = (const uint16_t*)o.B0; a.ldb0 = o.ldb0; a.K0 = o.K0;
+        a.B1 = (const uint16_t*)o.B1; a.ldb1 = o.ldb1;
+        a.C = (uint16_t*)o.C;         a.ldc = o.ldc;
+        a.M = o.M; a.N = o.N; a.K = o.K;
+        a.tiles_m = 1; a.tiles_n = (N + BN - 1) / BN; a.narrow_cols = 0;
+    }
+    for (int i = count; i < kGemmBatchMax; ++i) b.g[i] = b.g[0];
+    const dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)count);
+    if (narrow) hipLaunchKernelGGL(dma::gemm_bf16_dma_batched_kernel<192>, grid, dim3(512), (size_t)dma::lds_bytes<192>(), stream, b);
+    else hipLaunchKernelGGL(dma::gemm_bf16_dma_batched_kernel<256>, grid, dim3(512), (size_t)dma::lds_bytes<256>(), stream, b);
+    return hipGetLastError();
 }
 
 }  // namespace gelo
