@@ -431,7 +431,7 @@ def main() -> int:
     # the current batch runs.  Every timed step still generates one fresh A and consumes one.
     main = torch.cuda.current_stream()
     bid = [0]
-    if w.kind == g.GELO_ORTHOGONAL:
+    if w.kind in (g.GELO_ORTHOGONAL, g.GELO_BLOCK_ORTHOGONAL):
         # batched draws: `group` matrices per call (their factorisations share every launch), `rings` groups alive:
         # one being consumed while the others are drawn on side streams.  A group is drawn at every step whose
         # number is the warm-up count modulo the group size (so the first timed step issues one: a short timed

@@ -154,7 +154,8 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
 
 /* Trusted side, Section 3.2 step 1.2, many batches at once: `count` mixing objects (1..GELO_MAX_BATCH_DRAW) for
  * batch ids first_batch_id .. first_batch_id + count - 1, all of one shape.  A does not depend on the data, so
- * a decode step's worth, or the next few prefill batches, can be drawn ahead together.  GELO_ORTHOGONAL only.
+ * a decode step's worth, or the next few prefill batches, can be drawn ahead together.  GELO_ORTHOGONAL, and
+ * GELO_BLOCK_ORTHOGONAL (all full blocks of all objects share the launches of one batched factorisation).
  *  n <= GELO_STATIC_MAX_N  ONE launch draws all of them (at this size a fresh A per layer-step costs more in
  *                          launch latency than in work);
  *  larger n                up to 32 factorisations (fewer where 32 workspaces would exceed 4 GiB) share every

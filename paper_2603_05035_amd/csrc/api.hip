@@ -862,7 +862,8 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
     if (!out) return fail(ctx, GELO_EINVAL, "out is NULL");
     if (count < 1 || count > GELO_MAX_BATCH_DRAW) return fail(ctx, GELO_EINVAL, "count=%d outside 1..%d", count, GELO_MAX_BATCH_DRAW);
     for (int i = 0; i < count; ++i) out[i] = nullptr;
-    if (kind != GELO_ORTHOGONAL) return fail(ctx, GELO_EINVAL, "batched draws exist for GELO_ORTHOGONAL only");
+    if (kind != GELO_ORTHOGONAL && kind != GELO_BLOCK_ORTHOGONAL)
+        return fail(ctx, GELO_EINVAL, "batched draws exist for GELO_ORTHOGONAL and GELO_BLOCK_ORTHOGONAL only");
     if (first_batch_id > UINT64_MAX - (uint64_t)count) return fail(ctx, GELO_EINVAL, "batch ids leave 64 bits");
     int n = 0;
     for (int i = 0; i < count; ++i) {
@@ -871,18 +872,19 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
     }
     GELO_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
-    const bool small = n <= kSmallMaxN;
+    const bool blocked = kind == GELO_BLOCK_ORTHOGONAL;
+    const bool small = !blocked && n <= kSmallMaxN;
     // larger matrices: up to kQrSideBySide factorisations share every launch, each in a workspace of its own
     const size_t ws_bytes = up256(factor_workspace_bytes(n));
     const int side = qr_side_by_side(count, ws_bytes);
-    gelo_status st = small ? GELO_OK : grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, ws_bytes * side);
+    gelo_status st = small ? GELO_OK : grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, blocked ? block_workspace_bytes(n) * count : ws_bytes * side);
     if (st != GELO_OK) return st;
     SmallSampleTargets t;
     gelo_mixing* got[GELO_MAX_BATCH_DRAW];
     int have = 0;
     for (int i = 0; i < count && st == GELO_OK; ++i) {
         gelo_mixing* m = nullptr;
-        st = acquire_mixing(ctx, n_data, k_shield, d, dtype, kDense, &m);
+        st = acquire_mixing(ctx, n_data, k_shield, d, dtype, form_of(kind), &m);
         if (st != GELO_OK) break;
         if (m->last_stream != nullptr || m->mixed) {
             hipError_t e = hipStreamWaitEvent(s, m->released, 0);
@@ -900,7 +902,57 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
         hipError_t e = small_sample(t, count, first_batch_id, ps, kStreamShield << 8, n, k_shield, d, got[0]->ldk, s);
         if (e != hipSuccess) st = hip_fail(ctx, e, "small_sample");
     }
-    for (int base = 0; st == GELO_OK && !small && base < count; base += side) {
+    if (st == GELO_OK && blocked) {
+        // all full blocks of all objects share the launches of ONE batched factorisation (workspaces: object-major,
+        // then block), the last, shorter blocks of all objects those of a second one
+        constexpr int B = GELO_BLOCK_ROWS;
+        const int full = n / B, rest = n % B;
+        const size_t wb = up256(factor_workspace_bytes(B)), wr = rest ? up256(factor_workspace_bytes(rest)) : 0;
+        char* base_full = (char*)ctx->factor_ws;
+        char* base_rest = base_full + wb * (size_t)full * count;
+        hipError_t e = hipSuccess;
+        FactorWorkspace w;
+        for (int o = 0; o < count && e == hipSuccess; ++o) {
+            const uint64_t id = first_batch_id + (uint64_t)o;
+            ps.c2 = (uint32_t)id; ps.c3 = (uint32_t)(id >> 32);
+            for (int i = 0; i < full && e == hipSuccess; ++i) {
+                factor_workspace_carve(base_full + wb * ((size_t)o * full + i), B, &w);
+                ps.c1 = (kStreamBlock << 8) | (uint32_t)i;
+                e = fill_normal(w.M, w.n_pad / 16, B, B, ps, 1.0f, 1, s);
+            }
+            if (rest > 0 && e == hipSuccess) {
+                factor_workspace_carve(base_rest + wr * o, rest, &w);
+                ps.c1 = (kStreamBlock << 8) | (uint32_t)full;
+                e = fill_normal(w.M, w.n_pad / 16, rest, rest, ps, 1.0f, 1, s);
+            }
+        }
+        if (full > 0 && e == hipSuccess) {
+            factor_workspace_carve(base_full, B, &w);
+            e = householder_qr(w, B, full * count, (int64_t)(wb / sizeof(float)), s);
+        }
+        if (rest > 0 && e == hipSuccess) {
+            factor_workspace_carve(base_rest, rest, &w);
+            e = householder_qr(w, rest, count, (int64_t)(wr / sizeof(float)), s);
+        }
+        for (int o = 0; o < count && e == hipSuccess; ++o) {
+            gelo_mixing* m = got[o];
+            const uint64_t id = first_batch_id + (uint64_t)o;
+            for (int i = 0; i < full + (rest ? 1 : 0) && e == hipSuccess; ++i) {
+                const int rows = i < full ? B : rest;
+                if (i < full) factor_workspace_carve(base_full + wb * ((size_t)o * full + i), B, &w);
+                else factor_workspace_carve(base_rest + wr * o, rest, &w);
+                const int64_t at = (int64_t)i * B * m->ldk;
+                e = emit_matrix(w.X, w.n_pad / 16, 1, w.rdiag, rows, m->ldk, m->A32 + at, m->A16 ? m->A16 + at : nullptr,
+                                m->Ainv32 + at, m->Ainv16 ? m->Ainv16 + at : nullptr, s);
+            }
+            if (e == hipSuccess && k_shield > 0) {
+                ps.c1 = kStreamShield << 8; ps.c2 = (uint32_t)id; ps.c3 = (uint32_t)(id >> 32);
+                e = shield_directions(m->GS, k_shield, d, ps, m->gsnorm, s);
+            }
+        }
+        if (e != hipSuccess) st = hip_fail(ctx, e, "batched block-orthogonal draw");
+    }
+    for (int base = 0; st == GELO_OK && !small && !blocked && base < count; base += side) {
         const int c = count - base < side ? count - base : side;
         FactorWorkspace lw[kQrSideBySide];
         hipError_t e = hipSuccess;
@@ -1113,6 +1165,10 @@ gelo_status gelo_reserve(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_
     int lanes = 1;
     st = prepare_sampling(ctx, kind, n, dtype, max_attempts, &lanes);
     if (st != GELO_OK) return st;
+    if (kind == GELO_BLOCK_ORTHOGONAL && mixings > 1) {
+        st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, block_workspace_bytes(n) * (mixings < GELO_MAX_BATCH_DRAW ? mixings : GELO_MAX_BATCH_DRAW));
+        if (st != GELO_OK) return st;
+    }
     if (kind == GELO_ORTHOGONAL && n > kSmallMaxN && mixings > 1) {
         // a batched draw of `mixings` matrices factorises up to kQrSideBySide of them side by side
         const int side = qr_side_by_side(mixings, up256(factor_workspace_bytes(n)));

@@ -139,6 +139,33 @@ def test_static_entry_point_and_fresh_blocks(ctx):
         mats.append(g.gelo_mixing_export(ctx, m, 315, 15, 64, want_shields=False)[0])
         g.gelo_mixing_free(ctx, m)
     assert (mats[0] - mats[1]).abs().max() > 0.05
-    with pytest.raises(g.GeloError) as e:
-        g.gelo_sample_mixing_batch(ctx, g.GELO_BLOCK_ORTHOGONAL, 300, 15, 64, g.GELO_BF16, 20, 2)
-    assert g.STATUS_NAMES[e.value.status] == "GELO_EINVAL"
+
+
+@pytest.mark.parametrize("nd,k,d,count,picks", [(300, 15, 64, 5, (0, 4)), (2048, 102, 256, 6, (0, 3, 5)), (100, 0, 64, 3, (1,))])
+def test_batched_draw_equals_single_draws(ctx, nd, k, d, count, picks):
+    """All full blocks of all objects of a batched draw share one factorisation's launches; object i is still,
+    bit for bit, the single draw of its batch id."""
+    first = 40
+    n = nd + k
+    single = g.gelo_create(0, SEED, allow_batch_reuse=False)
+    try:
+        ms = g.gelo_sample_mixing_batch(ctx, g.GELO_BLOCK_ORTHOGONAL, nd, k, d, g.GELO_BF16, first, count)
+        H = dev(wl.make_hidden(nd, d, 78, 4), "bf16")
+        for i in picks:
+            m1 = g.gelo_sample_mixing(single, g.GELO_BLOCK_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=first + i)
+            U0 = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+            U1 = torch.empty_like(U0)
+            g.gelo_mix(ctx, ms[i], H, U0)
+            g.gelo_mix(single, m1, H, U1)
+            A0, Ai0, _, _, _ = g.gelo_mixing_export(ctx, ms[i], n, k, d, want_shields=False)
+            A1, Ai1, _, _, _ = g.gelo_mixing_export(single, m1, n, k, d, want_shields=False)
+            torch.cuda.synchronize()
+            assert torch.equal(A0, A1) and torch.equal(Ai0, Ai1) and torch.equal(U0, U1), f"object {i}"
+            g.gelo_mixing_free(single, m1)
+        for m in ms:
+            g.gelo_mixing_free(ctx, m)
+        with pytest.raises(g.GeloError) as e:
+            g.gelo_sample_mixing(ctx, g.GELO_BLOCK_ORTHOGONAL, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=first + count - 1)
+        assert g.STATUS_NAMES[e.value.status] == "GELO_EREUSE"
+    finally:
+        g.gelo_destroy(single)
