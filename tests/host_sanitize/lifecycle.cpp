@@ -98,6 +98,28 @@ int main() {
     EXPECT(gelo_mixing_free(ctx, m), GELO_OK);
     EXPECT(gelo_sample_mixing(ctx, GELO_ORTHOGONAL, nd, k, d, GELO_F32, 0.0, 1, 5001, &none, nullptr), GELO_EREUSE);   // fell out of the window
 
+    // the block-diagonal kind through the same life cycle, with more rows than one block holds (its host code: the block
+    // layout, one workspace per block, per-block launches, the dense export)
+    {
+        const int bnd = 280, bk = 14, bn = bnd + bk;
+        float *BH = nullptr, *BU = nullptr, *BY = nullptr, *BZ = nullptr, *BA = nullptr;
+        HIP_OK(hipMalloc(&BH, sizeof(float) * bnd * d)); HIP_OK(hipMalloc(&BU, sizeof(float) * bn * d));
+        HIP_OK(hipMalloc(&BY, sizeof(float) * bn * p)); HIP_OK(hipMalloc(&BZ, sizeof(float) * bnd * p));
+        HIP_OK(hipMalloc(&BA, sizeof(float) * bn * bn));
+        HIP_OK(hipMemset(BH, 0, sizeof(float) * bnd * d));
+        const uint64_t bid = 5000 + 3 * (uint64_t)GELO_BATCH_WINDOW;
+        EXPECT(gelo_sample_mixing(ctx, GELO_BLOCK_ORTHOGONAL, bnd, bk, d, GELO_F32, 0.0, 1, bid, &m, nullptr), GELO_OK);
+        EXPECT(gelo_mix(ctx, m, GELO_F32, BH, d, 10.f, GELO_NORM_MEDIAN, BU, d, nullptr), GELO_OK);
+        EXPECT(gelo_project(ctx, GELO_F32, bn, d, p, BU, d, W, p, BY, p, nullptr), GELO_OK);
+        EXPECT(gelo_unmix(ctx, m, GELO_F32, p, BY, p, BZ, p, nullptr), GELO_OK);
+        EXPECT(gelo_mixing_export(ctx, m, BA, nullptr, nullptr, nullptr, nullptr, nullptr), GELO_OK);
+        EXPECT(gelo_mixing_free(ctx, m), GELO_OK);
+        EXPECT(gelo_sample_mixing_batch(ctx, GELO_BLOCK_ORTHOGONAL, bnd, bk, d, GELO_F32, bid + 1, 3, many, nullptr), GELO_OK);
+        for (int i = 0; i < 3; ++i) EXPECT(gelo_mixing_free(ctx, many[i]), GELO_OK);
+        HIP_OK(hipDeviceSynchronize());
+        HIP_OK(hipFree(BH)); HIP_OK(hipFree(BU)); HIP_OK(hipFree(BY)); HIP_OK(hipFree(BZ)); HIP_OK(hipFree(BA));
+    }
+
     size_t bytes = 0;
     EXPECT(gelo_fp8_weight_bytes(128, 64, &bytes), GELO_OK);
     EXPECT(gelo_fp8_weight_bytes(128, 64, nullptr), GELO_EINVAL);
