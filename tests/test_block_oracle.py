@@ -67,3 +67,15 @@ def test_chain_identities():
     H2 = H.copy(); H2[d0 + dn + 3] += 1.0
     S_fixed = out["S"]
     assert np.array_equal(o.mix(out["A"], H, S_fixed)[:rows], o.mix(out["A"], H2, S_fixed)[:rows])
+
+
+def test_bench_restates_the_same_layout():
+    """bench.py counts the operations of the block kind from its own statement of the cut (it may not import the
+    oracle outside its CPU-baseline leg): both must describe the same blocks."""
+    import importlib.util
+    import os
+    spec = importlib.util.spec_from_file_location("bench_for_test", os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    for n_data, k in ((2048, 102), (4096, 205), (300, 15), (100, 0), (1, 0), (513, 7)):
+        assert bench.block_rows(n_data, k) == [(rows, dn) for _, rows, _, dn, _, _ in o.block_layout(n_data, k)]
