@@ -136,7 +136,8 @@ const char* gelo_status_string(gelo_status s);
 
 /* Trusted side, Section 3.2 step 1.2.  Draws the secrets of batch `batch_id`: A (n x n,
  * n = n_data + k_shield), its inverse, and k_shield Gaussian shield directions of width d.
- * A pure function of (seed, batch_id, kind, n, k_shield, d).  cond_max and max_attempts
+ * A pure function of (seed, batch_id, kind, n, k_shield, d) (GELO_BLOCK_ORTHOGONAL: its blocks depend on how n
+ * splits into n_data and k_shield).  cond_max and max_attempts
  * (1..GELO_MAX_ATTEMPTS) are used by GELO_GAUSSIAN only: it factorises up to four consecutive
  * attempts side by side on streams of its own (n <= 1024; one at a time beyond), reads their
  * condition estimates back (the only host synchronisation in the library) and returns the first
