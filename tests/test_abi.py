@@ -64,3 +64,12 @@ def test_enumerators_agree_between_header_binding_and_workloads():
         values["GELO_BLOCK_ORTHOGONAL"])
     assert binding.STATUS_NAMES[values["GELO_ESHAPE"]] == "GELO_ESHAPE" and binding.STATUS_NAMES[values["GELO_EHIP"]] == "GELO_EHIP"
     assert int(re.search(r"#define GELO_MAX_N (\d+)", text).group(1)) == binding.GELO_MAX_N
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """the measurement is a one-GPU figure: asking for more must end with a message, before anything touches a GPU"""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr)
