@@ -169,6 +169,8 @@ def run_composite(args, torch, np, g, wl):
         def chain(i):
             r, j, l = (i // group) % rings, i % group, i % L
             w = parts[l]
+            if j == (Wm * L) % group:                        # the timed region opens with a draw (as in main)
+                draw_group((r + rings - 1) % rings)
             m = ring[r][j]
             u, y, z = views(w)
             g.gelo_mix(ctxs[r], m, Hs[l], u, w.shield_scale)
@@ -176,9 +178,11 @@ def run_composite(args, torch, np, g, wl):
             g.gelo_unmix(ctxs[r], m, y, z)
             g.gelo_mixing_free(ctxs[r], m)
             ring[r][j] = None
-            if j == (Wm * L) % group:                        # the timed region opens with a draw (as in main)
-                draw_group((r + rings - 1) % rings)
 
+        draw_group(rings - 1)                                # every context has drawn once before anything is timed
+        for m in ring[rings - 1]:
+            g.gelo_mixing_free(ctxs[rings - 1], m)
+        ring[rings - 1] = None
         for r in range(rings - 1):
             draw_group(r)
         i = 0
@@ -452,15 +456,21 @@ def main() -> int:
 
         def pstep(i):
             r, j = (i // group) % rings, i % group
+            if j == Wm % group:                                     # the timed region opens with a draw and overlaps it whole
+                draw_group((r + rings - 1) % rings)                 # the group consumed before this one is replaced
             m = ring[r][j]
             g.gelo_mix(ctxs[r], m, H, U, w.shield_scale)             # waits for the draw through the object's event
             g.gelo_project(ctxs[r], U, W, Y)
             g.gelo_unmix(ctxs[r], m, Y, Z)
             g.gelo_mixing_free(ctxs[r], m)
             ring[r][j] = None
-            if j == Wm % group:                                     # the timed region opens with a draw and overlaps it whole
-                draw_group((r + rings - 1) % rings)                 # the group consumed before this one is replaced
 
+        # every context has drawn once before anything is timed (a context's first batched draw costs its host
+        # thread several milliseconds); the last one's objects go back unused
+        draw_group(rings - 1)
+        for m in ring[rings - 1]:
+            g.gelo_mixing_free(ctxs[rings - 1], m)
+        ring[rings - 1] = None
         for r in range(rings - 1):                                  # two groups ahead; the third is drawn at step Wm % group
             draw_group(r)
         leftovers = lambda: [(ctxs[r], m) for r in range(rings) for m in (ring[r] or []) if m is not None]
