@@ -428,8 +428,8 @@ template <int N> __device__ __forceinline__ void wait_fetches() { asm volatile("
 
 template <int NBLK>
 __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, int count, int64_t off, float* Cs, int nblocks) {
-    constexpr int GRP = NBLK % 2 == 0 ? 2 : 1, NG = NBLK / GRP;      // blocks per fetch group, groups per product
-    constexpr int DEPTH = 2;                                         // ring slots per wave: groups on their way or in use
+    constexpr int GRP = NBLK % 3 == 0 ? 3 : NBLK % 2 == 0 ? 2 : 1, NG = NBLK / GRP;      // blocks per fetch group, groups per product
+    constexpr int DEPTH = 2;                                         // ring slots per wave: one group in use, one on its way
     __shared__ __attribute__((aligned(1024))) float ring[8][DEPTH][GRP][256];
     __shared__ float Wp[2][8][NB][NB];
     __shared__ float Ts[2][NB][NB];
@@ -437,22 +437,29 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
     const int c = lane & 15, g = lane >> 4;
     float* Cl = Cs + c * 16 + 4 * g;
     const int last = nblocks - 1;
+    // The strip's own blocks arrive group by group behind the first product of the first reflector, each requested
+    // two groups ahead of its use, so that a workgroup starts on the matrix cores after two groups instead of
+    // after the whole strip.  (Blocks past the end load the last block again - a valid address, a fixed number of
+    // loads - and are never used: the products and the stores skip them.)
     f32x4_t cr[NBLK];
+    auto load_strip = [&](auto gc) {
+        constexpr int grp = decltype(gc)::value;
+        if constexpr (grp < NG) {
 #pragma unroll
-    for (int b = 0; b < NBLK; ++b) {
-        const int blk = wave + 8 * b;
-        // the strip passes through once: keep it out of the way of the reflectors, which every strip of the matrix re-reads from L2
-        const f32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(Cl + 256 * (blk < nblocks ? blk : last)));
-        const bool valid = blk < nblocks;
-        cr[b] = f32x4_t{valid ? v[0] : 0.f, valid ? v[1] : 0.f, valid ? v[2] : 0.f, valid ? v[3] : 0.f};
-    }
+            for (int k = 0; k < GRP; ++k) {
+                const int blk = wave + 8 * (grp * GRP + k);
+                // the strip passes through once: keep it out of the way of the reflectors, which every strip of the matrix re-reads from L2
+                cr[grp * GRP + k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(Cl + 256 * (blk < nblocks ? blk : last)));
+            }
+        }
+    };
     const uint32_t ring_addr = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)&ring[wave][0][0][0]);
     const float* mine = &ring[wave][0][0][0] + lane * 4;                 // this lane's operand inside a block
     const float* zero_l = g_zero_tile + c * 16 + 4 * g;
     // Group j of reflector q (first the NG groups of the tiled layout, then the NG of the row layout) is number
     // u = 2 NG q + j of the strip and goes to ring slot u % DEPTH.  Before a wave waits for group u it requests group
-    // u + DEPTH - 1 into the slot that group u - 1 has just left: DEPTH - 1 groups are on their way while one is
-    // in use, across the barriers and from one reflector to the next.
+    // u + 1 into the slot that group u - 1 has just left: one group is on its way while one is in use, across the
+    // barriers and from one reflector to the next.
     auto request = [&](const Reflector& R, auto uc) {
         constexpr int u = decltype(uc)::value, j = u % (2 * NG), phase = j / NG, grp = j % NG;
         const float* base = (phase == 0 ? R.Vt : R.Vr) + off + c * 16 + 4 * g;
@@ -464,23 +471,28 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
         }
     };
     float t_next = tid < NB * NB ? refl[0].T[off + tid] : 0.f;
-    static_for<DEPTH - 1>([&](auto uc) { request(refl[0], uc); });      // 2 NG >= DEPTH - 1: all of reflector 0
+    load_strip(std::integral_constant<int, 0>{});
+    load_strip(std::integral_constant<int, 1>{});
+    request(refl[0], std::integral_constant<int, 0>{});
     static_for<kMaxDelay>([&](auto qc) {
         constexpr int q = decltype(qc)::value;
         if (q >= count) return;
         const Reflector R = refl[q];
         const bool more = q + 1 < count;
         const Reflector Rn = more ? refl[q + 1] : R;
-        // Group j has landed once no more fetches are counted than those of the groups requested behind it (the
-        // counter runs in issue order; any other load of this wave in between only makes the wait longer).  Behind
-        // it are the next DEPTH - 1 groups - those of them that exist: the last reflector has no successor.
-        auto arrived = [&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            constexpr int here = (2 * NG - 1 - j) < (DEPTH - 1) ? (2 * NG - 1 - j) : (DEPTH - 1);      // behind it, same reflector
-            if (more) wait_fetches<(DEPTH - 1) * GRP>(); else wait_fetches<here * GRP>();
+        // Fetches (and the strip's loads) are counted in issue order, so block k of group j has landed once no more
+        // are outstanding than were issued behind it: the rest of its group, the strip group that went out with the
+        // request for group j + 1 (first product of the first reflector only), and group j + 1 itself - which does
+        // not exist behind the last group of the last reflector.  (Any other load of this wave in between only makes
+        // the wait longer.)
+        auto landed = [&](auto jc, auto kc) {
+            constexpr int j = decltype(jc)::value, k = decltype(kc)::value;
+            constexpr int own = GRP - 1 - k, strip = (q == 0 && j + 2 < NG) ? GRP : 0;
+            if constexpr (j + 1 < 2 * NG) wait_fetches<own + strip + GRP>();
+            else { if (more) wait_fetches<own + GRP>(); else wait_fetches<own>(); }
         };
-        auto request_ahead = [&](auto jc) {                   // the group DEPTH - 1 places on, into the slot consumed last
-            constexpr int j = decltype(jc)::value, nj = j + DEPTH - 1;
+        auto request_ahead = [&](auto jc) {                   // the next group, into the slot consumed last
+            constexpr int j = decltype(jc)::value, nj = j + 1;
             if constexpr (nj < 2 * NG) request(R, std::integral_constant<int, 2 * NG * q + nj>{});
             else if (more) request(Rn, std::integral_constant<int, 2 * NG * q + nj>{});
         };
@@ -488,18 +500,18 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
         f32x4_t w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
         static_for<NG>([&](auto gc) {
             constexpr int grp = decltype(gc)::value;
+            if constexpr (q == 0) load_strip(std::integral_constant<int, grp + 2>{});
             request_ahead(gc);
-            arrived(gc);
-#pragma unroll
-            for (int k = 0; k < GRP; ++k) {
-                const int b = grp * GRP + k;
-                if (wave + 8 * b > last) continue;            // a block past the end (wave-uniform): its fetch was the zero tile
+            static_for<GRP>([&](auto kc) {
+                constexpr int k = decltype(kc)::value, b = grp * GRP + k;
+                if (wave + 8 * b > last) return;              // a block past the end (wave-uniform): its fetch was the zero tile
+                landed(gc, kc);
                 const f32x4_t a = *reinterpret_cast<const f32x4_t*>(mine + (((2 * NG * q + grp) % DEPTH) * GRP + k) * 256);
                 w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], cr[b][0], w0, 0, 0, 0);
                 w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], cr[b][1], w1, 0, 0, 0);
                 w0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], cr[b][2], w0, 0, 0, 0);
                 w1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], cr[b][3], w1, 0, 0, 0);
-            }
+            });
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the operands are in registers before their ring slot is refilled
         });
         if (tid < NB * NB) { if (R.plain_t) Ts[q & 1][tid & 15][tid >> 4] = t_mine; else Ts[q & 1][tid >> 4][tid & 15] = t_mine; }
@@ -523,15 +535,14 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
         static_for<NG>([&](auto gc) {
             constexpr int grp = decltype(gc)::value, j = NG + grp;
             request_ahead(std::integral_constant<int, j>{});
-            arrived(std::integral_constant<int, j>{});
-#pragma unroll
-            for (int k = 0; k < GRP; ++k) {
-                const int b = grp * GRP + k;
-                if (wave + 8 * b > last) continue;
+            static_for<GRP>([&](auto kc) {
+                constexpr int k = decltype(kc)::value, b = grp * GRP + k;
+                if (wave + 8 * b > last) return;
+                landed(std::integral_constant<int, j>{}, kc);
                 const f32x4_t a4 = *reinterpret_cast<const f32x4_t*>(mine + (((2 * NG * q + j) % DEPTH) * GRP + k) * 256);
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) cr[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[kk], bq[kk], cr[b], 0, 0, 0);
-            }
+            });
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         });
     });
