@@ -48,7 +48,7 @@ def build_sanitized(verbose: bool = False) -> str:
     root = os.path.dirname(HERE)
     san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
     api_obj = os.path.join(obj_dir, "api_hostsan.o")
-    lib = os.path.join(HERE, "libgelo_hostsan.so")           # beside libgelo.so: what a GPU machine receives
+    lib = os.path.join(HERE, "libgelo_hostsan.so")           # beside libgelo.so, where the host-side tests look for it
     exe = os.path.join(HERE, "lifecycle_hostsan")
     cmds = [
         [HIPCC, *FLAGS, *san, "-c", os.path.join(CSRC, "api.hip"), "-o", api_obj],
