@@ -437,6 +437,7 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
     const int c = lane & 15, g = lane >> 4;
     float* Cl = Cs + c * 16 + 4 * g;
     const int last = nblocks - 1;
+    if (count < 1) return;                                           // no reflector: the strip stays as it is (and is not loaded at all)
     // The strip's own blocks arrive group by group behind the first product of the first reflector, each requested
     // two groups ahead of its use, so that a workgroup starts on the matrix cores after two groups instead of
     // after the whole strip.  (Blocks past the end load the last block again - a valid address, a fixed number of
