@@ -382,6 +382,45 @@ def sample_block_orthogonal(seed, batch_id, n_data, k, block=BLOCK_ROWS):
 
 
 # --------------------------------------------------------------------------
+# Orthogonal A as a product of reflectors drawn directly (Section 3.2 step 1.2 asks for a fresh random orthogonal
+# A; Section 4.2 and Table 3 name its generation as what grows like n^3; the Conclusion asks for faster
+# orthogonal transforms).  In the Householder QR of a Gaussian G the k-th reflector is built from column k of
+# the UPDATED matrix, rows k onward - which, given the earlier reflectors, is again a vector of independent
+# standard Gaussians.  So the reflectors have the same joint law when each is built from the raw entries
+# G[k:, k] instead, and  A = H_0 H_1 ... H_{n-1} diag(sign beta_k)  (H_k x_k = beta_k e_0) is Haar-distributed
+# like the QR factor - without factorising anything (Stewart, SIAM J. Numer. Anal. 17, 1980).
+# --------------------------------------------------------------------------
+def orthogonal_from_reflectors(G):
+    """A = H_0 H_1 ... H_{n-1} diag(sign beta_k), H_k = diag(I_k, I - 2 v v^T / (v^T v)) with
+    v = x + sign(x_0) ||x|| e_0 and x = G[k:, k] (raw entries), so that H_k maps x to beta_k e_0,
+    beta_k = -sign(x_0) ||x||.  A column of zeros contributes the identity and the sign +1."""
+    G = np.asarray(G, dtype=np.float64)
+    n = G.shape[0]
+    if G.shape[1] != n:
+        raise ValueError("square matrix expected")
+    Q = np.eye(n)
+    beta = np.zeros(n)
+    for k in range(n - 1, -1, -1):                     # Q <- H_k Q: H_{n-1} first, H_0 last
+        x = G[k:, k]
+        norm_x = math.sqrt(float(x @ x))
+        if norm_x == 0.0:
+            continue
+        v = x.copy()
+        v[0] += norm_x if x[0] >= 0.0 else -norm_x
+        beta[k] = -norm_x if x[0] >= 0.0 else norm_x
+        Q[k:, :] -= (2.0 / float(v @ v)) * np.outer(v, v @ Q[k:, :])
+    signs = np.where(beta < 0.0, -1.0, 1.0)
+    return Q * signs[None, :]
+
+
+def sample_reflector_product(seed, batch_id, n):
+    """Fresh orthogonal A for one batch from the same Gaussian draw as sample_orthogonal; returns (A, A^T)."""
+    G = gaussian_matrix(seed, batch_id, STREAM_MIXING, 0, n, n)
+    A = orthogonal_from_reflectors(G)
+    return A, A.T.copy()
+
+
+# --------------------------------------------------------------------------
 # Shield rows (Section 3.2.1, Mitigation 2, eqs. 7-9).
 # --------------------------------------------------------------------------
 NORM_MEDIAN = 0
@@ -443,6 +482,7 @@ KIND_GAUSSIAN = 1
 KIND_CONDITIONED = 2
 KIND_STRUCTURED = 3
 KIND_BLOCK_ORTHOGONAL = 4
+KIND_REFLECTOR_PRODUCT = 5
 
 
 def sample_mixing(kind, seed, batch_id, n, cond_max=1e3, max_attempts=64):
@@ -458,6 +498,9 @@ def sample_mixing(kind, seed, batch_id, n, cond_max=1e3, max_attempts=64):
         return A, A_inv, {"attempt": 0, "kappa": kappa}
     if kind == KIND_STRUCTURED:
         A, A_inv = sample_structured(seed, batch_id, n)
+        return A, A_inv, {"attempt": 0, "kappa": 1.0}
+    if kind == KIND_REFLECTOR_PRODUCT:
+        A, A_inv = sample_reflector_product(seed, batch_id, n)
         return A, A_inv, {"attempt": 0, "kappa": 1.0}
     raise ValueError("unknown kind")
 
