@@ -26,7 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}          # MI355X dense matrix peaks
-KIND_NAME = {0: "orthogonal", 1: "gaussian", 2: "conditioned", 3: "structured", 4: "block_orthogonal"}
+KIND_NAME = {0: "orthogonal", 1: "gaussian", 2: "conditioned", 3: "structured", 4: "block_orthogonal", 5: "reflector_product"}
 BLOCK_ROWS = 256
 
 
@@ -61,7 +61,8 @@ def gen_flops(w, attempts=1):
     lu = 2.0 * n ** 3                  # LU + explicit inverse
     if w.kind == 4:
         return sum(8.0 / 3.0 * float(r) ** 3 for r, _ in block_rows(w.n_data, w.k_shield))
-    return {0: qr, 1: lu * attempts, 2: qr + lu, 3: 0.0}[w.kind]   # structured: sorting keys, no arithmetic to count
+    # structured: sorting keys, no arithmetic to count; product of directly drawn reflectors: only Q is formed
+    return {0: qr, 1: lu * attempts, 2: qr + lu, 3: 0.0, 5: 4.0 / 3.0 * n ** 3}[w.kind]
 
 
 CAL_ELEMS = 1 << 28                                   # fp32 elements of the calibration copy: 1 GiB read, 1 GiB written
@@ -435,7 +436,7 @@ def main() -> int:
     # the current batch runs.  Every timed step still generates one fresh A and consumes one.
     main = torch.cuda.current_stream()
     bid = [0]
-    if w.kind in (g.GELO_ORTHOGONAL, g.GELO_BLOCK_ORTHOGONAL):
+    if w.kind in (g.GELO_ORTHOGONAL, g.GELO_BLOCK_ORTHOGONAL, g.GELO_REFLECTOR_PRODUCT):
         # batched draws: `group` matrices per call (their factorisations share every launch), `rings` groups alive:
         # one being consumed while the others are drawn on side streams.  A group is drawn at every step whose
         # number is the warm-up count modulo the group size (so the first timed step issues one: a short timed
@@ -614,17 +615,18 @@ def main() -> int:
         result["fp8_projection"]["matrix_only_ceiling"] = {"achieved": flop8 / sec8 / 1e12, "unit": "TFLOP/s", "frac_of_peak": flop8 / sec8 / 1e12 / 5000.0,
                                                            "note": "v_mfma_f32_32x32x64_f8f6f4 (E4M3) only, same shape of loop"}
 
-    if w.kind in (0, 1, 2):
+    if w.kind in (0, 1, 2, 5):
         # A generation against the float matrix peak: the factorisations' trailing updates run on the float MFMA
         # path; their panels are bound by the latency of one workgroup, which is what keeps the fraction low
         t_gen = stage["sample"] * 1e-3
         result["a_gen"] = {"kernel": {0: "Philox + Householder QR with explicit Q", 1: "Philox + pivoted LU + inverse + condition estimate (per accepted draw)",
-                                      2: "Householder QR + pivoted LU + inverse + condition estimate"}[w.kind],
+                                      2: "Householder QR + pivoted LU + inverse + condition estimate",
+                                      5: "Philox + reflectors from the raw columns + their product"}[w.kind],
                            "bound": "mfma", "flop": f_gen, "ms": t_gen * 1e3, "achieved": f_gen / t_gen / 1e12, "peak": PEAK_TFLOPS["f32"],
                            "unit": "TFLOP/s", "frac": f_gen / t_gen / 1e12 / PEAK_TFLOPS["f32"],
                            "pipelined_ms_per_draw": t_step * 1e3,
                            "note": "one draw alone on one stream; pipelined_ms_per_draw bounds it from above when draws of other batches overlap"}
-        if w.kind == g.GELO_ORTHOGONAL and n > 128:
+        if w.kind in (g.GELO_ORTHOGONAL, g.GELO_REFLECTOR_PRODUCT) and n > 128:
             # the same factorisation as throughput work: `group` draws in one batched call (side by side in the same
             # launches), nothing else on the GPU
             bctx = g.gelo_create(0, w.seed + 77, allow_batch_reuse=False)
@@ -723,7 +725,7 @@ def main() -> int:
         f_chain_s = 2.0 * ns * ns * d + 2.0 * ns * d * p + 2.0 * rows * ns * p
         if w.kind == 3:
             f_chain_s = 2.0 * ns * d * p + STRUCTURED_ROUNDS * butterfly_adds(ns) * (d + p)
-        f_gen_s = {0: 8.0 / 3.0, 1: 2.0 * (ref["info"]["attempt"] + 1), 2: 8.0 / 3.0 + 2.0, 3: 0.0, 4: 0.0}[w.kind] * float(ns) ** 3
+        f_gen_s = {0: 8.0 / 3.0, 1: 2.0 * (ref["info"]["attempt"] + 1), 2: 8.0 / 3.0 + 2.0, 3: 0.0, 4: 0.0, 5: 4.0 / 3.0}[w.kind] * float(ns) ** 3
         if w.kind == 4:
             f_chain_s = 2.0 * ns * d * p + sum(2.0 * r * r * d + 2.0 * dr * r * p for r, dr in block_rows(rows, ks))
             f_gen_s = sum(8.0 / 3.0 * float(r) ** 3 for r, _ in block_rows(rows, ks))

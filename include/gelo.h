@@ -92,9 +92,17 @@ typedef enum { GELO_F32 = 0, GELO_BF16 = 1 } gelo_dtype;
  *               mixing the paper's Conclusion asks for.  What it gives up: rows mix only inside their block
  *               (a block's U^T U is the Gram matrix of ITS rows of [H; S], so the leak of eq. 5 is per block,
  *               244 rows at a time here instead of all n_data), which the paper does not analyse.
- *               gelo_mixing_export builds the dense n x n matrix that acts on the stacked [H; S]. */
+ *               gelo_mixing_export builds the dense n x n matrix that acts on the stacked [H; S].
+ *  REFLECTOR_PRODUCT  A = H_0 H_1 ... H_{n-1} diag(sign beta_k): the Householder reflectors of the ORTHOGONAL
+ *               construction, but reflector k is built from the raw entries G[k:, k] of the Philox Gaussian (it
+ *               maps them to beta_k e_0) instead of from column k of a partly factorised matrix.  In the QR that
+ *               column, given the earlier reflectors, is again a vector of independent Gaussians, so A has
+ *               exactly the law of the ORTHOGONAL kind (Haar; Stewart 1980) - a dense orthogonal A with
+ *               A^-1 = A^T, the same leakage statement - at half the arithmetic (4/3 n^3: only the product is
+ *               formed) and without the chain of dependent panels: the cheaper generation of A that Section
+ *               4.2 finds wanting for n > 2048.  A different matrix than ORTHOGONAL gives for the same ids. */
 typedef enum { GELO_ORTHOGONAL = 0, GELO_GAUSSIAN = 1, GELO_CONDITIONED = 2, GELO_STRUCTURED = 3,
-               GELO_BLOCK_ORTHOGONAL = 4 } gelo_kind;
+               GELO_BLOCK_ORTHOGONAL = 4, GELO_REFLECTOR_PRODUCT = 5 } gelo_kind;
 
 /* Row-norm statistic of H that the shield rows are scaled by. */
 typedef enum { GELO_NORM_MEDIAN = 0, GELO_NORM_MEAN = 1 } gelo_norm_stat;
@@ -155,7 +163,8 @@ gelo_status gelo_sample_mixing(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_
 
 /* Trusted side, Section 3.2 step 1.2, many batches at once: `count` mixing objects (1..GELO_MAX_BATCH_DRAW) for
  * batch ids first_batch_id .. first_batch_id + count - 1, all of one shape.  A does not depend on the data, so
- * a decode step's worth, or the next few prefill batches, can be drawn ahead together.  GELO_ORTHOGONAL, and
+ * a decode step's worth, or the next few prefill batches, can be drawn ahead together.  GELO_ORTHOGONAL,
+ * GELO_REFLECTOR_PRODUCT (always by the launches for larger n below), and
  * GELO_BLOCK_ORTHOGONAL (all full blocks of all objects share the launches of one batched factorisation).
  *  n <= GELO_STATIC_MAX_N  ONE launch draws all of them (at this size a fresh A per layer-step costs more in
  *                          launch latency than in work);
@@ -233,7 +242,7 @@ gelo_status gelo_qkv_forward(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, in
  * Calls no hipMalloc / hipFree and creates no stream, event or pooled object.  n = n_data + k_shield
  * <= GELO_STATIC_MAX_N, and the batch's buffers (about 0.6 MB at n = 128 plus 10 bytes (bf16) or
  * 12 bytes (float) per element of the k_shield x d shield block) must fit the static buffer:
- * GELO_ESHAPE otherwise.  kind: GELO_ORTHOGONAL, GELO_CONDITIONED, GELO_STRUCTURED or GELO_BLOCK_ORTHOGONAL.  U (n x d) and
+ * GELO_ESHAPE otherwise.  kind: any but GELO_GAUSSIAN.  U (n x d) and
  * Y (n x p) are required; H, W, Z, U, Y densely packed as in gelo_qkv_forward.  All calls on one GPU
  * share the one buffer, whatever their context or stream: calls that overlap in time on a GPU race;
  * issue them on one stream or order them yourself.  Same results, bit for bit, as gelo_qkv_forward

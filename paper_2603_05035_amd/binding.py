@@ -12,7 +12,7 @@ from ctypes import (POINTER, byref, c_char_p, c_double, c_float, c_int, c_int64,
 import torch
 
 GELO_F32, GELO_BF16 = 0, 1
-GELO_ORTHOGONAL, GELO_GAUSSIAN, GELO_CONDITIONED, GELO_STRUCTURED, GELO_BLOCK_ORTHOGONAL = 0, 1, 2, 3, 4
+GELO_ORTHOGONAL, GELO_GAUSSIAN, GELO_CONDITIONED, GELO_STRUCTURED, GELO_BLOCK_ORTHOGONAL, GELO_REFLECTOR_PRODUCT = 0, 1, 2, 3, 4, 5
 GELO_NORM_MEDIAN, GELO_NORM_MEAN = 0, 1
 GELO_OK = 0
 STATUS_NAMES = ["GELO_OK", "GELO_EINVAL", "GELO_ESHAPE", "GELO_EDTYPE", "GELO_EALIGN", "GELO_ENOMEM",

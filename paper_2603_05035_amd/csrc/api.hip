@@ -411,7 +411,7 @@ static size_t block_workspace_bytes(int n) {
 static gelo_status check_sample_args(gelo_ctx* ctx, gelo_kind kind, int n_data, int k_shield, int d, gelo_dtype dtype,
                                      double cond_max, int max_attempts, uint64_t batch_id, int* n_out) {
     if (kind != GELO_ORTHOGONAL && kind != GELO_GAUSSIAN && kind != GELO_CONDITIONED && kind != GELO_STRUCTURED &&
-        kind != GELO_BLOCK_ORTHOGONAL)
+        kind != GELO_BLOCK_ORTHOGONAL && kind != GELO_REFLECTOR_PRODUCT)
         return fail(ctx, GELO_EINVAL, "unknown kind %d", (int)kind);
     if (dtype != GELO_F32 && dtype != GELO_BF16) return fail(ctx, GELO_EINVAL, "unknown dtype %d", (int)dtype);
     if (n_data < 1 || k_shield < 0 || d < 1) return fail(ctx, GELO_EINVAL, "n_data=%d k_shield=%d d=%d", n_data, k_shield, d);
@@ -447,10 +447,10 @@ static gelo_status sample_into(gelo_ctx* ctx, gelo_mixing* m, FactorWorkspace ws
     const bool bf = m->dtype == GELO_BF16;
     m->kind = kind; m->attempt = 0; m->kappa = 1.0f;
 
-    auto orthogonal_into_X = [&]() -> hipError_t {
+    auto orthogonal_into_X = [&](bool direct) -> hipError_t {
         ps.c1 = kStreamMixing << 8;
         hipError_t e = fill_normal(ws.M, ws.n_pad / 16, n, n, ps, 1.0f, 1, s);     // straight into the QR's tiles
-        if (e == hipSuccess) e = householder_qr(ws, n, 1, 0, s);
+        if (e == hipSuccess) e = householder_qr(ws, n, 1, 0, s, direct);
         return e;
     };
 
@@ -499,12 +499,12 @@ static gelo_status sample_into(gelo_ctx* ctx, gelo_mixing* m, FactorWorkspace ws
             GELO_HIP(ctx, householder_qr(w, rest, 1, 0, s));
             GELO_HIP(ctx, emit_block(w, full, rest));
         }
-    } else if (kind == GELO_ORTHOGONAL) {
-        GELO_HIP(ctx, orthogonal_into_X());
-        // A = Q diag(sign r_ii); A^-1 = A^T
+    } else if (kind == GELO_ORTHOGONAL || kind == GELO_REFLECTOR_PRODUCT) {
+        GELO_HIP(ctx, orthogonal_into_X(kind == GELO_REFLECTOR_PRODUCT));
+        // A = Q diag(sign r_ii) (sign beta_k for the product of reflectors); A^-1 = A^T
         GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, m->A16, m->Ainv32, m->Ainv16, s));
     } else if (kind == GELO_CONDITIONED) {
-        GELO_HIP(ctx, orthogonal_into_X());
+        GELO_HIP(ctx, orthogonal_into_X(false));
         GELO_HIP(ctx, emit_matrix(ws.X, ws.n_pad / 16, 1, ws.rdiag, n, ldk, m->A32, nullptr, nullptr, nullptr, s));
         ps.c1 = kStreamPerturb << 8;
         GELO_HIP(ctx, fill_normal(ws.M, ld, n, n, ps, 1.0f, 0, s));
@@ -862,8 +862,8 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
     if (!out) return fail(ctx, GELO_EINVAL, "out is NULL");
     if (count < 1 || count > GELO_MAX_BATCH_DRAW) return fail(ctx, GELO_EINVAL, "count=%d outside 1..%d", count, GELO_MAX_BATCH_DRAW);
     for (int i = 0; i < count; ++i) out[i] = nullptr;
-    if (kind != GELO_ORTHOGONAL && kind != GELO_BLOCK_ORTHOGONAL)
-        return fail(ctx, GELO_EINVAL, "batched draws exist for GELO_ORTHOGONAL and GELO_BLOCK_ORTHOGONAL only");
+    if (kind != GELO_ORTHOGONAL && kind != GELO_BLOCK_ORTHOGONAL && kind != GELO_REFLECTOR_PRODUCT)
+        return fail(ctx, GELO_EINVAL, "batched draws exist for GELO_ORTHOGONAL, GELO_BLOCK_ORTHOGONAL and GELO_REFLECTOR_PRODUCT only");
     if (first_batch_id > UINT64_MAX - (uint64_t)count) return fail(ctx, GELO_EINVAL, "batch ids leave 64 bits");
     int n = 0;
     for (int i = 0; i < count; ++i) {
@@ -873,7 +873,7 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
     GELO_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t s = (hipStream_t)stream;
     const bool blocked = kind == GELO_BLOCK_ORTHOGONAL;
-    const bool small = !blocked && n <= kSmallMaxN;
+    const bool small = kind == GELO_ORTHOGONAL && n <= kSmallMaxN;
     // larger matrices: up to kQrSideBySide factorisations share every launch, each in a workspace of its own
     const size_t ws_bytes = up256(factor_workspace_bytes(n));
     const int side = qr_side_by_side(count, ws_bytes);
@@ -962,7 +962,7 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
             ps.c1 = kStreamMixing << 8; ps.c2 = (uint32_t)id; ps.c3 = (uint32_t)(id >> 32);
             e = fill_normal(lw[i].M, lw[i].n_pad / 16, n, n, ps, 1.0f, 1, s);      // straight into the QR's tiles
         }
-        if (e == hipSuccess) e = householder_qr(lw[0], n, c, (int64_t)(ws_bytes / sizeof(float)), s);
+        if (e == hipSuccess) e = householder_qr(lw[0], n, c, (int64_t)(ws_bytes / sizeof(float)), s, kind == GELO_REFLECTOR_PRODUCT);
         for (int i = 0; i < c && e == hipSuccess; ++i) {
             gelo_mixing* m = got[base + i];
             const uint64_t id = first_batch_id + (uint64_t)(base + i);
@@ -1169,7 +1169,7 @@ gelo_status gelo_reserve(gelo_ctx* ctx, gelo_kind kind, gelo_dtype dtype, int n_
         st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, block_workspace_bytes(n) * (mixings < GELO_MAX_BATCH_DRAW ? mixings : GELO_MAX_BATCH_DRAW));
         if (st != GELO_OK) return st;
     }
-    if (kind == GELO_ORTHOGONAL && n > kSmallMaxN && mixings > 1) {
+    if (((kind == GELO_ORTHOGONAL && n > kSmallMaxN) || kind == GELO_REFLECTOR_PRODUCT) && mixings > 1) {
         // a batched draw of `mixings` matrices factorises up to kQrSideBySide of them side by side
         const int side = qr_side_by_side(mixings, up256(factor_workspace_bytes(n)));
         st = grow(ctx, &ctx->factor_ws, &ctx->factor_ws_bytes, up256(factor_workspace_bytes(n)) * side);

@@ -92,7 +92,10 @@ __device__ __forceinline__ float lane_value(float v) {
 // (element (r, c) at Mp[(r / 16) * 256 + c * 16 + r % 16]).  The reflector block is written twice,
 // compactly: Vr[r * 16 + c] (row-major, the A operand of C += V W') and Vt in the same tiles as
 // the panel (the A operand of W = V^T C), both with explicit unit diagonal and zeros above.
-template <int NTHR, int R>
+// UPDATE = false builds every reflector from the column as it stands in memory - the later columns of the panel do
+// not see the earlier reflectors - which is what the product of directly drawn reflectors needs (householder_qr with
+// `direct`): the same reflector formulas, the same T, no factorisation.
+template <int NTHR, int R, bool UPDATE = true>
 __device__ __forceinline__ void qr_panel_body(float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, int m) {
     constexpr int NW = NTHR / 64;
     __shared__ float red[2][NW][NB];
@@ -165,16 +168,20 @@ __device__ __forceinline__ void qr_panel_body(float* Mp, float* Vr, float* Vt, f
             const float v = tid > j ? P[0][j] * scale : (tid == j ? 1.f : 0.f);
             P[0][j] = tid > j ? v : (tid == j ? beta : P[0][j]);
             const float tv = tau * v;
+            if constexpr (UPDATE) {
 #pragma unroll
-            for (int s = j + 1; s < NB; ++s) P[0][s] = fmaf(-tv, w[s], P[0][s]);
+                for (int s = j + 1; s < NB; ++s) P[0][s] = fmaf(-tv, w[s], P[0][s]);
+            }
         }
 #pragma unroll
         for (int i = 1; i < R; ++i) {
             const float v = P[i][j] * scale;
             P[i][j] = v;
             const float tv = tau * v;
+            if constexpr (UPDATE) {
 #pragma unroll
-            for (int s = j + 1; s < NB; ++s) P[i][s] = fmaf(-tv, w[s], P[i][s]);
+                for (int s = j + 1; s < NB; ++s) P[i][s] = fmaf(-tv, w[s], P[i][s]);
+            }
         }
     });
     __syncthreads();
@@ -225,6 +232,18 @@ __global__ __launch_bounds__(NTHR)
 void qr_panel_kernel(float* Mp, float* Vr, float* Vt, float* Tg, float* rdiag, int m, int64_t batch_stride) {
     const int64_t off = (int64_t)blockIdx.y * batch_stride;
     qr_panel_body<NTHR, R>(Mp + off, Vr + off, Vt + off, Tg + off, rdiag + off, m);
+}
+
+// All the panels of a matrix at once, every reflector from the raw column (grid x = panel, grid y = matrix): panel p
+// is the tile column p from its diagonal tile down, 16 (panels - p) rows; its reflector block goes where
+// householder_qr keeps panel p's (Vr side by side in Vc, Vt in place of the panel, T and diag(R) in their arrays).
+template <int NTHR, int R>
+__global__ __launch_bounds__(NTHR)
+void direct_panels_kernel(float* M, float* Vc, float* Tmat, float* rdiag, int nbr, int64_t batch_stride) {
+    const int p = blockIdx.x;
+    const int64_t off = (int64_t)blockIdx.y * batch_stride;
+    float* Mp = M + off + (int64_t)p * nbr * 256 + (int64_t)p * 256;
+    qr_panel_body<NTHR, R, false>(Mp, Vc + off + (int64_t)p * nbr * 16 * NB, Mp, Tmat + off + (int64_t)p * NB * NB, rdiag + off + p * NB, (nbr - p) * NB);
 }
 
 // ------------------------------------------------- fused block-reflector update --
@@ -709,6 +728,18 @@ hipError_t launch_qr_panel(int rows_per_thread, float* Mp, float* Vr, float* Vt,
     return hipGetLastError();
 }
 
+template <int NTHR>
+hipError_t launch_direct_panels(int rows_per_thread, const FactorWorkspace& ws, int nbr, int count, int64_t batch_stride, hipStream_t s) {
+    switch (rows_per_thread) {
+#define GELO_CASE(RR) case RR: hipLaunchKernelGGL((direct_panels_kernel<NTHR, RR>), dim3(nbr, count), dim3(NTHR), 0, s, ws.M, ws.Vc, ws.Tmat, ws.rdiag, nbr, batch_stride); break;
+        GELO_CASE(1) GELO_CASE(2) GELO_CASE(3) GELO_CASE(4) GELO_CASE(5)
+        GELO_CASE(6) GELO_CASE(7) GELO_CASE(8) GELO_CASE(9) GELO_CASE(10)
+#undef GELO_CASE
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 #define GELO_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return e_; } while (0)
 
 }  // namespace
@@ -846,7 +877,7 @@ hipError_t launch_qr_step(const QrStepArgs& a, int count, hipStream_t s) {
 
 }  // namespace
 
-hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t batch_stride, hipStream_t s) {
+hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t batch_stride, hipStream_t s, bool direct) {
     if (count < 1 || count > 65535) return hipErrorInvalidValue;
     const int n_pad = ws.n_pad;
     const int nbr = n_pad / NB;                               // tile rows (= tile columns)
@@ -870,13 +901,19 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
         hipLaunchKernelGGL(qr_prepare_kernel, dim3((unsigned)((elems + 255) / 256), count), dim3(256), 0, s, ws.M, ws.X, n, n_pad, batch_stride);
         GELO_TRY(hipGetLastError());
     }
+    if (direct) {
+        // every panel's reflectors from the raw columns, in one launch: nothing to factorise, no chain of panels
+        const int m = n_pad;
+        if (m <= kPanelRows256) GELO_TRY(launch_direct_panels<256>((m + 255) / 256, ws, nbr, count, batch_stride, s));
+        else GELO_TRY(launch_direct_panels<512>((m + 511) / 512, ws, nbr, count, batch_stride, s));
+    }
     // panel 0 on its own; then one launch per step
-    {
+    if (!direct) {
         const int m = n_pad;
         if (m <= kPanelRows256) GELO_TRY(launch_qr_panel<256>((m + 255) / 256, ws.M, Vr_of(0), Vt_of(0), ws.Tmat, ws.rdiag, m, count, batch_stride, s));
         else GELO_TRY(launch_qr_panel<512>((m + 511) / 512, ws.M, Vr_of(0), Vt_of(0), ws.Tmat, ws.rdiag, m, count, batch_stride, s));
     }
-    for (int p = 0; p < panels; ++p) {
+    for (int p = 0; p < panels && !direct; ++p) {
         const int p0 = p / D * D, i = p - p0;                 // first panel of p's block, p's position in it
         const bool last = p + 1 == panels;
         const int block_end = p0 + D < panels ? p0 + D : panels;     // one past the block's last panel

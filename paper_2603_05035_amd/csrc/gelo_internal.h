@@ -241,7 +241,10 @@ void factor_workspace_carve(void* base, int n, FactorWorkspace* ws);
 // QR in the same tiled layout (identity in the padding block), ws.M and ws.Vc the reflectors, and
 // ws.rdiag the diagonal of R.  `count` > 1 factorises that many matrices side by side in the same launches (grid y):
 // matrix i's workspace is the one carved at `batch_stride` floats times i behind ws's (same n for all).
-hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t batch_stride, hipStream_t stream);
+// `direct`: the reflectors are NOT those of a factorisation: reflector k is built from column k of ws.M as it
+// stands (rows k onward), so ws.X becomes the product H_0 H_1 ... H_{n-1} of directly drawn reflectors and
+// ws.rdiag the values beta_k those reflectors map their columns to; no chain of dependent panels.
+hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t batch_stride, hipStream_t stream, bool direct = false);
 // ws.M holds an n_pad x n_pad matrix with an identity block in the padding.  On return ws.X holds
 // its inverse (via row-pivoted LU), *ws.flag != 0 if a zero pivot was met.
 hipError_t lu_inverse(const FactorWorkspace& ws, hipStream_t stream);

@@ -21,6 +21,7 @@ KIND_GAUSSIAN = 1
 KIND_CONDITIONED = 2
 KIND_STRUCTURED = 3
 KIND_BLOCK_ORTHOGONAL = 4
+KIND_REFLECTOR_PRODUCT = 5
 
 
 @dataclass(frozen=True)
@@ -82,6 +83,11 @@ WORKLOADS = {
                                             KIND_BLOCK_ORTHOGONAL, 8, 0xCB),
     "sweep_bf16_blocks": Workload("sweep_bf16_blocks", "bf16", 4096, 205, 4096, 12288,
                                   KIND_BLOCK_ORTHOGONAL, 8, 0xCC),
+    # ... and with the dense Haar-distributed A built as a product of directly drawn reflectors (nothing factorised)
+    "llama7b_bf16_prefill_reflectors": Workload("llama7b_bf16_prefill_reflectors", "bf16", 2048, 102, 4096, 12288,
+                                                KIND_REFLECTOR_PRODUCT, 8, 0xCD),
+    "sweep_bf16_reflectors": Workload("sweep_bf16_reflectors", "bf16", 4096, 205, 4096, 12288,
+                                      KIND_REFLECTOR_PRODUCT, 8, 0xCE),
     "decode_bf16_structured": Workload("decode_bf16_structured", "bf16", 64, 4, 4096, 12288,
                                        KIND_STRUCTURED, 8, 0xC8),
 }

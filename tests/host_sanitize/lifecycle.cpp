@@ -116,6 +116,15 @@ int main() {
         EXPECT(gelo_mixing_free(ctx, m), GELO_OK);
         EXPECT(gelo_sample_mixing_batch(ctx, GELO_BLOCK_ORTHOGONAL, bnd, bk, d, GELO_F32, bid + 1, 3, many, nullptr), GELO_OK);
         for (int i = 0; i < 3; ++i) EXPECT(gelo_mixing_free(ctx, many[i]), GELO_OK);
+        // the product of directly drawn reflectors: the host path of the QR kind with the factorisation left out
+        EXPECT(gelo_sample_mixing(ctx, GELO_REFLECTOR_PRODUCT, bnd, bk, d, GELO_F32, 0.0, 1, bid + 8, &m, nullptr), GELO_OK);
+        EXPECT(gelo_mix(ctx, m, GELO_F32, BH, d, 10.f, GELO_NORM_MEDIAN, BU, d, nullptr), GELO_OK);
+        EXPECT(gelo_project(ctx, GELO_F32, bn, d, p, BU, d, W, p, BY, p, nullptr), GELO_OK);
+        EXPECT(gelo_unmix(ctx, m, GELO_F32, p, BY, p, BZ, p, nullptr), GELO_OK);
+        EXPECT(gelo_mixing_export(ctx, m, BA, nullptr, nullptr, nullptr, nullptr, nullptr), GELO_OK);
+        EXPECT(gelo_mixing_free(ctx, m), GELO_OK);
+        EXPECT(gelo_sample_mixing_batch(ctx, GELO_REFLECTOR_PRODUCT, bnd, bk, d, GELO_F32, bid + 9, 3, many, nullptr), GELO_OK);
+        for (int i = 0; i < 3; ++i) EXPECT(gelo_mixing_free(ctx, many[i]), GELO_OK);
         HIP_OK(hipDeviceSynchronize());
         HIP_OK(hipFree(BH)); HIP_OK(hipFree(BU)); HIP_OK(hipFree(BY)); HIP_OK(hipFree(BZ)); HIP_OK(hipFree(BA));
     }

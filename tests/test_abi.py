@@ -56,12 +56,13 @@ def test_enumerators_agree_between_header_binding_and_workloads():
     from paper_2603_05035_amd import workloads as wl
     text = open(os.path.join(ROOT, "include", "gelo.h")).read()
     values = {name: int(v) for name, v in re.findall(r"\b(GELO_[A-Z0-9_]+)\s*=\s*(\d+)", text)}
-    for name in ("GELO_ORTHOGONAL", "GELO_GAUSSIAN", "GELO_CONDITIONED", "GELO_STRUCTURED", "GELO_BLOCK_ORTHOGONAL", "GELO_F32", "GELO_BF16",
+    for name in ("GELO_ORTHOGONAL", "GELO_GAUSSIAN", "GELO_CONDITIONED", "GELO_STRUCTURED", "GELO_BLOCK_ORTHOGONAL", "GELO_REFLECTOR_PRODUCT", "GELO_F32", "GELO_BF16",
                  "GELO_NORM_MEDIAN", "GELO_NORM_MEAN", "GELO_OK"):
         assert getattr(binding, name) == values[name], name
-    assert (wl.KIND_ORTHOGONAL, wl.KIND_GAUSSIAN, wl.KIND_CONDITIONED, wl.KIND_STRUCTURED, wl.KIND_BLOCK_ORTHOGONAL) == (
+    assert (wl.KIND_ORTHOGONAL, wl.KIND_GAUSSIAN, wl.KIND_CONDITIONED, wl.KIND_STRUCTURED, wl.KIND_BLOCK_ORTHOGONAL,
+            wl.KIND_REFLECTOR_PRODUCT) == (
         values["GELO_ORTHOGONAL"], values["GELO_GAUSSIAN"], values["GELO_CONDITIONED"], values["GELO_STRUCTURED"],
-        values["GELO_BLOCK_ORTHOGONAL"])
+        values["GELO_BLOCK_ORTHOGONAL"], values["GELO_REFLECTOR_PRODUCT"])
     assert binding.STATUS_NAMES[values["GELO_ESHAPE"]] == "GELO_ESHAPE" and binding.STATUS_NAMES[values["GELO_EHIP"]] == "GELO_EHIP"
     assert int(re.search(r"#define GELO_MAX_N (\d+)", text).group(1)) == binding.GELO_MAX_N
 

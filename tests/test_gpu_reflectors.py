@@ -1,0 +1,203 @@
+"""GPU parity of the orthogonal kind built as a product of directly drawn reflectors (GELO_REFLECTOR_PRODUCT):
+the exported matrix against the oracle's product element by element (up to the full prefill size), the chain stage
+by stage on the library's own secrets, eq. 4 end to end at the contract's bounds (1e-4 f32 / 2e-2 bf16), batched
+draws against single ones bit for bit."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import gelo_oracle as o
+from paper_2603_05035_amd import binding as g
+from paper_2603_05035_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+SEED = 0x5EED5
+KIND = g.GELO_REFLECTOR_PRODUCT
+TOL_END = {"f32": 1e-4, "bf16": 2e-2}
+TOL_STAGE = {"f32": 1e-5, "bf16": 4e-3}
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+CODE = {"f32": g.GELO_F32, "bf16": g.GELO_BF16}
+EPS = 2.0 ** -24
+
+
+def dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(TORCH_DTYPE[dtype]).cuda()
+
+
+def f64(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+@pytest.fixture()
+def ctx():
+    c = g.gelo_create(0, SEED, allow_batch_reuse=False)
+    yield c
+    g.gelo_destroy(c)
+
+
+def product_bound(n):
+    """Nothing is factorised, so the error of the float product does not grow with the condition of G: every entry
+    of A has passed through at most n reflector applications of a few roundings each, which add up like a random
+    walk.  2 sqrt(n) eps leaves a factor of three to six over what is measured (2 rows: 1.1e-7 against 3.7e-7;
+    2150 rows: 8.8e-7 against 5.7e-6)."""
+    return 2.0 * math.sqrt(n) * EPS + 2e-7
+
+
+@pytest.mark.parametrize("n_data,k", [(1, 0), (2, 0), (12, 2), (100, 5), (129, 0), (300, 15), (1000, 50), (2048, 102)])
+def test_exported_matrix_is_the_oracles(ctx, n_data, k):
+    """From a single entry through sizes below and above the one-launch limit of the QR kind, ragged panels, up to
+    the prefill batch: every entry against the oracle's product of the same reflectors; A^-1 = A^T exactly."""
+    n = n_data + k
+    bid = 20 + n
+    m = g.gelo_sample_mixing(ctx, KIND, n_data, k, 64, g.GELO_F32, 0.0, 1, batch_id=bid)
+    A, A_inv, _, attempt, kappa = g.gelo_mixing_export(ctx, m, n, k, 64, want_shields=False)
+    g.gelo_mixing_free(ctx, m)
+    A, A_inv = f64(A), f64(A_inv)
+    assert attempt == 0 and kappa == 1.0
+    assert np.array_equal(A_inv, A.T)
+    assert np.linalg.norm(A.T @ A - np.eye(n)) / math.sqrt(n) < 1e-5
+    G = o.gaussian_matrix(SEED, bid, o.STREAM_MIXING, 0, n, n)
+    assert np.abs(A[:, 0] - G[:, 0] / np.linalg.norm(G[:, 0])).max() < 1e-6          # column 0 is G's, normalised
+    A_ref = o.orthogonal_from_reflectors(G)
+    err = o.rel_frobenius(A, A_ref)
+    print(f"n = {n}: rel Frobenius error {err:.2e} (bound {product_bound(n):.2e}), largest entry error {np.abs(A - A_ref).max():.2e}")
+    assert err < product_bound(n)
+    assert np.abs(A - A_ref).max() < 16 * EPS                                         # measured: at most 4.7 eps at any of these sizes
+
+
+def test_sweep_size_is_orthogonal_and_differs_from_the_qr_kind(ctx):
+    """4096 + 205 rows (columns of more than 2560 rows: the long-strip kernel forms the product): orthogonality,
+    the first column, and that the same batch id under the QR kind gives another matrix with the same first column."""
+    n_data, k = 4096, 205
+    n = n_data + k
+    m = g.gelo_sample_mixing(ctx, KIND, n_data, k, 64, g.GELO_F32, 0.0, 1, batch_id=5)
+    A = g.gelo_mixing_export(ctx, m, n, k, 64, want_shields=False)[0]
+    g.gelo_mixing_free(ctx, m)
+    I = torch.eye(n, device="cuda", dtype=torch.float64)
+    Ad = A.to(torch.float64)
+    assert float((Ad.T @ Ad - I).norm()) / math.sqrt(n) < 1e-5
+    assert float((Ad @ Ad.T - I).norm()) / math.sqrt(n) < 1e-5
+    g0 = o.gaussian_matrix(SEED, 5, o.STREAM_MIXING, 0, n, n)[:, 0]
+    assert np.abs(f64(A[:, 0]) - g0 / np.linalg.norm(g0)).max() < 1e-6
+    other = g.gelo_create(0, SEED, allow_batch_reuse=False)
+    try:
+        m = g.gelo_sample_mixing(other, g.GELO_ORTHOGONAL, 300, 0, 64, g.GELO_F32, 0.0, 1, batch_id=6)
+        Q = g.gelo_mixing_export(other, m, 300, 0, 64, want_shields=False)[0]
+        g.gelo_mixing_free(other, m)
+        m = g.gelo_sample_mixing(ctx, KIND, 300, 0, 64, g.GELO_F32, 0.0, 1, batch_id=6)
+        P = g.gelo_mixing_export(ctx, m, 300, 0, 64, want_shields=False)[0]
+        g.gelo_mixing_free(ctx, m)
+        assert float((Q[:, 0] - P[:, 0]).abs().max()) < 1e-6 and float((Q[:, 1:] - P[:, 1:]).abs().max()) > 0.05
+    finally:
+        g.gelo_destroy(other)
+
+
+CASES = [("f32", 12, 2, 64, 72), ("bf16", 12, 2, 64, 72), ("f32", 300, 15, 256, 520), ("bf16", 300, 15, 264, 520),
+         ("f32", 129, 0, 72, 40), ("bf16", 1000, 50, 512, 776), ("f32", 700, 35, 128, 264)]
+
+
+@pytest.mark.parametrize("dtype,nd,k,d,p", CASES)
+def test_chain_stagewise_and_end_to_end(ctx, dtype, nd, k, d, p):
+    H32 = wl.make_hidden(nd, d, 5, min(8, d // 8))
+    W32 = wl.make_weight(d, p, 5)
+    H, W = dev(H32, dtype), dev(W32, dtype)
+    n = nd + k
+    m = g.gelo_sample_mixing(ctx, KIND, nd, k, d, CODE[dtype], 0.0, 1, batch_id=77)
+    U = torch.empty((n, d), dtype=H.dtype, device="cuda")
+    Y = torch.empty((n, p), dtype=H.dtype, device="cuda")
+    Z = torch.full((nd, p), float("nan"), dtype=H.dtype, device="cuda")
+    g.gelo_mix(ctx, m, H, U, 10.0)
+    g.gelo_project(ctx, U, W, Y)
+    A, A_inv, S, _, _ = g.gelo_mixing_export(ctx, m, n, k, d)
+    g.gelo_unmix(ctx, m, Y, Z)
+    torch.cuda.synchronize()
+    g.gelo_mixing_free(ctx, m)
+    Hd, Wd = f64(H), f64(W)
+    A64, Ai64 = f64(A), f64(A_inv)
+    if dtype == "bf16":                                   # the kernels consume A rounded once to bf16
+        A64, Ai64 = f64(A.to(torch.bfloat16)), f64(A_inv.to(torch.bfloat16))
+    S64 = f64(S) if k > 0 else None
+    tol = TOL_STAGE[dtype]
+    assert o.rel_frobenius(f64(U), o.mix(A64, Hd, S64)) < tol
+    assert o.rel_frobenius(f64(Y), o.project(f64(U), Wd)) < tol
+    assert o.rel_frobenius(f64(Z), o.unmix(Ai64, f64(Y), nd)) < tol
+    assert o.rel_frobenius(f64(Z), o.plain_projection(Hd, Wd)) < TOL_END[dtype]          # eq. 4
+    if dtype == "f32":                                    # the whole chain against the oracle's own, same seed and id
+        ref = o.qkv_forward(o.KIND_REFLECTOR_PRODUCT, SEED, 77, Hd, Wd, k_shield=k, shield_scale=10.0)
+        assert o.rel_frobenius(f64(U), ref["U"]) < 1e-4 and o.rel_frobenius(f64(Z), ref["Z"]) < TOL_END[dtype]
+
+
+@pytest.mark.parametrize("name", ["llama7b_bf16_prefill_reflectors", "sweep_bf16_reflectors"])
+def test_full_size_workloads(ctx, name):
+    """The bench workloads at full size, in one call: eq. 4 on sampled rows (the oracle computes them one by one)
+    and Freivalds on everything."""
+    w = wl.WORKLOADS[name]
+    H32, W32 = wl.make_inputs(w)
+    H, W = dev(H32, w.dtype), dev(W32, w.dtype)
+    Z = torch.full((w.n_data, w.p), float("nan"), dtype=H.dtype, device="cuda")
+    g.gelo_qkv_forward(ctx, w.kind, H, W, Z, k_shield=w.k_shield, shield_scale=w.shield_scale, batch_id=3)
+    torch.cuda.synchronize()
+    Hd, Wd, Zd = f64(H), f64(W), f64(Z)
+    rows = np.random.default_rng(9).choice(w.n_data, size=48, replace=False)
+    ref = Hd[rows] @ Wd
+    assert np.linalg.norm(Zd[rows] - ref) / np.linalg.norm(ref) < TOL_END[w.dtype]
+    r = np.random.default_rng(10).standard_normal(w.p)
+    lhs, rhs = Zd @ r, Hd @ (Wd @ r)
+    assert np.linalg.norm(lhs - rhs) / np.linalg.norm(rhs) < TOL_END[w.dtype]
+    assert np.isfinite(Zd).all()
+
+
+def test_static_entry_point_and_fresh_matrices(ctx):
+    nd, k, d, p = 100, 6, 128, 136
+    H = dev(wl.make_hidden(nd, d, 3, 4), "bf16")
+    W = dev(wl.make_weight(d, p, 3), "bf16")
+    Z0 = torch.empty((nd, p), dtype=H.dtype, device="cuda")
+    Z1 = torch.empty_like(Z0)
+    U = torch.empty((nd + k, d), dtype=H.dtype, device="cuda")
+    Y = torch.empty((nd + k, p), dtype=H.dtype, device="cuda")
+    other = g.gelo_create(0, SEED, allow_batch_reuse=False)
+    try:
+        g.gelo_qkv_forward(ctx, KIND, H, W, Z0, k_shield=k, batch_id=5)
+        g.gelo_qkv_forward_static(other, KIND, H, W, Z1, U, Y, k_shield=k, batch_id=5)
+        torch.cuda.synchronize()
+        assert torch.equal(Z0, Z1)
+    finally:
+        g.gelo_destroy(other)
+    mats = []
+    for bid in (8, 9):
+        m = g.gelo_sample_mixing(ctx, KIND, 300, 15, 64, g.GELO_F32, 0.0, 1, batch_id=bid)
+        mats.append(g.gelo_mixing_export(ctx, m, 315, 15, 64, want_shields=False)[0])
+        g.gelo_mixing_free(ctx, m)
+    assert (mats[0] - mats[1]).abs().max() > 0.05
+    with pytest.raises(g.GeloError) as e:
+        g.gelo_sample_mixing(ctx, KIND, 300, 15, 64, g.GELO_F32, 0.0, 1, batch_id=9)
+    assert g.STATUS_NAMES[e.value.status] == "GELO_EREUSE"
+
+
+@pytest.mark.parametrize("nd,k,d,count,picks", [(300, 15, 64, 5, (0, 4)), (2048, 102, 256, 3, (0, 2)), (100, 0, 64, 3, (1,)), (2048, 102, 64, 20, (7, 19))])
+def test_batched_draw_equals_single_draws(ctx, nd, k, d, count, picks):
+    """The matrices of a batched draw share every launch; object i is still, bit for bit, the single draw of its id."""
+    first = 40
+    n = nd + k
+    single = g.gelo_create(0, SEED, allow_batch_reuse=False)
+    try:
+        ms = g.gelo_sample_mixing_batch(ctx, KIND, nd, k, d, g.GELO_BF16, first, count)
+        H = dev(wl.make_hidden(nd, d, 78, 4), "bf16")
+        for i in picks:
+            m1 = g.gelo_sample_mixing(single, KIND, nd, k, d, g.GELO_BF16, 0.0, 1, batch_id=first + i)
+            U0 = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+            U1 = torch.empty_like(U0)
+            g.gelo_mix(ctx, ms[i], H, U0)
+            g.gelo_mix(single, m1, H, U1)
+            A0, Ai0, _, _, _ = g.gelo_mixing_export(ctx, ms[i], n, k, d, want_shields=False)
+            A1, Ai1, _, _, _ = g.gelo_mixing_export(single, m1, n, k, d, want_shields=False)
+            torch.cuda.synchronize()
+            assert torch.equal(A0, A1) and torch.equal(Ai0, Ai1) and torch.equal(U0, U1), f"object {i}"
+            g.gelo_mixing_free(single, m1)
+        for m in ms:
+            g.gelo_mixing_free(ctx, m)
+    finally:
+        g.gelo_destroy(single)

@@ -148,9 +148,10 @@ def test_gram_measures_on_the_library_output():
     ctx = g.gelo_create(0, 0xBEEF, allow_batch_reuse=True)
     try:
         for kind, k, lo, hi in ((g.GELO_ORTHOGONAL, 0, 0.0, 1e-5), (g.GELO_CONDITIONED, 0, 0.2, 10.0),
-                                (g.GELO_ORTHOGONAL, 2, 8.0, 1e9), (g.GELO_BLOCK_ORTHOGONAL, 0, 0.0, 1e-5)):
+                                (g.GELO_ORTHOGONAL, 2, 8.0, 1e9), (g.GELO_BLOCK_ORTHOGONAL, 0, 0.0, 1e-5),
+                                (g.GELO_REFLECTOR_PRODUCT, 0, 0.0, 1e-5), (g.GELO_REFLECTOR_PRODUCT, 2, 8.0, 1e9)):
             n = ND + k
-            m = g.gelo_sample_mixing(ctx, kind, ND, k, 512, g.GELO_F32, 0.0, 1, batch_id=11 + k)
+            m = g.gelo_sample_mixing(ctx, kind, ND, k, 512, g.GELO_F32, 0.0, 1, batch_id=11 + k + 16 * int(kind))
             U = torch.empty((n, 512), dtype=torch.float32, device="cuda")
             g.gelo_mix(ctx, m, Ht, U, 10.0)
             torch.cuda.synchronize()
