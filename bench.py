@@ -435,24 +435,25 @@ def main() -> int:
     # of the next batches on side streams (one context = one workspace per stream) while the chain of
     # the current batch runs.  Every timed step still generates one fresh A and consumes one.
     main = torch.cuda.current_stream()
-    bid = [0]
-    if w.kind in (g.GELO_ORTHOGONAL, g.GELO_BLOCK_ORTHOGONAL, g.GELO_REFLECTOR_PRODUCT):
-        # batched draws: `group` matrices per call (their factorisations share every launch), `rings` groups alive:
-        # one being consumed while the others are drawn on side streams.  A group is drawn at every step whose
-        # number is the warm-up count modulo the group size (so the first timed step issues one: a short timed
-        # region then overlaps its draws with its chains as a long one does); the group size divides K, so ANY K
-        # consecutive steps - the timed region - issue exactly K / group draw calls = K draws, and K chains.
+
+    def pipelined_batched(kind):
+        """batched draws: `group` matrices per call (their factorisations share every launch), `rings` groups alive:
+        one being consumed while the others are drawn on side streams.  A group is drawn at every step whose
+        number is the warm-up count modulo the group size (so the first timed step issues one: a short timed
+        region then overlaps its draws with its chains as a long one does); the group size divides K, so ANY K
+        consecutive steps - the timed region - issue exactly K / group draw calls = K draws, and K chains.
+        Returns (seconds per step, group, matrices alive)."""
+        bid = [0]
         group = next(b for b in range(min(max(1, args.draw_batch), K), 0, -1) if K % b == 0)
         rings = 3
-        depth = group * rings
         side = [torch.cuda.Stream() for _ in range(rings)]
         ctxs = [g.gelo_create(0, w.seed + 1 + i, allow_batch_reuse=False) for i in range(rings)]
         for c in ctxs:
-            g.gelo_reserve(c, w.kind, code, nd, k, d, p, 1, group)     # nothing allocates inside the timed region
+            g.gelo_reserve(c, kind, code, nd, k, d, p, 1, group)     # nothing allocates inside the timed region
         ring = [None] * rings
 
         def draw_group(r):
-            ring[r] = g.gelo_sample_mixing_batch(ctxs[r], w.kind, nd, k, d, code, bid[0], group, stream=side[r])
+            ring[r] = g.gelo_sample_mixing_batch(ctxs[r], kind, nd, k, d, code, bid[0], group, stream=side[r])
             bid[0] += group
 
         def pstep(i):
@@ -474,8 +475,26 @@ def main() -> int:
         ring[rings - 1] = None
         for r in range(rings - 1):                                  # two groups ahead; the third is drawn at step Wm % group
             draw_group(r)
-        leftovers = lambda: [(ctxs[r], m) for r in range(rings) for m in (ring[r] or []) if m is not None]
+        for i in range(Wm):
+            pstep(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(Wm, Wm + K):
+            pstep(i)
+        torch.cuda.synchronize()              # exactly K draws and K chains were issued and have finished in the region
+        t = (time.perf_counter() - t0) / K
+        for r in range(rings):
+            for m in (ring[r] or []):
+                if m is not None:
+                    g.gelo_mixing_free(ctxs[r], m)
+        for c in ctxs:
+            g.gelo_destroy(c)
+        return t, group, group * rings
+
+    if w.kind in (g.GELO_ORTHOGONAL, g.GELO_BLOCK_ORTHOGONAL, g.GELO_REFLECTOR_PRODUCT):
+        t_step, group, depth = pipelined_batched(w.kind)
     else:
+        bid = [0]
         group = 1
         depth = args.pipeline
         side = [torch.cuda.Stream() for _ in range(depth)]
@@ -497,19 +516,23 @@ def main() -> int:
 
         for slot in range(depth):
             draw(slot)
-        leftovers = lambda: [(ctxs[slot], ring[slot]) for slot in range(depth)]
-    for i in range(Wm):
-        pstep(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(Wm, Wm + K):
-        pstep(i)
-    torch.cuda.synchronize()                  # exactly K draws and K chains were issued and have finished in the region
-    t_step = (time.perf_counter() - t0) / K
-    for c, m in leftovers():
-        g.gelo_mixing_free(c, m)
-    for c in ctxs:
-        g.gelo_destroy(c)
+        for i in range(Wm):
+            pstep(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(Wm, Wm + K):
+            pstep(i)
+        torch.cuda.synchronize()              # exactly K draws and K chains were issued and have finished in the region
+        t_step = (time.perf_counter() - t0) / K
+        for slot in range(depth):
+            g.gelo_mixing_free(ctxs[slot], ring[slot])
+        for c in ctxs:
+            g.gelo_destroy(c)
+    # The same step with the orthogonal A drawn as a product of reflectors (the same distribution of A, no factorisation):
+    # reported beside the headline figure, which keeps the QR.
+    t_alt = None
+    if w.kind == g.GELO_ORTHOGONAL and n > 128:
+        t_alt = pipelined_batched(g.GELO_REFLECTOR_PRODUCT)[0]
 
     # ---- per-stage times with events on the launch stream ----
     def ev():
@@ -583,6 +606,14 @@ def main() -> int:
                      "peak": peak, "unit": "TFLOP/s", "frac": f_proj / t_proj / 1e12 / peak, "traffic": None,
                      "avg_launch_us": t_proj * 1e6},
     }
+
+    if t_alt is not None:
+        f_alt = f_chain + 4.0 / 3.0 * float(n) ** 3
+        result["same_law_cheaper_draw"] = {
+            "mixing": KIND_NAME[5], "ms_per_step": t_alt * 1e3, "tflops": f_alt / t_alt / 1e12,
+            "overhead_vs_plain_gemm_pct": (t_alt * 1e3 / stage["plain"] - 1.0) * 100.0,
+            "note": "the same pipelined step with A drawn as a product of reflectors built from the Gaussian's raw columns: Haar-distributed "
+                    "like the QR factor, (4/3) n^3 operations, no chain of panels; `value` above keeps the Householder QR"}
 
     if w.dtype == "bf16" and n > 128:
         # the ceiling the published peak leaves out: matrix instructions from registers only, every wave of every CU
