@@ -269,7 +269,9 @@ struct Reflector { const float* Vr; const float* Vt; const float* T; int shift; 
 
 constexpr int kBulkFromCount = 2;         // from this many factorisations side by side the block strips get launches of their own
 constexpr int kPanelRows256 = 1024;      // panels of up to this many rows are factorised by 256 threads, longer ones by 512
-constexpr int kMaxDelay = 4;             // most reflectors one strip pass applies (panels per block of the delayed update)
+constexpr int kMaxDelay = 4;             // panels per block of the delayed update: most reflectors a strip pass of the factorisation applies
+constexpr int kMaxProduct = 8;           // most reflectors a strip pass applies while Q is formed (qr_bulk_kernel: all reflectors exist by then,
+                                         // so the passes can be longer: measured 10% less time for the same reflectors than passes of four)
 
 // a tile of zeros: what a strip block reads in place of a reflector block that does not exist for it
 __device__ __attribute__((aligned(1024))) float g_zero_tile[256];
@@ -494,7 +496,7 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
     load_strip(std::integral_constant<int, 0>{});
     load_strip(std::integral_constant<int, 1>{});
     request(refl[0], std::integral_constant<int, 0>{});
-    static_for<kMaxDelay>([&](auto qc) {
+    static_for<kMaxProduct>([&](auto qc) {
         constexpr int q = decltype(qc)::value;
         if (q >= count) return;
         const Reflector R = refl[q];
@@ -583,7 +585,7 @@ __device__ __forceinline__ void reflect_strip_lds_body(const Reflector* refl, in
 // matrices with their strips split over the dies that share each (20 matrices: two rounds, then 4 matrices on two
 // dies each - a die works off 2.5 matrices' strips, not 3).
 struct QrBulkArgs {
-    Reflector refl[kMaxDelay]; int pending;
+    Reflector refl[kMaxProduct]; int pending;
     float* Cout; float* X; int outer, acc;
     int64_t strip_stride; int nb_block; int64_t batch_stride; int count;
 };
@@ -942,7 +944,7 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
         // Either way every column sees the same arithmetic.
         if (count >= kBulkFromCount && a.block_done && a.outer > 0 && a.nb_block <= kBulkMaxBlocks) {
             QrBulkArgs b;
-            for (int q = 0; q < kMaxDelay; ++q) b.refl[q] = a.refl[q < a.pending ? q : 0];
+            for (int q = 0; q < kMaxProduct; ++q) b.refl[q] = a.refl[q < a.pending ? q : 0];
             b.pending = a.pending; b.Cout = a.Cout; b.X = a.Cout; b.outer = a.outer; b.acc = 0;
             b.strip_stride = strip_stride; b.nb_block = a.nb_block; b.batch_stride = batch_stride; b.count = count;
             GELO_TRY(launch_qr_bulk(b, count, s));
@@ -954,10 +956,14 @@ hipError_t householder_qr(const FactorWorkspace& ws, int n, int count, int64_t b
     {
         // X = I so far.  Block by block from the last: X[p0:, p0:] <- H_p0 (H_p0+1 (... X[p0:, p0:])), one 16-column
         // strip per workgroup, the block's reflectors newest first, each as I - V T V^T.
-        for (int p0 = (panels - 1) / D * D; p0 >= 0; p0 -= D) {
-            const int pend = panels - p0 < D ? panels - p0 : D;
+        // (passes of kMaxProduct reflectors where the strips fit qr_bulk_kernel; the longer strips' kernel takes kMaxDelay.
+        // Columns that a pass meets before their own block's turn hold the identity below the pass's first row: the
+        // reflectors beyond their block leave them as they are, bit for bit, so the grouping does not show in Q.)
+        const int Dq = nbr <= kBulkMaxBlocks ? (ws.ld >= 64 * kMaxProduct ? kMaxProduct : D) : D;
+        for (int p0 = (panels - 1) / Dq * Dq; p0 >= 0; p0 -= Dq) {
+            const int pend = panels - p0 < Dq ? panels - p0 : Dq;
             QrBulkArgs b;
-            for (int q = 0; q < kMaxDelay; ++q) {
+            for (int q = 0; q < kMaxProduct; ++q) {
                 const int src = q < pend ? pend - 1 - q : 0;
                 b.refl[q].Vr = Vr_of(p0 + src); b.refl[q].Vt = Vt_of(p0 + src);
                 b.refl[q].T = ws.Tmat + (int64_t)(p0 + src) * NB * NB; b.refl[q].shift = src; b.refl[q].plain_t = 1;
