@@ -390,15 +390,16 @@ def sample_block_orthogonal(seed, batch_id, n_data, k, block=BLOCK_ROWS):
 # G[k:, k] instead, and  A = H_0 H_1 ... H_{n-1} diag(sign beta_k)  (H_k x_k = beta_k e_0) is Haar-distributed
 # like the QR factor - without factorising anything (Stewart, SIAM J. Numer. Anal. 17, 1980).
 # --------------------------------------------------------------------------
-def orthogonal_from_reflectors(G):
+def orthogonal_from_reflectors(G, columns=None):
     """A = H_0 H_1 ... H_{n-1} diag(sign beta_k), H_k = diag(I_k, I - 2 v v^T / (v^T v)) with
     v = x + sign(x_0) ||x|| e_0 and x = G[k:, k] (raw entries), so that H_k maps x to beta_k e_0,
-    beta_k = -sign(x_0) ||x||.  A column of zeros contributes the identity and the sign +1."""
+    beta_k = -sign(x_0) ||x||.  A column of zeros contributes the identity and the sign +1.
+    `columns`: only these columns of A (the product applied to those unit vectors: O(n^2) per column)."""
     G = np.asarray(G, dtype=np.float64)
     n = G.shape[0]
     if G.shape[1] != n:
         raise ValueError("square matrix expected")
-    Q = np.eye(n)
+    Q = np.eye(n) if columns is None else np.eye(n)[:, list(columns)]
     beta = np.zeros(n)
     for k in range(n - 1, -1, -1):                     # Q <- H_k Q: H_{n-1} first, H_0 last
         x = G[k:, k]
@@ -410,6 +411,8 @@ def orthogonal_from_reflectors(G):
         beta[k] = -norm_x if x[0] >= 0.0 else norm_x
         Q[k:, :] -= (2.0 / float(v @ v)) * np.outer(v, v @ Q[k:, :])
     signs = np.where(beta < 0.0, -1.0, 1.0)
+    if columns is not None:
+        signs = signs[list(columns)]
     return Q * signs[None, :]
 
 

@@ -68,6 +68,26 @@ def test_exported_matrix_is_the_oracles(ctx, n_data, k):
     assert np.abs(A - A_ref).max() < 16 * EPS                                         # measured: at most 4.7 eps at any of these sizes
 
 
+@pytest.mark.parametrize("n_data,k", [(1024, 0), (1025, 0), (2560, 0), (2561, 0), (4096, 205), (5120, 0)])
+def test_sampled_columns_at_the_kernel_boundaries_and_the_largest_size(ctx, n_data, k):
+    """Where the panel kernel changes its thread count (1024 rows), where the strips change kernels (2560 rows),
+    the sweep's layer size and the largest n: columns of A that the oracle computes one by one (the product applied
+    to a unit vector), among them the first and last of a panel and the last column of all."""
+    n = n_data + k
+    bid = 300 + n
+    m = g.gelo_sample_mixing(ctx, KIND, n_data, k, 64, g.GELO_F32, 0.0, 1, batch_id=bid)
+    A = g.gelo_mixing_export(ctx, m, n, k, 64, want_shields=False)[0]
+    g.gelo_mixing_free(ctx, m)
+    cols = [0, 1, 15, 16, n // 2, n - 17, n - 2, n - 1]
+    G = o.gaussian_matrix(SEED, bid, o.STREAM_MIXING, 0, n, n)
+    ref = o.orthogonal_from_reflectors(G, columns=cols)
+    got = f64(A[:, cols])
+    assert o.rel_frobenius(got, ref) < product_bound(n)
+    assert np.abs(got - ref).max() < 16 * EPS
+    Ad = A.to(torch.float64)
+    assert float((Ad.T @ Ad - torch.eye(n, device="cuda", dtype=torch.float64)).norm()) / math.sqrt(n) < 1e-5
+
+
 def test_sweep_size_is_orthogonal_and_differs_from_the_qr_kind(ctx):
     """4096 + 205 rows (columns of more than 2560 rows: the long-strip kernel forms the product): orthogonality,
     the first column, and that the same batch id under the QR kind gives another matrix with the same first column."""

@@ -70,6 +70,13 @@ def test_entries_above_the_diagonal_are_not_used():
     assert np.array_equal(o.orthogonal_from_reflectors(L), o.orthogonal_from_reflectors(G))
 
 
+def test_selected_columns_are_the_full_matrix_columns():
+    G = _gauss(21, 37)
+    A = o.orthogonal_from_reflectors(G)
+    cols = [0, 1, 15, 16, 17, 36]
+    assert np.abs(o.orthogonal_from_reflectors(G, columns=cols) - A[:, cols]).max() < 1e-14      # same sums, the library's own blocking
+
+
 def test_haar_moments():
     """For Haar-distributed A in O(n), n >= 2: E tr A = 0, E (tr A)^2 = 1, E tr(A^2) = 1, E det A = 0, and every entry
     has variance 1/n (Diaconis and Shahshahani, J. Appl. Probab. 31A, 1994).  A product without the sign matrix has
