@@ -449,7 +449,8 @@ static gelo_status sample_into(gelo_ctx* ctx, gelo_mixing* m, FactorWorkspace ws
 
     auto orthogonal_into_X = [&](bool direct) -> hipError_t {
         ps.c1 = kStreamMixing << 8;
-        hipError_t e = fill_normal(ws.M, ws.n_pad / 16, n, n, ps, 1.0f, 1, s);     // straight into the QR's tiles
+        // straight into the QR's tiles; the product of reflectors reads column k from row k down only
+        hipError_t e = fill_normal(ws.M, ws.n_pad / 16, n, n, ps, 1.0f, direct ? 2 : 1, s);
         if (e == hipSuccess) e = householder_qr(ws, n, 1, 0, s, direct);
         return e;
     };
@@ -960,7 +961,7 @@ gelo_status gelo_sample_mixing_batch(gelo_ctx* ctx, gelo_kind kind, int n_data, 
             factor_workspace_carve((char*)ctx->factor_ws + ws_bytes * i, n, &lw[i]);
             const uint64_t id = first_batch_id + (uint64_t)(base + i);
             ps.c1 = kStreamMixing << 8; ps.c2 = (uint32_t)id; ps.c3 = (uint32_t)(id >> 32);
-            e = fill_normal(lw[i].M, lw[i].n_pad / 16, n, n, ps, 1.0f, 1, s);      // straight into the QR's tiles
+            e = fill_normal(lw[i].M, lw[i].n_pad / 16, n, n, ps, 1.0f, kind == GELO_REFLECTOR_PRODUCT ? 2 : 1, s);      // straight into the QR's tiles
         }
         if (e == hipSuccess) e = householder_qr(lw[0], n, c, (int64_t)(ws_bytes / sizeof(float)), s, kind == GELO_REFLECTOR_PRODUCT);
         for (int i = 0; i < c && e == hipSuccess; ++i) {

@@ -136,7 +136,8 @@ __host__ __device__ inline int64_t qr_tile_index(int r, int c, int tile_rows) {
 }
 // out = scale * N(0,1) for r < rows, c < cols; element e = r*cols + c is output e % 4 of Philox
 // block e / 4 (counter word 0 = block index).  tiled == 0: out[r * ld + c]; tiled != 0: the same
-// element goes to out[qr_tile_index(r, c, ld)] (ld = number of tile rows).
+// element goes to out[qr_tile_index(r, c, ld)] (ld = number of tile rows); tiled == 2: the same, but pieces of 16 rows x
+// 256 columns that lie wholly above the diagonal are left as they are (for a reader of the lower triangle only).
 hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream ps, float scale,
                        int tiled, hipStream_t stream);
 // words[4 i .. 4 i + 3] = the four output words of Philox block first_block + i (counter word 0), 16-byte aligned

@@ -33,11 +33,12 @@ void fill_normal_kernel(float* out, int64_t ld, int rows, int cols, PhiloxStream
 // row than the segment holds when its ends fall inside blocks), sets the values down in LDS and writes the 16
 // tiles out as they lie in memory, 16 bytes per lane.
 __global__ __launch_bounds__(256)
-void fill_normal_tiled_kernel(float* out, int tile_rows, int rows, int cols, PhiloxStream ps, float scale) {
+void fill_normal_tiled_kernel(float* out, int tile_rows, int rows, int cols, PhiloxStream ps, float scale, int lower_only) {
     constexpr int CW = 256, PITCH = CW + 1, PER_ROW = CW / 4 + 1;
     __shared__ float tile[16 * PITCH];
     const int tid = threadIdx.x;
     const int r0 = blockIdx.y * 16, c0 = blockIdx.x * CW;
+    if (lower_only && c0 >= r0 + 16) return;                 // every column of this piece lies to the right of every row's diagonal entry
     const int width = min(CW, cols - c0);
     for (int idx = tid; idx < 16 * PER_ROW; idx += 256) {
         const int ri = idx / PER_ROW, bi = idx - ri * PER_ROW;
@@ -264,7 +265,7 @@ hipError_t fill_normal(float* out, int64_t ld, int rows, int cols, PhiloxStream 
     if (quads == 0) return hipSuccess;
     if (tiled && (int64_t)rows * cols < ((int64_t)1 << 32)) {
         hipLaunchKernelGGL(fill_normal_tiled_kernel, dim3((cols + 255) / 256, (rows + 15) / 16), dim3(256), 0, stream,
-                           out, (int)ld, rows, cols, ps, scale);
+                           out, (int)ld, rows, cols, ps, scale, tiled == 2 ? 1 : 0);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(fill_normal_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, stream,
