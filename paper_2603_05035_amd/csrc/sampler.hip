@@ -245,6 +245,55 @@ void emit_matrix_kernel(const float* src, int64_t lds, int src_tiled, const floa
     }
 }
 
+// The same for a source in the factorisations' 16 x 16 tiles, 64 x 64 elements per workgroup: a wave reads a whole
+// source tile at a time (one contiguous kilobyte, 16 bytes per lane: four rows of a column), and both the matrix and
+// its transpose leave in pieces of four elements per lane over whole 64-element row segments.  ldd % 64 == 0.
+__global__ __launch_bounds__(256)
+void emit_tiled_kernel(const float* src, int tile_rows, const float* rdiag, int n, int64_t ldd,
+                       float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16) {
+    __shared__ float tile[64][65];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+    for (int t = wave; t < 16; t += 4) {                         // source tile (t & 3, t >> 2) of the 4 x 4 in this piece
+        const int cl = (t >> 2) * 16 + (lane >> 2), rl = (t & 3) * 16 + (lane & 3) * 4;
+        const int r = r0 + rl, c = c0 + cl;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r < n && c < n) {
+            v = *reinterpret_cast<const float4*>(src + qr_tile_index(r, c, tile_rows));
+            if (rdiag != nullptr && rdiag[c] < 0.f) v = make_float4(-v.x, -v.y, -v.z, -v.w);
+            if (r + 1 >= n) v.y = 0.f;
+            if (r + 2 >= n) v.z = 0.f;
+            if (r + 3 >= n) v.w = 0.f;
+        }
+        tile[rl][cl] = v.x; tile[rl + 1][cl] = v.y; tile[rl + 2][cl] = v.z; tile[rl + 3][cl] = v.w;
+    }
+    __syncthreads();
+    auto pack4 = [](float a, float b, float c, float d) {
+        typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+        const bf16x4_t h = {(__bf16)a, (__bf16)b, (__bf16)c, (__bf16)d};
+        return __builtin_bit_cast(uint2, h);
+    };
+    for (int item = tid; item < 64 * 16; item += 256) {
+        const int i = item >> 4, q = (item & 15) * 4;
+        {                                                        // row r0 + i of the matrix, columns c0 + q ..
+            const int r = r0 + i, c = c0 + q;
+            if (r < n && c < ldd) {
+                const float a = tile[i][q], b = tile[i][q + 1], cc = tile[i][q + 2], d = tile[i][q + 3];
+                if (dst32) *reinterpret_cast<float4*>(dst32 + (int64_t)r * ldd + c) = make_float4(a, b, cc, d);
+                if (dst16) *reinterpret_cast<uint2*>(dst16 + (int64_t)r * ldd + c) = pack4(a, b, cc, d);
+            }
+        }
+        {                                                        // row c0 + i of the transpose, columns r0 + q ..
+            const int r = c0 + i, c = r0 + q;
+            if (r < n && c < ldd) {
+                const float a = tile[q][i], b = tile[q + 1][i], cc = tile[q + 2][i], d = tile[q + 3][i];
+                if (dstT32) *reinterpret_cast<float4*>(dstT32 + (int64_t)r * ldd + c) = make_float4(a, b, cc, d);
+                if (dstT16) *reinterpret_cast<uint2*>(dstT16 + (int64_t)r * ldd + c) = pack4(a, b, cc, d);
+            }
+        }
+    }
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(256)
 void export_dense_kernel(const void* src, int64_t ld, int rows, int cols, float* out) {
@@ -321,6 +370,12 @@ hipError_t make_shields(const float* G, int64_t ldg, const float* gnorm, const f
 
 hipError_t emit_matrix(const float* src, int64_t lds, int src_tiled, const float* rdiag, int n, int64_t ldd,
                        float* dst32, uint16_t* dst16, float* dstT32, uint16_t* dstT16, hipStream_t stream) {
+    if (src_tiled && ldd % 64 == 0) {
+        const int t64 = (int)(ldd / 64);
+        hipLaunchKernelGGL(emit_tiled_kernel, dim3(t64, t64), dim3(256), 0, stream,
+                           src, (int)lds, rdiag, n, ldd, dst32, dst16, dstT32, dstT16);
+        return hipGetLastError();
+    }
     const int t = (int)((ldd + 31) / 32);
     hipLaunchKernelGGL(emit_matrix_kernel, dim3(t, t), dim3(256), 0, stream,
                        src, lds, src_tiled, rdiag, n, ldd, dst32, dst16, dstT32, dstT16);
